@@ -1,0 +1,359 @@
+"""CPU oracle for the W4A8 quantized linear layer -- TEST INFRASTRUCTURE ONLY.
+
+This module is the plain, slow, obviously-correct statement of what the hot path
+computes, written from the paper's definitions (Dual Precision Quantization,
+arXiv 2505.14638).  It exists so that the HIP kernels can be checked element by
+element.  Only tests, the smoke check and the `cpu_baseline` leg of the
+benchmark may import it; the product path never does, and this module imports
+nothing from the product package.
+
+Everything here is NumPy on the host.  Floating-point sums run in float64; the
+two places where the method itself fixes a precision (the fp32 division in front
+of the FP8 rounding, and the fp32 division / round-half-even of the INT4
+round-to-nearest quantizer) are done in float32 on purpose, so that integer
+decisions (an FP8 code, an INT4 code) are taken in the same precision on both
+sides.
+
+Notation follows the paper: M tokens, K input features, N output features,
+W[N, K] (a row is one output channel; quantization groups of G consecutive
+weights run along a row, Sec. 3.1 and App. A.1), X[M, K] activations.
+
+Function                     follows
+---------------------------  ---------------------------------------------------
+e4m3_decode / e4m3_encode    Sec. 2.2 (E4M3 grid Z, nearest-in-Z), Sec. 4.1
+                             (range +-448 when the top exponent holds normals)
+act_scale_from_amax          Eq. 13 (s_x = max|X| / Z_max)
+quantize_act                 Eq. 13 (X8 = nearest_Z(X / s_x))
+rtn_quantize_weights         Eq. 1, symmetric special case of Sec. 2.1
+dequant_codes_to_e4m3        Eq. 10 / Eq. 14 with zero-point 0 and the scale
+                             factored out of the group sum (see linear_ref)
+linear_ref                   Eq. 10, Eq. 4 and Eq. 11: Y = X_hat . W_hat^T
+linear_ref_paper_literal     Eq. 6-11 read literally: the product code*scale is
+                             itself rounded onto the E4M3 grid before the matmul
+pack_* / unpack_*            storage formats of the C-ABI boundary
+silu_mul_ref, block_ref      the decoder-block linear stack workload
+
+Every function above is pinned by tests that do not use the function itself as
+the expected value (brute force over all 256 codes, exact rational arithmetic,
+closed forms, an independent library's FP8 cast, integer special cases); see
+tests/test_oracle_*.py.  No function here is "parity unpinned".
+"""
+from __future__ import annotations
+
+import numpy as np
+
+E4M3_MAX = 448.0          # largest finite E4M3 value when the top exponent is used for normals (Sec. 4.1)
+E4M3_NAN = 0x7F
+GROUP_DEFAULT = 128       # group size used in all of the paper's experiments (Sec. 4.1)
+
+
+# --------------------------------------------------------------------------------------
+# E4M3: 1 sign bit, 4 exponent bits (bias 7), 3 mantissa bits (Sec. 2.2).  The variant with
+# range +-448 (Sec. 4.1) keeps exponent 15 for normal numbers; only S.1111.111 is NaN and
+# there are no infinities.
+# --------------------------------------------------------------------------------------
+def e4m3_decode(codes) -> np.ndarray:
+    """Exact real value (float64) of each E4M3 byte; NaN for 0x7F / 0xFF."""
+    c = np.asarray(codes, dtype=np.uint8).astype(np.int64)
+    sign = np.where((c >> 7) & 1, -1.0, 1.0)
+    e = (c >> 3) & 0xF
+    m = c & 0x7
+    normal = np.ldexp(1.0 + m / 8.0, e - 7)
+    subnormal = np.ldexp(m / 8.0, -6)
+    v = sign * np.where(e == 0, subnormal, normal)
+    return np.where((c & 0x7F) == 0x7F, np.nan, v)
+
+
+def _positive_grid() -> np.ndarray:
+    # codes 0x00 .. 0x7E in ascending order of value (the format is monotone in its code)
+    return e4m3_decode(np.arange(0x7F, dtype=np.uint8))
+
+
+_GRID = _positive_grid()
+
+
+def e4m3_encode(t) -> np.ndarray:
+    """nearest_Z of Sec. 2.2 for float32 inputs: the E4M3 byte whose value is nearest to t.
+
+    Ties go to the code with an even mantissa (the reading taken for "nearest"); magnitudes
+    beyond the largest grid point map to that point (+-448: saturation, never NaN from a
+    finite or infinite input); NaN maps to 0x7F; the sign of zero is kept.
+    """
+    t = np.asarray(t, dtype=np.float32)
+    a = np.abs(t).astype(np.float64)
+    nan = np.isnan(a)
+    a = np.where(nan, 0.0, a)
+    lo = np.searchsorted(_GRID, a, side="right") - 1      # largest grid point <= a
+    lo = np.clip(lo, 0, _GRID.size - 1)
+    hi = np.minimum(lo + 1, _GRID.size - 1)
+    with np.errstate(invalid="ignore"):
+        d_lo = a - _GRID[lo]
+        d_hi = _GRID[hi] - a
+    d_hi = np.where(hi == lo, np.inf, d_hi)               # nothing above 448: stay
+    take_hi = (d_hi < d_lo) | ((d_hi == d_lo) & (hi % 2 == 0))
+    code = np.where(take_hi, hi, lo).astype(np.uint8)
+    code = code | (np.signbit(t).astype(np.uint8) << 7)
+    return np.where(nan, np.uint8(E4M3_NAN), code).astype(np.uint8)
+
+
+# --------------------------------------------------------------------------------------
+# bf16 helpers (activations arrive as bf16 in the paper's flow, Sec. 3; outputs leave as bf16)
+# bf16 arrays are carried as uint16 bit patterns.
+# --------------------------------------------------------------------------------------
+def bf16_bits_to_f32(bits) -> np.ndarray:
+    b = np.asarray(bits, dtype=np.uint16).astype(np.uint32) << 16
+    return b.view(np.float32)
+
+
+def round_to_bf16_bits(x) -> np.ndarray:
+    """Round float64 values to the nearest bf16 (ties to even), returned as uint16 bit patterns.
+
+    Done by scaling with the power of two that makes one bf16 ulp equal 1 and rounding to the
+    nearest integer, so there is a single rounding from the float64 value.
+    """
+    x = np.asarray(x, dtype=np.float64)
+    a = np.abs(x)
+    with np.errstate(divide="ignore"):
+        e = np.floor(np.log2(np.where(a > 0, a, 1.0))).astype(np.int64)
+    # guard against log2 landing one off next to powers of two
+    e = np.where(np.ldexp(1.0, e) > a, e - 1, e)
+    e = np.where(np.ldexp(1.0, e + 1) <= a, e + 1, e)
+    e = np.maximum(e, -126)                                # subnormal range shares the ulp of 2^-126
+    ulp_exp = e - 7
+    r = np.rint(np.ldexp(a, -ulp_exp))                     # exact scaling, half-even rounding
+    v = np.ldexp(r, ulp_exp)
+    v = np.where(a > 0, v, 0.0)
+    f32 = (np.sign(x) * v).astype(np.float32)              # exact: v is a bf16 value
+    f32 = np.where(np.signbit(x) & (f32 == 0), np.float32(-0.0), f32).astype(np.float32)
+    return (f32.view(np.uint32) >> 16).astype(np.uint16)
+
+
+def bf16_half_ulp(x) -> np.ndarray:
+    """Half of the bf16 spacing at |x| (float64): the most a correct bf16 rounding may move x."""
+    a = np.abs(np.asarray(x, dtype=np.float64))
+    with np.errstate(divide="ignore"):
+        e = np.floor(np.log2(np.where(a > 0, a, 1.0)))
+    e = np.maximum(e, -126.0)
+    return np.ldexp(1.0, (e - 8).astype(np.int64))
+
+
+# --------------------------------------------------------------------------------------
+# Activations (Eq. 13)
+# --------------------------------------------------------------------------------------
+def act_scale_from_amax(x) -> np.float32:
+    """s_x = max|X| / Z_max, Eq. 13, as one float32 division.  Offline (static) in the paper."""
+    amax = np.float32(np.max(np.abs(np.asarray(x, dtype=np.float32))))
+    return np.float32(amax / np.float32(E4M3_MAX))
+
+
+def quantize_act(x, s_x, *, x_is_bf16_bits: bool = False) -> np.ndarray:
+    """X8 = nearest_Z(X / s_x), Eq. 13.
+
+    The quotient is one correctly rounded float32 division (bf16 inputs widen exactly to
+    float32 first); the quotient is then rounded once onto the E4M3 grid.
+    """
+    xf = bf16_bits_to_f32(x) if x_is_bf16_bits else np.asarray(x, dtype=np.float32)
+    with np.errstate(over="ignore", invalid="ignore", divide="ignore"):
+        q = (xf / np.float32(s_x)).astype(np.float32)
+    return e4m3_encode(q)
+
+
+# --------------------------------------------------------------------------------------
+# Weights: symmetric round-to-nearest INT4 (Sec. 2.1, Eq. 1 with z = 0 and 2^n - 2 levels)
+# --------------------------------------------------------------------------------------
+def rtn_quantize_weights(w, group_size: int):
+    """Per (row, group): s = max|W| / 7; code = clamp(round_half_even(W / s), -8, 7).
+
+    Both divisions are float32.  A group that is all zero gets s = 1 and codes 0.
+    Returns (codes int8 [N, K], scales float32 [N, K / group_size]).
+    """
+    w = np.asarray(w, dtype=np.float32)
+    n, k = w.shape
+    assert k % group_size == 0
+    wg = w.reshape(n, k // group_size, group_size)
+    amax = np.max(np.abs(wg), axis=2).astype(np.float32)
+    s = (amax / np.float32(7.0)).astype(np.float32)
+    s = np.where(amax == 0, np.float32(1.0), s).astype(np.float32)
+    r = np.rint((wg / s[:, :, None]).astype(np.float32))
+    q = np.clip(r, -8, 7).astype(np.int8).reshape(n, k)
+    return q, s
+
+
+# --------------------------------------------------------------------------------------
+# Storage formats of the boundary
+# --------------------------------------------------------------------------------------
+def pack_canonical(q) -> np.ndarray:
+    """Row-major, two codes per byte: byte j of row n = (q[n,2j] & 0xF) | ((q[n,2j+1] & 0xF) << 4),
+    codes as two's-complement nibbles."""
+    q = np.asarray(q, dtype=np.int8)
+    u = (q.astype(np.int16) & 0xF).astype(np.uint8)
+    return (u[:, 0::2] | (u[:, 1::2] << 4)).astype(np.uint8)
+
+
+def unpack_canonical(packed) -> np.ndarray:
+    p = np.asarray(packed, dtype=np.uint8)
+    n, kb = p.shape
+    u = np.empty((n, kb * 2), dtype=np.int16)
+    u[:, 0::2] = p & 0xF
+    u[:, 1::2] = p >> 4
+    return np.where(u >= 8, u - 16, u).astype(np.int8)
+
+
+TILE_N = 16       # rows of W per tile
+TILE_K = 128      # codes along K per tile
+TILE_BYTES = TILE_N * TILE_K // 2
+
+
+def _tiled_destination(n_rows: int, k: int):
+    """For every (n, kk): byte offset and nibble (0 = low, 1 = high) in the tiled buffer.
+
+    Tile (t, c) = (n // 16, kk // 128) starts at byte ((t * (K/128)) + c) * 1024.  A tile is 64
+    slots of 16 bytes; slot = 16 * ((kk % 128) // 32) + (n % 16).  With p = kk % 32, d = p // 8,
+    e = p % 8: the code sits in byte 4*d + (e % 4) of the slot, in the low nibble when e < 4 and
+    in the high nibble otherwise.
+    """
+    n = np.arange(n_rows, dtype=np.int64)[:, None]
+    kk = np.arange(k, dtype=np.int64)[None, :]
+    t, i = n // TILE_N, n % TILE_N
+    c, kq, p = kk // TILE_K, (kk % TILE_K) // 32, kk % 32
+    d, e = p // 8, p % 8
+    byte = ((t * (k // TILE_K)) + c) * TILE_BYTES + (16 * kq + i) * 16 + 4 * d + (e % 4)
+    nib = (e // 4) + 0 * n
+    return byte, nib
+
+
+def pack_tiled(q) -> np.ndarray:
+    """Tiled storage (see _tiled_destination); rows are padded with code 0 up to a multiple of 16."""
+    q = np.asarray(q, dtype=np.int8)
+    n, k = q.shape
+    assert k % TILE_K == 0
+    n_pad = -(-n // TILE_N) * TILE_N
+    qp = np.zeros((n_pad, k), dtype=np.int8)
+    qp[:n] = q
+    byte, nib = _tiled_destination(n_pad, k)
+    u = (qp.astype(np.int16) & 0xF).astype(np.uint8)
+    out = np.zeros(n_pad * k // 2, dtype=np.uint8)
+    np.bitwise_or.at(out, byte.ravel(), (u << (4 * nib).astype(np.uint8)).astype(np.uint8).ravel())
+    return out
+
+
+def unpack_tiled(buf, n: int, k: int) -> np.ndarray:
+    buf = np.asarray(buf, dtype=np.uint8).ravel()
+    n_pad = -(-n // TILE_N) * TILE_N
+    byte, nib = _tiled_destination(n_pad, k)
+    u = ((buf[byte] >> (4 * nib).astype(np.uint8)) & 0xF).astype(np.int16)
+    return np.where(u >= 8, u - 16, u).astype(np.int8)[:n]
+
+
+def tile_scales(s) -> np.ndarray:
+    """Tiled scale storage: element (n, g) at float index ((n // 16) * (K/G) + g) * 16 + n % 16;
+    padding rows get scale 0."""
+    s = np.asarray(s, dtype=np.float32)
+    n, ng = s.shape
+    n_pad = -(-n // TILE_N) * TILE_N
+    sp = np.zeros((n_pad, ng), dtype=np.float32)
+    sp[:n] = s
+    return np.ascontiguousarray(sp.reshape(n_pad // TILE_N, TILE_N, ng).transpose(0, 2, 1)).ravel()
+
+
+def untile_scales(buf, n: int, ng: int) -> np.ndarray:
+    n_pad = -(-n // TILE_N) * TILE_N
+    b = np.asarray(buf, dtype=np.float32).reshape(n_pad // TILE_N, ng, TILE_N)
+    return np.ascontiguousarray(b.transpose(0, 2, 1)).reshape(n_pad, ng)[:n]
+
+
+# --------------------------------------------------------------------------------------
+# INT4 -> FP8 dequantization (Eq. 10 / Eq. 14, zero-point 0)
+# --------------------------------------------------------------------------------------
+def dequant_codes_to_e4m3(q) -> np.ndarray:
+    """The FP8 operand byte for each INT4 code: nearest_Z of the integer itself.  Every integer
+    in [-8, 7] has at most four significant bits, so the rounding is exact; the group scale of
+    Eq. 10 multiplies the group's partial sum instead (see linear_ref)."""
+    return e4m3_encode(np.asarray(q, dtype=np.int8).astype(np.float32))
+
+
+# --------------------------------------------------------------------------------------
+# The layer (Sec. 3: FP8 x FP8 product, wide accumulation, high-precision output)
+# --------------------------------------------------------------------------------------
+def linear_ref(x8, s_x, q, s_w, group_size: int):
+    """Y[m,n] = s_x * sum_g s_w[n,g] * sum_{k in g} dec(x8[m,k]) * q[n,k], all in float64.
+
+    This is X_hat . W_hat^T with X_hat = dec(X8) * s_x (Eq. 4) and W_hat = q * s_w (Eq. 10 with
+    z = 0, Eq. 14), with the group scale taken out of the group's sum.  Also returns
+    A[m,n] = s_x * sum_k |dec(x8) * q * s_w|, the sum of absolute terms, used by the tests as the
+    scale of the accumulation-error allowance next to cancelling outputs.
+    """
+    xd = e4m3_decode(x8)                                   # [M, K] float64
+    q = np.asarray(q)
+    s_w = np.asarray(s_w, dtype=np.float64)
+    m, k = xd.shape
+    n = q.shape[0]
+    assert q.shape[1] == k and k % group_size == 0 and s_w.shape == (n, k // group_size)
+    y = np.zeros((m, n), dtype=np.float64)
+    a = np.zeros((m, n), dtype=np.float64)
+    for g in range(k // group_size):
+        sl = slice(g * group_size, (g + 1) * group_size)
+        qg = q[:, sl].astype(np.float64)
+        y += (xd[:, sl] @ qg.T) * s_w[:, g][None, :]
+        a += (np.abs(xd[:, sl]) @ np.abs(qg).T) * np.abs(s_w[:, g])[None, :]
+    sx = float(np.float32(s_x))
+    return sx * y, abs(sx) * a
+
+
+def linear_ref_paper_literal(x8, s_x, q, s8, s_w_out, group_size: int):
+    """The two-level reading of Eq. 6-11: w8_hat = nearest_Z(q * s8[n,g]) (float32 product, then
+    one rounding onto the E4M3 grid), Y = s_x * s_w_out[n] * sum_k dec(x8) * dec(w8_hat).
+    Returns (Y float64, w8 bytes)."""
+    q = np.asarray(q, dtype=np.int8)
+    n, k = q.shape
+    s8 = np.asarray(s8, dtype=np.float32)
+    prod = (q.astype(np.float32).reshape(n, k // group_size, group_size) * s8[:, :, None]).astype(np.float32)
+    w8 = e4m3_encode(prod.reshape(n, k))
+    y = e4m3_decode(x8) @ e4m3_decode(w8).T
+    return float(np.float32(s_x)) * y * np.asarray(s_w_out, dtype=np.float64)[None, :], w8
+
+
+def within_tolerance(y, ref, a, rel: float = 2e-3, floor: float = 1e-3):
+    """|y - ref| <= rel * max(|ref|, floor * A) element-wise; returns (ok, worst ratio)."""
+    y = np.asarray(y, dtype=np.float64)
+    bound = rel * np.maximum(np.abs(ref), floor * a)
+    err = np.abs(y - ref)
+    with np.errstate(divide="ignore", invalid="ignore"):
+        ratio = np.where(bound > 0, err / bound, np.where(err == 0, 0.0, np.inf))
+    return bool(np.all(err <= bound)), float(np.max(ratio)) if ratio.size else 0.0
+
+
+# --------------------------------------------------------------------------------------
+# Decoder-block linear stack (all linear layers of a block are quantized, Sec. 4.1)
+# --------------------------------------------------------------------------------------
+def silu_mul_ref(gate_up_bf16_bits, ffn: int) -> np.ndarray:
+    """h = silu(gate) * up in float64; gate = first `ffn` columns, up = the next `ffn`."""
+    gu = bf16_bits_to_f32(gate_up_bf16_bits).astype(np.float64)
+    g, u = gu[:, :ffn], gu[:, ffn:2 * ffn]
+    return g / (1.0 + np.exp(-g)) * u
+
+
+def block_ref(x_bf16_bits, layers, scales_x, group_size: int, hidden: int, ffn: int):
+    """QKV -> O -> gate|up -> SiLU*mul -> down with an FP8 activation quantization in front of
+    every linear layer and bf16 tensors between layers.
+
+    `layers` maps 'qkv', 'o', 'gate_up', 'down' to (codes, scales); `scales_x` maps the same
+    names to the static activation scale of that layer's input.  The O projection reads the
+    first `hidden` columns of the QKV output (a stand-in for attention, which is not part of
+    the quantized-linear path).  Returns a dict of every intermediate as bf16 bit patterns.
+    """
+    out = {}
+
+    def lin(name, x_bits):
+        x8 = quantize_act(x_bits, scales_x[name], x_is_bf16_bits=True)
+        y, _ = linear_ref(x8, scales_x[name], layers[name][0], layers[name][1], group_size)
+        out[name + "_x8"] = x8
+        out[name] = round_to_bf16_bits(y)
+        return out[name]
+
+    qkv = lin("qkv", x_bf16_bits)
+    o = lin("o", np.ascontiguousarray(qkv[:, :hidden]))
+    gu = lin("gate_up", o)
+    out["h"] = round_to_bf16_bits(silu_mul_ref(gu, ffn))
+    lin("down", out["h"])
+    return out

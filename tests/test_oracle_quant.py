@@ -1,0 +1,125 @@
+"""Pins for the oracle's activation quantizer (Eq. 13), the symmetric INT4 round-to-nearest
+quantizer (Eq. 1, symmetric case) and the two storage formats."""
+from fractions import Fraction
+
+import numpy as np
+
+from oracle import w4a8_oracle as o
+from paper_2505_14638_amd import synthetic as syn
+
+FINITE = np.array([c for c in range(256) if (c & 0x7F) != 0x7F], dtype=np.uint8)
+
+
+def test_quantize_act_idempotent_on_grid_with_pow2_scale():
+    for s in (1.0, 0.25, 8.0, 2.0 ** -20):
+        x = (o.e4m3_decode(FINITE) * s).astype(np.float32)
+        assert np.array_equal(o.quantize_act(x, np.float32(s)), FINITE)
+
+
+def test_quantize_act_pow2_scale_invariance_and_amax():
+    rng = np.random.default_rng(5)
+    x = syn.make_activations(rng, 16, 512, 0.01, 20.0)
+    s = o.act_scale_from_amax(x)
+    a = o.quantize_act(x, s)
+    assert np.array_equal(o.quantize_act(x * np.float32(4), s * np.float32(4)), a)
+    i = np.unravel_index(np.argmax(np.abs(x)), x.shape)
+    assert a[i] & 0x7F == 0x7E                                   # the amax element lands on +-448
+    assert s == syn.static_act_scale(x)                          # workload recipe == Eq. 13 rule
+    assert Fraction(float(s)) == Fraction(float(np.float32(np.abs(x).max()) / np.float32(448)))
+
+
+def test_quantize_act_is_nearest_grid_point_of_fp32_quotient():
+    """Definition check with exact rationals on a small sample: the code is the grid point nearest
+    to the float32 quotient x / s."""
+    rng = np.random.default_rng(6)
+    x = (rng.standard_normal(200) * 3).astype(np.float32)
+    s = np.float32(0.0123)
+    got = o.e4m3_decode(o.quantize_act(x, s))
+    grid = o.e4m3_decode(FINITE)
+    for xi, gi in zip(x, got):
+        quo = Fraction(float(np.float32(xi / s)))
+        best = min(abs(quo - Fraction(float(v))) for v in grid)
+        assert abs(quo - Fraction(float(gi))) == best
+
+
+def test_quantize_act_bf16_input_and_saturation():
+    bits = np.array([0x3F80, 0xBF80, 0x4000, 0x7F80, 0xFF80, 0x7FC0, 0x0000, 0x8000], dtype=np.uint16)
+    got = o.quantize_act(bits, np.float32(1.0), x_is_bf16_bits=True)
+    assert list(got) == [0x38, 0xB8, 0x40, 0x7E, 0xFE, 0x7F, 0x00, 0x80]
+    # a static scale that is too small for the data: saturate to +-448, never NaN
+    assert list(o.quantize_act(np.array([1000.0, -1000.0], np.float32), np.float32(1.0))) == [0x7E, 0xFE]
+
+
+def test_rtn_hand_cases_and_ties():
+    # one group of 8 with amax 7 -> s = 1: codes are the half-even roundings; nothing reaches -8
+    w = np.array([[7.0, -7.0, 0.5, 1.5, 2.5, -0.5, -1.5, 3.49]], dtype=np.float32)
+    q, s = o.rtn_quantize_weights(w, 8)
+    assert s.tolist() == [[1.0]] and q.tolist() == [[7, -7, 0, 2, 2, 0, -2, 3]]
+    # all-zero group: scale 1, codes 0
+    q, s = o.rtn_quantize_weights(np.zeros((2, 64), np.float32), 32)
+    assert np.all(s == 1.0) and not q.any()
+
+
+def test_rtn_roundtrip_pow2_scales():
+    rng = np.random.default_rng(8)
+    q0 = rng.integers(-7, 8, size=(32, 256)).astype(np.int8)
+    q0[:, ::32] = 7                                              # every group of 32 holds a 7
+    s0 = np.ldexp(1.0, rng.integers(-12, 3, size=(32, 8))).astype(np.float32)
+    w = (q0.reshape(32, 8, 32) * s0[:, :, None]).reshape(32, 256).astype(np.float32)
+    q, s = o.rtn_quantize_weights(w, 32)
+    assert np.array_equal(q, q0) and np.array_equal(s, s0)
+
+
+def test_rtn_reconstruction_error_bound():
+    """|W - q*s| <= s/2 for every weight (round-to-nearest), and codes stay in [-7, 7] for
+    absmax/7 scales."""
+    w = syn.make_weights(np.random.default_rng(9), 64, 512)
+    q, s = o.rtn_quantize_weights(w, 128)
+    rec = q.reshape(64, 4, 128) * s[:, :, None].astype(np.float64)
+    err = np.abs(rec.reshape(64, 512) - w)
+    assert np.all(err <= np.repeat(s, 128, axis=1) * 0.5 * (1 + 1e-6))
+    assert q.min() >= -7 and q.max() <= 7
+    assert np.all(np.abs(q).reshape(64, 4, 128).max(axis=2) == 7)
+
+
+def test_canonical_pack_hand_row_and_all_bytes():
+    q = np.array([[1, -1, -8, 7]], dtype=np.int8)
+    assert o.pack_canonical(q).tolist() == [[0xF1, 0x78]]       # low nibble first
+    # all 256 byte values survive unpack -> pack
+    allb = np.arange(256, dtype=np.uint8).reshape(1, 256)
+    assert np.array_equal(o.pack_canonical(o.unpack_canonical(allb)), allb)
+    u = o.unpack_canonical(allb)
+    assert u.min() == -8 and u.max() == 7
+
+
+def test_tiled_pack_is_a_permutation_with_the_documented_positions():
+    rng = np.random.default_rng(10)
+    n, k = 40, 384                                               # ragged N: pads to 48
+    q = rng.integers(-8, 8, size=(n, k)).astype(np.int8)
+    buf = o.pack_tiled(q)
+    assert buf.size == 48 * k // 2
+    assert np.array_equal(o.unpack_tiled(buf, n, k), q)
+    # hand-computed positions, straight from the layout's definition
+    def at(nn, kk):
+        t, i, c, kq, p = nn // 16, nn % 16, kk // 128, (kk % 128) // 32, kk % 32
+        byte = (t * (k // 128) + c) * 1024 + (16 * kq + i) * 16 + 4 * (p // 8) + (p % 8) % 4
+        v = int(buf[byte]) >> 4 if (p % 8) >= 4 else int(buf[byte]) & 0xF
+        return v - 16 if v >= 8 else v
+    for nn, kk in [(0, 0), (0, 4), (0, 7), (0, 8), (1, 0), (15, 31), (16, 32), (17, 127), (39, 383), (5, 200)]:
+        assert at(nn, kk) == q[nn, kk]
+    # one code set, everything else zero: exactly one nibble of the buffer is non-zero
+    z = np.zeros((16, 128), np.int8)
+    z[3, 37] = -3                                                # kq=1, p=5 -> d=0, e=5 -> byte 1, high nibble
+    b = o.pack_tiled(z)
+    assert np.flatnonzero(b).tolist() == [(16 * 1 + 3) * 16 + 1] and b[(16 + 3) * 16 + 1] == 0xD0
+    # padding rows are code 0
+    assert not o.unpack_tiled(buf, 48, k)[40:].any()
+
+
+def test_scale_tiling_roundtrip_and_position():
+    s = np.arange(40 * 3, dtype=np.float32).reshape(40, 3) + 1
+    t = o.tile_scales(s)
+    assert t.size == 48 * 3
+    assert np.array_equal(o.untile_scales(t, 40, 3), s)
+    assert t[((17 // 16) * 3 + 2) * 16 + 17 % 16] == s[17, 2]
+    assert not t.reshape(3, 3, 16)[2, :, 8:].any()              # rows 40..47 are padding
