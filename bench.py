@@ -1,0 +1,215 @@
+#!/usr/bin/env python3
+"""Benchmark of the W4A8 linear-layer hot path on one MI355X.
+
+A step is one pass of the hot path over the decode sweep of Llama-3-8B layer shapes (M in {1, 4, 16} x the four
+(K, N) pairs): for each of the 12 cases, FP8 activation quantization (Eq. 13) followed by the fused
+INT4 -> E4M3 -> FP8-MFMA linear layer (Eq. 10, 4, 11) with bf16 output.  Weights are packed once before timing
+(offline with respect to inference).  Inputs are resident in HBM when timing starts.  Several distinct weight sets
+rotate between cases and steps so that weights come from HBM, not from the 256 MB last-level cache.  Steps are
+replayed as HIP graphs so that the host's launch cost does not bound microsecond-scale kernels.
+
+`value` = algorithmic bytes of the 12 linear layers / step time, where per layer
+bytes = N*K/2 (codes) + 4*N*K/G (scales) + M*K (FP8 activations) + 2*M*N (bf16 output).
+
+Also reported: `roofline` for the dominant kernel (the skinny linear kernel, timed alone with HIP events on the
+launch stream), `prefill` (TFLOP/s of the MFMA-tiled kernel over the prefill sweep, with its own roofline), and
+`cpu_baseline` (the CPU oracle timed on a bounded sample of the same workload).
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+import numpy as np
+import torch
+
+from paper_2505_14638_amd import binding as B
+from paper_2505_14638_amd import synthetic as syn
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
+FP8_PEAK_TFLOPS = 5000.0       # MI355X dense FP8 MFMA
+G = 128
+
+
+def alg_bytes(m, k, n, out_bytes=2):
+    return n * k // 2 + 4 * n * k // G + m * k + out_bytes * m * n
+
+
+class Layer:
+    """One (K, N) layer shape with `copies` independently drawn, packed weight sets."""
+
+    def __init__(self, cfg_id, idx, k, n, copies, dev):
+        self.k, self.n = k, n
+        self.sets = []
+        for c in range(copies):
+            w = syn.make_weights(syn.rng_for(cfg_id, idx, k, n, c), n, k)
+            self.sets.append(B.pack_weights(torch.from_numpy(w).to(dev), G, B.LAYOUT_TILED))
+            del w
+        torch.cuda.synchronize()
+
+
+class Case:
+    def __init__(self, cfg_id, layer, m, dev, frac, mult):
+        self.layer, self.m = layer, m
+        x = syn.make_activations(syn.rng_for(cfg_id, m, layer.k, layer.n, 99), m, layer.k, frac, mult)
+        self.s_x = torch.tensor([syn.static_act_scale(x)], dtype=torch.float32, device=dev)
+        self.x = torch.from_numpy(x).to(dev)
+        self.x8 = torch.empty((m, layer.k), dtype=torch.uint8, device=dev)
+        self.y = torch.empty((m, layer.n), dtype=torch.bfloat16, device=dev)
+
+    def quantize(self):
+        B.quantize_act(self.x, self.s_x, out=self.x8)
+
+    def linear(self, s):
+        packed, scales = self.layer.sets[s % len(self.layer.sets)]
+        B.linear(self.x8, self.s_x, packed, scales, self.layer.n, G, B.LAYOUT_TILED, out=self.y)
+
+
+def capture(fn):
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        fn()
+    return g
+
+
+def time_graphs(graphs, reps, warmup):
+    """Replay graphs round-robin `reps` times after `warmup`; returns seconds for the timed replays."""
+    for i in range(warmup):
+        graphs[i % len(graphs)].replay()
+    torch.cuda.synchronize()
+    t0, t1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0.record()
+    for i in range(reps):
+        graphs[i % len(graphs)].replay()
+    t1.record()
+    torch.cuda.synchronize()
+    return t0.elapsed_time(t1) * 1e-3
+
+
+def cpu_baseline():
+    """The oracle as it stands, timed on this host: quantize + linear for the four layer shapes at M = 16."""
+    from oracle import w4a8_oracle as o
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        threads = os.cpu_count() or 1
+    total_bytes, total_t = 0, 0.0
+    for idx, (k, n) in enumerate(syn.LLAMA3_8B.values()):
+        rng = syn.rng_for(2, idx, 1234)
+        q = rng.integers(-7, 8, size=(n, k)).astype(np.int8)           # codes with the range of RTN output
+        s_w = rng.uniform(0.005, 0.02, size=(n, k // G)).astype(np.float32)
+        x = syn.make_activations(rng, 16, k, 0.01, 20.0)
+        s_x = syn.static_act_scale(x)
+        t = time.perf_counter()
+        x8 = o.quantize_act(x, s_x)
+        o.linear_ref(x8, s_x, q, s_w, G)
+        total_t += time.perf_counter() - t
+        total_bytes += alg_bytes(16, k, n)
+    return {"value": total_bytes / total_t / 1e9, "unit": "GB/s", "cores": int(threads), "kind": "oracle",
+            "sample": "oracle quantize_act + linear_ref (fp64) on the four Llama-3-8B layer shapes at M=16, once each; "
+                      "same algorithmic-byte count as the GPU metric", "seconds": round(total_t, 3)}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--copies", type=int, default=4, help="distinct weight sets per layer shape (cache defeat)")
+    ap.add_argument("--no-prefill", action="store_true")
+    ap.add_argument("--no-cpu", action="store_true")
+    ap.add_argument("--prefill-only", action="store_true", help="profiling aid: run only the prefill sweep")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
+        sys.exit(2)
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    B.lib()
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    cfg = syn.CONFIGS[2]
+    layers = [Layer(2, i, k, n, args.copies, dev) for i, (k, n) in enumerate(syn.LLAMA3_8B.values())]
+    result = {}
+
+    if not args.prefill_only:
+        cases = [Case(2, L, m, dev, cfg["frac"], cfg["mult"]) for L in layers for m in (1, 4, 16)]
+        step_bytes = sum(alg_bytes(c.m, c.layer.k, c.layer.n) for c in cases)
+
+        def step(i):
+            for j, c in enumerate(cases):
+                c.quantize()
+                c.linear(i + j)
+
+        def linears_only(i):
+            for j, c in enumerate(cases):
+                c.linear(i + j)
+
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            step(0)                                                     # eager run before capture
+            torch.cuda.synchronize()
+            step_graphs = [capture(lambda i=i: step(i)) for i in range(args.copies)]
+            lin_graphs = [capture(lambda i=i: linears_only(i)) for i in range(args.copies)]
+            sec = time_graphs(step_graphs, args.steps, args.warmup)
+            lin_sec = time_graphs(lin_graphs, args.steps, args.warmup)
+        ms_per_step = sec / args.steps * 1e3
+        value = step_bytes / (sec / args.steps) / 1e9
+        lin_gbs = step_bytes / (lin_sec / args.steps) / 1e9
+        result.update({
+            "metric": "W4A8 linear effective HBM GB/s (decode sweep)", "value": round(value, 1), "unit": "GB/s",
+            "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 5),
+            "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "fp8_e4m3", "data": "synthetic",
+            "config": {"workload": "configs[1]: decode sweep, Llama-3-8B shapes, M in {1,4,16} x 4 (K,N), INT4 g128 "
+                                   "weights, FP8 e4m3 activations, bf16 out; step = 12 x (quantize_act + linear)",
+                       "weight_sets": args.copies, "launch": "HIP graph replay"},
+            "roofline": {"bound": "hbm", "achieved": round(lin_gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                         "frac": round(lin_gbs / HBM_PEAK_GBS, 4), "traffic": None,
+                         "kernel": "linear_skinny_kernel", "launches_per_step": len(cases),
+                         "avg_launch_us": round(lin_sec / args.steps / len(cases) * 1e6, 3),
+                         "alg_bytes_per_launch": step_bytes // len(cases)},
+        })
+        del cases, step_graphs, lin_graphs
+
+    if not args.no_prefill:
+        pcfg = syn.CONFIGS[3]
+        per_shape, tot_flop, tot_sec = [], 0.0, 0.0
+        for L in layers:
+            for m in (512, 2048, 8192):
+                c = Case(3, L, m, dev, pcfg["frac"], pcfg["mult"])
+                c.quantize()
+                reps = max(3, min(50, int(2e13 / (2.0 * m * L.k * L.n))))
+                for i in range(2):
+                    c.linear(i)
+                torch.cuda.synchronize()
+                t0, t1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                t0.record()
+                for i in range(reps):
+                    c.linear(i)
+                t1.record()
+                torch.cuda.synchronize()
+                s = t0.elapsed_time(t1) * 1e-3 / reps
+                flop = 2.0 * m * L.k * L.n
+                per_shape.append({"M": m, "K": L.k, "N": L.n, "us": round(s * 1e6, 2), "tflops": round(flop / s / 1e12, 1)})
+                tot_flop += flop
+                tot_sec += s
+                del c
+        tfl = tot_flop / tot_sec / 1e12
+        result["prefill"] = {"metric": "W4A8 linear TFLOP/s (prefill sweep, configs[2])", "value": round(tfl, 1),
+                             "unit": "TFLOP/s", "shapes": per_shape,
+                             "roofline": {"bound": "mfma", "achieved": round(tfl, 1), "peak": FP8_PEAK_TFLOPS,
+                                          "unit": "TFLOP/s", "frac": round(tfl / FP8_PEAK_TFLOPS, 4), "traffic": None,
+                                          "kernel": "linear_mfma_kernel"}}
+
+    if not args.no_cpu and not args.prefill_only:
+        result["cpu_baseline"] = cpu_baseline()
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

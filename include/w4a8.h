@@ -1,0 +1,151 @@
+/*
+ * w4a8.h -- C-ABI of the MI355X (gfx950) W4A8 quantized linear layer.
+ *
+ * The scheme is the inference flow of "Dual Precision Quantization" (arXiv 2505.14638, Sec. 3):
+ * weights are stored as 4-bit integer codes with per-group scales, are dequantized to FP8 E4M3 at
+ * inference time (Eq. 10 / Eq. 14), activations are quantized to FP8 E4M3 with a static per-tensor
+ * scale (Eq. 13), the product runs on the FP8 matrix units with wide (fp32) accumulation, and the
+ * output leaves in high precision after rescaling (Eq. 4, Eq. 11).
+ *
+ * Conventions for every entry point
+ *   - returns W4A8_OK (0) or a positive w4a8_status; never throws, exits or prints.
+ *   - arguments are validated on the host before anything is enqueued: a non-zero return means
+ *     nothing was launched (W4A8_ERR_HIP excepted: a launch was refused by the runtime).
+ *   - pointers named *_dev are DEVICE pointers owned by the caller; they must stay valid until the
+ *     work enqueued on `stream` has completed.  No entry point allocates, frees or synchronizes.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *   - notation: M tokens, K input features, N output features; W is [N, K] (one row per output
+ *     channel), quantization groups are `group_size` consecutive weights along a row (Sec. 3.1,
+ *     App. A.1); group g of row n covers k in [g*group_size, (g+1)*group_size).
+ *   - the FP8 format is E4M3 with range +-448 (Sec. 2.2, Sec. 4.1): bias 7, no infinities,
+ *     S.1111.111 is NaN.  The INT4 codes are signed, in [-8, 7], stored as two's-complement nibbles.
+ */
+#ifndef W4A8_H
+#define W4A8_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    W4A8_OK = 0,
+    W4A8_ERR_NULL = 1,      /* a required pointer is NULL */
+    W4A8_ERR_SHAPE = 2,     /* M, N, K or a leading dimension is out of range */
+    W4A8_ERR_GROUP = 3,     /* group_size does not divide K, is odd, or is not supported by the layout */
+    W4A8_ERR_DTYPE = 4,     /* unknown w4a8_dtype / w4a8_src value */
+    W4A8_ERR_LAYOUT = 5,    /* unknown w4a8_layout value, or shape not supported by that layout */
+    W4A8_ERR_ALIGN = 6,     /* a pointer or leading dimension misses the required alignment */
+    W4A8_ERR_WORKSPACE = 7, /* workspace smaller than w4a8_linear_workspace_bytes() */
+    W4A8_ERR_HIP = 8        /* the HIP runtime refused a launch */
+} w4a8_status;
+
+typedef enum { W4A8_F32 = 0, W4A8_BF16 = 1 } w4a8_dtype;
+
+typedef enum {
+    W4A8_SRC_F32_RTN = 0,  /* src = W float32 [N, K]; the library quantizes: symmetric round-to-nearest
+                              INT4 (Eq. 1, symmetric case of Sec. 2.1): per (row, group)
+                              s = max|W| / 7 (s = 1 for an all-zero group),
+                              code = clamp(round_half_even(W / s), -8, 7), both divisions in float32 */
+    W4A8_SRC_I8_CODES = 1  /* src = int8 codes [N, K], each in [-8, 7] (only the low nibble is kept), plus
+                              float32 scales [N, K/group_size]: a pure re-layout, for codes produced by an
+                              offline calibrator (Alg. 1) */
+} w4a8_src;
+
+typedef enum {
+    /* Row-major.  packed: byte j of row n = (code[n,2j] & 0xF) | ((code[n,2j+1] & 0xF) << 4), N*K/2 bytes.
+       scales: float32 [N, K/group_size] row-major.  Any even K, any even group_size dividing K. */
+    W4A8_LAYOUT_CANONICAL = 0,
+    /* Tiled for the FP8 matrix unit; needs K % 128 == 0 and group_size % 128 == 0.  Rows are padded with
+       code 0 / scale 0 up to Np = ceil(N/16)*16.
+       packed (Np*K/2 bytes): tile (t, c) = (n / 16, k / 128) is the 1024 bytes at ((t * (K/128)) + c) * 1024.
+       A tile is 64 slots of 16 bytes, slot = 16 * ((k % 128) / 32) + (n % 16).  With p = k % 32, d = p / 8,
+       e = p % 8, the code sits in byte 4*d + (e % 4) of its slot: low nibble if e < 4, else high nibble.
+       scales (Np*K/group_size floats): element (n, g) at ((n / 16) * (K/group_size) + g) * 16 + (n % 16). */
+    W4A8_LAYOUT_TILED = 1
+} w4a8_layout;
+
+/* Sizes of the buffers w4a8_pack_weights writes, in bytes / in floats; 0 for unsupported arguments. */
+size_t w4a8_packed_bytes(int64_t N, int64_t K, w4a8_layout layout);
+size_t w4a8_scales_count(int64_t N, int64_t K, int32_t group_size, w4a8_layout layout);
+
+/*
+ * Activation FP8 quantization, Eq. 13: x8[m,k] = nearest_E4M3( X[m,k] / s_x ).
+ *   x_dev      X, [M, K] with row stride ldx elements, float32 or bf16 (x_dtype)
+ *   scale_dev  one float32 on the device: the static per-tensor scale s_x (computed offline, Sec. 3.1)
+ *   x8_dev     out, E4M3 bytes [M, K] with row stride ldx8 bytes
+ * The quotient is one correctly rounded float32 division, rounded once to the nearest E4M3 value with
+ * ties to even; magnitudes beyond 448 (infinities included) saturate to +-448; NaN gives a NaN byte; the
+ * sign of zero is kept.  M == 0 is a successful no-op.  ldx >= K, ldx8 >= K.
+ */
+int w4a8_quantize_act(const void* x_dev, w4a8_dtype x_dtype, int64_t M, int64_t K, int64_t ldx,
+                      const float* scale_dev, uint8_t* x8_dev, int64_t ldx8, void* stream);
+
+/*
+ * Weight packing (offline with respect to inference; part of the boundary because the packed bytes are
+ * compared bit for bit).  Writes w4a8_packed_bytes() bytes to packed_dev and w4a8_scales_count() floats to
+ * scales_dev in `layout`.  src_scales_dev is read only for W4A8_SRC_I8_CODES (NULL otherwise).
+ * group_size = K gives one scale per output channel.
+ */
+int w4a8_pack_weights(const void* src_dev, w4a8_src src_kind, const float* src_scales_dev,
+                      int64_t N, int64_t K, int32_t group_size, w4a8_layout layout,
+                      uint8_t* packed_dev, float* scales_dev, void* stream);
+
+/* Bytes of scratch w4a8_linear needs for these sizes (currently always 0: reductions stay on chip). */
+size_t w4a8_linear_workspace_bytes(int64_t M, int64_t K, int64_t N, int32_t group_size);
+
+/*
+ * The quantized linear layer (Sec. 3; Eq. 10, Eq. 4, Eq. 11):
+ *   Y[m,n] = cast( s_x * sum_g s_w[n,g] * sum_{k in g} val(x8[m,k]) * code[n,k] )
+ * The INT4 codes are expanded in registers to the E4M3 bytes of the same integers (exact: at most four
+ * significant bits), multiplied against the E4M3 activations on the FP8 matrix units with fp32
+ * accumulation; each group's partial sum is scaled by s_w[n,g] in fp32, the total by s_x.
+ *   x8_dev        E4M3 activations [M, K], row stride ldx8 bytes (TILED: ldx8 % 16 == 0, 16-byte aligned)
+ *   x_scale_dev   one float32 on the device: s_x
+ *   packed_dev, w_scales_dev   as written by w4a8_pack_weights for the same N, K, group_size, layout
+ *   y_dev         out [M, N], float32 or bf16 (round to nearest even), row stride ldy elements
+ *   workspace_dev may be NULL when w4a8_linear_workspace_bytes() is 0
+ * Kernel choice depends only on (M, K, N, layout): M <= 64 takes the bandwidth-bound skinny path, larger M
+ * the MFMA-tiled path; CANONICAL always takes a plain reference-speed kernel.  M == 0 is a no-op.
+ */
+int w4a8_linear(const uint8_t* x8_dev, int64_t M, int64_t K, int64_t ldx8, const float* x_scale_dev,
+                const uint8_t* packed_dev, const float* w_scales_dev, int64_t N, int32_t group_size,
+                w4a8_layout layout, void* y_dev, w4a8_dtype y_dtype, int64_t ldy,
+                void* workspace_dev, size_t workspace_bytes, void* stream);
+
+/*
+ * Same as w4a8_linear for W4A8_LAYOUT_TILED with the launch shape chosen by the caller; for tuning sweeps.
+ *   path    0 = skinny (M <= 64), 1 = MFMA-tiled
+ *   param0  skinny: n-tiles (of 16 rows) per wave, 1, 2 or 4.   tiled: reserved, pass 0
+ *   param1  skinny: waves per workgroup (K is split across them), 1..16.   tiled: reserved, pass 0
+ * Unsupported combinations return W4A8_ERR_SHAPE.
+ */
+int w4a8_linear_variant(const uint8_t* x8_dev, int64_t M, int64_t K, int64_t ldx8, const float* x_scale_dev,
+                        const uint8_t* packed_dev, const float* w_scales_dev, int64_t N, int32_t group_size,
+                        void* y_dev, w4a8_dtype y_dtype, int64_t ldy, int32_t path, int32_t param0,
+                        int32_t param1, void* stream);
+
+/*
+ * Test hook for Eq. 10: writes the E4M3 byte the fused kernels feed to the matrix unit for every code,
+ * w8[n,k] = nearest_E4M3(code[n,k]), row-major [N, K], using the same device routine as w4a8_linear.
+ */
+int w4a8_dequant_weights(const uint8_t* packed_dev, int64_t N, int64_t K, w4a8_layout layout,
+                         uint8_t* w8_dev, void* stream);
+
+/*
+ * Elementwise step of the decoder-block linear stack (all linear layers of a block are quantized, Sec. 4.1;
+ * this joins gate|up to down): h[m,f] = bf16( silu(gate[m,f]) * up[m,f] ) with gate = gu[m, f],
+ * up = gu[m, F + f]; gu_dev is bf16 [M, 2F] with row stride ldgu elements, h_dev bf16 [M, F], stride ldh.
+ * Computed in fp32: silu(g) = g / (1 + exp(-g)).
+ */
+int w4a8_silu_mul(const void* gu_dev, int64_t M, int64_t F, int64_t ldgu, void* h_dev, int64_t ldh, void* stream);
+
+/* Static, NUL-terminated description of a status value. */
+const char* w4a8_status_string(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* W4A8_H */

@@ -223,26 +223,43 @@ def _tiled_destination(n_rows: int, k: int):
 
 
 def pack_tiled(q) -> np.ndarray:
-    """Tiled storage (see _tiled_destination); rows are padded with code 0 up to a multiple of 16."""
+    """Tiled storage; rows are padded with code 0 up to a multiple of 16.
+
+    Written as a reshape: split n = (t, i) and k = (c, kq, d, h, b) with k % 32 = 8*d + 4*h + b; the byte order
+    of the buffer is (t, c, kq, i, d, b) and h picks the nibble (0 = low).  `_tiled_destination` states the same
+    layout as explicit offsets; the tests check one against the other.
+    """
     q = np.asarray(q, dtype=np.int8)
     n, k = q.shape
     assert k % TILE_K == 0
     n_pad = -(-n // TILE_N) * TILE_N
-    qp = np.zeros((n_pad, k), dtype=np.int8)
-    qp[:n] = q
-    byte, nib = _tiled_destination(n_pad, k)
-    u = (qp.astype(np.int16) & 0xF).astype(np.uint8)
-    out = np.zeros(n_pad * k // 2, dtype=np.uint8)
-    np.bitwise_or.at(out, byte.ravel(), (u << (4 * nib).astype(np.uint8)).astype(np.uint8).ravel())
-    return out
+    u = np.zeros((n_pad, k), dtype=np.uint8)
+    u[:n] = q.view(np.uint8) & 0xF
+    u = u.reshape(n_pad // TILE_N, TILE_N, k // TILE_K, 4, 4, 2, 4).transpose(0, 2, 3, 1, 4, 6, 5)
+    return np.ascontiguousarray(u[..., 0] | (u[..., 1] << 4)).ravel()
 
 
 def unpack_tiled(buf, n: int, k: int) -> np.ndarray:
-    buf = np.asarray(buf, dtype=np.uint8).ravel()
     n_pad = -(-n // TILE_N) * TILE_N
-    byte, nib = _tiled_destination(n_pad, k)
-    u = ((buf[byte] >> (4 * nib).astype(np.uint8)) & 0xF).astype(np.int16)
+    b = np.asarray(buf, dtype=np.uint8).reshape(n_pad // TILE_N, k // TILE_K, 4, TILE_N, 4, 4)   # t c kq i d b
+    u = np.stack([b & 0xF, b >> 4], axis=-1).astype(np.int8)                                     # ... h
+    u = u.transpose(0, 3, 1, 2, 4, 6, 5).reshape(n_pad, k)                                       # t i c kq d h b
     return np.where(u >= 8, u - 16, u).astype(np.int8)[:n]
+
+
+def pack_tiled_by_offsets(q) -> np.ndarray:
+    """Same buffer as pack_tiled, built nibble by nibble from the explicit offsets (small inputs only)."""
+    q = np.asarray(q, dtype=np.int8)
+    n, k = q.shape
+    n_pad = -(-n // TILE_N) * TILE_N
+    qp = np.zeros((n_pad, k), dtype=np.int8)
+    qp[:n] = q
+    byte, nib = _tiled_destination(n_pad, k)
+    out = np.zeros(n_pad * k // 2, dtype=np.uint8)
+    for nn in range(n_pad):
+        for kk in range(k):
+            out[byte[nn, kk]] |= (int(qp[nn, kk]) & 0xF) << (4 * int(nib[nn, kk]))
+    return out
 
 
 def tile_scales(s) -> np.ndarray:
@@ -313,8 +330,11 @@ def linear_ref_paper_literal(x8, s_x, q, s8, s_w_out, group_size: int):
     return float(np.float32(s_x)) * y * np.asarray(s_w_out, dtype=np.float64)[None, :], w8
 
 
-def within_tolerance(y, ref, a, rel: float = 2e-3, floor: float = 1e-3):
-    """|y - ref| <= rel * max(|ref|, floor * A) element-wise; returns (ok, worst ratio)."""
+def within_tolerance(y, ref, a, rel: float = 2e-3, floor: float = 2.0 ** -6):
+    """|y - ref| <= rel * max(|ref|, floor * A) element-wise; returns (ok, worst ratio).
+
+    A is the sum of the absolute terms of the output.  An output whose terms cancel has no meaningful
+    relative error of its own; below floor * A the error is measured against the magnitude that was summed."""
     y = np.asarray(y, dtype=np.float64)
     bound = rel * np.maximum(np.abs(ref), floor * a)
     err = np.abs(y - ref)

@@ -1,0 +1,160 @@
+"""Thin ctypes binding of libw4a8.so: same entry-point names as include/w4a8.h, argument marshalling only.
+
+PyTorch supplies device memory (`tensor.data_ptr()`) and the current stream; every computation happens in the
+library's kernels.  There is no CPU or eager fallback: `lib()` raises if the library has not been built, and every
+wrapper raises `W4A8Error` on a non-zero status.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import torch
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libw4a8.so")
+
+# enums of include/w4a8.h
+F32, BF16 = 0, 1
+SRC_F32_RTN, SRC_I8_CODES = 0, 1
+LAYOUT_CANONICAL, LAYOUT_TILED = 0, 1
+
+_c_i64, _c_i32, _c_vp, _c_sz = ctypes.c_int64, ctypes.c_int32, ctypes.c_void_p, ctypes.c_size_t
+
+SIGNATURES = {
+    "w4a8_packed_bytes": (_c_sz, [_c_i64, _c_i64, _c_i32]),
+    "w4a8_scales_count": (_c_sz, [_c_i64, _c_i64, _c_i32, _c_i32]),
+    "w4a8_quantize_act": (_c_i32, [_c_vp, _c_i32, _c_i64, _c_i64, _c_i64, _c_vp, _c_vp, _c_i64, _c_vp]),
+    "w4a8_pack_weights": (_c_i32, [_c_vp, _c_i32, _c_vp, _c_i64, _c_i64, _c_i32, _c_i32, _c_vp, _c_vp, _c_vp]),
+    "w4a8_linear_workspace_bytes": (_c_sz, [_c_i64, _c_i64, _c_i64, _c_i32]),
+    "w4a8_linear": (_c_i32, [_c_vp, _c_i64, _c_i64, _c_i64, _c_vp, _c_vp, _c_vp, _c_i64, _c_i32, _c_i32, _c_vp,
+                             _c_i32, _c_i64, _c_vp, _c_sz, _c_vp]),
+    "w4a8_linear_variant": (_c_i32, [_c_vp, _c_i64, _c_i64, _c_i64, _c_vp, _c_vp, _c_vp, _c_i64, _c_i32, _c_vp,
+                                     _c_i32, _c_i64, _c_i32, _c_i32, _c_i32, _c_vp]),
+    "w4a8_dequant_weights": (_c_i32, [_c_vp, _c_i64, _c_i64, _c_i32, _c_vp, _c_vp]),
+    "w4a8_silu_mul": (_c_i32, [_c_vp, _c_i64, _c_i64, _c_i64, _c_vp, _c_i64, _c_vp]),
+    "w4a8_status_string": (ctypes.c_char_p, [_c_i32]),
+}
+
+_lib = None
+
+
+class W4A8Error(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: status {status} ({status_string(status)})")
+
+
+def lib() -> ctypes.CDLL:
+    """Load libw4a8.so (built by paper_2505_14638_amd.build); no fallback when it is missing."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is missing: run `python -m paper_2505_14638_amd.build` "
+                               "(or __graft_entry__.build()) first; there is no fallback path")
+        handle = ctypes.CDLL(LIB_PATH)
+        for name, (res, args) in SIGNATURES.items():
+            fn = getattr(handle, name)
+            fn.restype, fn.argtypes = res, args
+        _lib = handle
+    return _lib
+
+
+def status_string(status: int) -> str:
+    return lib().w4a8_status_string(int(status)).decode()
+
+
+def _check(status: int, where: str) -> None:
+    if status != 0:
+        raise W4A8Error(status, where)
+
+
+def _stream() -> int:
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _dtype_code(t: torch.Tensor) -> int:
+    if t.dtype == torch.float32:
+        return F32
+    if t.dtype == torch.bfloat16:
+        return BF16
+    raise TypeError(f"unsupported dtype {t.dtype}")
+
+
+def packed_bytes(n: int, k: int, layout: int) -> int:
+    return lib().w4a8_packed_bytes(n, k, layout)
+
+
+def scales_count(n: int, k: int, group_size: int, layout: int) -> int:
+    return lib().w4a8_scales_count(n, k, group_size, layout)
+
+
+def quantize_act(x: torch.Tensor, scale: torch.Tensor, out: torch.Tensor | None = None) -> torch.Tensor:
+    """x [M, K] float32/bf16 (row stride free), scale: 1-element float32 device tensor -> uint8 [M, K]."""
+    m, k = x.shape
+    assert x.stride(1) == 1 and scale.dtype == torch.float32
+    if out is None:
+        out = torch.empty((m, k), dtype=torch.uint8, device=x.device)
+    _check(lib().w4a8_quantize_act(x.data_ptr(), _dtype_code(x), m, k, x.stride(0) if m > 1 else max(k, x.stride(0)),
+                                   scale.data_ptr(), out.data_ptr(), out.stride(0) if m > 1 else max(k, out.stride(0)),
+                                   _stream()), "w4a8_quantize_act")
+    return out
+
+
+def pack_weights(src: torch.Tensor, group_size: int, layout: int, src_scales: torch.Tensor | None = None):
+    """src: float32 W [N, K] (round-to-nearest inside the library) or int8 codes [N, K] with src_scales
+    [N, K/group_size].  Returns (packed uint8 1-D, scales float32 1-D) in `layout`."""
+    n, k = src.shape
+    assert src.is_contiguous()
+    kind = SRC_F32_RTN if src.dtype == torch.float32 else SRC_I8_CODES
+    nbytes, nscales = packed_bytes(n, k, layout), scales_count(n, k, group_size, layout)
+    packed = torch.empty(max(nbytes, 1), dtype=torch.uint8, device=src.device)
+    scales = torch.empty(max(nscales, 1), dtype=torch.float32, device=src.device)
+    sp = 0
+    if kind == SRC_I8_CODES:
+        assert src.dtype == torch.int8 and src_scales is not None and src_scales.is_contiguous()
+        sp = src_scales.data_ptr()
+    _check(lib().w4a8_pack_weights(src.data_ptr(), kind, sp, n, k, group_size, layout, packed.data_ptr(),
+                                   scales.data_ptr(), _stream()), "w4a8_pack_weights")
+    return packed[:nbytes], scales[:nscales]
+
+
+def linear(x8: torch.Tensor, x_scale: torch.Tensor, packed: torch.Tensor, w_scales: torch.Tensor, n: int,
+           group_size: int, layout: int, out_dtype: torch.dtype = torch.bfloat16,
+           out: torch.Tensor | None = None) -> torch.Tensor:
+    m, k = x8.shape
+    assert x8.dtype == torch.uint8 and x8.stride(1) == 1
+    if out is None:
+        out = torch.empty((m, n), dtype=out_dtype, device=x8.device)
+    _check(lib().w4a8_linear(x8.data_ptr(), m, k, x8.stride(0) if m > 1 else max(k, x8.stride(0)), x_scale.data_ptr(),
+                             packed.data_ptr(), w_scales.data_ptr(), n, group_size, layout, out.data_ptr(),
+                             _dtype_code(out), out.stride(0) if m > 1 else max(n, out.stride(0)), 0, 0, _stream()),
+           "w4a8_linear")
+    return out
+
+
+def linear_variant(x8, x_scale, packed, w_scales, n, group_size, out, path: int, param0: int, param1: int):
+    m, k = x8.shape
+    _check(lib().w4a8_linear_variant(x8.data_ptr(), m, k, x8.stride(0) if m > 1 else max(k, x8.stride(0)),
+                                     x_scale.data_ptr(), packed.data_ptr(), w_scales.data_ptr(), n, group_size,
+                                     out.data_ptr(), _dtype_code(out), out.stride(0) if m > 1 else max(n, out.stride(0)),
+                                     path, param0, param1, _stream()), "w4a8_linear_variant")
+    return out
+
+
+def dequant_weights(packed: torch.Tensor, n: int, k: int, layout: int) -> torch.Tensor:
+    w8 = torch.empty((n, k), dtype=torch.uint8, device=packed.device)
+    _check(lib().w4a8_dequant_weights(packed.data_ptr(), n, k, layout, w8.data_ptr(), _stream()),
+           "w4a8_dequant_weights")
+    return w8
+
+
+def silu_mul(gu: torch.Tensor, out: torch.Tensor | None = None) -> torch.Tensor:
+    m, f2 = gu.shape
+    f = f2 // 2
+    assert gu.dtype == torch.bfloat16 and gu.stride(1) == 1 and f2 == 2 * f
+    if out is None:
+        out = torch.empty((m, f), dtype=torch.bfloat16, device=gu.device)
+    _check(lib().w4a8_silu_mul(gu.data_ptr(), m, f, gu.stride(0) if m > 1 else max(f2, gu.stride(0)), out.data_ptr(),
+                               out.stride(0) if m > 1 else max(f, out.stride(0)), _stream()), "w4a8_silu_mul")
+    return out

@@ -1,0 +1,155 @@
+// C-ABI front end: argument validation on the host, then dispatch to the kernel launchers.
+// Validation never touches the device, so every error path can be exercised without a GPU.
+#include "w4a8_internal.hpp"
+
+using namespace w4a8;
+
+namespace {
+
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+inline bool valid_dtype(int d) { return d == W4A8_F32 || d == W4A8_BF16; }
+inline bool valid_layout(int l) { return l == W4A8_LAYOUT_CANONICAL || l == W4A8_LAYOUT_TILED; }
+constexpr int64_t DIM_MAX = (int64_t)1 << 30;      // keeps every 32-bit tile / chunk index in range
+
+int check_nk(int64_t N, int64_t K, int layout) {
+    if (!valid_layout(layout)) return W4A8_ERR_LAYOUT;
+    if (N < 1 || K < 2 || N > DIM_MAX || K > DIM_MAX || (K & 1)) return W4A8_ERR_SHAPE;
+    if (layout == W4A8_LAYOUT_TILED && K % 128 != 0) return W4A8_ERR_LAYOUT;
+    return W4A8_OK;
+}
+
+int check_weight_shape(int64_t N, int64_t K, int64_t G, int layout) {
+    if (int e = check_nk(N, K, layout)) return e;
+    if (G < 2 || (G & 1) || G > K || K % G != 0) return W4A8_ERR_GROUP;
+    if (layout == W4A8_LAYOUT_TILED && G % 128 != 0) return W4A8_ERR_GROUP;
+    return W4A8_OK;
+}
+
+int check_linear(const uint8_t* x8, int64_t M, int64_t K, int64_t ldx8, const float* xs, const uint8_t* packed,
+                 const float* ws, int64_t N, int32_t G, int layout, void* y, int ydt, int64_t ldy) {
+    if (M < 0 || M > DIM_MAX) return W4A8_ERR_SHAPE;
+    if (int e = check_weight_shape(N, K, G, layout)) return e;
+    if (!valid_dtype(ydt)) return W4A8_ERR_DTYPE;
+    if (ldx8 < K || ldy < N) return W4A8_ERR_SHAPE;
+    if (!x8 || !xs || !packed || !ws || !y) return W4A8_ERR_NULL;
+    if (layout == W4A8_LAYOUT_TILED) {
+        if (!aligned16(x8) || !aligned16(packed) || !aligned16(ws) || (ldx8 & 15)) return W4A8_ERR_ALIGN;
+    }
+    if (reinterpret_cast<uintptr_t>(y) % (ydt == W4A8_F32 ? 4 : 2)) return W4A8_ERR_ALIGN;
+    return W4A8_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t w4a8_packed_bytes(int64_t N, int64_t K, w4a8_layout layout) {
+    if (check_nk(N, K, layout) != W4A8_OK) return 0;
+    const int64_t rows = (layout == W4A8_LAYOUT_TILED) ? ((N + 15) / 16) * 16 : N;
+    return (size_t)(rows * (K / 2));
+}
+
+size_t w4a8_scales_count(int64_t N, int64_t K, int32_t group_size, w4a8_layout layout) {
+    if (check_weight_shape(N, K, group_size, layout) != W4A8_OK) return 0;
+    const int64_t rows = (layout == W4A8_LAYOUT_TILED) ? ((N + 15) / 16) * 16 : N;
+    return (size_t)(rows * (K / group_size));
+}
+
+int w4a8_quantize_act(const void* x_dev, w4a8_dtype x_dtype, int64_t M, int64_t K, int64_t ldx,
+                      const float* scale_dev, uint8_t* x8_dev, int64_t ldx8, void* stream) {
+    if (!valid_dtype(x_dtype)) return W4A8_ERR_DTYPE;
+    if (M < 0 || K < 1 || M > DIM_MAX || K > DIM_MAX || ldx < K || ldx8 < K) return W4A8_ERR_SHAPE;
+    if (!x_dev || !scale_dev || !x8_dev) return W4A8_ERR_NULL;
+    if (reinterpret_cast<uintptr_t>(x_dev) % (x_dtype == W4A8_F32 ? 4 : 2) || reinterpret_cast<uintptr_t>(scale_dev) % 4)
+        return W4A8_ERR_ALIGN;
+    if (M == 0) return W4A8_OK;
+    return launch_quantize_act(x_dev, x_dtype, M, K, ldx, scale_dev, x8_dev, ldx8, static_cast<hipStream_t>(stream));
+}
+
+int w4a8_pack_weights(const void* src_dev, w4a8_src src_kind, const float* src_scales_dev, int64_t N, int64_t K,
+                      int32_t group_size, w4a8_layout layout, uint8_t* packed_dev, float* scales_dev, void* stream) {
+    if (src_kind != W4A8_SRC_F32_RTN && src_kind != W4A8_SRC_I8_CODES) return W4A8_ERR_DTYPE;
+    if (int e = check_weight_shape(N, K, group_size, layout)) return e;
+    if (!src_dev || !packed_dev || !scales_dev) return W4A8_ERR_NULL;
+    if (src_kind == W4A8_SRC_I8_CODES && !src_scales_dev) return W4A8_ERR_NULL;
+    if (reinterpret_cast<uintptr_t>(scales_dev) % 4 || (src_kind == W4A8_SRC_F32_RTN && reinterpret_cast<uintptr_t>(src_dev) % 4))
+        return W4A8_ERR_ALIGN;
+    return launch_pack_weights(src_dev, src_kind, src_scales_dev, N, K, group_size, layout, packed_dev, scales_dev,
+                               static_cast<hipStream_t>(stream));
+}
+
+size_t w4a8_linear_workspace_bytes(int64_t, int64_t, int64_t, int32_t) { return 0; }
+
+int w4a8_linear(const uint8_t* x8_dev, int64_t M, int64_t K, int64_t ldx8, const float* x_scale_dev,
+                const uint8_t* packed_dev, const float* w_scales_dev, int64_t N, int32_t group_size,
+                w4a8_layout layout, void* y_dev, w4a8_dtype y_dtype, int64_t ldy, void* workspace_dev,
+                size_t workspace_bytes, void* stream) {
+    (void)workspace_dev;
+    (void)workspace_bytes;
+    if (int e = check_linear(x8_dev, M, K, ldx8, x_scale_dev, packed_dev, w_scales_dev, N, group_size, layout, y_dev,
+                             y_dtype, ldy))
+        return e;
+    if (M == 0) return W4A8_OK;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (layout == W4A8_LAYOUT_CANONICAL)
+        return launch_linear_canonical(x8_dev, M, K, ldx8, x_scale_dev, packed_dev, w_scales_dev, N, group_size, y_dev,
+                                       y_dtype, ldy, st);
+    if (M <= 64)
+        return launch_linear_skinny(x8_dev, M, K, ldx8, x_scale_dev, packed_dev, w_scales_dev, N, group_size, y_dev,
+                                    y_dtype, ldy, 0, 0, st);
+    return launch_linear_mfma_tiled(x8_dev, M, K, ldx8, x_scale_dev, packed_dev, w_scales_dev, N, group_size, y_dev,
+                                    y_dtype, ldy, 0, st);
+}
+
+int w4a8_linear_variant(const uint8_t* x8_dev, int64_t M, int64_t K, int64_t ldx8, const float* x_scale_dev,
+                        const uint8_t* packed_dev, const float* w_scales_dev, int64_t N, int32_t group_size,
+                        void* y_dev, w4a8_dtype y_dtype, int64_t ldy, int32_t path, int32_t param0, int32_t param1,
+                        void* stream) {
+    if (int e = check_linear(x8_dev, M, K, ldx8, x_scale_dev, packed_dev, w_scales_dev, N, group_size,
+                             W4A8_LAYOUT_TILED, y_dev, y_dtype, ldy))
+        return e;
+    if (M == 0) return W4A8_OK;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (path == 0) {
+        if (M > 64 || param0 < 0 || param1 < 0 || param1 > 16) return W4A8_ERR_SHAPE;
+        return launch_linear_skinny(x8_dev, M, K, ldx8, x_scale_dev, packed_dev, w_scales_dev, N, group_size, y_dev,
+                                    y_dtype, ldy, param0, param1, st);
+    }
+    if (path == 1)
+        return launch_linear_mfma_tiled(x8_dev, M, K, ldx8, x_scale_dev, packed_dev, w_scales_dev, N, group_size, y_dev,
+                                        y_dtype, ldy, param0, st);
+    return W4A8_ERR_SHAPE;
+}
+
+int w4a8_dequant_weights(const uint8_t* packed_dev, int64_t N, int64_t K, w4a8_layout layout, uint8_t* w8_dev,
+                         void* stream) {
+    if (int e = check_nk(N, K, layout)) return e;
+    if (!packed_dev || !w8_dev) return W4A8_ERR_NULL;
+    if (layout == W4A8_LAYOUT_TILED && (!aligned16(packed_dev) || !aligned16(w8_dev))) return W4A8_ERR_ALIGN;
+    return launch_dequant_weights(packed_dev, N, K, layout, w8_dev, static_cast<hipStream_t>(stream));
+}
+
+int w4a8_silu_mul(const void* gu_dev, int64_t M, int64_t F, int64_t ldgu, void* h_dev, int64_t ldh, void* stream) {
+    if (M < 0 || F < 1 || M > DIM_MAX || F > DIM_MAX || ldgu < 2 * F || ldh < F) return W4A8_ERR_SHAPE;
+    if (!gu_dev || !h_dev) return W4A8_ERR_NULL;
+    if (reinterpret_cast<uintptr_t>(gu_dev) % 2 || reinterpret_cast<uintptr_t>(h_dev) % 2) return W4A8_ERR_ALIGN;
+    if (M == 0) return W4A8_OK;
+    return launch_silu_mul(gu_dev, M, F, ldgu, h_dev, ldh, static_cast<hipStream_t>(stream));
+}
+
+const char* w4a8_status_string(int status) {
+    switch (status) {
+        case W4A8_OK: return "ok";
+        case W4A8_ERR_NULL: return "a required pointer is NULL";
+        case W4A8_ERR_SHAPE: return "shape or leading dimension out of range";
+        case W4A8_ERR_GROUP: return "group size does not divide K or is not supported by the layout";
+        case W4A8_ERR_DTYPE: return "unknown data type or source kind";
+        case W4A8_ERR_LAYOUT: return "unknown layout, or shape not supported by the layout";
+        case W4A8_ERR_ALIGN: return "pointer or leading dimension is not aligned as required";
+        case W4A8_ERR_WORKSPACE: return "workspace too small";
+        case W4A8_ERR_HIP: return "the HIP runtime refused a launch";
+    }
+    return "unknown status";
+}
+
+}  // extern "C"

@@ -1,0 +1,185 @@
+// W4A8 linear layer for few tokens (M <= 64): the memory-bound regime of Sec. 1, where the time is the time to
+// stream the 4-bit weights from HBM once.
+//
+// Work split: a workgroup owns NT tiles of 16 output channels; its wavefronts split K between them (each takes a
+// contiguous run of 128-deep chunks, which is contiguous memory in the tiled format) and their partial results
+// are summed through LDS.  Per chunk a wavefront issues one 16-byte load per lane and tile (the 1 KiB tile is read
+// fully coalesced), expands the nibbles to E4M3 in registers (Eq. 10) and feeds them as the A operand of one
+// 16x16x128 FP8 MFMA per (tile, 16-token block); the activations are the B operand, loaded straight from global
+// memory (they are small and stay in cache).  The chunk's partial product is scaled by the group scale in fp32.
+// The next chunk's loads are issued before the current chunk's arithmetic.
+#include "w4a8_device.hpp"
+#include "w4a8_internal.hpp"
+
+namespace w4a8 {
+namespace {
+
+constexpr int RED_STRIDE = 65;      // floats per (wave, register) row in LDS: 64 lanes + 1 to spread banks
+
+template <int MT, int NT>
+struct ChunkLoads {
+    uint4 w[NT];          // packed nibbles: this lane's slot of each tile
+    float4 s[NT];         // group scales of the four output channels this lane accumulates
+    uint4 x[MT][2];       // 32 activation bytes per 16-token block
+};
+
+// the launcher keeps waves * MT * NT <= 64, so larger register tiles never run with more threads than this
+constexpr int max_threads(int tiles) { return tiles <= 4 ? 1024 : (tiles <= 8 ? 512 : 256); }
+
+template <int MT, int NT, typename OutT>
+__global__ void __launch_bounds__(max_threads(MT * NT)) linear_skinny_kernel(
+    const uint8_t* __restrict__ x8, int M, int64_t ldx8, const float* __restrict__ s_x,
+    const uint4* __restrict__ packed, const float* __restrict__ scales, int N, int n_tiles, int C, int cpg, int NG,
+    OutT* __restrict__ y, int64_t ldy, int cpw) {
+    extern __shared__ float red[];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, waves = blockDim.x >> 6;
+    const int i = lane & 15, kq = lane >> 4;
+    const int t0 = blockIdx.x * NT;
+    const int c_begin = wave * cpw;
+    const int c_end = min(C, c_begin + cpw);
+
+    const uint4* wp[NT];
+    const float4* sp[NT];
+#pragma unroll
+    for (int j = 0; j < NT; ++j) {
+        const int t = min(t0 + j, n_tiles - 1);                  // tiles past the end reload the last one; not stored
+        wp[j] = packed + (int64_t)t * C * 64 + lane;
+        sp[j] = reinterpret_cast<const float4*>(scales + (int64_t)t * NG * 16 + 4 * kq);
+    }
+    const uint4* xp[MT];
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+        const int m = min(mt * 16 + i, M - 1);                   // rows past the end reload the last one; not stored
+        xp[mt] = reinterpret_cast<const uint4*>(x8 + (int64_t)m * ldx8 + kq * 32);
+    }
+
+    auto load_chunk = [&](int c, ChunkLoads<MT, NT>& L) {
+#pragma unroll
+        for (int j = 0; j < NT; ++j) {
+            L.w[j] = wp[j][(int64_t)c * 64];
+            L.s[j] = sp[j][(c / cpg) * 4];
+        }
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) {
+            L.x[mt][0] = xp[mt][c * 8];
+            L.x[mt][1] = xp[mt][c * 8 + 1];
+        }
+    };
+
+    v4f acc[MT][NT];
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+        for (int j = 0; j < NT; ++j) acc[mt][j] = v4f{0.f, 0.f, 0.f, 0.f};
+
+    if (c_begin < c_end) {
+        ChunkLoads<MT, NT> cur, nxt;
+        load_chunk(c_begin, cur);
+        for (int c = c_begin; c < c_end; ++c) {
+            const bool more = (c + 1 < c_end);
+            if (more) load_chunk(c + 1, nxt);
+            v8i xop[MT];
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt) {
+                const uint4 a = cur.x[mt][0], b = cur.x[mt][1];
+                xop[mt] = v8i{(int)a.x, (int)a.y, (int)a.z, (int)a.w, (int)b.x, (int)b.y, (int)b.z, (int)b.w};
+            }
+#pragma unroll
+            for (int j = 0; j < NT; ++j) {
+                const v8i wop = slot_to_operand(cur.w[j]);
+                const float4 s = cur.s[j];
+#pragma unroll
+                for (int mt = 0; mt < MT; ++mt) {
+                    const v4f p = mfma_16x16x128_e4m3(wop, xop[mt], v4f{0.f, 0.f, 0.f, 0.f});
+                    acc[mt][j][0] = fmaf(s.x, p[0], acc[mt][j][0]);
+                    acc[mt][j][1] = fmaf(s.y, p[1], acc[mt][j][1]);
+                    acc[mt][j][2] = fmaf(s.z, p[2], acc[mt][j][2]);
+                    acc[mt][j][3] = fmaf(s.w, p[3], acc[mt][j][3]);
+                }
+            }
+            if (more) cur = nxt;
+        }
+    }
+
+    // sum the wavefronts' partials through LDS: red[wave][e = (mt*NT + j)*4 + r][lane]
+    constexpr int E = MT * NT * 4;
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+        for (int j = 0; j < NT; ++j)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) red[(wave * E + (mt * NT + j) * 4 + r) * RED_STRIDE + lane] = acc[mt][j][r];
+    __syncthreads();
+
+    const float sx = *s_x;
+    constexpr int COLS = 16 * NT;                                // output channels of this workgroup
+    for (int idx = threadIdx.x; idx < MT * 16 * COLS; idx += blockDim.x) {
+        const int col = idx % COLS, row = idx / COLS;            // channel fastest: consecutive threads, consecutive y
+        const int j = col >> 4, nl = col & 15, mt = row >> 4, ml = row & 15;
+        const int e = (mt * NT + j) * 4 + (nl & 3), src_lane = ml + 16 * (nl >> 2);
+        float sum = 0.0f;
+        for (int w = 0; w < waves; ++w) sum += red[(w * E + e) * RED_STRIDE + src_lane];
+        const int m = mt * 16 + ml, n = (t0 + j) * 16 + nl;
+        if (m < M && n < N) y[(int64_t)m * ldy + n] = OutCast<OutT>::cast(sx * sum);
+    }
+}
+
+template <int MT, int NT, typename OutT>
+int launch_one(const uint8_t* x8, int M, int64_t ldx8, const float* s_x, const uint8_t* packed, const float* scales,
+               int N, int C, int cpg, int NG, void* y, int64_t ldy, int waves, hipStream_t st) {
+    const int n_tiles = (N + 15) / 16;
+    const int grid = (n_tiles + NT - 1) / NT;
+    const int cpw = (C + waves - 1) / waves;
+    const size_t lds = (size_t)waves * MT * NT * 4 * RED_STRIDE * sizeof(float);
+    hipLaunchKernelGGL((linear_skinny_kernel<MT, NT, OutT>), dim3(grid), dim3(waves * 64), lds, st, x8, M, ldx8, s_x,
+                       reinterpret_cast<const uint4*>(packed), scales, N, n_tiles, C, cpg, NG, static_cast<OutT*>(y),
+                       ldy, cpw);
+    return launch_status();
+}
+
+template <int MT, typename OutT>
+int launch_nt(int nt, const uint8_t* x8, int M, int64_t ldx8, const float* s_x, const uint8_t* packed,
+              const float* scales, int N, int C, int cpg, int NG, void* y, int64_t ldy, int waves, hipStream_t st) {
+    switch (nt) {
+        case 1: return launch_one<MT, 1, OutT>(x8, M, ldx8, s_x, packed, scales, N, C, cpg, NG, y, ldy, waves, st);
+        case 2: return launch_one<MT, 2, OutT>(x8, M, ldx8, s_x, packed, scales, N, C, cpg, NG, y, ldy, waves, st);
+        case 4: return launch_one<MT, 4, OutT>(x8, M, ldx8, s_x, packed, scales, N, C, cpg, NG, y, ldy, waves, st);
+    }
+    return W4A8_ERR_SHAPE;
+}
+
+template <typename OutT>
+int launch_mt(int mt, int nt, const uint8_t* x8, int M, int64_t ldx8, const float* s_x, const uint8_t* packed,
+              const float* scales, int N, int C, int cpg, int NG, void* y, int64_t ldy, int waves, hipStream_t st) {
+    switch (mt) {
+        case 1: return launch_nt<1, OutT>(nt, x8, M, ldx8, s_x, packed, scales, N, C, cpg, NG, y, ldy, waves, st);
+        case 2: return launch_nt<2, OutT>(nt, x8, M, ldx8, s_x, packed, scales, N, C, cpg, NG, y, ldy, waves, st);
+        default: return launch_nt<4, OutT>(nt, x8, M, ldx8, s_x, packed, scales, N, C, cpg, NG, y, ldy, waves, st);
+    }
+}
+
+}  // namespace
+
+int launch_linear_skinny(const uint8_t* x8, int64_t M, int64_t K, int64_t ldx8, const float* s_x,
+                         const uint8_t* packed, const float* scales, int64_t N, int32_t G, void* y, w4a8_dtype ydt,
+                         int64_t ldy, int nt, int waves, hipStream_t st) {
+    if (M < 1 || M > 64) return W4A8_ERR_SHAPE;
+    const int C = (int)(K / 128), cpg = G / 128, NG = (int)(K / G);
+    const int n_tiles = (int)((N + 15) / 16);
+    const int mt = (M <= 16) ? 1 : (M <= 32) ? 2 : 4;
+    if (nt == 0) nt = ((int64_t)n_tiles * C >= 32768 && mt <= 2) ? 2 : 1;
+    if (nt != 1 && nt != 2 && nt != 4) return W4A8_ERR_SHAPE;
+    if (waves == 0) {
+        const int grid = (n_tiles + nt - 1) / nt;
+        waves = (4096 + grid - 1) / grid;                        // aim at ~16 wavefronts per compute unit
+        if (waves > 16) waves = 16;
+    }
+    if (waves > C) waves = C;
+    while (waves > 1 && waves * mt * nt > 64) --waves;           // partial sums must fit in 64 KiB of LDS
+    if (waves < 1 || waves > 16 || waves * mt * nt > 64) return W4A8_ERR_SHAPE;
+    if (ydt == W4A8_F32)
+        return launch_mt<float>(mt, nt, x8, (int)M, ldx8, s_x, packed, scales, (int)N, C, cpg, NG, y, ldy, waves, st);
+    return launch_mt<uint16_t>(mt, nt, x8, (int)M, ldx8, s_x, packed, scales, (int)N, C, cpg, NG, y, ldy, waves, st);
+}
+
+}  // namespace w4a8

@@ -1,0 +1,159 @@
+// Weight packing: symmetric round-to-nearest INT4 (Eq. 1, symmetric case) or re-layout of given codes,
+// into the canonical or the tiled storage format; and the INT4 -> E4M3 test hook (Eq. 10).
+// Offline with respect to inference: written for exactness and simplicity, not speed.
+#include "w4a8_device.hpp"
+#include "w4a8_internal.hpp"
+
+namespace w4a8 {
+namespace {
+
+struct Geometry {
+    int64_t N, K, NG;      // rows, columns, groups per row
+    int64_t Np;            // rows of the destination (padded to 16 for the tiled layout)
+    int32_t G;
+    int tiled;
+};
+
+__device__ __forceinline__ int64_t scale_index(const Geometry& g, int64_t n, int64_t grp) {
+    return g.tiled ? ((n >> 4) * g.NG + grp) * 16 + (n & 15) : n * g.NG + grp;
+}
+
+// destination byte -> row and the two columns whose codes it holds (low nibble, high nibble)
+__device__ __forceinline__ void byte_to_coords(const Geometry& g, int64_t b, int64_t& n, int64_t& k_lo, int64_t& k_hi) {
+    if (g.tiled) {
+        const int64_t tile = b >> 10, C = g.K >> 7;
+        const int64_t t = tile / C, c = tile - t * C;
+        const int within = (int)(b & 1023), slot = within >> 4, byte = within & 15;
+        const int kq = slot >> 4, i = slot & 15, d = byte >> 2, bb = byte & 3;
+        n = t * 16 + i;
+        k_lo = c * 128 + kq * 32 + d * 8 + bb;
+        k_hi = k_lo + 4;
+    } else {
+        const int64_t half = g.K >> 1;
+        n = b / half;
+        k_lo = (b - n * half) * 2;
+        k_hi = k_lo + 1;
+    }
+}
+
+// one wavefront per (row, group): s = max|W| / 7, or 1 for an all-zero group; padding rows get 0
+__global__ void __launch_bounds__(256) rtn_scales_kernel(const float* __restrict__ w, Geometry g, float* __restrict__ scales) {
+    const int64_t wid = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
+    const int lane = threadIdx.x & 63;
+    if (wid >= g.Np * g.NG) return;
+    const int64_t n = wid / g.NG, grp = wid - n * g.NG;
+    float amax = 0.0f;
+    if (n < g.N) {
+        const float* p = w + n * g.K + grp * g.G;
+        for (int j = lane; j < g.G; j += 64) amax = fmaxf(amax, fabsf(p[j]));
+    }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) amax = fmaxf(amax, __shfl_xor(amax, off, 64));
+    if (lane == 0) {
+        float s = 0.0f;
+        if (n < g.N) s = (amax == 0.0f) ? 1.0f : amax / 7.0f;
+        scales[scale_index(g, n, grp)] = s;
+    }
+}
+
+__global__ void __launch_bounds__(256) copy_scales_kernel(const float* __restrict__ src, Geometry g, float* __restrict__ scales) {
+    const int64_t u = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (u >= g.Np * g.NG) return;
+    const int64_t n = u / g.NG, grp = u - n * g.NG;
+    scales[scale_index(g, n, grp)] = (n < g.N) ? src[n * g.NG + grp] : 0.0f;
+}
+
+__device__ __forceinline__ uint32_t rtn_code(float w, float s) {
+    float r = rintf(w / s);                      // float32 division, round half to even
+    r = fminf(fmaxf(r, -8.0f), 7.0f);
+    return ((uint32_t)(int)r) & 0xFu;
+}
+
+// one thread per destination byte
+template <bool FROM_F32>
+__global__ void __launch_bounds__(256) pack_kernel(const void* __restrict__ src, Geometry g,
+                                                   const float* __restrict__ scales, uint8_t* __restrict__ packed) {
+    const int64_t b = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (b >= g.Np * (g.K >> 1)) return;
+    int64_t n, k_lo, k_hi;
+    byte_to_coords(g, b, n, k_lo, k_hi);
+    uint32_t lo = 0, hi = 0;
+    if (n < g.N) {
+        if (FROM_F32) {
+            const float* w = static_cast<const float*>(src) + n * g.K;
+            lo = rtn_code(w[k_lo], scales[scale_index(g, n, k_lo / g.G)]);
+            hi = rtn_code(w[k_hi], scales[scale_index(g, n, k_hi / g.G)]);
+        } else {
+            const int8_t* q = static_cast<const int8_t*>(src) + n * g.K;
+            lo = ((uint32_t)q[k_lo]) & 0xFu;
+            hi = ((uint32_t)q[k_hi]) & 0xFu;
+        }
+    }
+    packed[b] = (uint8_t)(lo | (hi << 4));
+}
+
+// tiled: one thread per 16-byte slot -> 32 consecutive bytes of one row of w8
+__global__ void __launch_bounds__(256) dequant_tiled_kernel(const uint4* __restrict__ packed, int64_t N, int64_t K,
+                                                            int64_t slots, uint8_t* __restrict__ w8) {
+    const int64_t u = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (u >= slots) return;
+    const int64_t tile = u >> 6, C = K >> 7;
+    const int64_t t = tile / C, c = tile - t * C;
+    const int slot = (int)(u & 63), kq = slot >> 4, i = slot & 15;
+    const int64_t n = t * 16 + i;
+    if (n >= N) return;
+    const v8i op = slot_to_operand(packed[u]);
+    uint4* dst = reinterpret_cast<uint4*>(w8 + n * K + c * 128 + kq * 32);
+    dst[0] = make_uint4((uint32_t)op[0], (uint32_t)op[1], (uint32_t)op[2], (uint32_t)op[3]);
+    dst[1] = make_uint4((uint32_t)op[4], (uint32_t)op[5], (uint32_t)op[6], (uint32_t)op[7]);
+}
+
+// canonical: one thread per packed byte (two codes)
+__global__ void __launch_bounds__(256) dequant_canonical_kernel(const uint8_t* __restrict__ packed, int64_t bytes,
+                                                                uint8_t* __restrict__ w8) {
+    const int64_t b = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (b >= bytes) return;
+    uint32_t lo, hi;
+    nibbles_to_e4m3((uint32_t)packed[b], lo, hi);
+    w8[2 * b] = (uint8_t)(lo & 0xFFu);
+    w8[2 * b + 1] = (uint8_t)(hi & 0xFFu);
+}
+
+inline unsigned blocks_for(int64_t threads) { return (unsigned)((threads + 255) / 256); }
+
+}  // namespace
+
+int launch_pack_weights(const void* src, w4a8_src kind, const float* src_scales, int64_t N, int64_t K, int32_t G,
+                        w4a8_layout layout, uint8_t* packed, float* scales, hipStream_t st) {
+    Geometry g;
+    g.N = N; g.K = K; g.G = G; g.NG = K / G;
+    g.tiled = (layout == W4A8_LAYOUT_TILED);
+    g.Np = g.tiled ? ((N + 15) / 16) * 16 : N;
+    const int64_t n_scales = g.Np * g.NG, n_bytes = g.Np * (K / 2);
+    if (kind == W4A8_SRC_F32_RTN) {
+        hipLaunchKernelGGL(rtn_scales_kernel, dim3(blocks_for(n_scales * 64)), dim3(256), 0, st,
+                           static_cast<const float*>(src), g, scales);
+        if (int e = launch_status()) return e;
+        hipLaunchKernelGGL(pack_kernel<true>, dim3(blocks_for(n_bytes)), dim3(256), 0, st, src, g, scales, packed);
+    } else {
+        hipLaunchKernelGGL(copy_scales_kernel, dim3(blocks_for(n_scales)), dim3(256), 0, st, src_scales, g, scales);
+        if (int e = launch_status()) return e;
+        hipLaunchKernelGGL(pack_kernel<false>, dim3(blocks_for(n_bytes)), dim3(256), 0, st, src, g, scales, packed);
+    }
+    return launch_status();
+}
+
+int launch_dequant_weights(const uint8_t* packed, int64_t N, int64_t K, w4a8_layout layout, uint8_t* w8,
+                           hipStream_t st) {
+    if (layout == W4A8_LAYOUT_TILED) {
+        const int64_t slots = ((N + 15) / 16) * (K / 128) * 64;
+        hipLaunchKernelGGL(dequant_tiled_kernel, dim3(blocks_for(slots)), dim3(256), 0, st,
+                           reinterpret_cast<const uint4*>(packed), N, K, slots, w8);
+    } else {
+        const int64_t bytes = N * (K / 2);
+        hipLaunchKernelGGL(dequant_canonical_kernel, dim3(blocks_for(bytes)), dim3(256), 0, st, packed, bytes, w8);
+    }
+    return launch_status();
+}
+
+}  // namespace w4a8

@@ -1,0 +1,113 @@
+// Activation FP8 quantization (Eq. 13): x8 = nearest_E4M3(X / s_x), static per-tensor s_x.
+// Streaming kernel: HBM-bound, 16 elements per thread (one 16-byte store, 128-bit loads).
+#include "w4a8_device.hpp"
+#include "w4a8_internal.hpp"
+
+namespace w4a8 {
+namespace {
+
+// Saturate to the E4M3 range (Sec. 4.1: +-448) before the hardware rounding; NaN passes through.
+__device__ __forceinline__ float sat448(float t) {
+    const float c = __builtin_fminf(__builtin_fmaxf(t, -448.0f), 448.0f);
+    return (t != t) ? t : c;
+}
+
+// Two float32 -> two E4M3 bytes (round to nearest even) in the low or high half of `old`.
+__device__ __forceinline__ uint32_t cvt2(float a, float b, uint32_t old, bool high) {
+    return high ? (uint32_t)__builtin_amdgcn_cvt_pk_fp8_f32(sat448(a), sat448(b), (int)old, true)
+                : (uint32_t)__builtin_amdgcn_cvt_pk_fp8_f32(sat448(a), sat448(b), (int)old, false);
+}
+
+__device__ __forceinline__ uint32_t quant4(float a, float b, float c, float d, float s) {
+    // IEEE float32 division (correctly rounded), then one rounding onto the E4M3 grid
+    uint32_t r = cvt2(a / s, b / s, 0u, false);
+    return cvt2(c / s, d / s, r, true);
+}
+
+template <typename InT> struct Load16;   // 16 consecutive elements -> 16 floats
+template <> struct Load16<float> {
+    static __device__ __forceinline__ void load(const float* p, float (&v)[16]) {
+        const float4* q = reinterpret_cast<const float4*>(p);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const float4 t = q[i];
+            v[4 * i] = t.x; v[4 * i + 1] = t.y; v[4 * i + 2] = t.z; v[4 * i + 3] = t.w;
+        }
+    }
+    static __device__ __forceinline__ float one(const float* p) { return *p; }
+};
+template <> struct Load16<uint16_t> {
+    static __device__ __forceinline__ void load(const uint16_t* p, float (&v)[16]) {
+        const uint4* q = reinterpret_cast<const uint4*>(p);
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            const uint4 t = q[i];
+            const uint32_t w[4] = {t.x, t.y, t.z, t.w};
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                v[8 * i + 2 * j] = __uint_as_float(w[j] << 16);
+                v[8 * i + 2 * j + 1] = __uint_as_float(w[j] & 0xFFFF0000u);
+            }
+        }
+    }
+    static __device__ __forceinline__ float one(const uint16_t* p) { return bf16_bits_to_f32(*p); }
+};
+
+template <typename InT>
+__global__ void __launch_bounds__(256) quantize_act_vec_kernel(const InT* __restrict__ x, int64_t M, int64_t K16,
+                                                               int64_t ldx, const float* __restrict__ scale,
+                                                               uint8_t* __restrict__ x8, int64_t ldx8) {
+    const float s = *scale;
+    const int64_t total = M * K16;
+    for (int64_t u = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; u < total; u += (int64_t)gridDim.x * blockDim.x) {
+        const int64_t m = u / K16, k = (u - m * K16) * 16;
+        float v[16];
+        Load16<InT>::load(x + m * ldx + k, v);
+        uint4 o;
+        o.x = quant4(v[0], v[1], v[2], v[3], s);
+        o.y = quant4(v[4], v[5], v[6], v[7], s);
+        o.z = quant4(v[8], v[9], v[10], v[11], s);
+        o.w = quant4(v[12], v[13], v[14], v[15], s);
+        *reinterpret_cast<uint4*>(x8 + m * ldx8 + k) = o;
+    }
+}
+
+template <typename InT>
+__global__ void __launch_bounds__(256) quantize_act_scalar_kernel(const InT* __restrict__ x, int64_t M, int64_t K,
+                                                                  int64_t ldx, const float* __restrict__ scale,
+                                                                  uint8_t* __restrict__ x8, int64_t ldx8) {
+    const float s = *scale;
+    const int64_t total = M * K;
+    for (int64_t u = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; u < total; u += (int64_t)gridDim.x * blockDim.x) {
+        const int64_t m = u / K, k = u - m * K;
+        const float t = Load16<InT>::one(x + m * ldx + k) / s;
+        x8[m * ldx8 + k] = (uint8_t)(cvt2(t, 0.0f, 0u, false) & 0xFFu);
+    }
+}
+
+template <typename InT>
+int launch_t(const InT* x, int64_t M, int64_t K, int64_t ldx, const float* scale, uint8_t* x8, int64_t ldx8,
+             hipStream_t st) {
+    const bool vec = (K % 16 == 0) && (ldx % 16 == 0) && (ldx8 % 16 == 0) &&
+                     (reinterpret_cast<uintptr_t>(x) % 16 == 0) && (reinterpret_cast<uintptr_t>(x8) % 16 == 0);
+    const int64_t units = vec ? M * (K / 16) : M * K;
+    int64_t blocks = (units + 255) / 256;
+    if (blocks > 256 * 32) blocks = 256 * 32;     // grid-stride beyond 32 workgroups per compute unit
+    if (vec)
+        hipLaunchKernelGGL(quantize_act_vec_kernel<InT>, dim3((unsigned)blocks), dim3(256), 0, st, x, M, K / 16, ldx,
+                           scale, x8, ldx8);
+    else
+        hipLaunchKernelGGL(quantize_act_scalar_kernel<InT>, dim3((unsigned)blocks), dim3(256), 0, st, x, M, K, ldx,
+                           scale, x8, ldx8);
+    return launch_status();
+}
+
+}  // namespace
+
+int launch_quantize_act(const void* x, w4a8_dtype dt, int64_t M, int64_t K, int64_t ldx, const float* scale,
+                        uint8_t* x8, int64_t ldx8, hipStream_t st) {
+    if (dt == W4A8_F32) return launch_t(static_cast<const float*>(x), M, K, ldx, scale, x8, ldx8, st);
+    return launch_t(static_cast<const uint16_t*>(x), M, K, ldx, scale, x8, ldx8, st);
+}
+
+}  // namespace w4a8

@@ -1,0 +1,77 @@
+// Device-side helpers shared by the W4A8 kernels (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace w4a8 {
+
+typedef int v8i __attribute__((ext_vector_type(8)));
+typedef float v4f __attribute__((ext_vector_type(4)));
+
+// ---------------------------------------------------------------------------------------------
+// INT4 -> E4M3 (Eq. 10 with zero-point 0; the group scale is applied to the group's partial sum).
+// One dword holds eight two's-complement nibbles.  `lo` receives the E4M3 bytes of nibbles 0,2,4,6
+// (the low nibble of bytes 0..3), `hi` those of nibbles 1,3,5,7 (the high nibbles).
+// A nibble is split into its low three bits l and its top bit b3: the value is l when b3 = 0 and
+// l - 8 when b3 = 1.  Each case is an 8-entry byte table looked up with one v_perm_b32; a third
+// v_perm_b32 picks, byte by byte, the table that b3 names.
+//   value   0    1    2    3    4    5    6    7     |  -8   -7   -6   -5   -4   -3   -2   -1
+//   E4M3   00   38   40   44   48   4A   4C   4E     |  D0   CE   CC   CA   C8   C4   C0   B8
+// ---------------------------------------------------------------------------------------------
+__device__ __forceinline__ void nibbles_to_e4m3(uint32_t w, uint32_t& lo, uint32_t& hi) {
+    const uint32_t POS_LO = 0x44403800u, POS_HI = 0x4E4C4A48u;   // values 0..3, 4..7
+    const uint32_t NEG_LO = 0xCACCCED0u, NEG_HI = 0xB8C0C4C8u;   // values -8..-5, -4..-1
+    const uint32_t sel_l = w & 0x07070707u;
+    const uint32_t sel_h = (w >> 4) & 0x07070707u;
+    // v_perm_b32(S0, S1, sel): selector 0..3 -> bytes of S1, 4..7 -> bytes of S0
+    const uint32_t pos_l = __builtin_amdgcn_perm(POS_HI, POS_LO, sel_l);
+    const uint32_t neg_l = __builtin_amdgcn_perm(NEG_HI, NEG_LO, sel_l);
+    const uint32_t pos_h = __builtin_amdgcn_perm(POS_HI, POS_LO, sel_h);
+    const uint32_t neg_h = __builtin_amdgcn_perm(NEG_HI, NEG_LO, sel_h);
+    // byte i of the result = byte i of pos (selector i) or of neg (selector i + 4)
+    const uint32_t mix_l = ((w >> 1) & 0x04040404u) | 0x03020100u;
+    const uint32_t mix_h = ((w >> 5) & 0x04040404u) | 0x03020100u;
+    lo = __builtin_amdgcn_perm(neg_l, pos_l, mix_l);
+    hi = __builtin_amdgcn_perm(neg_h, pos_h, mix_h);
+}
+
+// The 16 bytes (four dwords) of one tiled-layout slot -> the 32 operand bytes of one lane, in the order the
+// layout defines: operand byte p (0..31) belongs to k = 32*kq + p.
+__device__ __forceinline__ v8i slot_to_operand(uint4 s) {
+    uint32_t r0, r1, r2, r3, r4, r5, r6, r7;
+    nibbles_to_e4m3(s.x, r0, r1);
+    nibbles_to_e4m3(s.y, r2, r3);
+    nibbles_to_e4m3(s.z, r4, r5);
+    nibbles_to_e4m3(s.w, r6, r7);
+    v8i v;
+    v[0] = (int)r0; v[1] = (int)r1; v[2] = (int)r2; v[3] = (int)r3;
+    v[4] = (int)r4; v[5] = (int)r5; v[6] = (int)r6; v[7] = (int)r7;
+    return v;
+}
+
+// D = A(16 x 128, E4M3) * B(128 x 16, E4M3) + C on the FP8 matrix unit, fp32 accumulation.
+// Lane l carries row (A) / column (B) l % 16 and the 32 contraction positions 32*(l/16) .. +31; the result
+// lane l carries column l % 16 and rows 4*(l/16) .. +3.
+__device__ __forceinline__ v4f mfma_16x16x128_e4m3(v8i a, v8i b, v4f c) {
+    return __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(a, b, c, 0 /*A: E4M3*/, 0 /*B: E4M3*/, 0, 0, 0, 0);
+}
+
+// float32 -> bf16 bits, round to nearest even (NaN stays NaN).
+__device__ __forceinline__ uint16_t f32_to_bf16_bits(float f) {
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7FFFFFFFu) > 0x7F800000u) return (uint16_t)((u >> 16) | 0x0040u);
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+
+__device__ __forceinline__ float bf16_bits_to_f32(uint16_t b) { return __uint_as_float(((uint32_t)b) << 16); }
+
+template <typename T> struct OutCast;
+template <> struct OutCast<float> {
+    static __device__ __forceinline__ float cast(float v) { return v; }
+};
+template <> struct OutCast<uint16_t> {
+    static __device__ __forceinline__ uint16_t cast(float v) { return f32_to_bf16_bits(v); }
+};
+
+}  // namespace w4a8

@@ -1,0 +1,121 @@
+"""Host-side checks of the C-ABI library: it loads, exports every function the header declares, and rejects bad
+arguments before anything is launched (so these run without a GPU; no compute call is made here)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2505_14638_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+P = 0x10000          # a non-NULL, 16-byte aligned dummy address; never dereferenced on the paths tested here
+
+
+@pytest.fixture(scope="module")
+def L():
+    if not os.path.exists(B.LIB_PATH):
+        from paper_2505_14638_amd import build
+        build.build()
+    return B.lib()
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "w4a8.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(w4a8_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_header_and_library_agree(L):
+    names = declared_functions()
+    assert {"w4a8_quantize_act", "w4a8_pack_weights", "w4a8_linear"} <= set(names)
+    for name in names:
+        assert hasattr(L, name), f"{name} declared in include/w4a8.h but not exported"
+        assert name in B.SIGNATURES, f"{name} has no ctypes signature in the binding"
+    assert sorted(B.SIGNATURES) == names
+
+
+def test_status_strings(L):
+    assert B.status_string(0) == "ok"
+    seen = {B.status_string(s) for s in range(0, 9)}
+    assert len(seen) == 9 and "unknown status" not in seen
+    assert B.status_string(99) == "unknown status"
+
+
+def test_sizes(L):
+    assert L.w4a8_packed_bytes(1024, 1024, B.LAYOUT_CANONICAL) == 1024 * 512
+    assert L.w4a8_packed_bytes(40, 384, B.LAYOUT_TILED) == 48 * 192
+    assert L.w4a8_packed_bytes(40, 100, B.LAYOUT_TILED) == 0            # K % 128 != 0
+    assert L.w4a8_scales_count(40, 384, 128, B.LAYOUT_TILED) == 48 * 3
+    assert L.w4a8_scales_count(40, 384, 384, B.LAYOUT_TILED) == 48
+    assert L.w4a8_scales_count(40, 384, 32, B.LAYOUT_CANONICAL) == 40 * 12
+    assert L.w4a8_scales_count(40, 384, 32, B.LAYOUT_TILED) == 0        # groups below 128 need the canonical layout
+    assert L.w4a8_scales_count(40, 384, 100, B.LAYOUT_CANONICAL) == 0
+    assert L.w4a8_linear_workspace_bytes(16, 4096, 4096, 128) == 0
+
+
+def test_quantize_act_validation(L):
+    f = L.w4a8_quantize_act
+    assert f(0, B.F32, 4, 64, 64, P, P, 64, None) == 1                  # NULL x
+    assert f(P, B.F32, 4, 64, 64, 0, P, 64, None) == 1                  # NULL scale
+    assert f(P, 7, 4, 64, 64, P, P, 64, None) == 4                      # dtype
+    assert f(P, B.F32, -1, 64, 64, P, P, 64, None) == 2
+    assert f(P, B.F32, 4, 64, 32, P, P, 64, None) == 2                  # ldx < K
+    assert f(P, B.F32, 4, 64, 64, P, P, 8, None) == 2                   # ldx8 < K
+    assert f(P + 2, B.F32, 4, 64, 64, P, P, 64, None) == 6              # misaligned float pointer
+    assert f(P, B.F32, 0, 64, 64, P, P, 64, None) == 0                  # M == 0: no-op
+
+
+def test_pack_validation(L):
+    f = L.w4a8_pack_weights
+    assert f(P, B.SRC_F32_RTN, 0, 16, 256, 128, B.LAYOUT_TILED, 0, P, None) == 1
+    assert f(P, B.SRC_I8_CODES, 0, 16, 256, 128, B.LAYOUT_TILED, P, P, None) == 1      # codes need scales
+    assert f(P, 5, 0, 16, 256, 128, B.LAYOUT_TILED, P, P, None) == 4
+    assert f(P, B.SRC_F32_RTN, 0, 16, 256, 100, B.LAYOUT_CANONICAL, P, P, None) == 3   # G does not divide K
+    assert f(P, B.SRC_F32_RTN, 0, 16, 256, 64, B.LAYOUT_TILED, P, P, None) == 3        # tiled needs G % 128 == 0
+    assert f(P, B.SRC_F32_RTN, 0, 16, 200, 200, B.LAYOUT_TILED, P, P, None) == 5       # tiled needs K % 128 == 0
+    assert f(P, B.SRC_F32_RTN, 0, 16, 255, 255, B.LAYOUT_CANONICAL, P, P, None) == 2   # odd K
+    assert f(P, B.SRC_F32_RTN, 0, 16, 256, 128, 9, P, P, None) == 5
+    assert f(P, B.SRC_F32_RTN, 0, 0, 256, 128, B.LAYOUT_TILED, P, P, None) == 2
+
+
+def test_linear_validation(L):
+    f = L.w4a8_linear
+    ok = dict(x8=P, M=4, K=256, ldx8=256, xs=P, packed=P, ws=P, N=64, G=128, layout=B.LAYOUT_TILED, y=P, ydt=B.BF16,
+              ldy=64)
+
+    def call(**kw):
+        a = {**ok, **kw}
+        return f(a["x8"], a["M"], a["K"], a["ldx8"], a["xs"], a["packed"], a["ws"], a["N"], a["G"], a["layout"],
+                 a["y"], a["ydt"], a["ldy"], None, 0, None)
+
+    assert call(M=0) == 0
+    for key in ("x8", "xs", "packed", "ws", "y"):
+        assert call(**{key: 0}) == 1, key
+    assert call(M=-3) == 2 and call(N=0) == 2 and call(K=0) == 2
+    assert call(ldx8=128) == 2 and call(ldy=32) == 2
+    assert call(G=96) == 3 and call(G=64) == 3
+    assert call(ydt=3) == 4
+    assert call(layout=4) == 5 and call(K=192, ldx8=192, G=192) == 5
+    assert call(x8=P + 4) == 6 and call(ldx8=264) == 6 and call(packed=P + 8) == 6
+    assert call(y=P + 1) == 6
+    assert call(layout=B.LAYOUT_CANONICAL, G=32, M=0) == 0
+    fv = L.w4a8_linear_variant
+    assert fv(P, 100, 256, 256, P, P, P, 64, 128, P, B.BF16, 64, 0, 1, 1, None) == 2   # skinny path needs M <= 64
+    assert fv(P, 4, 256, 256, P, P, P, 64, 128, P, B.BF16, 64, 7, 0, 0, None) == 2     # unknown path
+    assert fv(P, 0, 256, 256, P, P, P, 64, 128, P, B.BF16, 64, 0, 1, 1, None) == 0
+
+
+def test_other_validation(L):
+    assert L.w4a8_dequant_weights(0, 16, 256, B.LAYOUT_TILED, P, None) == 1
+    assert L.w4a8_dequant_weights(P, 16, 200, B.LAYOUT_TILED, P, None) == 5
+    assert L.w4a8_silu_mul(P, 4, 64, 64, P, 64, None) == 2              # ldgu < 2F
+    assert L.w4a8_silu_mul(0, 4, 64, 128, P, 64, None) == 1
+    assert L.w4a8_silu_mul(P, 0, 64, 128, P, 64, None) == 0
+
+
+def test_binding_fails_loudly_without_library(monkeypatch, tmp_path):
+    monkeypatch.setattr(B, "_lib", None)
+    monkeypatch.setattr(B, "LIB_PATH", str(tmp_path / "missing.so"))
+    with pytest.raises(RuntimeError, match="no fallback"):
+        B.lib()

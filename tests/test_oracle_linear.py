@@ -97,8 +97,8 @@ def test_tolerance_rule():
     a = np.array([[10.0, 10.0, 10.0]])
     assert o.within_tolerance(ref * (1 + 1.9e-3), ref, a)[0]
     assert not o.within_tolerance(ref * (1 + 2.1e-3), ref, a)[0]
-    assert o.within_tolerance(np.array([[1.0, 1.9e-5, -2.0]]), ref, a)[0]      # floor = 2e-3 * 1e-3 * A
-    assert not o.within_tolerance(np.array([[1.0, 2.1e-5, -2.0]]), ref, a)[0]
+    assert o.within_tolerance(np.array([[1.0, 3.0e-4, -2.0]]), ref, a)[0]      # floor = 2e-3 * 2^-6 * A = 3.125e-4
+    assert not o.within_tolerance(np.array([[1.0, 3.2e-4, -2.0]]), ref, a)[0]
 
 
 def test_paper_literal_mode():

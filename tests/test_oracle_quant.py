@@ -99,6 +99,7 @@ def test_tiled_pack_is_a_permutation_with_the_documented_positions():
     buf = o.pack_tiled(q)
     assert buf.size == 48 * k // 2
     assert np.array_equal(o.unpack_tiled(buf, n, k), q)
+    assert np.array_equal(buf, o.pack_tiled_by_offsets(q))          # reshape form == explicit offsets
     # hand-computed positions, straight from the layout's definition
     def at(nn, kk):
         t, i, c, kq, p = nn // 16, nn % 16, kk // 128, (kk % 128) // 32, kk % 32
