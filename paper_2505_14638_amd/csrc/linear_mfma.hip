@@ -1,15 +1,23 @@
 // W4A8 linear layer for many tokens (the compute-bound regime of Sec. 1): an MFMA-tiled GEMM with the INT4 -> E4M3
 // expansion (Eq. 10) fused in front of the FP8 matrix unit.
 //
-// A workgroup of four wavefronts computes a 128-token x 256-channel block of Y.  Each wavefront owns 64 channels
-// (four 16-row weight tiles) and all 128 tokens:
-//   - weights never touch LDS: per 128-deep chunk a lane loads its 16-byte slot of each of the four tiles straight
-//     from the tiled format (coalesced 1 KiB reads), expands it once to 32 E4M3 bytes and reuses that A operand for
+// A workgroup computes a 128-token x 256-channel block of Y.  Each wavefront owns TPW 16-row weight tiles and all
+// 128 tokens:
+//   - weights never touch LDS: per 128-deep chunk a lane loads its 16-byte slot of each of its tiles straight
+//     from the tiled format (coalesced 1 KiB reads), expands it once to 32 E4M3 bytes and reuses that operand for
 //     all eight 16-token blocks;
-//   - the activation block (128 tokens x 128 bytes) is shared by the four wavefronts through LDS, double
-//     buffered, stored in MFMA operand order so that the reads are two conflict-free ds_read_b128 per operand;
-//   - every 16x16x128 MFMA starts from a zero accumulator and its result is folded into the running sum with the
-//     fp32 group scale of the channel (four FMAs per MFMA), because group scales cannot be factored out of K.
+//   - the activation block (128 tokens x 128 bytes) is shared by the wavefronts through LDS, double
+//     buffered, filled by LDS-direct global loads (no staging registers) in MFMA operand order, so that the reads
+//     are two conflict-free ds_read_b128 per operand;
+//   - activations are the row operand and weights the column operand of the MFMA, so a result lane holds one
+//     channel: its group scale is a single register, and every 16x16x128 MFMA (started from a zero accumulator)
+//     is folded into the running sum with four FMAs against that scale -- group scales cannot be factored out
+//     of the sum over K;
+//   - the block of Y goes through LDS once at the end so that global stores are whole row segments.
+// The FMAs and the nibble expansion keep the vector ALU about as busy as the matrix unit; the kernel relies on
+// several resident wavefronts per SIMD (small register tiles) so that one wavefront's MFMAs overlap another's ALU work.
+// Workgroups are numbered so that the ones resident on one XCD (one L2) at a time cover a compact rectangle of
+// token blocks x channel blocks.
 #include "w4a8_device.hpp"
 #include "w4a8_internal.hpp"
 
@@ -17,51 +25,61 @@ namespace w4a8 {
 namespace {
 
 constexpr int BM = 128;             // tokens per workgroup
-constexpr int WAVES = 4;
-constexpr int TPW = 4;              // weight tiles (16 channels each) per wavefront
-constexpr int BN = WAVES * TPW * 16;
+constexpr int BN = 256;             // channels per workgroup
 constexpr int MF = BM / 16;         // 16-token operand blocks per workgroup
 constexpr int STAGE_BYTES = BM * 128;
+constexpr int XCDS = 8;
+constexpr int GROUP_M = 8;          // token blocks per super-column of the block order
 
-// LDS position of the 16-byte unit (row, u) of an activation block: operand order.
-// u = 2*kq + h: the lane (kq, row % 16) of block row / 16 reads halves h = 0, 1 at +0 and +1024.
-__device__ __forceinline__ int lds_unit_offset(int row, int u) {
-    return (row >> 4) * 2048 + (u & 1) * 1024 + ((u >> 1) * 16 + (row & 15)) * 16;
-}
-
-template <typename OutT>
-__global__ void __launch_bounds__(WAVES * 64) linear_mfma_kernel(
+// WAVES wavefronts per workgroup, each owning TPW = 16 / WAVES weight tiles (WN = 16 * TPW channels); OCC = wavefronts
+// per SIMD the register budget is sized for.
+template <typename OutT, int WAVES, int OCC>
+__global__ void __launch_bounds__(WAVES * 64, OCC) linear_mfma_kernel(
     const uint8_t* __restrict__ x8, int M, int64_t ldx8, const float* __restrict__ s_x,
-    const uint4* __restrict__ packed, const float* __restrict__ scales, int N, int n_tiles, int C, int cpg, int NG,
+    const uint8_t* __restrict__ packed, const float* __restrict__ scales, int N, int n_tiles, int C, int cpg, int NG,
     OutT* __restrict__ y, int64_t ldy, int grid_m, int grid_n) {
+    constexpr int TPW = (BN / 16) / WAVES, WN = TPW * 16;
+    constexpr int DMA_PER_WAVE = (2 * MF) / WAVES;               // 1 KiB half-blocks of activations staged per wavefront
     __shared__ __attribute__((aligned(16))) uint8_t xs[2][STAGE_BYTES];
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int kq = lane >> 4, i = lane & 15;
 
-    // block order: token blocks fastest, so that workgroups in flight together share weight tiles in L2
-    const int bm = blockIdx.x % grid_m, bn = blockIdx.x / grid_m;
+    // Block order.  Hardware deals consecutive workgroup ids round-robin to the eight XCDs; give each XCD a
+    // contiguous range of the virtual order, and make the virtual order walk GROUP_M token blocks per channel block.
+    const int total = grid_m * grid_n;
+    const int per_xcd = (gridDim.x + XCDS - 1) / XCDS;
+    const int v = (blockIdx.x % XCDS) * per_xcd + blockIdx.x / XCDS;
+    if (v >= total) return;
+    const int group = v / (GROUP_M * grid_n);
+    const int first_m = group * GROUP_M;
+    const int rows_in_group = min(GROUP_M, grid_m - first_m);
+    const int in_group = v - group * GROUP_M * grid_n;
+    const int bm = first_m + in_group % rows_in_group, bn = in_group / rows_in_group;
     const int m0 = bm * BM;
-    const int t0 = bn * (WAVES * TPW) + wave * TPW;
+    const int t0 = bn * (BN / 16) + wave * TPW;
 
-    const uint4* wp[TPW];
-    const float4* sp[TPW];
+    const uint8_t* wbase[TPW];
+    const uint8_t* sbase[TPW];
 #pragma unroll
     for (int j = 0; j < TPW; ++j) {
-        const int t = min(t0 + j, n_tiles - 1);
-        wp[j] = packed + (int64_t)t * C * 64 + lane;
-        sp[j] = reinterpret_cast<const float4*>(scales + (int64_t)t * NG * 16 + 4 * kq);
+        const int t = min(t0 + j, n_tiles - 1);                  // tiles past the end reload the last one; not stored
+        wbase[j] = packed + (int64_t)t * C * 1024;
+        sbase[j] = reinterpret_cast<const uint8_t*>(scales) + (int64_t)t * NG * 64;
     }
+    const uint32_t woff = lane * 16, soff = i * 4;
 
-    // activation staging: thread -> (row within a pass of 32 rows, 16-byte unit); four passes cover 128 rows
-    const int ld_row = tid >> 3, ld_u = tid & 7;
-    const uint8_t* xg[4];
-    int xo[4];
+    // activation staging: LDS-direct loads.  One wave-wide 16-byte load fills 1 KiB of LDS in lane order, which is
+    // exactly one half (h) of one operand block (f): lane (kq, i) fetches bytes 32*kq + 16*h .. +15 of token row
+    // 16*f + i.  The 16 half-blocks are dealt evenly to the wavefronts.  Rows past the end reload the last row; never stored.
+    uint32_t xvoff[DMA_PER_WAVE];
 #pragma unroll
-    for (int p = 0; p < 4; ++p) {
-        const int row = p * 32 + ld_row;
-        xg[p] = x8 + (int64_t)min(m0 + row, M - 1) * ldx8 + ld_u * 16;
-        xo[p] = lds_unit_offset(row, ld_u);
+    for (int q = 0; q < DMA_PER_WAVE; ++q) {
+        const int d = wave * DMA_PER_WAVE + q;                   // half-block index: f = d / 2, h = d % 2
+        const int row = (d >> 1) * 16 + i;
+        xvoff[q] = (uint32_t)(min(m0 + row, M - 1) - m0) * (uint32_t)ldx8 + kq * 32 + (d & 1) * 16;
     }
+    const uint8_t* xrow0 = x8 + (int64_t)m0 * ldx8;              // wave-uniform
 
     v4f acc[MF][TPW];
 #pragma unroll
@@ -69,34 +87,38 @@ __global__ void __launch_bounds__(WAVES * 64) linear_mfma_kernel(
 #pragma unroll
         for (int j = 0; j < TPW; ++j) acc[f][j] = v4f{0.f, 0.f, 0.f, 0.f};
 
-    uint4 xreg[4], wreg[TPW];
-    float4 sreg[TPW];
-    auto global_loads = [&](int c) {
+    uint4 wreg[TPW];
+    float sreg[TPW];
+    int g = 0, g_left = cpg;                                     // group of the chunk being loaded, chunks left in it
+    auto global_loads = [&](int c, int buf) {
+        const uint8_t* xsrc = xrow0 + (int64_t)c * 128;
 #pragma unroll
-        for (int p = 0; p < 4; ++p) xreg[p] = *reinterpret_cast<const uint4*>(xg[p] + (int64_t)c * 128);
+        for (int q = 0; q < DMA_PER_WAVE; ++q)
+            __builtin_amdgcn_global_load_lds(
+                (const __attribute__((address_space(1))) void*)(xsrc + xvoff[q]),
+                (__attribute__((address_space(3))) void*)&xs[buf][(wave * DMA_PER_WAVE + q) * 1024], 16, 0, 0);
 #pragma unroll
         for (int j = 0; j < TPW; ++j) {
-            wreg[j] = wp[j][(int64_t)c * 64];
-            sreg[j] = sp[j][(c / cpg) * 4];
+            wreg[j] = *reinterpret_cast<const uint4*>(wbase[j] + (int64_t)c * 1024 + woff);
+            sreg[j] = *reinterpret_cast<const float*>(sbase[j] + (int64_t)g * 64 + soff);
         }
+        if (--g_left == 0) { ++g; g_left = cpg; }
     };
 
-    global_loads(0);
-#pragma unroll
-    for (int p = 0; p < 4; ++p) *reinterpret_cast<uint4*>(&xs[0][xo[p]]) = xreg[p];
+    global_loads(0, 0);
     __syncthreads();
 
     for (int c = 0; c < C; ++c) {
         const int buf = c & 1;
         v8i wop[TPW];
-        float4 s[TPW];
+        float s[TPW];
 #pragma unroll
         for (int j = 0; j < TPW; ++j) {
             wop[j] = slot_to_operand(wreg[j]);
             s[j] = sreg[j];
         }
         const bool more = (c + 1 < C);
-        if (more) global_loads(c + 1);
+        if (more) global_loads(c + 1, buf ^ 1);
         const uint8_t* xb = &xs[buf][lane * 16];
 #pragma unroll
         for (int f = 0; f < MF; ++f) {
@@ -105,34 +127,49 @@ __global__ void __launch_bounds__(WAVES * 64) linear_mfma_kernel(
             const v8i xop = v8i{(int)a.x, (int)a.y, (int)a.z, (int)a.w, (int)b.x, (int)b.y, (int)b.z, (int)b.w};
 #pragma unroll
             for (int j = 0; j < TPW; ++j) {
-                const v4f p = mfma_16x16x128_e4m3(wop[j], xop, v4f{0.f, 0.f, 0.f, 0.f});
-                acc[f][j][0] = fmaf(s[j].x, p[0], acc[f][j][0]);
-                acc[f][j][1] = fmaf(s[j].y, p[1], acc[f][j][1]);
-                acc[f][j][2] = fmaf(s[j].z, p[2], acc[f][j][2]);
-                acc[f][j][3] = fmaf(s[j].w, p[3], acc[f][j][3]);
+                // rows = tokens (activations), columns = channels (weights)
+                const v4f p = mfma_16x16x128_e4m3(xop, wop[j], v4f{0.f, 0.f, 0.f, 0.f});
+                acc[f][j][0] = fmaf(s[j], p[0], acc[f][j][0]);
+                acc[f][j][1] = fmaf(s[j], p[1], acc[f][j][1]);
+                acc[f][j][2] = fmaf(s[j], p[2], acc[f][j][2]);
+                acc[f][j][3] = fmaf(s[j], p[3], acc[f][j][3]);
             }
-        }
-        if (more) {
-#pragma unroll
-            for (int p = 0; p < 4; ++p) *reinterpret_cast<uint4*>(&xs[buf ^ 1][xo[p]]) = xreg[p];
         }
         __syncthreads();
     }
 
-    // result lane: token = lane % 16 of block f, channels 4*kq .. 4*kq+3 of tile j
+    // Epilogue.  Result lane: channel = lane % 16 of tile j, tokens 4*kq .. 4*kq+3 of block f.  Each wavefront
+    // turns one 16-token x WN-channel slab at a time into row-major order in its own LDS region and stores rows.
     const float sx = *s_x;
+    constexpr int RS = WN + 16 / sizeof(OutT);                                 // row stride: rows stay 16-byte aligned
+    OutT* slab = reinterpret_cast<OutT*>(&xs[0][0]) + wave * (16 * RS);       // 16 rows per wavefront
+    constexpr int VEC = 16 / sizeof(OutT);                                     // elements per 16-byte store
+    constexpr int LANES_PER_ROW = WN / VEC;
+    constexpr int ROWS_PER_PASS = 64 / LANES_PER_ROW;
+    const int n_wave = t0 * 16;
+    const bool vec_ok = (ldy % VEC == 0) && (reinterpret_cast<uintptr_t>(y) % 16 == 0);
 #pragma unroll
     for (int f = 0; f < MF; ++f) {
-        const int m = m0 + f * 16 + i;
-        if (m >= M) continue;
 #pragma unroll
-        for (int j = 0; j < TPW; ++j) {
-            const int n = (t0 + j) * 16 + 4 * kq;
-            OutT* dst = y + (int64_t)m * ldy + n;
+        for (int j = 0; j < TPW; ++j)
 #pragma unroll
-            for (int r = 0; r < 4; ++r)
-                if (n + r < N) dst[r] = OutCast<OutT>::cast(sx * acc[f][j][r]);
+            for (int r = 0; r < 4; ++r) slab[(4 * kq + r) * RS + 16 * j + i] = OutCast<OutT>::cast(sx * acc[f][j][r]);
+        __builtin_amdgcn_wave_barrier();
+#pragma unroll
+        for (int pass = 0; pass < 16 / ROWS_PER_PASS; ++pass) {
+            const int row = pass * ROWS_PER_PASS + lane / LANES_PER_ROW, col = (lane % LANES_PER_ROW) * VEC;
+            const int m = m0 + f * 16 + row, n = n_wave + col;
+            if (m < M && n < N) {
+                OutT* dst = y + (int64_t)m * ldy + n;
+                const OutT* src = slab + row * RS + col;
+                if (vec_ok && n + VEC <= N) {
+                    *reinterpret_cast<uint4*>(dst) = *reinterpret_cast<const uint4*>(src);
+                } else {
+                    for (int e = 0; e < VEC && n + e < N; ++e) dst[e] = src[e];
+                }
+            }
         }
+        __builtin_amdgcn_wave_barrier();
     }
 }
 
@@ -141,19 +178,23 @@ __global__ void __launch_bounds__(WAVES * 64) linear_mfma_kernel(
 int launch_linear_mfma_tiled(const uint8_t* x8, int64_t M, int64_t K, int64_t ldx8, const float* s_x,
                              const uint8_t* packed, const float* scales, int64_t N, int32_t G, void* y,
                              w4a8_dtype ydt, int64_t ldy, int variant, hipStream_t st) {
-    if (variant != 0) return W4A8_ERR_SHAPE;
+    if (variant != 0 && variant != 1) return W4A8_ERR_SHAPE;
     const int C = (int)(K / 128), cpg = G / 128, NG = (int)(K / G);
     const int n_tiles = (int)((N + 15) / 16);
     const int grid_m = (int)((M + BM - 1) / BM), grid_n = (n_tiles * 16 + BN - 1) / BN;
-    const dim3 grid((unsigned)grid_m * (unsigned)grid_n), block(WAVES * 64);
-    if (ydt == W4A8_F32)
-        hipLaunchKernelGGL(linear_mfma_kernel<float>, grid, block, 0, st, x8, (int)M, ldx8, s_x,
-                           reinterpret_cast<const uint4*>(packed), scales, (int)N, n_tiles, C, cpg, NG,
-                           static_cast<float*>(y), ldy, grid_m, grid_n);
-    else
-        hipLaunchKernelGGL(linear_mfma_kernel<uint16_t>, grid, block, 0, st, x8, (int)M, ldx8, s_x,
-                           reinterpret_cast<const uint4*>(packed), scales, (int)N, n_tiles, C, cpg, NG,
-                           static_cast<uint16_t*>(y), ldy, grid_m, grid_n);
+    const int64_t total = (int64_t)grid_m * grid_n;
+    if (total > (1 << 30)) return W4A8_ERR_SHAPE;
+    if (ldx8 >= (1 << 25)) return W4A8_ERR_SHAPE;               // 32-bit activation offsets inside a token block
+    const dim3 grid((unsigned)((total + XCDS - 1) / XCDS * XCDS));
+#define W4A8_LAUNCH_MFMA(T, WV, OC)                                                                                  \
+    hipLaunchKernelGGL((linear_mfma_kernel<T, WV, OC>), grid, dim3(WV * 64), 0, st, x8, (int)M, ldx8, s_x, packed,   \
+                       scales, (int)N, n_tiles, C, cpg, NG, static_cast<T*>(y), ldy, grid_m, grid_n)
+    if (variant == 0) {
+        if (ydt == W4A8_F32) W4A8_LAUNCH_MFMA(float, 8, 4); else W4A8_LAUNCH_MFMA(uint16_t, 8, 4);
+    } else {
+        if (ydt == W4A8_F32) W4A8_LAUNCH_MFMA(float, 4, 2); else W4A8_LAUNCH_MFMA(uint16_t, 4, 2);
+    }
+#undef W4A8_LAUNCH_MFMA
     return launch_status();
 }
 

@@ -29,41 +29,49 @@ constexpr int max_threads(int tiles) { return tiles <= 4 ? 1024 : (tiles <= 8 ? 
 template <int MT, int NT, typename OutT>
 __global__ void __launch_bounds__(max_threads(MT * NT)) linear_skinny_kernel(
     const uint8_t* __restrict__ x8, int M, int64_t ldx8, const float* __restrict__ s_x,
-    const uint4* __restrict__ packed, const float* __restrict__ scales, int N, int n_tiles, int C, int cpg, int NG,
+    const uint8_t* __restrict__ packed, const float* __restrict__ scales, int N, int n_tiles, int C, int cpg, int NG,
     OutT* __restrict__ y, int64_t ldy, int cpw) {
     extern __shared__ float red[];
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, waves = blockDim.x >> 6;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);     // wave-uniform: keeps the loop scalar
+    const int waves = blockDim.x >> 6;
     const int i = lane & 15, kq = lane >> 4;
     const int t0 = blockIdx.x * NT;
     const int c_begin = wave * cpw;
     const int c_end = min(C, c_begin + cpw);
 
-    const uint4* wp[NT];
-    const float4* sp[NT];
+    // wave-uniform base pointers (advance by one chunk per step) plus small per-lane offsets
+    const uint8_t* wbase[NT];
+    const uint8_t* sbase[NT];
 #pragma unroll
     for (int j = 0; j < NT; ++j) {
         const int t = min(t0 + j, n_tiles - 1);                  // tiles past the end reload the last one; not stored
-        wp[j] = packed + (int64_t)t * C * 64 + lane;
-        sp[j] = reinterpret_cast<const float4*>(scales + (int64_t)t * NG * 16 + 4 * kq);
+        wbase[j] = packed + ((int64_t)t * C + c_begin) * 1024;
+        sbase[j] = reinterpret_cast<const uint8_t*>(scales) + (int64_t)t * NG * 64;
     }
-    const uint4* xp[MT];
+    const uint32_t woff = lane * 16, soff = kq * 16;
+    const uint8_t* xp[MT];
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) {
         const int m = min(mt * 16 + i, M - 1);                   // rows past the end reload the last one; not stored
-        xp[mt] = reinterpret_cast<const uint4*>(x8 + (int64_t)m * ldx8 + kq * 32);
+        xp[mt] = x8 + (int64_t)m * ldx8 + kq * 32 + (int64_t)c_begin * 128;
     }
+    int g = c_begin / cpg, g_left = cpg - (c_begin - g * cpg);   // current group and chunks left in it
 
-    auto load_chunk = [&](int c, ChunkLoads<MT, NT>& L) {
+    auto load_chunk = [&](ChunkLoads<MT, NT>& L) {
 #pragma unroll
         for (int j = 0; j < NT; ++j) {
-            L.w[j] = wp[j][(int64_t)c * 64];
-            L.s[j] = sp[j][(c / cpg) * 4];
+            L.w[j] = *reinterpret_cast<const uint4*>(wbase[j] + woff);
+            L.s[j] = *reinterpret_cast<const float4*>(sbase[j] + (int64_t)g * 64 + soff);
+            wbase[j] += 1024;
         }
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt) {
-            L.x[mt][0] = xp[mt][c * 8];
-            L.x[mt][1] = xp[mt][c * 8 + 1];
+            L.x[mt][0] = *reinterpret_cast<const uint4*>(xp[mt]);
+            L.x[mt][1] = *reinterpret_cast<const uint4*>(xp[mt] + 16);
+            xp[mt] += 128;
         }
+        if (--g_left == 0) { ++g; g_left = cpg; }
     };
 
     v4f acc[MT][NT];
@@ -72,33 +80,50 @@ __global__ void __launch_bounds__(max_threads(MT * NT)) linear_skinny_kernel(
 #pragma unroll
         for (int j = 0; j < NT; ++j) acc[mt][j] = v4f{0.f, 0.f, 0.f, 0.f};
 
-    if (c_begin < c_end) {
-        ChunkLoads<MT, NT> cur, nxt;
-        load_chunk(c_begin, cur);
-        for (int c = c_begin; c < c_end; ++c) {
-            const bool more = (c + 1 < c_end);
-            if (more) load_chunk(c + 1, nxt);
-            v8i xop[MT];
+    auto compute_chunk = [&](const ChunkLoads<MT, NT>& L) {
+        v8i xop[MT];
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) {
+            const uint4 a = L.x[mt][0], b = L.x[mt][1];
+            xop[mt] = v8i{(int)a.x, (int)a.y, (int)a.z, (int)a.w, (int)b.x, (int)b.y, (int)b.z, (int)b.w};
+        }
+#pragma unroll
+        for (int j = 0; j < NT; ++j) {
+            const v8i wop = slot_to_operand(L.w[j]);
+            const float4 s = L.s[j];
 #pragma unroll
             for (int mt = 0; mt < MT; ++mt) {
-                const uint4 a = cur.x[mt][0], b = cur.x[mt][1];
-                xop[mt] = v8i{(int)a.x, (int)a.y, (int)a.z, (int)a.w, (int)b.x, (int)b.y, (int)b.z, (int)b.w};
+                const v4f p = mfma_16x16x128_e4m3(wop, xop[mt], v4f{0.f, 0.f, 0.f, 0.f});
+                acc[mt][j][0] = fmaf(s.x, p[0], acc[mt][j][0]);
+                acc[mt][j][1] = fmaf(s.y, p[1], acc[mt][j][1]);
+                acc[mt][j][2] = fmaf(s.z, p[2], acc[mt][j][2]);
+                acc[mt][j][3] = fmaf(s.w, p[3], acc[mt][j][3]);
             }
-#pragma unroll
-            for (int j = 0; j < NT; ++j) {
-                const v8i wop = slot_to_operand(cur.w[j]);
-                const float4 s = cur.s[j];
-#pragma unroll
-                for (int mt = 0; mt < MT; ++mt) {
-                    const v4f p = mfma_16x16x128_e4m3(wop, xop[mt], v4f{0.f, 0.f, 0.f, 0.f});
-                    acc[mt][j][0] = fmaf(s.x, p[0], acc[mt][j][0]);
-                    acc[mt][j][1] = fmaf(s.y, p[1], acc[mt][j][1]);
-                    acc[mt][j][2] = fmaf(s.z, p[2], acc[mt][j][2]);
-                    acc[mt][j][3] = fmaf(s.w, p[3], acc[mt][j][3]);
-                }
-            }
-            if (more) cur = nxt;
         }
+    };
+
+    // two chunks in flight per wavefront, ping-pong between two register sets (no copies)
+    int left = c_end - c_begin;
+    if (left > 0) {
+        ChunkLoads<MT, NT> b0, b1;
+        load_chunk(b0);
+        if (left > 1) load_chunk(b1);
+        while (left > 2) {
+            compute_chunk(b0);
+            load_chunk(b0);
+            if (left > 3) {
+                compute_chunk(b1);
+                load_chunk(b1);
+            } else {
+                compute_chunk(b1);
+                compute_chunk(b0);
+                left = 0;
+                break;
+            }
+            left -= 2;
+        }
+        if (left > 0) compute_chunk(b0);
+        if (left > 1) compute_chunk(b1);
     }
 
     // sum the wavefronts' partials through LDS: red[wave][e = (mt*NT + j)*4 + r][lane]
@@ -132,7 +157,7 @@ int launch_one(const uint8_t* x8, int M, int64_t ldx8, const float* s_x, const u
     const int cpw = (C + waves - 1) / waves;
     const size_t lds = (size_t)waves * MT * NT * 4 * RED_STRIDE * sizeof(float);
     hipLaunchKernelGGL((linear_skinny_kernel<MT, NT, OutT>), dim3(grid), dim3(waves * 64), lds, st, x8, M, ldx8, s_x,
-                       reinterpret_cast<const uint4*>(packed), scales, N, n_tiles, C, cpg, NG, static_cast<OutT*>(y),
+                       packed, scales, N, n_tiles, C, cpg, NG, static_cast<OutT*>(y),
                        ldy, cpw);
     return launch_status();
 }
@@ -167,11 +192,11 @@ int launch_linear_skinny(const uint8_t* x8, int64_t M, int64_t K, int64_t ldx8, 
     const int C = (int)(K / 128), cpg = G / 128, NG = (int)(K / G);
     const int n_tiles = (int)((N + 15) / 16);
     const int mt = (M <= 16) ? 1 : (M <= 32) ? 2 : 4;
-    if (nt == 0) nt = ((int64_t)n_tiles * C >= 32768 && mt <= 2) ? 2 : 1;
+    if (nt == 0) nt = (M > 8 && n_tiles >= 1024) ? 2 : 1;       // two tiles share each activation operand when it is wide
     if (nt != 1 && nt != 2 && nt != 4) return W4A8_ERR_SHAPE;
     if (waves == 0) {
         const int grid = (n_tiles + nt - 1) / nt;
-        waves = (4096 + grid - 1) / grid;                        // aim at ~16 wavefronts per compute unit
+        waves = ((nt == 1 ? 6144 : 3072) + grid - 1) / grid;     // enough wavefronts in flight to cover HBM latency
         if (waves > 16) waves = 16;
     }
     if (waves > C) waves = C;

@@ -171,6 +171,7 @@ def test_config1_single_layer(gpu_lib):
     (64, 256, 48, 256, None), (65, 384, 40, 128, None), (130, 512, 300, 128, None), (300, 1024, 520, 512, None),
     (7, 1024, 96, 128, (0, 1, 1)), (7, 1024, 96, 128, (0, 2, 3)), (20, 1024, 96, 128, (0, 4, 2)),
     (50, 2048, 144, 128, (0, 4, 4)), (33, 2048, 64, 128, (0, 1, 16)), (9, 384, 40, 128, (1, 0, 0)),
+    (9, 384, 40, 128, (1, 1, 0)), (300, 1024, 520, 512, (1, 1, 0)), (129, 256, 272, 128, (1, 0, 0)),
 ])
 def test_linear_small_ragged(gpu_lib, m, k, n, g, path):
     """Several tiles, ragged tails in M and N, group sizes of one or more chunks, both kernels."""
@@ -187,7 +188,7 @@ def test_linear_small_ragged(gpu_lib, m, k, n, g, path):
     check_outputs(y32, y16, ref, a, f"ragged {m}x{k}x{n} g{g} {path}")
 
 
-@pytest.mark.parametrize("m,path", [(3, None), (16, (0, 2, 4)), (48, None), (200, None)])
+@pytest.mark.parametrize("m,path", [(3, None), (16, (0, 2, 4)), (48, None), (200, None), (200, (1, 1, 0))])
 def test_linear_exact_integer_case_bit_for_bit(gpu_lib, m, path):
     """Small-integer activations, all sixteen codes, power-of-two scales: every partial sum is an integer (or a
     dyadic rational) below 2^24, so fp32 accumulation is exact in any order and the fp32 output must equal the
