@@ -90,29 +90,88 @@ def time_graphs(graphs, reps, warmup):
     return t0.elapsed_time(t1) * 1e-3
 
 
-def cpu_baseline():
-    """The oracle as it stands, timed on this host: quantize + linear for the four layer shapes at M = 16."""
+def cpu_baseline(min_seconds=10.0):
+    """The oracle as it stands, timed on this host: quantize + linear for the decode sweep's layer shapes (the four
+    (K, N) pairs at M = 1, 4, 16, in sweep order), repeated until at least `min_seconds` of oracle time."""
     from oracle import w4a8_oracle as o
     try:
         from threadpoolctl import threadpool_info
         threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
     except Exception:
         threads = os.cpu_count() or 1
-    total_bytes, total_t = 0, 0.0
+    cases = []
     for idx, (k, n) in enumerate(syn.LLAMA3_8B.values()):
         rng = syn.rng_for(2, idx, 1234)
         q = rng.integers(-7, 8, size=(n, k)).astype(np.int8)           # codes with the range of RTN output
         s_w = rng.uniform(0.005, 0.02, size=(n, k // G)).astype(np.float32)
-        x = syn.make_activations(rng, 16, k, 0.01, 20.0)
-        s_x = syn.static_act_scale(x)
+        for m in (1, 4, 16):
+            x = syn.make_activations(rng, m, k, 0.01, 20.0)
+            cases.append((m, k, n, q, s_w, x, syn.static_act_scale(x)))
+    total_bytes, total_t, done = 0, 0.0, 0
+    while total_t < min_seconds:
+        m, k, n, q, s_w, x, s_x = cases[done % len(cases)]
         t = time.perf_counter()
         x8 = o.quantize_act(x, s_x)
         o.linear_ref(x8, s_x, q, s_w, G)
         total_t += time.perf_counter() - t
-        total_bytes += alg_bytes(16, k, n)
-    return {"value": total_bytes / total_t / 1e9, "unit": "GB/s", "cores": int(threads), "kind": "oracle",
-            "sample": "oracle quantize_act + linear_ref (fp64) on the four Llama-3-8B layer shapes at M=16, once each; "
-                      "same algorithmic-byte count as the GPU metric", "seconds": round(total_t, 3)}
+        total_bytes += alg_bytes(m, k, n)
+        done += 1
+    return {"value": round(total_bytes / total_t / 1e9, 4), "unit": "GB/s", "cores": int(threads), "kind": "oracle",
+            "sample": f"oracle quantize_act + linear_ref (fp64, numpy) over {done} layer passes of the decode sweep "
+                      f"(12 cases in order, wrapping around), {total_t:.1f} s of oracle time; same algorithmic-byte count "
+                      "as the GPU metric", "seconds": round(total_t, 2)}
+
+
+def measured_ceilings(dev):
+    """Achievable HBM read bandwidth and FP8 MFMA rate of this device, from the library's probe kernels."""
+    sink = torch.zeros(4, dtype=torch.float32, device=dev)
+    buf = torch.empty(1 << 30, dtype=torch.uint8, device=dev).fill_(1)
+    t0, t1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    B.probe_stream_read(buf, sink)
+    torch.cuda.synchronize()
+    t0.record()
+    for _ in range(5):
+        B.probe_stream_read(buf, sink)
+    t1.record()
+    torch.cuda.synchronize()
+    gbs = 5 * buf.numel() / (t0.elapsed_time(t1) * 1e-3) / 1e9
+    del buf
+    flop = B.probe_mfma(2000, sink)
+    torch.cuda.synchronize()
+    t0.record()
+    for _ in range(3):
+        B.probe_mfma(2000, sink)
+    t1.record()
+    torch.cuda.synchronize()
+    tfl = 3 * flop / (t0.elapsed_time(t1) * 1e-3) / 1e12
+    return round(gbs, 1), round(tfl, 1)
+
+
+def block_latency(dev, steps, warmup):
+    """Config 5: latency of the decoder-block linear stack per batch size, HIP graph replay."""
+    from paper_2505_14638_amd.block import LAYERS, DecoderBlockLinears
+    cfg = syn.CONFIGS[5]
+    blk = DecoderBlockLinears(cfg["hidden"], cfg["ffn"], syn.LLAMA3_8B["qkv"][1], cfg["group"], dev)
+    for idx, name in enumerate(LAYERS):
+        k, n = blk.dims[name]
+        blk.load_layer(name, torch.from_numpy(syn.make_weights(syn.rng_for(5, idx), n, k)))
+    for name, s in zip(LAYERS, (0.19, 0.012, 0.004, 0.0006)):          # typical static scales of this block
+        blk.set_act_scale(name, s)
+    out = {}
+    for m in cfg["batches"]:
+        x = syn.make_activations(syn.rng_for(5, 200 + m), m, cfg["hidden"], cfg["frac"], cfg["mult"])
+        x_d = torch.from_numpy(x).to(dev).to(torch.bfloat16)
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            blk.forward(x_d)
+            torch.cuda.synchronize()
+            g = capture(lambda: blk.forward(x_d))
+            sec = time_graphs([g], steps, warmup)
+        out[str(m)] = round(sec / steps * 1e6, 2)
+    return {"metric": "decoder-block linear stack latency (config 5: QKV, O, gate|up, SiLU*mul, down; hidden 4096, "
+                      "FFN 14336)", "unit": "us per block", "by_batch": out,
+            "note": "one weight set, so at small batch part of the 116 MB of weights is served by the 256 MB cache"}
 
 
 def main():
@@ -123,6 +182,7 @@ def main():
     ap.add_argument("--copies", type=int, default=4, help="distinct weight sets per layer shape (cache defeat)")
     ap.add_argument("--no-prefill", action="store_true")
     ap.add_argument("--no-cpu", action="store_true")
+    ap.add_argument("--no-block", action="store_true")
     ap.add_argument("--prefill-only", action="store_true", help="profiling aid: run only the prefill sweep")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -206,6 +266,16 @@ def main():
                                           "unit": "TFLOP/s", "frac": round(tfl / FP8_PEAK_TFLOPS, 4), "traffic": None,
                                           "kernel": "linear_mfma_kernel"}}
 
+    if not args.prefill_only:
+        hbm, mfma = measured_ceilings(dev)
+        result["measured_ceilings"] = {"stream_read_GBps": hbm, "mfma_e4m3_TFLOPs": mfma}
+        result["roofline"]["frac_of_measured"] = round(result["roofline"]["achieved"] / hbm, 4)
+        if "prefill" in result:
+            result["prefill"]["roofline"]["frac_of_measured"] = round(result["prefill"]["roofline"]["achieved"] / mfma, 4)
+        del layers
+        torch.cuda.empty_cache()
+        if not args.no_block:
+            result["block"] = block_latency(dev, 50, 5)
     if not args.no_cpu and not args.prefill_only:
         result["cpu_baseline"] = cpu_baseline()
     print(json.dumps(result))

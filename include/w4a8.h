@@ -118,7 +118,8 @@ int w4a8_linear(const uint8_t* x8_dev, int64_t M, int64_t K, int64_t ldx8, const
 /*
  * Same as w4a8_linear for W4A8_LAYOUT_TILED with the launch shape chosen by the caller; for tuning sweeps.
  *   path    0 = skinny (M <= 64), 1 = MFMA-tiled
- *   param0  skinny: n-tiles (of 16 rows) per wave, 1, 2 or 4.   tiled: reserved, pass 0
+ *   param0  skinny: n-tiles (of 16 rows) per wave, 1, 2 or 4.   tiled: 0 auto, 1 four wavefronts per workgroup,
+ *           2 token blocks of 64, 3 token blocks of 128
  *   param1  skinny: waves per workgroup (K is split across them), 1..16.   tiled: reserved, pass 0
  * Unsupported combinations return W4A8_ERR_SHAPE.
  */
@@ -141,6 +142,19 @@ int w4a8_dequant_weights(const uint8_t* packed_dev, int64_t N, int64_t K, w4a8_l
  * Computed in fp32: silu(g) = g / (1 + exp(-g)).
  */
 int w4a8_silu_mul(const void* gu_dev, int64_t M, int64_t F, int64_t ldgu, void* h_dev, int64_t ldh, void* stream);
+
+/*
+ * Measurement aids (not part of the layer): the two hardware ceilings the kernels are compared with, measured
+ * on the device at hand.  Time the calls with events on `stream`.
+ *   w4a8_probe_stream_read  loads every 16 bytes of buf_dev[0 .. bytes) once; bytes / time is the achievable HBM
+ *                           read bandwidth when `bytes` is far larger than the caches.  sink_dev: 4 bytes, scratch.
+ *   w4a8_probe_mfma_e4m3    issues back-to-back 16x16x128 E4M3 MFMAs on independent accumulators from two
+ *                           workgroups per compute unit; w4a8_probe_mfma_flop(iters) / time is the achievable dense
+ *                           FP8 MFMA rate.  sink_dev: 4 bytes, scratch.  1 <= iters <= 2^20.
+ */
+int w4a8_probe_stream_read(const void* buf_dev, size_t bytes, uint32_t* sink_dev, void* stream);
+int w4a8_probe_mfma_e4m3(int32_t iters, float* sink_dev, void* stream);
+double w4a8_probe_mfma_flop(int32_t iters);
 
 /* Static, NUL-terminated description of a status value. */
 const char* w4a8_status_string(int status);

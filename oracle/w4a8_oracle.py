@@ -31,7 +31,8 @@ linear_ref                   Eq. 10, Eq. 4 and Eq. 11: Y = X_hat . W_hat^T
 linear_ref_paper_literal     Eq. 6-11 read literally: the product code*scale is
                              itself rounded onto the E4M3 grid before the matmul
 pack_* / unpack_*            storage formats of the C-ABI boundary
-silu_mul_ref, block_ref      the decoder-block linear stack workload
+silu_mul_ref, block_ref,     the decoder-block linear stack workload (static scales
+calibrate_block_scales       by Eq. 13 on the oracle's own intermediates)
 
 Every function above is pinned by tests that do not use the function itself as
 the expected value (brute force over all 256 codes, exact rational arithmetic,
@@ -350,7 +351,8 @@ def silu_mul_ref(gate_up_bf16_bits, ffn: int) -> np.ndarray:
     """h = silu(gate) * up in float64; gate = first `ffn` columns, up = the next `ffn`."""
     gu = bf16_bits_to_f32(gate_up_bf16_bits).astype(np.float64)
     g, u = gu[:, :ffn], gu[:, ffn:2 * ffn]
-    return g / (1.0 + np.exp(-g)) * u
+    with np.errstate(over="ignore"):
+        return g / (1.0 + np.exp(-g)) * u
 
 
 def block_ref(x_bf16_bits, layers, scales_x, group_size: int, hidden: int, ffn: int):
@@ -377,3 +379,22 @@ def block_ref(x_bf16_bits, layers, scales_x, group_size: int, hidden: int, ffn: 
     out["h"] = round_to_bf16_bits(silu_mul_ref(gu, ffn))
     lin("down", out["h"])
     return out
+
+
+def calibrate_block_scales(x_bf16_bits, layers, group_size: int, hidden: int, ffn: int):
+    """Static activation scales of the block (Eq. 13: s_x = max|X| / Z_max on calibration data): one pass
+    through the block, taking each linear layer's input range from the tensor the oracle itself produces.
+    Returns the dict of scales for block_ref."""
+    scales = {}
+
+    def lin(name, x_bits):
+        scales[name] = act_scale_from_amax(bf16_bits_to_f32(x_bits))
+        x8 = quantize_act(x_bits, scales[name], x_is_bf16_bits=True)
+        y, _ = linear_ref(x8, scales[name], layers[name][0], layers[name][1], group_size)
+        return round_to_bf16_bits(y)
+
+    qkv = lin("qkv", x_bf16_bits)
+    o = lin("o", np.ascontiguousarray(qkv[:, :hidden]))
+    gu = lin("gate_up", o)
+    lin("down", round_to_bf16_bits(silu_mul_ref(gu, ffn)))
+    return scales

@@ -33,6 +33,9 @@ SIGNATURES = {
                                      _c_i32, _c_i64, _c_i32, _c_i32, _c_i32, _c_vp]),
     "w4a8_dequant_weights": (_c_i32, [_c_vp, _c_i64, _c_i64, _c_i32, _c_vp, _c_vp]),
     "w4a8_silu_mul": (_c_i32, [_c_vp, _c_i64, _c_i64, _c_i64, _c_vp, _c_i64, _c_vp]),
+    "w4a8_probe_stream_read": (_c_i32, [_c_vp, _c_sz, _c_vp, _c_vp]),
+    "w4a8_probe_mfma_e4m3": (_c_i32, [_c_i32, _c_vp, _c_vp]),
+    "w4a8_probe_mfma_flop": (ctypes.c_double, [_c_i32]),
     "w4a8_status_string": (ctypes.c_char_p, [_c_i32]),
 }
 
@@ -158,3 +161,14 @@ def silu_mul(gu: torch.Tensor, out: torch.Tensor | None = None) -> torch.Tensor:
     _check(lib().w4a8_silu_mul(gu.data_ptr(), m, f, gu.stride(0) if m > 1 else max(f2, gu.stride(0)), out.data_ptr(),
                                out.stride(0) if m > 1 else max(f, out.stride(0)), _stream()), "w4a8_silu_mul")
     return out
+
+
+def probe_stream_read(buf: torch.Tensor, sink: torch.Tensor) -> None:
+    _check(lib().w4a8_probe_stream_read(buf.data_ptr(), buf.numel() * buf.element_size(), sink.data_ptr(), _stream()),
+           "w4a8_probe_stream_read")
+
+
+def probe_mfma(iters: int, sink: torch.Tensor) -> float:
+    """Enqueues the MFMA issue probe; returns the flop count of the call."""
+    _check(lib().w4a8_probe_mfma_e4m3(iters, sink.data_ptr(), _stream()), "w4a8_probe_mfma_e4m3")
+    return lib().w4a8_probe_mfma_flop(iters)

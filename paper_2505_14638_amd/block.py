@@ -1,0 +1,62 @@
+"""The decoder-block linear stack (QKV -> O -> gate|up -> SiLU*mul -> down) on the HIP path.
+
+Orchestration only: every tensor operation is one call into the C-ABI library (activation quantization, linear
+layer, SiLU*mul); PyTorch provides buffers and views.  The O projection reads the first `hidden` columns of the QKV
+output (a strided view -- the quantizer takes a row stride), standing in for attention, which is not part of the
+quantized-linear path.  Intermediates are bf16, each linear layer's input is quantized to FP8 with its own static
+per-tensor scale (Eq. 13; all linear layers of a block are quantized, Sec. 4.1).
+"""
+from __future__ import annotations
+
+import torch
+
+from . import binding as B
+
+LAYERS = ("qkv", "o", "gate_up", "down")
+
+
+class DecoderBlockLinears:
+    def __init__(self, hidden: int, ffn: int, qkv_out: int, group_size: int = 128, device: str = "cuda:0"):
+        self.hidden, self.ffn, self.group_size, self.device = hidden, ffn, group_size, device
+        self.dims = {"qkv": (hidden, qkv_out), "o": (hidden, hidden), "gate_up": (hidden, 2 * ffn), "down": (ffn, hidden)}
+        self.weights = {}
+        self.scales_x = {}
+        self._buffers = {}
+
+    def load_layer(self, name: str, w_f32: torch.Tensor) -> None:
+        """Quantize (round-to-nearest INT4) and pack one [N, K] float32 weight matrix on the device."""
+        k, n = self.dims[name]
+        assert tuple(w_f32.shape) == (n, k)
+        self.weights[name] = B.pack_weights(w_f32.to(self.device), self.group_size, B.LAYOUT_TILED)
+
+    def set_act_scale(self, name: str, s_x: float) -> None:
+        self.scales_x[name] = torch.tensor([s_x], dtype=torch.float32, device=self.device)
+
+    def _buf(self, key, shape, dtype):
+        b = self._buffers.get(key)
+        if b is None or tuple(b.shape) != tuple(shape):
+            b = torch.empty(shape, dtype=dtype, device=self.device)
+            self._buffers[key] = b
+        return b
+
+    def _linear(self, name: str, x: torch.Tensor, m: int) -> torch.Tensor:
+        k, n = self.dims[name]
+        x8 = self._buf((name, "x8", m), (m, k), torch.uint8)
+        y = self._buf((name, "y", m), (m, n), torch.bfloat16)
+        B.quantize_act(x, self.scales_x[name], out=x8)
+        packed, scales = self.weights[name]
+        B.linear(x8, self.scales_x[name], packed, scales, n, self.group_size, B.LAYOUT_TILED, out=y)
+        return y
+
+    def forward(self, x: torch.Tensor, keep: dict | None = None) -> torch.Tensor:
+        """x: bf16 [M, hidden] on the device.  `keep`, if given, receives every intermediate tensor."""
+        m = x.shape[0]
+        qkv = self._linear("qkv", x, m)
+        o = self._linear("o", qkv[:, :self.hidden], m)
+        gu = self._linear("gate_up", o, m)
+        h = B.silu_mul(gu, out=self._buf(("h", m), (m, self.ffn), torch.bfloat16))
+        y = self._linear("down", h, m)
+        if keep is not None:
+            keep.update(qkv=qkv, o=o, gate_up=gu, h=h, down=y,
+                        **{nm + "_x8": self._buffers[(nm, "x8", m)] for nm in LAYERS})
+        return y

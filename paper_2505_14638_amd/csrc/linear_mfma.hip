@@ -24,23 +24,27 @@
 namespace w4a8 {
 namespace {
 
-constexpr int BM = 128;             // tokens per workgroup
 constexpr int BN = 256;             // channels per workgroup
-constexpr int MF = BM / 16;         // 16-token operand blocks per workgroup
-constexpr int STAGE_BYTES = BM * 128;
 constexpr int XCDS = 8;
 constexpr int GROUP_M = 8;          // token blocks per super-column of the block order
 
 // WAVES wavefronts per workgroup, each owning TPW = 16 / WAVES weight tiles (WN = 16 * TPW channels); OCC = wavefronts
 // per SIMD the register budget is sized for.
-template <typename OutT, int WAVES, int OCC>
+// MF 16-token operand blocks per workgroup (BM = 16 * MF tokens): 8 for large M, 4 when the grid would be too small.
+template <typename OutT, int WAVES, int OCC, int MF>
 __global__ void __launch_bounds__(WAVES * 64, OCC) linear_mfma_kernel(
     const uint8_t* __restrict__ x8, int M, int64_t ldx8, const float* __restrict__ s_x,
     const uint8_t* __restrict__ packed, const float* __restrict__ scales, int N, int n_tiles, int C, int cpg, int NG,
     OutT* __restrict__ y, int64_t ldy, int grid_m, int grid_n) {
+    constexpr int BM = 16 * MF, STAGE_BYTES = BM * 128;
     constexpr int TPW = (BN / 16) / WAVES, WN = TPW * 16;
+    static_assert((2 * MF) % WAVES == 0, "activation half-blocks must divide evenly among the wavefronts");
     constexpr int DMA_PER_WAVE = (2 * MF) / WAVES;               // 1 KiB half-blocks of activations staged per wavefront
-    __shared__ __attribute__((aligned(16))) uint8_t xs[2][STAGE_BYTES];
+    constexpr int RS = WN + 16 / sizeof(OutT);                   // epilogue row stride: rows stay 16-byte aligned
+    constexpr int SLAB_BYTES = WAVES * 16 * RS * (int)sizeof(OutT);
+    constexpr int LDS_BYTES = (2 * STAGE_BYTES > SLAB_BYTES) ? 2 * STAGE_BYTES : SLAB_BYTES;
+    __shared__ __attribute__((aligned(16))) uint8_t lds[LDS_BYTES];
+    uint8_t (*xs)[STAGE_BYTES] = reinterpret_cast<uint8_t (*)[STAGE_BYTES]>(lds);
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int kq = lane >> 4, i = lane & 15;
@@ -118,13 +122,17 @@ __global__ void __launch_bounds__(WAVES * 64, OCC) linear_mfma_kernel(
             s[j] = sreg[j];
         }
         const bool more = (c + 1 < C);
-        if (more) global_loads(c + 1, buf ^ 1);
+        if (more) global_loads(c + 1, buf ^ 1);                  // lands while this chunk is being multiplied
         const uint8_t* xb = &xs[buf][lane * 16];
+        uint4 xa = *reinterpret_cast<const uint4*>(xb);
+        uint4 xc = *reinterpret_cast<const uint4*>(xb + 1024);
 #pragma unroll
         for (int f = 0; f < MF; ++f) {
-            const uint4 a = *reinterpret_cast<const uint4*>(xb + f * 2048);
-            const uint4 b = *reinterpret_cast<const uint4*>(xb + f * 2048 + 1024);
-            const v8i xop = v8i{(int)a.x, (int)a.y, (int)a.z, (int)a.w, (int)b.x, (int)b.y, (int)b.z, (int)b.w};
+            const v8i xop = v8i{(int)xa.x, (int)xa.y, (int)xa.z, (int)xa.w, (int)xc.x, (int)xc.y, (int)xc.z, (int)xc.w};
+            if (f + 1 < MF) {                                    // next block's operand is in flight during the MFMAs
+                xa = *reinterpret_cast<const uint4*>(xb + (f + 1) * 2048);
+                xc = *reinterpret_cast<const uint4*>(xb + (f + 1) * 2048 + 1024);
+            }
 #pragma unroll
             for (int j = 0; j < TPW; ++j) {
                 // rows = tokens (activations), columns = channels (weights)
@@ -141,8 +149,7 @@ __global__ void __launch_bounds__(WAVES * 64, OCC) linear_mfma_kernel(
     // Epilogue.  Result lane: channel = lane % 16 of tile j, tokens 4*kq .. 4*kq+3 of block f.  Each wavefront
     // turns one 16-token x WN-channel slab at a time into row-major order in its own LDS region and stores rows.
     const float sx = *s_x;
-    constexpr int RS = WN + 16 / sizeof(OutT);                                 // row stride: rows stay 16-byte aligned
-    OutT* slab = reinterpret_cast<OutT*>(&xs[0][0]) + wave * (16 * RS);       // 16 rows per wavefront
+    OutT* slab = reinterpret_cast<OutT*>(lds) + wave * (16 * RS);       // 16 rows per wavefront
     constexpr int VEC = 16 / sizeof(OutT);                                     // elements per 16-byte store
     constexpr int LANES_PER_ROW = WN / VEC;
     constexpr int ROWS_PER_PASS = 64 / LANES_PER_ROW;
@@ -178,21 +185,28 @@ __global__ void __launch_bounds__(WAVES * 64, OCC) linear_mfma_kernel(
 int launch_linear_mfma_tiled(const uint8_t* x8, int64_t M, int64_t K, int64_t ldx8, const float* s_x,
                              const uint8_t* packed, const float* scales, int64_t N, int32_t G, void* y,
                              w4a8_dtype ydt, int64_t ldy, int variant, hipStream_t st) {
-    if (variant != 0 && variant != 1) return W4A8_ERR_SHAPE;
+    if (variant < 0 || variant > 3) return W4A8_ERR_SHAPE;      // 0 auto, 1 four-wave, 2 BM=64, 3 BM=128
     const int C = (int)(K / 128), cpg = G / 128, NG = (int)(K / G);
     const int n_tiles = (int)((N + 15) / 16);
-    const int grid_m = (int)((M + BM - 1) / BM), grid_n = (n_tiles * 16 + BN - 1) / BN;
+    const int grid_n = (n_tiles * 16 + BN - 1) / BN;
+    // token-block height: 128 unless that leaves most compute units without a workgroup (two fit per unit)
+    int mf = 8;
+    if (variant == 2 || (variant == 0 && ((M + 127) / 128) * (int64_t)grid_n < 384)) mf = 4;
+    const int bm = 16 * mf;
+    const int grid_m = (int)((M + bm - 1) / bm);
     const int64_t total = (int64_t)grid_m * grid_n;
     if (total > (1 << 30)) return W4A8_ERR_SHAPE;
     if (ldx8 >= (1 << 25)) return W4A8_ERR_SHAPE;               // 32-bit activation offsets inside a token block
     const dim3 grid((unsigned)((total + XCDS - 1) / XCDS * XCDS));
-#define W4A8_LAUNCH_MFMA(T, WV, OC)                                                                                  \
-    hipLaunchKernelGGL((linear_mfma_kernel<T, WV, OC>), grid, dim3(WV * 64), 0, st, x8, (int)M, ldx8, s_x, packed,   \
-                       scales, (int)N, n_tiles, C, cpg, NG, static_cast<T*>(y), ldy, grid_m, grid_n)
-    if (variant == 0) {
-        if (ydt == W4A8_F32) W4A8_LAUNCH_MFMA(float, 8, 4); else W4A8_LAUNCH_MFMA(uint16_t, 8, 4);
+#define W4A8_LAUNCH_MFMA(T, WV, OC, MFV)                                                                             \
+    hipLaunchKernelGGL((linear_mfma_kernel<T, WV, OC, MFV>), grid, dim3(WV * 64), 0, st, x8, (int)M, ldx8, s_x,      \
+                       packed, scales, (int)N, n_tiles, C, cpg, NG, static_cast<T*>(y), ldy, grid_m, grid_n)
+    if (variant == 1) {
+        if (ydt == W4A8_F32) W4A8_LAUNCH_MFMA(float, 4, 2, 8); else W4A8_LAUNCH_MFMA(uint16_t, 4, 2, 8);
+    } else if (mf == 8) {
+        if (ydt == W4A8_F32) W4A8_LAUNCH_MFMA(float, 8, 4, 8); else W4A8_LAUNCH_MFMA(uint16_t, 8, 4, 8);
     } else {
-        if (ydt == W4A8_F32) W4A8_LAUNCH_MFMA(float, 4, 2); else W4A8_LAUNCH_MFMA(uint16_t, 4, 2);
+        if (ydt == W4A8_F32) W4A8_LAUNCH_MFMA(float, 8, 4, 4); else W4A8_LAUNCH_MFMA(uint16_t, 8, 4, 4);
     }
 #undef W4A8_LAUNCH_MFMA
     return launch_status();

@@ -1,0 +1,76 @@
+// Measurement aids: the two hardware ceilings the linear kernels are judged against, measured on the device at hand.
+//   - streaming read: every byte of a buffer is loaded once with 16-byte loads (the HBM ceiling of the skinny path);
+//   - MFMA issue: back-to-back 16x16x128 E4M3 MFMAs on independent accumulators (the ceiling of the tiled path).
+#include "w4a8_device.hpp"
+#include "w4a8_internal.hpp"
+
+namespace w4a8 {
+namespace {
+
+__global__ void __launch_bounds__(256) stream_read_kernel(const uint4* __restrict__ p, size_t n, uint32_t* sink) {
+    uint32_t acc = 0;
+    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (; i + 3 * stride < n; i += 4 * stride) {
+        const uint4 a = p[i], b = p[i + stride], c = p[i + 2 * stride], d = p[i + 3 * stride];
+        acc += a.x ^ a.y ^ a.z ^ a.w ^ b.x ^ b.y ^ b.z ^ b.w ^ c.x ^ c.y ^ c.z ^ c.w ^ d.x ^ d.y ^ d.z ^ d.w;
+    }
+    for (; i < n; i += stride) {
+        const uint4 a = p[i];
+        acc += a.x ^ a.y ^ a.z ^ a.w;
+    }
+    if (acc == 0x9E3779B9u) sink[0] = acc;                       // keeps the loads alive; practically never taken
+}
+
+constexpr int PROBE_ACCS = 8;
+constexpr int PROBE_WORKGROUPS = 512;                            // two per compute unit
+
+__global__ void __launch_bounds__(256) mfma_issue_kernel(int iters, float* sink) {
+    v8i a, b;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        a[i] = 0x38383838 + (int)threadIdx.x;
+        b[i] = 0x40404040 ^ (int)threadIdx.x;
+    }
+    v4f acc[PROBE_ACCS];
+#pragma unroll
+    for (int j = 0; j < PROBE_ACCS; ++j) acc[j] = v4f{0.f, 0.f, 0.f, 0.f};
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int j = 0; j < PROBE_ACCS; ++j) acc[j] = mfma_16x16x128_e4m3(a, b, acc[j]);
+    }
+    float r = 0.f;
+#pragma unroll
+    for (int j = 0; j < PROBE_ACCS; ++j) r += acc[j][0] + acc[j][1] + acc[j][2] + acc[j][3];
+    if (r == 123.456f) sink[0] = r;
+}
+
+}  // namespace
+}  // namespace w4a8
+
+using namespace w4a8;
+
+extern "C" {
+
+int w4a8_probe_stream_read(const void* buf_dev, size_t bytes, uint32_t* sink_dev, void* stream) {
+    if (!buf_dev || !sink_dev) return W4A8_ERR_NULL;
+    if (bytes < 16 || reinterpret_cast<uintptr_t>(buf_dev) % 16) return W4A8_ERR_ALIGN;
+    hipLaunchKernelGGL(stream_read_kernel, dim3(16384), dim3(256), 0, static_cast<hipStream_t>(stream),
+                       static_cast<const uint4*>(buf_dev), bytes / 16, sink_dev);
+    return launch_status();
+}
+
+int w4a8_probe_mfma_e4m3(int32_t iters, float* sink_dev, void* stream) {
+    if (!sink_dev) return W4A8_ERR_NULL;
+    if (iters < 1 || iters > (1 << 20)) return W4A8_ERR_SHAPE;
+    hipLaunchKernelGGL(mfma_issue_kernel, dim3(PROBE_WORKGROUPS), dim3(256), 0, static_cast<hipStream_t>(stream), iters,
+                       sink_dev);
+    return launch_status();
+}
+
+double w4a8_probe_mfma_flop(int32_t iters) {
+    // workgroups x wavefronts x iterations x MFMAs per iteration x (2 * 16 * 16 * 128) flop per MFMA
+    return (double)PROBE_WORKGROUPS * 4.0 * (double)iters * PROBE_ACCS * 65536.0;
+}
+
+}  // extern "C"

@@ -172,6 +172,7 @@ def test_config1_single_layer(gpu_lib):
     (7, 1024, 96, 128, (0, 1, 1)), (7, 1024, 96, 128, (0, 2, 3)), (20, 1024, 96, 128, (0, 4, 2)),
     (50, 2048, 144, 128, (0, 4, 4)), (33, 2048, 64, 128, (0, 1, 16)), (9, 384, 40, 128, (1, 0, 0)),
     (9, 384, 40, 128, (1, 1, 0)), (300, 1024, 520, 512, (1, 1, 0)), (129, 256, 272, 128, (1, 0, 0)),
+    (100, 384, 300, 128, (1, 2, 0)), (300, 1024, 520, 512, (1, 3, 0)),
 ])
 def test_linear_small_ragged(gpu_lib, m, k, n, g, path):
     """Several tiles, ragged tails in M and N, group sizes of one or more chunks, both kernels."""

@@ -140,6 +140,12 @@ def test_block_ref_wiring_small():
     h = gu[:, :ffn] * (1 / (1 + np.exp(-gu[:, :ffn]))) * gu[:, ffn:]
     assert np.array_equal(o.round_to_bf16_bits(h), out["h"])
     assert out["down"].shape == (m, hidden)
+    # calibration: every scale is amax / 448 of that layer's bf16 input, so the input's largest element hits +-448
+    cal = o.calibrate_block_scales(x, layers, g, hidden, ffn)
+    out = o.block_ref(x, layers, cal, g, hidden, ffn)
+    for nm in ("qkv", "o", "gate_up", "down"):
+        assert (out[nm + "_x8"] & 0x7F).max() == 0x7E
+    assert cal["qkv"] == o.act_scale_from_amax(o.bf16_bits_to_f32(x))
     # silu closed forms: silu(0) = 0, silu(x) -> x for large x, -> 0 for very negative x
     t = syn.f32_to_bf16_bits(np.array([[0.0, 40.0, -40.0, 1.0, 1.0, 1.0]], np.float32))
     r = o.silu_mul_ref(t, 3)[0]
