@@ -119,8 +119,9 @@ int w4a8_linear(const uint8_t* x8_dev, int64_t M, int64_t K, int64_t ldx8, const
  * Same as w4a8_linear for W4A8_LAYOUT_TILED with the launch shape chosen by the caller; for tuning sweeps.
  *   path    0 = skinny (M <= 64), 1 = MFMA-tiled
  *   param0  skinny: n-tiles (of 16 rows) per wave, 1, 2 or 4.   tiled: 0 auto, 1 four wavefronts per workgroup,
- *           2 token blocks of 64, 3 token blocks of 128
- *   param1  skinny: waves per workgroup (K is split across them), 1..16.   tiled: reserved, pass 0
+ *           2 = 64 tokens x 256 channels per workgroup, 3 = 128 x 256, 4 = 256 x 128, 5 = 256 x 128 software-pipelined
+ *   param1  skinny: waves per workgroup (K is split across them), 1..16, plus 256 * chunks in flight per wave
+ *           (0 auto, 2 or 4).   tiled: reserved, pass 0
  * Unsupported combinations return W4A8_ERR_SHAPE.
  */
 int w4a8_linear_variant(const uint8_t* x8_dev, int64_t M, int64_t K, int64_t ldx8, const float* x_scale_dev,

@@ -96,7 +96,7 @@ int w4a8_linear(const uint8_t* x8_dev, int64_t M, int64_t K, int64_t ldx8, const
                                        y_dtype, ldy, st);
     if (M <= 64)
         return launch_linear_skinny(x8_dev, M, K, ldx8, x_scale_dev, packed_dev, w_scales_dev, N, group_size, y_dev,
-                                    y_dtype, ldy, 0, 0, st);
+                                    y_dtype, ldy, 0, 0, 0, st);
     return launch_linear_mfma_tiled(x8_dev, M, K, ldx8, x_scale_dev, packed_dev, w_scales_dev, N, group_size, y_dev,
                                     y_dtype, ldy, 0, st);
 }
@@ -111,9 +111,9 @@ int w4a8_linear_variant(const uint8_t* x8_dev, int64_t M, int64_t K, int64_t ldx
     if (M == 0) return W4A8_OK;
     hipStream_t st = static_cast<hipStream_t>(stream);
     if (path == 0) {
-        if (M > 64 || param0 < 0 || param1 < 0 || param1 > 16) return W4A8_ERR_SHAPE;
+        if (M > 64 || param0 < 0 || param1 < 0 || (param1 & 0xFF) > 16) return W4A8_ERR_SHAPE;
         return launch_linear_skinny(x8_dev, M, K, ldx8, x_scale_dev, packed_dev, w_scales_dev, N, group_size, y_dev,
-                                    y_dtype, ldy, param0, param1, st);
+                                    y_dtype, ldy, param0, param1 & 0xFF, param1 >> 8, st);
     }
     if (path == 1)
         return launch_linear_mfma_tiled(x8_dev, M, K, ldx8, x_scale_dev, packed_dev, w_scales_dev, N, group_size, y_dev,

@@ -24,14 +24,13 @@
 namespace w4a8 {
 namespace {
 
-constexpr int BN = 256;             // channels per workgroup
 constexpr int XCDS = 8;
 constexpr int GROUP_M = 8;          // token blocks per super-column of the block order
 
 // WAVES wavefronts per workgroup, each owning TPW = 16 / WAVES weight tiles (WN = 16 * TPW channels); OCC = wavefronts
 // per SIMD the register budget is sized for.
-// MF 16-token operand blocks per workgroup (BM = 16 * MF tokens): 8 for large M, 4 when the grid would be too small.
-template <typename OutT, int WAVES, int OCC, int MF>
+// MF 16-token operand blocks per workgroup (BM = 16 * MF tokens), BN channels per workgroup.
+template <typename OutT, int WAVES, int OCC, int MF, int BN>
 __global__ void __launch_bounds__(WAVES * 64, OCC) linear_mfma_kernel(
     const uint8_t* __restrict__ x8, int M, int64_t ldx8, const float* __restrict__ s_x,
     const uint8_t* __restrict__ packed, const float* __restrict__ scales, int N, int n_tiles, int C, int cpg, int NG,
@@ -40,9 +39,10 @@ __global__ void __launch_bounds__(WAVES * 64, OCC) linear_mfma_kernel(
     constexpr int TPW = (BN / 16) / WAVES, WN = TPW * 16;
     static_assert((2 * MF) % WAVES == 0, "activation half-blocks must divide evenly among the wavefronts");
     constexpr int DMA_PER_WAVE = (2 * MF) / WAVES;               // 1 KiB half-blocks of activations staged per wavefront
-    constexpr int RS = WN + 16 / sizeof(OutT);                   // epilogue row stride: rows stay 16-byte aligned
-    constexpr int SLAB_BYTES = WAVES * 16 * RS * (int)sizeof(OutT);
-    constexpr int LDS_BYTES = (2 * STAGE_BYTES > SLAB_BYTES) ? 2 * STAGE_BYTES : SLAB_BYTES;
+    constexpr int RS = BN + 16 / sizeof(OutT);                   // epilogue row stride: rows stay 16-byte aligned
+    constexpr int SLAB16_BYTES = 16 * RS * (int)sizeof(OutT);    // one 16-token slab of the workgroup's output
+    constexpr int LDS_BYTES = (2 * STAGE_BYTES > SLAB16_BYTES) ? 2 * STAGE_BYTES : SLAB16_BYTES;
+    constexpr int FR = (LDS_BYTES / SLAB16_BYTES < MF) ? LDS_BYTES / SLAB16_BYTES : MF;   // slabs per epilogue round
     __shared__ __attribute__((aligned(16))) uint8_t lds[LDS_BYTES];
     uint8_t (*xs)[STAGE_BYTES] = reinterpret_cast<uint8_t (*)[STAGE_BYTES]>(lds);
     const int tid = threadIdx.x, lane = tid & 63;
@@ -146,27 +146,33 @@ __global__ void __launch_bounds__(WAVES * 64, OCC) linear_mfma_kernel(
         __syncthreads();
     }
 
-    // Epilogue.  Result lane: channel = lane % 16 of tile j, tokens 4*kq .. 4*kq+3 of block f.  Each wavefront
-    // turns one 16-token x WN-channel slab at a time into row-major order in its own LDS region and stores rows.
+    // Epilogue.  Result lane: channel = lane % 16 of tile j, tokens 4*kq .. 4*kq+3 of block f.  The workgroup turns
+    // FR 16-token slabs at a time into row-major order in LDS and stores whole BN-channel row segments.
     const float sx = *s_x;
-    OutT* slab = reinterpret_cast<OutT*>(lds) + wave * (16 * RS);       // 16 rows per wavefront
-    constexpr int VEC = 16 / sizeof(OutT);                                     // elements per 16-byte store
-    constexpr int LANES_PER_ROW = WN / VEC;
-    constexpr int ROWS_PER_PASS = 64 / LANES_PER_ROW;
-    const int n_wave = t0 * 16;
+    OutT* slab = reinterpret_cast<OutT*>(lds);
+    constexpr int VEC = 16 / sizeof(OutT);                       // elements per 16-byte store
+    constexpr int UPR = BN / VEC;                                // 16-byte units per row
+    const int n_block = bn * BN;
     const bool vec_ok = (ldy % VEC == 0) && (reinterpret_cast<uintptr_t>(y) % 16 == 0);
 #pragma unroll
-    for (int f = 0; f < MF; ++f) {
+    for (int f0 = 0; f0 < MF; f0 += FR) {
 #pragma unroll
-        for (int j = 0; j < TPW; ++j)
+        for (int ff = 0; ff < FR; ++ff) {
+            if (f0 + ff < MF) {
 #pragma unroll
-            for (int r = 0; r < 4; ++r) slab[(4 * kq + r) * RS + 16 * j + i] = OutCast<OutT>::cast(sx * acc[f][j][r]);
-        __builtin_amdgcn_wave_barrier();
+                for (int j = 0; j < TPW; ++j)
 #pragma unroll
-        for (int pass = 0; pass < 16 / ROWS_PER_PASS; ++pass) {
-            const int row = pass * ROWS_PER_PASS + lane / LANES_PER_ROW, col = (lane % LANES_PER_ROW) * VEC;
-            const int m = m0 + f * 16 + row, n = n_wave + col;
-            if (m < M && n < N) {
+                    for (int r = 0; r < 4; ++r)
+                        slab[(ff * 16 + 4 * kq + r) * RS + wave * WN + 16 * j + i] =
+                            OutCast<OutT>::cast(sx * acc[(f0 + ff < MF) ? f0 + ff : 0][j][r]);
+            }
+        }
+        __syncthreads();
+        constexpr int ROWS = FR * 16;
+        for (int u = tid; u < ROWS * UPR; u += WAVES * 64) {
+            const int row = u / UPR, col = (u % UPR) * VEC;
+            const int m = m0 + f0 * 16 + row, n = n_block + col;
+            if (row < (MF - f0) * 16 && m < M && n < N) {
                 OutT* dst = y + (int64_t)m * ldy + n;
                 const OutT* src = slab + row * RS + col;
                 if (vec_ok && n + VEC <= N) {
@@ -176,7 +182,159 @@ __global__ void __launch_bounds__(WAVES * 64, OCC) linear_mfma_kernel(
                 }
             }
         }
-        __builtin_amdgcn_wave_barrier();
+        __syncthreads();
+    }
+}
+
+// The tall workgroup shape (256 tokens x 128 channels, eight wavefronts, one weight band each) as its own kernel with
+// a hand-laid software pipeline: the nibble expansion of the NEXT chunk's band is spread over the sixteen MFMAs of the
+// current chunk (one dword, 14 ALU ops, every fourth MFMA) instead of running as a burst that idles the matrix unit,
+// and the raw nibbles are fetched two chunks ahead.  Two raw buffers and two operand buffers alternate by chunk
+// parity, so nothing is copied.
+template <typename OutT>
+__global__ void __launch_bounds__(512, 4) linear_mfma_tall_kernel(
+    const uint8_t* __restrict__ x8, int M, int64_t ldx8, const float* __restrict__ s_x,
+    const uint8_t* __restrict__ packed, const float* __restrict__ scales, int N, int n_tiles, int C, int cpg, int NG,
+    OutT* __restrict__ y, int64_t ldy, int grid_m, int grid_n) {
+    constexpr int WAVES = 8, MF = 16, BN = 128, BM = 256, STAGE_BYTES = BM * 128, DMA_PER_WAVE = 4;
+    constexpr int RS = BN + 16 / sizeof(OutT);
+    constexpr int SLAB16_BYTES = 16 * RS * (int)sizeof(OutT);
+    constexpr int LDS_BYTES = 2 * STAGE_BYTES;
+    constexpr int FR = (LDS_BYTES / SLAB16_BYTES < MF) ? LDS_BYTES / SLAB16_BYTES : MF;
+    __shared__ __attribute__((aligned(16))) uint8_t lds[LDS_BYTES];
+    uint8_t (*xs)[STAGE_BYTES] = reinterpret_cast<uint8_t (*)[STAGE_BYTES]>(lds);
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int kq = lane >> 4, i = lane & 15;
+
+    const int total = grid_m * grid_n;
+    const int per_xcd = (gridDim.x + XCDS - 1) / XCDS;
+    const int v = (blockIdx.x % XCDS) * per_xcd + blockIdx.x / XCDS;
+    if (v >= total) return;
+    const int group = v / (GROUP_M * grid_n);
+    const int first_m = group * GROUP_M;
+    const int rows_in_group = min(GROUP_M, grid_m - first_m);
+    const int in_group = v - group * GROUP_M * grid_n;
+    const int bm = first_m + in_group % rows_in_group, bn = in_group / rows_in_group;
+    const int m0 = bm * BM;
+    const int t = min(bn * (BN / 16) + wave, n_tiles - 1);       // bands past the end reload the last one; not stored
+
+    const uint8_t* wbase = packed + (int64_t)t * C * 1024 + lane * 16;
+    const uint8_t* sbase = reinterpret_cast<const uint8_t*>(scales) + (int64_t)t * NG * 64 + i * 4;
+    uint32_t xvoff[DMA_PER_WAVE];
+#pragma unroll
+    for (int q = 0; q < DMA_PER_WAVE; ++q) {
+        const int d = wave * DMA_PER_WAVE + q;                   // half-block index: f = d / 2, h = d % 2
+        const int row = (d >> 1) * 16 + i;
+        xvoff[q] = (uint32_t)(min(m0 + row, M - 1) - m0) * (uint32_t)ldx8 + kq * 32 + (d & 1) * 16;
+    }
+    const uint8_t* xrow0 = x8 + (int64_t)m0 * ldx8;
+
+    auto stage_x = [&](int c, int buf) {
+        const uint8_t* xsrc = xrow0 + (int64_t)c * 128;
+#pragma unroll
+        for (int q = 0; q < DMA_PER_WAVE; ++q)
+            __builtin_amdgcn_global_load_lds(
+                (const __attribute__((address_space(1))) void*)(xsrc + xvoff[q]),
+                (__attribute__((address_space(3))) void*)&xs[buf][(wave * DMA_PER_WAVE + q) * 1024], 16, 0, 0);
+    };
+    int g = 0, g_left = cpg;                                     // group of the next chunk to be fetched
+    int c_fetch = 0;
+    auto fetch_w = [&](uint4& raw, float& s) {                   // raw nibbles and scale of chunk c_fetch, then advance
+        raw = *reinterpret_cast<const uint4*>(wbase + (int64_t)c_fetch * 1024);
+        s = *reinterpret_cast<const float*>(sbase + (int64_t)g * 64);
+        ++c_fetch;
+        if (--g_left == 0) { ++g; g_left = cpg; }
+    };
+
+    v4f acc[MF];
+#pragma unroll
+    for (int f = 0; f < MF; ++f) acc[f] = v4f{0.f, 0.f, 0.f, 0.f};
+
+    // One chunk: multiply with `cur`; meanwhile expand `raw_next` (chunk c+1) into `next` and fetch chunk c+2 into `raw_far`.
+    auto chunk = [&](int c, const v8i& cur, float s_cur, const uint4& raw_next, v8i& next, uint4& raw_far, float& s_far) {
+        const int buf = c & 1;
+        if (c + 1 < C) stage_x(c + 1, buf ^ 1);
+        if (c + 2 < C) fetch_w(raw_far, s_far);
+        const uint8_t* xb = &xs[buf][lane * 16];
+        uint4 xa = *reinterpret_cast<const uint4*>(xb);
+        uint4 xc = *reinterpret_cast<const uint4*>(xb + 1024);
+        const uint32_t rn[4] = {raw_next.x, raw_next.y, raw_next.z, raw_next.w};
+#pragma unroll
+        for (int f = 0; f < MF; ++f) {
+            const v8i xop = v8i{(int)xa.x, (int)xa.y, (int)xa.z, (int)xa.w, (int)xc.x, (int)xc.y, (int)xc.z, (int)xc.w};
+            if (f + 1 < MF) {
+                xa = *reinterpret_cast<const uint4*>(xb + (f + 1) * 2048);
+                xc = *reinterpret_cast<const uint4*>(xb + (f + 1) * 2048 + 1024);
+            }
+            const v4f p = mfma_16x16x128_e4m3(xop, cur, v4f{0.f, 0.f, 0.f, 0.f});
+            if ((f & 3) == 1) {                                  // a quarter of the next band's expansion
+                uint32_t lo, hi;
+                nibbles_to_e4m3(rn[f >> 2], lo, hi);
+                next[2 * (f >> 2)] = (int)lo;
+                next[2 * (f >> 2) + 1] = (int)hi;
+            }
+            acc[f][0] = fmaf(s_cur, p[0], acc[f][0]);
+            acc[f][1] = fmaf(s_cur, p[1], acc[f][1]);
+            acc[f][2] = fmaf(s_cur, p[2], acc[f][2]);
+            acc[f][3] = fmaf(s_cur, p[3], acc[f][3]);
+        }
+        __syncthreads();
+    };
+
+    uint4 raw_a, raw_b = make_uint4(0u, 0u, 0u, 0u);
+    float s_raw_a = 0.f, s_raw_b = 0.f;
+    v8i wop_a, wop_b;
+    stage_x(0, 0);
+    fetch_w(raw_a, s_raw_a);                                     // chunk 0
+    if (C > 1) fetch_w(raw_b, s_raw_b);                          // chunk 1
+    wop_a = slot_to_operand(raw_a);
+    float s_a = s_raw_a, s_b = 0.f;
+    __syncthreads();
+
+    for (int c = 0; c < C; c += 2) {
+        // even chunk: operand A multiplies, raw B (chunk c+1) expands into operand B, chunk c+2 lands in raw A
+        s_b = s_raw_b;
+        chunk(c, wop_a, s_a, raw_b, wop_b, raw_a, s_raw_a);
+        if (c + 1 < C) {
+            s_a = s_raw_a;
+            chunk(c + 1, wop_b, s_b, raw_a, wop_a, raw_b, s_raw_b);
+        }
+    }
+
+    const float sx = *s_x;
+    OutT* slab = reinterpret_cast<OutT*>(lds);
+    constexpr int VEC = 16 / sizeof(OutT);
+    constexpr int UPR = BN / VEC;
+    const int n_block = bn * BN;
+    const bool vec_ok = (ldy % VEC == 0) && (reinterpret_cast<uintptr_t>(y) % 16 == 0);
+#pragma unroll
+    for (int f0 = 0; f0 < MF; f0 += FR) {
+#pragma unroll
+        for (int ff = 0; ff < FR; ++ff) {
+            if (f0 + ff < MF) {
+#pragma unroll
+                for (int r = 0; r < 4; ++r)
+                    slab[(ff * 16 + 4 * kq + r) * RS + wave * 16 + i] =
+                        OutCast<OutT>::cast(sx * acc[(f0 + ff < MF) ? f0 + ff : 0][r]);
+            }
+        }
+        __syncthreads();
+        constexpr int ROWS = FR * 16;
+        for (int u = tid; u < ROWS * UPR; u += WAVES * 64) {
+            const int row = u / UPR, col = (u % UPR) * VEC;
+            const int m = m0 + f0 * 16 + row, n = n_block + col;
+            if (row < (MF - f0) * 16 && m < M && n < N) {
+                OutT* dst = y + (int64_t)m * ldy + n;
+                const OutT* src = slab + row * RS + col;
+                if (vec_ok && n + VEC <= N) {
+                    *reinterpret_cast<uint4*>(dst) = *reinterpret_cast<const uint4*>(src);
+                } else {
+                    for (int e = 0; e < VEC && n + e < N; ++e) dst[e] = src[e];
+                }
+            }
+        }
+        __syncthreads();
     }
 }
 
@@ -185,28 +343,46 @@ __global__ void __launch_bounds__(WAVES * 64, OCC) linear_mfma_kernel(
 int launch_linear_mfma_tiled(const uint8_t* x8, int64_t M, int64_t K, int64_t ldx8, const float* s_x,
                              const uint8_t* packed, const float* scales, int64_t N, int32_t G, void* y,
                              w4a8_dtype ydt, int64_t ldy, int variant, hipStream_t st) {
-    if (variant < 0 || variant > 3) return W4A8_ERR_SHAPE;      // 0 auto, 1 four-wave, 2 BM=64, 3 BM=128
+    if (variant < 0 || variant > 5) return W4A8_ERR_SHAPE;      // 0 auto, 1 four-wave, 2 64x256, 3 128x256, 4 256x128
     const int C = (int)(K / 128), cpg = G / 128, NG = (int)(K / G);
     const int n_tiles = (int)((N + 15) / 16);
-    const int grid_n = (n_tiles * 16 + BN - 1) / BN;
-    // token-block height: 128 unless that leaves most compute units without a workgroup (two fit per unit)
-    int mf = 8;
-    if (variant == 2 || (variant == 0 && ((M + 127) / 128) * (int64_t)grid_n < 384)) mf = 4;
+    // Workgroup shape.  Tall (256 tokens x 128 channels, one weight band per wavefront) amortizes the nibble expansion
+    // over twice as many MFMAs and is the default; when that grid cannot fill the chip, shorter token blocks.
+    int mf = 16, bn = 128;
+    if (variant == 1 || variant == 3) { mf = 8; bn = 256; }
+    bool pipelined = (variant == 5);
+    if (variant == 2) { mf = 4; bn = 256; }
+    if (variant == 0) {
+        const int64_t wg_tall = ((M + 255) / 256) * (int64_t)((n_tiles * 16 + 127) / 128);
+        const int64_t wg_mid = ((M + 127) / 128) * (int64_t)((n_tiles * 16 + 255) / 256);
+        if (wg_tall < 384) { mf = 8; bn = 256; if (wg_mid < 384) mf = 4; }
+        else pipelined = true;
+    }
+    const int grid_n = (n_tiles * 16 + bn - 1) / bn;
     const int bm = 16 * mf;
     const int grid_m = (int)((M + bm - 1) / bm);
     const int64_t total = (int64_t)grid_m * grid_n;
     if (total > (1 << 30)) return W4A8_ERR_SHAPE;
-    if (ldx8 >= (1 << 25)) return W4A8_ERR_SHAPE;               // 32-bit activation offsets inside a token block
+    if (ldx8 >= (1 << 24)) return W4A8_ERR_SHAPE;               // 32-bit activation offsets inside a token block
     const dim3 grid((unsigned)((total + XCDS - 1) / XCDS * XCDS));
-#define W4A8_LAUNCH_MFMA(T, WV, OC, MFV)                                                                             \
-    hipLaunchKernelGGL((linear_mfma_kernel<T, WV, OC, MFV>), grid, dim3(WV * 64), 0, st, x8, (int)M, ldx8, s_x,      \
+#define W4A8_LAUNCH_MFMA(T, WV, OC, MFV, BNV)                                                                        \
+    hipLaunchKernelGGL((linear_mfma_kernel<T, WV, OC, MFV, BNV>), grid, dim3(WV * 64), 0, st, x8, (int)M, ldx8, s_x, \
                        packed, scales, (int)N, n_tiles, C, cpg, NG, static_cast<T*>(y), ldy, grid_m, grid_n)
-    if (variant == 1) {
-        if (ydt == W4A8_F32) W4A8_LAUNCH_MFMA(float, 4, 2, 8); else W4A8_LAUNCH_MFMA(uint16_t, 4, 2, 8);
+    if (pipelined) {
+        if (ydt == W4A8_F32)
+            hipLaunchKernelGGL(linear_mfma_tall_kernel<float>, grid, dim3(512), 0, st, x8, (int)M, ldx8, s_x, packed, scales,
+                               (int)N, n_tiles, C, cpg, NG, static_cast<float*>(y), ldy, grid_m, grid_n);
+        else
+            hipLaunchKernelGGL(linear_mfma_tall_kernel<uint16_t>, grid, dim3(512), 0, st, x8, (int)M, ldx8, s_x, packed,
+                               scales, (int)N, n_tiles, C, cpg, NG, static_cast<uint16_t*>(y), ldy, grid_m, grid_n);
+    } else if (variant == 1) {
+        if (ydt == W4A8_F32) W4A8_LAUNCH_MFMA(float, 4, 2, 8, 256); else W4A8_LAUNCH_MFMA(uint16_t, 4, 2, 8, 256);
+    } else if (mf == 16) {
+        if (ydt == W4A8_F32) W4A8_LAUNCH_MFMA(float, 8, 4, 16, 128); else W4A8_LAUNCH_MFMA(uint16_t, 8, 4, 16, 128);
     } else if (mf == 8) {
-        if (ydt == W4A8_F32) W4A8_LAUNCH_MFMA(float, 8, 4, 8); else W4A8_LAUNCH_MFMA(uint16_t, 8, 4, 8);
+        if (ydt == W4A8_F32) W4A8_LAUNCH_MFMA(float, 8, 4, 8, 256); else W4A8_LAUNCH_MFMA(uint16_t, 8, 4, 8, 256);
     } else {
-        if (ydt == W4A8_F32) W4A8_LAUNCH_MFMA(float, 8, 4, 4); else W4A8_LAUNCH_MFMA(uint16_t, 8, 4, 4);
+        if (ydt == W4A8_F32) W4A8_LAUNCH_MFMA(float, 8, 4, 4, 256); else W4A8_LAUNCH_MFMA(uint16_t, 8, 4, 4, 256);
     }
 #undef W4A8_LAUNCH_MFMA
     return launch_status();

@@ -7,7 +7,7 @@
 // fully coalesced), expands the nibbles to E4M3 in registers (Eq. 10) and feeds them as the A operand of one
 // 16x16x128 FP8 MFMA per (tile, 16-token block); the activations are the B operand, loaded straight from global
 // memory (they are small and stay in cache).  The chunk's partial product is scaled by the group scale in fp32.
-// The next chunk's loads are issued before the current chunk's arithmetic.
+// Several chunks' loads are in flight ahead of the current chunk's arithmetic.
 #include "w4a8_device.hpp"
 #include "w4a8_internal.hpp"
 
@@ -23,10 +23,12 @@ struct ChunkLoads {
     uint4 x[MT][2];       // 32 activation bytes per 16-token block
 };
 
-// the launcher keeps waves * MT * NT <= 64, so larger register tiles never run with more threads than this
-constexpr int max_threads(int tiles) { return tiles <= 4 ? 1024 : (tiles <= 8 ? 512 : 256); }
+// larger register tiles run with fewer wavefronts per workgroup (the launcher enforces it), which raises the
+// register budget per lane: 128 at 1024 threads, 256 at 512 and below
+constexpr int max_threads(int tiles) { return tiles <= 2 ? 1024 : (tiles <= 8 ? 512 : 256); }
 
-template <int MT, int NT, typename OutT>
+// DEPTH = chunks in flight per wavefront (a ring of register buffers)
+template <int MT, int NT, int DEPTH, typename OutT>
 __global__ void __launch_bounds__(max_threads(MT * NT)) linear_skinny_kernel(
     const uint8_t* __restrict__ x8, int M, int64_t ldx8, const float* __restrict__ s_x,
     const uint8_t* __restrict__ packed, const float* __restrict__ scales, int N, int n_tiles, int C, int cpg, int NG,
@@ -102,28 +104,21 @@ __global__ void __launch_bounds__(max_threads(MT * NT)) linear_skinny_kernel(
         }
     };
 
-    // two chunks in flight per wavefront, ping-pong between two register sets (no copies)
-    int left = c_end - c_begin;
-    if (left > 0) {
-        ChunkLoads<MT, NT> b0, b1;
-        load_chunk(b0);
-        if (left > 1) load_chunk(b1);
-        while (left > 2) {
-            compute_chunk(b0);
-            load_chunk(b0);
-            if (left > 3) {
-                compute_chunk(b1);
-                load_chunk(b1);
-            } else {
-                compute_chunk(b1);
-                compute_chunk(b0);
-                left = 0;
-                break;
+    // DEPTH chunks in flight per wavefront: a ring of register buffers, refilled in chunk order right after use
+    {
+        ChunkLoads<MT, NT> ring[DEPTH];
+#pragma unroll
+        for (int d = 0; d < DEPTH; ++d)
+            if (c_begin + d < c_end) load_chunk(ring[d]);
+        for (int c = c_begin; c < c_end; c += DEPTH) {
+#pragma unroll
+            for (int d = 0; d < DEPTH; ++d) {
+                if (c + d < c_end) {
+                    compute_chunk(ring[d]);
+                    if (c + d + DEPTH < c_end) load_chunk(ring[d]);
+                }
             }
-            left -= 2;
         }
-        if (left > 0) compute_chunk(b0);
-        if (left > 1) compute_chunk(b1);
     }
 
     // sum the wavefronts' partials through LDS: red[wave][e = (mt*NT + j)*4 + r][lane]
@@ -150,36 +145,40 @@ __global__ void __launch_bounds__(max_threads(MT * NT)) linear_skinny_kernel(
 }
 
 template <int MT, int NT, typename OutT>
-int launch_one(const uint8_t* x8, int M, int64_t ldx8, const float* s_x, const uint8_t* packed, const float* scales,
+int launch_one(int depth, const uint8_t* x8, int M, int64_t ldx8, const float* s_x, const uint8_t* packed, const float* scales,
                int N, int C, int cpg, int NG, void* y, int64_t ldy, int waves, hipStream_t st) {
     const int n_tiles = (N + 15) / 16;
     const int grid = (n_tiles + NT - 1) / NT;
     const int cpw = (C + waves - 1) / waves;
     const size_t lds = (size_t)waves * MT * NT * 4 * RED_STRIDE * sizeof(float);
-    hipLaunchKernelGGL((linear_skinny_kernel<MT, NT, OutT>), dim3(grid), dim3(waves * 64), lds, st, x8, M, ldx8, s_x,
-                       packed, scales, N, n_tiles, C, cpg, NG, static_cast<OutT*>(y),
-                       ldy, cpw);
+    constexpr int DEEP = (MT * NT == 1) ? 4 : 2;                 // deeper ring while the registers allow it
+    if (depth == DEEP)
+        hipLaunchKernelGGL((linear_skinny_kernel<MT, NT, DEEP, OutT>), dim3(grid), dim3(waves * 64), lds, st, x8, M,
+                           ldx8, s_x, packed, scales, N, n_tiles, C, cpg, NG, static_cast<OutT*>(y), ldy, cpw);
+    else
+        hipLaunchKernelGGL((linear_skinny_kernel<MT, NT, 2, OutT>), dim3(grid), dim3(waves * 64), lds, st, x8, M, ldx8,
+                           s_x, packed, scales, N, n_tiles, C, cpg, NG, static_cast<OutT*>(y), ldy, cpw);
     return launch_status();
 }
 
 template <int MT, typename OutT>
-int launch_nt(int nt, const uint8_t* x8, int M, int64_t ldx8, const float* s_x, const uint8_t* packed,
+int launch_nt(int nt, int depth, const uint8_t* x8, int M, int64_t ldx8, const float* s_x, const uint8_t* packed,
               const float* scales, int N, int C, int cpg, int NG, void* y, int64_t ldy, int waves, hipStream_t st) {
     switch (nt) {
-        case 1: return launch_one<MT, 1, OutT>(x8, M, ldx8, s_x, packed, scales, N, C, cpg, NG, y, ldy, waves, st);
-        case 2: return launch_one<MT, 2, OutT>(x8, M, ldx8, s_x, packed, scales, N, C, cpg, NG, y, ldy, waves, st);
-        case 4: return launch_one<MT, 4, OutT>(x8, M, ldx8, s_x, packed, scales, N, C, cpg, NG, y, ldy, waves, st);
+        case 1: return launch_one<MT, 1, OutT>(depth, x8, M, ldx8, s_x, packed, scales, N, C, cpg, NG, y, ldy, waves, st);
+        case 2: return launch_one<MT, 2, OutT>(depth, x8, M, ldx8, s_x, packed, scales, N, C, cpg, NG, y, ldy, waves, st);
+        case 4: return launch_one<MT, 4, OutT>(depth, x8, M, ldx8, s_x, packed, scales, N, C, cpg, NG, y, ldy, waves, st);
     }
     return W4A8_ERR_SHAPE;
 }
 
 template <typename OutT>
-int launch_mt(int mt, int nt, const uint8_t* x8, int M, int64_t ldx8, const float* s_x, const uint8_t* packed,
+int launch_mt(int mt, int nt, int depth, const uint8_t* x8, int M, int64_t ldx8, const float* s_x, const uint8_t* packed,
               const float* scales, int N, int C, int cpg, int NG, void* y, int64_t ldy, int waves, hipStream_t st) {
     switch (mt) {
-        case 1: return launch_nt<1, OutT>(nt, x8, M, ldx8, s_x, packed, scales, N, C, cpg, NG, y, ldy, waves, st);
-        case 2: return launch_nt<2, OutT>(nt, x8, M, ldx8, s_x, packed, scales, N, C, cpg, NG, y, ldy, waves, st);
-        default: return launch_nt<4, OutT>(nt, x8, M, ldx8, s_x, packed, scales, N, C, cpg, NG, y, ldy, waves, st);
+        case 1: return launch_nt<1, OutT>(nt, depth, x8, M, ldx8, s_x, packed, scales, N, C, cpg, NG, y, ldy, waves, st);
+        case 2: return launch_nt<2, OutT>(nt, depth, x8, M, ldx8, s_x, packed, scales, N, C, cpg, NG, y, ldy, waves, st);
+        default: return launch_nt<4, OutT>(nt, depth, x8, M, ldx8, s_x, packed, scales, N, C, cpg, NG, y, ldy, waves, st);
     }
 }
 
@@ -187,24 +186,31 @@ int launch_mt(int mt, int nt, const uint8_t* x8, int M, int64_t ldx8, const floa
 
 int launch_linear_skinny(const uint8_t* x8, int64_t M, int64_t K, int64_t ldx8, const float* s_x,
                          const uint8_t* packed, const float* scales, int64_t N, int32_t G, void* y, w4a8_dtype ydt,
-                         int64_t ldy, int nt, int waves, hipStream_t st) {
+                         int64_t ldy, int nt, int waves, int depth, hipStream_t st) {
     if (M < 1 || M > 64) return W4A8_ERR_SHAPE;
     const int C = (int)(K / 128), cpg = G / 128, NG = (int)(K / G);
     const int n_tiles = (int)((N + 15) / 16);
     const int mt = (M <= 16) ? 1 : (M <= 32) ? 2 : 4;
-    if (nt == 0) nt = (M > 8 && n_tiles >= 1024) ? 2 : 1;       // two tiles share each activation operand when it is wide
+    // Launch shape, from sweeps over the Llama-3-8B/70B layer shapes:
+    //  - two bands per wavefront when the activation operand is wide enough to be worth sharing (M > 8 on layers
+    //    with enough bands) or when the layer is large enough that fewer, longer-running workgroups ramp better;
+    //  - split K over as many wavefronts as it takes to have ~8192 (~4096 for M > 8) of them in flight.
+    if (nt == 0) nt = ((M > 8 && n_tiles >= 384) || (int64_t)n_tiles * C >= 100000) ? 2 : 1;
     if (nt != 1 && nt != 2 && nt != 4) return W4A8_ERR_SHAPE;
     if (waves == 0) {
         const int grid = (n_tiles + nt - 1) / nt;
-        waves = ((nt == 1 ? 6144 : 3072) + grid - 1) / grid;     // enough wavefronts in flight to cover HBM latency
+        waves = ((M > 8 ? 4096 : 8192) + grid - 1) / grid;
+        if (waves < 2) waves = 2;
         if (waves > 16) waves = 16;
     }
     if (waves > C) waves = C;
-    while (waves > 1 && waves * mt * nt > 64) --waves;           // partial sums must fit in 64 KiB of LDS
-    if (waves < 1 || waves > 16 || waves * mt * nt > 64) return W4A8_ERR_SHAPE;
+    while (waves > 1 && (waves * mt * nt > 64 || waves * 64 > max_threads(mt * nt))) --waves;   // LDS and registers
+    if (waves < 1 || waves > 16 || waves * mt * nt > 64 || waves * 64 > max_threads(mt * nt)) return W4A8_ERR_SHAPE;
+    if (depth == 0) depth = 2;                                   // deeper rings cost occupancy and measured no faster
+    if (depth != 2 && depth != 4) return W4A8_ERR_SHAPE;
     if (ydt == W4A8_F32)
-        return launch_mt<float>(mt, nt, x8, (int)M, ldx8, s_x, packed, scales, (int)N, C, cpg, NG, y, ldy, waves, st);
-    return launch_mt<uint16_t>(mt, nt, x8, (int)M, ldx8, s_x, packed, scales, (int)N, C, cpg, NG, y, ldy, waves, st);
+        return launch_mt<float>(mt, nt, depth, x8, (int)M, ldx8, s_x, packed, scales, (int)N, C, cpg, NG, y, ldy, waves, st);
+    return launch_mt<uint16_t>(mt, nt, depth, x8, (int)M, ldx8, s_x, packed, scales, (int)N, C, cpg, NG, y, ldy, waves, st);
 }
 
 }  // namespace w4a8

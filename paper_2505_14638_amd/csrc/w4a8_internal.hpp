@@ -20,10 +20,10 @@ int launch_dequant_weights(const uint8_t* packed, int64_t N, int64_t K, w4a8_lay
 int launch_linear_canonical(const uint8_t* x8, int64_t M, int64_t K, int64_t ldx8, const float* s_x,
                             const uint8_t* packed, const float* scales, int64_t N, int32_t G, void* y,
                             w4a8_dtype ydt, int64_t ldy, hipStream_t st);
-// nt / waves = 0: chosen from the shape
+// nt / waves / depth = 0: chosen from the shape
 int launch_linear_skinny(const uint8_t* x8, int64_t M, int64_t K, int64_t ldx8, const float* s_x,
                          const uint8_t* packed, const float* scales, int64_t N, int32_t G, void* y, w4a8_dtype ydt,
-                         int64_t ldy, int nt, int waves, hipStream_t st);
+                         int64_t ldy, int nt, int waves, int depth, hipStream_t st);
 int launch_linear_mfma_tiled(const uint8_t* x8, int64_t M, int64_t K, int64_t ldx8, const float* s_x,
                              const uint8_t* packed, const float* scales, int64_t N, int32_t G, void* y,
                              w4a8_dtype ydt, int64_t ldy, int variant, hipStream_t st);
