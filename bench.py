@@ -33,6 +33,13 @@ from paper_2505_14638_amd import synthetic as syn
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
 FP8_PEAK_TFLOPS = 5000.0       # MI355X dense FP8 MFMA
 G = 128
+# HBM traffic per launch of the dominant kernel on the default workload, from two hardware-counter runs of this file
+# (profiles/linear_skinny_decode_sweep_hbm_traffic.txt): FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, the factors that make the
+# same counters read 1 GiB + 1 GiB for a plain 1 GiB device-to-device copy.  Counters cannot be read from inside a
+# timed run, so the figure is carried here and reported only for the workload it was measured on.
+SKINNY_TRAFFIC_BYTES_PER_LAUNCH = {4: 29.582e6}          # by --copies
+# same for the prefill sweep (profiles/linear_mfma_prefill_sweep_hbm_traffic.txt): mean over its 12 shapes, one launch each
+PREFILL_TRAFFIC_BYTES_PER_LAUNCH = 325.0e6
 
 
 def alg_bytes(m, k, n, out_bytes=2):
@@ -74,6 +81,13 @@ def capture(fn):
     with torch.cuda.graph(g):
         fn()
     return g
+
+
+class Eager:
+    """Stand-in for a captured graph that launches its kernels one by one."""
+
+    def __init__(self, fn):
+        self.replay = fn
 
 
 def time_graphs(graphs, reps, warmup):
@@ -135,7 +149,18 @@ def measured_ceilings(dev):
     t1.record()
     torch.cuda.synchronize()
     gbs = 5 * buf.numel() / (t0.elapsed_time(t1) * 1e-3) / 1e9
-    del buf
+    # a plain device-to-device copy of known size (1 GiB read + 1 GiB written): the reference the FETCH_SIZE and
+    # WRITE_SIZE counters of a profiling run are scaled by
+    dst = torch.empty_like(buf)
+    dst.copy_(buf)
+    torch.cuda.synchronize()
+    t0.record()
+    for _ in range(3):
+        dst.copy_(buf)
+    t1.record()
+    torch.cuda.synchronize()
+    copy_gbs = 3 * 2 * buf.numel() / (t0.elapsed_time(t1) * 1e-3) / 1e9
+    del buf, dst
     flop = B.probe_mfma(2000, sink)
     torch.cuda.synchronize()
     t0.record()
@@ -144,7 +169,7 @@ def measured_ceilings(dev):
     t1.record()
     torch.cuda.synchronize()
     tfl = 3 * flop / (t0.elapsed_time(t1) * 1e-3) / 1e12
-    return round(gbs, 1), round(tfl, 1)
+    return round(gbs, 1), round(copy_gbs, 1), round(tfl, 1)
 
 
 def block_latency(dev, steps, warmup):
@@ -184,6 +209,8 @@ def main():
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--no-block", action="store_true")
     ap.add_argument("--prefill-only", action="store_true", help="profiling aid: run only the prefill sweep")
+    ap.add_argument("--eager", action="store_true", help="profiling aid: launch the decode sweep kernel by kernel "
+                    "instead of replaying HIP graphs (for hardware-counter runs)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
@@ -214,8 +241,12 @@ def main():
         with torch.cuda.stream(side):
             step(0)                                                     # eager run before capture
             torch.cuda.synchronize()
-            step_graphs = [capture(lambda i=i: step(i)) for i in range(args.copies)]
-            lin_graphs = [capture(lambda i=i: linears_only(i)) for i in range(args.copies)]
+            if args.eager:
+                step_graphs = [Eager(lambda i=i: step(i)) for i in range(args.copies)]
+                lin_graphs = [Eager(lambda i=i: linears_only(i)) for i in range(args.copies)]
+            else:
+                step_graphs = [capture(lambda i=i: step(i)) for i in range(args.copies)]
+                lin_graphs = [capture(lambda i=i: linears_only(i)) for i in range(args.copies)]
             sec = time_graphs(step_graphs, args.steps, args.warmup)
             lin_sec = time_graphs(lin_graphs, args.steps, args.warmup)
         ms_per_step = sec / args.steps * 1e3
@@ -227,9 +258,10 @@ def main():
             "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "fp8_e4m3", "data": "synthetic",
             "config": {"workload": "configs[1]: decode sweep, Llama-3-8B shapes, M in {1,4,16} x 4 (K,N), INT4 g128 "
                                    "weights, FP8 e4m3 activations, bf16 out; step = 12 x (quantize_act + linear)",
-                       "weight_sets": args.copies, "launch": "HIP graph replay"},
+                       "weight_sets": args.copies, "launch": "eager" if args.eager else "HIP graph replay"},
             "roofline": {"bound": "hbm", "achieved": round(lin_gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                         "frac": round(lin_gbs / HBM_PEAK_GBS, 4), "traffic": None,
+                         "frac": round(lin_gbs / HBM_PEAK_GBS, 4),
+                         "traffic": SKINNY_TRAFFIC_BYTES_PER_LAUNCH.get(args.copies),
                          "kernel": "linear_skinny_kernel", "launches_per_step": len(cases),
                          "avg_launch_us": round(lin_sec / args.steps / len(cases) * 1e6, 3),
                          "alg_bytes_per_launch": step_bytes // len(cases)},
@@ -238,7 +270,7 @@ def main():
 
     if not args.no_prefill:
         pcfg = syn.CONFIGS[3]
-        per_shape, tot_flop, tot_sec = [], 0.0, 0.0
+        per_shape, tot_flop, tot_sec, tot_bytes = [], 0.0, 0.0, 0
         for L in layers:
             for m in (512, 2048, 8192):
                 c = Case(3, L, m, dev, pcfg["frac"], pcfg["mult"])
@@ -258,17 +290,21 @@ def main():
                 per_shape.append({"M": m, "K": L.k, "N": L.n, "us": round(s * 1e6, 2), "tflops": round(flop / s / 1e12, 1)})
                 tot_flop += flop
                 tot_sec += s
+                tot_bytes += alg_bytes(m, L.k, L.n)
                 del c
         tfl = tot_flop / tot_sec / 1e12
         result["prefill"] = {"metric": "W4A8 linear TFLOP/s (prefill sweep, configs[2])", "value": round(tfl, 1),
                              "unit": "TFLOP/s", "shapes": per_shape,
                              "roofline": {"bound": "mfma", "achieved": round(tfl, 1), "peak": FP8_PEAK_TFLOPS,
-                                          "unit": "TFLOP/s", "frac": round(tfl / FP8_PEAK_TFLOPS, 4), "traffic": None,
-                                          "kernel": "linear_mfma_kernel"}}
+                                          "unit": "TFLOP/s", "frac": round(tfl / FP8_PEAK_TFLOPS, 4),
+                                          "traffic": PREFILL_TRAFFIC_BYTES_PER_LAUNCH,
+                                          "alg_bytes_per_launch": tot_bytes // len(per_shape),
+                                          "kernel": "linear_mfma_tall_kernel, linear_mfma_kernel"}}
 
     if not args.prefill_only:
-        hbm, mfma = measured_ceilings(dev)
-        result["measured_ceilings"] = {"stream_read_GBps": hbm, "mfma_e4m3_TFLOPs": mfma}
+        hbm, copy, mfma = measured_ceilings(dev)
+        result["measured_ceilings"] = {"stream_read_GBps": hbm, "copy_read_plus_write_GBps": copy,
+                                       "mfma_e4m3_TFLOPs": mfma}
         result["roofline"]["frac_of_measured"] = round(result["roofline"]["achieved"] / hbm, 4)
         if "prefill" in result:
             result["prefill"]["roofline"]["frac_of_measured"] = round(result["prefill"]["roofline"]["achieved"] / mfma, 4)
