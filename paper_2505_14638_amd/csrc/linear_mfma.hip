@@ -187,22 +187,28 @@ __global__ void __launch_bounds__(WAVES * 64, OCC) linear_mfma_kernel(
 }
 
 // The tall workgroup shape (256 tokens x 128 channels, eight wavefronts, one weight band each) as its own kernel with
-// a hand-laid software pipeline: the nibble expansion of the NEXT chunk's band is spread over the sixteen MFMAs of the
-// current chunk (one dword, 14 ALU ops, every fourth MFMA) instead of running as a burst that idles the matrix unit,
-// and the raw nibbles are fetched two chunks ahead.  Two raw buffers and two operand buffers alternate by chunk
-// parity, so nothing is copied.
+// a hand-laid software pipeline.
+//   - Everything the main loop reads from global memory travels global -> LDS without passing through registers
+//     (lds_dma_*): the activation block of the next chunk (shared, double buffered), and -- into slots private to
+//     each wavefront -- the raw nibbles and the group scales of the band one chunk further ahead.  The loop therefore
+//     holds no register-destination global load, and the only wait for memory is one `vmcnt(0)` at the end of a chunk,
+//     a full chunk of MFMAs after the copies were issued.
+//   - The nibble expansion of the NEXT chunk's band is spread over the sixteen MFMAs of the current chunk (one dword
+//     every fourth MFMA) instead of running as a burst that idles the matrix unit.  Two operand buffers alternate by
+//     chunk parity, so nothing is copied.
 template <typename OutT>
 __global__ void __launch_bounds__(512, 4) linear_mfma_tall_kernel(
     const uint8_t* __restrict__ x8, int M, int64_t ldx8, const float* __restrict__ s_x,
     const uint8_t* __restrict__ packed, const float* __restrict__ scales, int N, int n_tiles, int C, int cpg, int NG,
     OutT* __restrict__ y, int64_t ldy, int grid_m, int grid_n) {
     constexpr int WAVES = 8, MF = 16, BN = 128, BM = 256, STAGE_BYTES = BM * 128, DMA_PER_WAVE = 4;
+    constexpr int RAW_OFF = 2 * STAGE_BYTES;                     // per wavefront: 1 KiB of raw nibbles (one tile)
+    constexpr int SC_OFF = RAW_OFF + WAVES * 1024;               // per wavefront: 256 B, the band's 16 scales x 4 copies
+    constexpr int LDS_BYTES = SC_OFF + WAVES * 256;
     constexpr int RS = BN + 16 / sizeof(OutT);
     constexpr int SLAB16_BYTES = 16 * RS * (int)sizeof(OutT);
-    constexpr int LDS_BYTES = 2 * STAGE_BYTES;
-    constexpr int FR = (LDS_BYTES / SLAB16_BYTES < MF) ? LDS_BYTES / SLAB16_BYTES : MF;
+    constexpr int FR = (RAW_OFF / SLAB16_BYTES < MF) ? RAW_OFF / SLAB16_BYTES : MF;
     __shared__ __attribute__((aligned(16))) uint8_t lds[LDS_BYTES];
-    uint8_t (*xs)[STAGE_BYTES] = reinterpret_cast<uint8_t (*)[STAGE_BYTES]>(lds);
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int kq = lane >> 4, i = lane & 15;
@@ -219,8 +225,11 @@ __global__ void __launch_bounds__(512, 4) linear_mfma_tall_kernel(
     const int m0 = bm * BM;
     const int t = min(bn * (BN / 16) + wave, n_tiles - 1);       // bands past the end reload the last one; not stored
 
-    const uint8_t* wbase = packed + (int64_t)t * C * 1024 + lane * 16;
-    const uint8_t* sbase = reinterpret_cast<const uint8_t*>(scales) + (int64_t)t * NG * 64 + i * 4;
+    // wave-uniform bases (scalar registers) and small per-lane offsets
+    const uint8_t* wbase = packed + (int64_t)t * C * 1024;       // + c * 1024 + lane * 16
+    const uint8_t* sbase = reinterpret_cast<const uint8_t*>(scales) + (int64_t)t * NG * 64;   // + g * 64 + i * 4
+    const uint8_t* xrow0 = x8 + (int64_t)m0 * ldx8;              // + c * 128 + xvoff
+    const uint32_t woff = lane * 16, soff = i * 4;
     uint32_t xvoff[DMA_PER_WAVE];
 #pragma unroll
     for (int q = 0; q < DMA_PER_WAVE; ++q) {
@@ -228,38 +237,48 @@ __global__ void __launch_bounds__(512, 4) linear_mfma_tall_kernel(
         const int row = (d >> 1) * 16 + i;
         xvoff[q] = (uint32_t)(min(m0 + row, M - 1) - m0) * (uint32_t)ldx8 + kq * 32 + (d & 1) * 16;
     }
-    const uint8_t* xrow0 = x8 + (int64_t)m0 * ldx8;
+    const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint8_t*)lds;
+    const uint32_t lds_x = lds0 + (uint32_t)wave * (DMA_PER_WAVE * 1024);
+    const uint32_t lds_raw = lds0 + RAW_OFF + (uint32_t)wave * 1024, lds_sc = lds0 + SC_OFF + (uint32_t)wave * 256;
+    const uint8_t* my_raw = lds + RAW_OFF + wave * 1024 + lane * 16;
+    const uint8_t* my_sc = lds + SC_OFF + wave * 256 + lane * 4;
 
     auto stage_x = [&](int c, int buf) {
         const uint8_t* xsrc = xrow0 + (int64_t)c * 128;
 #pragma unroll
-        for (int q = 0; q < DMA_PER_WAVE; ++q)
-            __builtin_amdgcn_global_load_lds(
-                (const __attribute__((address_space(1))) void*)(xsrc + xvoff[q]),
-                (__attribute__((address_space(3))) void*)&xs[buf][(wave * DMA_PER_WAVE + q) * 1024], 16, 0, 0);
+        for (int q = 0; q < DMA_PER_WAVE; ++q) lds_dma_16(xsrc, xvoff[q], lds_x + (uint32_t)buf * STAGE_BYTES + q * 1024);
     };
-    int g = 0, g_left = cpg;                                     // group of the next chunk to be fetched
-    int c_fetch = 0;
-    auto fetch_w = [&](uint4& raw, float& s) {                   // raw nibbles and scale of chunk c_fetch, then advance
-        raw = *reinterpret_cast<const uint4*>(wbase + (int64_t)c_fetch * 1024);
-        s = *reinterpret_cast<const float*>(sbase + (int64_t)g * 64);
-        ++c_fetch;
-        if (--g_left == 0) { ++g; g_left = cpg; }
+    // Copies the band's tile and scales of chunk c into the wavefront's slots.  `after` is a value read from those
+    // slots earlier: the copy is issued only once that read has returned.
+    auto stage_w = [&](int c, uint32_t after) {
+        lds_dma_16_after(wbase + (int64_t)c * 1024, woff, lds_raw, after);
+        lds_dma_4(sbase + (int64_t)(c / cpg) * 64, soff, lds_sc);
     };
 
     v4f acc[MF];
 #pragma unroll
     for (int f = 0; f < MF; ++f) acc[f] = v4f{0.f, 0.f, 0.f, 0.f};
 
-    // One chunk: multiply with `cur`; meanwhile expand `raw_next` (chunk c+1) into `next` and fetch chunk c+2 into `raw_far`.
-    auto chunk = [&](int c, const v8i& cur, float s_cur, const uint4& raw_next, v8i& next, uint4& raw_far, float& s_far) {
+    // One chunk: multiply with `cur`; meanwhile read chunk c+1's nibbles and scale from the slots, expand them into
+    // `next`, and start the copies of chunk c+2.
+    auto chunk = [&](int c, const v8i& cur, float s_cur, v8i& next, float& s_next) {
         const int buf = c & 1;
         if (c + 1 < C) stage_x(c + 1, buf ^ 1);
-        if (c + 2 < C) fetch_w(raw_far, s_far);
-        const uint8_t* xb = &xs[buf][lane * 16];
+        uint4 raw = make_uint4(0u, 0u, 0u, 0u);
+        if (c + 1 < C) {
+            raw = *reinterpret_cast<const uint4*>(my_raw);
+            s_next = *reinterpret_cast<const float*>(my_sc);
+            if (c + 2 < C) stage_w(c + 2, raw.x ^ __float_as_uint(s_next));
+        }
+        const uint32_t rn[4] = {raw.x, raw.y, raw.z, raw.w};
+        const uint8_t* xb = lds + buf * STAGE_BYTES + lane * 16;
         uint4 xa = *reinterpret_cast<const uint4*>(xb);
         uint4 xc = *reinterpret_cast<const uint4*>(xb + 1024);
-        const uint32_t rn[4] = {raw_next.x, raw_next.y, raw_next.z, raw_next.w};
+        // Step f: start the LDS reads of block f+1, issue the MFMA of block f, and fold the result of block f-1 (it
+        // finished while this wavefront was waiting for its turn on the matrix unit) into the running sums.  The
+        // scheduling fences keep the steps apart: without them the compiler batches all MFMAs before all FMAs and
+        // needs sixteen result tiles of registers.
+        v4f p_prev = v4f{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int f = 0; f < MF; ++f) {
             const v8i xop = v8i{(int)xa.x, (int)xa.y, (int)xa.z, (int)xa.w, (int)xc.x, (int)xc.y, (int)xc.z, (int)xc.w};
@@ -268,38 +287,48 @@ __global__ void __launch_bounds__(512, 4) linear_mfma_tall_kernel(
                 xc = *reinterpret_cast<const uint4*>(xb + (f + 1) * 2048 + 1024);
             }
             const v4f p = mfma_16x16x128_e4m3(xop, cur, v4f{0.f, 0.f, 0.f, 0.f});
+            if (f > 0) {
+                acc[f - 1][0] = fmaf(s_cur, p_prev[0], acc[f - 1][0]);
+                acc[f - 1][1] = fmaf(s_cur, p_prev[1], acc[f - 1][1]);
+                acc[f - 1][2] = fmaf(s_cur, p_prev[2], acc[f - 1][2]);
+                acc[f - 1][3] = fmaf(s_cur, p_prev[3], acc[f - 1][3]);
+                keep_here(acc[f - 1]);
+            }
             if ((f & 3) == 1) {                                  // a quarter of the next band's expansion
                 uint32_t lo, hi;
                 nibbles_to_e4m3(rn[f >> 2], lo, hi);
+                keep_here(lo, hi);
                 next[2 * (f >> 2)] = (int)lo;
                 next[2 * (f >> 2) + 1] = (int)hi;
             }
-            acc[f][0] = fmaf(s_cur, p[0], acc[f][0]);
-            acc[f][1] = fmaf(s_cur, p[1], acc[f][1]);
-            acc[f][2] = fmaf(s_cur, p[2], acc[f][2]);
-            acc[f][3] = fmaf(s_cur, p[3], acc[f][3]);
+            p_prev = p;
+            __builtin_amdgcn_sched_barrier(0);
         }
-        __syncthreads();
+        acc[MF - 1][0] = fmaf(s_cur, p_prev[0], acc[MF - 1][0]);
+        acc[MF - 1][1] = fmaf(s_cur, p_prev[1], acc[MF - 1][1]);
+        acc[MF - 1][2] = fmaf(s_cur, p_prev[2], acc[MF - 1][2]);
+        acc[MF - 1][3] = fmaf(s_cur, p_prev[3], acc[MF - 1][3]);
+        lds_dma_wait_all();                                      // this wavefront's copies have landed ...
+        __syncthreads();                                         // ... and so have everyone's; the block just read is free
     };
 
-    uint4 raw_a, raw_b = make_uint4(0u, 0u, 0u, 0u);
-    float s_raw_a = 0.f, s_raw_b = 0.f;
     v8i wop_a, wop_b;
+    float s_a, s_b = 0.f;
     stage_x(0, 0);
-    fetch_w(raw_a, s_raw_a);                                     // chunk 0
-    if (C > 1) fetch_w(raw_b, s_raw_b);                          // chunk 1
-    wop_a = slot_to_operand(raw_a);
-    float s_a = s_raw_a, s_b = 0.f;
+    stage_w(0, 0u);
+    lds_dma_wait_all();
+    {
+        const uint4 raw0 = *reinterpret_cast<const uint4*>(my_raw);
+        s_a = *reinterpret_cast<const float*>(my_sc);
+        if (C > 1) stage_w(1, raw0.x ^ __float_as_uint(s_a));
+        wop_a = slot_to_operand(raw0);
+    }
+    lds_dma_wait_all();
     __syncthreads();
 
     for (int c = 0; c < C; c += 2) {
-        // even chunk: operand A multiplies, raw B (chunk c+1) expands into operand B, chunk c+2 lands in raw A
-        s_b = s_raw_b;
-        chunk(c, wop_a, s_a, raw_b, wop_b, raw_a, s_raw_a);
-        if (c + 1 < C) {
-            s_a = s_raw_a;
-            chunk(c + 1, wop_b, s_b, raw_a, wop_a, raw_b, s_raw_b);
-        }
+        chunk(c, wop_a, s_a, wop_b, s_b);                        // even chunk: A multiplies, chunk c+1 expands into B
+        if (c + 1 < C) chunk(c + 1, wop_b, s_b, wop_a, s_a);
     }
 
     const float sx = *s_x;
@@ -343,7 +372,7 @@ __global__ void __launch_bounds__(512, 4) linear_mfma_tall_kernel(
 int launch_linear_mfma_tiled(const uint8_t* x8, int64_t M, int64_t K, int64_t ldx8, const float* s_x,
                              const uint8_t* packed, const float* scales, int64_t N, int32_t G, void* y,
                              w4a8_dtype ydt, int64_t ldy, int variant, hipStream_t st) {
-    if (variant < 0 || variant > 5) return W4A8_ERR_SHAPE;      // 0 auto, 1 four-wave, 2 64x256, 3 128x256, 4 256x128
+    if (variant < 0 || variant > 6) return W4A8_ERR_SHAPE;      // 0 auto, 1 four-wave, 2 64x256, 3 128x256, 4 256x128
     const int C = (int)(K / 128), cpg = G / 128, NG = (int)(K / G);
     const int n_tiles = (int)((N + 15) / 16);
     // Workgroup shape.  Tall (256 tokens x 128 channels, one weight band per wavefront) amortizes the nibble expansion
@@ -352,6 +381,7 @@ int launch_linear_mfma_tiled(const uint8_t* x8, int64_t M, int64_t K, int64_t ld
     if (variant == 1 || variant == 3) { mf = 8; bn = 256; }
     bool pipelined = (variant == 5);
     if (variant == 2) { mf = 4; bn = 256; }
+    if (variant == 6) { mf = 16; bn = 256; }
     if (variant == 0) {
         const int64_t wg_tall = ((M + 255) / 256) * (int64_t)((n_tiles * 16 + 127) / 128);
         const int64_t wg_mid = ((M + 127) / 128) * (int64_t)((n_tiles * 16 + 255) / 256);
@@ -375,6 +405,8 @@ int launch_linear_mfma_tiled(const uint8_t* x8, int64_t M, int64_t K, int64_t ld
         else
             hipLaunchKernelGGL(linear_mfma_tall_kernel<uint16_t>, grid, dim3(512), 0, st, x8, (int)M, ldx8, s_x, packed,
                                scales, (int)N, n_tiles, C, cpg, NG, static_cast<uint16_t*>(y), ldy, grid_m, grid_n);
+    } else if (variant == 6) {
+        if (ydt == W4A8_F32) W4A8_LAUNCH_MFMA(float, 8, 2, 16, 256); else W4A8_LAUNCH_MFMA(uint16_t, 8, 2, 16, 256);
     } else if (variant == 1) {
         if (ydt == W4A8_F32) W4A8_LAUNCH_MFMA(float, 4, 2, 8, 256); else W4A8_LAUNCH_MFMA(uint16_t, 4, 2, 8, 256);
     } else if (mf == 16) {

@@ -56,6 +56,43 @@ __device__ __forceinline__ v4f mfma_16x16x128_e4m3(v8i a, v8i b, v4f c) {
     return __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(a, b, c, 0 /*A: E4M3*/, 0 /*B: E4M3*/, 0, 0, 0, 0);
 }
 
+// Global memory -> LDS without staging registers: each lane copies 16 (4) bytes from base + offset (base
+// wave-uniform, offset per lane) to LDS byte address lds_addr + 16 (4) * lane (lds_addr wave-uniform).  Written as
+// assembly so that the compiler's wait-count pass does not treat the copy as an LDS store that every later LDS read
+// might alias (it would wait for the just-issued prefetch before each read).  The caller orders a copy against its
+// readers with lds_dma_wait_all() (plus a workgroup barrier when other wavefronts read the data), and against earlier
+// reads of the destination with the `after` argument: a value obtained from those reads, which the copy waits for.
+// A kernel that uses these must not also use the compiler's own LDS-copy builtins (both program M0).
+__device__ __forceinline__ void lds_dma_16(const uint8_t* base, uint32_t offset, uint32_t lds_addr) {
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+                 :
+                 : "v"(offset), "s"(base), "s"(lds_addr)
+                 : "memory");
+}
+__device__ __forceinline__ void lds_dma_16_after(const uint8_t* base, uint32_t offset, uint32_t lds_addr, uint32_t after) {
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+                 :
+                 : "v"(offset), "s"(base), "s"(lds_addr), "v"(after)
+                 : "memory");
+}
+__device__ __forceinline__ void lds_dma_4(const uint8_t* base, uint32_t offset, uint32_t lds_addr) {
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dword %0, %1"
+                 :
+                 : "v"(offset), "s"(base), "s"(lds_addr)
+                 : "memory");
+}
+
+// Waits until every outstanding global load of this wavefront, the copies above included, has completed.
+__device__ __forceinline__ void lds_dma_wait_all() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+
+// Marks the point in program order at which the four values must have been computed: an empty statement the
+// compiler can neither move code across nor sink the producers of `v` below.  Emits no instruction.
+__device__ __forceinline__ void keep_here(v4f& v) {
+    asm volatile("" : "+v"(v[0]), "+v"(v[1]), "+v"(v[2]), "+v"(v[3]));
+}
+
+__device__ __forceinline__ void keep_here(uint32_t& a, uint32_t& b) { asm volatile("" : "+v"(a), "+v"(b)); }
+
 // float32 -> bf16 bits, round to nearest even (NaN stays NaN).
 __device__ __forceinline__ uint16_t f32_to_bf16_bits(float f) {
     const uint32_t u = __float_as_uint(f);
