@@ -230,13 +230,22 @@ __global__ void __launch_bounds__(512, 4) linear_mfma_tall_kernel(
     const uint8_t* sbase = reinterpret_cast<const uint8_t*>(scales) + (int64_t)t * NG * 64;   // + g * 64 + i * 4
     const uint8_t* xrow0 = x8 + (int64_t)m0 * ldx8;              // + c * 128 + xvoff
     const uint32_t woff = lane * 16, soff = i * 4;
+    // Activation block in LDS: 16-token block f = 2 KiB = two 1 KiB pages of 8 rows x 128 bytes; 16-byte segment sg
+    // (0..7) of row r (0..15) sits in page r / 8 at slot (r % 8) * 8 + (sg ^ ((r >> 1) & 7)).  One copy instruction
+    // fills one page from eight whole 128-byte row segments of global memory (whole cache lines: the L2 -> CU path
+    // moves about 2.5x more bytes per clock than with half lines), and the swizzle makes the two ds_read_b128 of an
+    // operand (segments 2kq, 2kq+1 of row i, sixteen rows per quarter-wave) conflict-free.
     uint32_t xvoff[DMA_PER_WAVE];
 #pragma unroll
     for (int q = 0; q < DMA_PER_WAVE; ++q) {
-        const int d = wave * DMA_PER_WAVE + q;                   // half-block index: f = d / 2, h = d % 2
-        const int row = (d >> 1) * 16 + i;
-        xvoff[q] = (uint32_t)(min(m0 + row, M - 1) - m0) * (uint32_t)ldx8 + kq * 32 + (d & 1) * 16;
+        const int d = wave * DMA_PER_WAVE + q;                   // page index: f = d / 2, rows 8 * (d % 2) .. + 7
+        const int r = (d & 1) * 8 + (lane >> 3);
+        const int sg = (lane & 7) ^ ((r >> 1) & 7);
+        const int row = (d >> 1) * 16 + r;
+        xvoff[q] = (uint32_t)(min(m0 + row, M - 1) - m0) * (uint32_t)ldx8 + sg * 16;
     }
+    const uint32_t xa_off = (i >> 3) * 1024 + ((i & 7) * 8 + ((2 * kq) ^ ((i >> 1) & 7))) * 16;
+    const uint32_t xc_off = (i >> 3) * 1024 + ((i & 7) * 8 + ((2 * kq + 1) ^ ((i >> 1) & 7))) * 16;
     const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint8_t*)lds;
     const uint32_t lds_x = lds0 + (uint32_t)wave * (DMA_PER_WAVE * 1024);
     const uint32_t lds_raw = lds0 + RAW_OFF + (uint32_t)wave * 1024, lds_sc = lds0 + SC_OFF + (uint32_t)wave * 256;
@@ -271,9 +280,9 @@ __global__ void __launch_bounds__(512, 4) linear_mfma_tall_kernel(
             if (c + 2 < C) stage_w(c + 2, raw.x ^ __float_as_uint(s_next));
         }
         const uint32_t rn[4] = {raw.x, raw.y, raw.z, raw.w};
-        const uint8_t* xb = lds + buf * STAGE_BYTES + lane * 16;
-        uint4 xa = *reinterpret_cast<const uint4*>(xb);
-        uint4 xc = *reinterpret_cast<const uint4*>(xb + 1024);
+        const uint8_t* xb = lds + buf * STAGE_BYTES;
+        uint4 xa = *reinterpret_cast<const uint4*>(xb + xa_off);
+        uint4 xc = *reinterpret_cast<const uint4*>(xb + xc_off);
         // Step f: start the LDS reads of block f+1, issue the MFMA of block f, and fold the result of block f-1 (it
         // finished while this wavefront was waiting for its turn on the matrix unit) into the running sums.  The
         // scheduling fences keep the steps apart: without them the compiler batches all MFMAs before all FMAs and
@@ -283,8 +292,8 @@ __global__ void __launch_bounds__(512, 4) linear_mfma_tall_kernel(
         for (int f = 0; f < MF; ++f) {
             const v8i xop = v8i{(int)xa.x, (int)xa.y, (int)xa.z, (int)xa.w, (int)xc.x, (int)xc.y, (int)xc.z, (int)xc.w};
             if (f + 1 < MF) {
-                xa = *reinterpret_cast<const uint4*>(xb + (f + 1) * 2048);
-                xc = *reinterpret_cast<const uint4*>(xb + (f + 1) * 2048 + 1024);
+                xa = *reinterpret_cast<const uint4*>(xb + xa_off + (f + 1) * 2048);
+                xc = *reinterpret_cast<const uint4*>(xb + xc_off + (f + 1) * 2048);
             }
             const v4f p = mfma_16x16x128_e4m3(xop, cur, v4f{0.f, 0.f, 0.f, 0.f});
             if (f > 0) {
@@ -294,14 +303,15 @@ __global__ void __launch_bounds__(512, 4) linear_mfma_tall_kernel(
                 acc[f - 1][3] = fmaf(s_cur, p_prev[3], acc[f - 1][3]);
                 keep_here(acc[f - 1]);
             }
-            if ((f & 3) == 1) {                                  // a quarter of the next band's expansion
-                uint32_t lo, hi;
-                nibbles_to_e4m3(rn[f >> 2], lo, hi);
-                keep_here(lo, hi);
-                next[2 * (f >> 2)] = (int)lo;
-                next[2 * (f >> 2) + 1] = (int)hi;
+            if ((f & 1) == 1) {                                  // an eighth of the next band's expansion
+                uint32_t e = (f & 2) ? nibbles_half_to_e4m3<4>(rn[f >> 2]) : nibbles_half_to_e4m3<0>(rn[f >> 2]);
+                keep_here(e);
+                next[f >> 1] = (int)e;
             }
             p_prev = p;
+            __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);   // LDS reads of the next block
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // this block's MFMA
+            __builtin_amdgcn_sched_group_barrier(0x002, 12, 0);  // vector ALU work that does not depend on it
             __builtin_amdgcn_sched_barrier(0);
         }
         acc[MF - 1][0] = fmaf(s_cur, p_prev[0], acc[MF - 1][0]);
@@ -314,13 +324,12 @@ __global__ void __launch_bounds__(512, 4) linear_mfma_tall_kernel(
 
     v8i wop_a, wop_b;
     float s_a, s_b = 0.f;
-    stage_x(0, 0);
-    stage_w(0, 0u);
-    lds_dma_wait_all();
     {
-        const uint4 raw0 = *reinterpret_cast<const uint4*>(my_raw);
-        s_a = *reinterpret_cast<const float*>(my_sc);
-        if (C > 1) stage_w(1, raw0.x ^ __float_as_uint(s_a));
+        // chunk 0's band comes through registers, so that chunk 1's copies into the slots need not wait for it
+        const uint4 raw0 = *reinterpret_cast<const uint4*>(wbase + woff);
+        s_a = *reinterpret_cast<const float*>(sbase + soff);
+        stage_x(0, 0);
+        if (C > 1) stage_w(1, 0u);
         wop_a = slot_to_operand(raw0);
     }
     lds_dma_wait_all();

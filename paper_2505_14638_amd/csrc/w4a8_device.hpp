@@ -18,21 +18,23 @@ typedef float v4f __attribute__((ext_vector_type(4)));
 //   value   0    1    2    3    4    5    6    7     |  -8   -7   -6   -5   -4   -3   -2   -1
 //   E4M3   00   38   40   44   48   4A   4C   4E     |  D0   CE   CC   CA   C8   C4   C0   B8
 // ---------------------------------------------------------------------------------------------
-__device__ __forceinline__ void nibbles_to_e4m3(uint32_t w, uint32_t& lo, uint32_t& hi) {
+// E4M3 bytes of the four nibbles at bit offset `shift` (0: low nibbles, 4: high nibbles) of the bytes of w.
+template <int SHIFT>
+__device__ __forceinline__ uint32_t nibbles_half_to_e4m3(uint32_t w) {
     const uint32_t POS_LO = 0x44403800u, POS_HI = 0x4E4C4A48u;   // values 0..3, 4..7
     const uint32_t NEG_LO = 0xCACCCED0u, NEG_HI = 0xB8C0C4C8u;   // values -8..-5, -4..-1
-    const uint32_t sel_l = w & 0x07070707u;
-    const uint32_t sel_h = (w >> 4) & 0x07070707u;
+    const uint32_t sel = (w >> SHIFT) & 0x07070707u;
     // v_perm_b32(S0, S1, sel): selector 0..3 -> bytes of S1, 4..7 -> bytes of S0
-    const uint32_t pos_l = __builtin_amdgcn_perm(POS_HI, POS_LO, sel_l);
-    const uint32_t neg_l = __builtin_amdgcn_perm(NEG_HI, NEG_LO, sel_l);
-    const uint32_t pos_h = __builtin_amdgcn_perm(POS_HI, POS_LO, sel_h);
-    const uint32_t neg_h = __builtin_amdgcn_perm(NEG_HI, NEG_LO, sel_h);
+    const uint32_t pos = __builtin_amdgcn_perm(POS_HI, POS_LO, sel);
+    const uint32_t neg = __builtin_amdgcn_perm(NEG_HI, NEG_LO, sel);
     // byte i of the result = byte i of pos (selector i) or of neg (selector i + 4)
-    const uint32_t mix_l = ((w >> 1) & 0x04040404u) | 0x03020100u;
-    const uint32_t mix_h = ((w >> 5) & 0x04040404u) | 0x03020100u;
-    lo = __builtin_amdgcn_perm(neg_l, pos_l, mix_l);
-    hi = __builtin_amdgcn_perm(neg_h, pos_h, mix_h);
+    const uint32_t mix = ((w >> (SHIFT + 1)) & 0x04040404u) | 0x03020100u;
+    return __builtin_amdgcn_perm(neg, pos, mix);
+}
+
+__device__ __forceinline__ void nibbles_to_e4m3(uint32_t w, uint32_t& lo, uint32_t& hi) {
+    lo = nibbles_half_to_e4m3<0>(w);
+    hi = nibbles_half_to_e4m3<4>(w);
 }
 
 // The 16 bytes (four dwords) of one tiled-layout slot -> the 32 operand bytes of one lane, in the order the
@@ -92,6 +94,7 @@ __device__ __forceinline__ void keep_here(v4f& v) {
 }
 
 __device__ __forceinline__ void keep_here(uint32_t& a, uint32_t& b) { asm volatile("" : "+v"(a), "+v"(b)); }
+__device__ __forceinline__ void keep_here(uint32_t& a) { asm volatile("" : "+v"(a)); }
 
 // float32 -> bf16 bits, round to nearest even (NaN stays NaN).
 __device__ __forceinline__ uint16_t f32_to_bf16_bits(float f) {
