@@ -299,7 +299,7 @@ def main():
                                           "unit": "TFLOP/s", "frac": round(tfl / FP8_PEAK_TFLOPS, 4),
                                           "traffic": PREFILL_TRAFFIC_BYTES_PER_LAUNCH,
                                           "alg_bytes_per_launch": tot_bytes // len(per_shape),
-                                          "kernel": "linear_mfma_tall_kernel, linear_mfma_kernel"}}
+                                          "kernel": "linear_mfma_kernel"}}
 
     if not args.prefill_only:
         hbm, copy, mfma = measured_ceilings(dev)

@@ -107,8 +107,9 @@ size_t w4a8_linear_workspace_bytes(int64_t M, int64_t K, int64_t N, int32_t grou
  *   packed_dev, w_scales_dev   as written by w4a8_pack_weights for the same N, K, group_size, layout
  *   y_dev         out [M, N], float32 or bf16 (round to nearest even), row stride ldy elements
  *   workspace_dev may be NULL when w4a8_linear_workspace_bytes() is 0
- * Kernel choice depends only on (M, K, N, layout): M <= 64 takes the bandwidth-bound skinny path, larger M
- * the MFMA-tiled path; CANONICAL always takes a plain reference-speed kernel.  M == 0 is a no-op.
+ * Kernel choice depends only on (M, K, N, layout): up to 32 tokens (64 for K >= 8192 with N <= 8192) take the
+ * bandwidth-bound skinny path, larger M the MFMA-tiled path; CANONICAL always takes a plain reference-speed kernel.
+ * M == 0 is a no-op.
  */
 int w4a8_linear(const uint8_t* x8_dev, int64_t M, int64_t K, int64_t ldx8, const float* x_scale_dev,
                 const uint8_t* packed_dev, const float* w_scales_dev, int64_t N, int32_t group_size,
@@ -118,10 +119,11 @@ int w4a8_linear(const uint8_t* x8_dev, int64_t M, int64_t K, int64_t ldx8, const
 /*
  * Same as w4a8_linear for W4A8_LAYOUT_TILED with the launch shape chosen by the caller; for tuning sweeps.
  *   path    0 = skinny (M <= 64), 1 = MFMA-tiled
- *   param0  skinny: n-tiles (of 16 rows) per wave, 1, 2 or 4.   tiled: 0 auto, 1 four wavefronts per workgroup,
- *           2 = 64 tokens x 256 channels per workgroup, 3 = 128 x 256, 4 = 256 x 128, 5 = 256 x 128 software-pipelined
+ *   param0  skinny: n-tiles (of 16 rows) per wave, 1, 2 or 4.   tiled: 16-token blocks per workgroup, 4, 8 or 16
+ *           (the workgroup covers 16 * param0 tokens); 0 = chosen from the shape
  *   param1  skinny: waves per workgroup (K is split across them), 1..16, plus 256 * chunks in flight per wave
- *           (0 auto, 2 or 4).   tiled: reserved, pass 0
+ *           (0 auto, 2 or 4).   tiled: K-split groups per workgroup, 1, 2 or 4 (the workgroup covers 128 / param1
+ *           channels); 0 = chosen from the shape; 16 blocks with 4 groups is not offered
  * Unsupported combinations return W4A8_ERR_SHAPE.
  */
 int w4a8_linear_variant(const uint8_t* x8_dev, int64_t M, int64_t K, int64_t ldx8, const float* x_scale_dev,

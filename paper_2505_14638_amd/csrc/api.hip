@@ -94,11 +94,15 @@ int w4a8_linear(const uint8_t* x8_dev, int64_t M, int64_t K, int64_t ldx8, const
     if (layout == W4A8_LAYOUT_CANONICAL)
         return launch_linear_canonical(x8_dev, M, K, ldx8, x_scale_dev, packed_dev, w_scales_dev, N, group_size, y_dev,
                                        y_dtype, ldy, st);
-    if (M <= 64)
+    // Few tokens: the skinny kernel streams the weights once with K split across wavefronts.  From 33 tokens on the
+    // MFMA-tiled kernel (activations staged once per workgroup, nibble expansion shared by several token blocks) is
+    // faster, except for deep, narrow layers, where the skinny kernel's finer split of K still wins up to 64 tokens.
+    const bool deep_narrow = K >= 8192 && N <= 8192;
+    if (M <= 32 || (M <= 64 && deep_narrow))
         return launch_linear_skinny(x8_dev, M, K, ldx8, x_scale_dev, packed_dev, w_scales_dev, N, group_size, y_dev,
                                     y_dtype, ldy, 0, 0, 0, st);
     return launch_linear_mfma_tiled(x8_dev, M, K, ldx8, x_scale_dev, packed_dev, w_scales_dev, N, group_size, y_dev,
-                                    y_dtype, ldy, 0, st);
+                                    y_dtype, ldy, 0, 0, st);
 }
 
 int w4a8_linear_variant(const uint8_t* x8_dev, int64_t M, int64_t K, int64_t ldx8, const float* x_scale_dev,
@@ -117,7 +121,7 @@ int w4a8_linear_variant(const uint8_t* x8_dev, int64_t M, int64_t K, int64_t ldx
     }
     if (path == 1)
         return launch_linear_mfma_tiled(x8_dev, M, K, ldx8, x_scale_dev, packed_dev, w_scales_dev, N, group_size, y_dev,
-                                        y_dtype, ldy, param0, st);
+                                        y_dtype, ldy, param0, param1, st);
     return W4A8_ERR_SHAPE;
 }
 
