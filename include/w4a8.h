@@ -122,8 +122,9 @@ int w4a8_linear(const uint8_t* x8_dev, int64_t M, int64_t K, int64_t ldx8, const
  *   param0  skinny: n-tiles (of 16 rows) per wave, 1, 2 or 4.   tiled: 16-token blocks per workgroup, 4, 8 or 16
  *           (the workgroup covers 16 * param0 tokens); 0 = chosen from the shape
  *   param1  skinny: waves per workgroup (K is split across them), 1..16, plus 256 * chunks in flight per wave
- *           (0 auto, 2 or 4).   tiled: K-split groups per workgroup, 1, 2 or 4 (the workgroup covers 128 / param1
- *           channels); 0 = chosen from the shape; 16 blocks with 4 groups is not offered
+ *           (0 auto, 2 or 4).   tiled: K-split groups per workgroup (1, 2 or 4; 0 = chosen) plus 256 * weight bands
+ *           per wavefront (1 or 2; 0 = chosen): the workgroup covers 128 * bands / groups channels.  Built shapes
+ *           (blocks, groups, bands): (16,1,1) (8,1,1) (8,2,1) (4,1,1) (4,2,1) (4,4,1) (16,1,2)
  * Unsupported combinations return W4A8_ERR_SHAPE.
  */
 int w4a8_linear_variant(const uint8_t* x8_dev, int64_t M, int64_t K, int64_t ldx8, const float* x_scale_dev,

@@ -102,7 +102,7 @@ int w4a8_linear(const uint8_t* x8_dev, int64_t M, int64_t K, int64_t ldx8, const
         return launch_linear_skinny(x8_dev, M, K, ldx8, x_scale_dev, packed_dev, w_scales_dev, N, group_size, y_dev,
                                     y_dtype, ldy, 0, 0, 0, st);
     return launch_linear_mfma_tiled(x8_dev, M, K, ldx8, x_scale_dev, packed_dev, w_scales_dev, N, group_size, y_dev,
-                                    y_dtype, ldy, 0, 0, st);
+                                    y_dtype, ldy, 0, 0, 0, st);
 }
 
 int w4a8_linear_variant(const uint8_t* x8_dev, int64_t M, int64_t K, int64_t ldx8, const float* x_scale_dev,
@@ -121,7 +121,7 @@ int w4a8_linear_variant(const uint8_t* x8_dev, int64_t M, int64_t K, int64_t ldx
     }
     if (path == 1)
         return launch_linear_mfma_tiled(x8_dev, M, K, ldx8, x_scale_dev, packed_dev, w_scales_dev, N, group_size, y_dev,
-                                        y_dtype, ldy, param0, param1, st);
+                                        y_dtype, ldy, param0, param1 & 0xFF, param1 >> 8, st);
     return W4A8_ERR_SHAPE;
 }
 

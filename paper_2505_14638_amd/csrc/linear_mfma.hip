@@ -31,22 +31,27 @@ constexpr int XCDS = 8;
 constexpr int GROUP_M = 8;          // token blocks per super-column of the block order
 constexpr int WAVES = 8;
 
+// Built workgroup shapes {token blocks, K-split groups, bands per wavefront}, in the launcher's order of preference
+// (the last one is considered first, under its own condition).
+#define W4A8_MFMA_SHAPES 7
+#define W4A8_MFMA_SHAPE_LIST {{16, 1, 1}, {8, 1, 1}, {8, 2, 1}, {4, 1, 1}, {4, 2, 1}, {4, 4, 1}, {16, 1, 2}}
+
 template <int A, int B> struct MaxOf { static constexpr int value = A > B ? A : B; };
 
-template <typename OutT, int MF, int KS>
-__global__ void __launch_bounds__(512, (KS * MF > 16) ? 2 : 4) linear_mfma_kernel(
+template <typename OutT, int MF, int KS, int TPW>
+__global__ void __launch_bounds__(512, (KS * MF > 16 || MF * TPW > 16) ? 2 : 4) linear_mfma_kernel(
     const uint8_t* __restrict__ x8, int M, int64_t ldx8, const float* __restrict__ s_x,
     const uint8_t* __restrict__ packed, const float* __restrict__ scales, int N, int n_tiles, int C, int cpg, int NG,
     OutT* __restrict__ y, int64_t ldy, int grid_m, int grid_n) {
-    constexpr int NB = WAVES / KS;                               // weight bands (wavefronts) per K-split group
-    constexpr int BN = 16 * NB, BM = 16 * MF;
+    constexpr int NB = WAVES / KS;                               // wavefronts per K-split group, TPW weight bands each
+    constexpr int BN = 16 * NB * TPW, BM = 16 * MF;
     constexpr int PAGES = KS * MF * 2;                           // 1 KiB pages of activations per pass
     constexpr int STAGE_BYTES = PAGES * 1024, DMA_PER_WAVE = PAGES / WAVES;
     static_assert(PAGES % WAVES == 0, "activation pages must divide evenly among the wavefronts");
-    constexpr int RAW_OFF = 2 * STAGE_BYTES;                     // per wavefront: 1 KiB of raw nibbles (one tile)
-    constexpr int SC_OFF = RAW_OFF + WAVES * 1024;               // per wavefront: 256 B, the band's 16 scales x 4 copies
-    constexpr int LOOP_BYTES = SC_OFF + WAVES * 256;
-    constexpr int RED_BYTES = (KS - 1) * NB * MF * 4 * 64 * 4;   // partial sums of groups 1 .. KS-1
+    constexpr int RAW_OFF = 2 * STAGE_BYTES;                     // per wavefront and band: 1 KiB of raw nibbles (one tile)
+    constexpr int SC_OFF = RAW_OFF + WAVES * TPW * 1024;         // per wavefront and band: 256 B, 16 scales x 4 copies
+    constexpr int LOOP_BYTES = SC_OFF + WAVES * TPW * 256;
+    constexpr int RED_BYTES = (KS - 1) * NB * TPW * MF * 4 * 64 * 4;   // partial sums of groups 1 .. KS-1
     constexpr int RS = BN + 16 / sizeof(OutT);                   // epilogue row stride: rows stay 16-byte aligned
     constexpr int SLAB16_BYTES = 16 * RS * (int)sizeof(OutT);    // one 16-token slab of the workgroup's output
     constexpr int LDS_BYTES = MaxOf<MaxOf<LOOP_BYTES, RED_BYTES>::value, SLAB16_BYTES>::value;
@@ -70,11 +75,16 @@ __global__ void __launch_bounds__(512, (KS * MF > 16) ? 2 : 4) linear_mfma_kerne
     const int in_group = v - group * GROUP_M * grid_n;
     const int bm = first_m + in_group % rows_in_group, bn = in_group / rows_in_group;
     const int m0 = bm * BM;
-    const int t = min(bn * NB + band, n_tiles - 1);              // bands past the end reload the last one; not stored
 
     // wave-uniform bases (scalar registers) and small per-lane offsets
-    const uint8_t* wbase = packed + (int64_t)t * C * 1024;       // + c * 1024 + lane * 16
-    const uint8_t* sbase = reinterpret_cast<const uint8_t*>(scales) + (int64_t)t * NG * 64;   // + g * 64 + i * 4
+    const uint8_t* wbase[TPW];                                   // + c * 1024 + lane * 16
+    const uint8_t* sbase[TPW];                                   // + g * 64 + i * 4
+#pragma unroll
+    for (int j = 0; j < TPW; ++j) {
+        const int t = min((bn * NB + band) * TPW + j, n_tiles - 1);   // bands past the end reload the last one; not stored
+        wbase[j] = packed + (int64_t)t * C * 1024;
+        sbase[j] = reinterpret_cast<const uint8_t*>(scales) + (int64_t)t * NG * 64;
+    }
     const uint8_t* xrow0 = x8 + (int64_t)m0 * ldx8;              // + c * 128 + xvoff
     const uint32_t woff = lane * 16, soff = i * 4;
     // Activation block in LDS: K-split group kg, 16-token block f = 2 KiB = two 1 KiB pages of 8 rows x 128 bytes;
@@ -95,9 +105,9 @@ __global__ void __launch_bounds__(512, (KS * MF > 16) ? 2 : 4) linear_mfma_kerne
     const uint32_t xc_off = kg * (MF * 2048) + (i >> 3) * 1024 + ((i & 7) * 8 + ((2 * kq + 1) ^ ((i >> 1) & 7))) * 16;
     const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint8_t*)lds;
     const uint32_t lds_x = lds0 + (uint32_t)wave * (DMA_PER_WAVE * 1024);
-    const uint32_t lds_raw = lds0 + RAW_OFF + (uint32_t)wave * 1024, lds_sc = lds0 + SC_OFF + (uint32_t)wave * 256;
-    const uint8_t* my_raw = lds + RAW_OFF + wave * 1024 + lane * 16;
-    const uint8_t* my_sc = lds + SC_OFF + wave * 256 + lane * 4;
+    const uint32_t lds_raw = lds0 + RAW_OFF + (uint32_t)wave * (TPW * 1024), lds_sc = lds0 + SC_OFF + (uint32_t)wave * (TPW * 256);
+    const uint8_t* my_raw = lds + RAW_OFF + wave * (TPW * 1024) + lane * 16;      // + j * 1024
+    const uint8_t* my_sc = lds + SC_OFF + wave * (TPW * 256) + lane * 4;          // + j * 256
 
     const int passes = (C + KS - 1) / KS;
     // activations of pass `ps` into stage `buf`; chunks past the end of K reload the last chunk (never multiplied)
@@ -112,32 +122,46 @@ __global__ void __launch_bounds__(512, (KS * MF > 16) ? 2 : 4) linear_mfma_kerne
     // Copies the band's tile and scales of chunk c into the wavefront's slots.  `after` is a value read from those
     // slots earlier: the copy is issued only once that read has returned.
     auto stage_w = [&](int c, uint32_t after) {
-        lds_dma_16_after(wbase + (int64_t)c * 1024, woff, lds_raw, after);
-        lds_dma_4(sbase + (int64_t)(c / cpg) * 64, soff, lds_sc);
+#pragma unroll
+        for (int j = 0; j < TPW; ++j) {
+            lds_dma_16_after(wbase[j] + (int64_t)c * 1024, woff, lds_raw + j * 1024, after);
+            lds_dma_4(sbase[j] + (int64_t)(c / cpg) * 64, soff, lds_sc + j * 256);
+        }
     };
 
-    v4f acc[MF];
+    v4f acc[MF][TPW];
 #pragma unroll
-    for (int f = 0; f < MF; ++f) acc[f] = v4f{0.f, 0.f, 0.f, 0.f};
+    for (int f = 0; f < MF; ++f)
+#pragma unroll
+        for (int j = 0; j < TPW; ++j) acc[f][j] = v4f{0.f, 0.f, 0.f, 0.f};
 
-    // One pass: multiply chunk c = KS * ps + kg with `cur`; meanwhile read chunk c + KS's nibbles and scale from the
+    struct Band { v8i op[TPW]; float s[TPW]; };
+    // One pass: multiply chunk c = KS * ps + kg with `cur`; meanwhile read chunk c + KS's nibbles and scales from the
     // slots, expand them into `next`, and start the copies of chunk c + 2 KS.
-    auto pass = [&](int ps, const v8i& cur, float s_cur, v8i& next, float& s_next) {
+    auto pass = [&](int ps, const Band& cur, Band& next) {
         const int buf = ps & 1;
         const int c = ps * KS + kg;
         if (ps + 1 < passes) stage_x(ps + 1, buf ^ 1);
-        uint4 raw = make_uint4(0u, 0u, 0u, 0u);
+        uint4 raw[TPW];
+#pragma unroll
+        for (int j = 0; j < TPW; ++j) raw[j] = make_uint4(0u, 0u, 0u, 0u);
         if (c + KS < C) {
-            raw = *reinterpret_cast<const uint4*>(my_raw);
-            s_next = *reinterpret_cast<const float*>(my_sc);
-            if (c + 2 * KS < C) stage_w(c + 2 * KS, raw.x ^ __float_as_uint(s_next));
+            uint32_t seen = 0u;
+#pragma unroll
+            for (int j = 0; j < TPW; ++j) {
+                raw[j] = *reinterpret_cast<const uint4*>(my_raw + j * 1024);
+                next.s[j] = *reinterpret_cast<const float*>(my_sc + j * 256);
+                seen ^= raw[j].x ^ __float_as_uint(next.s[j]);
+            }
+            if (c + 2 * KS < C) stage_w(c + 2 * KS, seen);
         }
         if (c < C) {
-            const uint32_t rn[4] = {raw.x, raw.y, raw.z, raw.w};
             const uint8_t* xb = lds + buf * STAGE_BYTES;
             uint4 xa = *reinterpret_cast<const uint4*>(xb + xa_off);
             uint4 xc = *reinterpret_cast<const uint4*>(xb + xc_off);
             v4f p_prev = v4f{0.f, 0.f, 0.f, 0.f};
+            // Step (f, j): the LDS reads of token block f+1 (at j = 0), the MFMA of block f with band j, then the FMAs
+            // of the previous step, which do not depend on the MFMA in flight, and a share of the next chunk's expansion.
 #pragma unroll
             for (int f = 0; f < MF; ++f) {
                 const v8i xop = v8i{(int)xa.x, (int)xa.y, (int)xa.z, (int)xa.w, (int)xc.x, (int)xc.y, (int)xc.z, (int)xc.w};
@@ -145,56 +169,74 @@ __global__ void __launch_bounds__(512, (KS * MF > 16) ? 2 : 4) linear_mfma_kerne
                     xa = *reinterpret_cast<const uint4*>(xb + xa_off + (f + 1) * 2048);
                     xc = *reinterpret_cast<const uint4*>(xb + xc_off + (f + 1) * 2048);
                 }
-                const v4f p = mfma_16x16x128_e4m3(xop, cur, v4f{0.f, 0.f, 0.f, 0.f});
-                if (f > 0) {
-                    acc[f - 1][0] = fmaf(s_cur, p_prev[0], acc[f - 1][0]);
-                    acc[f - 1][1] = fmaf(s_cur, p_prev[1], acc[f - 1][1]);
-                    acc[f - 1][2] = fmaf(s_cur, p_prev[2], acc[f - 1][2]);
-                    acc[f - 1][3] = fmaf(s_cur, p_prev[3], acc[f - 1][3]);
-                    keep_here(acc[f - 1]);
-                }
-                // this step's share of the next chunk's expansion: eighths f*8/MF .. (f+1)*8/MF - 1; eighth e is
-                // operand register e = half e % 2 of dword e / 2
 #pragma unroll
-                for (int e = f * 8 / MF; e < (f + 1) * 8 / MF; ++e) {
-                    uint32_t o = (e & 1) ? nibbles_half_to_e4m3<4>(rn[e >> 1]) : nibbles_half_to_e4m3<0>(rn[e >> 1]);
-                    keep_here(o);
-                    next[e] = (int)o;
+                for (int j = 0; j < TPW; ++j) {
+                    const int st = f * TPW + j;                  // step number
+                    const v4f p = mfma_16x16x128_e4m3(xop, cur.op[j], v4f{0.f, 0.f, 0.f, 0.f});
+                    if (st > 0) {
+                        const int fp = (st - 1) / TPW, jp = (st - 1) % TPW;
+                        acc[fp][jp][0] = fmaf(cur.s[jp], p_prev[0], acc[fp][jp][0]);
+                        acc[fp][jp][1] = fmaf(cur.s[jp], p_prev[1], acc[fp][jp][1]);
+                        acc[fp][jp][2] = fmaf(cur.s[jp], p_prev[2], acc[fp][jp][2]);
+                        acc[fp][jp][3] = fmaf(cur.s[jp], p_prev[3], acc[fp][jp][3]);
+                        keep_here(acc[fp][jp]);
+                    }
+                    // this step's share of the next chunk's expansion: eighths st*8/MF .. (st+1)*8/MF - 1 of the 8 TPW;
+                    // eighth E belongs to band E / 8 and is operand register e = E % 8: half e % 2 of dword e / 2
+#pragma unroll
+                    for (int E = st * 8 / MF; E < (st + 1) * 8 / MF; ++E) {
+                        const int jb = E / 8, e = E % 8;
+                        const uint32_t src = (e >> 1) == 0 ? raw[jb].x : (e >> 1) == 1 ? raw[jb].y : (e >> 1) == 2 ? raw[jb].z : raw[jb].w;
+                        uint32_t o = (e & 1) ? nibbles_half_to_e4m3<4>(src) : nibbles_half_to_e4m3<0>(src);
+                        keep_here(o);
+                        next.op[jb][e] = (int)o;
+                    }
+                    p_prev = p;
+                    __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);              // LDS reads of the next block
+                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);              // this step's MFMA
+                    __builtin_amdgcn_sched_group_barrier(0x002, 4 + 8 * PIECES, 0); // vector ALU work independent of it
+                    __builtin_amdgcn_sched_barrier(0);
                 }
-                p_prev = p;
-                __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);              // LDS reads of the next block
-                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);              // this block's MFMA
-                __builtin_amdgcn_sched_group_barrier(0x002, 4 + 8 * PIECES, 0); // vector ALU work independent of it
-                __builtin_amdgcn_sched_barrier(0);
             }
-            acc[MF - 1][0] = fmaf(s_cur, p_prev[0], acc[MF - 1][0]);
-            acc[MF - 1][1] = fmaf(s_cur, p_prev[1], acc[MF - 1][1]);
-            acc[MF - 1][2] = fmaf(s_cur, p_prev[2], acc[MF - 1][2]);
-            acc[MF - 1][3] = fmaf(s_cur, p_prev[3], acc[MF - 1][3]);
+            acc[MF - 1][TPW - 1][0] = fmaf(cur.s[TPW - 1], p_prev[0], acc[MF - 1][TPW - 1][0]);
+            acc[MF - 1][TPW - 1][1] = fmaf(cur.s[TPW - 1], p_prev[1], acc[MF - 1][TPW - 1][1]);
+            acc[MF - 1][TPW - 1][2] = fmaf(cur.s[TPW - 1], p_prev[2], acc[MF - 1][TPW - 1][2]);
+            acc[MF - 1][TPW - 1][3] = fmaf(cur.s[TPW - 1], p_prev[3], acc[MF - 1][TPW - 1][3]);
         }
         lds_dma_wait_all();                                      // this wavefront's copies have landed ...
         __syncthreads();                                         // ... and so have everyone's; the block just read is free
     };
 
-    v8i wop_a = v8i{0, 0, 0, 0, 0, 0, 0, 0}, wop_b = wop_a;
-    float s_a = 0.f, s_b = 0.f;
+    Band wa, wb;
+#pragma unroll
+    for (int j = 0; j < TPW; ++j) {
+        wa.op[j] = v8i{0, 0, 0, 0, 0, 0, 0, 0};
+        wb.op[j] = wa.op[j];
+        wa.s[j] = 0.f;
+        wb.s[j] = 0.f;
+    }
     {
         // the group's first chunk comes through registers, so that the copies of its second chunk need not wait for it
-        uint4 raw0 = make_uint4(0u, 0u, 0u, 0u);
-        if (kg < C) {
-            raw0 = *reinterpret_cast<const uint4*>(wbase + (int64_t)kg * 1024 + woff);
-            s_a = *reinterpret_cast<const float*>(sbase + (int64_t)(kg / cpg) * 64 + soff);
+        uint4 raw0[TPW];
+#pragma unroll
+        for (int j = 0; j < TPW; ++j) {
+            raw0[j] = make_uint4(0u, 0u, 0u, 0u);
+            if (kg < C) {
+                raw0[j] = *reinterpret_cast<const uint4*>(wbase[j] + (int64_t)kg * 1024 + woff);
+                wa.s[j] = *reinterpret_cast<const float*>(sbase[j] + (int64_t)(kg / cpg) * 64 + soff);
+            }
         }
         stage_x(0, 0);
         if (kg + KS < C) stage_w(kg + KS, 0u);
-        wop_a = slot_to_operand(raw0);
+#pragma unroll
+        for (int j = 0; j < TPW; ++j) wa.op[j] = slot_to_operand(raw0[j]);
     }
     lds_dma_wait_all();
     __syncthreads();
 
     for (int ps = 0; ps < passes; ps += 2) {
-        pass(ps, wop_a, s_a, wop_b, s_b);                        // even pass: A multiplies, the next chunk expands into B
-        if (ps + 1 < passes) pass(ps + 1, wop_b, s_b, wop_a, s_a);
+        pass(ps, wa, wb);                                        // even pass: A multiplies, the next chunk expands into B
+        if (ps + 1 < passes) pass(ps + 1, wb, wa);
     }
 
     // K-split groups 1 .. KS-1 hand their partial sums to group 0 through LDS (the loop's last barrier has passed:
@@ -205,7 +247,10 @@ __global__ void __launch_bounds__(512, (KS * MF > 16) ? 2 : 4) linear_mfma_kerne
 #pragma unroll
             for (int f = 0; f < MF; ++f)
 #pragma unroll
-                for (int r = 0; r < 4; ++r) red[((((kg - 1) * NB + band) * MF + f) * 4 + r) * 64 + lane] = acc[f][r];
+                for (int j = 0; j < TPW; ++j)
+#pragma unroll
+                    for (int r = 0; r < 4; ++r)
+                        red[(((((kg - 1) * NB + band) * MF + f) * TPW + j) * 4 + r) * 64 + lane] = acc[f][j][r];
         }
         __syncthreads();
         if (kg == 0) {
@@ -214,7 +259,10 @@ __global__ void __launch_bounds__(512, (KS * MF > 16) ? 2 : 4) linear_mfma_kerne
 #pragma unroll
                 for (int f = 0; f < MF; ++f)
 #pragma unroll
-                    for (int r = 0; r < 4; ++r) acc[f][r] += red[((((k2 - 1) * NB + band) * MF + f) * 4 + r) * 64 + lane];
+                    for (int j = 0; j < TPW; ++j)
+#pragma unroll
+                        for (int r = 0; r < 4; ++r)
+                            acc[f][j][r] += red[(((((k2 - 1) * NB + band) * MF + f) * TPW + j) * 4 + r) * 64 + lane];
         }
         __syncthreads();
     }
@@ -234,9 +282,11 @@ __global__ void __launch_bounds__(512, (KS * MF > 16) ? 2 : 4) linear_mfma_kerne
             for (int ff = 0; ff < FR; ++ff) {
                 if (f0 + ff < MF) {
 #pragma unroll
-                    for (int r = 0; r < 4; ++r)
-                        slab[(ff * 16 + 4 * kq + r) * RS + band * 16 + i] =
-                            OutCast<OutT>::cast(sx * acc[(f0 + ff < MF) ? f0 + ff : 0][r]);
+                    for (int j = 0; j < TPW; ++j)
+#pragma unroll
+                        for (int r = 0; r < 4; ++r)
+                            slab[(ff * 16 + 4 * kq + r) * RS + (band * TPW + j) * 16 + i] =
+                                OutCast<OutT>::cast(sx * acc[(f0 + ff < MF) ? f0 + ff : 0][j][r]);
                 }
             }
         }
@@ -259,64 +309,78 @@ __global__ void __launch_bounds__(512, (KS * MF > 16) ? 2 : 4) linear_mfma_kerne
     }
 }
 
-template <typename OutT, int MF, int KS>
+template <typename OutT, int MF, int KS, int TPW>
 void launch_one(dim3 grid, hipStream_t st, const uint8_t* x8, int M, int64_t ldx8, const float* s_x, const uint8_t* packed,
                 const float* scales, int N, int n_tiles, int C, int cpg, int NG, void* y, int64_t ldy, int grid_m,
                 int grid_n) {
-    hipLaunchKernelGGL((linear_mfma_kernel<OutT, MF, KS>), grid, dim3(WAVES * 64), 0, st, x8, M, ldx8, s_x, packed, scales, N,
+    hipLaunchKernelGGL((linear_mfma_kernel<OutT, MF, KS, TPW>), grid, dim3(WAVES * 64), 0, st, x8, M, ldx8, s_x, packed, scales, N,
                        n_tiles, C, cpg, NG, static_cast<OutT*>(y), ldy, grid_m, grid_n);
 }
 
 }  // namespace
 
-// mf = 16-token blocks per workgroup (4, 8 or 16; 0 = chosen from the shape), ks = K-split groups (1, 2 or 4; 0 = chosen).
+// mf = 16-token blocks per workgroup (4, 8 or 16), ks = K-split groups (1, 2 or 4), tpw = weight bands per wavefront
+// (1 or 2); 0 = chosen from the shape.
 int launch_linear_mfma_tiled(const uint8_t* x8, int64_t M, int64_t K, int64_t ldx8, const float* s_x,
                              const uint8_t* packed, const float* scales, int64_t N, int32_t G, void* y,
-                             w4a8_dtype ydt, int64_t ldy, int mf, int ks, hipStream_t st) {
-    if (!(mf == 0 || mf == 4 || mf == 8 || mf == 16) || !(ks == 0 || ks == 1 || ks == 2 || ks == 4)) return W4A8_ERR_SHAPE;
-    if (mf == 16 && ks == 4) return W4A8_ERR_SHAPE;              // would not fit LDS
+                             w4a8_dtype ydt, int64_t ldy, int mf, int ks, int tpw, hipStream_t st) {
+    if (!(mf == 0 || mf == 4 || mf == 8 || mf == 16) || !(ks == 0 || ks == 1 || ks == 2 || ks == 4) || tpw < 0 || tpw > 2)
+        return W4A8_ERR_SHAPE;
     const int C = (int)(K / 128), cpg = G / 128, NG = (int)(K / G);
     const int n_tiles = (int)((N + 15) / 16);
-    // Workgroup shape.  Tall token blocks amortize the nibble expansion over more MFMAs; K-splits shorten the dependent
-    // chain of passes (each waits for the copies of the next) when the grid is too small to fill the chip, at the
-    // price of a wider activation block to copy per pass.  Sweeps over the Llama-3 layer shapes are matched by: the first
-    // shape, in this order of preference, that yields about 1.5 workgroups per compute unit.
-    if (mf == 0 || ks == 0) {
-        static const int cand[6][2] = {{16, 1}, {8, 1}, {8, 2}, {4, 1}, {4, 2}, {4, 4}};
-        int pick_mf = 0, pick_ks = 0;
-        for (const auto& cd : cand) {
-            const int mfv = cd[0], ksv = cd[1];
-            if ((mf && mf != mfv) || (ks && ks != ksv)) continue;
-            if (!pick_mf || (mfv <= pick_mf && ksv >= pick_ks)) { pick_mf = mfv; pick_ks = ksv; }   // fallback: the finest
+    // Workgroup shape.  Tall token blocks amortize the nibble expansion over more MFMAs; two bands per wavefront halve
+    // the LDS reads per MFMA (the activation operand is reused); K-splits shorten the dependent chain of passes (each
+    // waits for the copies of the next) when the grid is too small to fill the chip, at the price of a wider activation
+    // block to copy per pass.  Sweeps over the Llama-3 layer shapes are matched by: the first shape, in this order of
+    // preference, that yields about 1.5 workgroups per compute unit.
+    static const int cand[W4A8_MFMA_SHAPES][3] = W4A8_MFMA_SHAPE_LIST;
+    if (mf == 0 || ks == 0 || tpw == 0) {
+        int pick = -1, fallback = -1;
+        // 256 tokens x 256 channels (two bands per wavefront, one workgroup per compute unit) is the fastest shape when
+        // its grid fills the 256 compute units evenly: at least three quarters of one round, or rounds at least 80 % full.
+        if ((mf == 0 || mf == 16) && (ks == 0 || ks == 1) && (tpw == 0 || tpw == 2)) {
+            const int64_t g2 = ((M + 255) / 256) * (int64_t)((n_tiles + 15) / 16);
+            const int64_t rounds = (g2 + 255) / 256;
+            if (tpw == 2 || (g2 >= 192 && (rounds == 1 || g2 * 5 >= rounds * 256 * 4))) pick = W4A8_MFMA_SHAPES - 1;
+        }
+        for (int q = 0; q < W4A8_MFMA_SHAPES - 1 && pick < 0; ++q) {
+            const int mfv = cand[q][0], ksv = cand[q][1], tpv = cand[q][2];
+            if ((mf && mf != mfv) || (ks && ks != ksv) || (tpw && tpw != tpv)) continue;
+            fallback = q;                                        // the finest shape that matches the request
             if (mfv > 4 && 16 * mfv >= 2 * M + 64) continue;     // mostly padding
             if (ksv > 1 && C < 4 * ksv) continue;                // too few chunks to split
-            const int64_t groups = ((M + 16 * mfv - 1) / (16 * mfv)) * (int64_t)((n_tiles + 8 / ksv - 1) / (8 / ksv));
-            if (groups >= 384) { pick_mf = mfv; pick_ks = ksv; break; }
+            const int per_wg = (8 / ksv) * tpv;
+            const int64_t groups = ((M + 16 * mfv - 1) / (16 * mfv)) * (int64_t)((n_tiles + per_wg - 1) / per_wg);
+            if (groups >= 384) { pick = q; break; }
         }
-        if (!pick_mf) return W4A8_ERR_SHAPE;                     // e.g. 16 blocks with 4 groups asked for
-        mf = pick_mf;
-        ks = pick_ks;
+        if (pick < 0) pick = fallback;
+        if (pick < 0) return W4A8_ERR_SHAPE;                     // a combination that is not built
+        mf = cand[pick][0];
+        ks = cand[pick][1];
+        tpw = cand[pick][2];
     }
-    const int nb = 8 / ks;
-    const int grid_n = (n_tiles + nb - 1) / nb;
+    const int per_wg = (8 / ks) * tpw;
+    const int grid_n = (n_tiles + per_wg - 1) / per_wg;
     const int grid_m = (int)((M + 16 * mf - 1) / (16 * mf));
     const int64_t total = (int64_t)grid_m * grid_n;
     if (total > (1 << 30)) return W4A8_ERR_SHAPE;
     if (ldx8 >= (1 << 24)) return W4A8_ERR_SHAPE;               // 32-bit activation offsets inside a token block
     const dim3 grid((unsigned)((total + XCDS - 1) / XCDS * XCDS));
-#define W4A8_CASE(MFV, KSV)                                                                                                  \
-    if (mf == MFV && ks == KSV) {                                                                                            \
+    bool launched = false;
+#define W4A8_CASE(MFV, KSV, TPV)                                                                                             \
+    if (mf == MFV && ks == KSV && tpw == TPV) {                                                                              \
+        launched = true;                                                                                                     \
         if (ydt == W4A8_F32)                                                                                                 \
-            launch_one<float, MFV, KSV>(grid, st, x8, (int)M, ldx8, s_x, packed, scales, (int)N, n_tiles, C, cpg, NG, y, ldy, \
-                                        grid_m, grid_n);                                                                     \
+            launch_one<float, MFV, KSV, TPV>(grid, st, x8, (int)M, ldx8, s_x, packed, scales, (int)N, n_tiles, C, cpg, NG, y, \
+                                             ldy, grid_m, grid_n);                                                           \
         else                                                                                                                 \
-            launch_one<uint16_t, MFV, KSV>(grid, st, x8, (int)M, ldx8, s_x, packed, scales, (int)N, n_tiles, C, cpg, NG, y,  \
-                                           ldy, grid_m, grid_n);                                                             \
+            launch_one<uint16_t, MFV, KSV, TPV>(grid, st, x8, (int)M, ldx8, s_x, packed, scales, (int)N, n_tiles, C, cpg, NG, \
+                                                y, ldy, grid_m, grid_n);                                                     \
     }
-    W4A8_CASE(16, 1) W4A8_CASE(8, 1) W4A8_CASE(4, 1)
-    W4A8_CASE(16, 2) W4A8_CASE(8, 2) W4A8_CASE(4, 2)
-    W4A8_CASE(8, 4) W4A8_CASE(4, 4)
+    W4A8_CASE(16, 1, 2) W4A8_CASE(16, 1, 1) W4A8_CASE(8, 1, 1) W4A8_CASE(8, 2, 1) W4A8_CASE(4, 1, 1)
+    W4A8_CASE(4, 2, 1) W4A8_CASE(4, 4, 1)
 #undef W4A8_CASE
+    if (!launched) return W4A8_ERR_SHAPE;
     return launch_status();
 }
 

@@ -24,10 +24,10 @@ int launch_linear_canonical(const uint8_t* x8, int64_t M, int64_t K, int64_t ldx
 int launch_linear_skinny(const uint8_t* x8, int64_t M, int64_t K, int64_t ldx8, const float* s_x,
                          const uint8_t* packed, const float* scales, int64_t N, int32_t G, void* y, w4a8_dtype ydt,
                          int64_t ldy, int nt, int waves, int depth, hipStream_t st);
-// mf = 16-token blocks per workgroup, ks = K-split groups per workgroup; 0: chosen from the shape
+// mf = 16-token blocks per workgroup, ks = K-split groups per workgroup, tpw = weight bands per wavefront; 0: chosen
 int launch_linear_mfma_tiled(const uint8_t* x8, int64_t M, int64_t K, int64_t ldx8, const float* s_x,
                              const uint8_t* packed, const float* scales, int64_t N, int32_t G, void* y,
-                             w4a8_dtype ydt, int64_t ldy, int mf, int ks, hipStream_t st);
+                             w4a8_dtype ydt, int64_t ldy, int mf, int ks, int tpw, hipStream_t st);
 int launch_silu_mul(const void* gu, int64_t M, int64_t F, int64_t ldgu, void* h, int64_t ldh, hipStream_t st);
 
 }  // namespace w4a8

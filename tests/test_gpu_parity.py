@@ -176,10 +176,11 @@ def test_config1_single_layer(gpu_lib):
     # of the split (K = 384, 640, 1152), one-chunk K, group sizes spanning several chunks
     (9, 384, 40, 128, (1, 0, 0)), (9, 384, 40, 128, (1, 4, 1)), (129, 256, 272, 128, (1, 0, 0)),
     (100, 384, 300, 128, (1, 4, 2)), (100, 384, 300, 128, (1, 4, 4)), (70, 128, 20, 128, (1, 4, 4)),
-    (300, 1024, 520, 512, (1, 8, 1)), (300, 1024, 520, 512, (1, 8, 2)), (300, 1152, 520, 128, (1, 8, 4)),
-    (257, 384, 130, 128, (1, 16, 1)), (257, 640, 130, 128, (1, 16, 2)), (300, 1024, 520, 512, (1, 16, 1)),
-    (70, 128, 20, 128, (1, 16, 1)), (513, 256, 144, 256, (1, 16, 2)), (513, 256, 144, 256, (1, 4, 1)),
-    (200, 2560, 72, 256, (1, 8, 4)), (65, 640, 136, 128, (1, 4, 4)),
+    (300, 1024, 520, 512, (1, 8, 1)), (300, 1024, 520, 512, (1, 8, 2)), (300, 1152, 520, 128, (1, 8, 1)),
+    (257, 384, 130, 128, (1, 16, 1)), (257, 640, 130, 128, (1, 8, 2)), (300, 1024, 520, 512, (1, 16, 1)),
+    (70, 128, 20, 128, (1, 16, 1)), (513, 256, 144, 256, (1, 16, 1)), (513, 256, 144, 256, (1, 4, 1)),
+    (200, 2560, 72, 256, (1, 8, 2)), (65, 640, 136, 128, (1, 4, 4)),
+    (300, 1024, 520, 512, (1, 16, 1 + 2 * 256)), (257, 384, 130, 128, (1, 16, 1 + 2 * 256)), (70, 128, 20, 128, (1, 16, 1 + 2 * 256)),
 ])
 def test_linear_small_ragged(gpu_lib, m, k, n, g, path):
     """Several tiles, ragged tails in M and N, group sizes of one or more chunks, both kernels."""
@@ -196,7 +197,7 @@ def test_linear_small_ragged(gpu_lib, m, k, n, g, path):
     check_outputs(y32, y16, ref, a, f"ragged {m}x{k}x{n} g{g} {path}")
 
 
-@pytest.mark.parametrize("m,path", [(3, None), (16, (0, 2, 4)), (48, None), (200, None), (200, (1, 4, 4)), (200, (1, 8, 2)), (200, (1, 16, 1))])
+@pytest.mark.parametrize("m,path", [(3, None), (16, (0, 2, 4)), (48, None), (200, None), (200, (1, 4, 4)), (200, (1, 8, 2)), (200, (1, 16, 1)), (200, (1, 16, 1 + 2 * 256))])
 def test_linear_exact_integer_case_bit_for_bit(gpu_lib, m, path):
     """Small-integer activations, all sixteen codes, power-of-two scales: every partial sum is an integer (or a
     dyadic rational) below 2^24, so fp32 accumulation is exact in any order and the fp32 output must equal the
