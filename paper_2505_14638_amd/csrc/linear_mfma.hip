@@ -88,21 +88,23 @@ __global__ void __launch_bounds__(512, (KS * MF > 16 || MF * TPW > 16) ? 2 : 4) 
     const uint8_t* xrow0 = x8 + (int64_t)m0 * ldx8;              // + c * 128 + xvoff
     const uint32_t woff = lane * 16, soff = i * 4;
     // Activation block in LDS: K-split group kg, 16-token block f = 2 KiB = two 1 KiB pages of 8 rows x 128 bytes;
-    // 16-byte segment sg (0..7) of row r (0..15) sits in page r / 8 at slot (r % 8) * 8 + (sg ^ ((r >> 1) & 7)).
-    // One copy instruction fills one page from eight whole 128-byte row segments of global memory (whole cache
-    // lines), and the swizzle makes the two ds_read_b128 of an operand (segments 2kq, 2kq+1 of row i, sixteen rows per
-    // quarter-wave) conflict-free.  Page d of a pass belongs to group d / (2 MF), block (d / 2) % MF, rows 8 (d % 2)..+7.
+    // 16-byte segment sg (0..7) of row r (0..15) sits in page r / 8 at slot (r % 8) * 8 + (sg ^ sw(r)) with
+    // sw(r) = (r % 8) ^ (r / 8).  One copy instruction fills one page from eight whole 128-byte row segments of global
+    // memory (whole cache lines).  The swizzle keeps the two ds_read_b128 of an operand (segments 2kq, 2kq+1 of row i)
+    // free of bank conflicts whether the LDS serves eight consecutive lanes per clock from 32 banks or sixteen from 64:
+    // any eight consecutive rows differ in slot % 8, any sixteen in slot % 16.  Page d of a pass belongs to group
+    // d / (2 MF), block (d / 2) % MF, rows 8 (d % 2)..+7.
     uint32_t xvoff[DMA_PER_WAVE];
 #pragma unroll
     for (int q = 0; q < DMA_PER_WAVE; ++q) {
         const int d = wave * DMA_PER_WAVE + q;
         const int r = (d & 1) * 8 + (lane >> 3);
-        const int sg = (lane & 7) ^ ((r >> 1) & 7);
+        const int sg = (lane & 7) ^ ((r & 7) ^ (r >> 3));
         const int row = ((d >> 1) % MF) * 16 + r;
         xvoff[q] = (uint32_t)(min(m0 + row, M - 1) - m0) * (uint32_t)ldx8 + sg * 16;   // rows past the end: last row
     }
-    const uint32_t xa_off = kg * (MF * 2048) + (i >> 3) * 1024 + ((i & 7) * 8 + ((2 * kq) ^ ((i >> 1) & 7))) * 16;
-    const uint32_t xc_off = kg * (MF * 2048) + (i >> 3) * 1024 + ((i & 7) * 8 + ((2 * kq + 1) ^ ((i >> 1) & 7))) * 16;
+    const uint32_t xa_off = kg * (MF * 2048) + (i >> 3) * 1024 + ((i & 7) * 8 + ((2 * kq) ^ ((i & 7) ^ (i >> 3)))) * 16;
+    const uint32_t xc_off = kg * (MF * 2048) + (i >> 3) * 1024 + ((i & 7) * 8 + ((2 * kq + 1) ^ ((i & 7) ^ (i >> 3)))) * 16;
     const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint8_t*)lds;
     const uint32_t lds_x = lds0 + (uint32_t)wave * (DMA_PER_WAVE * 1024);
     const uint32_t lds_raw = lds0 + RAW_OFF + (uint32_t)wave * (TPW * 1024), lds_sc = lds0 + SC_OFF + (uint32_t)wave * (TPW * 256);
