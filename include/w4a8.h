@@ -18,7 +18,7 @@
  *     channel), quantization groups are `group_size` consecutive weights along a row (Sec. 3.1,
  *     App. A.1); group g of row n covers k in [g*group_size, (g+1)*group_size).
  *   - the FP8 format is E4M3 with range +-448 (Sec. 2.2, Sec. 4.1): bias 7, no infinities,
- *     S.1111.111 is NaN.  The INT4 codes are signed, in [-8, 7], stored as two's-complement nibbles.
+ *     S.1111.111 is NaN.  The INT4 codes are signed, in [-8, 7]; group scales are non-negative.
  */
 #ifndef W4A8_H
 #define W4A8_H
@@ -50,8 +50,8 @@ typedef enum {
                               s = max|W| / 7 (s = 1 for an all-zero group),
                               code = clamp(round_half_even(W / s), -8, 7), both divisions in float32 */
     W4A8_SRC_I8_CODES = 1  /* src = int8 codes [N, K], each in [-8, 7] (only the low nibble is kept), plus
-                              float32 scales [N, K/group_size]: a pure re-layout, for codes produced by an
-                              offline calibrator (Alg. 1) */
+                              float32 scales [N, K/group_size] (their magnitude is used): a pure re-layout, for
+                              codes produced by an offline calibrator (Alg. 1) */
 } w4a8_src;
 
 typedef enum {
@@ -63,7 +63,10 @@ typedef enum {
        packed (Np*K/2 bytes): tile (t, c) = (n / 16, k / 128) is the 1024 bytes at ((t * (K/128)) + c) * 1024.
        A tile is 64 slots of 16 bytes, slot = 16 * ((k % 128) / 32) + (n % 16).  With p = k % 32, d = p / 8,
        e = p % 8, the code sits in byte 4*d + (e % 4) of its slot: low nibble if e < 4, else high nibble.
-       scales (Np*K/group_size floats): element (n, g) at ((n / 16) * (K/group_size) + g) * 16 + (n % 16). */
+       Nibbles are sign-magnitude: bit 3 = sign, bits 0..2 = |code| for codes in [-7, 7]; -8 is the pattern 1000.
+       scales (Np*K/group_size floats): element (n, g) at ((n / 16) * (K/group_size) + g) * 16 + (n % 16), stored
+       as |scale|, with the sign bit set exactly for the (n, g) whose codes contain -8 (a hint that lets the
+       kernels expand nibbles the short way elsewhere; the packed codes alone still determine every weight). */
     W4A8_LAYOUT_TILED = 1
 } w4a8_layout;
 

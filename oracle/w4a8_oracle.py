@@ -30,7 +30,8 @@ dequant_codes_to_e4m3        Eq. 10 / Eq. 14 with zero-point 0 and the scale
 linear_ref                   Eq. 10, Eq. 4 and Eq. 11: Y = X_hat . W_hat^T
 linear_ref_paper_literal     Eq. 6-11 read literally: the product code*scale is
                              itself rounded onto the E4M3 grid before the matmul
-pack_* / unpack_*            storage formats of the C-ABI boundary
+pack_* / unpack_*            storage formats of the C-ABI boundary (the tiled one keeps
+                             sign-magnitude nibbles and marks groups that hold -8)
 silu_mul_ref, block_ref,     the decoder-block linear stack workload (static scales
 calibrate_block_scales       by Eq. 13 on the oracle's own intermediates)
 
@@ -223,8 +224,22 @@ def _tiled_destination(n_rows: int, k: int):
     return byte, nib
 
 
+def tiled_nibble(q) -> np.ndarray:
+    """Nibble of a code in the tiled storage: sign-magnitude, bit 3 = sign, bits 0..2 = |code| for codes in
+    [-7, 7]; the one code without a 3-bit magnitude, -8, takes the otherwise unused pattern 1000 ("minus zero").
+    (The paper fixes no storage format beyond "4-bit", Sec. 3 and Eq. 14; this is the library's own.)"""
+    q = np.asarray(q, dtype=np.int16)
+    return np.where(q >= 0, q, np.where(q == -8, 8, 8 + (-q))).astype(np.uint8)
+
+
+def tiled_nibble_to_code(nib) -> np.ndarray:
+    nib = np.asarray(nib, dtype=np.int16)
+    mag = nib & 7
+    return np.where(nib < 8, nib, np.where(mag == 0, -8, -mag)).astype(np.int8)
+
+
 def pack_tiled(q) -> np.ndarray:
-    """Tiled storage; rows are padded with code 0 up to a multiple of 16.
+    """Tiled storage; rows are padded with code 0 up to a multiple of 16; nibbles as in `tiled_nibble`.
 
     Written as a reshape: split n = (t, i) and k = (c, kq, d, h, b) with k % 32 = 8*d + 4*h + b; the byte order
     of the buffer is (t, c, kq, i, d, b) and h picks the nibble (0 = low).  `_tiled_destination` states the same
@@ -235,7 +250,7 @@ def pack_tiled(q) -> np.ndarray:
     assert k % TILE_K == 0
     n_pad = -(-n // TILE_N) * TILE_N
     u = np.zeros((n_pad, k), dtype=np.uint8)
-    u[:n] = q.view(np.uint8) & 0xF
+    u[:n] = tiled_nibble(q)
     u = u.reshape(n_pad // TILE_N, TILE_N, k // TILE_K, 4, 4, 2, 4).transpose(0, 2, 3, 1, 4, 6, 5)
     return np.ascontiguousarray(u[..., 0] | (u[..., 1] << 4)).ravel()
 
@@ -243,13 +258,14 @@ def pack_tiled(q) -> np.ndarray:
 def unpack_tiled(buf, n: int, k: int) -> np.ndarray:
     n_pad = -(-n // TILE_N) * TILE_N
     b = np.asarray(buf, dtype=np.uint8).reshape(n_pad // TILE_N, k // TILE_K, 4, TILE_N, 4, 4)   # t c kq i d b
-    u = np.stack([b & 0xF, b >> 4], axis=-1).astype(np.int8)                                     # ... h
+    u = np.stack([b & 0xF, b >> 4], axis=-1)                                                     # ... h
     u = u.transpose(0, 3, 1, 2, 4, 6, 5).reshape(n_pad, k)                                       # t i c kq d h b
-    return np.where(u >= 8, u - 16, u).astype(np.int8)[:n]
+    return tiled_nibble_to_code(u)[:n]
 
 
 def pack_tiled_by_offsets(q) -> np.ndarray:
-    """Same buffer as pack_tiled, built nibble by nibble from the explicit offsets (small inputs only)."""
+    """Same buffer as pack_tiled, built nibble by nibble from the explicit offsets, with the nibble spelled out
+    case by case (small inputs only)."""
     q = np.asarray(q, dtype=np.int8)
     n, k = q.shape
     n_pad = -(-n // TILE_N) * TILE_N
@@ -259,25 +275,43 @@ def pack_tiled_by_offsets(q) -> np.ndarray:
     out = np.zeros(n_pad * k // 2, dtype=np.uint8)
     for nn in range(n_pad):
         for kk in range(k):
-            out[byte[nn, kk]] |= (int(qp[nn, kk]) & 0xF) << (4 * int(nib[nn, kk]))
+            code = int(qp[nn, kk])
+            if code >= 0:
+                pattern = code                    # 0xxx
+            elif code == -8:
+                pattern = 0b1000                  # the spare pattern
+            else:
+                pattern = 0b1000 | (-code)        # 1xxx, magnitude 1..7
+            out[byte[nn, kk]] |= pattern << (4 * int(nib[nn, kk]))
     return out
 
 
-def tile_scales(s) -> np.ndarray:
-    """Tiled scale storage: element (n, g) at float index ((n // 16) * (K/G) + g) * 16 + n % 16;
-    padding rows get scale 0."""
-    s = np.asarray(s, dtype=np.float32)
+def tile_scales(s, q=None, group_size: int | None = None) -> np.ndarray:
+    """Tiled scale storage: element (n, g) at float index ((n // 16) * (K/G) + g) * 16 + n % 16; padding rows
+    get scale 0.  Scales are non-negative; the sign bit of a stored scale is a hint for the kernels: it is set
+    exactly when the group's codes `q[n, g*G:(g+1)*G]` contain -8 (pass `q` to have it set; without `q` no group
+    is marked, which is right for round-to-nearest codes with s = max|W|/7, where -8 cannot occur)."""
+    s = np.abs(np.asarray(s, dtype=np.float32))
     n, ng = s.shape
+    if q is not None:
+        q = np.asarray(q, dtype=np.int8)
+        g = q.shape[1] // ng if group_size is None else group_size
+        has_m8 = (q.reshape(n, ng, g) == -8).any(axis=2)
+        s = np.where(has_m8, -s, s).astype(np.float32)           # -0.0 for a zero scale: the sign bit is what counts
     n_pad = -(-n // TILE_N) * TILE_N
     sp = np.zeros((n_pad, ng), dtype=np.float32)
     sp[:n] = s
     return np.ascontiguousarray(sp.reshape(n_pad // TILE_N, TILE_N, ng).transpose(0, 2, 1)).ravel()
 
 
-def untile_scales(buf, n: int, ng: int) -> np.ndarray:
+def untile_scales(buf, n: int, ng: int, with_marks: bool = False):
+    """Inverse of tile_scales: the scales (magnitudes) and, on request, the per-group -8 marks."""
     n_pad = -(-n // TILE_N) * TILE_N
     b = np.asarray(buf, dtype=np.float32).reshape(n_pad // TILE_N, ng, TILE_N)
-    return np.ascontiguousarray(b.transpose(0, 2, 1)).reshape(n_pad, ng)[:n]
+    raw = np.ascontiguousarray(b.transpose(0, 2, 1)).reshape(n_pad, ng)[:n]
+    if with_marks:
+        return np.abs(raw), np.signbit(raw)
+    return np.abs(raw)
 
 
 # --------------------------------------------------------------------------------------

@@ -147,6 +147,9 @@ __global__ void __launch_bounds__(512, (KS * MF > 16 || MF * TPW > 16) ? 2 : 4) 
         uint4 raw[TPW];
 #pragma unroll
         for (int j = 0; j < TPW; ++j) raw[j] = make_uint4(0u, 0u, 0u, 0u);
+        bool m8[TPW];                                            // the band's next chunk lies in a group that holds -8
+#pragma unroll
+        for (int j = 0; j < TPW; ++j) m8[j] = false;
         if (c + KS < C) {
             uint32_t seen = 0u;
 #pragma unroll
@@ -154,6 +157,7 @@ __global__ void __launch_bounds__(512, (KS * MF > 16 || MF * TPW > 16) ? 2 : 4) 
                 raw[j] = *reinterpret_cast<const uint4*>(my_raw + j * 1024);
                 next.s[j] = *reinterpret_cast<const float*>(my_sc + j * 256);
                 seen ^= raw[j].x ^ __float_as_uint(next.s[j]);
+                m8[j] = any_marked(next.s[j]);
             }
             if (c + 2 * KS < C) stage_w(c + 2 * KS, seen);
         }
@@ -177,10 +181,11 @@ __global__ void __launch_bounds__(512, (KS * MF > 16 || MF * TPW > 16) ? 2 : 4) 
                     const v4f p = mfma_16x16x128_e4m3(xop, cur.op[j], v4f{0.f, 0.f, 0.f, 0.f});
                     if (st > 0) {
                         const int fp = (st - 1) / TPW, jp = (st - 1) % TPW;
-                        acc[fp][jp][0] = fmaf(cur.s[jp], p_prev[0], acc[fp][jp][0]);
-                        acc[fp][jp][1] = fmaf(cur.s[jp], p_prev[1], acc[fp][jp][1]);
-                        acc[fp][jp][2] = fmaf(cur.s[jp], p_prev[2], acc[fp][jp][2]);
-                        acc[fp][jp][3] = fmaf(cur.s[jp], p_prev[3], acc[fp][jp][3]);
+                        const float sc = fabsf(cur.s[jp]);       // the sign bit is the packer's mark, not part of the scale
+                        acc[fp][jp][0] = fmaf(sc, p_prev[0], acc[fp][jp][0]);
+                        acc[fp][jp][1] = fmaf(sc, p_prev[1], acc[fp][jp][1]);
+                        acc[fp][jp][2] = fmaf(sc, p_prev[2], acc[fp][jp][2]);
+                        acc[fp][jp][3] = fmaf(sc, p_prev[3], acc[fp][jp][3]);
                         keep_here(acc[fp][jp]);
                     }
                     // this step's share of the next chunk's expansion: eighths st*8/MF .. (st+1)*8/MF - 1 of the 8 TPW;
@@ -189,21 +194,23 @@ __global__ void __launch_bounds__(512, (KS * MF > 16 || MF * TPW > 16) ? 2 : 4) 
                     for (int E = st * 8 / MF; E < (st + 1) * 8 / MF; ++E) {
                         const int jb = E / 8, e = E % 8;
                         const uint32_t src = (e >> 1) == 0 ? raw[jb].x : (e >> 1) == 1 ? raw[jb].y : (e >> 1) == 2 ? raw[jb].z : raw[jb].w;
-                        uint32_t o = (e & 1) ? nibbles_half_to_e4m3<4>(src) : nibbles_half_to_e4m3<0>(src);
+                        uint32_t o = (e & 1) ? sm_half_to_e4m3_fast<4>(src) : sm_half_to_e4m3_fast<0>(src);
+                        if (m8[jb]) o = sm_fix_minus_eight(o);   // wave-uniform, rare
                         keep_here(o);
                         next.op[jb][e] = (int)o;
                     }
                     p_prev = p;
                     __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);              // LDS reads of the next block
                     __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);              // this step's MFMA
-                    __builtin_amdgcn_sched_group_barrier(0x002, 4 + 8 * PIECES, 0); // vector ALU work independent of it
+                    __builtin_amdgcn_sched_group_barrier(0x002, 4 + 4 * PIECES, 0); // vector ALU work independent of it
                     __builtin_amdgcn_sched_barrier(0);
                 }
             }
-            acc[MF - 1][TPW - 1][0] = fmaf(cur.s[TPW - 1], p_prev[0], acc[MF - 1][TPW - 1][0]);
-            acc[MF - 1][TPW - 1][1] = fmaf(cur.s[TPW - 1], p_prev[1], acc[MF - 1][TPW - 1][1]);
-            acc[MF - 1][TPW - 1][2] = fmaf(cur.s[TPW - 1], p_prev[2], acc[MF - 1][TPW - 1][2]);
-            acc[MF - 1][TPW - 1][3] = fmaf(cur.s[TPW - 1], p_prev[3], acc[MF - 1][TPW - 1][3]);
+            const float sc = fabsf(cur.s[TPW - 1]);
+            acc[MF - 1][TPW - 1][0] = fmaf(sc, p_prev[0], acc[MF - 1][TPW - 1][0]);
+            acc[MF - 1][TPW - 1][1] = fmaf(sc, p_prev[1], acc[MF - 1][TPW - 1][1]);
+            acc[MF - 1][TPW - 1][2] = fmaf(sc, p_prev[2], acc[MF - 1][TPW - 1][2]);
+            acc[MF - 1][TPW - 1][3] = fmaf(sc, p_prev[3], acc[MF - 1][TPW - 1][3]);
         }
         lds_dma_wait_all();                                      // this wavefront's copies have landed ...
         __syncthreads();                                         // ... and so have everyone's; the block just read is free
@@ -231,7 +238,7 @@ __global__ void __launch_bounds__(512, (KS * MF > 16 || MF * TPW > 16) ? 2 : 4) 
         stage_x(0, 0);
         if (kg + KS < C) stage_w(kg + KS, 0u);
 #pragma unroll
-        for (int j = 0; j < TPW; ++j) wa.op[j] = slot_to_operand(raw0[j]);
+        for (int j = 0; j < TPW; ++j) wa.op[j] = slot_to_operand<true>(raw0[j]);
     }
     lds_dma_wait_all();
     __syncthreads();
@@ -338,13 +345,9 @@ int launch_linear_mfma_tiled(const uint8_t* x8, int64_t M, int64_t K, int64_t ld
     static const int cand[W4A8_MFMA_SHAPES][3] = W4A8_MFMA_SHAPE_LIST;
     if (mf == 0 || ks == 0 || tpw == 0) {
         int pick = -1, fallback = -1;
-        // 256 tokens x 256 channels (two bands per wavefront, one workgroup per compute unit) is the fastest shape when
-        // its grid fills the 256 compute units evenly: at least three quarters of one round, or rounds at least 80 % full.
-        if ((mf == 0 || mf == 16) && (ks == 0 || ks == 1) && (tpw == 0 || tpw == 2)) {
-            const int64_t g2 = ((M + 255) / 256) * (int64_t)((n_tiles + 15) / 16);
-            const int64_t rounds = (g2 + 255) / 256;
-            if (tpw == 2 || (g2 >= 192 && (rounds == 1 || g2 * 5 >= rounds * 256 * 4))) pick = W4A8_MFMA_SHAPES - 1;
-        }
+        // 256 tokens x 256 channels (two bands per wavefront, half the LDS reads per MFMA, one workgroup per compute unit)
+        // measured no faster than 256 x 128 at twice the occupancy on any swept shape: on request only.
+        if (tpw == 2 && (mf == 0 || mf == 16) && (ks == 0 || ks == 1)) pick = W4A8_MFMA_SHAPES - 1;
         for (int q = 0; q < W4A8_MFMA_SHAPES - 1 && pick < 0; ++q) {
             const int mfv = cand[q][0], ksv = cand[q][1], tpv = cand[q][2];
             if ((mf && mf != mfv) || (ks && ks != ksv) || (tpw && tpw != tpv)) continue;

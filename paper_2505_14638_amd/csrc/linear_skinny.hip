@@ -4,7 +4,8 @@
 // Work split: a workgroup owns NT tiles of 16 output channels; its wavefronts split K between them (each takes a
 // contiguous run of 128-deep chunks, which is contiguous memory in the tiled format) and their partial results
 // are summed through LDS.  Per chunk a wavefront issues one 16-byte load per lane and tile (the 1 KiB tile is read
-// fully coalesced), expands the nibbles to E4M3 in registers (Eq. 10) and feeds them as the A operand of one
+// fully coalesced), expands the sign-magnitude nibbles to E4M3 in registers (Eq. 10; four ALU ops per four weights,
+// plus a fix-up for -8 on chunks whose scales the packer has marked) and feeds them as the A operand of one
 // 16x16x128 FP8 MFMA per (tile, 16-token block); the activations are the B operand, loaded straight from global
 // memory (they are small and stay in cache).  The chunk's partial product is scaled by the group scale in fp32.
 // Several chunks' loads are in flight ahead of the current chunk's arithmetic.
@@ -91,15 +92,22 @@ __global__ void __launch_bounds__(max_threads(MT * NT)) linear_skinny_kernel(
         }
 #pragma unroll
         for (int j = 0; j < NT; ++j) {
-            const v8i wop = slot_to_operand(L.w[j]);
             const float4 s = L.s[j];
+            // a marked scale (sign bit) on any of the band's 16 channels: this chunk's tile may hold -8
+            const bool m8 = any_marked(__uint_as_float(__float_as_uint(s.x) | __float_as_uint(s.y) | __float_as_uint(s.z) |
+                                                       __float_as_uint(s.w)));
+            v8i wop = slot_to_operand<false>(L.w[j]);
+            if (m8) {                                            // wave-uniform, rare
+#pragma unroll
+                for (int e = 0; e < 8; ++e) wop[e] = (int)sm_fix_minus_eight((uint32_t)wop[e]);
+            }
 #pragma unroll
             for (int mt = 0; mt < MT; ++mt) {
                 const v4f p = mfma_16x16x128_e4m3(wop, xop[mt], v4f{0.f, 0.f, 0.f, 0.f});
-                acc[mt][j][0] = fmaf(s.x, p[0], acc[mt][j][0]);
-                acc[mt][j][1] = fmaf(s.y, p[1], acc[mt][j][1]);
-                acc[mt][j][2] = fmaf(s.z, p[2], acc[mt][j][2]);
-                acc[mt][j][3] = fmaf(s.w, p[3], acc[mt][j][3]);
+                acc[mt][j][0] = fmaf(fabsf(s.x), p[0], acc[mt][j][0]);
+                acc[mt][j][1] = fmaf(fabsf(s.y), p[1], acc[mt][j][1]);
+                acc[mt][j][2] = fmaf(fabsf(s.z), p[2], acc[mt][j][2]);
+                acc[mt][j][3] = fmaf(fabsf(s.w), p[3], acc[mt][j][3]);
             }
         }
     };
@@ -194,14 +202,14 @@ int launch_linear_skinny(const uint8_t* x8, int64_t M, int64_t K, int64_t ldx8, 
     // Launch shape, from sweeps over the Llama-3-8B/70B layer shapes:
     //  - two bands per wavefront when the activation operand is wide enough to be worth sharing (M > 8 on layers
     //    with enough bands) or when the layer is large enough that fewer, longer-running workgroups ramp better;
-    //  - split K over as many wavefronts as it takes to have ~8192 (~4096 for M > 8) of them in flight.
+    //  - split K over as many wavefronts (a power of two) as it takes to have ~8192 (~4096 for M > 8) of them in flight.
     if (nt == 0) nt = ((M > 8 && n_tiles >= 384) || (int64_t)n_tiles * C >= 100000) ? 2 : 1;
     if (nt != 1 && nt != 2 && nt != 4) return W4A8_ERR_SHAPE;
     if (waves == 0) {
         const int grid = (n_tiles + nt - 1) / nt;
-        waves = ((M > 8 ? 4096 : 8192) + grid - 1) / grid;
-        if (waves < 2) waves = 2;
-        if (waves > 16) waves = 16;
+        const int want = ((M > 8 ? 4096 : 8192) + grid - 1) / grid;
+        waves = 2;                                               // the power of two nearest to `want` (ratio-wise), 2..16:
+        while (waves < 16 && waves * waves * 2 < want * want) waves *= 2;   // odd counts split K unevenly and measured slower
     }
     if (waves > C) waves = C;
     while (waves > 1 && (waves * mt * nt > 64 || waves * 64 > max_threads(mt * nt))) --waves;   // LDS and registers

@@ -56,17 +56,38 @@ __global__ void __launch_bounds__(256) rtn_scales_kernel(const float* __restrict
     }
 }
 
-__global__ void __launch_bounds__(256) copy_scales_kernel(const float* __restrict__ src, Geometry g, float* __restrict__ scales) {
-    const int64_t u = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (u >= g.Np * g.NG) return;
-    const int64_t n = u / g.NG, grp = u - n * g.NG;
-    scales[scale_index(g, n, grp)] = (n < g.N) ? src[n * g.NG + grp] : 0.0f;
+// One wavefront per (row, group): copies the magnitude of the given scale; in the tiled layout the sign bit marks the
+// groups whose codes contain -8 (the one code the fast nibble expansion gets wrong, see w4a8_device.hpp).
+__global__ void __launch_bounds__(256) copy_scales_kernel(const float* __restrict__ src, const int8_t* __restrict__ q,
+                                                          Geometry g, float* __restrict__ scales) {
+    const int64_t wid = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
+    const int lane = threadIdx.x & 63;
+    if (wid >= g.Np * g.NG) return;
+    const int64_t n = wid / g.NG, grp = wid - n * g.NG;
+    bool m8 = false;
+    if (g.tiled && n < g.N) {
+        const int8_t* p = q + n * g.K + grp * g.G;
+        for (int j = lane; j < g.G; j += 64) m8 |= ((p[j] & 0xF) == 0x8);
+    }
+    const bool any = __builtin_amdgcn_ballot_w64(m8) != 0;
+    if (lane == 0) {
+        float s = (n < g.N) ? fabsf(src[n * g.NG + grp]) : 0.0f;
+        if (any) s = __uint_as_float(__float_as_uint(s) | 0x80000000u);
+        scales[scale_index(g, n, grp)] = s;
+    }
 }
 
-__device__ __forceinline__ uint32_t rtn_code(float w, float s) {
+__device__ __forceinline__ int rtn_code(float w, float s) {
     float r = rintf(w / s);                      // float32 division, round half to even
     r = fminf(fmaxf(r, -8.0f), 7.0f);
-    return ((uint32_t)(int)r) & 0xFu;
+    return (int)r;
+}
+
+// nibble of a code in [-8, 7]: two's complement (canonical) or sign-magnitude with -8 as 1000 (tiled)
+__device__ __forceinline__ uint32_t nibble_of(int code, int tiled) {
+    if (!tiled) return ((uint32_t)code) & 0xFu;
+    if (code >= 0) return (uint32_t)code;
+    return code == -8 ? 8u : (8u | (uint32_t)(-code));
 }
 
 // one thread per destination byte
@@ -81,12 +102,13 @@ __global__ void __launch_bounds__(256) pack_kernel(const void* __restrict__ src,
     if (n < g.N) {
         if (FROM_F32) {
             const float* w = static_cast<const float*>(src) + n * g.K;
-            lo = rtn_code(w[k_lo], scales[scale_index(g, n, k_lo / g.G)]);
-            hi = rtn_code(w[k_hi], scales[scale_index(g, n, k_hi / g.G)]);
+            // round-to-nearest with s = max|W| / 7 never yields -8, so no scale needs a mark
+            lo = nibble_of(rtn_code(w[k_lo], scales[scale_index(g, n, k_lo / g.G)]), g.tiled);
+            hi = nibble_of(rtn_code(w[k_hi], scales[scale_index(g, n, k_hi / g.G)]), g.tiled);
         } else {
             const int8_t* q = static_cast<const int8_t*>(src) + n * g.K;
-            lo = ((uint32_t)q[k_lo]) & 0xFu;
-            hi = ((uint32_t)q[k_hi]) & 0xFu;
+            lo = nibble_of((int)(int8_t)(((int)q[k_lo] << 28) >> 28), g.tiled);   // only the low nibble of the input counts
+            hi = nibble_of((int)(int8_t)(((int)q[k_hi] << 28) >> 28), g.tiled);
         }
     }
     packed[b] = (uint8_t)(lo | (hi << 4));
@@ -102,7 +124,7 @@ __global__ void __launch_bounds__(256) dequant_tiled_kernel(const uint4* __restr
     const int slot = (int)(u & 63), kq = slot >> 4, i = slot & 15;
     const int64_t n = t * 16 + i;
     if (n >= N) return;
-    const v8i op = slot_to_operand(packed[u]);
+    const v8i op = slot_to_operand<true>(packed[u]);
     uint4* dst = reinterpret_cast<uint4*>(w8 + n * K + c * 128 + kq * 32);
     dst[0] = make_uint4((uint32_t)op[0], (uint32_t)op[1], (uint32_t)op[2], (uint32_t)op[3]);
     dst[1] = make_uint4((uint32_t)op[4], (uint32_t)op[5], (uint32_t)op[6], (uint32_t)op[7]);
@@ -136,7 +158,8 @@ int launch_pack_weights(const void* src, w4a8_src kind, const float* src_scales,
         if (int e = launch_status()) return e;
         hipLaunchKernelGGL(pack_kernel<true>, dim3(blocks_for(n_bytes)), dim3(256), 0, st, src, g, scales, packed);
     } else {
-        hipLaunchKernelGGL(copy_scales_kernel, dim3(blocks_for(n_scales)), dim3(256), 0, st, src_scales, g, scales);
+        hipLaunchKernelGGL(copy_scales_kernel, dim3(blocks_for(n_scales * 64)), dim3(256), 0, st, src_scales,
+                           static_cast<const int8_t*>(src), g, scales);
         if (int e = launch_status()) return e;
         hipLaunchKernelGGL(pack_kernel<false>, dim3(blocks_for(n_bytes)), dim3(256), 0, st, src, g, scales, packed);
     }

@@ -10,46 +10,75 @@ typedef float v4f __attribute__((ext_vector_type(4)));
 
 // ---------------------------------------------------------------------------------------------
 // INT4 -> E4M3 (Eq. 10 with zero-point 0; the group scale is applied to the group's partial sum).
-// One dword holds eight two's-complement nibbles.  `lo` receives the E4M3 bytes of nibbles 0,2,4,6
-// (the low nibble of bytes 0..3), `hi` those of nibbles 1,3,5,7 (the high nibbles).
-// A nibble is split into its low three bits l and its top bit b3: the value is l when b3 = 0 and
-// l - 8 when b3 = 1.  Each case is an 8-entry byte table looked up with one v_perm_b32; a third
-// v_perm_b32 picks, byte by byte, the table that b3 names.
 //   value   0    1    2    3    4    5    6    7     |  -8   -7   -6   -5   -4   -3   -2   -1
 //   E4M3   00   38   40   44   48   4A   4C   4E     |  D0   CE   CC   CA   C8   C4   C0   B8
+//
+// Tiled layout: sign-magnitude nibbles, bit 3 = sign, bits 0..2 = |value| for values in [-7, 7]; -8 is stored as 1000.
+// The E4M3 byte is then sign << 7 | table[magnitude]: one 8-entry table (one v_perm_b32 per four weights) and one
+// and-or, four ALU ops per four weights.  1000 comes out of that as 0x80 (minus zero) and needs a fix-up to 0xD0;
+// the packer marks every (row, group) that holds a -8 in the sign bit of the group's scale, so that the kernels
+// run the fix-up only on chunks where a wavefront sees a marked scale.
+//
+// Canonical layout: two's-complement nibbles; the value is l when b3 = 0 and l - 8 when b3 = 1 (l = low three bits),
+// each case an 8-entry table and a third v_perm_b32 to pick, byte by byte, the table that b3 names.
 // ---------------------------------------------------------------------------------------------
-// E4M3 bytes of the four nibbles at bit offset `shift` (0: low nibbles, 4: high nibbles) of the bytes of w.
+// E4M3 bytes of the four sign-magnitude nibbles at bit offset SHIFT (0: low nibbles, 4: high nibbles) of the bytes
+// of w, exact for every pattern except 1000, which gives 0x80.
 template <int SHIFT>
-__device__ __forceinline__ uint32_t nibbles_half_to_e4m3(uint32_t w) {
-    const uint32_t POS_LO = 0x44403800u, POS_HI = 0x4E4C4A48u;   // values 0..3, 4..7
-    const uint32_t NEG_LO = 0xCACCCED0u, NEG_HI = 0xB8C0C4C8u;   // values -8..-5, -4..-1
+__device__ __forceinline__ uint32_t sm_half_to_e4m3_fast(uint32_t w) {
+    const uint32_t MAG_LO = 0x44403800u, MAG_HI = 0x4E4C4A48u;   // magnitudes 0..3, 4..7
     const uint32_t sel = (w >> SHIFT) & 0x07070707u;
     // v_perm_b32(S0, S1, sel): selector 0..3 -> bytes of S1, 4..7 -> bytes of S0
-    const uint32_t pos = __builtin_amdgcn_perm(POS_HI, POS_LO, sel);
-    const uint32_t neg = __builtin_amdgcn_perm(NEG_HI, NEG_LO, sel);
-    // byte i of the result = byte i of pos (selector i) or of neg (selector i + 4)
-    const uint32_t mix = ((w >> (SHIFT + 1)) & 0x04040404u) | 0x03020100u;
-    return __builtin_amdgcn_perm(neg, pos, mix);
+    const uint32_t mag = __builtin_amdgcn_perm(MAG_HI, MAG_LO, sel);
+    const uint32_t sign = SHIFT ? w : (w << 4);
+    return (sign & 0x80808080u) | mag;
 }
 
-__device__ __forceinline__ void nibbles_to_e4m3(uint32_t w, uint32_t& lo, uint32_t& hi) {
-    lo = nibbles_half_to_e4m3<0>(w);
-    hi = nibbles_half_to_e4m3<4>(w);
+// Turns every byte 0x80 of four E4M3 bytes produced by sm_half_to_e4m3_fast into 0xD0 (-8).
+__device__ __forceinline__ uint32_t sm_fix_minus_eight(uint32_t e) {
+    const uint32_t t = e ^ 0x80808080u;                          // zero exactly in the bytes to fix
+    // zero-byte detector; exact here because a byte 0x01 cannot occur in t (0x81 is no output of the table)
+    const uint32_t z = (t - 0x01010101u) & ~t & 0x80808080u;
+    return e | (z >> 1) | (z >> 3);                              // 0x40 | 0x10 on top of the 0x80
 }
+
+template <int SHIFT>
+__device__ __forceinline__ uint32_t sm_half_to_e4m3(uint32_t w) { return sm_fix_minus_eight(sm_half_to_e4m3_fast<SHIFT>(w)); }
 
 // The 16 bytes (four dwords) of one tiled-layout slot -> the 32 operand bytes of one lane, in the order the
-// layout defines: operand byte p (0..31) belongs to k = 32*kq + p.
+// layout defines: operand byte p (0..31) belongs to k = 32*kq + p.  ANY_M8 = false skips the -8 fix-up.
+template <bool ANY_M8>
 __device__ __forceinline__ v8i slot_to_operand(uint4 s) {
-    uint32_t r0, r1, r2, r3, r4, r5, r6, r7;
-    nibbles_to_e4m3(s.x, r0, r1);
-    nibbles_to_e4m3(s.y, r2, r3);
-    nibbles_to_e4m3(s.z, r4, r5);
-    nibbles_to_e4m3(s.w, r6, r7);
+    const uint32_t w[4] = {s.x, s.y, s.z, s.w};
     v8i v;
-    v[0] = (int)r0; v[1] = (int)r1; v[2] = (int)r2; v[3] = (int)r3;
-    v[4] = (int)r4; v[5] = (int)r5; v[6] = (int)r6; v[7] = (int)r7;
+#pragma unroll
+    for (int d = 0; d < 4; ++d) {
+        v[2 * d] = (int)(ANY_M8 ? sm_half_to_e4m3<0>(w[d]) : sm_half_to_e4m3_fast<0>(w[d]));
+        v[2 * d + 1] = (int)(ANY_M8 ? sm_half_to_e4m3<4>(w[d]) : sm_half_to_e4m3_fast<4>(w[d]));
+    }
     return v;
 }
+
+// Canonical layout: one dword holds eight two's-complement nibbles.  `lo` receives the E4M3 bytes of nibbles
+// 0,2,4,6 (the low nibble of bytes 0..3), `hi` those of nibbles 1,3,5,7 (the high nibbles).
+__device__ __forceinline__ void nibbles_to_e4m3(uint32_t w, uint32_t& lo, uint32_t& hi) {
+    const uint32_t POS_LO = 0x44403800u, POS_HI = 0x4E4C4A48u;   // values 0..3, 4..7
+    const uint32_t NEG_LO = 0xCACCCED0u, NEG_HI = 0xB8C0C4C8u;   // values -8..-5, -4..-1
+    const uint32_t sel_l = w & 0x07070707u;
+    const uint32_t sel_h = (w >> 4) & 0x07070707u;
+    const uint32_t pos_l = __builtin_amdgcn_perm(POS_HI, POS_LO, sel_l);
+    const uint32_t neg_l = __builtin_amdgcn_perm(NEG_HI, NEG_LO, sel_l);
+    const uint32_t pos_h = __builtin_amdgcn_perm(POS_HI, POS_LO, sel_h);
+    const uint32_t neg_h = __builtin_amdgcn_perm(NEG_HI, NEG_LO, sel_h);
+    // byte i of the result = byte i of pos (selector i) or of neg (selector i + 4)
+    const uint32_t mix_l = ((w >> 1) & 0x04040404u) | 0x03020100u;
+    const uint32_t mix_h = ((w >> 5) & 0x04040404u) | 0x03020100u;
+    lo = __builtin_amdgcn_perm(neg_l, pos_l, mix_l);
+    hi = __builtin_amdgcn_perm(neg_h, pos_h, mix_h);
+}
+
+// True when some lane of the wavefront holds a scale whose sign bit is set (the packer's "-8 in this group" mark).
+__device__ __forceinline__ bool any_marked(float s) { return __builtin_amdgcn_ballot_w64(__float_as_int(s) < 0) != 0; }
 
 // D = A(16 x 128, E4M3) * B(128 x 16, E4M3) + C on the FP8 matrix unit, fp32 accumulation.
 // Lane l carries row (A) / column (B) l % 16 and the 32 contraction positions 32*(l/16) .. +31; the result

@@ -127,7 +127,9 @@ def test_pack_codes_all_sixteen_values_and_small_groups(gpu_lib):
     s = rng.uniform(0.001, 0.1, size=(n, k // 128)).astype(np.float32)
     p_t, s_t = B.pack_weights(dev(q), 128, B.LAYOUT_TILED, dev(s))
     assert np.array_equal(host(p_t), o.pack_tiled(q))
-    assert np.array_equal(host(s_t), o.tile_scales(s))
+    want_s = o.tile_scales(s, q)                                  # sign bit marks the groups that hold -8
+    assert np.signbit(want_s).any() and not np.signbit(want_s).all()
+    assert np.array_equal(host(s_t).view(np.uint32), want_s.view(np.uint32))
     assert np.array_equal(host(B.dequant_weights(p_t, n, k, B.LAYOUT_TILED)), o.dequant_codes_to_e4m3(q))
     s32 = rng.uniform(0.001, 0.1, size=(n, k // 32)).astype(np.float32)
     p_c, s_c = B.pack_weights(dev(q), 32, B.LAYOUT_CANONICAL, dev(s32))
@@ -214,6 +216,37 @@ def test_linear_exact_integer_case_bit_for_bit(gpu_lib, m, path):
     ref, _ = o.linear_ref(x8, np.float32(0.5), q, s_w, g)
     assert np.array_equal(ref.astype(np.float32), want)
     packed, scales = B.pack_weights(dev(q), g, B.LAYOUT_TILED, dev(s_w))
+    y32, _ = run_linear(dev(x8), dev(np.array([0.5], np.float32)), packed, scales, n, g, B.LAYOUT_TILED, path)
+    assert np.array_equal(y32, want)
+
+
+@pytest.mark.parametrize("m,g,path", [(1, 128, None), (16, 128, (0, 2, 4)), (40, 256, (0, 1, 8)), (64, 128, None), (200, 128, None),
+                                      (200, 256, (1, 4, 4)), (200, 128, (1, 8, 2)), (300, 256, (1, 16, 1)), (300, 128, (1, 16, 1 + 2 * 256)),
+                                      (100, 128, (1, 4, 2)), (130, 512, (1, 8, 1))])
+def test_linear_minus_eight_in_some_groups_bit_for_bit(gpu_lib, m, g, path):
+    """The tiled format stores -8 as the spare nibble 1000 and marks its (row, group) in the scale's sign bit; the
+    kernels expand nibbles the short way except on marked chunks.  Codes in [-7, 7] with -8 sprinkled into a quarter
+    of the (row, group) pairs (and into none of the first band), exact-integer inputs: marked and unmarked chunks
+    meet in every wavefront, and the fp32 output must equal the integer matmul bit for bit."""
+    rng = np.random.default_rng([17, m, g])
+    k, n = 2048, 176
+    ng = k // g
+    xi = rng.integers(-4, 5, size=(m, k))
+    x8 = o.e4m3_encode(xi.astype(np.float32))
+    q = rng.integers(-7, 8, size=(n, k)).astype(np.int8)
+    marked = rng.random((n, ng)) < 0.25
+    marked[:16] = False
+    for nn, gg in zip(*np.nonzero(marked)):
+        pos = rng.choice(g, size=rng.integers(1, 4), replace=False)
+        q[nn, gg * g + pos] = -8
+    e = rng.integers(-1, 2, size=(n, ng))
+    s_w = np.ldexp(1.0, e).astype(np.float32)
+    part = np.einsum("mgk,ngk->mng", xi.reshape(m, ng, g).astype(np.int64), q.reshape(n, ng, g).astype(np.int64))
+    want = (0.5 * (part * np.ldexp(1.0, e)[None]).sum(axis=2)).astype(np.float32)
+    packed, scales = B.pack_weights(dev(q), g, B.LAYOUT_TILED, dev(s_w))
+    assert np.array_equal(host(packed), o.pack_tiled(q))
+    assert np.array_equal(host(scales).view(np.uint32), o.tile_scales(s_w, q).view(np.uint32))
+    assert np.array_equal(host(B.dequant_weights(packed, n, k, B.LAYOUT_TILED)), o.dequant_codes_to_e4m3(q))
     y32, _ = run_linear(dev(x8), dev(np.array([0.5], np.float32)), packed, scales, n, g, B.LAYOUT_TILED, path)
     assert np.array_equal(y32, want)
 

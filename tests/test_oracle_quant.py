@@ -100,19 +100,24 @@ def test_tiled_pack_is_a_permutation_with_the_documented_positions():
     assert buf.size == 48 * k // 2
     assert np.array_equal(o.unpack_tiled(buf, n, k), q)
     assert np.array_equal(buf, o.pack_tiled_by_offsets(q))          # reshape form == explicit offsets
-    # hand-computed positions, straight from the layout's definition
+    # hand-computed positions and nibble patterns, straight from the layout's definition
+    hand = {0: 0x0, 1: 0x1, 2: 0x2, 3: 0x3, 4: 0x4, 5: 0x5, 6: 0x6, 7: 0x7,
+            -1: 0x9, -2: 0xA, -3: 0xB, -4: 0xC, -5: 0xD, -6: 0xE, -7: 0xF, -8: 0x8}      # sign-magnitude; -8 = 1000
     def at(nn, kk):
         t, i, c, kq, p = nn // 16, nn % 16, kk // 128, (kk % 128) // 32, kk % 32
         byte = (t * (k // 128) + c) * 1024 + (16 * kq + i) * 16 + 4 * (p // 8) + (p % 8) % 4
-        v = int(buf[byte]) >> 4 if (p % 8) >= 4 else int(buf[byte]) & 0xF
-        return v - 16 if v >= 8 else v
+        return int(buf[byte]) >> 4 if (p % 8) >= 4 else int(buf[byte]) & 0xF
     for nn, kk in [(0, 0), (0, 4), (0, 7), (0, 8), (1, 0), (15, 31), (16, 32), (17, 127), (39, 383), (5, 200)]:
-        assert at(nn, kk) == q[nn, kk]
+        assert at(nn, kk) == hand[int(q[nn, kk])]
+    assert [int(v) for v in o.tiled_nibble(np.arange(-8, 8))] == [hand[c] for c in range(-8, 8)]
+    assert np.array_equal(o.tiled_nibble_to_code(np.arange(16)), [0, 1, 2, 3, 4, 5, 6, 7, -8, -1, -2, -3, -4, -5, -6, -7])
     # one code set, everything else zero: exactly one nibble of the buffer is non-zero
     z = np.zeros((16, 128), np.int8)
     z[3, 37] = -3                                                # kq=1, p=5 -> d=0, e=5 -> byte 1, high nibble
     b = o.pack_tiled(z)
-    assert np.flatnonzero(b).tolist() == [(16 * 1 + 3) * 16 + 1] and b[(16 + 3) * 16 + 1] == 0xD0
+    assert np.flatnonzero(b).tolist() == [(16 * 1 + 3) * 16 + 1] and b[(16 + 3) * 16 + 1] == 0xB0
+    z[3, 37] = -8
+    assert o.pack_tiled(z)[(16 + 3) * 16 + 1] == 0x80
     # padding rows are code 0
     assert not o.unpack_tiled(buf, 48, k)[40:].any()
 
@@ -124,3 +129,25 @@ def test_scale_tiling_roundtrip_and_position():
     assert np.array_equal(o.untile_scales(t, 40, 3), s)
     assert t[((17 // 16) * 3 + 2) * 16 + 17 % 16] == s[17, 2]
     assert not t.reshape(3, 3, 16)[2, :, 8:].any()              # rows 40..47 are padding
+
+
+def test_scale_sign_marks_exactly_the_groups_that_hold_minus_eight():
+    rng = np.random.default_rng(12)
+    n, k, g = 40, 512, 128
+    q = rng.integers(-7, 8, size=(n, k)).astype(np.int8)        # no -8 anywhere ...
+    s = rng.uniform(0.0, 1.0, size=(n, k // g)).astype(np.float32)
+    s[5, 1] = 0.0
+    assert not np.signbit(o.tile_scales(s, q)).any()
+    assert np.array_equal(o.tile_scales(s, q), o.tile_scales(s))
+    q[3, 130] = -8                                               # ... then in row 3 group 1, row 5 group 1 (zero scale), row 39 group 3
+    q[5, 255] = -8
+    q[39, 384] = -8
+    t = o.tile_scales(s, q)
+    mag, marks = o.untile_scales(t, n, k // g, with_marks=True)
+    assert np.array_equal(mag, s)
+    want = np.zeros((n, k // g), bool)
+    want[3, 1] = want[5, 1] = want[39, 3] = True
+    assert np.array_equal(marks, want)
+    assert np.signbit(t[((3 // 16) * 4 + 1) * 16 + 3]) and t[((3 // 16) * 4 + 1) * 16 + 3] == -s[3, 1]
+    # the mark is a hint only: the packed codes alone decode to the same integers
+    assert np.array_equal(o.unpack_tiled(o.pack_tiled(q), n, k), q)
