@@ -112,13 +112,24 @@ __global__ void __launch_bounds__(max_threads(MT * NT)) linear_skinny_kernel(
         }
     };
 
-    // DEPTH chunks in flight per wavefront: a ring of register buffers, refilled in chunk order right after use
+    // DEPTH chunks in flight per wavefront: a ring of register buffers, refilled in chunk order right after use.
+    // The steady-state loop refills unconditionally: with a load that may or may not have been issued the compiler has
+    // to wait for the youngest load before every chunk (vmcnt(0)), which exposes the memory latency again; the last
+    // chunks, whose refills fall off the end of the wavefront's K range, run in a separate tail.
     {
         ChunkLoads<MT, NT> ring[DEPTH];
 #pragma unroll
         for (int d = 0; d < DEPTH; ++d)
             if (c_begin + d < c_end) load_chunk(ring[d]);
-        for (int c = c_begin; c < c_end; c += DEPTH) {
+        int c = c_begin;
+        for (; c + 2 * DEPTH <= c_end; c += DEPTH) {
+#pragma unroll
+            for (int d = 0; d < DEPTH; ++d) {
+                compute_chunk(ring[d]);
+                load_chunk(ring[d]);
+            }
+        }
+        for (; c < c_end; c += DEPTH) {
 #pragma unroll
             for (int d = 0; d < DEPTH; ++d) {
                 if (c + d < c_end) {
