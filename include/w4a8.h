@@ -55,7 +55,7 @@ typedef enum {
 } w4a8_src;
 
 typedef enum {
-    /* Row-major.  packed: byte j of row n = (code[n,2j] & 0xF) | ((code[n,2j+1] & 0xF) << 4), N*K/2 bytes.
+    /* Row-major, two's-complement nibbles.  packed: byte j of row n = (code[n,2j] & 0xF) | ((code[n,2j+1] & 0xF) << 4), N*K/2 bytes.
        scales: float32 [N, K/group_size] row-major.  Any even K, any even group_size dividing K. */
     W4A8_LAYOUT_CANONICAL = 0,
     /* Tiled for the FP8 matrix unit; needs K % 128 == 0 and group_size % 128 == 0.  Rows are padded with
