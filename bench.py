@@ -276,7 +276,9 @@ def main():
                 c = Case(3, L, m, dev, pcfg["frac"], pcfg["mult"])
                 c.quantize()
                 reps = max(3, min(50, int(2e13 / (2.0 * m * L.k * L.n))))
-                for i in range(2):
+                # untimed launches first, about as many as will be timed: building the inputs on the host leaves the GPU
+                # idle for seconds, and its clocks take some milliseconds of load to come back up
+                for i in range(max(2, reps)):
                     c.linear(i)
                 torch.cuda.synchronize()
                 t0, t1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
