@@ -321,12 +321,13 @@ LLAMA70B = list(syn.LLAMA3_70B.values())
 
 @pytest.mark.parametrize("idx", range(4))
 def test_config2_config3_llama8b_full_shapes(gpu_lib, idx):
-    """Decode (M = 1, 4, 16: every output checked) and prefill (M = 512, 2048, 8192: 32 sampled token rows, all
-    output channels) on the four Llama-3-8B layer shapes; one set of packed weights per shape."""
+    """Decode (M = 1, 4, 16: every output checked), the sizes around the kernels' crossover and the K-split launch
+    shapes (M = 33, 64, 128, 256) and prefill (M = 512, 2048, 8192) with 32 sampled token rows and all output
+    channels, on the four Llama-3-8B layer shapes; one set of packed weights per shape."""
     k, n = LLAMA8B[idx]
     for m in (1, 4, 16):
         layer_case(2, idx, m, k, n, 0.01, 20.0)
-    for m in (512, 2048, 8192):
+    for m in (33, 64, 128, 256, 512, 2048, 8192):
         layer_case(2, idx, m, k, n, 0.01, 20.0, sample_m=32)
 
 
