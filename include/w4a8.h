@@ -143,6 +143,26 @@ int w4a8_dequant_weights(const uint8_t* packed_dev, int64_t N, int64_t K, w4a8_l
                          uint8_t* w8_dev, void* stream);
 
 /*
+ * The same layer in the paper's two-level reading (Eq. 6-11 taken literally): the group scale s8[n,g] lives in the
+ * FP8 domain, the FP8 weight is the product rounded onto the E4M3 grid,
+ *   w8[n,k] = nearest_E4M3( float32(code[n,k]) * s8[n, k / group_size] )      (float32 product, ties to even,
+ *                                                                              saturating at +-448),
+ *   Y[m,n]  = cast( s_x * s_w[n] * sum_k val(x8[m,k]) * val(w8[n,k]) ),
+ * with the sum over all of K accumulated in fp32 on the matrix units and one rescale at the end (Eq. 11); s_w is the
+ * per-channel (per_channel = 1: N floats) or per-tensor (per_channel = 0: one float) scale of Eq. 6.
+ *   packed_dev, w_scales8_dev   W4A8_LAYOUT_TILED buffers as written by w4a8_pack_weights from W4A8_SRC_I8_CODES with
+ *                               the FP8-domain group scales as its scales
+ * Everything else as in w4a8_linear.  w4a8_dequant_weights_two_level writes the bytes w8 row-major [N, K] with the
+ * device routine the kernels use (test hook).
+ */
+int w4a8_linear_two_level(const uint8_t* x8_dev, int64_t M, int64_t K, int64_t ldx8, const float* x_scale_dev,
+                          const uint8_t* packed_dev, const float* w_scales8_dev, const float* w_out_scales_dev,
+                          int32_t per_channel, int64_t N, int32_t group_size, void* y_dev, w4a8_dtype y_dtype,
+                          int64_t ldy, void* stream);
+int w4a8_dequant_weights_two_level(const uint8_t* packed_dev, const float* w_scales8_dev, int64_t N, int64_t K,
+                                   int32_t group_size, uint8_t* w8_dev, void* stream);
+
+/*
  * Elementwise step of the decoder-block linear stack (all linear layers of a block are quantized, Sec. 4.1;
  * this joins gate|up to down): h[m,f] = bf16( silu(gate[m,f]) * up[m,f] ) with gate = gu[m, f],
  * up = gu[m, F + f]; gu_dev is bf16 [M, 2F] with row stride ldgu elements, h_dev bf16 [M, F], stride ldh.

@@ -32,6 +32,9 @@ SIGNATURES = {
     "w4a8_linear_variant": (_c_i32, [_c_vp, _c_i64, _c_i64, _c_i64, _c_vp, _c_vp, _c_vp, _c_i64, _c_i32, _c_vp,
                                      _c_i32, _c_i64, _c_i32, _c_i32, _c_i32, _c_vp]),
     "w4a8_dequant_weights": (_c_i32, [_c_vp, _c_i64, _c_i64, _c_i32, _c_vp, _c_vp]),
+    "w4a8_linear_two_level": (_c_i32, [_c_vp, _c_i64, _c_i64, _c_i64, _c_vp, _c_vp, _c_vp, _c_vp, _c_i32, _c_i64, _c_i32,
+                                       _c_vp, _c_i32, _c_i64, _c_vp]),
+    "w4a8_dequant_weights_two_level": (_c_i32, [_c_vp, _c_vp, _c_i64, _c_i64, _c_i32, _c_vp, _c_vp]),
     "w4a8_silu_mul": (_c_i32, [_c_vp, _c_i64, _c_i64, _c_i64, _c_vp, _c_i64, _c_vp]),
     "w4a8_probe_stream_read": (_c_i32, [_c_vp, _c_sz, _c_vp, _c_vp]),
     "w4a8_probe_mfma_e4m3": (_c_i32, [_c_i32, _c_vp, _c_vp]),
@@ -143,6 +146,28 @@ def linear_variant(x8, x_scale, packed, w_scales, n, group_size, out, path: int,
                                      out.data_ptr(), _dtype_code(out), out.stride(0) if m > 1 else max(n, out.stride(0)),
                                      path, param0, param1, _stream()), "w4a8_linear_variant")
     return out
+
+
+def linear_two_level(x8, x_scale, packed, w_scales8, w_out_scales, n, group_size, out=None, out_dtype=torch.bfloat16):
+    """w4a8_linear_two_level; `w_out_scales` holds N floats (per channel) or one (per tensor)."""
+    m, k = x8.shape
+    if out is None:
+        out = torch.empty((m, n), dtype=out_dtype, device=x8.device)
+    per_channel = 1 if w_out_scales.numel() > 1 else 0
+    assert w_out_scales.numel() in (1, n) and w_out_scales.dtype == torch.float32
+    _check(lib().w4a8_linear_two_level(x8.data_ptr(), m, k, x8.stride(0) if m > 1 else max(k, x8.stride(0)),
+                                       x_scale.data_ptr(), packed.data_ptr(), w_scales8.data_ptr(),
+                                       w_out_scales.data_ptr(), per_channel, n, group_size, out.data_ptr(),
+                                       _dtype_code(out), out.stride(0) if m > 1 else max(n, out.stride(0)), _stream()),
+           "w4a8_linear_two_level")
+    return out
+
+
+def dequant_weights_two_level(packed: torch.Tensor, w_scales8: torch.Tensor, n: int, k: int, group_size: int) -> torch.Tensor:
+    w8 = torch.empty((n, k), dtype=torch.uint8, device=packed.device)
+    _check(lib().w4a8_dequant_weights_two_level(packed.data_ptr(), w_scales8.data_ptr(), n, k, group_size, w8.data_ptr(),
+                                                _stream()), "w4a8_dequant_weights_two_level")
+    return w8
 
 
 def dequant_weights(packed: torch.Tensor, n: int, k: int, layout: int) -> torch.Tensor:

@@ -38,11 +38,14 @@ constexpr int WAVES = 8;
 
 template <int A, int B> struct MaxOf { static constexpr int value = A > B ? A : B; };
 
-template <typename OutT, int MF, int KS, int TPW>
+// TWO = false: code-exact mode (group scales applied to the partial sums in fp32).  TWO = true: two-level mode, the
+// weight operand is nearest_E4M3(code * s8[n,g]) and the sum over all of K stays in the MFMA accumulator; the output
+// is scaled by s_x * w_out[n] (w_out[0] when per_channel is 0).
+template <typename OutT, int MF, int KS, int TPW, bool TWO>
 __global__ void __launch_bounds__(512, (KS * MF > 16 || MF * TPW > 16) ? 2 : 4) linear_mfma_kernel(
     const uint8_t* __restrict__ x8, int M, int64_t ldx8, const float* __restrict__ s_x,
     const uint8_t* __restrict__ packed, const float* __restrict__ scales, int N, int n_tiles, int C, int cpg, int NG,
-    OutT* __restrict__ y, int64_t ldy, int grid_m, int grid_n) {
+    OutT* __restrict__ y, int64_t ldy, int grid_m, int grid_n, const float* __restrict__ w_out, int per_channel) {
     constexpr int NB = WAVES / KS;                               // wavefronts per K-split group, TPW weight bands each
     constexpr int BN = 16 * NB * TPW, BM = 16 * MF;
     constexpr int PAGES = KS * MF * 2;                           // 1 KiB pages of activations per pass
@@ -161,6 +164,9 @@ __global__ void __launch_bounds__(512, (KS * MF > 16 || MF * TPW > 16) ? 2 : 4) 
             }
             if (c + 2 * KS < C) stage_w(c + 2 * KS, seen);
         }
+        MagTable tab[TPW];                                       // two-level mode: the next chunk's magnitude tables
+#pragma unroll
+        for (int j = 0; j < TPW; ++j) tab[j] = TWO ? two_level_table(next.s[j]) : MagTable{0u, 0u, 0u};
         if (c < C) {
             const uint8_t* xb = lds + buf * STAGE_BYTES;
             uint4 xa = *reinterpret_cast<const uint4*>(xb + xa_off);
@@ -178,8 +184,9 @@ __global__ void __launch_bounds__(512, (KS * MF > 16 || MF * TPW > 16) ? 2 : 4) 
 #pragma unroll
                 for (int j = 0; j < TPW; ++j) {
                     const int st = f * TPW + j;                  // step number
-                    const v4f p = mfma_16x16x128_e4m3(xop, cur.op[j], v4f{0.f, 0.f, 0.f, 0.f});
-                    if (st > 0) {
+                    if (TWO) acc[f][j] = mfma_16x16x128_e4m3(xop, cur.op[j], acc[f][j]);
+                    const v4f p = TWO ? v4f{0.f, 0.f, 0.f, 0.f} : mfma_16x16x128_e4m3(xop, cur.op[j], v4f{0.f, 0.f, 0.f, 0.f});
+                    if (!TWO && st > 0) {
                         const int fp = (st - 1) / TPW, jp = (st - 1) % TPW;
                         const float sc = fabsf(cur.s[jp]);       // the sign bit is the packer's mark, not part of the scale
                         acc[fp][jp][0] = fmaf(sc, p_prev[0], acc[fp][jp][0]);
@@ -194,23 +201,31 @@ __global__ void __launch_bounds__(512, (KS * MF > 16 || MF * TPW > 16) ? 2 : 4) 
                     for (int E = st * 8 / MF; E < (st + 1) * 8 / MF; ++E) {
                         const int jb = E / 8, e = E % 8;
                         const uint32_t src = (e >> 1) == 0 ? raw[jb].x : (e >> 1) == 1 ? raw[jb].y : (e >> 1) == 2 ? raw[jb].z : raw[jb].w;
-                        uint32_t o = (e & 1) ? sm_half_to_e4m3_fast<4>(src) : sm_half_to_e4m3_fast<0>(src);
-                        if (m8[jb]) o = sm_fix_minus_eight(o);   // wave-uniform, rare
+                        uint32_t o;
+                        if (TWO) {
+                            o = (e & 1) ? two_level_half_fast<4>(src, tab[jb]) : two_level_half_fast<0>(src, tab[jb]);
+                            if (m8[jb]) o = (e & 1) ? two_level_fix_minus_eight<4>(o, src, tab[jb]) : two_level_fix_minus_eight<0>(o, src, tab[jb]);
+                        } else {
+                            o = (e & 1) ? sm_half_to_e4m3_fast<4>(src) : sm_half_to_e4m3_fast<0>(src);
+                            if (m8[jb]) o = sm_fix_minus_eight(o);   // wave-uniform, rare
+                        }
                         keep_here(o);
                         next.op[jb][e] = (int)o;
                     }
                     p_prev = p;
                     __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);              // LDS reads of the next block
                     __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);              // this step's MFMA
-                    __builtin_amdgcn_sched_group_barrier(0x002, 4 + 4 * PIECES, 0); // vector ALU work independent of it
+                    __builtin_amdgcn_sched_group_barrier(0x002, (TWO ? 0 : 4) + 4 * PIECES, 0);   // ALU work independent of it
                     __builtin_amdgcn_sched_barrier(0);
                 }
             }
-            const float sc = fabsf(cur.s[TPW - 1]);
-            acc[MF - 1][TPW - 1][0] = fmaf(sc, p_prev[0], acc[MF - 1][TPW - 1][0]);
-            acc[MF - 1][TPW - 1][1] = fmaf(sc, p_prev[1], acc[MF - 1][TPW - 1][1]);
-            acc[MF - 1][TPW - 1][2] = fmaf(sc, p_prev[2], acc[MF - 1][TPW - 1][2]);
-            acc[MF - 1][TPW - 1][3] = fmaf(sc, p_prev[3], acc[MF - 1][TPW - 1][3]);
+            if (!TWO) {
+                const float sc = fabsf(cur.s[TPW - 1]);
+                acc[MF - 1][TPW - 1][0] = fmaf(sc, p_prev[0], acc[MF - 1][TPW - 1][0]);
+                acc[MF - 1][TPW - 1][1] = fmaf(sc, p_prev[1], acc[MF - 1][TPW - 1][1]);
+                acc[MF - 1][TPW - 1][2] = fmaf(sc, p_prev[2], acc[MF - 1][TPW - 1][2]);
+                acc[MF - 1][TPW - 1][3] = fmaf(sc, p_prev[3], acc[MF - 1][TPW - 1][3]);
+            }
         }
         lds_dma_wait_all();                                      // this wavefront's copies have landed ...
         __syncthreads();                                         // ... and so have everyone's; the block just read is free
@@ -238,7 +253,8 @@ __global__ void __launch_bounds__(512, (KS * MF > 16 || MF * TPW > 16) ? 2 : 4) 
         stage_x(0, 0);
         if (kg + KS < C) stage_w(kg + KS, 0u);
 #pragma unroll
-        for (int j = 0; j < TPW; ++j) wa.op[j] = slot_to_operand<true>(raw0[j]);
+        for (int j = 0; j < TPW; ++j)
+            wa.op[j] = TWO ? slot_to_operand_two_level<true>(raw0[j], two_level_table(wa.s[j])) : slot_to_operand<true>(raw0[j]);
     }
     lds_dma_wait_all();
     __syncthreads();
@@ -279,6 +295,12 @@ __global__ void __launch_bounds__(512, (KS * MF > 16 || MF * TPW > 16) ? 2 : 4) 
     // Epilogue.  Result lane: channel = lane % 16 of the band, tokens 4*kq .. 4*kq+3 of block f.  The workgroup turns
     // FR 16-token slabs at a time into row-major order in LDS and stores whole BN-channel row segments.
     const float sx = *s_x;
+    float so[TPW];                                               // output scale of the lane's channel of each band
+#pragma unroll
+    for (int j = 0; j < TPW; ++j) {
+        const int n = bn * BN + (band * TPW + j) * 16 + i;
+        so[j] = TWO ? sx * w_out[per_channel ? min(n, N - 1) : 0] : sx;
+    }
     OutT* slab = reinterpret_cast<OutT*>(lds);
     constexpr int VEC = 16 / sizeof(OutT);                       // elements per 16-byte store
     constexpr int UPR = BN / VEC;                                // 16-byte units per row
@@ -295,7 +317,7 @@ __global__ void __launch_bounds__(512, (KS * MF > 16 || MF * TPW > 16) ? 2 : 4) 
 #pragma unroll
                         for (int r = 0; r < 4; ++r)
                             slab[(ff * 16 + 4 * kq + r) * RS + (band * TPW + j) * 16 + i] =
-                                OutCast<OutT>::cast(sx * acc[(f0 + ff < MF) ? f0 + ff : 0][j][r]);
+                                OutCast<OutT>::cast(so[j] * acc[(f0 + ff < MF) ? f0 + ff : 0][j][r]);
                 }
             }
         }
@@ -319,20 +341,25 @@ __global__ void __launch_bounds__(512, (KS * MF > 16 || MF * TPW > 16) ? 2 : 4) 
 }
 
 template <typename OutT, int MF, int KS, int TPW>
-void launch_one(dim3 grid, hipStream_t st, const uint8_t* x8, int M, int64_t ldx8, const float* s_x, const uint8_t* packed,
+void launch_one(const float* w_out, int per_channel, dim3 grid, hipStream_t st, const uint8_t* x8, int M, int64_t ldx8, const float* s_x, const uint8_t* packed,
                 const float* scales, int N, int n_tiles, int C, int cpg, int NG, void* y, int64_t ldy, int grid_m,
                 int grid_n) {
-    hipLaunchKernelGGL((linear_mfma_kernel<OutT, MF, KS, TPW>), grid, dim3(WAVES * 64), 0, st, x8, M, ldx8, s_x, packed, scales, N,
-                       n_tiles, C, cpg, NG, static_cast<OutT*>(y), ldy, grid_m, grid_n);
+    if (w_out)
+        hipLaunchKernelGGL((linear_mfma_kernel<OutT, MF, KS, TPW, true>), grid, dim3(WAVES * 64), 0, st, x8, M, ldx8, s_x, packed,
+                           scales, N, n_tiles, C, cpg, NG, static_cast<OutT*>(y), ldy, grid_m, grid_n, w_out, per_channel);
+    else
+        hipLaunchKernelGGL((linear_mfma_kernel<OutT, MF, KS, TPW, false>), grid, dim3(WAVES * 64), 0, st, x8, M, ldx8, s_x, packed,
+                           scales, N, n_tiles, C, cpg, NG, static_cast<OutT*>(y), ldy, grid_m, grid_n, nullptr, 0);
 }
 
 }  // namespace
 
 // mf = 16-token blocks per workgroup (4, 8 or 16), ks = K-split groups (1, 2 or 4), tpw = weight bands per wavefront
-// (1 or 2); 0 = chosen from the shape.
+// (1 or 2); 0 = chosen from the shape.  w_out != nullptr selects the two-level mode.
 int launch_linear_mfma_tiled(const uint8_t* x8, int64_t M, int64_t K, int64_t ldx8, const float* s_x,
                              const uint8_t* packed, const float* scales, int64_t N, int32_t G, void* y,
-                             w4a8_dtype ydt, int64_t ldy, int mf, int ks, int tpw, hipStream_t st) {
+                             w4a8_dtype ydt, int64_t ldy, int mf, int ks, int tpw, const float* w_out, int per_channel,
+                             hipStream_t st) {
     if (!(mf == 0 || mf == 4 || mf == 8 || mf == 16) || !(ks == 0 || ks == 1 || ks == 2 || ks == 4) || tpw < 0 || tpw > 2)
         return W4A8_ERR_SHAPE;
     const int C = (int)(K / 128), cpg = G / 128, NG = (int)(K / G);
@@ -376,10 +403,10 @@ int launch_linear_mfma_tiled(const uint8_t* x8, int64_t M, int64_t K, int64_t ld
     if (mf == MFV && ks == KSV && tpw == TPV) {                                                                              \
         launched = true;                                                                                                     \
         if (ydt == W4A8_F32)                                                                                                 \
-            launch_one<float, MFV, KSV, TPV>(grid, st, x8, (int)M, ldx8, s_x, packed, scales, (int)N, n_tiles, C, cpg, NG, y, \
+            launch_one<float, MFV, KSV, TPV>(w_out, per_channel, grid, st, x8, (int)M, ldx8, s_x, packed, scales, (int)N, n_tiles, C, cpg, NG, y, \
                                              ldy, grid_m, grid_n);                                                           \
         else                                                                                                                 \
-            launch_one<uint16_t, MFV, KSV, TPV>(grid, st, x8, (int)M, ldx8, s_x, packed, scales, (int)N, n_tiles, C, cpg, NG, \
+            launch_one<uint16_t, MFV, KSV, TPV>(w_out, per_channel, grid, st, x8, (int)M, ldx8, s_x, packed, scales, (int)N, n_tiles, C, cpg, NG, \
                                                 y, ldy, grid_m, grid_n);                                                     \
     }
     W4A8_CASE(16, 1, 2) W4A8_CASE(16, 1, 1) W4A8_CASE(8, 1, 1) W4A8_CASE(8, 2, 1) W4A8_CASE(4, 1, 1)

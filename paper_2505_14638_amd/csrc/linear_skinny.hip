@@ -28,12 +28,15 @@ struct ChunkLoads {
 // register budget per lane: 128 at 1024 threads, 256 at 512 and below
 constexpr int max_threads(int tiles) { return tiles <= 2 ? 1024 : (tiles <= 8 ? 512 : 256); }
 
-// DEPTH = chunks in flight per wavefront (a ring of register buffers)
-template <int MT, int NT, int DEPTH, typename OutT>
+// DEPTH = chunks in flight per wavefront (a ring of register buffers).  TWO = false: code-exact mode (group scales
+// applied to the partial sums in fp32).  TWO = true: two-level mode, the weight operand is nearest_E4M3(code * s8[n,g]),
+// the sum over the wavefront's share of K stays in the MFMA accumulator and the output is scaled by s_x * w_out[n]
+// (w_out[0] when per_channel is 0).
+template <int MT, int NT, int DEPTH, typename OutT, bool TWO>
 __global__ void __launch_bounds__(max_threads(MT * NT)) linear_skinny_kernel(
     const uint8_t* __restrict__ x8, int M, int64_t ldx8, const float* __restrict__ s_x,
     const uint8_t* __restrict__ packed, const float* __restrict__ scales, int N, int n_tiles, int C, int cpg, int NG,
-    OutT* __restrict__ y, int64_t ldy, int cpw) {
+    OutT* __restrict__ y, int64_t ldy, int cpw, const float* __restrict__ w_out, int per_channel) {
     extern __shared__ float red[];
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);     // wave-uniform: keeps the loop scalar
@@ -65,7 +68,10 @@ __global__ void __launch_bounds__(max_threads(MT * NT)) linear_skinny_kernel(
 #pragma unroll
         for (int j = 0; j < NT; ++j) {
             L.w[j] = *reinterpret_cast<const uint4*>(wbase[j] + woff);
-            L.s[j] = *reinterpret_cast<const float4*>(sbase[j] + (int64_t)g * 64 + soff);
+            if (TWO)                                            // the scale of the channel whose nibbles this lane expands
+                L.s[j] = make_float4(*reinterpret_cast<const float*>(sbase[j] + (int64_t)g * 64 + i * 4), 0.f, 0.f, 0.f);
+            else
+                L.s[j] = *reinterpret_cast<const float4*>(sbase[j] + (int64_t)g * 64 + soff);
             wbase[j] += 1024;
         }
 #pragma unroll
@@ -96,13 +102,23 @@ __global__ void __launch_bounds__(max_threads(MT * NT)) linear_skinny_kernel(
             // a marked scale (sign bit) on any of the band's 16 channels: this chunk's tile may hold -8
             const bool m8 = any_marked(__uint_as_float(__float_as_uint(s.x) | __float_as_uint(s.y) | __float_as_uint(s.z) |
                                                        __float_as_uint(s.w)));
-            v8i wop = slot_to_operand<false>(L.w[j]);
-            if (m8) {                                            // wave-uniform, rare
+            v8i wop;
+            if (TWO) {
+                const MagTable tab = two_level_table(s.x);
+                wop = m8 ? slot_to_operand_two_level<true>(L.w[j], tab) : slot_to_operand_two_level<false>(L.w[j], tab);
+            } else {
+                wop = slot_to_operand<false>(L.w[j]);
+                if (m8) {                                        // wave-uniform, rare
 #pragma unroll
-                for (int e = 0; e < 8; ++e) wop[e] = (int)sm_fix_minus_eight((uint32_t)wop[e]);
+                    for (int e = 0; e < 8; ++e) wop[e] = (int)sm_fix_minus_eight((uint32_t)wop[e]);
+                }
             }
 #pragma unroll
             for (int mt = 0; mt < MT; ++mt) {
+                if (TWO) {
+                    acc[mt][j] = mfma_16x16x128_e4m3(wop, xop[mt], acc[mt][j]);
+                    continue;
+                }
                 const v4f p = mfma_16x16x128_e4m3(wop, xop[mt], v4f{0.f, 0.f, 0.f, 0.f});
                 acc[mt][j][0] = fmaf(fabsf(s.x), p[0], acc[mt][j][0]);
                 acc[mt][j][1] = fmaf(fabsf(s.y), p[1], acc[mt][j][1]);
@@ -159,45 +175,48 @@ __global__ void __launch_bounds__(max_threads(MT * NT)) linear_skinny_kernel(
         float sum = 0.0f;
         for (int w = 0; w < waves; ++w) sum += red[(w * E + e) * RED_STRIDE + src_lane];
         const int m = mt * 16 + ml, n = (t0 + j) * 16 + nl;
-        if (m < M && n < N) y[(int64_t)m * ldy + n] = OutCast<OutT>::cast(sx * sum);
+        if (m < M && n < N) y[(int64_t)m * ldy + n] = OutCast<OutT>::cast((TWO ? sx * w_out[per_channel ? n : 0] : sx) * sum);
     }
 }
 
 template <int MT, int NT, typename OutT>
-int launch_one(int depth, const uint8_t* x8, int M, int64_t ldx8, const float* s_x, const uint8_t* packed, const float* scales,
+int launch_one(const float* w_out, int per_channel, int depth, const uint8_t* x8, int M, int64_t ldx8, const float* s_x, const uint8_t* packed, const float* scales,
                int N, int C, int cpg, int NG, void* y, int64_t ldy, int waves, hipStream_t st) {
     const int n_tiles = (N + 15) / 16;
     const int grid = (n_tiles + NT - 1) / NT;
     const int cpw = (C + waves - 1) / waves;
     const size_t lds = (size_t)waves * MT * NT * 4 * RED_STRIDE * sizeof(float);
     constexpr int DEEP = (MT * NT == 1) ? 4 : 2;                 // deeper ring while the registers allow it
-    if (depth == DEEP)
-        hipLaunchKernelGGL((linear_skinny_kernel<MT, NT, DEEP, OutT>), dim3(grid), dim3(waves * 64), lds, st, x8, M,
-                           ldx8, s_x, packed, scales, N, n_tiles, C, cpg, NG, static_cast<OutT*>(y), ldy, cpw);
+    if (w_out)
+        hipLaunchKernelGGL((linear_skinny_kernel<MT, NT, 2, OutT, true>), dim3(grid), dim3(waves * 64), lds, st, x8, M, ldx8,
+                           s_x, packed, scales, N, n_tiles, C, cpg, NG, static_cast<OutT*>(y), ldy, cpw, w_out, per_channel);
+    else if (depth == DEEP)
+        hipLaunchKernelGGL((linear_skinny_kernel<MT, NT, DEEP, OutT, false>), dim3(grid), dim3(waves * 64), lds, st, x8, M,
+                           ldx8, s_x, packed, scales, N, n_tiles, C, cpg, NG, static_cast<OutT*>(y), ldy, cpw, nullptr, 0);
     else
-        hipLaunchKernelGGL((linear_skinny_kernel<MT, NT, 2, OutT>), dim3(grid), dim3(waves * 64), lds, st, x8, M, ldx8,
-                           s_x, packed, scales, N, n_tiles, C, cpg, NG, static_cast<OutT*>(y), ldy, cpw);
+        hipLaunchKernelGGL((linear_skinny_kernel<MT, NT, 2, OutT, false>), dim3(grid), dim3(waves * 64), lds, st, x8, M, ldx8,
+                           s_x, packed, scales, N, n_tiles, C, cpg, NG, static_cast<OutT*>(y), ldy, cpw, nullptr, 0);
     return launch_status();
 }
 
 template <int MT, typename OutT>
-int launch_nt(int nt, int depth, const uint8_t* x8, int M, int64_t ldx8, const float* s_x, const uint8_t* packed,
+int launch_nt(const float* w_out, int per_channel, int nt, int depth, const uint8_t* x8, int M, int64_t ldx8, const float* s_x, const uint8_t* packed,
               const float* scales, int N, int C, int cpg, int NG, void* y, int64_t ldy, int waves, hipStream_t st) {
     switch (nt) {
-        case 1: return launch_one<MT, 1, OutT>(depth, x8, M, ldx8, s_x, packed, scales, N, C, cpg, NG, y, ldy, waves, st);
-        case 2: return launch_one<MT, 2, OutT>(depth, x8, M, ldx8, s_x, packed, scales, N, C, cpg, NG, y, ldy, waves, st);
-        case 4: return launch_one<MT, 4, OutT>(depth, x8, M, ldx8, s_x, packed, scales, N, C, cpg, NG, y, ldy, waves, st);
+        case 1: return launch_one<MT, 1, OutT>(w_out, per_channel, depth, x8, M, ldx8, s_x, packed, scales, N, C, cpg, NG, y, ldy, waves, st);
+        case 2: return launch_one<MT, 2, OutT>(w_out, per_channel, depth, x8, M, ldx8, s_x, packed, scales, N, C, cpg, NG, y, ldy, waves, st);
+        case 4: return launch_one<MT, 4, OutT>(w_out, per_channel, depth, x8, M, ldx8, s_x, packed, scales, N, C, cpg, NG, y, ldy, waves, st);
     }
     return W4A8_ERR_SHAPE;
 }
 
 template <typename OutT>
-int launch_mt(int mt, int nt, int depth, const uint8_t* x8, int M, int64_t ldx8, const float* s_x, const uint8_t* packed,
+int launch_mt(const float* w_out, int per_channel, int mt, int nt, int depth, const uint8_t* x8, int M, int64_t ldx8, const float* s_x, const uint8_t* packed,
               const float* scales, int N, int C, int cpg, int NG, void* y, int64_t ldy, int waves, hipStream_t st) {
     switch (mt) {
-        case 1: return launch_nt<1, OutT>(nt, depth, x8, M, ldx8, s_x, packed, scales, N, C, cpg, NG, y, ldy, waves, st);
-        case 2: return launch_nt<2, OutT>(nt, depth, x8, M, ldx8, s_x, packed, scales, N, C, cpg, NG, y, ldy, waves, st);
-        default: return launch_nt<4, OutT>(nt, depth, x8, M, ldx8, s_x, packed, scales, N, C, cpg, NG, y, ldy, waves, st);
+        case 1: return launch_nt<1, OutT>(w_out, per_channel, nt, depth, x8, M, ldx8, s_x, packed, scales, N, C, cpg, NG, y, ldy, waves, st);
+        case 2: return launch_nt<2, OutT>(w_out, per_channel, nt, depth, x8, M, ldx8, s_x, packed, scales, N, C, cpg, NG, y, ldy, waves, st);
+        default: return launch_nt<4, OutT>(w_out, per_channel, nt, depth, x8, M, ldx8, s_x, packed, scales, N, C, cpg, NG, y, ldy, waves, st);
     }
 }
 
@@ -205,7 +224,7 @@ int launch_mt(int mt, int nt, int depth, const uint8_t* x8, int M, int64_t ldx8,
 
 int launch_linear_skinny(const uint8_t* x8, int64_t M, int64_t K, int64_t ldx8, const float* s_x,
                          const uint8_t* packed, const float* scales, int64_t N, int32_t G, void* y, w4a8_dtype ydt,
-                         int64_t ldy, int nt, int waves, int depth, hipStream_t st) {
+                         int64_t ldy, int nt, int waves, int depth, const float* w_out, int per_channel, hipStream_t st) {
     if (M < 1 || M > 64) return W4A8_ERR_SHAPE;
     const int C = (int)(K / 128), cpg = G / 128, NG = (int)(K / G);
     const int n_tiles = (int)((N + 15) / 16);
@@ -228,8 +247,8 @@ int launch_linear_skinny(const uint8_t* x8, int64_t M, int64_t K, int64_t ldx8, 
     if (depth == 0) depth = 2;                                   // deeper rings cost occupancy and measured no faster
     if (depth != 2 && depth != 4) return W4A8_ERR_SHAPE;
     if (ydt == W4A8_F32)
-        return launch_mt<float>(mt, nt, depth, x8, (int)M, ldx8, s_x, packed, scales, (int)N, C, cpg, NG, y, ldy, waves, st);
-    return launch_mt<uint16_t>(mt, nt, depth, x8, (int)M, ldx8, s_x, packed, scales, (int)N, C, cpg, NG, y, ldy, waves, st);
+        return launch_mt<float>(w_out, per_channel, mt, nt, depth, x8, (int)M, ldx8, s_x, packed, scales, (int)N, C, cpg, NG, y, ldy, waves, st);
+    return launch_mt<uint16_t>(w_out, per_channel, mt, nt, depth, x8, (int)M, ldx8, s_x, packed, scales, (int)N, C, cpg, NG, y, ldy, waves, st);
 }
 
 }  // namespace w4a8

@@ -115,8 +115,10 @@ __global__ void __launch_bounds__(256) pack_kernel(const void* __restrict__ src,
 }
 
 // tiled: one thread per 16-byte slot -> 32 consecutive bytes of one row of w8
+// scales8 != nullptr: two-level bytes nearest_E4M3(code * s8[n, g]) with the tiled scale buffer of group size G
 __global__ void __launch_bounds__(256) dequant_tiled_kernel(const uint4* __restrict__ packed, int64_t N, int64_t K,
-                                                            int64_t slots, uint8_t* __restrict__ w8) {
+                                                            int64_t slots, uint8_t* __restrict__ w8,
+                                                            const float* __restrict__ scales8, int32_t G) {
     const int64_t u = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (u >= slots) return;
     const int64_t tile = u >> 6, C = K >> 7;
@@ -124,7 +126,13 @@ __global__ void __launch_bounds__(256) dequant_tiled_kernel(const uint4* __restr
     const int slot = (int)(u & 63), kq = slot >> 4, i = slot & 15;
     const int64_t n = t * 16 + i;
     if (n >= N) return;
-    const v8i op = slot_to_operand<true>(packed[u]);
+    v8i op;
+    if (scales8) {
+        const int64_t NG = K / G, grp = (c * 128) / G;
+        op = slot_to_operand_two_level<true>(packed[u], two_level_table(scales8[(t * NG + grp) * 16 + i]));
+    } else {
+        op = slot_to_operand<true>(packed[u]);
+    }
     uint4* dst = reinterpret_cast<uint4*>(w8 + n * K + c * 128 + kq * 32);
     dst[0] = make_uint4((uint32_t)op[0], (uint32_t)op[1], (uint32_t)op[2], (uint32_t)op[3]);
     dst[1] = make_uint4((uint32_t)op[4], (uint32_t)op[5], (uint32_t)op[6], (uint32_t)op[7]);
@@ -167,11 +175,11 @@ int launch_pack_weights(const void* src, w4a8_src kind, const float* src_scales,
 }
 
 int launch_dequant_weights(const uint8_t* packed, int64_t N, int64_t K, w4a8_layout layout, uint8_t* w8,
-                           hipStream_t st) {
+                           const float* scales8, int32_t G, hipStream_t st) {
     if (layout == W4A8_LAYOUT_TILED) {
         const int64_t slots = ((N + 15) / 16) * (K / 128) * 64;
         hipLaunchKernelGGL(dequant_tiled_kernel, dim3(blocks_for(slots)), dim3(256), 0, st,
-                           reinterpret_cast<const uint4*>(packed), N, K, slots, w8);
+                           reinterpret_cast<const uint4*>(packed), N, K, slots, w8, scales8, G);
     } else {
         const int64_t bytes = N * (K / 2);
         hipLaunchKernelGGL(dequant_canonical_kernel, dim3(blocks_for(bytes)), dim3(256), 0, st, packed, bytes, w8);

@@ -77,6 +77,63 @@ __device__ __forceinline__ void nibbles_to_e4m3(uint32_t w, uint32_t& lo, uint32
     hi = __builtin_amdgcn_perm(neg_h, pos_h, mix_h);
 }
 
+// ---------------------------------------------------------------------------------------------
+// Two-level mode (Eq. 6-11 read literally): the FP8 weight is nearest_E4M3(code * s8), s8 the group's scale in the FP8
+// domain.  nearest_E4M3 is odd, so the byte is sign << 7 | nearest_E4M3(|code| * |s8|): per (lane, chunk) a table of
+// the nine magnitudes 0..8 times |s8| (float32 products, clamped to 448, rounded by the hardware converter), looked up
+// exactly like the constant table of the code-exact mode.
+// ---------------------------------------------------------------------------------------------
+struct MagTable {
+    uint32_t lo, hi;      // bytes: nearest_E4M3(m * |s8|) for m = 0..3 and m = 4..7
+    uint32_t m8;          // the same for m = 8, in the low byte
+};
+
+__device__ __forceinline__ MagTable two_level_table(float s8) {
+    const float a = fabsf(s8);
+    auto c = [&](float m) { const float v = m * a; return v > 448.0f ? 448.0f : v; };   // a NaN scale stays NaN
+    MagTable t;
+    t.lo = (uint32_t)__builtin_amdgcn_cvt_pk_fp8_f32(0.0f, c(1.0f), 0, false);
+    t.lo = (uint32_t)__builtin_amdgcn_cvt_pk_fp8_f32(c(2.0f), c(3.0f), (int)t.lo, true);
+    t.hi = (uint32_t)__builtin_amdgcn_cvt_pk_fp8_f32(c(4.0f), c(5.0f), 0, false);
+    t.hi = (uint32_t)__builtin_amdgcn_cvt_pk_fp8_f32(c(6.0f), c(7.0f), (int)t.hi, true);
+    t.m8 = (uint32_t)__builtin_amdgcn_cvt_pk_fp8_f32(c(8.0f), 0.0f, 0, false) & 0xFFu;
+    return t;
+}
+
+// E4M3 bytes of the four sign-magnitude nibbles at bit offset SHIFT of the bytes of w under table t; the pattern 1000
+// (-8) comes out as 0x80 | t[0] and is put right by two_level_fix_minus_eight.
+template <int SHIFT>
+__device__ __forceinline__ uint32_t two_level_half_fast(uint32_t w, const MagTable& t) {
+    const uint32_t sel = (w >> SHIFT) & 0x07070707u;
+    const uint32_t mag = __builtin_amdgcn_perm(t.hi, t.lo, sel);
+    const uint32_t sign = SHIFT ? w : (w << 4);
+    return (sign & 0x80808080u) | mag;
+}
+
+template <int SHIFT>
+__device__ __forceinline__ uint32_t two_level_fix_minus_eight(uint32_t e, uint32_t w, const MagTable& t) {
+    const uint32_t x = ((w >> SHIFT) & 0x0F0F0F0Fu) ^ 0x08080808u;                   // zero bytes: nibble 1000
+    const uint32_t z = ~(((x & 0x7F7F7F7Fu) + 0x7F7F7F7Fu) | x | 0x7F7F7F7Fu);       // 0x80 there, exact
+    return e | ((z >> 7) * t.m8);                                                    // m8 < 0x80: no carries
+}
+
+template <bool ANY_M8>
+__device__ __forceinline__ v8i slot_to_operand_two_level(uint4 s, const MagTable& t) {
+    const uint32_t w[4] = {s.x, s.y, s.z, s.w};
+    v8i v;
+#pragma unroll
+    for (int d = 0; d < 4; ++d) {
+        uint32_t a = two_level_half_fast<0>(w[d], t), b = two_level_half_fast<4>(w[d], t);
+        if (ANY_M8) {
+            a = two_level_fix_minus_eight<0>(a, w[d], t);
+            b = two_level_fix_minus_eight<4>(b, w[d], t);
+        }
+        v[2 * d] = (int)a;
+        v[2 * d + 1] = (int)b;
+    }
+    return v;
+}
+
 // True when some lane of the wavefront holds a scale whose sign bit is set (the packer's "-8 in this group" mark).
 __device__ __forceinline__ bool any_marked(float s) { return __builtin_amdgcn_ballot_w64(__float_as_int(s) < 0) != 0; }
 

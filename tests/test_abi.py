@@ -106,6 +106,22 @@ def test_linear_validation(L):
     assert fv(P, 0, 256, 256, P, P, P, 64, 128, P, B.BF16, 64, 0, 1, 1, None) == 0
 
 
+def test_two_level_validation(L):
+    f = L.w4a8_linear_two_level
+    # x8, M, K, ldx8, xs, packed, s8, s_out, per_channel, N, G, y, ydt, ldy, stream
+    assert f(P, 0, 256, 256, P, P, P, P, 1, 64, 128, P, B.BF16, 64, None) == 0         # M == 0: no-op
+    assert f(P, 4, 256, 256, P, P, P, 0, 1, 64, 128, P, B.BF16, 64, None) == 1         # NULL output scales
+    assert f(P, 4, 256, 256, P, P, 0, P, 1, 64, 128, P, B.BF16, 64, None) == 1         # NULL group scales
+    assert f(P, 4, 256, 256, P, P, P, P, 2, 64, 128, P, B.BF16, 64, None) == 4         # per_channel is 0 or 1
+    assert f(P, 4, 256, 256, P, P, P, P + 2, 1, 64, 128, P, B.BF16, 64, None) == 6     # misaligned output scales
+    assert f(P, 4, 256, 256, P, P, P, P, 1, 64, 96, P, B.BF16, 64, None) == 3          # tiled needs G % 128 == 0
+    assert f(P, 4, 200, 200, P, P, P, P, 1, 64, 200, P, B.BF16, 64, None) == 5         # tiled needs K % 128 == 0
+    d = L.w4a8_dequant_weights_two_level
+    assert d(P, 0, 16, 256, 128, P, None) == 1
+    assert d(P, P, 16, 256, 64, P, None) == 3
+    assert d(P + 8, P, 16, 256, 128, P, None) == 6
+
+
 def test_other_validation(L):
     assert L.w4a8_dequant_weights(0, 16, 256, B.LAYOUT_TILED, P, None) == 1
     assert L.w4a8_dequant_weights(P, 16, 200, B.LAYOUT_TILED, P, None) == 5
