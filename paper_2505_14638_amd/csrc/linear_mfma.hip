@@ -200,11 +200,14 @@ __global__ void __launch_bounds__(512, (KS * MF > 16 || MF * TPW > 16) ? 2 : 4) 
 #pragma unroll
                     for (int E = st * 8 / MF; E < (st + 1) * 8 / MF; ++E) {
                         const int jb = E / 8, e = E % 8;
-                        const uint32_t src = (e >> 1) == 0 ? raw[jb].x : (e >> 1) == 1 ? raw[jb].y : (e >> 1) == 2 ? raw[jb].z : raw[jb].w;
+                        const int d = e >> 1;
+                        const uint32_t src = d == 0 ? raw[jb].x : d == 1 ? raw[jb].y : d == 2 ? raw[jb].z : raw[jb].w;
                         uint32_t o;
                         if (TWO) {
                             o = (e & 1) ? two_level_half_fast<4>(src, tab[jb]) : two_level_half_fast<0>(src, tab[jb]);
-                            if (m8[jb]) o = (e & 1) ? two_level_fix_minus_eight<4>(o, src, tab[jb]) : two_level_fix_minus_eight<0>(o, src, tab[jb]);
+                            if (m8[jb])
+                                o = (e & 1) ? two_level_fix_minus_eight<4>(o, src, tab[jb])
+                                            : two_level_fix_minus_eight<0>(o, src, tab[jb]);
                         } else {
                             o = (e & 1) ? sm_half_to_e4m3_fast<4>(src) : sm_half_to_e4m3_fast<0>(src);
                             if (m8[jb]) o = sm_fix_minus_eight(o);   // wave-uniform, rare
@@ -341,15 +344,16 @@ __global__ void __launch_bounds__(512, (KS * MF > 16 || MF * TPW > 16) ? 2 : 4) 
 }
 
 template <typename OutT, int MF, int KS, int TPW>
-void launch_one(const float* w_out, int per_channel, dim3 grid, hipStream_t st, const uint8_t* x8, int M, int64_t ldx8, const float* s_x, const uint8_t* packed,
-                const float* scales, int N, int n_tiles, int C, int cpg, int NG, void* y, int64_t ldy, int grid_m,
-                int grid_n) {
-    if (w_out)
-        hipLaunchKernelGGL((linear_mfma_kernel<OutT, MF, KS, TPW, true>), grid, dim3(WAVES * 64), 0, st, x8, M, ldx8, s_x, packed,
-                           scales, N, n_tiles, C, cpg, NG, static_cast<OutT*>(y), ldy, grid_m, grid_n, w_out, per_channel);
+void launch_one(const LinearArgs& a, dim3 grid, int grid_m, int grid_n, hipStream_t st) {
+#define W4A8_MFMA(TWOV)                                                                                                   \
+    hipLaunchKernelGGL((linear_mfma_kernel<OutT, MF, KS, TPW, TWOV>), grid, dim3(WAVES * 64), 0, st, a.x8, a.M, a.ldx8, a.s_x, \
+                       a.packed, a.scales, a.N, a.n_tiles, a.C, a.cpg, a.NG, static_cast<OutT*>(a.y), a.ldy, grid_m, grid_n,  \
+                       a.w_out, a.per_channel)
+    if (a.w_out)
+        W4A8_MFMA(true);
     else
-        hipLaunchKernelGGL((linear_mfma_kernel<OutT, MF, KS, TPW, false>), grid, dim3(WAVES * 64), 0, st, x8, M, ldx8, s_x, packed,
-                           scales, N, n_tiles, C, cpg, NG, static_cast<OutT*>(y), ldy, grid_m, grid_n, nullptr, 0);
+        W4A8_MFMA(false);
+#undef W4A8_MFMA
 }
 
 }  // namespace
@@ -398,16 +402,15 @@ int launch_linear_mfma_tiled(const uint8_t* x8, int64_t M, int64_t K, int64_t ld
     if (total > (1 << 30)) return W4A8_ERR_SHAPE;
     if (ldx8 >= (1 << 24)) return W4A8_ERR_SHAPE;               // 32-bit activation offsets inside a token block
     const dim3 grid((unsigned)((total + XCDS - 1) / XCDS * XCDS));
+    const LinearArgs a{x8, (int)M, ldx8, s_x, packed, scales, (int)N, n_tiles, C, cpg, NG, y, ldy, w_out, per_channel};
     bool launched = false;
-#define W4A8_CASE(MFV, KSV, TPV)                                                                                             \
-    if (mf == MFV && ks == KSV && tpw == TPV) {                                                                              \
-        launched = true;                                                                                                     \
-        if (ydt == W4A8_F32)                                                                                                 \
-            launch_one<float, MFV, KSV, TPV>(w_out, per_channel, grid, st, x8, (int)M, ldx8, s_x, packed, scales, (int)N, n_tiles, C, cpg, NG, y, \
-                                             ldy, grid_m, grid_n);                                                           \
-        else                                                                                                                 \
-            launch_one<uint16_t, MFV, KSV, TPV>(w_out, per_channel, grid, st, x8, (int)M, ldx8, s_x, packed, scales, (int)N, n_tiles, C, cpg, NG, \
-                                                y, ldy, grid_m, grid_n);                                                     \
+#define W4A8_CASE(MFV, KSV, TPV)                                              \
+    if (mf == MFV && ks == KSV && tpw == TPV) {                               \
+        launched = true;                                                      \
+        if (ydt == W4A8_F32)                                                  \
+            launch_one<float, MFV, KSV, TPV>(a, grid, grid_m, grid_n, st);    \
+        else                                                                  \
+            launch_one<uint16_t, MFV, KSV, TPV>(a, grid, grid_m, grid_n, st); \
     }
     W4A8_CASE(16, 1, 2) W4A8_CASE(16, 1, 1) W4A8_CASE(8, 1, 1) W4A8_CASE(8, 2, 1) W4A8_CASE(4, 1, 1)
     W4A8_CASE(4, 2, 1) W4A8_CASE(4, 4, 1)

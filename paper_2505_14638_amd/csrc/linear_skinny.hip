@@ -180,43 +180,41 @@ __global__ void __launch_bounds__(max_threads(MT * NT)) linear_skinny_kernel(
 }
 
 template <int MT, int NT, typename OutT>
-int launch_one(const float* w_out, int per_channel, int depth, const uint8_t* x8, int M, int64_t ldx8, const float* s_x, const uint8_t* packed, const float* scales,
-               int N, int C, int cpg, int NG, void* y, int64_t ldy, int waves, hipStream_t st) {
-    const int n_tiles = (N + 15) / 16;
-    const int grid = (n_tiles + NT - 1) / NT;
-    const int cpw = (C + waves - 1) / waves;
+int launch_one(const LinearArgs& a, int depth, int waves, hipStream_t st) {
+    const int grid = (a.n_tiles + NT - 1) / NT;
+    const int cpw = (a.C + waves - 1) / waves;
     const size_t lds = (size_t)waves * MT * NT * 4 * RED_STRIDE * sizeof(float);
     constexpr int DEEP = (MT * NT == 1) ? 4 : 2;                 // deeper ring while the registers allow it
-    if (w_out)
-        hipLaunchKernelGGL((linear_skinny_kernel<MT, NT, 2, OutT, true>), dim3(grid), dim3(waves * 64), lds, st, x8, M, ldx8,
-                           s_x, packed, scales, N, n_tiles, C, cpg, NG, static_cast<OutT*>(y), ldy, cpw, w_out, per_channel);
+#define W4A8_SKINNY(DEPTHV, TWOV)                                                                                        \
+    hipLaunchKernelGGL((linear_skinny_kernel<MT, NT, DEPTHV, OutT, TWOV>), dim3(grid), dim3(waves * 64), lds, st, a.x8, a.M, \
+                       a.ldx8, a.s_x, a.packed, a.scales, a.N, a.n_tiles, a.C, a.cpg, a.NG, static_cast<OutT*>(a.y), a.ldy,  \
+                       cpw, a.w_out, a.per_channel)
+    if (a.w_out)
+        W4A8_SKINNY(2, true);
     else if (depth == DEEP)
-        hipLaunchKernelGGL((linear_skinny_kernel<MT, NT, DEEP, OutT, false>), dim3(grid), dim3(waves * 64), lds, st, x8, M,
-                           ldx8, s_x, packed, scales, N, n_tiles, C, cpg, NG, static_cast<OutT*>(y), ldy, cpw, nullptr, 0);
+        W4A8_SKINNY(DEEP, false);
     else
-        hipLaunchKernelGGL((linear_skinny_kernel<MT, NT, 2, OutT, false>), dim3(grid), dim3(waves * 64), lds, st, x8, M, ldx8,
-                           s_x, packed, scales, N, n_tiles, C, cpg, NG, static_cast<OutT*>(y), ldy, cpw, nullptr, 0);
+        W4A8_SKINNY(2, false);
+#undef W4A8_SKINNY
     return launch_status();
 }
 
 template <int MT, typename OutT>
-int launch_nt(const float* w_out, int per_channel, int nt, int depth, const uint8_t* x8, int M, int64_t ldx8, const float* s_x, const uint8_t* packed,
-              const float* scales, int N, int C, int cpg, int NG, void* y, int64_t ldy, int waves, hipStream_t st) {
+int launch_nt(const LinearArgs& a, int nt, int depth, int waves, hipStream_t st) {
     switch (nt) {
-        case 1: return launch_one<MT, 1, OutT>(w_out, per_channel, depth, x8, M, ldx8, s_x, packed, scales, N, C, cpg, NG, y, ldy, waves, st);
-        case 2: return launch_one<MT, 2, OutT>(w_out, per_channel, depth, x8, M, ldx8, s_x, packed, scales, N, C, cpg, NG, y, ldy, waves, st);
-        case 4: return launch_one<MT, 4, OutT>(w_out, per_channel, depth, x8, M, ldx8, s_x, packed, scales, N, C, cpg, NG, y, ldy, waves, st);
+        case 1: return launch_one<MT, 1, OutT>(a, depth, waves, st);
+        case 2: return launch_one<MT, 2, OutT>(a, depth, waves, st);
+        case 4: return launch_one<MT, 4, OutT>(a, depth, waves, st);
     }
     return W4A8_ERR_SHAPE;
 }
 
 template <typename OutT>
-int launch_mt(const float* w_out, int per_channel, int mt, int nt, int depth, const uint8_t* x8, int M, int64_t ldx8, const float* s_x, const uint8_t* packed,
-              const float* scales, int N, int C, int cpg, int NG, void* y, int64_t ldy, int waves, hipStream_t st) {
+int launch_mt(const LinearArgs& a, int mt, int nt, int depth, int waves, hipStream_t st) {
     switch (mt) {
-        case 1: return launch_nt<1, OutT>(w_out, per_channel, nt, depth, x8, M, ldx8, s_x, packed, scales, N, C, cpg, NG, y, ldy, waves, st);
-        case 2: return launch_nt<2, OutT>(w_out, per_channel, nt, depth, x8, M, ldx8, s_x, packed, scales, N, C, cpg, NG, y, ldy, waves, st);
-        default: return launch_nt<4, OutT>(w_out, per_channel, nt, depth, x8, M, ldx8, s_x, packed, scales, N, C, cpg, NG, y, ldy, waves, st);
+        case 1: return launch_nt<1, OutT>(a, nt, depth, waves, st);
+        case 2: return launch_nt<2, OutT>(a, nt, depth, waves, st);
+        default: return launch_nt<4, OutT>(a, nt, depth, waves, st);
     }
 }
 
@@ -246,9 +244,9 @@ int launch_linear_skinny(const uint8_t* x8, int64_t M, int64_t K, int64_t ldx8, 
     if (waves < 1 || waves > 16 || waves * mt * nt > 64 || waves * 64 > max_threads(mt * nt)) return W4A8_ERR_SHAPE;
     if (depth == 0) depth = 2;                                   // deeper rings cost occupancy and measured no faster
     if (depth != 2 && depth != 4) return W4A8_ERR_SHAPE;
-    if (ydt == W4A8_F32)
-        return launch_mt<float>(w_out, per_channel, mt, nt, depth, x8, (int)M, ldx8, s_x, packed, scales, (int)N, C, cpg, NG, y, ldy, waves, st);
-    return launch_mt<uint16_t>(w_out, per_channel, mt, nt, depth, x8, (int)M, ldx8, s_x, packed, scales, (int)N, C, cpg, NG, y, ldy, waves, st);
+    const LinearArgs a{x8, (int)M, ldx8, s_x, packed, scales, (int)N, n_tiles, C, cpg, NG, y, ldy, w_out, per_channel};
+    if (ydt == W4A8_F32) return launch_mt<float>(a, mt, nt, depth, waves, st);
+    return launch_mt<uint16_t>(a, mt, nt, depth, waves, st);
 }
 
 }  // namespace w4a8

@@ -11,6 +11,23 @@ namespace w4a8 {
 inline int hip_status(hipError_t e) { return e == hipSuccess ? W4A8_OK : W4A8_ERR_HIP; }
 inline int launch_status() { return hip_status(hipGetLastError()); }
 
+// What the launchers of the tiled-layout linear kernels pass down to a launch: the operands of w4a8_linear after
+// validation.  w_out != nullptr selects the two-level mode (scales = FP8-domain group scales, output scaled by
+// s_x * w_out[n], or s_x * w_out[0] when per_channel is 0).
+struct LinearArgs {
+    const uint8_t* x8;
+    int M;
+    int64_t ldx8;
+    const float* s_x;
+    const uint8_t* packed;
+    const float* scales;
+    int N, n_tiles, C, cpg, NG;      // channels, 16-row bands, 128-deep chunks, chunks per group, groups per row
+    void* y;
+    int64_t ldy;
+    const float* w_out;
+    int per_channel;
+};
+
 int launch_quantize_act(const void* x, w4a8_dtype dt, int64_t M, int64_t K, int64_t ldx, const float* scale,
                         uint8_t* x8, int64_t ldx8, hipStream_t st);
 int launch_pack_weights(const void* src, w4a8_src kind, const float* src_scales, int64_t N, int64_t K, int32_t G,
