@@ -30,8 +30,16 @@ dequant_codes_to_e4m3        Eq. 10 / Eq. 14 with zero-point 0 and the scale
 linear_ref                   Eq. 10, Eq. 4 and Eq. 11: Y = X_hat . W_hat^T
 linear_ref_paper_literal     Eq. 6-11 read literally: the product code*scale is
                              itself rounded onto the E4M3 grid before the matmul
-pack_* / unpack_*            storage formats of the C-ABI boundary (the tiled one keeps
-                             sign-magnitude nibbles and marks groups that hold -8)
+asym_quantize_weights        Eq. 1 in its asymmetric form with q_min = 0, q_max = 15
+                             (Sec. 2.1; the form Eq. 8-9 give it)
+dequant_asym_to_e4m3         Eq. 10 / Eq. 14: the integer (code - zero_point) as an
+                             E4M3 byte
+linear_ref_asym              Eq. 14, Eq. 4, Eq. 11 with unsigned codes and
+                             per-group zero-points
+pack_* / unpack_* / tile_*   storage formats of the C-ABI boundary (the tiled one keeps
+                             sign-magnitude nibbles and marks groups that hold -8; the
+                             asymmetric one plain unsigned nibbles and 80-byte records
+                             of scales and zero-points)
 silu_mul_ref, block_ref,     the decoder-block linear stack workload (static scales
 calibrate_block_scales       by Eq. 13 on the oracle's own intermediates)
 
@@ -181,6 +189,36 @@ def rtn_quantize_weights(w, group_size: int):
     return q, s
 
 
+def asym_quantize_weights(w, group_size: int):
+    """Asymmetric round-to-nearest to unsigned 4-bit codes, Eq. 1 with q_min = 0 and q_max = 15 (the storage
+    format the paper names in Sec. 2.1 and uses in Eq. 8-9), per (row, group):
+
+        lo = min(min W, 0), hi = max(max W, 0)          the range always contains zero, so that the zero-point
+                                                        is itself an unsigned 4-bit integer (a reading: Eq. 1
+                                                        leaves the zero-point of a one-signed group outside 0..15)
+        s  = (hi - lo) / 15                             (1 for an all-zero group)
+        z  = round(-lo / s)                             in 0..15
+        u  = clamp(round(W / s + z), 0, 15)             the clamp only ever acts on a 15.5 that rounds up to 16
+
+    Every operation is float32 (division, then addition, then round half to even), so that the integer
+    decisions match a float32 implementation.  Returns (codes uint8 [N, K], scales float32 [N, K/G],
+    zero-points uint8 [N, K/G])."""
+    w = np.asarray(w, dtype=np.float32)
+    n, k = w.shape
+    assert k % group_size == 0
+    wg = w.reshape(n, k // group_size, group_size)
+    lo = np.minimum(np.min(wg, axis=2), np.float32(0.0)).astype(np.float32)
+    hi = np.maximum(np.max(wg, axis=2), np.float32(0.0)).astype(np.float32)
+    span = (hi - lo).astype(np.float32)
+    s = (span / np.float32(15.0)).astype(np.float32)
+    s = np.where(span == 0, np.float32(1.0), s).astype(np.float32)
+    z = np.clip(np.rint(((-lo) / s).astype(np.float32)), 0, 15).astype(np.float32)
+    t = (wg / s[:, :, None]).astype(np.float32)
+    t = (t + z[:, :, None]).astype(np.float32)
+    u = np.clip(np.rint(t), 0, 15).astype(np.uint8).reshape(n, k)
+    return u, s, z.astype(np.uint8)
+
+
 # --------------------------------------------------------------------------------------
 # Storage formats of the boundary
 # --------------------------------------------------------------------------------------
@@ -314,6 +352,59 @@ def untile_scales(buf, n: int, ng: int, with_marks: bool = False):
     return np.abs(raw)
 
 
+ASYM_RECORD_BYTES = 80     # per (16-row band, group): 16 float32 scales, then 16 zero-point bytes
+
+
+def pack_tiled_asym(u) -> np.ndarray:
+    """Tiled storage of unsigned codes 0..15: the byte and nibble positions of `pack_tiled`, the nibble being the
+    code itself; rows are padded with code 0 up to a multiple of 16."""
+    u = np.asarray(u, dtype=np.uint8)
+    n, k = u.shape
+    assert k % TILE_K == 0 and int(u.max(initial=0)) <= 15
+    n_pad = -(-n // TILE_N) * TILE_N
+    p = np.zeros((n_pad, k), dtype=np.uint8)
+    p[:n] = u
+    p = p.reshape(n_pad // TILE_N, TILE_N, k // TILE_K, 4, 4, 2, 4).transpose(0, 2, 3, 1, 4, 6, 5)   # t c kq i d b h
+    return np.ascontiguousarray(p[..., 0] | (p[..., 1] << 4)).ravel()
+
+
+def unpack_tiled_asym(buf, n: int, k: int) -> np.ndarray:
+    n_pad = -(-n // TILE_N) * TILE_N
+    b = np.asarray(buf, dtype=np.uint8).reshape(n_pad // TILE_N, k // TILE_K, 4, TILE_N, 4, 4)   # t c kq i d b
+    u = np.stack([b & 0xF, b >> 4], axis=-1)                                                     # ... h
+    return np.ascontiguousarray(u.transpose(0, 3, 1, 2, 4, 6, 5).reshape(n_pad, k)[:n])          # t i c kq d h b
+
+
+def tile_params_asym(s, z) -> np.ndarray:
+    """Scales and zero-points of the asymmetric format, as bytes: one 80-byte record per (16-row band t, group g)
+    at byte (t * (K/G) + g) * 80: the 16 float32 scales of rows 16t .. 16t+15 (little endian), then their 16
+    zero-point bytes.  Padding rows get scale 0 and zero-point 0."""
+    s = np.asarray(s, dtype=np.float32)
+    z = np.asarray(z, dtype=np.uint8)
+    n, ng = s.shape
+    assert z.shape == (n, ng) and int(z.max(initial=0)) <= 15
+    n_pad = -(-n // TILE_N) * TILE_N
+    sp = np.zeros((n_pad, ng), dtype="<f4")
+    zp = np.zeros((n_pad, ng), dtype=np.uint8)
+    sp[:n] = s
+    zp[:n] = z
+    rec = np.zeros((n_pad // TILE_N, ng, ASYM_RECORD_BYTES), dtype=np.uint8)
+    rec[:, :, :64] = np.ascontiguousarray(sp.reshape(n_pad // TILE_N, TILE_N, ng).transpose(0, 2, 1)).view(np.uint8).reshape(
+        n_pad // TILE_N, ng, 64)
+    rec[:, :, 64:] = zp.reshape(n_pad // TILE_N, TILE_N, ng).transpose(0, 2, 1)
+    return rec.ravel()
+
+
+def untile_params_asym(buf, n: int, ng: int):
+    """Inverse of tile_params_asym: (scales float32 [n, ng], zero-points uint8 [n, ng])."""
+    n_pad = -(-n // TILE_N) * TILE_N
+    rec = np.asarray(buf, dtype=np.uint8).reshape(n_pad // TILE_N, ng, ASYM_RECORD_BYTES)
+    sp = np.ascontiguousarray(rec[:, :, :64]).view("<f4").reshape(n_pad // TILE_N, ng, TILE_N)
+    s = np.ascontiguousarray(sp.transpose(0, 2, 1)).reshape(n_pad, ng)[:n].astype(np.float32)
+    z = np.ascontiguousarray(rec[:, :, 64:].transpose(0, 2, 1)).reshape(n_pad, ng)[:n]
+    return s, z
+
+
 # --------------------------------------------------------------------------------------
 # INT4 -> FP8 dequantization (Eq. 10 / Eq. 14, zero-point 0)
 # --------------------------------------------------------------------------------------
@@ -363,6 +454,29 @@ def linear_ref_paper_literal(x8, s_x, q, s8, s_w_out, group_size: int):
     w8 = e4m3_encode(prod.reshape(n, k))
     y = e4m3_decode(x8) @ e4m3_decode(w8).T
     return float(np.float32(s_x)) * y * np.asarray(s_w_out, dtype=np.float64)[None, :], w8
+
+
+def _codes_minus_zero_points(u, z, group_size: int) -> np.ndarray:
+    """The integers W4 - z of Eq. 14, [N, K] int16: zero-point z[n, g] belongs to columns g*G .. (g+1)*G - 1."""
+    u = np.asarray(u, dtype=np.uint8).astype(np.int16)
+    z = np.asarray(z, dtype=np.uint8).astype(np.int16)
+    n, k = u.shape
+    assert z.shape == (n, k // group_size)
+    return (u.reshape(n, k // group_size, group_size) - z[:, :, None]).reshape(n, k)
+
+
+def dequant_asym_to_e4m3(u, z, group_size: int) -> np.ndarray:
+    """The FP8 operand byte of each weight in the asymmetric format: nearest_Z of the integer code - zero_point
+    (Eq. 10 / Eq. 14 with the group scale taken out of the group's sum, as in linear_ref).  The integers lie in
+    [-15, 15] and have at most four significant bits, so the rounding is exact."""
+    return e4m3_encode(_codes_minus_zero_points(u, z, group_size).astype(np.float32))
+
+
+def linear_ref_asym(x8, s_x, u, z, s_w, group_size: int):
+    """Y[m,n] = s_x * sum_g s_w[n,g] * sum_{k in g} dec(x8[m,k]) * (u[n,k] - z[n,g]) in float64: Eq. 14 for the
+    weights (unsigned 4-bit codes, per-group scale and zero-point), Eq. 4 for the activations, Eq. 11 for the
+    output.  Returns (Y, A) like linear_ref."""
+    return linear_ref(x8, s_x, _codes_minus_zero_points(u, z, group_size), s_w, group_size)
 
 
 def within_tolerance(y, ref, a, rel: float = 2e-3, floor: float = 2.0 ** -6):
