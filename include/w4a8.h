@@ -19,6 +19,8 @@
  *     App. A.1); group g of row n covers k in [g*group_size, (g+1)*group_size).
  *   - the FP8 format is E4M3 with range +-448 (Sec. 2.2, Sec. 4.1): bias 7, no infinities,
  *     S.1111.111 is NaN.  The INT4 codes are signed, in [-8, 7]; group scales are non-negative.
+ *     The *_asym entry points take the paper's own storage format instead (Sec. 2.1, Eq. 8-9): unsigned
+ *     codes in [0, 15] with a per-group zero-point.
  */
 #ifndef W4A8_H
 #define W4A8_H
@@ -161,6 +163,39 @@ int w4a8_linear_two_level(const uint8_t* x8_dev, int64_t M, int64_t K, int64_t l
                           int64_t ldy, void* stream);
 int w4a8_dequant_weights_two_level(const uint8_t* packed_dev, const float* w_scales8_dev, int64_t N, int64_t K,
                                    int32_t group_size, uint8_t* w8_dev, void* stream);
+
+/*
+ * The asymmetric format (Eq. 1 with q_min = 0, q_max = 15; Eq. 8-9; dequantization by Eq. 14): unsigned 4-bit codes u
+ * with a scale s[n,g] and a zero-point z[n,g] per (row, group), z an integer in [0, 15] like the codes;
+ *   Y[m,n] = cast( s_x * sum_g s[n,g] * sum_{k in g} val(x8[m,k]) * (u[n,k] - z[n,g]) ).
+ * The integers u - z lie in [-15, 15] and are exact in E4M3: the kernels expand each nibble to the E4M3 byte of
+ * u - z (per lane a 16-entry table built from the zero-point), multiply on the FP8 matrix units and apply the group
+ * scale to each group's partial sum in fp32, exactly as w4a8_linear does with signed codes.
+ * Storage (tiled only; K % 128 == 0, group_size % 128 == 0; rows padded to Np = ceil(N/16)*16 with code 0, scale 0,
+ * zero-point 0):
+ *   packed  the byte and nibble positions of W4A8_LAYOUT_TILED, the nibble being the code u itself;
+ *   params  w4a8_asym_params_bytes() bytes, 16-byte aligned: one 80-byte record per (16-row band t, group g) at byte
+ *           (t * (K/group_size) + g) * 80: the 16 float32 scales of rows 16t .. 16t+15, then their 16 zero-point bytes.
+ * w4a8_pack_weights_asym writes both.  src_kind W4A8_SRC_F32_RTN: src = W float32 [N, K]; per (row, group)
+ *   lo = min(min W, 0), hi = max(max W, 0), s = (hi - lo) / 15 (1 for an all-zero group), z = round(-lo / s),
+ *   u = clamp(round(W / s + z), 0, 15), every step in float32, rounding half to even
+ * (the range is made to contain zero so that z fits the 4 bits).  W4A8_SRC_I8_CODES: src = bytes [N, K] holding the
+ * codes (only the low nibble is kept), src_scales_dev float32 [N, K/group_size], src_zeros_dev bytes
+ * [N, K/group_size] (values above 15 are stored as 15): a pure re-layout for codes from an offline calibrator
+ * (Alg. 1).  src_scales_dev and src_zeros_dev are read only for W4A8_SRC_I8_CODES.
+ * w4a8_linear_asym: arguments as in w4a8_linear (TILED alignment rules; params_dev in place of the scales), same
+ * kernel choice.  w4a8_dequant_weights_asym writes the bytes nearest_E4M3(u - z) row-major [N, K] with the device
+ * routine the kernels use (test hook).
+ */
+size_t w4a8_asym_params_bytes(int64_t N, int64_t K, int32_t group_size);
+int w4a8_pack_weights_asym(const void* src_dev, w4a8_src src_kind, const float* src_scales_dev,
+                           const uint8_t* src_zeros_dev, int64_t N, int64_t K, int32_t group_size, uint8_t* packed_dev,
+                           void* params_dev, void* stream);
+int w4a8_linear_asym(const uint8_t* x8_dev, int64_t M, int64_t K, int64_t ldx8, const float* x_scale_dev,
+                     const uint8_t* packed_dev, const void* params_dev, int64_t N, int32_t group_size, void* y_dev,
+                     w4a8_dtype y_dtype, int64_t ldy, void* stream);
+int w4a8_dequant_weights_asym(const uint8_t* packed_dev, const void* params_dev, int64_t N, int64_t K, int32_t group_size,
+                              uint8_t* w8_dev, void* stream);
 
 /*
  * Elementwise step of the decoder-block linear stack (all linear layers of a block are quantized, Sec. 4.1;

@@ -35,6 +35,11 @@ SIGNATURES = {
     "w4a8_linear_two_level": (_c_i32, [_c_vp, _c_i64, _c_i64, _c_i64, _c_vp, _c_vp, _c_vp, _c_vp, _c_i32, _c_i64, _c_i32,
                                        _c_vp, _c_i32, _c_i64, _c_vp]),
     "w4a8_dequant_weights_two_level": (_c_i32, [_c_vp, _c_vp, _c_i64, _c_i64, _c_i32, _c_vp, _c_vp]),
+    "w4a8_asym_params_bytes": (_c_sz, [_c_i64, _c_i64, _c_i32]),
+    "w4a8_pack_weights_asym": (_c_i32, [_c_vp, _c_i32, _c_vp, _c_vp, _c_i64, _c_i64, _c_i32, _c_vp, _c_vp, _c_vp]),
+    "w4a8_linear_asym": (_c_i32, [_c_vp, _c_i64, _c_i64, _c_i64, _c_vp, _c_vp, _c_vp, _c_i64, _c_i32, _c_vp, _c_i32,
+                                  _c_i64, _c_vp]),
+    "w4a8_dequant_weights_asym": (_c_i32, [_c_vp, _c_vp, _c_i64, _c_i64, _c_i32, _c_vp, _c_vp]),
     "w4a8_silu_mul": (_c_i32, [_c_vp, _c_i64, _c_i64, _c_i64, _c_vp, _c_i64, _c_vp]),
     "w4a8_probe_stream_read": (_c_i32, [_c_vp, _c_sz, _c_vp, _c_vp]),
     "w4a8_probe_mfma_e4m3": (_c_i32, [_c_i32, _c_vp, _c_vp]),
@@ -167,6 +172,49 @@ def dequant_weights_two_level(packed: torch.Tensor, w_scales8: torch.Tensor, n: 
     w8 = torch.empty((n, k), dtype=torch.uint8, device=packed.device)
     _check(lib().w4a8_dequant_weights_two_level(packed.data_ptr(), w_scales8.data_ptr(), n, k, group_size, w8.data_ptr(),
                                                 _stream()), "w4a8_dequant_weights_two_level")
+    return w8
+
+
+def asym_params_bytes(n: int, k: int, group_size: int) -> int:
+    return lib().w4a8_asym_params_bytes(n, k, group_size)
+
+
+def pack_weights_asym(src: torch.Tensor, group_size: int, src_scales: torch.Tensor | None = None,
+                      src_zeros: torch.Tensor | None = None):
+    """Asymmetric format.  src: float32 W [N, K] (quantized inside the library) or uint8 codes [N, K] with src_scales
+    float32 and src_zeros uint8, both [N, K/group_size].  Returns (packed uint8 1-D, params uint8 1-D)."""
+    n, k = src.shape
+    assert src.is_contiguous()
+    kind = SRC_F32_RTN if src.dtype == torch.float32 else SRC_I8_CODES
+    nbytes, nparams = packed_bytes(n, k, LAYOUT_TILED), asym_params_bytes(n, k, group_size)
+    packed = torch.empty(max(nbytes, 1), dtype=torch.uint8, device=src.device)
+    params = torch.empty(max(nparams, 16), dtype=torch.uint8, device=src.device)
+    sp = zp = 0
+    if kind == SRC_I8_CODES:
+        assert src.dtype == torch.uint8 and src_scales is not None and src_zeros is not None
+        assert src_scales.dtype == torch.float32 and src_zeros.dtype == torch.uint8
+        assert src_scales.is_contiguous() and src_zeros.is_contiguous()
+        sp, zp = src_scales.data_ptr(), src_zeros.data_ptr()
+    _check(lib().w4a8_pack_weights_asym(src.data_ptr(), kind, sp, zp, n, k, group_size, packed.data_ptr(),
+                                        params.data_ptr(), _stream()), "w4a8_pack_weights_asym")
+    return packed[:nbytes], params[:nparams]
+
+
+def linear_asym(x8, x_scale, packed, params, n, group_size, out=None, out_dtype=torch.bfloat16):
+    m, k = x8.shape
+    assert x8.dtype == torch.uint8 and x8.stride(1) == 1
+    if out is None:
+        out = torch.empty((m, n), dtype=out_dtype, device=x8.device)
+    _check(lib().w4a8_linear_asym(x8.data_ptr(), m, k, x8.stride(0) if m > 1 else max(k, x8.stride(0)), x_scale.data_ptr(),
+                                  packed.data_ptr(), params.data_ptr(), n, group_size, out.data_ptr(), _dtype_code(out),
+                                  out.stride(0) if m > 1 else max(n, out.stride(0)), _stream()), "w4a8_linear_asym")
+    return out
+
+
+def dequant_weights_asym(packed: torch.Tensor, params: torch.Tensor, n: int, k: int, group_size: int) -> torch.Tensor:
+    w8 = torch.empty((n, k), dtype=torch.uint8, device=packed.device)
+    _check(lib().w4a8_dequant_weights_asym(packed.data_ptr(), params.data_ptr(), n, k, group_size, w8.data_ptr(),
+                                           _stream()), "w4a8_dequant_weights_asym")
     return w8
 
 

@@ -100,9 +100,9 @@ int w4a8_linear(const uint8_t* x8_dev, int64_t M, int64_t K, int64_t ldx8, const
     const bool deep_narrow = K >= 8192 && N <= 8192;
     if (M <= 32 || (M <= 64 && deep_narrow))
         return launch_linear_skinny(x8_dev, M, K, ldx8, x_scale_dev, packed_dev, w_scales_dev, N, group_size, y_dev,
-                                    y_dtype, ldy, 0, 0, 0, nullptr, 0, st);
+                                    y_dtype, ldy, 0, 0, 0, nullptr, 0, MODE_CODE_EXACT, st);
     return launch_linear_mfma_tiled(x8_dev, M, K, ldx8, x_scale_dev, packed_dev, w_scales_dev, N, group_size, y_dev,
-                                    y_dtype, ldy, 0, 0, 0, nullptr, 0, st);
+                                    y_dtype, ldy, 0, 0, 0, nullptr, 0, MODE_CODE_EXACT, st);
 }
 
 int w4a8_linear_two_level(const uint8_t* x8_dev, int64_t M, int64_t K, int64_t ldx8, const float* x_scale_dev,
@@ -120,9 +120,9 @@ int w4a8_linear_two_level(const uint8_t* x8_dev, int64_t M, int64_t K, int64_t l
     const bool deep_narrow = K >= 8192 && N <= 8192;             // same kernel choice as w4a8_linear
     if (M <= 32 || (M <= 64 && deep_narrow))
         return launch_linear_skinny(x8_dev, M, K, ldx8, x_scale_dev, packed_dev, w_scales8_dev, N, group_size, y_dev,
-                                    y_dtype, ldy, 0, 0, 0, w_out_scales_dev, per_channel, st);
+                                    y_dtype, ldy, 0, 0, 0, w_out_scales_dev, per_channel, MODE_TWO_LEVEL, st);
     return launch_linear_mfma_tiled(x8_dev, M, K, ldx8, x_scale_dev, packed_dev, w_scales8_dev, N, group_size, y_dev,
-                                    y_dtype, ldy, 0, 0, 0, w_out_scales_dev, per_channel, st);
+                                    y_dtype, ldy, 0, 0, 0, w_out_scales_dev, per_channel, MODE_TWO_LEVEL, st);
 }
 
 int w4a8_linear_variant(const uint8_t* x8_dev, int64_t M, int64_t K, int64_t ldx8, const float* x_scale_dev,
@@ -137,11 +137,11 @@ int w4a8_linear_variant(const uint8_t* x8_dev, int64_t M, int64_t K, int64_t ldx
     if (path == 0) {
         if (M > 64 || param0 < 0 || param1 < 0 || (param1 & 0xFF) > 16) return W4A8_ERR_SHAPE;
         return launch_linear_skinny(x8_dev, M, K, ldx8, x_scale_dev, packed_dev, w_scales_dev, N, group_size, y_dev,
-                                    y_dtype, ldy, param0, param1 & 0xFF, param1 >> 8, nullptr, 0, st);
+                                    y_dtype, ldy, param0, param1 & 0xFF, param1 >> 8, nullptr, 0, MODE_CODE_EXACT, st);
     }
     if (path == 1)
         return launch_linear_mfma_tiled(x8_dev, M, K, ldx8, x_scale_dev, packed_dev, w_scales_dev, N, group_size, y_dev,
-                                        y_dtype, ldy, param0, param1 & 0xFF, param1 >> 8, nullptr, 0, st);
+                                        y_dtype, ldy, param0, param1 & 0xFF, param1 >> 8, nullptr, 0, MODE_CODE_EXACT, st);
     return W4A8_ERR_SHAPE;
 }
 
@@ -150,7 +150,7 @@ int w4a8_dequant_weights(const uint8_t* packed_dev, int64_t N, int64_t K, w4a8_l
     if (int e = check_nk(N, K, layout)) return e;
     if (!packed_dev || !w8_dev) return W4A8_ERR_NULL;
     if (layout == W4A8_LAYOUT_TILED && (!aligned16(packed_dev) || !aligned16(w8_dev))) return W4A8_ERR_ALIGN;
-    return launch_dequant_weights(packed_dev, N, K, layout, w8_dev, nullptr, 0, static_cast<hipStream_t>(stream));
+    return launch_dequant_weights(packed_dev, N, K, layout, w8_dev, nullptr, nullptr, 0, static_cast<hipStream_t>(stream));
 }
 
 int w4a8_dequant_weights_two_level(const uint8_t* packed_dev, const float* w_scales8_dev, int64_t N, int64_t K,
@@ -158,8 +158,53 @@ int w4a8_dequant_weights_two_level(const uint8_t* packed_dev, const float* w_sca
     if (int e = check_weight_shape(N, K, group_size, W4A8_LAYOUT_TILED)) return e;
     if (!packed_dev || !w_scales8_dev || !w8_dev) return W4A8_ERR_NULL;
     if (!aligned16(packed_dev) || !aligned16(w8_dev) || reinterpret_cast<uintptr_t>(w_scales8_dev) % 4) return W4A8_ERR_ALIGN;
-    return launch_dequant_weights(packed_dev, N, K, W4A8_LAYOUT_TILED, w8_dev, w_scales8_dev, group_size,
+    return launch_dequant_weights(packed_dev, N, K, W4A8_LAYOUT_TILED, w8_dev, w_scales8_dev, nullptr, group_size,
                                   static_cast<hipStream_t>(stream));
+}
+
+size_t w4a8_asym_params_bytes(int64_t N, int64_t K, int32_t group_size) {
+    if (check_weight_shape(N, K, group_size, W4A8_LAYOUT_TILED) != W4A8_OK) return 0;
+    return (size_t)(((N + 15) / 16) * (K / group_size) * 80);
+}
+
+int w4a8_pack_weights_asym(const void* src_dev, w4a8_src src_kind, const float* src_scales_dev,
+                           const uint8_t* src_zeros_dev, int64_t N, int64_t K, int32_t group_size, uint8_t* packed_dev,
+                           void* params_dev, void* stream) {
+    if (src_kind != W4A8_SRC_F32_RTN && src_kind != W4A8_SRC_I8_CODES) return W4A8_ERR_DTYPE;
+    if (int e = check_weight_shape(N, K, group_size, W4A8_LAYOUT_TILED)) return e;
+    if (!src_dev || !packed_dev || !params_dev) return W4A8_ERR_NULL;
+    if (src_kind == W4A8_SRC_I8_CODES && (!src_scales_dev || !src_zeros_dev)) return W4A8_ERR_NULL;
+    if (!aligned16(params_dev) || (src_kind == W4A8_SRC_F32_RTN && reinterpret_cast<uintptr_t>(src_dev) % 4) ||
+        (src_kind == W4A8_SRC_I8_CODES && reinterpret_cast<uintptr_t>(src_scales_dev) % 4))
+        return W4A8_ERR_ALIGN;
+    return launch_pack_weights_asym(src_dev, src_kind, src_scales_dev, src_zeros_dev, N, K, group_size, packed_dev,
+                                    static_cast<uint8_t*>(params_dev), static_cast<hipStream_t>(stream));
+}
+
+int w4a8_linear_asym(const uint8_t* x8_dev, int64_t M, int64_t K, int64_t ldx8, const float* x_scale_dev,
+                     const uint8_t* packed_dev, const void* params_dev, int64_t N, int32_t group_size, void* y_dev,
+                     w4a8_dtype y_dtype, int64_t ldy, void* stream) {
+    const float* params = static_cast<const float*>(params_dev);
+    if (int e = check_linear(x8_dev, M, K, ldx8, x_scale_dev, packed_dev, params, N, group_size, W4A8_LAYOUT_TILED, y_dev,
+                             y_dtype, ldy))
+        return e;
+    if (M == 0) return W4A8_OK;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const bool deep_narrow = K >= 8192 && N <= 8192;             // same kernel choice as w4a8_linear
+    if (M <= 32 || (M <= 64 && deep_narrow))
+        return launch_linear_skinny(x8_dev, M, K, ldx8, x_scale_dev, packed_dev, params, N, group_size, y_dev, y_dtype, ldy,
+                                    0, 0, 0, nullptr, 0, MODE_ASYM, st);
+    return launch_linear_mfma_tiled(x8_dev, M, K, ldx8, x_scale_dev, packed_dev, params, N, group_size, y_dev, y_dtype, ldy,
+                                    0, 0, 0, nullptr, 0, MODE_ASYM, st);
+}
+
+int w4a8_dequant_weights_asym(const uint8_t* packed_dev, const void* params_dev, int64_t N, int64_t K, int32_t group_size,
+                              uint8_t* w8_dev, void* stream) {
+    if (int e = check_weight_shape(N, K, group_size, W4A8_LAYOUT_TILED)) return e;
+    if (!packed_dev || !params_dev || !w8_dev) return W4A8_ERR_NULL;
+    if (!aligned16(packed_dev) || !aligned16(w8_dev) || !aligned16(params_dev)) return W4A8_ERR_ALIGN;
+    return launch_dequant_weights(packed_dev, N, K, W4A8_LAYOUT_TILED, w8_dev, nullptr,
+                                  static_cast<const uint8_t*>(params_dev), group_size, static_cast<hipStream_t>(stream));
 }
 
 int w4a8_silu_mul(const void* gu_dev, int64_t M, int64_t F, int64_t ldgu, void* h_dev, int64_t ldh, void* stream) {

@@ -38,14 +38,18 @@ constexpr int WAVES = 8;
 
 template <int A, int B> struct MaxOf { static constexpr int value = A > B ? A : B; };
 
-// TWO = false: code-exact mode (group scales applied to the partial sums in fp32).  TWO = true: two-level mode, the
-// weight operand is nearest_E4M3(code * s8[n,g]) and the sum over all of K stays in the MFMA accumulator; the output
-// is scaled by s_x * w_out[n] (w_out[0] when per_channel is 0).
-template <typename OutT, int MF, int KS, int TPW, bool TWO>
+// MODE_CODE_EXACT: signed codes, group scales applied to the partial sums in fp32.  MODE_TWO_LEVEL: the weight operand
+// is nearest_E4M3(code * s8[n,g]) and the sum over all of K stays in the MFMA accumulator; the output is scaled by
+// s_x * w_out[n] (w_out[0] when per_channel is 0).  MODE_ASYM: unsigned codes with per-group zero-points, the weight
+// operand is the integer code - zero_point, group scales as in the code-exact mode; `scales` then points at the
+// 80-byte records of scales and zero-points.
+template <typename OutT, int MF, int KS, int TPW, int MODE>
 __global__ void __launch_bounds__(512, (KS * MF > 16 || MF * TPW > 16) ? 2 : 4) linear_mfma_kernel(
     const uint8_t* __restrict__ x8, int M, int64_t ldx8, const float* __restrict__ s_x,
     const uint8_t* __restrict__ packed, const float* __restrict__ scales, int N, int n_tiles, int C, int cpg, int NG,
     OutT* __restrict__ y, int64_t ldy, int grid_m, int grid_n, const float* __restrict__ w_out, int per_channel) {
+    constexpr bool TWO = MODE == MODE_TWO_LEVEL, ASYM = MODE == MODE_ASYM;
+    constexpr int REC = ASYM ? ASYM_RECORD_BYTES : 64;           // bytes of scales (and zero-points) per band and group
     constexpr int NB = WAVES / KS;                               // wavefronts per K-split group, TPW weight bands each
     constexpr int BN = 16 * NB * TPW, BM = 16 * MF;
     constexpr int PAGES = KS * MF * 2;                           // 1 KiB pages of activations per pass
@@ -53,7 +57,8 @@ __global__ void __launch_bounds__(512, (KS * MF > 16 || MF * TPW > 16) ? 2 : 4) 
     static_assert(PAGES % WAVES == 0, "activation pages must divide evenly among the wavefronts");
     constexpr int RAW_OFF = 2 * STAGE_BYTES;                     // per wavefront and band: 1 KiB of raw nibbles (one tile)
     constexpr int SC_OFF = RAW_OFF + WAVES * TPW * 1024;         // per wavefront and band: 256 B, 16 scales x 4 copies
-    constexpr int LOOP_BYTES = SC_OFF + WAVES * TPW * 256;
+    constexpr int ZP_OFF = SC_OFF + WAVES * TPW * 256;           // asymmetric format: per lane the dword that holds its zero-point
+    constexpr int LOOP_BYTES = ZP_OFF + (ASYM ? WAVES * TPW * 256 : 0);
     constexpr int RED_BYTES = (KS - 1) * NB * TPW * MF * 4 * 64 * 4;   // partial sums of groups 1 .. KS-1
     constexpr int RS = BN + 16 / sizeof(OutT);                   // epilogue row stride: rows stay 16-byte aligned
     constexpr int SLAB16_BYTES = 16 * RS * (int)sizeof(OutT);    // one 16-token slab of the workgroup's output
@@ -86,10 +91,10 @@ __global__ void __launch_bounds__(512, (KS * MF > 16 || MF * TPW > 16) ? 2 : 4) 
     for (int j = 0; j < TPW; ++j) {
         const int t = min((bn * NB + band) * TPW + j, n_tiles - 1);   // bands past the end reload the last one; not stored
         wbase[j] = packed + (int64_t)t * C * 1024;
-        sbase[j] = reinterpret_cast<const uint8_t*>(scales) + (int64_t)t * NG * 64;
+        sbase[j] = reinterpret_cast<const uint8_t*>(scales) + (int64_t)t * NG * REC;
     }
     const uint8_t* xrow0 = x8 + (int64_t)m0 * ldx8;              // + c * 128 + xvoff
-    const uint32_t woff = lane * 16, soff = i * 4;
+    const uint32_t woff = lane * 16, soff = i * 4, zoff = 64 + (i >> 2) * 4;   // zoff: the dword with channel i's zero-point
     // Activation block in LDS: K-split group kg, 16-token block f = 2 KiB = two 1 KiB pages of 8 rows x 128 bytes;
     // 16-byte segment sg (0..7) of row r (0..15) sits in page r / 8 at slot (r % 8) * 8 + (sg ^ sw(r)) with
     // sw(r) = (r % 8) ^ (r / 8).  One copy instruction fills one page from eight whole 128-byte row segments of global
@@ -113,6 +118,8 @@ __global__ void __launch_bounds__(512, (KS * MF > 16 || MF * TPW > 16) ? 2 : 4) 
     const uint32_t lds_raw = lds0 + RAW_OFF + (uint32_t)wave * (TPW * 1024), lds_sc = lds0 + SC_OFF + (uint32_t)wave * (TPW * 256);
     const uint8_t* my_raw = lds + RAW_OFF + wave * (TPW * 1024) + lane * 16;      // + j * 1024
     const uint8_t* my_sc = lds + SC_OFF + wave * (TPW * 256) + lane * 4;          // + j * 256
+    const uint32_t lds_zp = lds0 + ZP_OFF + (uint32_t)wave * (TPW * 256);
+    const uint8_t* my_zp = lds + ZP_OFF + wave * (TPW * 256) + lane * 4;          // + j * 256
 
     const int passes = (C + KS - 1) / KS;
     // activations of pass `ps` into stage `buf`; chunks past the end of K reload the last chunk (never multiplied)
@@ -130,7 +137,8 @@ __global__ void __launch_bounds__(512, (KS * MF > 16 || MF * TPW > 16) ? 2 : 4) 
 #pragma unroll
         for (int j = 0; j < TPW; ++j) {
             lds_dma_16_after(wbase[j] + (int64_t)c * 1024, woff, lds_raw + j * 1024, after);
-            lds_dma_4(sbase[j] + (int64_t)(c / cpg) * 64, soff, lds_sc + j * 256);
+            lds_dma_4(sbase[j] + (int64_t)(c / cpg) * REC, soff, lds_sc + j * 256);
+            if (ASYM) lds_dma_4(sbase[j] + (int64_t)(c / cpg) * REC, zoff, lds_zp + j * 256);
         }
     };
 
@@ -151,8 +159,12 @@ __global__ void __launch_bounds__(512, (KS * MF > 16 || MF * TPW > 16) ? 2 : 4) 
 #pragma unroll
         for (int j = 0; j < TPW; ++j) raw[j] = make_uint4(0u, 0u, 0u, 0u);
         bool m8[TPW];                                            // the band's next chunk lies in a group that holds -8
+        uint32_t zp[TPW];                                        // asymmetric format: the lane's zero-point in the next chunk
 #pragma unroll
-        for (int j = 0; j < TPW; ++j) m8[j] = false;
+        for (int j = 0; j < TPW; ++j) {
+            m8[j] = false;
+            zp[j] = 0u;
+        }
         if (c + KS < C) {
             uint32_t seen = 0u;
 #pragma unroll
@@ -160,13 +172,22 @@ __global__ void __launch_bounds__(512, (KS * MF > 16 || MF * TPW > 16) ? 2 : 4) 
                 raw[j] = *reinterpret_cast<const uint4*>(my_raw + j * 1024);
                 next.s[j] = *reinterpret_cast<const float*>(my_sc + j * 256);
                 seen ^= raw[j].x ^ __float_as_uint(next.s[j]);
-                m8[j] = any_marked(next.s[j]);
+                if (ASYM) {
+                    const uint32_t zw = *reinterpret_cast<const uint32_t*>(my_zp + j * 256);
+                    seen ^= zw;
+                    zp[j] = (zw >> (8 * (i & 3))) & 0xFFu;
+                } else {
+                    m8[j] = any_marked(next.s[j]);
+                }
             }
             if (c + 2 * KS < C) stage_w(c + 2 * KS, seen);
         }
         MagTable tab[TPW];                                       // two-level mode: the next chunk's magnitude tables
 #pragma unroll
         for (int j = 0; j < TPW; ++j) tab[j] = TWO ? two_level_table(next.s[j]) : MagTable{0u, 0u, 0u};
+        AsymTable atab[TPW];                                     // asymmetric format: the next chunk's code - zero_point bytes
+#pragma unroll
+        for (int j = 0; j < TPW; ++j) atab[j] = ASYM ? asym_table(zp[j]) : AsymTable{{0u, 0u, 0u, 0u}};
         if (c < C) {
             const uint8_t* xb = lds + buf * STAGE_BYTES;
             uint4 xa = *reinterpret_cast<const uint4*>(xb + xa_off);
@@ -208,6 +229,8 @@ __global__ void __launch_bounds__(512, (KS * MF > 16 || MF * TPW > 16) ? 2 : 4) 
                             if (m8[jb])
                                 o = (e & 1) ? two_level_fix_minus_eight<4>(o, src, tab[jb])
                                             : two_level_fix_minus_eight<0>(o, src, tab[jb]);
+                        } else if (ASYM) {
+                            o = (e & 1) ? asym_half<4>(src, atab[jb]) : asym_half<0>(src, atab[jb]);
                         } else {
                             o = (e & 1) ? sm_half_to_e4m3_fast<4>(src) : sm_half_to_e4m3_fast<0>(src);
                             if (m8[jb]) o = sm_fix_minus_eight(o);   // wave-uniform, rare
@@ -218,7 +241,7 @@ __global__ void __launch_bounds__(512, (KS * MF > 16 || MF * TPW > 16) ? 2 : 4) 
                     p_prev = p;
                     __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);              // LDS reads of the next block
                     __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);              // this step's MFMA
-                    __builtin_amdgcn_sched_group_barrier(0x002, (TWO ? 0 : 4) + 4 * PIECES, 0);   // ALU work independent of it
+                    __builtin_amdgcn_sched_group_barrier(0x002, (TWO ? 0 : 4) + (ASYM ? 7 : 4) * PIECES, 0);   // ALU work independent of it
                     __builtin_amdgcn_sched_barrier(0);
                 }
             }
@@ -245,19 +268,24 @@ __global__ void __launch_bounds__(512, (KS * MF > 16 || MF * TPW > 16) ? 2 : 4) 
     {
         // the group's first chunk comes through registers, so that the copies of its second chunk need not wait for it
         uint4 raw0[TPW];
+        uint32_t zp0[TPW];
 #pragma unroll
         for (int j = 0; j < TPW; ++j) {
             raw0[j] = make_uint4(0u, 0u, 0u, 0u);
+            zp0[j] = 0u;
             if (kg < C) {
                 raw0[j] = *reinterpret_cast<const uint4*>(wbase[j] + (int64_t)kg * 1024 + woff);
-                wa.s[j] = *reinterpret_cast<const float*>(sbase[j] + (int64_t)(kg / cpg) * 64 + soff);
+                wa.s[j] = *reinterpret_cast<const float*>(sbase[j] + (int64_t)(kg / cpg) * REC + soff);
+                if (ASYM) zp0[j] = sbase[j][(int64_t)(kg / cpg) * REC + 64 + i];
             }
         }
         stage_x(0, 0);
         if (kg + KS < C) stage_w(kg + KS, 0u);
 #pragma unroll
         for (int j = 0; j < TPW; ++j)
-            wa.op[j] = TWO ? slot_to_operand_two_level<true>(raw0[j], two_level_table(wa.s[j])) : slot_to_operand<true>(raw0[j]);
+            wa.op[j] = TWO    ? slot_to_operand_two_level<true>(raw0[j], two_level_table(wa.s[j]))
+                       : ASYM ? slot_to_operand_asym(raw0[j], asym_table(zp0[j]))
+                              : slot_to_operand<true>(raw0[j]);
     }
     lds_dma_wait_all();
     __syncthreads();
@@ -345,25 +373,27 @@ __global__ void __launch_bounds__(512, (KS * MF > 16 || MF * TPW > 16) ? 2 : 4) 
 
 template <typename OutT, int MF, int KS, int TPW>
 void launch_one(const LinearArgs& a, dim3 grid, int grid_m, int grid_n, hipStream_t st) {
-#define W4A8_MFMA(TWOV)                                                                                                   \
-    hipLaunchKernelGGL((linear_mfma_kernel<OutT, MF, KS, TPW, TWOV>), grid, dim3(WAVES * 64), 0, st, a.x8, a.M, a.ldx8, a.s_x, \
-                       a.packed, a.scales, a.N, a.n_tiles, a.C, a.cpg, a.NG, static_cast<OutT*>(a.y), a.ldy, grid_m, grid_n,  \
+#define W4A8_MFMA(MODEV)                                                                                                   \
+    hipLaunchKernelGGL((linear_mfma_kernel<OutT, MF, KS, TPW, MODEV>), grid, dim3(WAVES * 64), 0, st, a.x8, a.M, a.ldx8, a.s_x, \
+                       a.packed, a.scales, a.N, a.n_tiles, a.C, a.cpg, a.NG, static_cast<OutT*>(a.y), a.ldy, grid_m, grid_n,   \
                        a.w_out, a.per_channel)
-    if (a.w_out)
-        W4A8_MFMA(true);
+    if (a.mode == MODE_TWO_LEVEL)
+        W4A8_MFMA(MODE_TWO_LEVEL);
+    else if (a.mode == MODE_ASYM)
+        W4A8_MFMA(MODE_ASYM);
     else
-        W4A8_MFMA(false);
+        W4A8_MFMA(MODE_CODE_EXACT);
 #undef W4A8_MFMA
 }
 
 }  // namespace
 
 // mf = 16-token blocks per workgroup (4, 8 or 16), ks = K-split groups (1, 2 or 4), tpw = weight bands per wavefront
-// (1 or 2); 0 = chosen from the shape.  w_out != nullptr selects the two-level mode.
+// (1 or 2); 0 = chosen from the shape.
 int launch_linear_mfma_tiled(const uint8_t* x8, int64_t M, int64_t K, int64_t ldx8, const float* s_x,
                              const uint8_t* packed, const float* scales, int64_t N, int32_t G, void* y,
                              w4a8_dtype ydt, int64_t ldy, int mf, int ks, int tpw, const float* w_out, int per_channel,
-                             hipStream_t st) {
+                             int mode, hipStream_t st) {
     if (!(mf == 0 || mf == 4 || mf == 8 || mf == 16) || !(ks == 0 || ks == 1 || ks == 2 || ks == 4) || tpw < 0 || tpw > 2)
         return W4A8_ERR_SHAPE;
     const int C = (int)(K / 128), cpg = G / 128, NG = (int)(K / G);
@@ -402,7 +432,7 @@ int launch_linear_mfma_tiled(const uint8_t* x8, int64_t M, int64_t K, int64_t ld
     if (total > (1 << 30)) return W4A8_ERR_SHAPE;
     if (ldx8 >= (1 << 24)) return W4A8_ERR_SHAPE;               // 32-bit activation offsets inside a token block
     const dim3 grid((unsigned)((total + XCDS - 1) / XCDS * XCDS));
-    const LinearArgs a{x8, (int)M, ldx8, s_x, packed, scales, (int)N, n_tiles, C, cpg, NG, y, ldy, w_out, per_channel};
+    const LinearArgs a{x8, (int)M, ldx8, s_x, packed, scales, (int)N, n_tiles, C, cpg, NG, y, ldy, w_out, per_channel, mode};
     bool launched = false;
 #define W4A8_CASE(MFV, KSV, TPV)                                              \
     if (mf == MFV && ks == KSV && tpw == TPV) {                               \

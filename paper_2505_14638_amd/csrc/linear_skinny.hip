@@ -22,21 +22,26 @@ struct ChunkLoads {
     uint4 w[NT];          // packed nibbles: this lane's slot of each tile
     float4 s[NT];         // group scales of the four output channels this lane accumulates
     uint4 x[MT][2];       // 32 activation bytes per 16-token block
+    uint32_t z[NT];       // asymmetric format: zero-point of the channel whose nibbles this lane expands
 };
 
 // larger register tiles run with fewer wavefronts per workgroup (the launcher enforces it), which raises the
 // register budget per lane: 128 at 1024 threads, 256 at 512 and below
 constexpr int max_threads(int tiles) { return tiles <= 2 ? 1024 : (tiles <= 8 ? 512 : 256); }
 
-// DEPTH = chunks in flight per wavefront (a ring of register buffers).  TWO = false: code-exact mode (group scales
-// applied to the partial sums in fp32).  TWO = true: two-level mode, the weight operand is nearest_E4M3(code * s8[n,g]),
-// the sum over the wavefront's share of K stays in the MFMA accumulator and the output is scaled by s_x * w_out[n]
-// (w_out[0] when per_channel is 0).
-template <int MT, int NT, int DEPTH, typename OutT, bool TWO>
+// DEPTH = chunks in flight per wavefront (a ring of register buffers).  MODE_CODE_EXACT: signed codes, group scales
+// applied to the partial sums in fp32.  MODE_TWO_LEVEL: the weight operand is nearest_E4M3(code * s8[n,g]), the sum over
+// the wavefront's share of K stays in the MFMA accumulator and the output is scaled by s_x * w_out[n] (w_out[0] when
+// per_channel is 0).  MODE_ASYM: unsigned codes with per-group zero-points, the weight operand is the integer
+// code - zero_point, scales as in the code-exact mode; `scales` then points at the 80-byte records of scales and
+// zero-points.
+template <int MT, int NT, int DEPTH, typename OutT, int MODE>
 __global__ void __launch_bounds__(max_threads(MT * NT)) linear_skinny_kernel(
     const uint8_t* __restrict__ x8, int M, int64_t ldx8, const float* __restrict__ s_x,
     const uint8_t* __restrict__ packed, const float* __restrict__ scales, int N, int n_tiles, int C, int cpg, int NG,
     OutT* __restrict__ y, int64_t ldy, int cpw, const float* __restrict__ w_out, int per_channel) {
+    constexpr bool TWO = MODE == MODE_TWO_LEVEL, ASYM = MODE == MODE_ASYM;
+    constexpr int REC = ASYM ? ASYM_RECORD_BYTES : 64;           // bytes of scales (and zero-points) per tile and group
     extern __shared__ float red[];
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);     // wave-uniform: keeps the loop scalar
@@ -53,7 +58,7 @@ __global__ void __launch_bounds__(max_threads(MT * NT)) linear_skinny_kernel(
     for (int j = 0; j < NT; ++j) {
         const int t = min(t0 + j, n_tiles - 1);                  // tiles past the end reload the last one; not stored
         wbase[j] = packed + ((int64_t)t * C + c_begin) * 1024;
-        sbase[j] = reinterpret_cast<const uint8_t*>(scales) + (int64_t)t * NG * 64;
+        sbase[j] = reinterpret_cast<const uint8_t*>(scales) + (int64_t)t * NG * REC;
     }
     const uint32_t woff = lane * 16, soff = kq * 16;
     const uint8_t* xp[MT];
@@ -69,9 +74,10 @@ __global__ void __launch_bounds__(max_threads(MT * NT)) linear_skinny_kernel(
         for (int j = 0; j < NT; ++j) {
             L.w[j] = *reinterpret_cast<const uint4*>(wbase[j] + woff);
             if (TWO)                                            // the scale of the channel whose nibbles this lane expands
-                L.s[j] = make_float4(*reinterpret_cast<const float*>(sbase[j] + (int64_t)g * 64 + i * 4), 0.f, 0.f, 0.f);
+                L.s[j] = make_float4(*reinterpret_cast<const float*>(sbase[j] + (int64_t)g * REC + i * 4), 0.f, 0.f, 0.f);
             else
-                L.s[j] = *reinterpret_cast<const float4*>(sbase[j] + (int64_t)g * 64 + soff);
+                L.s[j] = *reinterpret_cast<const float4*>(sbase[j] + (int64_t)g * REC + soff);
+            L.z[j] = ASYM ? (uint32_t)sbase[j][(int64_t)g * REC + 64 + i] : 0u;
             wbase[j] += 1024;
         }
 #pragma unroll
@@ -100,12 +106,14 @@ __global__ void __launch_bounds__(max_threads(MT * NT)) linear_skinny_kernel(
         for (int j = 0; j < NT; ++j) {
             const float4 s = L.s[j];
             // a marked scale (sign bit) on any of the band's 16 channels: this chunk's tile may hold -8
-            const bool m8 = any_marked(__uint_as_float(__float_as_uint(s.x) | __float_as_uint(s.y) | __float_as_uint(s.z) |
-                                                       __float_as_uint(s.w)));
+            const bool m8 = !ASYM && any_marked(__uint_as_float(__float_as_uint(s.x) | __float_as_uint(s.y) |
+                                                                __float_as_uint(s.z) | __float_as_uint(s.w)));
             v8i wop;
             if (TWO) {
                 const MagTable tab = two_level_table(s.x);
                 wop = m8 ? slot_to_operand_two_level<true>(L.w[j], tab) : slot_to_operand_two_level<false>(L.w[j], tab);
+            } else if (ASYM) {
+                wop = slot_to_operand_asym(L.w[j], asym_table(L.z[j]));
             } else {
                 wop = slot_to_operand<false>(L.w[j]);
                 if (m8) {                                        // wave-uniform, rare
@@ -185,16 +193,18 @@ int launch_one(const LinearArgs& a, int depth, int waves, hipStream_t st) {
     const int cpw = (a.C + waves - 1) / waves;
     const size_t lds = (size_t)waves * MT * NT * 4 * RED_STRIDE * sizeof(float);
     constexpr int DEEP = (MT * NT == 1) ? 4 : 2;                 // deeper ring while the registers allow it
-#define W4A8_SKINNY(DEPTHV, TWOV)                                                                                        \
-    hipLaunchKernelGGL((linear_skinny_kernel<MT, NT, DEPTHV, OutT, TWOV>), dim3(grid), dim3(waves * 64), lds, st, a.x8, a.M, \
-                       a.ldx8, a.s_x, a.packed, a.scales, a.N, a.n_tiles, a.C, a.cpg, a.NG, static_cast<OutT*>(a.y), a.ldy,  \
+#define W4A8_SKINNY(DEPTHV, MODEV)                                                                                        \
+    hipLaunchKernelGGL((linear_skinny_kernel<MT, NT, DEPTHV, OutT, MODEV>), dim3(grid), dim3(waves * 64), lds, st, a.x8, a.M, \
+                       a.ldx8, a.s_x, a.packed, a.scales, a.N, a.n_tiles, a.C, a.cpg, a.NG, static_cast<OutT*>(a.y), a.ldy,   \
                        cpw, a.w_out, a.per_channel)
-    if (a.w_out)
-        W4A8_SKINNY(2, true);
+    if (a.mode == MODE_TWO_LEVEL)
+        W4A8_SKINNY(2, MODE_TWO_LEVEL);
+    else if (a.mode == MODE_ASYM)
+        W4A8_SKINNY(2, MODE_ASYM);
     else if (depth == DEEP)
-        W4A8_SKINNY(DEEP, false);
+        W4A8_SKINNY(DEEP, MODE_CODE_EXACT);
     else
-        W4A8_SKINNY(2, false);
+        W4A8_SKINNY(2, MODE_CODE_EXACT);
 #undef W4A8_SKINNY
     return launch_status();
 }
@@ -222,7 +232,8 @@ int launch_mt(const LinearArgs& a, int mt, int nt, int depth, int waves, hipStre
 
 int launch_linear_skinny(const uint8_t* x8, int64_t M, int64_t K, int64_t ldx8, const float* s_x,
                          const uint8_t* packed, const float* scales, int64_t N, int32_t G, void* y, w4a8_dtype ydt,
-                         int64_t ldy, int nt, int waves, int depth, const float* w_out, int per_channel, hipStream_t st) {
+                         int64_t ldy, int nt, int waves, int depth, const float* w_out, int per_channel, int mode,
+                         hipStream_t st) {
     if (M < 1 || M > 64) return W4A8_ERR_SHAPE;
     const int C = (int)(K / 128), cpg = G / 128, NG = (int)(K / G);
     const int n_tiles = (int)((N + 15) / 16);
@@ -244,7 +255,7 @@ int launch_linear_skinny(const uint8_t* x8, int64_t M, int64_t K, int64_t ldx8, 
     if (waves < 1 || waves > 16 || waves * mt * nt > 64 || waves * 64 > max_threads(mt * nt)) return W4A8_ERR_SHAPE;
     if (depth == 0) depth = 2;                                   // deeper rings cost occupancy and measured no faster
     if (depth != 2 && depth != 4) return W4A8_ERR_SHAPE;
-    const LinearArgs a{x8, (int)M, ldx8, s_x, packed, scales, (int)N, n_tiles, C, cpg, NG, y, ldy, w_out, per_channel};
+    const LinearArgs a{x8, (int)M, ldx8, s_x, packed, scales, (int)N, n_tiles, C, cpg, NG, y, ldy, w_out, per_channel, mode};
     if (ydt == W4A8_F32) return launch_mt<float>(a, mt, nt, depth, waves, st);
     return launch_mt<uint16_t>(a, mt, nt, depth, waves, st);
 }

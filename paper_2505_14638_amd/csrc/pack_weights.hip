@@ -1,5 +1,6 @@
 // Weight packing: symmetric round-to-nearest INT4 (Eq. 1, symmetric case) or re-layout of given codes,
-// into the canonical or the tiled storage format; and the INT4 -> E4M3 test hook (Eq. 10).
+// into the canonical or the tiled storage format; the asymmetric format (Eq. 1 with unsigned codes and zero-points,
+// Eq. 8-9) into its tiled storage; and the INT4 -> E4M3 test hooks (Eq. 10).
 // Offline with respect to inference: written for exactness and simplicity, not speed.
 #include "w4a8_device.hpp"
 #include "w4a8_internal.hpp"
@@ -114,11 +115,85 @@ __global__ void __launch_bounds__(256) pack_kernel(const void* __restrict__ src,
     packed[b] = (uint8_t)(lo | (hi << 4));
 }
 
+// Asymmetric format, parameters: one wavefront per (row, group) writes the row's scale and zero-point into the 80-byte
+// record of its (16-row band, group).  FROM_F32: lo = min(min W, 0), hi = max(max W, 0), s = (hi - lo) / 15 (1 for an
+// all-zero group), z = round(-lo / s), all float32; otherwise the given scale and zero-point (kept to 0..15).
+template <bool FROM_F32>
+__global__ void __launch_bounds__(256) asym_params_kernel(const float* __restrict__ w, const float* __restrict__ src_scales,
+                                                          const uint8_t* __restrict__ src_zeros, Geometry g,
+                                                          uint8_t* __restrict__ params) {
+    const int64_t wid = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
+    const int lane = threadIdx.x & 63;
+    if (wid >= g.Np * g.NG) return;
+    const int64_t n = wid / g.NG, grp = wid - n * g.NG;
+    float s = 0.0f;
+    uint32_t z = 0u;
+    if (n < g.N) {
+        if (FROM_F32) {
+            float lo = 0.0f, hi = 0.0f;
+            const float* p = w + n * g.K + grp * g.G;
+            for (int j = lane; j < g.G; j += 64) {
+                lo = fminf(lo, p[j]);
+                hi = fmaxf(hi, p[j]);
+            }
+#pragma unroll
+            for (int off = 32; off > 0; off >>= 1) {
+                lo = fminf(lo, __shfl_xor(lo, off, 64));
+                hi = fmaxf(hi, __shfl_xor(hi, off, 64));
+            }
+            const float span = __fsub_rn(hi, lo);
+            s = (span == 0.0f) ? 1.0f : __fdiv_rn(span, 15.0f);
+            z = (uint32_t)fminf(fmaxf(rintf(__fdiv_rn(-lo, s)), 0.0f), 15.0f);
+        } else {
+            s = src_scales[n * g.NG + grp];
+            z = min((uint32_t)src_zeros[n * g.NG + grp], 15u);
+        }
+    }
+    if (lane == 0) {
+        uint8_t* rec = params + ((n >> 4) * g.NG + grp) * ASYM_RECORD_BYTES;
+        reinterpret_cast<float*>(rec)[n & 15] = s;
+        rec[64 + (n & 15)] = (uint8_t)z;
+    }
+}
+
+// u = clamp(round(W / s + z), 0, 15): float32 division, float32 addition, round half to even
+__device__ __forceinline__ uint32_t asym_code(float w, float s, uint32_t z) {
+    const float r = rintf(__fadd_rn(__fdiv_rn(w, s), (float)z));
+    return (uint32_t)fminf(fmaxf(r, 0.0f), 15.0f);
+}
+
+// asymmetric format, codes: one thread per destination byte of the tiled storage
+template <bool FROM_F32>
+__global__ void __launch_bounds__(256) pack_asym_kernel(const void* __restrict__ src, Geometry g,
+                                                        const uint8_t* __restrict__ params, uint8_t* __restrict__ packed) {
+    const int64_t b = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (b >= g.Np * (g.K >> 1)) return;
+    int64_t n, k_lo, k_hi;
+    byte_to_coords(g, b, n, k_lo, k_hi);
+    uint32_t lo = 0, hi = 0;
+    if (n < g.N) {
+        if (FROM_F32) {
+            const float* w = static_cast<const float*>(src) + n * g.K;
+            const uint8_t* rec_lo = params + ((n >> 4) * g.NG + k_lo / g.G) * ASYM_RECORD_BYTES;
+            const uint8_t* rec_hi = params + ((n >> 4) * g.NG + k_hi / g.G) * ASYM_RECORD_BYTES;
+            lo = asym_code(w[k_lo], reinterpret_cast<const float*>(rec_lo)[n & 15], rec_lo[64 + (n & 15)]);
+            hi = asym_code(w[k_hi], reinterpret_cast<const float*>(rec_hi)[n & 15], rec_hi[64 + (n & 15)]);
+        } else {
+            const uint8_t* q = static_cast<const uint8_t*>(src) + n * g.K;
+            lo = q[k_lo] & 0xFu;                                 // only the low nibble of the input counts
+            hi = q[k_hi] & 0xFu;
+        }
+    }
+    packed[b] = (uint8_t)(lo | (hi << 4));
+}
+
 // tiled: one thread per 16-byte slot -> 32 consecutive bytes of one row of w8
 // scales8 != nullptr: two-level bytes nearest_E4M3(code * s8[n, g]) with the tiled scale buffer of group size G
+// asym_params != nullptr: asymmetric format, bytes nearest_E4M3(code - zero_point[n, g])
 __global__ void __launch_bounds__(256) dequant_tiled_kernel(const uint4* __restrict__ packed, int64_t N, int64_t K,
                                                             int64_t slots, uint8_t* __restrict__ w8,
-                                                            const float* __restrict__ scales8, int32_t G) {
+                                                            const float* __restrict__ scales8,
+                                                            const uint8_t* __restrict__ asym_params, int32_t G) {
     const int64_t u = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (u >= slots) return;
     const int64_t tile = u >> 6, C = K >> 7;
@@ -130,6 +205,9 @@ __global__ void __launch_bounds__(256) dequant_tiled_kernel(const uint4* __restr
     if (scales8) {
         const int64_t NG = K / G, grp = (c * 128) / G;
         op = slot_to_operand_two_level<true>(packed[u], two_level_table(scales8[(t * NG + grp) * 16 + i]));
+    } else if (asym_params) {
+        const int64_t NG = K / G, grp = (c * 128) / G;
+        op = slot_to_operand_asym(packed[u], asym_table(asym_params[(t * NG + grp) * ASYM_RECORD_BYTES + 64 + i]));
     } else {
         op = slot_to_operand<true>(packed[u]);
     }
@@ -174,12 +252,33 @@ int launch_pack_weights(const void* src, w4a8_src kind, const float* src_scales,
     return launch_status();
 }
 
+int launch_pack_weights_asym(const void* src, w4a8_src kind, const float* src_scales, const uint8_t* src_zeros,
+                             int64_t N, int64_t K, int32_t G, uint8_t* packed, uint8_t* params, hipStream_t st) {
+    Geometry g;
+    g.N = N; g.K = K; g.G = G; g.NG = K / G;
+    g.tiled = 1;
+    g.Np = ((N + 15) / 16) * 16;
+    const int64_t n_groups = g.Np * g.NG, n_bytes = g.Np * (K / 2);
+    if (kind == W4A8_SRC_F32_RTN) {
+        hipLaunchKernelGGL(asym_params_kernel<true>, dim3(blocks_for(n_groups * 64)), dim3(256), 0, st,
+                           static_cast<const float*>(src), nullptr, nullptr, g, params);
+        if (int e = launch_status()) return e;
+        hipLaunchKernelGGL(pack_asym_kernel<true>, dim3(blocks_for(n_bytes)), dim3(256), 0, st, src, g, params, packed);
+    } else {
+        hipLaunchKernelGGL(asym_params_kernel<false>, dim3(blocks_for(n_groups * 64)), dim3(256), 0, st, nullptr,
+                           src_scales, src_zeros, g, params);
+        if (int e = launch_status()) return e;
+        hipLaunchKernelGGL(pack_asym_kernel<false>, dim3(blocks_for(n_bytes)), dim3(256), 0, st, src, g, params, packed);
+    }
+    return launch_status();
+}
+
 int launch_dequant_weights(const uint8_t* packed, int64_t N, int64_t K, w4a8_layout layout, uint8_t* w8,
-                           const float* scales8, int32_t G, hipStream_t st) {
+                           const float* scales8, const uint8_t* asym_params, int32_t G, hipStream_t st) {
     if (layout == W4A8_LAYOUT_TILED) {
         const int64_t slots = ((N + 15) / 16) * (K / 128) * 64;
         hipLaunchKernelGGL(dequant_tiled_kernel, dim3(blocks_for(slots)), dim3(256), 0, st,
-                           reinterpret_cast<const uint4*>(packed), N, K, slots, w8, scales8, G);
+                           reinterpret_cast<const uint4*>(packed), N, K, slots, w8, scales8, asym_params, G);
     } else {
         const int64_t bytes = N * (K / 2);
         hipLaunchKernelGGL(dequant_canonical_kernel, dim3(blocks_for(bytes)), dim3(256), 0, st, packed, bytes, w8);

@@ -134,6 +134,54 @@ __device__ __forceinline__ v8i slot_to_operand_two_level(uint4 s, const MagTable
     return v;
 }
 
+// ---------------------------------------------------------------------------------------------
+// Asymmetric format (Eq. 1 with unsigned codes 0..15, Eq. 8-9, Eq. 14): the FP8 weight is the integer code - zero_point,
+// in [-15, 15], exact in E4M3.  The zero-point belongs to a (row, group), that is to a lane for the length of a chunk:
+// per (lane, chunk) a 16-entry table of the bytes nearest_E4M3(u - z), u = 0..15 (sixteen float32 differences, rounded
+// by the hardware converter, which is exact on them); the plain unsigned nibbles index it -- an 8-entry lookup for
+// each half of the table and a third v_perm_b32 that picks, byte by byte, the half that bit 3 names.
+// ---------------------------------------------------------------------------------------------
+struct AsymTable {
+    uint32_t t[4];        // byte u % 4 of t[u / 4] = nearest_E4M3(u - z)
+};
+
+__device__ __forceinline__ AsymTable asym_table(uint32_t z) {
+    const float zf = (float)(z & 15u);
+    AsymTable T;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+        int r = __builtin_amdgcn_cvt_pk_fp8_f32((float)(4 * w) - zf, (float)(4 * w + 1) - zf, 0, false);
+        r = __builtin_amdgcn_cvt_pk_fp8_f32((float)(4 * w + 2) - zf, (float)(4 * w + 3) - zf, r, true);
+        T.t[w] = (uint32_t)r;
+    }
+    return T;
+}
+
+// E4M3 bytes of the four unsigned nibbles at bit offset SHIFT (0: low nibbles, 4: high nibbles) of the bytes of w.
+template <int SHIFT>
+__device__ __forceinline__ uint32_t asym_half(uint32_t w, const AsymTable& T) {
+    const uint32_t v = SHIFT ? (w >> 4) : w;
+    const uint32_t sel = v & 0x07070707u;
+    const uint32_t lo = __builtin_amdgcn_perm(T.t[1], T.t[0], sel);          // entries 0..7
+    const uint32_t hi = __builtin_amdgcn_perm(T.t[3], T.t[2], sel);          // entries 8..15
+    const uint32_t mix = ((v >> 1) & 0x04040404u) | 0x03020100u;             // byte i: selector i (lo) or i + 4 (hi)
+    return __builtin_amdgcn_perm(hi, lo, mix);
+}
+
+__device__ __forceinline__ v8i slot_to_operand_asym(uint4 s, const AsymTable& T) {
+    const uint32_t w[4] = {s.x, s.y, s.z, s.w};
+    v8i v;
+#pragma unroll
+    for (int d = 0; d < 4; ++d) {
+        v[2 * d] = (int)asym_half<0>(w[d], T);
+        v[2 * d + 1] = (int)asym_half<4>(w[d], T);
+    }
+    return v;
+}
+
+// Bytes per (16-row band, group) record of the asymmetric format's parameters: 16 float32 scales, 16 zero-point bytes.
+constexpr int ASYM_RECORD_BYTES = 80;
+
 // True when some lane of the wavefront holds a scale whose sign bit is set (the packer's "-8 in this group" mark).
 __device__ __forceinline__ bool any_marked(float s) { return __builtin_amdgcn_ballot_w64(__float_as_int(s) < 0) != 0; }
 

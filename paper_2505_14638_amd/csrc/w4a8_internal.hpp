@@ -11,9 +11,15 @@ namespace w4a8 {
 inline int hip_status(hipError_t e) { return e == hipSuccess ? W4A8_OK : W4A8_ERR_HIP; }
 inline int launch_status() { return hip_status(hipGetLastError()); }
 
+// How the tiled-layout linear kernels read the weights.
+//   MODE_CODE_EXACT  signed codes, fp32 group scales applied to the partial sums
+//   MODE_TWO_LEVEL   signed codes, `scales` = FP8-domain group scales, output scaled by s_x * w_out[n] (w_out[0] when
+//                    per_channel is 0)
+//   MODE_ASYM        unsigned codes, `scales` = the 80-byte records of group scales and zero-points
+enum WeightMode { MODE_CODE_EXACT = 0, MODE_TWO_LEVEL = 1, MODE_ASYM = 2 };
+
 // What the launchers of the tiled-layout linear kernels pass down to a launch: the operands of w4a8_linear after
-// validation.  w_out != nullptr selects the two-level mode (scales = FP8-domain group scales, output scaled by
-// s_x * w_out[n], or s_x * w_out[0] when per_channel is 0).
+// validation.
 struct LinearArgs {
     const uint8_t* x8;
     int M;
@@ -26,28 +32,34 @@ struct LinearArgs {
     int64_t ldy;
     const float* w_out;
     int per_channel;
+    int mode;                        // a WeightMode
 };
 
 int launch_quantize_act(const void* x, w4a8_dtype dt, int64_t M, int64_t K, int64_t ldx, const float* scale,
                         uint8_t* x8, int64_t ldx8, hipStream_t st);
 int launch_pack_weights(const void* src, w4a8_src kind, const float* src_scales, int64_t N, int64_t K, int32_t G,
                         w4a8_layout layout, uint8_t* packed, float* scales, hipStream_t st);
-// scales8 != nullptr (tiled layout only): the two-level bytes nearest_E4M3(code * s8[n,g])
+// asymmetric format (tiled storage): src = float32 weights (W4A8_SRC_F32_RTN) or unsigned codes with their scales and
+// zero-points; params = the 80-byte records
+int launch_pack_weights_asym(const void* src, w4a8_src kind, const float* src_scales, const uint8_t* src_zeros,
+                             int64_t N, int64_t K, int32_t G, uint8_t* packed, uint8_t* params, hipStream_t st);
+// tiled layout only: scales8 != nullptr: the two-level bytes nearest_E4M3(code * s8[n,g]); asym_params != nullptr: the
+// asymmetric format's bytes nearest_E4M3(code - zero_point[n,g])
 int launch_dequant_weights(const uint8_t* packed, int64_t N, int64_t K, w4a8_layout layout, uint8_t* w8,
-                           const float* scales8, int32_t G, hipStream_t st);
+                           const float* scales8, const uint8_t* asym_params, int32_t G, hipStream_t st);
 int launch_linear_canonical(const uint8_t* x8, int64_t M, int64_t K, int64_t ldx8, const float* s_x,
                             const uint8_t* packed, const float* scales, int64_t N, int32_t G, void* y,
                             w4a8_dtype ydt, int64_t ldy, hipStream_t st);
-// nt / waves / depth = 0: chosen from the shape.  w_out != nullptr: two-level mode (scales are FP8-domain group scales,
-// the output is scaled by s_x * w_out[n], or s_x * w_out[0] when per_channel is 0).
+// nt / waves / depth = 0: chosen from the shape.  mode: a WeightMode; w_out and per_channel count in MODE_TWO_LEVEL.
 int launch_linear_skinny(const uint8_t* x8, int64_t M, int64_t K, int64_t ldx8, const float* s_x,
                          const uint8_t* packed, const float* scales, int64_t N, int32_t G, void* y, w4a8_dtype ydt,
-                         int64_t ldy, int nt, int waves, int depth, const float* w_out, int per_channel, hipStream_t st);
+                         int64_t ldy, int nt, int waves, int depth, const float* w_out, int per_channel, int mode,
+                         hipStream_t st);
 // mf = 16-token blocks per workgroup, ks = K-split groups per workgroup, tpw = weight bands per wavefront; 0: chosen
 int launch_linear_mfma_tiled(const uint8_t* x8, int64_t M, int64_t K, int64_t ldx8, const float* s_x,
                              const uint8_t* packed, const float* scales, int64_t N, int32_t G, void* y,
                              w4a8_dtype ydt, int64_t ldy, int mf, int ks, int tpw, const float* w_out, int per_channel,
-                             hipStream_t st);
+                             int mode, hipStream_t st);
 int launch_silu_mul(const void* gu, int64_t M, int64_t F, int64_t ldgu, void* h, int64_t ldh, hipStream_t st);
 
 }  // namespace w4a8

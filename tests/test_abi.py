@@ -122,6 +122,33 @@ def test_two_level_validation(L):
     assert d(P + 8, P, 16, 256, 128, P, None) == 6
 
 
+def test_asym_validation(L):
+    assert L.w4a8_asym_params_bytes(40, 384, 128) == 3 * 3 * 80
+    assert L.w4a8_asym_params_bytes(40, 384, 384) == 3 * 80
+    assert L.w4a8_asym_params_bytes(40, 384, 64) == 0                   # tiled storage needs G % 128 == 0
+    p = L.w4a8_pack_weights_asym
+    # src, kind, src_scales, src_zeros, N, K, G, packed, params, stream
+    assert p(P, B.SRC_F32_RTN, 0, 0, 16, 256, 128, 0, P, None) == 1
+    assert p(P, B.SRC_I8_CODES, P, 0, 16, 256, 128, P, P, None) == 1    # codes need scales and zero-points
+    assert p(P, B.SRC_I8_CODES, 0, P, 16, 256, 128, P, P, None) == 1
+    assert p(P, 3, 0, 0, 16, 256, 128, P, P, None) == 4
+    assert p(P, B.SRC_F32_RTN, 0, 0, 16, 256, 64, P, P, None) == 3
+    assert p(P, B.SRC_F32_RTN, 0, 0, 16, 200, 200, P, P, None) == 5
+    assert p(P, B.SRC_F32_RTN, 0, 0, 16, 256, 128, P, P + 4, None) == 6 # records are 16-byte aligned
+    f = L.w4a8_linear_asym
+    # x8, M, K, ldx8, xs, packed, params, N, G, y, ydt, ldy, stream
+    assert f(P, 0, 256, 256, P, P, P, 64, 128, P, B.BF16, 64, None) == 0
+    assert f(P, 4, 256, 256, P, P, 0, 64, 128, P, B.BF16, 64, None) == 1
+    assert f(P, 4, 256, 256, P, P, P + 8, 64, 128, P, B.BF16, 64, None) == 6
+    assert f(P, 4, 256, 256, P, P, P, 64, 96, P, B.BF16, 64, None) == 3
+    assert f(P, 4, 256, 128, P, P, P, 64, 128, P, B.BF16, 64, None) == 2
+    assert f(P, 4, 256, 256, P, P, P, 64, 128, P, 5, 64, None) == 4
+    d = L.w4a8_dequant_weights_asym
+    assert d(P, 0, 16, 256, 128, P, None) == 1
+    assert d(P, P, 16, 256, 64, P, None) == 3
+    assert d(P, P + 8, 16, 256, 128, P, None) == 6
+
+
 def test_other_validation(L):
     assert L.w4a8_dequant_weights(0, 16, 256, B.LAYOUT_TILED, P, None) == 1
     assert L.w4a8_dequant_weights(P, 16, 200, B.LAYOUT_TILED, P, None) == 5
