@@ -30,6 +30,8 @@ dequant_codes_to_e4m3        Eq. 10 / Eq. 14 with zero-point 0 and the scale
 linear_ref                   Eq. 10, Eq. 4 and Eq. 11: Y = X_hat . W_hat^T
 linear_ref_paper_literal     Eq. 6-11 read literally: the product code*scale is
                              itself rounded onto the E4M3 grid before the matmul
+rtn_quantize_weights_pow2    the same with power-of-two group scales (Sec. 2.2); the
+                             layer on such weights is linear_ref itself
 asym_quantize_weights        Eq. 1 in its asymmetric form with q_min = 0, q_max = 15
                              (Sec. 2.1; the form Eq. 8-9 give it)
 dequant_asym_to_e4m3         Eq. 10 / Eq. 14: the integer (code - zero_point) as an
@@ -186,6 +188,25 @@ def rtn_quantize_weights(w, group_size: int):
     s = np.where(amax == 0, np.float32(1.0), s).astype(np.float32)
     r = np.rint((wg / s[:, :, None]).astype(np.float32))
     q = np.clip(r, -8, 7).astype(np.int8).reshape(n, k)
+    return q, s
+
+
+def rtn_quantize_weights_pow2(w, group_size: int):
+    """Symmetric round-to-nearest INT4 with power-of-two group scales (the scaling factors Sec. 2.2 asks for, so
+    that scaling is an exponent adjustment): per (row, group) s = the smallest power of two >= max|W| / 7 (the
+    quotient as one float32 division; rounding the scale up rather than to the nearest power keeps every code inside
+    [-7, 7], a reading: the paper gives no rule), 1 for an all-zero group; code = round_half_even(W / s), exact
+    because s is a power of two.  Returns (codes int8 [N, K], scales float32 [N, K / group_size])."""
+    w = np.asarray(w, dtype=np.float32)
+    n, k = w.shape
+    assert k % group_size == 0
+    wg = w.reshape(n, k // group_size, group_size)
+    amax = np.max(np.abs(wg), axis=2).astype(np.float32)
+    t = (amax / np.float32(7.0)).astype(np.float32)
+    mant, expo = np.frexp(t)                                # t = mant * 2^expo, mant in [0.5, 1)
+    s = np.ldexp(np.float32(1.0), np.where(mant == 0.5, expo - 1, expo)).astype(np.float32)
+    s = np.where(amax == 0, np.float32(1.0), s).astype(np.float32)
+    q = np.clip(np.rint((wg / s[:, :, None]).astype(np.float32)), -8, 7).astype(np.int8).reshape(n, k)
     return q, s
 
 

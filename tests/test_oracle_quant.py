@@ -151,3 +151,26 @@ def test_scale_sign_marks_exactly_the_groups_that_hold_minus_eight():
     assert np.signbit(t[((3 // 16) * 4 + 1) * 16 + 3]) and t[((3 // 16) * 4 + 1) * 16 + 3] == -s[3, 1]
     # the mark is a hint only: the packed codes alone decode to the same integers
     assert np.array_equal(o.unpack_tiled(o.pack_tiled(q), n, k), q)
+
+
+def test_pow2_quantizer_hand_example_and_invariants():
+    """max|W| / 7 = 0.3 / 7 = 0.0428.. lies between 2^-5 and 2^-4: s = 2^-4; max|W| = 7 * 2^-3 exactly: s = 2^-3."""
+    w = np.array([[0.3, -0.1, 0.05, 0.0, 0.875, -0.875, 0.25, 0.1]], dtype=np.float32)
+    q, s = o.rtn_quantize_weights_pow2(w, 4)
+    assert s.tolist() == [[2.0 ** -4, 2.0 ** -3]]
+    assert q.tolist() == [[5, -2, 1, 0, 7, -7, 2, 1]]            # 0.3*16 = 4.8, 0.1*16 = 1.6, 0.05*16 = 0.8; 0.1*8 = 0.8
+    rng = np.random.default_rng(31)
+    w = syn.make_weights(rng, 48, 1024)
+    w[0, :128] = 0.0
+    q, s = o.rtn_quantize_weights_pow2(w, 128)
+    mant, _ = np.frexp(s)
+    assert np.all(mant == 0.5) and s[0, 0] == 1.0                # powers of two
+    amax = np.abs(w.reshape(48, 8, 128)).max(axis=2).astype(np.float64)
+    nz = amax > 0
+    assert np.all(7.0 * s[nz] >= amax[nz] * (1 - 1e-7)) and np.all(7.0 * s[nz] < 2.0 * amax[nz] * (1 + 1e-7))
+    assert q.min() >= -7 and q.max() <= 7
+    rec = q.reshape(48, 8, 128) * s[..., None].astype(np.float64)
+    assert np.all(np.abs(rec - w.reshape(48, 8, 128)) <= 0.5 * s[..., None])
+    # with a power-of-two scale the quotient is exact, so the code is the nearest integer of the exact quotient
+    exact = w.reshape(48, 8, 128).astype(np.float64) / s[..., None]
+    assert np.array_equal(q.reshape(48, 8, 128), np.rint(exact).astype(np.int8))
