@@ -51,9 +51,11 @@ typedef enum {
                               INT4 (Eq. 1, symmetric case of Sec. 2.1): per (row, group)
                               s = max|W| / 7 (s = 1 for an all-zero group),
                               code = clamp(round_half_even(W / s), -8, 7), both divisions in float32 */
-    W4A8_SRC_I8_CODES = 1  /* src = int8 codes [N, K], each in [-8, 7] (only the low nibble is kept), plus
+    W4A8_SRC_I8_CODES = 1, /* src = int8 codes [N, K], each in [-8, 7] (only the low nibble is kept), plus
                               float32 scales [N, K/group_size] (their magnitude is used): a pure re-layout, for
                               codes produced by an offline calibrator (Alg. 1) */
+    W4A8_SRC_F32_RTN_POW2 = 2 /* as W4A8_SRC_F32_RTN with power-of-two scales (Sec. 2.2): s = the smallest power of
+                              two >= max|W| / 7 (so that every code stays in [-7, 7]); for w4a8_linear_pow2 */
 } w4a8_src;
 
 typedef enum {
@@ -163,6 +165,19 @@ int w4a8_linear_two_level(const uint8_t* x8_dev, int64_t M, int64_t K, int64_t l
                           int64_t ldy, void* stream);
 int w4a8_dequant_weights_two_level(const uint8_t* packed_dev, const float* w_scales8_dev, int64_t N, int64_t K,
                                    int32_t group_size, uint8_t* w8_dev, void* stream);
+
+/*
+ * The layer for power-of-two group scales (Sec. 2.2: scaling factors that are powers of two turn scaling into an
+ * exponent adjustment).  Same definition and arguments as w4a8_linear with W4A8_LAYOUT_TILED; every group scale must
+ * be a power of two 2^e with -127 <= e <= 127: only the exponent field of each float32 scale is read (a mantissa is
+ * ignored, i.e. the scale is rounded down to a power of two; a zero scale acts as 2^-127).  The FP8 matrix unit
+ * applies 2^e to each 32-deep partial sum itself (block-scaled MFMA with an E8M0 scale per lane), so the sum over all
+ * of K stays in the unit's fp32 accumulator and the per-group multiply-adds of w4a8_linear disappear.  Buffers as
+ * written by w4a8_pack_weights (W4A8_SRC_F32_RTN_POW2, or W4A8_SRC_I8_CODES with power-of-two scales).
+ */
+int w4a8_linear_pow2(const uint8_t* x8_dev, int64_t M, int64_t K, int64_t ldx8, const float* x_scale_dev,
+                     const uint8_t* packed_dev, const float* w_scales_dev, int64_t N, int32_t group_size, void* y_dev,
+                     w4a8_dtype y_dtype, int64_t ldy, void* stream);
 
 /*
  * The asymmetric format (Eq. 1 with q_min = 0, q_max = 15; Eq. 8-9; dequantization by Eq. 14): unsigned 4-bit codes u

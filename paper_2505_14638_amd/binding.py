@@ -16,7 +16,7 @@ LIB_PATH = os.path.join(HERE, "libw4a8.so")
 
 # enums of include/w4a8.h
 F32, BF16 = 0, 1
-SRC_F32_RTN, SRC_I8_CODES = 0, 1
+SRC_F32_RTN, SRC_I8_CODES, SRC_F32_RTN_POW2 = 0, 1, 2
 LAYOUT_CANONICAL, LAYOUT_TILED = 0, 1
 
 _c_i64, _c_i32, _c_vp, _c_sz = ctypes.c_int64, ctypes.c_int32, ctypes.c_void_p, ctypes.c_size_t
@@ -35,6 +35,8 @@ SIGNATURES = {
     "w4a8_linear_two_level": (_c_i32, [_c_vp, _c_i64, _c_i64, _c_i64, _c_vp, _c_vp, _c_vp, _c_vp, _c_i32, _c_i64, _c_i32,
                                        _c_vp, _c_i32, _c_i64, _c_vp]),
     "w4a8_dequant_weights_two_level": (_c_i32, [_c_vp, _c_vp, _c_i64, _c_i64, _c_i32, _c_vp, _c_vp]),
+    "w4a8_linear_pow2": (_c_i32, [_c_vp, _c_i64, _c_i64, _c_i64, _c_vp, _c_vp, _c_vp, _c_i64, _c_i32, _c_vp, _c_i32,
+                                  _c_i64, _c_vp]),
     "w4a8_asym_params_bytes": (_c_sz, [_c_i64, _c_i64, _c_i32]),
     "w4a8_pack_weights_asym": (_c_i32, [_c_vp, _c_i32, _c_vp, _c_vp, _c_i64, _c_i64, _c_i32, _c_vp, _c_vp, _c_vp]),
     "w4a8_linear_asym": (_c_i32, [_c_vp, _c_i64, _c_i64, _c_i64, _c_vp, _c_vp, _c_vp, _c_i64, _c_i32, _c_vp, _c_i32,
@@ -112,12 +114,13 @@ def quantize_act(x: torch.Tensor, scale: torch.Tensor, out: torch.Tensor | None 
     return out
 
 
-def pack_weights(src: torch.Tensor, group_size: int, layout: int, src_scales: torch.Tensor | None = None):
-    """src: float32 W [N, K] (round-to-nearest inside the library) or int8 codes [N, K] with src_scales
-    [N, K/group_size].  Returns (packed uint8 1-D, scales float32 1-D) in `layout`."""
+def pack_weights(src: torch.Tensor, group_size: int, layout: int, src_scales: torch.Tensor | None = None,
+                 pow2: bool = False):
+    """src: float32 W [N, K] (round-to-nearest inside the library; pow2: with power-of-two scales) or int8 codes
+    [N, K] with src_scales [N, K/group_size].  Returns (packed uint8 1-D, scales float32 1-D) in `layout`."""
     n, k = src.shape
     assert src.is_contiguous()
-    kind = SRC_F32_RTN if src.dtype == torch.float32 else SRC_I8_CODES
+    kind = (SRC_F32_RTN_POW2 if pow2 else SRC_F32_RTN) if src.dtype == torch.float32 else SRC_I8_CODES
     nbytes, nscales = packed_bytes(n, k, layout), scales_count(n, k, group_size, layout)
     packed = torch.empty(max(nbytes, 1), dtype=torch.uint8, device=src.device)
     scales = torch.empty(max(nscales, 1), dtype=torch.float32, device=src.device)
@@ -173,6 +176,17 @@ def dequant_weights_two_level(packed: torch.Tensor, w_scales8: torch.Tensor, n: 
     _check(lib().w4a8_dequant_weights_two_level(packed.data_ptr(), w_scales8.data_ptr(), n, k, group_size, w8.data_ptr(),
                                                 _stream()), "w4a8_dequant_weights_two_level")
     return w8
+
+
+def linear_pow2(x8, x_scale, packed, w_scales, n, group_size, out=None, out_dtype=torch.bfloat16):
+    m, k = x8.shape
+    assert x8.dtype == torch.uint8 and x8.stride(1) == 1
+    if out is None:
+        out = torch.empty((m, n), dtype=out_dtype, device=x8.device)
+    _check(lib().w4a8_linear_pow2(x8.data_ptr(), m, k, x8.stride(0) if m > 1 else max(k, x8.stride(0)), x_scale.data_ptr(),
+                                  packed.data_ptr(), w_scales.data_ptr(), n, group_size, out.data_ptr(), _dtype_code(out),
+                                  out.stride(0) if m > 1 else max(n, out.stride(0)), _stream()), "w4a8_linear_pow2")
+    return out
 
 
 def asym_params_bytes(n: int, k: int, group_size: int) -> int:

@@ -68,11 +68,12 @@ int w4a8_quantize_act(const void* x_dev, w4a8_dtype x_dtype, int64_t M, int64_t 
 
 int w4a8_pack_weights(const void* src_dev, w4a8_src src_kind, const float* src_scales_dev, int64_t N, int64_t K,
                       int32_t group_size, w4a8_layout layout, uint8_t* packed_dev, float* scales_dev, void* stream) {
-    if (src_kind != W4A8_SRC_F32_RTN && src_kind != W4A8_SRC_I8_CODES) return W4A8_ERR_DTYPE;
+    if (src_kind != W4A8_SRC_F32_RTN && src_kind != W4A8_SRC_I8_CODES && src_kind != W4A8_SRC_F32_RTN_POW2)
+        return W4A8_ERR_DTYPE;
     if (int e = check_weight_shape(N, K, group_size, layout)) return e;
     if (!src_dev || !packed_dev || !scales_dev) return W4A8_ERR_NULL;
     if (src_kind == W4A8_SRC_I8_CODES && !src_scales_dev) return W4A8_ERR_NULL;
-    if (reinterpret_cast<uintptr_t>(scales_dev) % 4 || (src_kind == W4A8_SRC_F32_RTN && reinterpret_cast<uintptr_t>(src_dev) % 4))
+    if (reinterpret_cast<uintptr_t>(scales_dev) % 4 || (src_kind != W4A8_SRC_I8_CODES && reinterpret_cast<uintptr_t>(src_dev) % 4))
         return W4A8_ERR_ALIGN;
     return launch_pack_weights(src_dev, src_kind, src_scales_dev, N, K, group_size, layout, packed_dev, scales_dev,
                                static_cast<hipStream_t>(stream));
@@ -162,6 +163,22 @@ int w4a8_dequant_weights_two_level(const uint8_t* packed_dev, const float* w_sca
                                   static_cast<hipStream_t>(stream));
 }
 
+int w4a8_linear_pow2(const uint8_t* x8_dev, int64_t M, int64_t K, int64_t ldx8, const float* x_scale_dev,
+                     const uint8_t* packed_dev, const float* w_scales_dev, int64_t N, int32_t group_size, void* y_dev,
+                     w4a8_dtype y_dtype, int64_t ldy, void* stream) {
+    if (int e = check_linear(x8_dev, M, K, ldx8, x_scale_dev, packed_dev, w_scales_dev, N, group_size, W4A8_LAYOUT_TILED,
+                             y_dev, y_dtype, ldy))
+        return e;
+    if (M == 0) return W4A8_OK;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const bool deep_narrow = K >= 8192 && N <= 8192;             // same kernel choice as w4a8_linear
+    if (M <= 32 || (M <= 64 && deep_narrow))
+        return launch_linear_skinny(x8_dev, M, K, ldx8, x_scale_dev, packed_dev, w_scales_dev, N, group_size, y_dev,
+                                    y_dtype, ldy, 0, 0, 0, nullptr, 0, MODE_POW2, st);
+    return launch_linear_mfma_tiled(x8_dev, M, K, ldx8, x_scale_dev, packed_dev, w_scales_dev, N, group_size, y_dev,
+                                    y_dtype, ldy, 0, 0, 0, nullptr, 0, MODE_POW2, st);
+}
+
 size_t w4a8_asym_params_bytes(int64_t N, int64_t K, int32_t group_size) {
     if (check_weight_shape(N, K, group_size, W4A8_LAYOUT_TILED) != W4A8_OK) return 0;
     return (size_t)(((N + 15) / 16) * (K / group_size) * 80);
@@ -170,7 +187,7 @@ size_t w4a8_asym_params_bytes(int64_t N, int64_t K, int32_t group_size) {
 int w4a8_pack_weights_asym(const void* src_dev, w4a8_src src_kind, const float* src_scales_dev,
                            const uint8_t* src_zeros_dev, int64_t N, int64_t K, int32_t group_size, uint8_t* packed_dev,
                            void* params_dev, void* stream) {
-    if (src_kind != W4A8_SRC_F32_RTN && src_kind != W4A8_SRC_I8_CODES) return W4A8_ERR_DTYPE;
+    if (src_kind != W4A8_SRC_F32_RTN && src_kind != W4A8_SRC_I8_CODES) return W4A8_ERR_DTYPE;   // no power-of-two form
     if (int e = check_weight_shape(N, K, group_size, W4A8_LAYOUT_TILED)) return e;
     if (!src_dev || !packed_dev || !params_dev) return W4A8_ERR_NULL;
     if (src_kind == W4A8_SRC_I8_CODES && (!src_scales_dev || !src_zeros_dev)) return W4A8_ERR_NULL;

@@ -42,13 +42,15 @@ template <int A, int B> struct MaxOf { static constexpr int value = A > B ? A : 
 // is nearest_E4M3(code * s8[n,g]) and the sum over all of K stays in the MFMA accumulator; the output is scaled by
 // s_x * w_out[n] (w_out[0] when per_channel is 0).  MODE_ASYM: unsigned codes with per-group zero-points, the weight
 // operand is the integer code - zero_point, group scales as in the code-exact mode; `scales` then points at the
-// 80-byte records of scales and zero-points.
+// 80-byte records of scales and zero-points.  MODE_POW2: signed codes, the group scale is a power of two that the
+// matrix unit applies itself (block-scaled MFMA), so the sum over all of K stays in the MFMA accumulator.
 template <typename OutT, int MF, int KS, int TPW, int MODE>
 __global__ void __launch_bounds__(512, (KS * MF > 16 || MF * TPW > 16) ? 2 : 4) linear_mfma_kernel(
     const uint8_t* __restrict__ x8, int M, int64_t ldx8, const float* __restrict__ s_x,
     const uint8_t* __restrict__ packed, const float* __restrict__ scales, int N, int n_tiles, int C, int cpg, int NG,
     OutT* __restrict__ y, int64_t ldy, int grid_m, int grid_n, const float* __restrict__ w_out, int per_channel) {
-    constexpr bool TWO = MODE == MODE_TWO_LEVEL, ASYM = MODE == MODE_ASYM;
+    constexpr bool TWO = MODE == MODE_TWO_LEVEL, ASYM = MODE == MODE_ASYM, POW2 = MODE == MODE_POW2;
+    constexpr bool IN_MFMA = TWO || POW2;                        // the sum over K stays in the MFMA accumulator
     constexpr int REC = ASYM ? ASYM_RECORD_BYTES : 64;           // bytes of scales (and zero-points) per band and group
     constexpr int NB = WAVES / KS;                               // wavefronts per K-split group, TPW weight bands each
     constexpr int BN = 16 * NB * TPW, BM = 16 * MF;
@@ -206,8 +208,9 @@ __global__ void __launch_bounds__(512, (KS * MF > 16 || MF * TPW > 16) ? 2 : 4) 
                 for (int j = 0; j < TPW; ++j) {
                     const int st = f * TPW + j;                  // step number
                     if (TWO) acc[f][j] = mfma_16x16x128_e4m3(xop, cur.op[j], acc[f][j]);
-                    const v4f p = TWO ? v4f{0.f, 0.f, 0.f, 0.f} : mfma_16x16x128_e4m3(xop, cur.op[j], v4f{0.f, 0.f, 0.f, 0.f});
-                    if (!TWO && st > 0) {
+                    if (POW2) acc[f][j] = mfma_16x16x128_e4m3_scaled(xop, cur.op[j], acc[f][j], E8M0_ONE, e8m0_of(cur.s[j]));
+                    const v4f p = IN_MFMA ? v4f{0.f, 0.f, 0.f, 0.f} : mfma_16x16x128_e4m3(xop, cur.op[j], v4f{0.f, 0.f, 0.f, 0.f});
+                    if (!IN_MFMA && st > 0) {
                         const int fp = (st - 1) / TPW, jp = (st - 1) % TPW;
                         const float sc = fabsf(cur.s[jp]);       // the sign bit is the packer's mark, not part of the scale
                         acc[fp][jp][0] = fmaf(sc, p_prev[0], acc[fp][jp][0]);
@@ -241,11 +244,11 @@ __global__ void __launch_bounds__(512, (KS * MF > 16 || MF * TPW > 16) ? 2 : 4) 
                     p_prev = p;
                     __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);              // LDS reads of the next block
                     __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);              // this step's MFMA
-                    __builtin_amdgcn_sched_group_barrier(0x002, (TWO ? 0 : 4) + (ASYM ? 7 : 4) * PIECES, 0);   // ALU work independent of it
+                    __builtin_amdgcn_sched_group_barrier(0x002, (IN_MFMA ? 0 : 4) + (ASYM ? 7 : 4) * PIECES, 0);   // ALU work independent of it
                     __builtin_amdgcn_sched_barrier(0);
                 }
             }
-            if (!TWO) {
+            if (!IN_MFMA) {
                 const float sc = fabsf(cur.s[TPW - 1]);
                 acc[MF - 1][TPW - 1][0] = fmaf(sc, p_prev[0], acc[MF - 1][TPW - 1][0]);
                 acc[MF - 1][TPW - 1][1] = fmaf(sc, p_prev[1], acc[MF - 1][TPW - 1][1]);
@@ -381,6 +384,8 @@ void launch_one(const LinearArgs& a, dim3 grid, int grid_m, int grid_n, hipStrea
         W4A8_MFMA(MODE_TWO_LEVEL);
     else if (a.mode == MODE_ASYM)
         W4A8_MFMA(MODE_ASYM);
+    else if (a.mode == MODE_POW2)
+        W4A8_MFMA(MODE_POW2);
     else
         W4A8_MFMA(MODE_CODE_EXACT);
 #undef W4A8_MFMA

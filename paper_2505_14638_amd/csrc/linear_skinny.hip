@@ -34,13 +34,14 @@ constexpr int max_threads(int tiles) { return tiles <= 2 ? 1024 : (tiles <= 8 ? 
 // the wavefront's share of K stays in the MFMA accumulator and the output is scaled by s_x * w_out[n] (w_out[0] when
 // per_channel is 0).  MODE_ASYM: unsigned codes with per-group zero-points, the weight operand is the integer
 // code - zero_point, scales as in the code-exact mode; `scales` then points at the 80-byte records of scales and
-// zero-points.
+// zero-points.  MODE_POW2: signed codes, the group scale is a power of two that the matrix unit applies itself
+// (block-scaled MFMA); the sum over the wavefront's share of K stays in the MFMA accumulator.
 template <int MT, int NT, int DEPTH, typename OutT, int MODE>
 __global__ void __launch_bounds__(max_threads(MT * NT)) linear_skinny_kernel(
     const uint8_t* __restrict__ x8, int M, int64_t ldx8, const float* __restrict__ s_x,
     const uint8_t* __restrict__ packed, const float* __restrict__ scales, int N, int n_tiles, int C, int cpg, int NG,
     OutT* __restrict__ y, int64_t ldy, int cpw, const float* __restrict__ w_out, int per_channel) {
-    constexpr bool TWO = MODE == MODE_TWO_LEVEL, ASYM = MODE == MODE_ASYM;
+    constexpr bool TWO = MODE == MODE_TWO_LEVEL, ASYM = MODE == MODE_ASYM, POW2 = MODE == MODE_POW2;
     constexpr int REC = ASYM ? ASYM_RECORD_BYTES : 64;           // bytes of scales (and zero-points) per tile and group
     extern __shared__ float red[];
     const int lane = threadIdx.x & 63;
@@ -73,7 +74,7 @@ __global__ void __launch_bounds__(max_threads(MT * NT)) linear_skinny_kernel(
 #pragma unroll
         for (int j = 0; j < NT; ++j) {
             L.w[j] = *reinterpret_cast<const uint4*>(wbase[j] + woff);
-            if (TWO)                                            // the scale of the channel whose nibbles this lane expands
+            if (TWO || POW2)                                    // the scale of the channel whose nibbles this lane expands
                 L.s[j] = make_float4(*reinterpret_cast<const float*>(sbase[j] + (int64_t)g * REC + i * 4), 0.f, 0.f, 0.f);
             else
                 L.s[j] = *reinterpret_cast<const float4*>(sbase[j] + (int64_t)g * REC + soff);
@@ -125,6 +126,10 @@ __global__ void __launch_bounds__(max_threads(MT * NT)) linear_skinny_kernel(
             for (int mt = 0; mt < MT; ++mt) {
                 if (TWO) {
                     acc[mt][j] = mfma_16x16x128_e4m3(wop, xop[mt], acc[mt][j]);
+                    continue;
+                }
+                if (POW2) {
+                    acc[mt][j] = mfma_16x16x128_e4m3_scaled(wop, xop[mt], acc[mt][j], e8m0_of(s.x), E8M0_ONE);
                     continue;
                 }
                 const v4f p = mfma_16x16x128_e4m3(wop, xop[mt], v4f{0.f, 0.f, 0.f, 0.f});
@@ -201,6 +206,8 @@ int launch_one(const LinearArgs& a, int depth, int waves, hipStream_t st) {
         W4A8_SKINNY(2, MODE_TWO_LEVEL);
     else if (a.mode == MODE_ASYM)
         W4A8_SKINNY(2, MODE_ASYM);
+    else if (a.mode == MODE_POW2)
+        W4A8_SKINNY(2, MODE_POW2);
     else if (depth == DEEP)
         W4A8_SKINNY(DEEP, MODE_CODE_EXACT);
     else

@@ -37,8 +37,10 @@ __device__ __forceinline__ void byte_to_coords(const Geometry& g, int64_t b, int
     }
 }
 
-// one wavefront per (row, group): s = max|W| / 7, or 1 for an all-zero group; padding rows get 0
-__global__ void __launch_bounds__(256) rtn_scales_kernel(const float* __restrict__ w, Geometry g, float* __restrict__ scales) {
+// one wavefront per (row, group): s = max|W| / 7 -- with pow2, the smallest power of two not below that quotient
+// (Sec. 2.2: power-of-two scaling factors) -- or 1 for an all-zero group; padding rows get 0
+__global__ void __launch_bounds__(256) rtn_scales_kernel(const float* __restrict__ w, Geometry g, int pow2,
+                                                         float* __restrict__ scales) {
     const int64_t wid = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
     const int lane = threadIdx.x & 63;
     if (wid >= g.Np * g.NG) return;
@@ -52,7 +54,12 @@ __global__ void __launch_bounds__(256) rtn_scales_kernel(const float* __restrict
     for (int off = 32; off > 0; off >>= 1) amax = fmaxf(amax, __shfl_xor(amax, off, 64));
     if (lane == 0) {
         float s = 0.0f;
-        if (n < g.N) s = (amax == 0.0f) ? 1.0f : amax / 7.0f;
+        if (n < g.N) s = (amax == 0.0f) ? 1.0f : __fdiv_rn(amax, 7.0f);
+        if (pow2 && n < g.N && amax != 0.0f) {
+            int e;
+            const float m = frexpf(s, &e);                       // s = m * 2^e, m in [0.5, 1)
+            s = ldexpf(1.0f, m == 0.5f ? e - 1 : e);
+        }
         scales[scale_index(g, n, grp)] = s;
     }
 }
@@ -238,9 +245,9 @@ int launch_pack_weights(const void* src, w4a8_src kind, const float* src_scales,
     g.tiled = (layout == W4A8_LAYOUT_TILED);
     g.Np = g.tiled ? ((N + 15) / 16) * 16 : N;
     const int64_t n_scales = g.Np * g.NG, n_bytes = g.Np * (K / 2);
-    if (kind == W4A8_SRC_F32_RTN) {
+    if (kind == W4A8_SRC_F32_RTN || kind == W4A8_SRC_F32_RTN_POW2) {
         hipLaunchKernelGGL(rtn_scales_kernel, dim3(blocks_for(n_scales * 64)), dim3(256), 0, st,
-                           static_cast<const float*>(src), g, scales);
+                           static_cast<const float*>(src), g, kind == W4A8_SRC_F32_RTN_POW2 ? 1 : 0, scales);
         if (int e = launch_status()) return e;
         hipLaunchKernelGGL(pack_kernel<true>, dim3(blocks_for(n_bytes)), dim3(256), 0, st, src, g, scales, packed);
     } else {

@@ -192,6 +192,19 @@ __device__ __forceinline__ v4f mfma_16x16x128_e4m3(v8i a, v8i b, v4f c) {
     return __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(a, b, c, 0 /*A: E4M3*/, 0 /*B: E4M3*/, 0, 0, 0, 0);
 }
 
+// The same with block scales (the scaled form of the instruction): every lane supplies one E8M0 byte (2^(byte - 127))
+// per operand for its 32 contraction positions, and the matrix unit multiplies each 32-deep partial sum by
+// 2^(scale_a - 127) * 2^(scale_b - 127) before adding it up -- the power-of-two group scale of a weight band applied
+// inside the instruction (Sec. 2.2: power-of-two scaling factors turn scaling into an exponent adjustment).
+__device__ __forceinline__ v4f mfma_16x16x128_e4m3_scaled(v8i a, v8i b, v4f c, int scale_a, int scale_b) {
+    return __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(a, b, c, 0 /*A: E4M3*/, 0 /*B: E4M3*/, 0 /*byte 0*/, scale_a,
+                                                            0 /*byte 0*/, scale_b);
+}
+
+constexpr int E8M0_ONE = 127;
+// E8M0 byte of a float32 power of two: its exponent field (a mantissa, and the sign, are ignored).
+__device__ __forceinline__ int e8m0_of(float s) { return (int)((__float_as_uint(s) >> 23) & 0xFFu); }
+
 // Global memory -> LDS without staging registers: each lane copies 16 (4) bytes from base + offset (base
 // wave-uniform, offset per lane) to LDS byte address lds_addr + 16 (4) * lane (lds_addr wave-uniform).  Written as
 // assembly so that the compiler's wait-count pass does not treat the copy as an LDS store that every later LDS read

@@ -16,7 +16,8 @@ inline int launch_status() { return hip_status(hipGetLastError()); }
 //   MODE_TWO_LEVEL   signed codes, `scales` = FP8-domain group scales, output scaled by s_x * w_out[n] (w_out[0] when
 //                    per_channel is 0)
 //   MODE_ASYM        unsigned codes, `scales` = the 80-byte records of group scales and zero-points
-enum WeightMode { MODE_CODE_EXACT = 0, MODE_TWO_LEVEL = 1, MODE_ASYM = 2 };
+//   MODE_POW2        signed codes, power-of-two group scales applied by the matrix unit (block-scaled MFMA)
+enum WeightMode { MODE_CODE_EXACT = 0, MODE_TWO_LEVEL = 1, MODE_ASYM = 2, MODE_POW2 = 3 };
 
 // What the launchers of the tiled-layout linear kernels pass down to a launch: the operands of w4a8_linear after
 // validation.

@@ -122,6 +122,21 @@ def test_two_level_validation(L):
     assert d(P + 8, P, 16, 256, 128, P, None) == 6
 
 
+def test_pow2_validation(L):
+    f = L.w4a8_linear_pow2
+    # x8, M, K, ldx8, xs, packed, scales, N, G, y, ydt, ldy, stream
+    assert f(P, 0, 256, 256, P, P, P, 64, 128, P, B.BF16, 64, None) == 0
+    assert f(P, 4, 256, 256, P, P, 0, 64, 128, P, B.BF16, 64, None) == 1
+    assert f(P, 4, 256, 256, P, P, P, 64, 64, P, B.BF16, 64, None) == 3
+    assert f(P, 4, 200, 200, P, P, P, 64, 200, P, B.BF16, 64, None) == 5
+    assert f(P, 4, 256, 256, P, P + 4, P, 64, 128, P, B.BF16, 64, None) == 6
+    p = L.w4a8_pack_weights
+    assert p(P, B.SRC_F32_RTN_POW2, 0, 16, 256, 128, B.LAYOUT_TILED, 0, P, None) == 1
+    assert p(P + 2, B.SRC_F32_RTN_POW2, 0, 16, 256, 128, B.LAYOUT_TILED, P, P, None) == 6
+    assert p(P, 3, 0, 16, 256, 128, B.LAYOUT_TILED, P, P, None) == 4
+    assert L.w4a8_pack_weights_asym(P, B.SRC_F32_RTN_POW2, 0, 0, 16, 256, 128, P, P, None) == 4
+
+
 def test_asym_validation(L):
     assert L.w4a8_asym_params_bytes(40, 384, 128) == 3 * 3 * 80
     assert L.w4a8_asym_params_bytes(40, 384, 384) == 3 * 80
