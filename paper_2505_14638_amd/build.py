@@ -13,6 +13,10 @@ SOURCES = ["api.hip", "quantize_act.hip", "pack_weights.hip", "linear_canonical.
 # packed fp32 instructions are switched off for all device code (scalar fp32 only)
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
+# linear_mfma.hip orders MFMAs, LDS reads and ALU work step by step; the backend's sinking pass otherwise moves the MFMAs
+# of the modes that accumulate inside the matrix unit past the branches of a pass to its end, where all of the pass's
+# activation operands are live at once and spill
+EXTRA_FLAGS = {"linear_mfma.hip": ["-mllvm", "-disable-machine-sink"]}
 
 
 def build(verbose: bool = False) -> str:
@@ -22,7 +26,7 @@ def build(verbose: bool = False) -> str:
     procs = []
     for src in SOURCES:
         obj = os.path.join(CSRC, src.replace(".hip", ".o"))
-        cmd = [hipcc, *FLAGS, "-c", os.path.join(CSRC, src), "-o", obj]
+        cmd = [hipcc, *FLAGS, *EXTRA_FLAGS.get(src, []), "-c", os.path.join(CSRC, src), "-o", obj]
         if verbose:
             print(" ".join(cmd), flush=True)
         procs.append((src, subprocess.Popen(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)))
