@@ -270,8 +270,10 @@ def main():
 
     if not args.no_prefill:
         pcfg = syn.CONFIGS[3]
-        per_shape, tot_flop, tot_sec, tot_bytes = [], 0.0, 0.0, 0
+        per_shape, tot_flop, tot_sec, tot_sec_p2, tot_bytes = [], 0.0, 0.0, 0.0, 0
         for L in layers:
+            # the same codes with every group scale rounded up to a power of two, for the block-scaled variant
+            p2 = [torch.exp2(torch.ceil(torch.log2(sc.abs()))) for (_, sc) in L.sets]
             for m in (512, 2048, 8192):
                 c = Case(3, L, m, dev, pcfg["frac"], pcfg["mult"])
                 c.quantize()
@@ -289,19 +291,39 @@ def main():
                 torch.cuda.synchronize()
                 s = t0.elapsed_time(t1) * 1e-3 / reps
                 flop = 2.0 * m * L.k * L.n
-                per_shape.append({"M": m, "K": L.k, "N": L.n, "us": round(s * 1e6, 2), "tflops": round(flop / s / 1e12, 1)})
+
+                def pow2(i):
+                    B.linear_pow2(c.x8, c.s_x, L.sets[i % len(L.sets)][0], p2[i % len(p2)], L.n, G, out=c.y)
+                for i in range(max(2, reps)):
+                    pow2(i)
+                torch.cuda.synchronize()
+                t0.record()
+                for i in range(reps):
+                    pow2(i)
+                t1.record()
+                torch.cuda.synchronize()
+                s2 = t0.elapsed_time(t1) * 1e-3 / reps
+                per_shape.append({"M": m, "K": L.k, "N": L.n, "us": round(s * 1e6, 2), "tflops": round(flop / s / 1e12, 1),
+                                  "pow2_tflops": round(flop / s2 / 1e12, 1)})
                 tot_flop += flop
                 tot_sec += s
+                tot_sec_p2 += s2
                 tot_bytes += alg_bytes(m, L.k, L.n)
                 del c
+            del p2
         tfl = tot_flop / tot_sec / 1e12
+        tfl2 = tot_flop / tot_sec_p2 / 1e12
         result["prefill"] = {"metric": "W4A8 linear TFLOP/s (prefill sweep, configs[2])", "value": round(tfl, 1),
                              "unit": "TFLOP/s", "shapes": per_shape,
                              "roofline": {"bound": "mfma", "achieved": round(tfl, 1), "peak": FP8_PEAK_TFLOPS,
                                           "unit": "TFLOP/s", "frac": round(tfl / FP8_PEAK_TFLOPS, 4),
                                           "traffic": PREFILL_TRAFFIC_BYTES_PER_LAUNCH,
                                           "alg_bytes_per_launch": tot_bytes // len(per_shape),
-                                          "kernel": "linear_mfma_kernel"}}
+                                          "kernel": "linear_mfma_kernel"},
+                             "pow2_scales": {"metric": "the same sweep through w4a8_linear_pow2 (group scales rounded up "
+                                                       "to powers of two and applied by the block-scaled MFMA)",
+                                             "value": round(tfl2, 1), "unit": "TFLOP/s",
+                                             "frac": round(tfl2 / FP8_PEAK_TFLOPS, 4)}}
 
     if not args.prefill_only:
         hbm, copy, mfma = measured_ceilings(dev)
