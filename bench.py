@@ -37,9 +37,9 @@ G = 128
 # (profiles/linear_skinny_decode_sweep_hbm_traffic.txt): FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, the factors that make the
 # same counters read 1 GiB + 1 GiB for a plain 1 GiB device-to-device copy.  Counters cannot be read from inside a
 # timed run, so the figure is carried here and reported only for the workload it was measured on.
-SKINNY_TRAFFIC_BYTES_PER_LAUNCH = {4: 29.574e6}          # by --copies
+SKINNY_TRAFFIC_BYTES_PER_LAUNCH = {4: 29.584e6}          # by --copies
 # same for the prefill sweep (profiles/linear_mfma_prefill_sweep_hbm_traffic.txt): mean over its 12 shapes, one launch each
-PREFILL_TRAFFIC_BYTES_PER_LAUNCH = 410.5e6
+PREFILL_TRAFFIC_BYTES_PER_LAUNCH = 436.6e6
 
 
 def alg_bytes(m, k, n, out_bytes=2):
@@ -208,6 +208,7 @@ def main():
     ap.add_argument("--no-prefill", action="store_true")
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--no-block", action="store_true")
+    ap.add_argument("--no-pow2", action="store_true", help="profiling aid: leave the power-of-two leg out of the prefill sweep")
     ap.add_argument("--prefill-only", action="store_true", help="profiling aid: run only the prefill sweep")
     ap.add_argument("--eager", action="store_true", help="profiling aid: launch the decode sweep kernel by kernel "
                     "instead of replaying HIP graphs (for hardware-counter runs)")
@@ -294,36 +295,40 @@ def main():
 
                 def pow2(i):
                     B.linear_pow2(c.x8, c.s_x, L.sets[i % len(L.sets)][0], p2[i % len(p2)], L.n, G, out=c.y)
-                for i in range(max(2, reps)):
-                    pow2(i)
-                torch.cuda.synchronize()
-                t0.record()
-                for i in range(reps):
-                    pow2(i)
-                t1.record()
-                torch.cuda.synchronize()
-                s2 = t0.elapsed_time(t1) * 1e-3 / reps
-                per_shape.append({"M": m, "K": L.k, "N": L.n, "us": round(s * 1e6, 2), "tflops": round(flop / s / 1e12, 1),
-                                  "pow2_tflops": round(flop / s2 / 1e12, 1)})
+                s2 = s
+                if not args.no_pow2:
+                    for i in range(max(2, reps)):
+                        pow2(i)
+                    torch.cuda.synchronize()
+                    t0.record()
+                    for i in range(reps):
+                        pow2(i)
+                    t1.record()
+                    torch.cuda.synchronize()
+                    s2 = t0.elapsed_time(t1) * 1e-3 / reps
+                per_shape.append({"M": m, "K": L.k, "N": L.n, "us": round(s * 1e6, 2), "tflops": round(flop / s / 1e12, 1)})
+                if not args.no_pow2:
+                    per_shape[-1]["pow2_tflops"] = round(flop / s2 / 1e12, 1)
                 tot_flop += flop
                 tot_sec += s
-                tot_sec_p2 += s2
+                tot_sec_p2 += 0.0 if args.no_pow2 else s2
                 tot_bytes += alg_bytes(m, L.k, L.n)
                 del c
             del p2
         tfl = tot_flop / tot_sec / 1e12
-        tfl2 = tot_flop / tot_sec_p2 / 1e12
+        tfl2 = tot_flop / tot_sec_p2 / 1e12 if tot_sec_p2 > 0 else 0.0
         result["prefill"] = {"metric": "W4A8 linear TFLOP/s (prefill sweep, configs[2])", "value": round(tfl, 1),
                              "unit": "TFLOP/s", "shapes": per_shape,
                              "roofline": {"bound": "mfma", "achieved": round(tfl, 1), "peak": FP8_PEAK_TFLOPS,
                                           "unit": "TFLOP/s", "frac": round(tfl / FP8_PEAK_TFLOPS, 4),
                                           "traffic": PREFILL_TRAFFIC_BYTES_PER_LAUNCH,
                                           "alg_bytes_per_launch": tot_bytes // len(per_shape),
-                                          "kernel": "linear_mfma_kernel"},
-                             "pow2_scales": {"metric": "the same sweep through w4a8_linear_pow2 (group scales rounded up "
+                                          "kernel": "linear_mfma_kernel"}}
+        if not args.no_pow2:
+            result["prefill"]["pow2_scales"] = {"metric": "the same sweep through w4a8_linear_pow2 (group scales rounded up "
                                                        "to powers of two and applied by the block-scaled MFMA)",
                                              "value": round(tfl2, 1), "unit": "TFLOP/s",
-                                             "frac": round(tfl2 / FP8_PEAK_TFLOPS, 4)}}
+                                             "frac": round(tfl2 / FP8_PEAK_TFLOPS, 4)}
 
     if not args.prefill_only:
         hbm, copy, mfma = measured_ceilings(dev)
