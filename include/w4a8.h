@@ -221,6 +221,23 @@ int w4a8_dequant_weights_asym(const uint8_t* packed_dev, const void* params_dev,
 int w4a8_silu_mul(const void* gu_dev, int64_t M, int64_t F, int64_t ldgu, void* h_dev, int64_t ldh, void* stream);
 
 /*
+ * Fused forms for a stack of quantized layers (all linear layers of a block are quantized, Sec. 4.1, so the tensor
+ * between two of them is only ever read by the next layer's activation quantization, Eq. 13).  Both produce, byte
+ * for byte, what the unfused sequence produces -- the bf16 tensor is formed in registers, rounded to bf16 and then
+ * quantized with the NEXT layer's static scale -- without writing the bf16 tensor or launching the quantize kernel.
+ *   w4a8_linear_fp8_out     = w4a8_linear (W4A8_LAYOUT_TILED, bf16 output) followed by w4a8_quantize_act of that
+ *                             output with *y_scale_dev; y8_dev receives E4M3 bytes [M, N], row stride ldy8 bytes.
+ *                             Arguments otherwise as in w4a8_linear.
+ *   w4a8_silu_mul_quantize  = w4a8_silu_mul followed by w4a8_quantize_act of h with *scale_dev; h8_dev receives E4M3
+ *                             bytes [M, F], row stride ldh8 bytes.
+ */
+int w4a8_linear_fp8_out(const uint8_t* x8_dev, int64_t M, int64_t K, int64_t ldx8, const float* x_scale_dev,
+                        const uint8_t* packed_dev, const float* w_scales_dev, int64_t N, int32_t group_size,
+                        const float* y_scale_dev, uint8_t* y8_dev, int64_t ldy8, void* stream);
+int w4a8_silu_mul_quantize(const void* gu_dev, int64_t M, int64_t F, int64_t ldgu, const float* scale_dev,
+                           uint8_t* h8_dev, int64_t ldh8, void* stream);
+
+/*
  * Measurement aids (not part of the layer): the two hardware ceilings the kernels are compared with, measured
  * on the device at hand.  Time the calls with events on `stream`.
  *   w4a8_probe_stream_read  loads every 16 bytes of buf_dev[0 .. bytes) once; bytes / time is the achievable HBM

@@ -43,6 +43,9 @@ SIGNATURES = {
                                   _c_i64, _c_vp]),
     "w4a8_dequant_weights_asym": (_c_i32, [_c_vp, _c_vp, _c_i64, _c_i64, _c_i32, _c_vp, _c_vp]),
     "w4a8_silu_mul": (_c_i32, [_c_vp, _c_i64, _c_i64, _c_i64, _c_vp, _c_i64, _c_vp]),
+    "w4a8_linear_fp8_out": (_c_i32, [_c_vp, _c_i64, _c_i64, _c_i64, _c_vp, _c_vp, _c_vp, _c_i64, _c_i32, _c_vp, _c_vp,
+                                     _c_i64, _c_vp]),
+    "w4a8_silu_mul_quantize": (_c_i32, [_c_vp, _c_i64, _c_i64, _c_i64, _c_vp, _c_vp, _c_i64, _c_vp]),
     "w4a8_probe_stream_read": (_c_i32, [_c_vp, _c_sz, _c_vp, _c_vp]),
     "w4a8_probe_mfma_e4m3": (_c_i32, [_c_i32, _c_vp, _c_vp]),
     "w4a8_probe_mfma_flop": (ctypes.c_double, [_c_i32]),
@@ -247,6 +250,31 @@ def silu_mul(gu: torch.Tensor, out: torch.Tensor | None = None) -> torch.Tensor:
         out = torch.empty((m, f), dtype=torch.bfloat16, device=gu.device)
     _check(lib().w4a8_silu_mul(gu.data_ptr(), m, f, gu.stride(0) if m > 1 else max(f2, gu.stride(0)), out.data_ptr(),
                                out.stride(0) if m > 1 else max(f, out.stride(0)), _stream()), "w4a8_silu_mul")
+    return out
+
+
+def linear_fp8_out(x8, x_scale, packed, w_scales, n, group_size, y_scale, out=None):
+    """w4a8_linear_fp8_out: the layer's bf16 output quantized with `y_scale` (the next layer's static scale)."""
+    m, k = x8.shape
+    assert x8.dtype == torch.uint8 and x8.stride(1) == 1 and y_scale.dtype == torch.float32
+    if out is None:
+        out = torch.empty((m, n), dtype=torch.uint8, device=x8.device)
+    _check(lib().w4a8_linear_fp8_out(x8.data_ptr(), m, k, x8.stride(0) if m > 1 else max(k, x8.stride(0)),
+                                     x_scale.data_ptr(), packed.data_ptr(), w_scales.data_ptr(), n, group_size,
+                                     y_scale.data_ptr(), out.data_ptr(), out.stride(0) if m > 1 else max(n, out.stride(0)),
+                                     _stream()), "w4a8_linear_fp8_out")
+    return out
+
+
+def silu_mul_quantize(gu: torch.Tensor, scale: torch.Tensor, out: torch.Tensor | None = None) -> torch.Tensor:
+    m, f2 = gu.shape
+    f = f2 // 2
+    assert gu.dtype == torch.bfloat16 and gu.stride(1) == 1 and f2 == 2 * f and scale.dtype == torch.float32
+    if out is None:
+        out = torch.empty((m, f), dtype=torch.uint8, device=gu.device)
+    _check(lib().w4a8_silu_mul_quantize(gu.data_ptr(), m, f, gu.stride(0) if m > 1 else max(f2, gu.stride(0)),
+                                        scale.data_ptr(), out.data_ptr(), out.stride(0) if m > 1 else max(f, out.stride(0)),
+                                        _stream()), "w4a8_silu_mul_quantize")
     return out
 
 

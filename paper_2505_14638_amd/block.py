@@ -5,6 +5,10 @@ layer, SiLU*mul); PyTorch provides buffers and views.  The O projection reads th
 output (a strided view -- the quantizer takes a row stride), standing in for attention, which is not part of the
 quantized-linear path.  Intermediates are bf16, each linear layer's input is quantized to FP8 with its own static
 per-tensor scale (Eq. 13; all linear layers of a block are quantized, Sec. 4.1).
+
+`fused=True` runs the same computation with the quantization of each intermediate folded into the kernel that produces
+it (w4a8_linear_fp8_out for QKV and O, w4a8_silu_mul_quantize for SiLU*mul): six launches instead of nine, the same
+bytes at every layer input and the same block output.
 """
 from __future__ import annotations
 
@@ -16,8 +20,9 @@ LAYERS = ("qkv", "o", "gate_up", "down")
 
 
 class DecoderBlockLinears:
-    def __init__(self, hidden: int, ffn: int, qkv_out: int, group_size: int = 128, device: str = "cuda:0"):
-        self.hidden, self.ffn, self.group_size, self.device = hidden, ffn, group_size, device
+    def __init__(self, hidden: int, ffn: int, qkv_out: int, group_size: int = 128, device: str = "cuda:0",
+                 fused: bool = False):
+        self.hidden, self.ffn, self.group_size, self.device, self.fused = hidden, ffn, group_size, device, fused
         self.dims = {"qkv": (hidden, qkv_out), "o": (hidden, hidden), "gate_up": (hidden, 2 * ffn), "down": (ffn, hidden)}
         self.weights = {}
         self.scales_x = {}
@@ -48,8 +53,26 @@ class DecoderBlockLinears:
         B.linear(x8, self.scales_x[name], packed, scales, n, self.group_size, B.LAYOUT_TILED, out=y)
         return y
 
+    def _forward_fused(self, x: torch.Tensor, keep: dict | None) -> torch.Tensor:
+        m, g, sx, w = x.shape[0], self.group_size, self.scales_x, self.weights
+        x8 = B.quantize_act(x, sx["qkv"], out=self._buf(("qkv", "x8", m), (m, self.hidden), torch.uint8))
+        qkv8 = B.linear_fp8_out(x8, sx["qkv"], *w["qkv"], self.dims["qkv"][1], g, sx["o"],
+                                out=self._buf(("qkv", "y8", m), (m, self.dims["qkv"][1]), torch.uint8))
+        o8 = B.linear_fp8_out(qkv8[:, :self.hidden], sx["o"], *w["o"], self.hidden, g, sx["gate_up"],
+                              out=self._buf(("o", "y8", m), (m, self.hidden), torch.uint8))
+        gu = B.linear(o8, sx["gate_up"], *w["gate_up"], 2 * self.ffn, g, B.LAYOUT_TILED,
+                      out=self._buf(("gate_up", "y", m), (m, 2 * self.ffn), torch.bfloat16))
+        h8 = B.silu_mul_quantize(gu, sx["down"], out=self._buf(("h8", m), (m, self.ffn), torch.uint8))
+        y = B.linear(h8, sx["down"], *w["down"], self.hidden, g, B.LAYOUT_TILED,
+                     out=self._buf(("down", "y", m), (m, self.hidden), torch.bfloat16))
+        if keep is not None:
+            keep.update(qkv_x8=x8, o_x8=qkv8[:, :self.hidden], gate_up_x8=o8, gate_up=gu, down_x8=h8, down=y)
+        return y
+
     def forward(self, x: torch.Tensor, keep: dict | None = None) -> torch.Tensor:
         """x: bf16 [M, hidden] on the device.  `keep`, if given, receives every intermediate tensor."""
+        if self.fused:
+            return self._forward_fused(x, keep)
         m = x.shape[0]
         qkv = self._linear("qkv", x, m)
         o = self._linear("o", qkv[:, :self.hidden], m)

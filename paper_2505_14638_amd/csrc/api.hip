@@ -29,13 +29,13 @@ int check_linear(const uint8_t* x8, int64_t M, int64_t K, int64_t ldx8, const fl
                  const float* ws, int64_t N, int32_t G, int layout, void* y, int ydt, int64_t ldy) {
     if (M < 0 || M > DIM_MAX) return W4A8_ERR_SHAPE;
     if (int e = check_weight_shape(N, K, G, layout)) return e;
-    if (!valid_dtype(ydt)) return W4A8_ERR_DTYPE;
+    if (!valid_dtype(ydt) && ydt != YDT_E4M3) return W4A8_ERR_DTYPE;   // callers with a public y_dtype check it first
     if (ldx8 < K || ldy < N) return W4A8_ERR_SHAPE;
     if (!x8 || !xs || !packed || !ws || !y) return W4A8_ERR_NULL;
     if (layout == W4A8_LAYOUT_TILED) {
         if (!aligned16(x8) || !aligned16(packed) || !aligned16(ws) || (ldx8 & 15)) return W4A8_ERR_ALIGN;
     }
-    if (reinterpret_cast<uintptr_t>(y) % (ydt == W4A8_F32 ? 4 : 2)) return W4A8_ERR_ALIGN;
+    if (reinterpret_cast<uintptr_t>(y) % (ydt == W4A8_F32 ? 4 : ydt == W4A8_BF16 ? 2 : 1)) return W4A8_ERR_ALIGN;
     return W4A8_OK;
 }
 
@@ -87,6 +87,7 @@ int w4a8_linear(const uint8_t* x8_dev, int64_t M, int64_t K, int64_t ldx8, const
                 size_t workspace_bytes, void* stream) {
     (void)workspace_dev;
     (void)workspace_bytes;
+    if (!valid_dtype(y_dtype)) return W4A8_ERR_DTYPE;
     if (int e = check_linear(x8_dev, M, K, ldx8, x_scale_dev, packed_dev, w_scales_dev, N, group_size, layout, y_dev,
                              y_dtype, ldy))
         return e;
@@ -101,15 +102,16 @@ int w4a8_linear(const uint8_t* x8_dev, int64_t M, int64_t K, int64_t ldx8, const
     const bool deep_narrow = K >= 8192 && N <= 8192;
     if (M <= 32 || (M <= 64 && deep_narrow))
         return launch_linear_skinny(x8_dev, M, K, ldx8, x_scale_dev, packed_dev, w_scales_dev, N, group_size, y_dev,
-                                    y_dtype, ldy, 0, 0, 0, nullptr, 0, MODE_CODE_EXACT, st);
+                                    y_dtype, ldy, 0, 0, 0, nullptr, 0, MODE_CODE_EXACT, nullptr, st);
     return launch_linear_mfma_tiled(x8_dev, M, K, ldx8, x_scale_dev, packed_dev, w_scales_dev, N, group_size, y_dev,
-                                    y_dtype, ldy, 0, 0, 0, nullptr, 0, MODE_CODE_EXACT, st);
+                                    y_dtype, ldy, 0, 0, 0, nullptr, 0, MODE_CODE_EXACT, nullptr, st);
 }
 
 int w4a8_linear_two_level(const uint8_t* x8_dev, int64_t M, int64_t K, int64_t ldx8, const float* x_scale_dev,
                           const uint8_t* packed_dev, const float* w_scales8_dev, const float* w_out_scales_dev,
                           int32_t per_channel, int64_t N, int32_t group_size, void* y_dev, w4a8_dtype y_dtype,
                           int64_t ldy, void* stream) {
+    if (!valid_dtype(y_dtype)) return W4A8_ERR_DTYPE;
     if (int e = check_linear(x8_dev, M, K, ldx8, x_scale_dev, packed_dev, w_scales8_dev, N, group_size,
                              W4A8_LAYOUT_TILED, y_dev, y_dtype, ldy))
         return e;
@@ -121,15 +123,16 @@ int w4a8_linear_two_level(const uint8_t* x8_dev, int64_t M, int64_t K, int64_t l
     const bool deep_narrow = K >= 8192 && N <= 8192;             // same kernel choice as w4a8_linear
     if (M <= 32 || (M <= 64 && deep_narrow))
         return launch_linear_skinny(x8_dev, M, K, ldx8, x_scale_dev, packed_dev, w_scales8_dev, N, group_size, y_dev,
-                                    y_dtype, ldy, 0, 0, 0, w_out_scales_dev, per_channel, MODE_TWO_LEVEL, st);
+                                    y_dtype, ldy, 0, 0, 0, w_out_scales_dev, per_channel, MODE_TWO_LEVEL, nullptr, st);
     return launch_linear_mfma_tiled(x8_dev, M, K, ldx8, x_scale_dev, packed_dev, w_scales8_dev, N, group_size, y_dev,
-                                    y_dtype, ldy, 0, 0, 0, w_out_scales_dev, per_channel, MODE_TWO_LEVEL, st);
+                                    y_dtype, ldy, 0, 0, 0, w_out_scales_dev, per_channel, MODE_TWO_LEVEL, nullptr, st);
 }
 
 int w4a8_linear_variant(const uint8_t* x8_dev, int64_t M, int64_t K, int64_t ldx8, const float* x_scale_dev,
                         const uint8_t* packed_dev, const float* w_scales_dev, int64_t N, int32_t group_size,
                         void* y_dev, w4a8_dtype y_dtype, int64_t ldy, int32_t path, int32_t param0, int32_t param1,
                         void* stream) {
+    if (!valid_dtype(y_dtype)) return W4A8_ERR_DTYPE;
     if (int e = check_linear(x8_dev, M, K, ldx8, x_scale_dev, packed_dev, w_scales_dev, N, group_size,
                              W4A8_LAYOUT_TILED, y_dev, y_dtype, ldy))
         return e;
@@ -138,11 +141,11 @@ int w4a8_linear_variant(const uint8_t* x8_dev, int64_t M, int64_t K, int64_t ldx
     if (path == 0) {
         if (M > 64 || param0 < 0 || param1 < 0 || (param1 & 0xFF) > 16) return W4A8_ERR_SHAPE;
         return launch_linear_skinny(x8_dev, M, K, ldx8, x_scale_dev, packed_dev, w_scales_dev, N, group_size, y_dev,
-                                    y_dtype, ldy, param0, param1 & 0xFF, param1 >> 8, nullptr, 0, MODE_CODE_EXACT, st);
+                                    y_dtype, ldy, param0, param1 & 0xFF, param1 >> 8, nullptr, 0, MODE_CODE_EXACT, nullptr, st);
     }
     if (path == 1)
         return launch_linear_mfma_tiled(x8_dev, M, K, ldx8, x_scale_dev, packed_dev, w_scales_dev, N, group_size, y_dev,
-                                        y_dtype, ldy, param0, param1 & 0xFF, param1 >> 8, nullptr, 0, MODE_CODE_EXACT, st);
+                                        y_dtype, ldy, param0, param1 & 0xFF, param1 >> 8, nullptr, 0, MODE_CODE_EXACT, nullptr, st);
     return W4A8_ERR_SHAPE;
 }
 
@@ -166,6 +169,7 @@ int w4a8_dequant_weights_two_level(const uint8_t* packed_dev, const float* w_sca
 int w4a8_linear_pow2(const uint8_t* x8_dev, int64_t M, int64_t K, int64_t ldx8, const float* x_scale_dev,
                      const uint8_t* packed_dev, const float* w_scales_dev, int64_t N, int32_t group_size, void* y_dev,
                      w4a8_dtype y_dtype, int64_t ldy, void* stream) {
+    if (!valid_dtype(y_dtype)) return W4A8_ERR_DTYPE;
     if (int e = check_linear(x8_dev, M, K, ldx8, x_scale_dev, packed_dev, w_scales_dev, N, group_size, W4A8_LAYOUT_TILED,
                              y_dev, y_dtype, ldy))
         return e;
@@ -174,9 +178,28 @@ int w4a8_linear_pow2(const uint8_t* x8_dev, int64_t M, int64_t K, int64_t ldx8, 
     const bool deep_narrow = K >= 8192 && N <= 8192;             // same kernel choice as w4a8_linear
     if (M <= 32 || (M <= 64 && deep_narrow))
         return launch_linear_skinny(x8_dev, M, K, ldx8, x_scale_dev, packed_dev, w_scales_dev, N, group_size, y_dev,
-                                    y_dtype, ldy, 0, 0, 0, nullptr, 0, MODE_POW2, st);
+                                    y_dtype, ldy, 0, 0, 0, nullptr, 0, MODE_POW2, nullptr, st);
     return launch_linear_mfma_tiled(x8_dev, M, K, ldx8, x_scale_dev, packed_dev, w_scales_dev, N, group_size, y_dev,
-                                    y_dtype, ldy, 0, 0, 0, nullptr, 0, MODE_POW2, st);
+                                    y_dtype, ldy, 0, 0, 0, nullptr, 0, MODE_POW2, nullptr, st);
+}
+
+int w4a8_linear_fp8_out(const uint8_t* x8_dev, int64_t M, int64_t K, int64_t ldx8, const float* x_scale_dev,
+                        const uint8_t* packed_dev, const float* w_scales_dev, int64_t N, int32_t group_size,
+                        const float* y_scale_dev, uint8_t* y8_dev, int64_t ldy8, void* stream) {
+    if (int e = check_linear(x8_dev, M, K, ldx8, x_scale_dev, packed_dev, w_scales_dev, N, group_size, W4A8_LAYOUT_TILED,
+                             y8_dev, YDT_E4M3, ldy8))
+        return e;
+    if (!y_scale_dev) return W4A8_ERR_NULL;
+    if (reinterpret_cast<uintptr_t>(y_scale_dev) % 4) return W4A8_ERR_ALIGN;
+    if (M == 0) return W4A8_OK;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const w4a8_dtype ydt = static_cast<w4a8_dtype>(YDT_E4M3);
+    const bool deep_narrow = K >= 8192 && N <= 8192;             // same kernel choice as w4a8_linear
+    if (M <= 32 || (M <= 64 && deep_narrow))
+        return launch_linear_skinny(x8_dev, M, K, ldx8, x_scale_dev, packed_dev, w_scales_dev, N, group_size, y8_dev, ydt,
+                                    ldy8, 0, 0, 0, nullptr, 0, MODE_CODE_EXACT, y_scale_dev, st);
+    return launch_linear_mfma_tiled(x8_dev, M, K, ldx8, x_scale_dev, packed_dev, w_scales_dev, N, group_size, y8_dev, ydt,
+                                    ldy8, 0, 0, 0, nullptr, 0, MODE_CODE_EXACT, y_scale_dev, st);
 }
 
 size_t w4a8_asym_params_bytes(int64_t N, int64_t K, int32_t group_size) {
@@ -202,6 +225,7 @@ int w4a8_linear_asym(const uint8_t* x8_dev, int64_t M, int64_t K, int64_t ldx8, 
                      const uint8_t* packed_dev, const void* params_dev, int64_t N, int32_t group_size, void* y_dev,
                      w4a8_dtype y_dtype, int64_t ldy, void* stream) {
     const float* params = static_cast<const float*>(params_dev);
+    if (!valid_dtype(y_dtype)) return W4A8_ERR_DTYPE;
     if (int e = check_linear(x8_dev, M, K, ldx8, x_scale_dev, packed_dev, params, N, group_size, W4A8_LAYOUT_TILED, y_dev,
                              y_dtype, ldy))
         return e;
@@ -210,9 +234,9 @@ int w4a8_linear_asym(const uint8_t* x8_dev, int64_t M, int64_t K, int64_t ldx8, 
     const bool deep_narrow = K >= 8192 && N <= 8192;             // same kernel choice as w4a8_linear
     if (M <= 32 || (M <= 64 && deep_narrow))
         return launch_linear_skinny(x8_dev, M, K, ldx8, x_scale_dev, packed_dev, params, N, group_size, y_dev, y_dtype, ldy,
-                                    0, 0, 0, nullptr, 0, MODE_ASYM, st);
+                                    0, 0, 0, nullptr, 0, MODE_ASYM, nullptr, st);
     return launch_linear_mfma_tiled(x8_dev, M, K, ldx8, x_scale_dev, packed_dev, params, N, group_size, y_dev, y_dtype, ldy,
-                                    0, 0, 0, nullptr, 0, MODE_ASYM, st);
+                                    0, 0, 0, nullptr, 0, MODE_ASYM, nullptr, st);
 }
 
 int w4a8_dequant_weights_asym(const uint8_t* packed_dev, const void* params_dev, int64_t N, int64_t K, int32_t group_size,
@@ -229,7 +253,16 @@ int w4a8_silu_mul(const void* gu_dev, int64_t M, int64_t F, int64_t ldgu, void* 
     if (!gu_dev || !h_dev) return W4A8_ERR_NULL;
     if (reinterpret_cast<uintptr_t>(gu_dev) % 2 || reinterpret_cast<uintptr_t>(h_dev) % 2) return W4A8_ERR_ALIGN;
     if (M == 0) return W4A8_OK;
-    return launch_silu_mul(gu_dev, M, F, ldgu, h_dev, ldh, static_cast<hipStream_t>(stream));
+    return launch_silu_mul(gu_dev, M, F, ldgu, h_dev, ldh, nullptr, static_cast<hipStream_t>(stream));
+}
+
+int w4a8_silu_mul_quantize(const void* gu_dev, int64_t M, int64_t F, int64_t ldgu, const float* scale_dev,
+                           uint8_t* h8_dev, int64_t ldh8, void* stream) {
+    if (M < 0 || F < 1 || M > DIM_MAX || F > DIM_MAX || ldgu < 2 * F || ldh8 < F) return W4A8_ERR_SHAPE;
+    if (!gu_dev || !h8_dev || !scale_dev) return W4A8_ERR_NULL;
+    if (reinterpret_cast<uintptr_t>(gu_dev) % 2 || reinterpret_cast<uintptr_t>(scale_dev) % 4) return W4A8_ERR_ALIGN;
+    if (M == 0) return W4A8_OK;
+    return launch_silu_mul(gu_dev, M, F, ldgu, h8_dev, ldh8, scale_dev, static_cast<hipStream_t>(stream));
 }
 
 const char* w4a8_status_string(int status) {

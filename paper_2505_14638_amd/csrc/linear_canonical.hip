@@ -38,7 +38,7 @@ __global__ void __launch_bounds__(256) linear_canonical_kernel(const uint8_t* __
     }
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) acc += __shfl_xor(acc, off, 64);
-    if (lane == 0) y[m * ldy + n] = OutCast<OutT>::cast(*s_x * acc);
+    if (lane == 0) y[m * ldy + n] = OutCast<OutT>::cast(*s_x * acc, 1.0f);
 }
 
 }  // namespace

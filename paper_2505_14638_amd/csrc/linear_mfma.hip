@@ -48,7 +48,8 @@ template <typename OutT, int MF, int KS, int TPW, int MODE>
 __global__ void __launch_bounds__(512, (KS * MF > 16 || MF * TPW > 16) ? 2 : 4) linear_mfma_kernel(
     const uint8_t* __restrict__ x8, int M, int64_t ldx8, const float* __restrict__ s_x,
     const uint8_t* __restrict__ packed, const float* __restrict__ scales, int N, int n_tiles, int C, int cpg, int NG,
-    OutT* __restrict__ y, int64_t ldy, int grid_m, int grid_n, const float* __restrict__ w_out, int per_channel) {
+    OutT* __restrict__ y, int64_t ldy, int grid_m, int grid_n, const float* __restrict__ w_out, int per_channel,
+    const float* __restrict__ y_scale) {
     constexpr bool TWO = MODE == MODE_TWO_LEVEL, ASYM = MODE == MODE_ASYM, POW2 = MODE == MODE_POW2;
     constexpr bool IN_MFMA = TWO || POW2;                        // the sum over K stays in the MFMA accumulator
     constexpr int REC = ASYM ? ASYM_RECORD_BYTES : 64;           // bytes of scales (and zero-points) per band and group
@@ -329,6 +330,7 @@ __global__ void __launch_bounds__(512, (KS * MF > 16 || MF * TPW > 16) ? 2 : 4) 
     // Epilogue.  Result lane: channel = lane % 16 of the band, tokens 4*kq .. 4*kq+3 of block f.  The workgroup turns
     // FR 16-token slabs at a time into row-major order in LDS and stores whole BN-channel row segments.
     const float sx = *s_x;
+    const float yq = (sizeof(OutT) == 1) ? *y_scale : 1.0f;      // FP8 output: the next layer's activation scale
     float so[TPW];                                               // output scale of the lane's channel of each band
 #pragma unroll
     for (int j = 0; j < TPW; ++j) {
@@ -351,7 +353,7 @@ __global__ void __launch_bounds__(512, (KS * MF > 16 || MF * TPW > 16) ? 2 : 4) 
 #pragma unroll
                         for (int r = 0; r < 4; ++r)
                             slab[(ff * 16 + 4 * kq + r) * RS + (band * TPW + j) * 16 + i] =
-                                OutCast<OutT>::cast(so[j] * acc[(f0 + ff < MF) ? f0 + ff : 0][j][r]);
+                                OutCast<OutT>::cast(so[j] * acc[(f0 + ff < MF) ? f0 + ff : 0][j][r], yq);
                 }
             }
         }
@@ -379,7 +381,11 @@ void launch_one(const LinearArgs& a, dim3 grid, int grid_m, int grid_n, hipStrea
 #define W4A8_MFMA(MODEV)                                                                                                   \
     hipLaunchKernelGGL((linear_mfma_kernel<OutT, MF, KS, TPW, MODEV>), grid, dim3(WAVES * 64), 0, st, a.x8, a.M, a.ldx8, a.s_x, \
                        a.packed, a.scales, a.N, a.n_tiles, a.C, a.cpg, a.NG, static_cast<OutT*>(a.y), a.ldy, grid_m, grid_n,   \
-                       a.w_out, a.per_channel)
+                       a.w_out, a.per_channel, a.y_scale)
+    if (sizeof(OutT) == 1) {                                     // FP8 output exists for the code-exact mode only
+        W4A8_MFMA(MODE_CODE_EXACT);
+        return;
+    }
     if (a.mode == MODE_TWO_LEVEL)
         W4A8_MFMA(MODE_TWO_LEVEL);
     else if (a.mode == MODE_ASYM)
@@ -398,7 +404,8 @@ void launch_one(const LinearArgs& a, dim3 grid, int grid_m, int grid_n, hipStrea
 int launch_linear_mfma_tiled(const uint8_t* x8, int64_t M, int64_t K, int64_t ldx8, const float* s_x,
                              const uint8_t* packed, const float* scales, int64_t N, int32_t G, void* y,
                              w4a8_dtype ydt, int64_t ldy, int mf, int ks, int tpw, const float* w_out, int per_channel,
-                             int mode, hipStream_t st) {
+                             int mode, const float* y_scale, hipStream_t st) {
+    if ((int)ydt == YDT_E4M3 && (mode != MODE_CODE_EXACT || !y_scale)) return W4A8_ERR_DTYPE;
     if (!(mf == 0 || mf == 4 || mf == 8 || mf == 16) || !(ks == 0 || ks == 1 || ks == 2 || ks == 4) || tpw < 0 || tpw > 2)
         return W4A8_ERR_SHAPE;
     const int C = (int)(K / 128), cpg = G / 128, NG = (int)(K / G);
@@ -437,13 +444,15 @@ int launch_linear_mfma_tiled(const uint8_t* x8, int64_t M, int64_t K, int64_t ld
     if (total > (1 << 30)) return W4A8_ERR_SHAPE;
     if (ldx8 >= (1 << 24)) return W4A8_ERR_SHAPE;               // 32-bit activation offsets inside a token block
     const dim3 grid((unsigned)((total + XCDS - 1) / XCDS * XCDS));
-    const LinearArgs a{x8, (int)M, ldx8, s_x, packed, scales, (int)N, n_tiles, C, cpg, NG, y, ldy, w_out, per_channel, mode};
+    const LinearArgs a{x8, (int)M, ldx8, s_x, packed, scales, (int)N, n_tiles, C, cpg, NG, y, ldy, w_out, per_channel, mode, y_scale};
     bool launched = false;
 #define W4A8_CASE(MFV, KSV, TPV)                                              \
     if (mf == MFV && ks == KSV && tpw == TPV) {                               \
         launched = true;                                                      \
         if (ydt == W4A8_F32)                                                  \
             launch_one<float, MFV, KSV, TPV>(a, grid, grid_m, grid_n, st);    \
+        else if ((int)ydt == YDT_E4M3)                                        \
+            launch_one<uint8_t, MFV, KSV, TPV>(a, grid, grid_m, grid_n, st);  \
         else                                                                  \
             launch_one<uint16_t, MFV, KSV, TPV>(a, grid, grid_m, grid_n, st); \
     }

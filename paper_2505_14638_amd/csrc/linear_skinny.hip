@@ -40,7 +40,8 @@ template <int MT, int NT, int DEPTH, typename OutT, int MODE>
 __global__ void __launch_bounds__(max_threads(MT * NT)) linear_skinny_kernel(
     const uint8_t* __restrict__ x8, int M, int64_t ldx8, const float* __restrict__ s_x,
     const uint8_t* __restrict__ packed, const float* __restrict__ scales, int N, int n_tiles, int C, int cpg, int NG,
-    OutT* __restrict__ y, int64_t ldy, int cpw, const float* __restrict__ w_out, int per_channel) {
+    OutT* __restrict__ y, int64_t ldy, int cpw, const float* __restrict__ w_out, int per_channel,
+    const float* __restrict__ y_scale) {
     constexpr bool TWO = MODE == MODE_TWO_LEVEL, ASYM = MODE == MODE_ASYM, POW2 = MODE == MODE_POW2;
     constexpr int REC = ASYM ? ASYM_RECORD_BYTES : 64;           // bytes of scales (and zero-points) per tile and group
     extern __shared__ float red[];
@@ -180,6 +181,7 @@ __global__ void __launch_bounds__(max_threads(MT * NT)) linear_skinny_kernel(
     __syncthreads();
 
     const float sx = *s_x;
+    const float yq = (sizeof(OutT) == 1) ? *y_scale : 1.0f;      // FP8 output: the next layer's activation scale
     constexpr int COLS = 16 * NT;                                // output channels of this workgroup
     for (int idx = threadIdx.x; idx < MT * 16 * COLS; idx += blockDim.x) {
         const int col = idx % COLS, row = idx / COLS;            // channel fastest: consecutive threads, consecutive y
@@ -188,7 +190,7 @@ __global__ void __launch_bounds__(max_threads(MT * NT)) linear_skinny_kernel(
         float sum = 0.0f;
         for (int w = 0; w < waves; ++w) sum += red[(w * E + e) * RED_STRIDE + src_lane];
         const int m = mt * 16 + ml, n = (t0 + j) * 16 + nl;
-        if (m < M && n < N) y[(int64_t)m * ldy + n] = OutCast<OutT>::cast((TWO ? sx * w_out[per_channel ? n : 0] : sx) * sum);
+        if (m < M && n < N) y[(int64_t)m * ldy + n] = OutCast<OutT>::cast((TWO ? sx * w_out[per_channel ? n : 0] : sx) * sum, yq);
     }
 }
 
@@ -201,7 +203,11 @@ int launch_one(const LinearArgs& a, int depth, int waves, hipStream_t st) {
 #define W4A8_SKINNY(DEPTHV, MODEV)                                                                                        \
     hipLaunchKernelGGL((linear_skinny_kernel<MT, NT, DEPTHV, OutT, MODEV>), dim3(grid), dim3(waves * 64), lds, st, a.x8, a.M, \
                        a.ldx8, a.s_x, a.packed, a.scales, a.N, a.n_tiles, a.C, a.cpg, a.NG, static_cast<OutT*>(a.y), a.ldy,   \
-                       cpw, a.w_out, a.per_channel)
+                       cpw, a.w_out, a.per_channel, a.y_scale)
+    if (sizeof(OutT) == 1) {                                     // FP8 output exists for the code-exact mode only
+        W4A8_SKINNY(2, MODE_CODE_EXACT);
+        return launch_status();
+    }
     if (a.mode == MODE_TWO_LEVEL)
         W4A8_SKINNY(2, MODE_TWO_LEVEL);
     else if (a.mode == MODE_ASYM)
@@ -240,7 +246,7 @@ int launch_mt(const LinearArgs& a, int mt, int nt, int depth, int waves, hipStre
 int launch_linear_skinny(const uint8_t* x8, int64_t M, int64_t K, int64_t ldx8, const float* s_x,
                          const uint8_t* packed, const float* scales, int64_t N, int32_t G, void* y, w4a8_dtype ydt,
                          int64_t ldy, int nt, int waves, int depth, const float* w_out, int per_channel, int mode,
-                         hipStream_t st) {
+                         const float* y_scale, hipStream_t st) {
     if (M < 1 || M > 64) return W4A8_ERR_SHAPE;
     const int C = (int)(K / 128), cpg = G / 128, NG = (int)(K / G);
     const int n_tiles = (int)((N + 15) / 16);
@@ -262,7 +268,11 @@ int launch_linear_skinny(const uint8_t* x8, int64_t M, int64_t K, int64_t ldx8, 
     if (waves < 1 || waves > 16 || waves * mt * nt > 64 || waves * 64 > max_threads(mt * nt)) return W4A8_ERR_SHAPE;
     if (depth == 0) depth = 2;                                   // deeper rings cost occupancy and measured no faster
     if (depth != 2 && depth != 4) return W4A8_ERR_SHAPE;
-    const LinearArgs a{x8, (int)M, ldx8, s_x, packed, scales, (int)N, n_tiles, C, cpg, NG, y, ldy, w_out, per_channel, mode};
+    const LinearArgs a{x8, (int)M, ldx8, s_x, packed, scales, (int)N, n_tiles, C, cpg, NG, y, ldy, w_out, per_channel, mode, y_scale};
+    if ((int)ydt == YDT_E4M3) {
+        if (mode != MODE_CODE_EXACT || !y_scale) return W4A8_ERR_DTYPE;
+        return launch_mt<uint8_t>(a, mt, nt, depth, waves, st);
+    }
     if (ydt == W4A8_F32) return launch_mt<float>(a, mt, nt, depth, waves, st);
     return launch_mt<uint16_t>(a, mt, nt, depth, waves, st);
 }

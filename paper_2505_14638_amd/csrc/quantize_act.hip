@@ -6,18 +6,6 @@
 namespace w4a8 {
 namespace {
 
-// Saturate to the E4M3 range (Sec. 4.1: +-448) before the hardware rounding; NaN passes through.
-__device__ __forceinline__ float sat448(float t) {
-    const float c = __builtin_fminf(__builtin_fmaxf(t, -448.0f), 448.0f);
-    return (t != t) ? t : c;
-}
-
-// Two float32 -> two E4M3 bytes (round to nearest even) in the low or high half of `old`.
-__device__ __forceinline__ uint32_t cvt2(float a, float b, uint32_t old, bool high) {
-    return high ? (uint32_t)__builtin_amdgcn_cvt_pk_fp8_f32(sat448(a), sat448(b), (int)old, true)
-                : (uint32_t)__builtin_amdgcn_cvt_pk_fp8_f32(sat448(a), sat448(b), (int)old, false);
-}
-
 __device__ __forceinline__ uint32_t quant4(float a, float b, float c, float d, float s) {
     // IEEE float32 division (correctly rounded), then one rounding onto the E4M3 grid
     uint32_t r = cvt2(a / s, b / s, 0u, false);

@@ -253,12 +253,35 @@ __device__ __forceinline__ uint16_t f32_to_bf16_bits(float f) {
 
 __device__ __forceinline__ float bf16_bits_to_f32(uint16_t b) { return __uint_as_float(((uint32_t)b) << 16); }
 
+// Saturate to the E4M3 range (Sec. 4.1: +-448) before the hardware rounding; NaN passes through.
+__device__ __forceinline__ float sat448(float t) {
+    const float c = __builtin_fminf(__builtin_fmaxf(t, -448.0f), 448.0f);
+    return (t != t) ? t : c;
+}
+
+// Two float32 -> two E4M3 bytes (round to nearest even, saturating) in the low or high half of `old`.
+__device__ __forceinline__ uint32_t cvt2(float a, float b, uint32_t old, bool high) {
+    return high ? (uint32_t)__builtin_amdgcn_cvt_pk_fp8_f32(sat448(a), sat448(b), (int)old, true)
+                : (uint32_t)__builtin_amdgcn_cvt_pk_fp8_f32(sat448(a), sat448(b), (int)old, false);
+}
+
+// Eq. 13 for one value: nearest_E4M3(x / s), the quotient one IEEE float32 division.
+__device__ __forceinline__ uint8_t quantize_one(float x, float s) { return (uint8_t)(cvt2(x / s, 0.0f, 0u, false) & 0xFFu); }
+
+// Output conversions of the linear kernels.  `q` is the static scale of the NEXT layer's activation quantization and
+// counts only for FP8 output (uint8_t): the value is rounded to bf16 first, then quantized by Eq. 13, which is exactly
+// what a bf16 output followed by the activation-quantize kernel produces.
 template <typename T> struct OutCast;
 template <> struct OutCast<float> {
-    static __device__ __forceinline__ float cast(float v) { return v; }
+    static __device__ __forceinline__ float cast(float v, float) { return v; }
 };
 template <> struct OutCast<uint16_t> {
-    static __device__ __forceinline__ uint16_t cast(float v) { return f32_to_bf16_bits(v); }
+    static __device__ __forceinline__ uint16_t cast(float v, float) { return f32_to_bf16_bits(v); }
+};
+template <> struct OutCast<uint8_t> {
+    static __device__ __forceinline__ uint8_t cast(float v, float q) {
+        return quantize_one(bf16_bits_to_f32(f32_to_bf16_bits(v)), q);
+    }
 };
 
 }  // namespace w4a8

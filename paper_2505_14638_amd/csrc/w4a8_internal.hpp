@@ -34,7 +34,12 @@ struct LinearArgs {
     const float* w_out;
     int per_channel;
     int mode;                        // a WeightMode
+    const float* y_scale;            // FP8 output only: the static scale the output is quantized with (Eq. 13)
 };
+
+// Output type beyond the public w4a8_dtype values, for the launchers: E4M3 bytes, the bf16 result quantized with the
+// next layer's static activation scale (code-exact mode only).
+constexpr int YDT_E4M3 = 2;
 
 int launch_quantize_act(const void* x, w4a8_dtype dt, int64_t M, int64_t K, int64_t ldx, const float* scale,
                         uint8_t* x8, int64_t ldx8, hipStream_t st);
@@ -55,12 +60,14 @@ int launch_linear_canonical(const uint8_t* x8, int64_t M, int64_t K, int64_t ldx
 int launch_linear_skinny(const uint8_t* x8, int64_t M, int64_t K, int64_t ldx8, const float* s_x,
                          const uint8_t* packed, const float* scales, int64_t N, int32_t G, void* y, w4a8_dtype ydt,
                          int64_t ldy, int nt, int waves, int depth, const float* w_out, int per_channel, int mode,
-                         hipStream_t st);
+                         const float* y_scale, hipStream_t st);
 // mf = 16-token blocks per workgroup, ks = K-split groups per workgroup, tpw = weight bands per wavefront; 0: chosen
 int launch_linear_mfma_tiled(const uint8_t* x8, int64_t M, int64_t K, int64_t ldx8, const float* s_x,
                              const uint8_t* packed, const float* scales, int64_t N, int32_t G, void* y,
                              w4a8_dtype ydt, int64_t ldy, int mf, int ks, int tpw, const float* w_out, int per_channel,
-                             int mode, hipStream_t st);
-int launch_silu_mul(const void* gu, int64_t M, int64_t F, int64_t ldgu, void* h, int64_t ldh, hipStream_t st);
+                             int mode, const float* y_scale, hipStream_t st);
+// q_scale != nullptr: h is E4M3 bytes, the bf16 result quantized with *q_scale (Eq. 13)
+int launch_silu_mul(const void* gu, int64_t M, int64_t F, int64_t ldgu, void* h, int64_t ldh, const float* q_scale,
+                    hipStream_t st);
 
 }  // namespace w4a8

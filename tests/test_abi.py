@@ -164,6 +164,23 @@ def test_asym_validation(L):
     assert d(P, P + 8, 16, 256, 128, P, None) == 6
 
 
+def test_fused_validation(L):
+    f = L.w4a8_linear_fp8_out
+    # x8, M, K, ldx8, xs, packed, scales, N, G, y_scale, y8, ldy8, stream
+    assert f(P, 0, 256, 256, P, P, P, 64, 128, P, P, 64, None) == 0
+    assert f(P, 4, 256, 256, P, P, P, 64, 128, 0, P, 64, None) == 1                    # NULL output scale
+    assert f(P, 4, 256, 256, P, P, P, 64, 128, P, 0, 64, None) == 1
+    assert f(P, 4, 256, 256, P, P, P, 64, 128, P + 2, P, 64, None) == 6
+    assert f(P, 4, 256, 256, P, P, P, 64, 128, P, P, 32, None) == 2                    # ldy8 < N
+    assert f(P, 4, 256, 256, P, P, P, 64, 96, P, P, 64, None) == 3
+    assert L.w4a8_linear(P, 4, 256, 256, P, P, P, 64, 128, B.LAYOUT_TILED, P, 2, 64, None, 0, None) == 4   # 2 is not public
+    q = L.w4a8_silu_mul_quantize
+    assert q(P, 0, 64, 128, P, P, 64, None) == 0
+    assert q(P, 4, 64, 64, P, P, 64, None) == 2                                        # ldgu < 2F
+    assert q(P, 4, 64, 128, 0, P, 64, None) == 1
+    assert q(P, 4, 64, 128, P, P, 32, None) == 2
+
+
 def test_other_validation(L):
     assert L.w4a8_dequant_weights(0, 16, 256, B.LAYOUT_TILED, P, None) == 1
     assert L.w4a8_dequant_weights(P, 16, 200, B.LAYOUT_TILED, P, None) == 5

@@ -80,3 +80,59 @@ def test_block_stack(block, m):
     rel = np.linalg.norm(yg - yo) / np.linalg.norm(yo)
     print(f"  M={m} end to end: relative Frobenius error {rel:.2e}", flush=True)
     assert rel < 5e-2
+
+
+@pytest.mark.parametrize("m", [1, 8, 32, 128, 1024])
+def test_block_stack_fused_is_the_same_computation(block, m):
+    """The fused block (FP8 output of QKV and O, SiLU*mul with quantization) gives, bit for bit, the FP8 codes at every
+    layer input and the block output of the unfused one (which the test above checks against the oracle)."""
+    blk, _, _ = block
+    fused = DecoderBlockLinears(HIDDEN, FFN, QKV_OUT, G, DEV, fused=True)
+    fused.weights, fused.scales_x = blk.weights, blk.scales_x
+    x_bits = syn.f32_to_bf16_bits(syn.make_activations(syn.rng_for(5, 200 + m), m, HIDDEN, CFG["frac"], CFG["mult"]))
+    x_d = torch.from_numpy(x_bits.view(np.int16)).to(DEV).view(torch.bfloat16)
+    a, b = {}, {}
+    blk.forward(x_d, a)
+    fused.forward(x_d, b)
+    torch.cuda.synchronize()
+    for name in ("qkv_x8", "o_x8", "gate_up_x8", "down_x8"):
+        assert torch.equal(a[name], b[name].contiguous()), name
+    for name in ("gate_up", "down"):
+        assert np.array_equal(bits(a[name]), bits(b[name])), name
+
+
+@pytest.mark.parametrize("m,k,n", [(1, 1024, 96), (16, 512, 200), (40, 1024, 72), (100, 384, 300), (300, 1024, 520),
+                                   (257, 640, 130)])
+def test_linear_fp8_out_equals_linear_then_quantize(gpu_lib, m, k, n):
+    """Ragged shapes on both kernels: the FP8 output equals the oracle's Eq. 13 applied to the bf16 output of the
+    unfused layer; rows with a stride (a column slice of a wider buffer) included."""
+    rng = np.random.default_rng([61, m, k, n])
+    w = syn.make_weights(rng, n, k)
+    x = syn.make_activations(rng, m, k, 0.02, 20.0)
+    s_x = syn.static_act_scale(x)
+    x8 = torch.from_numpy(o.quantize_act(x, s_x)).to(DEV)
+    sx = torch.tensor([s_x], dtype=torch.float32, device=DEV)
+    packed, scales = B.pack_weights(torch.from_numpy(w).to(DEV), G, B.LAYOUT_TILED)
+    y16 = bits(B.linear(x8, sx, packed, scales, n, G, B.LAYOUT_TILED, out_dtype=torch.bfloat16))
+    s_next = np.float32(np.abs(o.bf16_bits_to_f32(y16)).max() / 600.0)           # some values saturate
+    want = o.quantize_act(y16, s_next, x_is_bf16_bits=True)
+    wide = torch.zeros((m, n + 48), dtype=torch.uint8, device=DEV)
+    got = B.linear_fp8_out(x8, sx, packed, scales, n, G, torch.tensor([s_next], dtype=torch.float32, device=DEV),
+                           out=wide[:, 16:16 + n])
+    torch.cuda.synchronize()
+    assert np.array_equal(got.cpu().numpy(), want)
+    assert int(wide[:, :16].max()) == 0 and int(wide[:, 16 + n:].max()) == 0     # nothing written outside the slice
+    assert (want & 0x7F).max() == 0x7E
+
+
+@pytest.mark.parametrize("m,f", [(1, 14336), (5, 1000), (33, 263), (128, 2048)])
+def test_silu_mul_quantize_equals_silu_mul_then_quantize(gpu_lib, m, f):
+    rng = np.random.default_rng([62, m, f])
+    gu_bits = syn.f32_to_bf16_bits((rng.standard_normal((m, 2 * f)) * 3).astype(np.float32))
+    gu = torch.from_numpy(gu_bits.view(np.int16)).to(DEV).view(torch.bfloat16)
+    h = bits(B.silu_mul(gu))
+    s = np.float32(np.abs(o.bf16_bits_to_f32(h)).max() / 600.0)
+    want = o.quantize_act(h, s, x_is_bf16_bits=True)
+    got = B.silu_mul_quantize(gu, torch.tensor([s], dtype=torch.float32, device=DEV))
+    torch.cuda.synchronize()
+    assert np.array_equal(got.cpu().numpy(), want)
