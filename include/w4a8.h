@@ -183,12 +183,15 @@ int w4a8_linear_pow2(const uint8_t* x8_dev, int64_t M, int64_t K, int64_t ldx8, 
  * The asymmetric format (Eq. 1 with q_min = 0, q_max = 15; Eq. 8-9; dequantization by Eq. 14): unsigned 4-bit codes u
  * with a scale s[n,g] and a zero-point z[n,g] per (row, group), z an integer in [0, 15] like the codes;
  *   Y[m,n] = cast( s_x * sum_g s[n,g] * sum_{k in g} val(x8[m,k]) * (u[n,k] - z[n,g]) ).
- * The integers u - z lie in [-15, 15] and are exact in E4M3: the kernels expand each nibble to the E4M3 byte of
- * u - z (per lane a 16-entry table built from the zero-point), multiply on the FP8 matrix units and apply the group
- * scale to each group's partial sum in fp32, exactly as w4a8_linear does with signed codes.
+ * The integers u - z lie in [-15, 15] and are exact in E4M3: the MFMA-tiled kernel expands each nibble to the E4M3
+ * byte of u - z (per lane a 16-entry table built from the zero-point); the few-token kernel feeds the exact
+ * half-integer u - 7.5 instead and adds (7.5 - z) * sum_k val(x8) per 128 positions, the sum taken on the matrix unit
+ * as well.  Both multiply on the FP8 matrix units and apply the group scale to each group's partial sum in fp32, as
+ * w4a8_linear does with signed codes.
  * Storage (tiled only; K % 128 == 0, group_size % 128 == 0; rows padded to Np = ceil(N/16)*16 with code 0, scale 0,
  * zero-point 0):
- *   packed  the byte and nibble positions of W4A8_LAYOUT_TILED, the nibble being the code u itself;
+ *   packed  the byte and nibble positions of W4A8_LAYOUT_TILED; the nibble writes the code as u = 7.5 +- (m + 0.5):
+ *           bit 3 = 1 for codes 0..7 (then m = 7 - u), bits 0..2 = m (codes 8..15: m = u - 8);
  *   params  w4a8_asym_params_bytes() bytes, 16-byte aligned: one 80-byte record per (16-row band t, group g) at byte
  *           (t * (K/group_size) + g) * 80: the 16 float32 scales of rows 16t .. 16t+15, then their 16 zero-point bytes.
  * w4a8_pack_weights_asym writes both.  src_kind W4A8_SRC_F32_RTN: src = W float32 [N, K]; per (row, group)

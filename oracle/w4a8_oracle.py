@@ -376,15 +376,28 @@ def untile_scales(buf, n: int, ng: int, with_marks: bool = False):
 ASYM_RECORD_BYTES = 80     # per (16-row band, group): 16 float32 scales, then 16 zero-point bytes
 
 
+def asym_nibble(u) -> np.ndarray:
+    """Nibble of an unsigned code in the asymmetric tiled storage: the code is written as 7.5 + h with
+    h = +-(m + 0.5), m = 0..7, and stored sign-magnitude: bit 3 = 1 for the lower half (codes 0..7, m = 7 - code),
+    bits 0..2 = m (codes 8..15: m = code - 8).  (The library's own format: all sixteen h are exact E4M3 values.)"""
+    u = np.asarray(u, dtype=np.int16)
+    return np.where(u >= 8, u - 8, 8 | (7 - u)).astype(np.uint8)
+
+
+def asym_nibble_to_code(nib) -> np.ndarray:
+    nib = np.asarray(nib, dtype=np.int16)
+    return np.where(nib < 8, nib + 8, 7 - (nib & 7)).astype(np.uint8)
+
+
 def pack_tiled_asym(u) -> np.ndarray:
-    """Tiled storage of unsigned codes 0..15: the byte and nibble positions of `pack_tiled`, the nibble being the
-    code itself; rows are padded with code 0 up to a multiple of 16."""
+    """Tiled storage of unsigned codes 0..15: the byte and nibble positions of `pack_tiled`, the nibble as in
+    `asym_nibble`; rows are padded with code 0 up to a multiple of 16."""
     u = np.asarray(u, dtype=np.uint8)
     n, k = u.shape
     assert k % TILE_K == 0 and int(u.max(initial=0)) <= 15
     n_pad = -(-n // TILE_N) * TILE_N
-    p = np.zeros((n_pad, k), dtype=np.uint8)
-    p[:n] = u
+    p = np.full((n_pad, k), asym_nibble(0), dtype=np.uint8)
+    p[:n] = asym_nibble(u)
     p = p.reshape(n_pad // TILE_N, TILE_N, k // TILE_K, 4, 4, 2, 4).transpose(0, 2, 3, 1, 4, 6, 5)   # t c kq i d b h
     return np.ascontiguousarray(p[..., 0] | (p[..., 1] << 4)).ravel()
 
@@ -393,7 +406,7 @@ def unpack_tiled_asym(buf, n: int, k: int) -> np.ndarray:
     n_pad = -(-n // TILE_N) * TILE_N
     b = np.asarray(buf, dtype=np.uint8).reshape(n_pad // TILE_N, k // TILE_K, 4, TILE_N, 4, 4)   # t c kq i d b
     u = np.stack([b & 0xF, b >> 4], axis=-1)                                                     # ... h
-    return np.ascontiguousarray(u.transpose(0, 3, 1, 2, 4, 6, 5).reshape(n_pad, k)[:n])          # t i c kq d h b
+    return asym_nibble_to_code(np.ascontiguousarray(u.transpose(0, 3, 1, 2, 4, 6, 5).reshape(n_pad, k)[:n]))   # t i c kq d h b
 
 
 def tile_params_asym(s, z) -> np.ndarray:

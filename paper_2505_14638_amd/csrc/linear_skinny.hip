@@ -22,12 +22,15 @@ struct ChunkLoads {
     uint4 w[NT];          // packed nibbles: this lane's slot of each tile
     float4 s[NT];         // group scales of the four output channels this lane accumulates
     uint4 x[MT][2];       // 32 activation bytes per 16-token block
-    uint32_t z[NT];       // asymmetric format: zero-point of the channel whose nibbles this lane expands
+    uint32_t z[NT];       // asymmetric format: the zero-point bytes of the four output channels this lane accumulates
 };
 
 // larger register tiles run with fewer wavefronts per workgroup (the launcher enforces it), which raises the
-// register budget per lane: 128 at 1024 threads, 256 at 512 and below
-constexpr int max_threads(int tiles) { return tiles <= 2 ? 1024 : (tiles <= 8 ? 512 : 256); }
+// register budget per lane: 128 at 1024 threads, 256 at 512 and below; the asymmetric format's zero-point terms need
+// the larger budget from two tiles on
+constexpr int max_threads(int tiles, bool asym = false) {
+    return tiles <= (asym ? 1 : 2) ? 1024 : (tiles <= 8 ? 512 : 256);
+}
 
 // DEPTH = chunks in flight per wavefront (a ring of register buffers).  MODE_CODE_EXACT: signed codes, group scales
 // applied to the partial sums in fp32.  MODE_TWO_LEVEL: the weight operand is nearest_E4M3(code * s8[n,g]), the sum over
@@ -37,7 +40,7 @@ constexpr int max_threads(int tiles) { return tiles <= 2 ? 1024 : (tiles <= 8 ? 
 // zero-points.  MODE_POW2: signed codes, the group scale is a power of two that the matrix unit applies itself
 // (block-scaled MFMA); the sum over the wavefront's share of K stays in the MFMA accumulator.
 template <int MT, int NT, int DEPTH, typename OutT, int MODE>
-__global__ void __launch_bounds__(max_threads(MT * NT)) linear_skinny_kernel(
+__global__ void __launch_bounds__(max_threads(MT * NT, MODE == MODE_ASYM)) linear_skinny_kernel(
     const uint8_t* __restrict__ x8, int M, int64_t ldx8, const float* __restrict__ s_x,
     const uint8_t* __restrict__ packed, const float* __restrict__ scales, int N, int n_tiles, int C, int cpg, int NG,
     OutT* __restrict__ y, int64_t ldy, int cpw, const float* __restrict__ w_out, int per_channel,
@@ -79,7 +82,7 @@ __global__ void __launch_bounds__(max_threads(MT * NT)) linear_skinny_kernel(
                 L.s[j] = make_float4(*reinterpret_cast<const float*>(sbase[j] + (int64_t)g * REC + i * 4), 0.f, 0.f, 0.f);
             else
                 L.s[j] = *reinterpret_cast<const float4*>(sbase[j] + (int64_t)g * REC + soff);
-            L.z[j] = ASYM ? (uint32_t)sbase[j][(int64_t)g * REC + 64 + i] : 0u;
+            L.z[j] = ASYM ? *reinterpret_cast<const uint32_t*>(sbase[j] + (int64_t)g * REC + 64 + kq * 4) : 0u;
             wbase[j] += 1024;
         }
 #pragma unroll
@@ -104,6 +107,14 @@ __global__ void __launch_bounds__(max_threads(MT * NT)) linear_skinny_kernel(
             const uint4 a = L.x[mt][0], b = L.x[mt][1];
             xop[mt] = v8i{(int)a.x, (int)a.y, (int)a.z, (int)a.w, (int)b.x, (int)b.y, (int)b.z, (int)b.w};
         }
+        // asymmetric format: sum_k x over the chunk, per token, from an MFMA against an operand of ones (every row of
+        // the result is that sum)
+        float xs[MT];
+        if (ASYM) {
+            const v8i ones = v8i{0x38383838, 0x38383838, 0x38383838, 0x38383838, 0x38383838, 0x38383838, 0x38383838, 0x38383838};
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt) xs[mt] = mfma_16x16x128_e4m3(ones, xop[mt], v4f{0.f, 0.f, 0.f, 0.f})[0];
+        }
 #pragma unroll
         for (int j = 0; j < NT; ++j) {
             const float4 s = L.s[j];
@@ -115,7 +126,7 @@ __global__ void __launch_bounds__(max_threads(MT * NT)) linear_skinny_kernel(
                 const MagTable tab = two_level_table(s.x);
                 wop = m8 ? slot_to_operand_two_level<true>(L.w[j], tab) : slot_to_operand_two_level<false>(L.w[j], tab);
             } else if (ASYM) {
-                wop = slot_to_operand_asym(L.w[j], asym_table(L.z[j]));
+                wop = slot_to_operand_half_offset(L.w[j]);       // code - 7.5
             } else {
                 wop = slot_to_operand<false>(L.w[j]);
                 if (m8) {                                        // wave-uniform, rare
@@ -133,7 +144,14 @@ __global__ void __launch_bounds__(max_threads(MT * NT)) linear_skinny_kernel(
                     acc[mt][j] = mfma_16x16x128_e4m3_scaled(wop, xop[mt], acc[mt][j], e8m0_of(s.x), E8M0_ONE);
                     continue;
                 }
-                const v4f p = mfma_16x16x128_e4m3(wop, xop[mt], v4f{0.f, 0.f, 0.f, 0.f});
+                v4f p = mfma_16x16x128_e4m3(wop, xop[mt], v4f{0.f, 0.f, 0.f, 0.f});
+                if (ASYM) {                                      // sum x (u - z) = sum x (u - 7.5) + (7.5 - z) sum x
+                    const uint32_t z = L.z[j];
+                    p[0] = fmaf(7.5f - (float)(z & 0xFFu), xs[mt], p[0]);
+                    p[1] = fmaf(7.5f - (float)((z >> 8) & 0xFFu), xs[mt], p[1]);
+                    p[2] = fmaf(7.5f - (float)((z >> 16) & 0xFFu), xs[mt], p[2]);
+                    p[3] = fmaf(7.5f - (float)(z >> 24), xs[mt], p[3]);
+                }
                 acc[mt][j][0] = fmaf(fabsf(s.x), p[0], acc[mt][j][0]);
                 acc[mt][j][1] = fmaf(fabsf(s.y), p[1], acc[mt][j][1]);
                 acc[mt][j][2] = fmaf(fabsf(s.z), p[2], acc[mt][j][2]);
@@ -264,8 +282,9 @@ int launch_linear_skinny(const uint8_t* x8, int64_t M, int64_t K, int64_t ldx8, 
         while (waves < 16 && waves * waves * 2 < want * want) waves *= 2;   // odd counts split K unevenly and measured slower
     }
     if (waves > C) waves = C;
-    while (waves > 1 && (waves * mt * nt > 64 || waves * 64 > max_threads(mt * nt))) --waves;   // LDS and registers
-    if (waves < 1 || waves > 16 || waves * mt * nt > 64 || waves * 64 > max_threads(mt * nt)) return W4A8_ERR_SHAPE;
+    const int thread_cap = max_threads(mt * nt, mode == MODE_ASYM);
+    while (waves > 1 && (waves * mt * nt > 64 || waves * 64 > thread_cap)) --waves;   // LDS and registers
+    if (waves < 1 || waves > 16 || waves * mt * nt > 64 || waves * 64 > thread_cap) return W4A8_ERR_SHAPE;
     if (depth == 0) depth = 2;                                   // deeper rings cost occupancy and measured no faster
     if (depth != 2 && depth != 4) return W4A8_ERR_SHAPE;
     const LinearArgs a{x8, (int)M, ldx8, s_x, packed, scales, (int)N, n_tiles, C, cpg, NG, y, ldy, w_out, per_channel, mode, y_scale};

@@ -163,6 +163,9 @@ __global__ void __launch_bounds__(256) asym_params_kernel(const float* __restric
     }
 }
 
+// nibble of an unsigned code in the asymmetric storage: u = 7.5 +- (m + 0.5), sign-magnitude (see w4a8_device.hpp)
+__device__ __forceinline__ uint32_t asym_nibble(uint32_t u) { return u >= 8u ? u - 8u : 15u - u; }
+
 // u = clamp(round(W / s + z), 0, 15): float32 division, float32 addition, round half to even
 __device__ __forceinline__ uint32_t asym_code(float w, float s, uint32_t z) {
     const float r = rintf(__fadd_rn(__fdiv_rn(w, s), (float)z));
@@ -177,7 +180,7 @@ __global__ void __launch_bounds__(256) pack_asym_kernel(const void* __restrict__
     if (b >= g.Np * (g.K >> 1)) return;
     int64_t n, k_lo, k_hi;
     byte_to_coords(g, b, n, k_lo, k_hi);
-    uint32_t lo = 0, hi = 0;
+    uint32_t lo = 0, hi = 0;                                     // padding rows: code 0
     if (n < g.N) {
         if (FROM_F32) {
             const float* w = static_cast<const float*>(src) + n * g.K;
@@ -191,7 +194,7 @@ __global__ void __launch_bounds__(256) pack_asym_kernel(const void* __restrict__
             hi = q[k_hi] & 0xFu;
         }
     }
-    packed[b] = (uint8_t)(lo | (hi << 4));
+    packed[b] = (uint8_t)(asym_nibble(lo) | (asym_nibble(hi) << 4));
 }
 
 // tiled: one thread per 16-byte slot -> 32 consecutive bytes of one row of w8

@@ -135,14 +135,19 @@ __device__ __forceinline__ v8i slot_to_operand_two_level(uint4 s, const MagTable
 }
 
 // ---------------------------------------------------------------------------------------------
-// Asymmetric format (Eq. 1 with unsigned codes 0..15, Eq. 8-9, Eq. 14): the FP8 weight is the integer code - zero_point,
-// in [-15, 15], exact in E4M3.  The zero-point belongs to a (row, group), that is to a lane for the length of a chunk:
-// per (lane, chunk) a 16-entry table of the bytes nearest_E4M3(u - z), u = 0..15 (sixteen float32 differences, rounded
-// by the hardware converter, which is exact on them); the plain unsigned nibbles index it -- an 8-entry lookup for
-// each half of the table and a third v_perm_b32 that picks, byte by byte, the half that bit 3 names.
+// Asymmetric format (Eq. 1 with unsigned codes 0..15, Eq. 8-9, Eq. 14): the weight is the integer u - z (code minus
+// zero-point), in [-15, 15].  The stored nibble writes the code as u = 7.5 + h, h = +-(m + 0.5): bit 3 = 1 for codes
+// 0..7 (m = 7 - u), bits 0..2 = m (codes 8..15: m = u - 8).  Two ways to the product, both exact in the operand:
+//   - the MFMA-tiled kernel feeds nearest_E4M3(u - z), exact in E4M3.  The zero-point belongs to a (row, group), that
+//     is to a lane for the length of a chunk: per (lane, chunk) a 16-entry table indexed by the nibble (sixteen float32
+//     differences, rounded by the hardware converter, which is exact on them), an 8-entry lookup for each half of the
+//     table and a third v_perm_b32 that picks, byte by byte, the half that bit 3 names;
+//   - the skinny kernel feeds the half-integer h itself -- all sixteen values +-0.5 .. +-7.5 are exact in E4M3 and
+//     the nibble is their sign-magnitude form, so the expansion is the signed format's short one, with no special
+//     pattern -- and adds (7.5 - z) * sum_k x per chunk, the sum coming from one more MFMA against an operand of ones.
 // ---------------------------------------------------------------------------------------------
 struct AsymTable {
-    uint32_t t[4];        // byte u % 4 of t[u / 4] = nearest_E4M3(u - z)
+    uint32_t t[4];        // byte p % 4 of t[p / 4] = nearest_E4M3(code(p) - z) for nibble p
 };
 
 __device__ __forceinline__ AsymTable asym_table(uint32_t z) {
@@ -150,14 +155,38 @@ __device__ __forceinline__ AsymTable asym_table(uint32_t z) {
     AsymTable T;
 #pragma unroll
     for (int w = 0; w < 4; ++w) {
-        int r = __builtin_amdgcn_cvt_pk_fp8_f32((float)(4 * w) - zf, (float)(4 * w + 1) - zf, 0, false);
-        r = __builtin_amdgcn_cvt_pk_fp8_f32((float)(4 * w + 2) - zf, (float)(4 * w + 3) - zf, r, true);
+        // nibbles 4w .. 4w+3: codes 8 + p for p < 8, 15 - p for p >= 8
+        const float c0 = (float)(w < 2 ? 8 + 4 * w : 15 - 4 * w), step = w < 2 ? 1.0f : -1.0f;
+        int r = __builtin_amdgcn_cvt_pk_fp8_f32(c0 - zf, c0 + step - zf, 0, false);
+        r = __builtin_amdgcn_cvt_pk_fp8_f32(c0 + 2.0f * step - zf, c0 + 3.0f * step - zf, r, true);
         T.t[w] = (uint32_t)r;
     }
     return T;
 }
 
-// E4M3 bytes of the four unsigned nibbles at bit offset SHIFT (0: low nibbles, 4: high nibbles) of the bytes of w.
+// E4M3 bytes of the half-integers h = +-(m + 0.5) of the four nibbles at bit offset SHIFT of the bytes of w.
+template <int SHIFT>
+__device__ __forceinline__ uint32_t asym_half_offset(uint32_t w) {
+    const uint32_t MAG_LO = 0x46423C30u, MAG_HI = 0x4F4D4B49u;   // 0.5 1.5 2.5 3.5, 4.5 5.5 6.5 7.5
+    const uint32_t sel = (w >> SHIFT) & 0x07070707u;
+    const uint32_t mag = __builtin_amdgcn_perm(MAG_HI, MAG_LO, sel);
+    const uint32_t sign = SHIFT ? w : (w << 4);
+    return (sign & 0x80808080u) | mag;
+}
+
+__device__ __forceinline__ v8i slot_to_operand_half_offset(uint4 s) {
+    const uint32_t w[4] = {s.x, s.y, s.z, s.w};
+    v8i v;
+#pragma unroll
+    for (int d = 0; d < 4; ++d) {
+        v[2 * d] = (int)asym_half_offset<0>(w[d]);
+        v[2 * d + 1] = (int)asym_half_offset<4>(w[d]);
+    }
+    return v;
+}
+
+// E4M3 bytes of code - zero_point of the four nibbles at bit offset SHIFT (0: low nibbles, 4: high nibbles) of the
+// bytes of w.
 template <int SHIFT>
 __device__ __forceinline__ uint32_t asym_half(uint32_t w, const AsymTable& T) {
     const uint32_t v = SHIFT ? (w >> 4) : w;

@@ -109,10 +109,10 @@ def test_exact_integer_case_bit_for_bit(gpu_lib, m):
     assert np.array_equal(y32, want)
 
 
-@pytest.mark.parametrize("m", [8, 300])
+@pytest.mark.parametrize("m", [300, 1000])
 def test_coincides_with_the_signed_code_layer(gpu_lib, m):
-    """Codes q + 8 with zero-point 8 are the signed codes q: the same operand bytes reach the matrix unit and the same
-    fp32 operations follow, so the two entry points agree to the last bit."""
+    """Codes q + 8 with zero-point 8 are the signed codes q: in the MFMA-tiled kernel the same operand bytes reach the
+    matrix unit and the same fp32 operations follow, so the two entry points agree to the last bit."""
     rng = np.random.default_rng([46, m])
     k, n, g = 1024, 208, 128
     x = syn.make_activations(rng, m, k, 0.02, 20.0)

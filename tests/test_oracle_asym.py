@@ -150,12 +150,19 @@ def test_asym_storage_by_explicit_offsets():
     params = o.tile_params_asym(s, z)
     n_pad, ng = 48, k // g
     assert packed.size == n_pad * k // 2 and params.size == (n_pad // 16) * ng * 80
-    # nibbles: the positions the tiled format defines, the nibble being the code itself
+    # nibbles: the positions the tiled format defines; the nibble spelled out from its definition: the code is
+    # 7.5 + h, h = +-(m + 0.5); codes 8..15 are 0mmm with m = code - 8, codes 0..7 are 1mmm with m = 7 - code
+    patterns = {8: 0b0000, 9: 0b0001, 10: 0b0010, 11: 0b0011, 12: 0b0100, 13: 0b0101, 14: 0b0110, 15: 0b0111,
+                7: 0b1000, 6: 0b1001, 5: 0b1010, 4: 0b1011, 3: 0b1100, 2: 0b1101, 1: 0b1110, 0: 0b1111}
+    for code, pat in patterns.items():
+        h = (-1 if pat & 8 else 1) * ((pat & 7) + 0.5)
+        assert 7.5 + h == code
     byte, nib = o._tiled_destination(n_pad, k)
     want = np.zeros(n_pad * k // 2, dtype=np.uint8)
-    for nn in range(n):
+    for nn in range(n_pad):
         for kk in range(k):
-            want[byte[nn, kk]] |= int(u[nn, kk]) << (4 * int(nib[nn, kk]))
+            code = int(u[nn, kk]) if nn < n else 0
+            want[byte[nn, kk]] |= patterns[code] << (4 * int(nib[nn, kk]))
     assert np.array_equal(packed, want)
     # records: scale (n, g) as little-endian float32 at ((n // 16) * ng + g) * 80 + 4 * (n % 16), zero-point
     # at ((n // 16) * ng + g) * 80 + 64 + n % 16
