@@ -208,6 +208,53 @@ def block_latency(dev, steps, warmup):
             "note": "one weight set, so at small batch part of the 116 MB of weights is served by the 256 MB cache"}
 
 
+def weight_modes(dev):
+    """The other weight formats of the library on two shapes (gate|up at M = 1 and M = 8192): same measurement as the
+    main legs, eager launches over six rotating weight sets (decode) or one (prefill)."""
+    k, n = syn.LLAMA3_8B["gate_up"]
+    nt = (n + 15) // 16
+    out = {}
+    for m in (1, 8192):
+        sets = 6 if m == 1 else 1
+        x8 = torch.randint(0, 120, (m, k), dtype=torch.uint8, device=dev)
+        sx = torch.tensor([0.1], dtype=torch.float32, device=dev)
+        y = torch.empty((m, n), dtype=torch.bfloat16, device=dev)
+        packed = [torch.randint(0, 256, (n * k // 2,), dtype=torch.uint8, device=dev) for _ in range(sets)]
+        s32 = [torch.rand(nt * 16 * k // G, dtype=torch.float32, device=dev) * 0.01 + 0.005 for _ in range(sets)]
+        s8 = [sc * 400.0 for sc in s32]                                    # FP8-domain group scales, products up to ~56
+        sp2 = [torch.exp2(torch.ceil(torch.log2(sc))) for sc in s32]
+        w_out = torch.rand(n, dtype=torch.float32, device=dev) * 1e-3
+        params = []
+        for i in range(sets):
+            rec = torch.zeros((nt * (k // G), 80), dtype=torch.uint8, device=dev)
+            rec[:, :64] = s32[i].view(-1, 16).view(torch.uint8)
+            rec[:, 64:] = torch.randint(0, 16, (nt * (k // G), 16), dtype=torch.uint8, device=dev)
+            params.append(rec.reshape(-1))
+        calls = {
+            "code_exact": lambda i: B.linear(x8, sx, packed[i], s32[i], n, G, B.LAYOUT_TILED, out=y),
+            "two_level": lambda i: B.linear_two_level(x8, sx, packed[i], s8[i], w_out, n, G, out=y),
+            "asym": lambda i: B.linear_asym(x8, sx, packed[i], params[i], n, G, out=y),
+            "pow2": lambda i: B.linear_pow2(x8, sx, packed[i], sp2[i], n, G, out=y),
+        }
+        reps = 60 if m == 1 else 10
+        row = {}
+        for name, fn in calls.items():
+            for i in range(reps):
+                fn(i % sets)
+            torch.cuda.synchronize()
+            t0, t1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            t0.record()
+            for i in range(reps):
+                fn(i % sets)
+            t1.record()
+            torch.cuda.synchronize()
+            sec = t0.elapsed_time(t1) * 1e-3 / reps
+            extra = n * k // G if name == "asym" else 0                   # zero-point bytes
+            row[name] = round((alg_bytes(m, k, n) + extra) / sec / 1e9, 1) if m == 1 else round(2.0 * m * k * n / sec / 1e12, 1)
+        out[f"M={m}"] = {"unit": "GB/s" if m == 1 else "TFLOP/s", **row}
+    return {"metric": "weight formats on the gate|up layer (K = 4096, N = 28672), random codes", "by_case": out}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -350,6 +397,7 @@ def main():
         torch.cuda.empty_cache()
         if not args.no_block:
             result["block"] = block_latency(dev, 50, 5)
+            result["weight_modes"] = weight_modes(dev)
     if not args.no_cpu and not args.prefill_only:
         result["cpu_baseline"] = cpu_baseline()
     print(json.dumps(result))
