@@ -216,6 +216,23 @@ int w4a8_dequant_weights_asym(const uint8_t* packed_dev, const void* params_dev,
                               uint8_t* w8_dev, void* stream);
 
 /*
+ * The asymmetric format in the two-level reading, i.e. the inference flow exactly as Sec. 3.1 states it (Eq. 8-11):
+ * the group scale s8[n,g] and zero-point z[n,g] live in the FP8 domain, the 4-bit code is dequantized to FP8,
+ *   w8[n,k] = nearest_E4M3( float32(u[n,k] - z[n,g]) * s8[n,g] )      (one float32 product, ties to even, saturating),
+ *   Y[m,n]  = cast( s_x * s_w[n] * sum_k val(x8[m,k]) * val(w8[n,k]) ),
+ * with the sum over all of K in fp32 on the matrix units and s_w per channel (per_channel = 1: N floats) or per
+ * tensor (per_channel = 0: one float), Eq. 6.  packed_dev and params8_dev are the buffers of w4a8_pack_weights_asym
+ * from W4A8_SRC_I8_CODES, with the FP8-domain group scales as its scales (the output of Alg. 1).  Everything else as
+ * in w4a8_linear_two_level.  w4a8_dequant_weights_asym_two_level writes the bytes w8 row-major [N, K] (test hook).
+ */
+int w4a8_linear_asym_two_level(const uint8_t* x8_dev, int64_t M, int64_t K, int64_t ldx8, const float* x_scale_dev,
+                               const uint8_t* packed_dev, const void* params8_dev, const float* w_out_scales_dev,
+                               int32_t per_channel, int64_t N, int32_t group_size, void* y_dev, w4a8_dtype y_dtype,
+                               int64_t ldy, void* stream);
+int w4a8_dequant_weights_asym_two_level(const uint8_t* packed_dev, const void* params8_dev, int64_t N, int64_t K,
+                                        int32_t group_size, uint8_t* w8_dev, void* stream);
+
+/*
  * Elementwise step of the decoder-block linear stack (all linear layers of a block are quantized, Sec. 4.1;
  * this joins gate|up to down): h[m,f] = bf16( silu(gate[m,f]) * up[m,f] ) with gate = gu[m, f],
  * up = gu[m, F + f]; gu_dev is bf16 [M, 2F] with row stride ldgu elements, h_dev bf16 [M, F], stride ldh.

@@ -38,6 +38,8 @@ dequant_asym_to_e4m3         Eq. 10 / Eq. 14: the integer (code - zero_point) as
                              E4M3 byte
 linear_ref_asym              Eq. 14, Eq. 4, Eq. 11 with unsigned codes and
                              per-group zero-points
+linear_ref_asym_paper_literal  Eq. 8-11 read literally: (code - zero_point) * scale
+                             rounded onto the E4M3 grid before the matmul
 pack_* / unpack_* / tile_*   storage formats of the C-ABI boundary (the tiled one keeps
                              sign-magnitude nibbles and marks groups that hold -8; the
                              asymmetric one plain unsigned nibbles and 80-byte records
@@ -511,6 +513,20 @@ def linear_ref_asym(x8, s_x, u, z, s_w, group_size: int):
     weights (unsigned 4-bit codes, per-group scale and zero-point), Eq. 4 for the activations, Eq. 11 for the
     output.  Returns (Y, A) like linear_ref."""
     return linear_ref(x8, s_x, _codes_minus_zero_points(u, z, group_size), s_w, group_size)
+
+
+def linear_ref_asym_paper_literal(x8, s_x, u, z, s8, s_w_out, group_size: int):
+    """The inference flow of Sec. 3.1 as stated (Eq. 10, Eq. 11, Eq. 4) for the format Eq. 8-9 produce: the 4-bit code is
+    dequantized to FP8, w8_hat = nearest_Z((u - z[n,g]) * s8[n,g]) (the integer difference is exact, the product one
+    float32 multiplication, then one rounding onto the E4M3 grid), and Y = s_x * s_w_out[n] * sum_k dec(x8) * dec(w8_hat).
+    Returns (Y float64, w8 bytes)."""
+    d = _codes_minus_zero_points(u, z, group_size).astype(np.float32)
+    n, k = d.shape
+    s8 = np.asarray(s8, dtype=np.float32)
+    prod = (d.reshape(n, k // group_size, group_size) * s8[:, :, None]).astype(np.float32)
+    w8 = e4m3_encode(prod.reshape(n, k))
+    y = e4m3_decode(x8) @ e4m3_decode(w8).T
+    return float(np.float32(s_x)) * y * np.asarray(s_w_out, dtype=np.float64)[None, :], w8
 
 
 def within_tolerance(y, ref, a, rel: float = 2e-3, floor: float = 2.0 ** -6):

@@ -42,6 +42,9 @@ SIGNATURES = {
     "w4a8_linear_asym": (_c_i32, [_c_vp, _c_i64, _c_i64, _c_i64, _c_vp, _c_vp, _c_vp, _c_i64, _c_i32, _c_vp, _c_i32,
                                   _c_i64, _c_vp]),
     "w4a8_dequant_weights_asym": (_c_i32, [_c_vp, _c_vp, _c_i64, _c_i64, _c_i32, _c_vp, _c_vp]),
+    "w4a8_linear_asym_two_level": (_c_i32, [_c_vp, _c_i64, _c_i64, _c_i64, _c_vp, _c_vp, _c_vp, _c_vp, _c_i32, _c_i64,
+                                            _c_i32, _c_vp, _c_i32, _c_i64, _c_vp]),
+    "w4a8_dequant_weights_asym_two_level": (_c_i32, [_c_vp, _c_vp, _c_i64, _c_i64, _c_i32, _c_vp, _c_vp]),
     "w4a8_silu_mul": (_c_i32, [_c_vp, _c_i64, _c_i64, _c_i64, _c_vp, _c_i64, _c_vp]),
     "w4a8_linear_fp8_out": (_c_i32, [_c_vp, _c_i64, _c_i64, _c_i64, _c_vp, _c_vp, _c_vp, _c_i64, _c_i32, _c_vp, _c_vp,
                                      _c_i64, _c_vp]),
@@ -228,11 +231,28 @@ def linear_asym(x8, x_scale, packed, params, n, group_size, out=None, out_dtype=
     return out
 
 
-def dequant_weights_asym(packed: torch.Tensor, params: torch.Tensor, n: int, k: int, group_size: int) -> torch.Tensor:
+def dequant_weights_asym(packed: torch.Tensor, params: torch.Tensor, n: int, k: int, group_size: int,
+                         two_level: bool = False) -> torch.Tensor:
     w8 = torch.empty((n, k), dtype=torch.uint8, device=packed.device)
-    _check(lib().w4a8_dequant_weights_asym(packed.data_ptr(), params.data_ptr(), n, k, group_size, w8.data_ptr(),
-                                           _stream()), "w4a8_dequant_weights_asym")
+    fn = lib().w4a8_dequant_weights_asym_two_level if two_level else lib().w4a8_dequant_weights_asym
+    _check(fn(packed.data_ptr(), params.data_ptr(), n, k, group_size, w8.data_ptr(), _stream()),
+           "w4a8_dequant_weights_asym")
     return w8
+
+
+def linear_asym_two_level(x8, x_scale, packed, params8, w_out_scales, n, group_size, out=None, out_dtype=torch.bfloat16):
+    """w4a8_linear_asym_two_level; `w_out_scales` holds N floats (per channel) or one (per tensor)."""
+    m, k = x8.shape
+    if out is None:
+        out = torch.empty((m, n), dtype=out_dtype, device=x8.device)
+    per_channel = 1 if w_out_scales.numel() > 1 else 0
+    assert w_out_scales.numel() in (1, n) and w_out_scales.dtype == torch.float32
+    _check(lib().w4a8_linear_asym_two_level(x8.data_ptr(), m, k, x8.stride(0) if m > 1 else max(k, x8.stride(0)),
+                                            x_scale.data_ptr(), packed.data_ptr(), params8.data_ptr(),
+                                            w_out_scales.data_ptr(), per_channel, n, group_size, out.data_ptr(),
+                                            _dtype_code(out), out.stride(0) if m > 1 else max(n, out.stride(0)), _stream()),
+           "w4a8_linear_asym_two_level")
+    return out
 
 
 def dequant_weights(packed: torch.Tensor, n: int, k: int, layout: int) -> torch.Tensor:

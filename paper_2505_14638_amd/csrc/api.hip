@@ -154,7 +154,7 @@ int w4a8_dequant_weights(const uint8_t* packed_dev, int64_t N, int64_t K, w4a8_l
     if (int e = check_nk(N, K, layout)) return e;
     if (!packed_dev || !w8_dev) return W4A8_ERR_NULL;
     if (layout == W4A8_LAYOUT_TILED && (!aligned16(packed_dev) || !aligned16(w8_dev))) return W4A8_ERR_ALIGN;
-    return launch_dequant_weights(packed_dev, N, K, layout, w8_dev, nullptr, nullptr, 0, static_cast<hipStream_t>(stream));
+    return launch_dequant_weights(packed_dev, N, K, layout, w8_dev, nullptr, nullptr, 0, 0, static_cast<hipStream_t>(stream));
 }
 
 int w4a8_dequant_weights_two_level(const uint8_t* packed_dev, const float* w_scales8_dev, int64_t N, int64_t K,
@@ -162,7 +162,7 @@ int w4a8_dequant_weights_two_level(const uint8_t* packed_dev, const float* w_sca
     if (int e = check_weight_shape(N, K, group_size, W4A8_LAYOUT_TILED)) return e;
     if (!packed_dev || !w_scales8_dev || !w8_dev) return W4A8_ERR_NULL;
     if (!aligned16(packed_dev) || !aligned16(w8_dev) || reinterpret_cast<uintptr_t>(w_scales8_dev) % 4) return W4A8_ERR_ALIGN;
-    return launch_dequant_weights(packed_dev, N, K, W4A8_LAYOUT_TILED, w8_dev, w_scales8_dev, nullptr, group_size,
+    return launch_dequant_weights(packed_dev, N, K, W4A8_LAYOUT_TILED, w8_dev, w_scales8_dev, nullptr, 0, group_size,
                                   static_cast<hipStream_t>(stream));
 }
 
@@ -239,13 +239,46 @@ int w4a8_linear_asym(const uint8_t* x8_dev, int64_t M, int64_t K, int64_t ldx8, 
                                     0, 0, 0, nullptr, 0, MODE_ASYM, nullptr, st);
 }
 
-int w4a8_dequant_weights_asym(const uint8_t* packed_dev, const void* params_dev, int64_t N, int64_t K, int32_t group_size,
-                              uint8_t* w8_dev, void* stream) {
+int w4a8_linear_asym_two_level(const uint8_t* x8_dev, int64_t M, int64_t K, int64_t ldx8, const float* x_scale_dev,
+                               const uint8_t* packed_dev, const void* params8_dev, const float* w_out_scales_dev,
+                               int32_t per_channel, int64_t N, int32_t group_size, void* y_dev, w4a8_dtype y_dtype,
+                               int64_t ldy, void* stream) {
+    const float* params = static_cast<const float*>(params8_dev);
+    if (!valid_dtype(y_dtype)) return W4A8_ERR_DTYPE;
+    if (int e = check_linear(x8_dev, M, K, ldx8, x_scale_dev, packed_dev, params, N, group_size, W4A8_LAYOUT_TILED, y_dev,
+                             y_dtype, ldy))
+        return e;
+    if (!w_out_scales_dev) return W4A8_ERR_NULL;
+    if (reinterpret_cast<uintptr_t>(w_out_scales_dev) % 4) return W4A8_ERR_ALIGN;
+    if (per_channel != 0 && per_channel != 1) return W4A8_ERR_DTYPE;
+    if (M == 0) return W4A8_OK;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const bool deep_narrow = K >= 8192 && N <= 8192;             // same kernel choice as w4a8_linear
+    if (M <= 32 || (M <= 64 && deep_narrow))
+        return launch_linear_skinny(x8_dev, M, K, ldx8, x_scale_dev, packed_dev, params, N, group_size, y_dev, y_dtype, ldy,
+                                    0, 0, 0, w_out_scales_dev, per_channel, MODE_ASYM_TWO, nullptr, st);
+    return launch_linear_mfma_tiled(x8_dev, M, K, ldx8, x_scale_dev, packed_dev, params, N, group_size, y_dev, y_dtype, ldy,
+                                    0, 0, 0, w_out_scales_dev, per_channel, MODE_ASYM_TWO, nullptr, st);
+}
+
+static int dequant_asym(const uint8_t* packed_dev, const void* params_dev, int64_t N, int64_t K, int32_t group_size,
+                        uint8_t* w8_dev, int two_level, void* stream) {
     if (int e = check_weight_shape(N, K, group_size, W4A8_LAYOUT_TILED)) return e;
     if (!packed_dev || !params_dev || !w8_dev) return W4A8_ERR_NULL;
     if (!aligned16(packed_dev) || !aligned16(w8_dev) || !aligned16(params_dev)) return W4A8_ERR_ALIGN;
     return launch_dequant_weights(packed_dev, N, K, W4A8_LAYOUT_TILED, w8_dev, nullptr,
-                                  static_cast<const uint8_t*>(params_dev), group_size, static_cast<hipStream_t>(stream));
+                                  static_cast<const uint8_t*>(params_dev), two_level, group_size,
+                                  static_cast<hipStream_t>(stream));
+}
+
+int w4a8_dequant_weights_asym(const uint8_t* packed_dev, const void* params_dev, int64_t N, int64_t K, int32_t group_size,
+                              uint8_t* w8_dev, void* stream) {
+    return dequant_asym(packed_dev, params_dev, N, K, group_size, w8_dev, 0, stream);
+}
+
+int w4a8_dequant_weights_asym_two_level(const uint8_t* packed_dev, const void* params8_dev, int64_t N, int64_t K,
+                                        int32_t group_size, uint8_t* w8_dev, void* stream) {
+    return dequant_asym(packed_dev, params8_dev, N, K, group_size, w8_dev, 1, stream);
 }
 
 int w4a8_silu_mul(const void* gu_dev, int64_t M, int64_t F, int64_t ldgu, void* h_dev, int64_t ldh, void* stream) {

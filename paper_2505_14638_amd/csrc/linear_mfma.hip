@@ -44,14 +44,18 @@ template <int A, int B> struct MaxOf { static constexpr int value = A > B ? A : 
 // operand is the integer code - zero_point, group scales as in the code-exact mode; `scales` then points at the
 // 80-byte records of scales and zero-points.  MODE_POW2: signed codes, the group scale is a power of two that the
 // matrix unit applies itself (block-scaled MFMA), so the sum over all of K stays in the MFMA accumulator.
+// MODE_ASYM_TWO: the asymmetric records with FP8-domain scales; the weight operand is
+// nearest_E4M3((code - zero_point) * s8[n,g]), accumulation and output scale as in MODE_TWO_LEVEL.
 template <typename OutT, int MF, int KS, int TPW, int MODE>
 __global__ void __launch_bounds__(512, (KS * MF > 16 || MF * TPW > 16) ? 2 : 4) linear_mfma_kernel(
     const uint8_t* __restrict__ x8, int M, int64_t ldx8, const float* __restrict__ s_x,
     const uint8_t* __restrict__ packed, const float* __restrict__ scales, int N, int n_tiles, int C, int cpg, int NG,
     OutT* __restrict__ y, int64_t ldy, int grid_m, int grid_n, const float* __restrict__ w_out, int per_channel,
     const float* __restrict__ y_scale) {
-    constexpr bool TWO = MODE == MODE_TWO_LEVEL, ASYM = MODE == MODE_ASYM, POW2 = MODE == MODE_POW2;
-    constexpr bool IN_MFMA = TWO || POW2;                        // the sum over K stays in the MFMA accumulator
+    constexpr bool ASYM2 = MODE == MODE_ASYM_TWO;                // asymmetric records, two-level bytes
+    constexpr bool TWO = MODE == MODE_TWO_LEVEL, ASYM = MODE == MODE_ASYM || ASYM2, POW2 = MODE == MODE_POW2;
+    constexpr bool IN_MFMA = TWO || POW2 || ASYM2;               // the sum over K stays in the MFMA accumulator
+    constexpr bool OUT_SCALED = TWO || ASYM2;                    // output scaled by s_x * w_out[n]
     constexpr int REC = ASYM ? ASYM_RECORD_BYTES : 64;           // bytes of scales (and zero-points) per band and group
     constexpr int NB = WAVES / KS;                               // wavefronts per K-split group, TPW weight bands each
     constexpr int BN = 16 * NB * TPW, BM = 16 * MF;
@@ -190,7 +194,8 @@ __global__ void __launch_bounds__(512, (KS * MF > 16 || MF * TPW > 16) ? 2 : 4) 
         for (int j = 0; j < TPW; ++j) tab[j] = TWO ? two_level_table(next.s[j]) : MagTable{0u, 0u, 0u};
         AsymTable atab[TPW];                                     // asymmetric format: the next chunk's code - zero_point bytes
 #pragma unroll
-        for (int j = 0; j < TPW; ++j) atab[j] = ASYM ? asym_table(zp[j]) : AsymTable{{0u, 0u, 0u, 0u}};
+        for (int j = 0; j < TPW; ++j)
+            atab[j] = ASYM2 ? asym_two_level_table(zp[j], next.s[j]) : ASYM ? asym_table(zp[j]) : AsymTable{{0u, 0u, 0u, 0u}};
         if (c < C) {
             const uint8_t* xb = lds + buf * STAGE_BYTES;
             uint4 xa = *reinterpret_cast<const uint4*>(xb + xa_off);
@@ -208,7 +213,7 @@ __global__ void __launch_bounds__(512, (KS * MF > 16 || MF * TPW > 16) ? 2 : 4) 
 #pragma unroll
                 for (int j = 0; j < TPW; ++j) {
                     const int st = f * TPW + j;                  // step number
-                    if (TWO) acc[f][j] = mfma_16x16x128_e4m3(xop, cur.op[j], acc[f][j]);
+                    if (TWO || ASYM2) acc[f][j] = mfma_16x16x128_e4m3(xop, cur.op[j], acc[f][j]);
                     if (POW2) acc[f][j] = mfma_16x16x128_e4m3_scaled(xop, cur.op[j], acc[f][j], E8M0_ONE, e8m0_of(cur.s[j]));
                     const v4f p = IN_MFMA ? v4f{0.f, 0.f, 0.f, 0.f} : mfma_16x16x128_e4m3(xop, cur.op[j], v4f{0.f, 0.f, 0.f, 0.f});
                     if (!IN_MFMA && st > 0) {
@@ -288,7 +293,8 @@ __global__ void __launch_bounds__(512, (KS * MF > 16 || MF * TPW > 16) ? 2 : 4) 
 #pragma unroll
         for (int j = 0; j < TPW; ++j)
             wa.op[j] = TWO    ? slot_to_operand_two_level<true>(raw0[j], two_level_table(wa.s[j]))
-                       : ASYM ? slot_to_operand_asym(raw0[j], asym_table(zp0[j]))
+                       : ASYM2 ? slot_to_operand_asym(raw0[j], asym_two_level_table(zp0[j], wa.s[j]))
+                       : ASYM  ? slot_to_operand_asym(raw0[j], asym_table(zp0[j]))
                               : slot_to_operand<true>(raw0[j]);
     }
     lds_dma_wait_all();
@@ -335,7 +341,7 @@ __global__ void __launch_bounds__(512, (KS * MF > 16 || MF * TPW > 16) ? 2 : 4) 
 #pragma unroll
     for (int j = 0; j < TPW; ++j) {
         const int n = bn * BN + (band * TPW + j) * 16 + i;
-        so[j] = TWO ? sx * w_out[per_channel ? min(n, N - 1) : 0] : sx;
+        so[j] = OUT_SCALED ? sx * w_out[per_channel ? min(n, N - 1) : 0] : sx;
     }
     OutT* slab = reinterpret_cast<OutT*>(lds);
     constexpr int VEC = 16 / sizeof(OutT);                       // elements per 16-byte store
@@ -392,6 +398,8 @@ void launch_one(const LinearArgs& a, dim3 grid, int grid_m, int grid_n, hipStrea
         W4A8_MFMA(MODE_ASYM);
     else if (a.mode == MODE_POW2)
         W4A8_MFMA(MODE_POW2);
+    else if (a.mode == MODE_ASYM_TWO)
+        W4A8_MFMA(MODE_ASYM_TWO);
     else
         W4A8_MFMA(MODE_CODE_EXACT);
 #undef W4A8_MFMA

@@ -37,16 +37,19 @@ constexpr int max_threads(int tiles, bool asym = false) {
 // the wavefront's share of K stays in the MFMA accumulator and the output is scaled by s_x * w_out[n] (w_out[0] when
 // per_channel is 0).  MODE_ASYM: unsigned codes with per-group zero-points, the weight operand is the integer
 // code - zero_point, scales as in the code-exact mode; `scales` then points at the 80-byte records of scales and
-// zero-points.  MODE_POW2: signed codes, the group scale is a power of two that the matrix unit applies itself
+// zero-points; MODE_ASYM_TWO: the same records with FP8-domain scales, the weight operand is
+// nearest_E4M3((code - zero_point) * s8[n,g]), accumulation and output scale as in MODE_TWO_LEVEL.  MODE_POW2: signed codes, the group scale is a power of two that the matrix unit applies itself
 // (block-scaled MFMA); the sum over the wavefront's share of K stays in the MFMA accumulator.
 template <int MT, int NT, int DEPTH, typename OutT, int MODE>
-__global__ void __launch_bounds__(max_threads(MT * NT, MODE == MODE_ASYM)) linear_skinny_kernel(
+__global__ void __launch_bounds__(max_threads(MT * NT, MODE == MODE_ASYM || MODE == MODE_ASYM_TWO)) linear_skinny_kernel(
     const uint8_t* __restrict__ x8, int M, int64_t ldx8, const float* __restrict__ s_x,
     const uint8_t* __restrict__ packed, const float* __restrict__ scales, int N, int n_tiles, int C, int cpg, int NG,
     OutT* __restrict__ y, int64_t ldy, int cpw, const float* __restrict__ w_out, int per_channel,
     const float* __restrict__ y_scale) {
+    constexpr bool ASYM2 = MODE == MODE_ASYM_TWO;                // asymmetric records, two-level bytes, sum kept in the MFMA
     constexpr bool TWO = MODE == MODE_TWO_LEVEL, ASYM = MODE == MODE_ASYM, POW2 = MODE == MODE_POW2;
-    constexpr int REC = ASYM ? ASYM_RECORD_BYTES : 64;           // bytes of scales (and zero-points) per tile and group
+    constexpr bool OUT_SCALED = TWO || ASYM2;                    // output scaled by s_x * w_out[n]
+    constexpr int REC = (ASYM || ASYM2) ? ASYM_RECORD_BYTES : 64;   // bytes of scales (and zero-points) per tile and group
     extern __shared__ float red[];
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);     // wave-uniform: keeps the loop scalar
@@ -78,11 +81,12 @@ __global__ void __launch_bounds__(max_threads(MT * NT, MODE == MODE_ASYM)) linea
 #pragma unroll
         for (int j = 0; j < NT; ++j) {
             L.w[j] = *reinterpret_cast<const uint4*>(wbase[j] + woff);
-            if (TWO || POW2)                                    // the scale of the channel whose nibbles this lane expands
+            if (TWO || POW2 || ASYM2)                           // the scale of the channel whose nibbles this lane expands
                 L.s[j] = make_float4(*reinterpret_cast<const float*>(sbase[j] + (int64_t)g * REC + i * 4), 0.f, 0.f, 0.f);
             else
                 L.s[j] = *reinterpret_cast<const float4*>(sbase[j] + (int64_t)g * REC + soff);
-            L.z[j] = ASYM ? *reinterpret_cast<const uint32_t*>(sbase[j] + (int64_t)g * REC + 64 + kq * 4) : 0u;
+            L.z[j] = ASYM ? *reinterpret_cast<const uint32_t*>(sbase[j] + (int64_t)g * REC + 64 + kq * 4)
+                          : ASYM2 ? (uint32_t)sbase[j][(int64_t)g * REC + 64 + i] : 0u;   // ASYM2: the expanding channel's own
             wbase[j] += 1024;
         }
 #pragma unroll
@@ -119,12 +123,14 @@ __global__ void __launch_bounds__(max_threads(MT * NT, MODE == MODE_ASYM)) linea
         for (int j = 0; j < NT; ++j) {
             const float4 s = L.s[j];
             // a marked scale (sign bit) on any of the band's 16 channels: this chunk's tile may hold -8
-            const bool m8 = !ASYM && any_marked(__uint_as_float(__float_as_uint(s.x) | __float_as_uint(s.y) |
+            const bool m8 = !ASYM && !ASYM2 && any_marked(__uint_as_float(__float_as_uint(s.x) | __float_as_uint(s.y) |
                                                                 __float_as_uint(s.z) | __float_as_uint(s.w)));
             v8i wop;
             if (TWO) {
                 const MagTable tab = two_level_table(s.x);
                 wop = m8 ? slot_to_operand_two_level<true>(L.w[j], tab) : slot_to_operand_two_level<false>(L.w[j], tab);
+            } else if (ASYM2) {
+                wop = slot_to_operand_asym(L.w[j], asym_two_level_table(L.z[j], s.x));
             } else if (ASYM) {
                 wop = slot_to_operand_half_offset(L.w[j]);       // code - 7.5
             } else {
@@ -136,7 +142,7 @@ __global__ void __launch_bounds__(max_threads(MT * NT, MODE == MODE_ASYM)) linea
             }
 #pragma unroll
             for (int mt = 0; mt < MT; ++mt) {
-                if (TWO) {
+                if (TWO || ASYM2) {
                     acc[mt][j] = mfma_16x16x128_e4m3(wop, xop[mt], acc[mt][j]);
                     continue;
                 }
@@ -208,7 +214,7 @@ __global__ void __launch_bounds__(max_threads(MT * NT, MODE == MODE_ASYM)) linea
         float sum = 0.0f;
         for (int w = 0; w < waves; ++w) sum += red[(w * E + e) * RED_STRIDE + src_lane];
         const int m = mt * 16 + ml, n = (t0 + j) * 16 + nl;
-        if (m < M && n < N) y[(int64_t)m * ldy + n] = OutCast<OutT>::cast((TWO ? sx * w_out[per_channel ? n : 0] : sx) * sum, yq);
+        if (m < M && n < N) y[(int64_t)m * ldy + n] = OutCast<OutT>::cast((OUT_SCALED ? sx * w_out[per_channel ? n : 0] : sx) * sum, yq);
     }
 }
 
@@ -232,6 +238,8 @@ int launch_one(const LinearArgs& a, int depth, int waves, hipStream_t st) {
         W4A8_SKINNY(2, MODE_ASYM);
     else if (a.mode == MODE_POW2)
         W4A8_SKINNY(2, MODE_POW2);
+    else if (a.mode == MODE_ASYM_TWO)
+        W4A8_SKINNY(2, MODE_ASYM_TWO);
     else if (depth == DEEP)
         W4A8_SKINNY(DEEP, MODE_CODE_EXACT);
     else
@@ -282,7 +290,7 @@ int launch_linear_skinny(const uint8_t* x8, int64_t M, int64_t K, int64_t ldx8, 
         while (waves < 16 && waves * waves * 2 < want * want) waves *= 2;   // odd counts split K unevenly and measured slower
     }
     if (waves > C) waves = C;
-    const int thread_cap = max_threads(mt * nt, mode == MODE_ASYM);
+    const int thread_cap = max_threads(mt * nt, mode == MODE_ASYM || mode == MODE_ASYM_TWO);
     while (waves > 1 && (waves * mt * nt > 64 || waves * 64 > thread_cap)) --waves;   // LDS and registers
     if (waves < 1 || waves > 16 || waves * mt * nt > 64 || waves * 64 > thread_cap) return W4A8_ERR_SHAPE;
     if (depth == 0) depth = 2;                                   // deeper rings cost occupancy and measured no faster

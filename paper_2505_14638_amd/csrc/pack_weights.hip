@@ -203,7 +203,8 @@ __global__ void __launch_bounds__(256) pack_asym_kernel(const void* __restrict__
 __global__ void __launch_bounds__(256) dequant_tiled_kernel(const uint4* __restrict__ packed, int64_t N, int64_t K,
                                                             int64_t slots, uint8_t* __restrict__ w8,
                                                             const float* __restrict__ scales8,
-                                                            const uint8_t* __restrict__ asym_params, int32_t G) {
+                                                            const uint8_t* __restrict__ asym_params, int asym_two_level,
+                                                            int32_t G) {
     const int64_t u = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (u >= slots) return;
     const int64_t tile = u >> 6, C = K >> 7;
@@ -217,7 +218,9 @@ __global__ void __launch_bounds__(256) dequant_tiled_kernel(const uint4* __restr
         op = slot_to_operand_two_level<true>(packed[u], two_level_table(scales8[(t * NG + grp) * 16 + i]));
     } else if (asym_params) {
         const int64_t NG = K / G, grp = (c * 128) / G;
-        op = slot_to_operand_asym(packed[u], asym_table(asym_params[(t * NG + grp) * ASYM_RECORD_BYTES + 64 + i]));
+        const uint8_t* rec = asym_params + (t * NG + grp) * ASYM_RECORD_BYTES;
+        op = slot_to_operand_asym(packed[u], asym_two_level ? asym_two_level_table(rec[64 + i], reinterpret_cast<const float*>(rec)[i])
+                                                            : asym_table(rec[64 + i]));
     } else {
         op = slot_to_operand<true>(packed[u]);
     }
@@ -284,11 +287,12 @@ int launch_pack_weights_asym(const void* src, w4a8_src kind, const float* src_sc
 }
 
 int launch_dequant_weights(const uint8_t* packed, int64_t N, int64_t K, w4a8_layout layout, uint8_t* w8,
-                           const float* scales8, const uint8_t* asym_params, int32_t G, hipStream_t st) {
+                           const float* scales8, const uint8_t* asym_params, int asym_two_level, int32_t G,
+                           hipStream_t st) {
     if (layout == W4A8_LAYOUT_TILED) {
         const int64_t slots = ((N + 15) / 16) * (K / 128) * 64;
         hipLaunchKernelGGL(dequant_tiled_kernel, dim3(blocks_for(slots)), dim3(256), 0, st,
-                           reinterpret_cast<const uint4*>(packed), N, K, slots, w8, scales8, asym_params, G);
+                           reinterpret_cast<const uint4*>(packed), N, K, slots, w8, scales8, asym_params, asym_two_level, G);
     } else {
         const int64_t bytes = N * (K / 2);
         hipLaunchKernelGGL(dequant_canonical_kernel, dim3(blocks_for(bytes)), dim3(256), 0, st, packed, bytes, w8);

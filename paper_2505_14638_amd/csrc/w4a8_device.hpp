@@ -8,6 +8,18 @@ namespace w4a8 {
 typedef int v8i __attribute__((ext_vector_type(8)));
 typedef float v4f __attribute__((ext_vector_type(4)));
 
+// Saturate to the E4M3 range (Sec. 4.1: +-448) before the hardware rounding; NaN passes through.
+__device__ __forceinline__ float sat448(float t) {
+    const float c = __builtin_fminf(__builtin_fmaxf(t, -448.0f), 448.0f);
+    return (t != t) ? t : c;
+}
+
+// Two float32 -> two E4M3 bytes (round to nearest even, saturating) in the low or high half of `old`.
+__device__ __forceinline__ uint32_t cvt2(float a, float b, uint32_t old, bool high) {
+    return high ? (uint32_t)__builtin_amdgcn_cvt_pk_fp8_f32(sat448(a), sat448(b), (int)old, true)
+                : (uint32_t)__builtin_amdgcn_cvt_pk_fp8_f32(sat448(a), sat448(b), (int)old, false);
+}
+
 // ---------------------------------------------------------------------------------------------
 // INT4 -> E4M3 (Eq. 10 with zero-point 0; the group scale is applied to the group's partial sum).
 //   value   0    1    2    3    4    5    6    7     |  -8   -7   -6   -5   -4   -3   -2   -1
@@ -164,6 +176,20 @@ __device__ __forceinline__ AsymTable asym_table(uint32_t z) {
     return T;
 }
 
+// The same table for the two-level reading of the asymmetric format (Eq. 10 taken literally with a zero-point): byte
+// p = nearest_E4M3( float32(code(p) - z) * s8 ), the product one float32 multiplication, saturating at +-448.
+__device__ __forceinline__ AsymTable asym_two_level_table(uint32_t z, float s8) {
+    const float zf = (float)(z & 15u);
+    AsymTable T;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+        const float c0 = (float)(w < 2 ? 8 + 4 * w : 15 - 4 * w), step = w < 2 ? 1.0f : -1.0f;
+        T.t[w] = cvt2((c0 - zf) * s8, (c0 + step - zf) * s8, 0u, false);
+        T.t[w] = cvt2((c0 + 2.0f * step - zf) * s8, (c0 + 3.0f * step - zf) * s8, T.t[w], true);
+    }
+    return T;
+}
+
 // E4M3 bytes of the half-integers h = +-(m + 0.5) of the four nibbles at bit offset SHIFT of the bytes of w.
 template <int SHIFT>
 __device__ __forceinline__ uint32_t asym_half_offset(uint32_t w) {
@@ -281,18 +307,6 @@ __device__ __forceinline__ uint16_t f32_to_bf16_bits(float f) {
 }
 
 __device__ __forceinline__ float bf16_bits_to_f32(uint16_t b) { return __uint_as_float(((uint32_t)b) << 16); }
-
-// Saturate to the E4M3 range (Sec. 4.1: +-448) before the hardware rounding; NaN passes through.
-__device__ __forceinline__ float sat448(float t) {
-    const float c = __builtin_fminf(__builtin_fmaxf(t, -448.0f), 448.0f);
-    return (t != t) ? t : c;
-}
-
-// Two float32 -> two E4M3 bytes (round to nearest even, saturating) in the low or high half of `old`.
-__device__ __forceinline__ uint32_t cvt2(float a, float b, uint32_t old, bool high) {
-    return high ? (uint32_t)__builtin_amdgcn_cvt_pk_fp8_f32(sat448(a), sat448(b), (int)old, true)
-                : (uint32_t)__builtin_amdgcn_cvt_pk_fp8_f32(sat448(a), sat448(b), (int)old, false);
-}
 
 // Eq. 13 for one value: nearest_E4M3(x / s), the quotient one IEEE float32 division.
 __device__ __forceinline__ uint8_t quantize_one(float x, float s) { return (uint8_t)(cvt2(x / s, 0.0f, 0u, false) & 0xFFu); }

@@ -17,7 +17,9 @@ inline int launch_status() { return hip_status(hipGetLastError()); }
 //                    per_channel is 0)
 //   MODE_ASYM        unsigned codes, `scales` = the 80-byte records of group scales and zero-points
 //   MODE_POW2        signed codes, power-of-two group scales applied by the matrix unit (block-scaled MFMA)
-enum WeightMode { MODE_CODE_EXACT = 0, MODE_TWO_LEVEL = 1, MODE_ASYM = 2, MODE_POW2 = 3 };
+//   MODE_ASYM_TWO    unsigned codes and zero-points with FP8-domain group scales in the 80-byte records: the two-level
+//                    reading of the asymmetric format; output scaled like MODE_TWO_LEVEL
+enum WeightMode { MODE_CODE_EXACT = 0, MODE_TWO_LEVEL = 1, MODE_ASYM = 2, MODE_POW2 = 3, MODE_ASYM_TWO = 4 };
 
 // What the launchers of the tiled-layout linear kernels pass down to a launch: the operands of w4a8_linear after
 // validation.
@@ -50,9 +52,11 @@ int launch_pack_weights(const void* src, w4a8_src kind, const float* src_scales,
 int launch_pack_weights_asym(const void* src, w4a8_src kind, const float* src_scales, const uint8_t* src_zeros,
                              int64_t N, int64_t K, int32_t G, uint8_t* packed, uint8_t* params, hipStream_t st);
 // tiled layout only: scales8 != nullptr: the two-level bytes nearest_E4M3(code * s8[n,g]); asym_params != nullptr: the
-// asymmetric format's bytes nearest_E4M3(code - zero_point[n,g])
+// asymmetric format's bytes nearest_E4M3(code - zero_point[n,g]), or with asym_two_level its two-level bytes
+// nearest_E4M3((code - zero_point[n,g]) * s8[n,g])
 int launch_dequant_weights(const uint8_t* packed, int64_t N, int64_t K, w4a8_layout layout, uint8_t* w8,
-                           const float* scales8, const uint8_t* asym_params, int32_t G, hipStream_t st);
+                           const float* scales8, const uint8_t* asym_params, int asym_two_level, int32_t G,
+                           hipStream_t st);
 int launch_linear_canonical(const uint8_t* x8, int64_t M, int64_t K, int64_t ldx8, const float* s_x,
                             const uint8_t* packed, const float* scales, int64_t N, int32_t G, void* y,
                             w4a8_dtype ydt, int64_t ldy, hipStream_t st);

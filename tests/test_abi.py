@@ -158,6 +158,13 @@ def test_asym_validation(L):
     assert f(P, 4, 256, 256, P, P, P, 64, 96, P, B.BF16, 64, None) == 3
     assert f(P, 4, 256, 128, P, P, P, 64, 128, P, B.BF16, 64, None) == 2
     assert f(P, 4, 256, 256, P, P, P, 64, 128, P, 5, 64, None) == 4
+    t = L.w4a8_linear_asym_two_level
+    # x8, M, K, ldx8, xs, packed, params8, s_out, per_channel, N, G, y, ydt, ldy, stream
+    assert t(P, 0, 256, 256, P, P, P, P, 1, 64, 128, P, B.BF16, 64, None) == 0
+    assert t(P, 4, 256, 256, P, P, P, 0, 1, 64, 128, P, B.BF16, 64, None) == 1
+    assert t(P, 4, 256, 256, P, P, P, P, 3, 64, 128, P, B.BF16, 64, None) == 4
+    assert t(P, 4, 256, 256, P, P, P + 4, P, 1, 64, 128, P, B.BF16, 64, None) == 6
+    assert L.w4a8_dequant_weights_asym_two_level(P, 0, 16, 256, 128, P, None) == 1
     d = L.w4a8_dequant_weights_asym
     assert d(P, 0, 16, 256, 128, P, None) == 1
     assert d(P, P, 16, 256, 64, P, None) == 3

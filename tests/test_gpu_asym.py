@@ -149,3 +149,83 @@ def test_llama_shapes_sampled(gpu_lib, m, layer):
     ok, worst = o.within_tolerance(y32[np.ix_(rows, cols)], ref, a)
     print(f"  asym {layer} M={m}: worst err/bound {worst:.3e}", flush=True)
     assert ok
+
+
+# ---- the two-level reading of the asymmetric format (Eq. 8-11 literally) --------------------------------------------
+TWO_LEVEL_FLOOR = 2.0 ** -4      # both operands span the whole E4M3 range; same allowance as the signed two-level layer
+
+
+def literal_inputs(w, g):
+    """Offline side of Eq. 6-9 as test input: per-channel s_w = max|W| / 448, W8 = the E4M3 values of W / s_w, per
+    group (range extended to contain zero) s8 = (max W8 - min W8) / 15, z = round(-min W8 / s8),
+    u = clamp(round(W8 / s8 + z), 0, 15): the oracle's asymmetric quantizer applied to W8."""
+    s_w = (np.abs(w).max(axis=1) / np.float32(448.0)).astype(np.float32)
+    s_w[s_w == 0] = 1.0
+    w8 = o.e4m3_decode(o.e4m3_encode((w / s_w[:, None]).astype(np.float32))).astype(np.float32)
+    u, s8, z = o.asym_quantize_weights(w8, g)
+    return u, z, s8, s_w
+
+
+def test_two_level_bytes_bit_exact_with_saturation_ties_and_zero_scale(gpu_lib):
+    rng = np.random.default_rng(47)
+    n, k, g = 72, 1024, 128
+    u = rng.integers(0, 16, size=(n, k), dtype=np.uint8)
+    z = rng.integers(0, 16, size=(n, k // g), dtype=np.uint8)
+    s8 = np.exp(rng.uniform(np.log(2.0 ** -12), np.log(60.0), size=(n, k // g))).astype(np.float32)
+    s8[3, 2] = 0.0
+    s8[5, 1] = 2.0 ** -10 / 3                                           # 3 * s8 sits on the tie between 0 and 2^-9
+    s8[6, 0] = 64.0                                                     # 7 * 64 = 448 exactly; 8 * 64 saturates
+    z[6, 0] = 4
+    _, want = o.linear_ref_asym_paper_literal(np.zeros((1, k), np.uint8), np.float32(1), u, z, s8, np.ones(n), g)
+    packed, params = B.pack_weights_asym(dev(u), g, dev(s8), dev(z))
+    got = host(B.dequant_weights_asym(packed, params, n, k, g, two_level=True))
+    assert np.array_equal(got & 0x7F, want & 0x7F)
+    nz = (want & 0x7F) != 0
+    assert np.array_equal(got[nz], want[nz])                            # signs of all non-zero bytes
+    assert (want & 0x7F).max() == 0x7E and (~nz).any()
+
+
+@pytest.mark.parametrize("m,k,n,g", [(1, 1024, 96, 128), (16, 2048, 200, 256), (40, 1024, 72, 128), (64, 512, 48, 512),
+                                     (100, 384, 300, 128), (300, 1024, 520, 512), (257, 640, 130, 128), (600, 2048, 1024, 128)])
+def test_two_level_linear_against_the_oracle(gpu_lib, m, k, n, g):
+    rng = np.random.default_rng([48, m, k, n])
+    w = syn.make_weights(rng, n, k)
+    x = syn.make_activations(rng, m, k, 0.02, 20.0)
+    s_x = syn.static_act_scale(x)
+    x8 = o.quantize_act(x, s_x)
+    u, z, s8, s_w = literal_inputs(w, g)
+    ref, want8 = o.linear_ref_asym_paper_literal(x8, s_x, u, z, s8, s_w, g)
+    a = float(np.float32(s_x)) * (np.abs(o.e4m3_decode(x8)) @ np.abs(o.e4m3_decode(want8)).T) * s_w.astype(np.float64)[None, :]
+    packed, params = B.pack_weights_asym(dev(u), g, dev(s8), dev(z))
+    y32 = host(B.linear_asym_two_level(dev(x8), sx_dev(s_x), packed, params, dev(s_w), n, g, out_dtype=torch.float32))
+    y16 = host(B.linear_asym_two_level(dev(x8), sx_dev(s_x), packed, params, dev(s_w), n, g,
+                                       out_dtype=torch.bfloat16).view(torch.int16))
+    ok, worst = o.within_tolerance(y32, ref, a, floor=TWO_LEVEL_FLOOR)
+    print(f"  asym two-level {m}x{k}x{n} g{g}: worst err/bound {worst:.3e}", flush=True)
+    assert ok
+    assert np.array_equal(y16.view(np.uint16), o.round_to_bf16_bits(y32.astype(np.float64)))
+    full = x.astype(np.float64) @ w.astype(np.float64).T
+    assert np.linalg.norm(ref - full) / np.linalg.norm(full) < 0.25
+
+
+@pytest.mark.parametrize("m", [3, 48, 200])
+def test_two_level_exact_integer_case_bit_for_bit_and_per_tensor_scale(gpu_lib, m):
+    rng = np.random.default_rng([49, m])
+    k, n, g = 2048, 176, 128
+    ng = k // g
+    xi = rng.integers(-4, 5, size=(m, k))
+    x8 = o.e4m3_encode(xi.astype(np.float32))
+    u = rng.integers(0, 16, size=(n, k), dtype=np.uint8)
+    z = rng.integers(0, 16, size=(n, ng), dtype=np.uint8)
+    e = rng.integers(-1, 3, size=(n, ng))
+    s8 = np.ldexp(1.0, e).astype(np.float32)
+    d = u.reshape(n, ng, g).astype(np.int64) - z[:, :, None].astype(np.int64)
+    part = np.einsum("mgk,ngk->mng", xi.reshape(m, ng, g).astype(np.int64), d)
+    acc = (part * np.ldexp(1.0, e)[None]).sum(axis=2)
+    s_w = np.ldexp(1.0, rng.integers(-3, 2, size=n)).astype(np.float32)
+    packed, params = B.pack_weights_asym(dev(u), g, dev(s8), dev(z))
+    y32 = host(B.linear_asym_two_level(dev(x8), sx_dev(0.5), packed, params, dev(s_w), n, g, out_dtype=torch.float32))
+    assert np.array_equal(y32, (0.5 * acc * s_w[None, :]).astype(np.float32))
+    y32t = host(B.linear_asym_two_level(dev(x8), sx_dev(0.5), packed, params, dev(np.full(1, 0.25, np.float32)), n, g,
+                                        out_dtype=torch.float32))
+    assert np.array_equal(y32t, (0.5 * 0.25 * acc).astype(np.float32))

@@ -192,3 +192,34 @@ def test_quantize_then_layer_close_to_unquantized(g):
     ref = xd @ w.astype(np.float64).T
     bound = np.abs(xd) @ np.repeat(0.5 * s.astype(np.float64) * (1 + 1e-5), g, axis=1).T
     assert np.all(np.abs(y - ref) <= bound + 1e-12)
+
+
+def test_literal_asym_bytes_hand_values_and_special_cases():
+    """(u - z) * s8 on hand-picked cases: exact grid points, a tie (2^-10 * 3 / ... is covered by the E4M3 pins; here
+    17 * 1 = 17 lies between 16 and 18 -> ties to the even mantissa, 16), saturation, zero."""
+    u = np.array([[15, 0, 9, 7, 15, 15]], dtype=np.uint8)
+    z = np.array([[7, 7, 7, 7, 0, 0]], dtype=np.uint8)             # groups of one weight
+    s8 = np.array([[2.0, 3.0, 8.5, 100.0, 1.0, 40.0]], dtype=np.float32)
+    _, w8 = o.linear_ref_asym_paper_literal(np.zeros((1, 6), np.uint8), np.float32(1), u, z, s8, np.ones(1), 1)
+    # 8*2 = 16; -7*3 = -21 -> between -20 and -22: tie -> even mantissa: -20 (1.010 x 16) vs -22 (1.011 x 16) -> -20;
+    # 2*8.5 = 17 -> tie between 16 and 18 -> 16; 0*100 = 0; 15*1 = 15; 15*40 = 600 -> 448
+    assert o.e4m3_decode(w8).tolist() == [[16.0, -20.0, 16.0, 0.0, 15.0, 448.0]]
+
+
+def test_literal_asym_reduces_to_known_layers():
+    rng = np.random.default_rng(26)
+    x8, u, z, _ = _tiny_case(26, 4, 256, 9, 128)
+    # power-of-two scales keep (u - z) * s8 on the grid: the literal layer equals the factored one (Eq. 14)
+    e = rng.integers(-3, 3, size=(9, 2))
+    s8 = np.ldexp(1.0, e).astype(np.float32)
+    s_out = (rng.random(9) + 0.5).astype(np.float32)
+    y_lit, w8 = o.linear_ref_asym_paper_literal(x8, np.float32(0.1), u, z, s8, s_out, 128)
+    y_fac, _ = o.linear_ref_asym(x8, np.float32(0.1), u, z, s8, 128)
+    assert np.allclose(y_lit, y_fac * s_out.astype(np.float64)[None, :], rtol=1e-13, atol=0)
+    # zero-point 8 and codes q + 8: the signed two-level layer, byte for byte
+    q = rng.integers(-8, 8, size=(9, 256)).astype(np.int8)
+    s8r = (rng.random((9, 2), dtype=np.float32) + np.float32(0.2)) * np.float32(9.0)
+    y0, b0 = o.linear_ref_paper_literal(x8, np.float32(0.1), q, s8r, s_out, 128)
+    y1, b1 = o.linear_ref_asym_paper_literal(x8, np.float32(0.1), (q.astype(np.int16) + 8).astype(np.uint8),
+                                             np.full((9, 2), 8, np.uint8), s8r, s_out, 128)
+    assert np.array_equal(b0 & 0x7F, b1 & 0x7F) and np.array_equal(y0, y1)     # -0 / +0 bytes may differ in sign only
