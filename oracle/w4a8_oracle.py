@@ -38,6 +38,9 @@ dequant_asym_to_e4m3         Eq. 10 / Eq. 14: the integer (code - zero_point) as
                              E4M3 byte
 linear_ref_asym              Eq. 14, Eq. 4, Eq. 11 with unsigned codes and
                              per-group zero-points
+hessian_inverse_factor,      Alg. 1 (DPQ), Eq. 5-12, Sec. 3.3 (dampening, Cholesky), and
+gar_permutation,             Group-Aware Reordering (Sec. 3.2, App. A.3): the offline
+dpq_quantize                 calibration that produces the codes, scales and zero-points
 linear_ref_asym_paper_literal  Eq. 8-11 read literally: (code - zero_point) * scale
                              rounded onto the E4M3 grid before the matmul
 pack_* / unpack_* / tile_*   storage formats of the C-ABI boundary (the tiled one keeps
@@ -540,6 +543,99 @@ def within_tolerance(y, ref, a, rel: float = 2e-3, floor: float = 2.0 ** -6):
     with np.errstate(divide="ignore", invalid="ignore"):
         ratio = np.where(bound > 0, err / bound, np.where(err == 0, 0.0, np.inf))
     return bool(np.all(err <= bound)), float(np.max(ratio)) if ratio.size else 0.0
+
+
+# --------------------------------------------------------------------------------------
+# Offline calibration: DPQ (Alg. 1, Eq. 5-12) and Group-Aware Reordering (Sec. 3.2, App. A.3)
+# --------------------------------------------------------------------------------------
+def hessian_inverse_factor(x, damp: float = 0.01) -> np.ndarray:
+    """The matrix U that carries the updates of Eq. 12 for the layer-wise objective of Eq. 5 (Hessian H = X^T X,
+    App. A.2; dampened by `damp` times the mean of its diagonal, Sec. 3.3): U is the upper-triangular Cholesky factor
+    of H^-1 (H^-1 = U^T U).  Row q of U, right of the diagonal, divided by U[q, q], equals row q of the inverse of the
+    Hessian restricted to the not-yet-quantized weights q, q+1, ..., divided by its diagonal entry -- the factor of
+    Eq. 12 -- which is the reason Sec. 3.3 gives for using the Cholesky decomposition.  float64 throughout; x is [T, K]."""
+    x = np.asarray(x, dtype=np.float64)
+    h = x.T @ x
+    h = h + np.eye(h.shape[0]) * (damp * np.mean(np.diag(h)))
+    hinv = np.linalg.inv(h)
+    return np.linalg.cholesky(hinv).T.copy()                # lower factor L with H^-1 = L L^T; U = L^T
+
+
+def gar_permutation(h_diag, group_size: int) -> np.ndarray:
+    """Group-Aware Reordering (Sec. 3.2, App. A.3): position i of the reordered tensor holds original column perm[i].
+    Columns keep their group; inside a group they are ordered by descending Hessian diagonal, and whole groups are
+    ordered by the descending maximum of their diagonal entries (ties: lower original index first)."""
+    d = np.asarray(h_diag, dtype=np.float64)
+    k = d.size
+    assert k % group_size == 0
+    groups = d.reshape(k // group_size, group_size)
+    inside = np.argsort(-groups, axis=1, kind="stable")                       # per group, local order
+    order = np.argsort(-groups.max(axis=1), kind="stable")                   # order of the groups
+    return (order[:, None] * group_size + inside[order]).reshape(k).astype(np.int64)
+
+
+def dpq_quantize(w, u_factor, s_w, group_size: int, perm=None):
+    """Dual Precision Quantization, Alg. 1, for all rows at once.  `w` is W16 [N, K]; `u_factor` the matrix of
+    hessian_inverse_factor for the (reordered, if `perm` is given) columns; `s_w` the BF16 -> FP8 scale of Eq. 6, one
+    per row or a single one.  Columns are visited in the order perm[0], perm[1], ... (GAR; identity when perm is None)
+    and the results are returned in the original order, the group parameters with their original groups.
+
+    Every operation is one float32 operation, in this order, so that a float32 implementation can take the same
+    integer decisions:
+      at the start of each group (Eq. 8, on the group's current weights, range extended to contain zero as in
+      asym_quantize_weights):     W8 = val(nearest_Z(W / s_w)); s = (max W8 - min W8) / 15; z = round(-min W8 / s)
+      for each weight of the group, left to right:
+        w8     = val(nearest_Z(w / s_w))                          Eq. 7
+        u      = clamp(round(w8 / s + z), 0, 15)                  Eq. 9
+        w8_hat = val(nearest_Z((u - z) * s))                      Eq. 10, rounded onto the grid as inference will do
+        w_hat  = w8_hat * s_w                                     Eq. 11
+        err    = (w - w_hat) / U[q, q]
+        w_v    = w_v - err * U[q, v]  for every later column v    Eq. 12
+    Returns (codes uint8 [N, K], scales float32 [N, K/G] in the FP8 domain, zero-points uint8 [N, K/G])."""
+    w = np.array(w, dtype=np.float32, copy=True)
+    n, k = w.shape
+    u_factor = np.asarray(u_factor, dtype=np.float32)
+    assert u_factor.shape == (k, k) and k % group_size == 0
+    s_w = np.broadcast_to(np.asarray(s_w, dtype=np.float32).reshape(-1), (n,)).astype(np.float32)
+    perm = np.arange(k) if perm is None else np.asarray(perm, dtype=np.int64)
+    w = w[:, perm]
+    codes_p = np.zeros((n, k), dtype=np.uint8)
+    scales_p = np.zeros((n, k // group_size), dtype=np.float32)
+    zeros_p = np.zeros((n, k // group_size), dtype=np.uint8)
+
+    def to_fp8_value(t):
+        return e4m3_decode(e4m3_encode(t)).astype(np.float32)
+
+    for g in range(k // group_size):
+        q0 = g * group_size
+        w8g = to_fp8_value((w[:, q0:q0 + group_size] / s_w[:, None]).astype(np.float32))
+        lo = np.minimum(w8g.min(axis=1), np.float32(0.0)).astype(np.float32)
+        hi = np.maximum(w8g.max(axis=1), np.float32(0.0)).astype(np.float32)
+        span = (hi - lo).astype(np.float32)
+        s = np.where(span == 0, np.float32(1.0), (span / np.float32(15.0)).astype(np.float32)).astype(np.float32)
+        z = np.clip(np.rint(((-lo) / s).astype(np.float32)), 0, 15).astype(np.float32)
+        for q in range(q0, q0 + group_size):
+            wq = w[:, q].copy()
+            w8 = to_fp8_value((wq / s_w).astype(np.float32))
+            t = ((w8 / s).astype(np.float32) + z).astype(np.float32)
+            uq = np.clip(np.rint(t), 0, 15).astype(np.float32)
+            w8_hat = to_fp8_value(((uq - z).astype(np.float32) * s).astype(np.float32))
+            w_hat = (w8_hat * s_w).astype(np.float32)
+            err = ((wq - w_hat).astype(np.float32) / u_factor[q, q]).astype(np.float32)
+            if q + 1 < k:
+                step = (err[:, None] * u_factor[q, q + 1:][None, :]).astype(np.float32)
+                w[:, q + 1:] = (w[:, q + 1:] - step).astype(np.float32)
+            codes_p[:, q] = uq.astype(np.uint8)
+        scales_p[:, g] = s
+        zeros_p[:, g] = z.astype(np.uint8)
+    codes = np.zeros_like(codes_p)
+    codes[:, perm] = codes_p
+    orig_group = perm[::group_size] // group_size            # original group of each visited group
+    scales = np.zeros_like(scales_p)
+    zeros_ = np.zeros_like(zeros_p)
+    scales[:, orig_group] = scales_p
+    zeros_[:, orig_group] = zeros_p
+    return codes, scales, zeros_
 
 
 # --------------------------------------------------------------------------------------
