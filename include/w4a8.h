@@ -233,6 +233,39 @@ int w4a8_dequant_weights_asym_two_level(const uint8_t* packed_dev, const void* p
                                         int32_t group_size, uint8_t* w8_dev, void* stream);
 
 /*
+ * Offline calibration (not part of inference; its outputs are the inputs of w4a8_pack_weights_asym with
+ * W4A8_SRC_I8_CODES and of w4a8_linear_asym_two_level).
+ *
+ * w4a8_gar_permutation: Group-Aware Reordering (Sec. 3.2, App. A.3).  h_diag_dev: the K diagonal entries of the layer's
+ * Hessian X^T X.  perm_dev receives K int32: position i of the reordered tensor holds original column perm[i]; columns
+ * keep their group, inside a group they are ordered by descending diagonal entry, whole groups by the descending
+ * maximum of their entries (ties: lower original index first).  K % 128 == 0, group_size % 128 == 0.
+ *
+ * w4a8_dpq_calibrate: Dual Precision Quantization, Alg. 1 (Eq. 5-12), for all rows of W.
+ *   w_dev         W float32 [N, K] (not modified)
+ *   u_factor_dev  float32 [K, K] row-major: U, the upper-triangular Cholesky factor of the inverse (dampened) Hessian
+ *                 (H^-1 = U^T U; Sec. 3.3), of the REORDERED columns when perm_dev is given.  Only the upper triangle is read.
+ *   w_scale_dev   s_w of Eq. 6: N floats (per_channel = 1) or one (per_channel = 0)
+ *   perm_dev      the visiting order of the columns (from w4a8_gar_permutation), or NULL for left to right
+ *   codes_dev     out: unsigned 4-bit codes, one per byte, [N, K] in the original column order
+ *   scales8_dev   out: float32 [N, K/group_size], the per-group scales of Eq. 8 (FP8 domain), with their original groups
+ *   zeros_dev     out: bytes [N, K/group_size], the per-group zero-points of Eq. 8
+ *   workspace_dev w4a8_dpq_workspace_bytes(N, K) bytes, 16-byte aligned
+ * Per group, at its start (on the group's current weights, the range extended to contain zero):
+ *   W8 = val(nearest_E4M3(W / s_w)),  s = (max W8 - min W8) / 15 (1 if that is 0),  z = round(-min W8 / s);
+ * per weight, in visiting order: w8 = val(nearest_E4M3(w / s_w)) (Eq. 7); u = clamp(round(w8 / s + z), 0, 15) (Eq. 9);
+ * w8_hat = val(nearest_E4M3((u - z) * s)) (Eq. 10, on the grid, as inference computes it); w_hat = w8_hat * s_w
+ * (Eq. 11); err = (w - w_hat) / U[q,q]; every later weight w_v of the row becomes w_v - err * U[q,v] (Eq. 12).  Each
+ * step is one float32 operation, so the result is reproducible bit for bit.  The MSE search over scales that Sec. 3.3
+ * mentions is not included (the paper gives no search grid).  K % 128 == 0, group_size % 128 == 0.
+ */
+int w4a8_gar_permutation(const float* h_diag_dev, int64_t K, int32_t group_size, int32_t* perm_dev, void* stream);
+size_t w4a8_dpq_workspace_bytes(int64_t N, int64_t K);
+int w4a8_dpq_calibrate(const float* w_dev, const float* u_factor_dev, const float* w_scale_dev, int32_t per_channel,
+                       const int32_t* perm_dev, int64_t N, int64_t K, int32_t group_size, uint8_t* codes_dev,
+                       float* scales8_dev, uint8_t* zeros_dev, void* workspace_dev, size_t workspace_bytes, void* stream);
+
+/*
  * Elementwise step of the decoder-block linear stack (all linear layers of a block are quantized, Sec. 4.1;
  * this joins gate|up to down): h[m,f] = bf16( silu(gate[m,f]) * up[m,f] ) with gate = gu[m, f],
  * up = gu[m, F + f]; gu_dev is bf16 [M, 2F] with row stride ldgu elements, h_dev bf16 [M, F], stride ldh.

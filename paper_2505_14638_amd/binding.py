@@ -45,6 +45,10 @@ SIGNATURES = {
     "w4a8_linear_asym_two_level": (_c_i32, [_c_vp, _c_i64, _c_i64, _c_i64, _c_vp, _c_vp, _c_vp, _c_vp, _c_i32, _c_i64,
                                             _c_i32, _c_vp, _c_i32, _c_i64, _c_vp]),
     "w4a8_dequant_weights_asym_two_level": (_c_i32, [_c_vp, _c_vp, _c_i64, _c_i64, _c_i32, _c_vp, _c_vp]),
+    "w4a8_gar_permutation": (_c_i32, [_c_vp, _c_i64, _c_i32, _c_vp, _c_vp]),
+    "w4a8_dpq_workspace_bytes": (_c_sz, [_c_i64, _c_i64]),
+    "w4a8_dpq_calibrate": (_c_i32, [_c_vp, _c_vp, _c_vp, _c_i32, _c_vp, _c_i64, _c_i64, _c_i32, _c_vp, _c_vp, _c_vp, _c_vp,
+                                    _c_sz, _c_vp]),
     "w4a8_silu_mul": (_c_i32, [_c_vp, _c_i64, _c_i64, _c_i64, _c_vp, _c_i64, _c_vp]),
     "w4a8_linear_fp8_out": (_c_i32, [_c_vp, _c_i64, _c_i64, _c_i64, _c_vp, _c_vp, _c_vp, _c_i64, _c_i32, _c_vp, _c_vp,
                                      _c_i64, _c_vp]),
@@ -296,6 +300,36 @@ def silu_mul_quantize(gu: torch.Tensor, scale: torch.Tensor, out: torch.Tensor |
                                         scale.data_ptr(), out.data_ptr(), out.stride(0) if m > 1 else max(f, out.stride(0)),
                                         _stream()), "w4a8_silu_mul_quantize")
     return out
+
+
+def gar_permutation(h_diag: torch.Tensor, group_size: int) -> torch.Tensor:
+    """w4a8_gar_permutation: h_diag float32 [K] on the device -> int32 [K]."""
+    assert h_diag.dtype == torch.float32 and h_diag.is_contiguous()
+    k = h_diag.numel()
+    perm = torch.empty(k, dtype=torch.int32, device=h_diag.device)
+    _check(lib().w4a8_gar_permutation(h_diag.data_ptr(), k, group_size, perm.data_ptr(), _stream()), "w4a8_gar_permutation")
+    return perm
+
+
+def dpq_calibrate(w: torch.Tensor, u_factor: torch.Tensor, w_scale: torch.Tensor, group_size: int,
+                  perm: torch.Tensor | None = None):
+    """w4a8_dpq_calibrate.  w float32 [N, K]; u_factor float32 [K, K] (of the reordered columns when perm is given);
+    w_scale float32 with N elements or one.  Returns (codes uint8 [N, K], scales8 float32 [N, K/G], zeros uint8 [N, K/G])."""
+    n, k = w.shape
+    assert w.dtype == torch.float32 and w.is_contiguous() and u_factor.dtype == torch.float32 and u_factor.is_contiguous()
+    assert tuple(u_factor.shape) == (k, k) and w_scale.dtype == torch.float32 and w_scale.numel() in (1, n)
+    assert perm is None or (perm.dtype == torch.int32 and perm.numel() == k)
+    dev = w.device
+    codes = torch.empty((n, k), dtype=torch.uint8, device=dev)
+    scales = torch.empty((n, k // group_size), dtype=torch.float32, device=dev)
+    zeros = torch.empty((n, k // group_size), dtype=torch.uint8, device=dev)
+    nbytes = lib().w4a8_dpq_workspace_bytes(n, k)
+    work = torch.empty(max(nbytes, 16), dtype=torch.uint8, device=dev)
+    _check(lib().w4a8_dpq_calibrate(w.data_ptr(), u_factor.data_ptr(), w_scale.data_ptr(), 1 if w_scale.numel() > 1 else 0,
+                                    perm.data_ptr() if perm is not None else 0, n, k, group_size, codes.data_ptr(),
+                                    scales.data_ptr(), zeros.data_ptr(), work.data_ptr(), nbytes, _stream()),
+           "w4a8_dpq_calibrate")
+    return codes, scales, zeros
 
 
 def probe_stream_read(buf: torch.Tensor, sink: torch.Tensor) -> None:

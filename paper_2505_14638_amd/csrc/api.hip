@@ -281,6 +281,33 @@ int w4a8_dequant_weights_asym_two_level(const uint8_t* packed_dev, const void* p
     return dequant_asym(packed_dev, params8_dev, N, K, group_size, w8_dev, 1, stream);
 }
 
+int w4a8_gar_permutation(const float* h_diag_dev, int64_t K, int32_t group_size, int32_t* perm_dev, void* stream) {
+    if (int e = check_weight_shape(1, K, group_size, W4A8_LAYOUT_TILED)) return e;
+    if (!h_diag_dev || !perm_dev) return W4A8_ERR_NULL;
+    if (reinterpret_cast<uintptr_t>(h_diag_dev) % 4 || reinterpret_cast<uintptr_t>(perm_dev) % 4) return W4A8_ERR_ALIGN;
+    return launch_gar_permutation(h_diag_dev, K, group_size, perm_dev, static_cast<hipStream_t>(stream));
+}
+
+size_t w4a8_dpq_workspace_bytes(int64_t N, int64_t K) {
+    if (check_nk(N, K, W4A8_LAYOUT_TILED) != W4A8_OK) return 0;
+    return (size_t)(N * K + N * 128) * sizeof(float);
+}
+
+int w4a8_dpq_calibrate(const float* w_dev, const float* u_factor_dev, const float* w_scale_dev, int32_t per_channel,
+                       const int32_t* perm_dev, int64_t N, int64_t K, int32_t group_size, uint8_t* codes_dev,
+                       float* scales8_dev, uint8_t* zeros_dev, void* workspace_dev, size_t workspace_bytes, void* stream) {
+    if (int e = check_weight_shape(N, K, group_size, W4A8_LAYOUT_TILED)) return e;
+    if (per_channel != 0 && per_channel != 1) return W4A8_ERR_DTYPE;
+    if (!w_dev || !u_factor_dev || !w_scale_dev || !codes_dev || !scales8_dev || !zeros_dev || !workspace_dev) return W4A8_ERR_NULL;
+    if (reinterpret_cast<uintptr_t>(w_dev) % 4 || reinterpret_cast<uintptr_t>(u_factor_dev) % 4 ||
+        reinterpret_cast<uintptr_t>(w_scale_dev) % 4 || reinterpret_cast<uintptr_t>(scales8_dev) % 4 ||
+        reinterpret_cast<uintptr_t>(perm_dev) % 4 || !aligned16(workspace_dev))
+        return W4A8_ERR_ALIGN;
+    if (workspace_bytes < w4a8_dpq_workspace_bytes(N, K)) return W4A8_ERR_WORKSPACE;
+    return launch_dpq_calibrate(w_dev, u_factor_dev, w_scale_dev, per_channel, perm_dev, N, K, group_size, codes_dev,
+                                scales8_dev, zeros_dev, workspace_dev, static_cast<hipStream_t>(stream));
+}
+
 int w4a8_silu_mul(const void* gu_dev, int64_t M, int64_t F, int64_t ldgu, void* h_dev, int64_t ldh, void* stream) {
     if (M < 0 || F < 1 || M > DIM_MAX || F > DIM_MAX || ldgu < 2 * F || ldh < F) return W4A8_ERR_SHAPE;
     if (!gu_dev || !h_dev) return W4A8_ERR_NULL;

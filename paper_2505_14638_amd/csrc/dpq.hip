@@ -1,0 +1,189 @@
+// Offline calibration: Dual Precision Quantization (Alg. 1, Eq. 5-12) and the Group-Aware Reordering permutation
+// (Sec. 3.2, App. A.3).
+//
+// Alg. 1 walks along a row: quantize one weight (FP8, then INT4, Eq. 7-9), dequantize it the way inference will
+// (Eq. 10-11), and push the error onto every later weight of the row through the Hessian factor U (Eq. 12; U is the
+// upper Cholesky factor of the inverse Hessian, Sec. 3.3).  Rows are independent, columns strictly sequential.  The
+// work is arranged in blocks of 128 columns: inside a block one lane owns one row and applies each error to the rest
+// of the block at once; the columns right of the block receive the block's 128 errors afterwards, in one tiled pass
+// over the matrix.  Every weight still sees the same float32 operations in the same order as in the plain
+// column-by-column statement (w <- w - err_q * U[q, v] for q ascending, product and difference rounded separately),
+// so the integer decisions are reproducible bit for bit; only the time at which an update is applied moves.
+#include "w4a8_device.hpp"
+#include "w4a8_internal.hpp"
+
+namespace w4a8 {
+namespace {
+
+constexpr int DPQ_BLOCK = 128;      // columns per block
+constexpr int DPQ_ROWS = 128;       // rows (lanes) per workgroup of the block kernel
+
+// val(nearest_Z(t)): the E4M3 value nearest to t (ties to even, saturating), as a float32
+__device__ __forceinline__ float fp8_value(float t) {
+    const int b = __builtin_amdgcn_cvt_pk_fp8_f32(sat448(t), 0.0f, 0, false);
+    return __builtin_amdgcn_cvt_f32_fp8(b, 0);
+}
+
+// position i of the reordered tensor holds original column perm[i]: inside a group by descending diagonal, groups
+// by descending maximum; ties keep the lower original index first.  One thread per column.
+__global__ void __launch_bounds__(256) gar_permutation_kernel(const float* __restrict__ d, int K, int G, int32_t* __restrict__ perm) {
+    const int c = blockIdx.x * blockDim.x + threadIdx.x;
+    if (c >= K) return;
+    const int g = c / G, NG = K / G;
+    const float mine = d[c];
+    int inside = 0;
+    float gmax = d[g * G];
+    for (int j = 0; j < G; ++j) {
+        const float v = d[g * G + j];
+        inside += (v > mine) || (v == mine && g * G + j < c);
+        gmax = fmaxf(gmax, v);
+    }
+    int rank = 0;
+    for (int h = 0; h < NG; ++h) {
+        float m = d[h * G];
+        for (int j = 1; j < G; ++j) m = fmaxf(m, d[h * G + j]);
+        rank += (m > gmax) || (m == gmax && h < g);
+    }
+    perm[rank * G + inside] = c;
+}
+
+// work[n, i] = w[n, perm[i]] (perm == nullptr: a copy)
+__global__ void __launch_bounds__(256) dpq_gather_kernel(const float* __restrict__ w, const int32_t* __restrict__ perm,
+                                                         int64_t N, int64_t K, float* __restrict__ work) {
+    const int64_t u = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (u >= N * K) return;
+    const int64_t n = u / K, i = u - n * K;
+    work[u] = w[n * K + (perm ? perm[i] : i)];
+}
+
+struct DpqArgs {
+    float* work;                  // [N, K] current weights, reordered columns
+    const float* u;               // [K, K] upper factor, reordered columns
+    const float* s_w;
+    int per_channel;
+    const int32_t* perm;          // or nullptr
+    int N, K, G;
+    uint8_t* codes;               // [N, K], original column order
+    float* scales;                // [N, K / G], original group order
+    uint8_t* zeros;               // [N, K / G]
+    float* err;                   // [N, 128] errors of the current block
+};
+
+// One block of 128 columns starting at c0; one lane per row.
+__global__ void __launch_bounds__(DPQ_ROWS) dpq_block_kernel(DpqArgs a, int c0) {
+    __shared__ float wl[DPQ_BLOCK * DPQ_ROWS];                   // wl[v * DPQ_ROWS + lane]: column c0 + v of the lane's row
+    const int lane = threadIdx.x;
+    const int n = blockIdx.x * DPQ_ROWS + lane;
+    if (n >= a.N) return;                                        // no barrier below: lanes are independent
+    float* row = a.work + (int64_t)n * a.K;
+    const float sw = a.s_w[a.per_channel ? n : 0];
+    const int NG = a.K / a.G;
+    for (int v = 0; v < DPQ_BLOCK; ++v) wl[v * DPQ_ROWS + lane] = row[c0 + v];
+    // group parameters (Eq. 8 on the group's current weights): computed where the group starts, kept in the outputs
+    const int g = c0 / a.G;
+    const int og = a.perm ? a.perm[g * a.G] / a.G : g;           // the original group these columns belong to
+    float s, z;
+    if (c0 % a.G == 0) {
+        float lo = 0.0f, hi = 0.0f;
+        for (int j = 0; j < a.G; ++j) {
+            const float w8 = fp8_value(__fdiv_rn(row[c0 + j], sw));
+            lo = fminf(lo, w8);
+            hi = fmaxf(hi, w8);
+        }
+        const float span = __fsub_rn(hi, lo);
+        s = (span == 0.0f) ? 1.0f : __fdiv_rn(span, 15.0f);
+        z = fminf(fmaxf(rintf(__fdiv_rn(-lo, s)), 0.0f), 15.0f);
+        a.scales[(int64_t)n * NG + og] = s;
+        a.zeros[(int64_t)n * NG + og] = (uint8_t)z;
+    } else {
+        s = a.scales[(int64_t)n * NG + og];
+        z = (float)a.zeros[(int64_t)n * NG + og];
+    }
+    for (int q = 0; q < DPQ_BLOCK; ++q) {
+        const float w = wl[q * DPQ_ROWS + lane];
+        const float w8 = fp8_value(__fdiv_rn(w, sw));                                     // Eq. 7
+        const float t = __fadd_rn(__fdiv_rn(w8, s), z);
+        const float uq = fminf(fmaxf(rintf(t), 0.0f), 15.0f);                             // Eq. 9
+        const float w8_hat = fp8_value(__fmul_rn(__fsub_rn(uq, z), s));                   // Eq. 10
+        const float w_hat = __fmul_rn(w8_hat, sw);                                        // Eq. 11
+        const float* urow = a.u + (int64_t)(c0 + q) * a.K + c0;                           // U[c0 + q, c0 + v]
+        const float e = __fdiv_rn(__fsub_rn(w, w_hat), urow[q]);
+        a.err[(int64_t)n * DPQ_BLOCK + q] = e;
+        a.codes[(int64_t)n * a.K + (a.perm ? a.perm[c0 + q] : c0 + q)] = (uint8_t)uq;
+        for (int v = q + 1; v < DPQ_BLOCK; ++v)                                           // Eq. 12 inside the block
+            wl[v * DPQ_ROWS + lane] = __fsub_rn(wl[v * DPQ_ROWS + lane], __fmul_rn(e, urow[v]));
+    }
+}
+
+// Eq. 12 for the columns right of the block [c0, c0 + 128): work[n, v] <- work[n, v] - err[n, q] * U[c0 + q, v], q = 0..127
+// in ascending order.  A workgroup of 256 threads owns a 64 x 64 tile of (rows, columns), a thread 4 x 4 of it.
+__global__ void __launch_bounds__(256) dpq_lazy_update_kernel(DpqArgs a, int c0) {
+    __shared__ float el[DPQ_BLOCK * 64];                         // el[q * 64 + r]: error q of row r of the tile
+    __shared__ float ul[DPQ_BLOCK * 64];                         // ul[q * 64 + c]: U[c0 + q, column c of the tile]
+    const int tid = threadIdx.x;
+    const int r0 = blockIdx.y * 64, v0 = c0 + DPQ_BLOCK + blockIdx.x * 64;
+    for (int idx = tid; idx < DPQ_BLOCK * 64; idx += 256) {
+        const int q = idx & (DPQ_BLOCK - 1), r = idx >> 7;       // consecutive threads, consecutive q: coalesced reads of err
+        el[q * 64 + r] = (r0 + r < a.N) ? a.err[(int64_t)(r0 + r) * DPQ_BLOCK + q] : 0.0f;
+    }
+    for (int idx = tid; idx < DPQ_BLOCK * 64; idx += 256) {
+        const int c = idx & 63, q = idx >> 6;
+        ul[q * 64 + c] = (v0 + c < a.K) ? a.u[(int64_t)(c0 + q) * a.K + v0 + c] : 0.0f;
+    }
+    __syncthreads();
+    const int tr = (tid >> 4) * 4, tc = (tid & 15) * 4;
+    float w[4][4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            w[i][j] = (r0 + tr + i < a.N && v0 + tc + j < a.K) ? a.work[(int64_t)(r0 + tr + i) * a.K + v0 + tc + j] : 0.0f;
+    for (int q = 0; q < DPQ_BLOCK; ++q) {
+        const float4 e = *reinterpret_cast<const float4*>(&el[q * 64 + tr]);
+        const float4 u = *reinterpret_cast<const float4*>(&ul[q * 64 + tc]);
+        const float ev[4] = {e.x, e.y, e.z, e.w}, uv[4] = {u.x, u.y, u.z, u.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) w[i][j] = __fsub_rn(w[i][j], __fmul_rn(ev[i], uv[j]));
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            if (r0 + tr + i < a.N && v0 + tc + j < a.K) a.work[(int64_t)(r0 + tr + i) * a.K + v0 + tc + j] = w[i][j];
+}
+
+}  // namespace
+
+int launch_gar_permutation(const float* hdiag, int64_t K, int32_t G, int32_t* perm, hipStream_t st) {
+    hipLaunchKernelGGL(gar_permutation_kernel, dim3((unsigned)((K + 255) / 256)), dim3(256), 0, st, hdiag, (int)K, (int)G, perm);
+    return launch_status();
+}
+
+int launch_dpq_calibrate(const float* w, const float* u, const float* s_w, int per_channel, const int32_t* perm,
+                         int64_t N, int64_t K, int32_t G, uint8_t* codes, float* scales, uint8_t* zeros, void* workspace,
+                         hipStream_t st) {
+    DpqArgs a;
+    a.work = static_cast<float*>(workspace);
+    a.err = a.work + N * K;
+    a.u = u; a.s_w = s_w; a.per_channel = per_channel; a.perm = perm;
+    a.N = (int)N; a.K = (int)K; a.G = (int)G;
+    a.codes = codes; a.scales = scales; a.zeros = zeros;
+    hipLaunchKernelGGL(dpq_gather_kernel, dim3((unsigned)((N * K + 255) / 256)), dim3(256), 0, st, w, perm, N, K, a.work);
+    if (int e = launch_status()) return e;
+    const unsigned row_groups = (unsigned)((N + DPQ_ROWS - 1) / DPQ_ROWS);
+    for (int c0 = 0; c0 < K; c0 += DPQ_BLOCK) {
+        hipLaunchKernelGGL(dpq_block_kernel, dim3(row_groups), dim3(DPQ_ROWS), 0, st, a, c0);
+        if (int e = launch_status()) return e;
+        const int64_t rest = K - c0 - DPQ_BLOCK;
+        if (rest > 0) {
+            hipLaunchKernelGGL(dpq_lazy_update_kernel, dim3((unsigned)((rest + 63) / 64), (unsigned)((N + 63) / 64)), dim3(256),
+                               0, st, a, c0);
+            if (int e = launch_status()) return e;
+        }
+    }
+    return W4A8_OK;
+}
+
+}  // namespace w4a8

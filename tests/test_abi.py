@@ -188,6 +188,23 @@ def test_fused_validation(L):
     assert q(P, 4, 64, 128, P, P, 32, None) == 2
 
 
+def test_calibration_validation(L):
+    gp = L.w4a8_gar_permutation
+    assert gp(0, 256, 128, P, None) == 1 and gp(P, 256, 128, 0, None) == 1
+    assert gp(P, 200, 200, P, None) == 5 and gp(P, 256, 64, P, None) == 3
+    assert L.w4a8_dpq_workspace_bytes(10, 256) == (10 * 256 + 10 * 128) * 4
+    f = L.w4a8_dpq_calibrate
+    # w, u, s_w, per_channel, perm, N, K, G, codes, scales, zeros, workspace, bytes, stream
+    ok = L.w4a8_dpq_workspace_bytes(16, 256)
+    assert f(0, P, P, 1, 0, 16, 256, 128, P, P, P, P, ok, None) == 1
+    assert f(P, P, P, 1, 0, 16, 256, 128, P, P, P, 0, ok, None) == 1
+    assert f(P, P, P, 2, 0, 16, 256, 128, P, P, P, P, ok, None) == 4
+    assert f(P, P, P, 1, 0, 16, 256, 96, P, P, P, P, ok, None) == 3
+    assert f(P, P, P, 1, 0, 16, 200, 200, P, P, P, P, ok, None) == 5
+    assert f(P, P, P, 1, P + 2, 16, 256, 128, P, P, P, P, ok, None) == 6
+    assert f(P, P, P, 1, 0, 16, 256, 128, P, P, P, P, ok - 1, None) == 7
+
+
 def test_other_validation(L):
     assert L.w4a8_dequant_weights(0, 16, 256, B.LAYOUT_TILED, P, None) == 1
     assert L.w4a8_dequant_weights(P, 16, 200, B.LAYOUT_TILED, P, None) == 5
