@@ -4,9 +4,9 @@
 // Alg. 1 walks along a row: quantize one weight (FP8, then INT4, Eq. 7-9), dequantize it the way inference will
 // (Eq. 10-11), and push the error onto every later weight of the row through the Hessian factor U (Eq. 12; U is the
 // upper Cholesky factor of the inverse Hessian, Sec. 3.3).  Rows are independent, columns strictly sequential.  The
-// work is arranged in blocks of 128 columns: inside a block one lane owns one row and applies each error to the rest
-// of the block at once; the columns right of the block receive the block's 128 errors afterwards, in one tiled pass
-// over the matrix.  Every weight still sees the same float32 operations in the same order as in the plain
+// work is arranged in blocks of 128 columns: inside a block eight lanes of one wavefront own one row (each takes
+// the quantization step itself and applies the error to its share of the rest of the block); the columns right of
+// the block receive the block's 128 errors afterwards, in one tiled pass over the matrix.  Every weight still sees the same float32 operations in the same order as in the plain
 // column-by-column statement (w <- w - err_q * U[q, v] for q ascending, product and difference rounded separately),
 // so the integer decisions are reproducible bit for bit; only the time at which an update is applied moves.
 #include "w4a8_device.hpp"
@@ -16,7 +16,9 @@ namespace w4a8 {
 namespace {
 
 constexpr int DPQ_BLOCK = 128;      // columns per block
-constexpr int DPQ_ROWS = 128;       // rows (lanes) per workgroup of the block kernel
+constexpr int DPQ_THREADS = 128;    // threads per workgroup of the block kernel
+constexpr int DPQ_LPR = 8;          // lanes per row (neighbours in one wavefront)
+constexpr int DPQ_ROWS = DPQ_THREADS / DPQ_LPR;   // rows per workgroup
 
 // val(nearest_Z(t)): the E4M3 value nearest to t (ties to even, saturating), as a float32
 __device__ __forceinline__ float fp8_value(float t) {
@@ -69,16 +71,20 @@ struct DpqArgs {
     float* err;                   // [N, 128] errors of the current block
 };
 
-// One block of 128 columns starting at c0; one lane per row.
-__global__ void __launch_bounds__(DPQ_ROWS) dpq_block_kernel(DpqArgs a, int c0) {
-    __shared__ float wl[DPQ_BLOCK * DPQ_ROWS];                   // wl[v * DPQ_ROWS + lane]: column c0 + v of the lane's row
-    const int lane = threadIdx.x;
+// One block of 128 columns starting at c0.  The DPQ_LPR lanes of a row sit next to each other in one wavefront and
+// share the row's 128 weights through LDS; a wavefront executes its LDS accesses in program order, so a lane's update
+// of a column is in place before every lane of the row reads that column in a later step -- no barrier is needed.
+// All lanes of a row take the (identical) quantization step; lane p updates the columns v with v % DPQ_LPR == p.
+__global__ void __launch_bounds__(DPQ_THREADS) dpq_block_kernel(DpqArgs a, int c0) {
+    __shared__ float wl[DPQ_BLOCK * DPQ_ROWS];                   // wl[v * DPQ_ROWS + r]: column c0 + v of row r of the workgroup
+    const int lane = threadIdx.x / DPQ_LPR, part = threadIdx.x % DPQ_LPR;
     const int n = blockIdx.x * DPQ_ROWS + lane;
-    if (n >= a.N) return;                                        // no barrier below: lanes are independent
+    if (n >= a.N) return;                                        // whole rows leave together
     float* row = a.work + (int64_t)n * a.K;
     const float sw = a.s_w[a.per_channel ? n : 0];
     const int NG = a.K / a.G;
-    for (int v = 0; v < DPQ_BLOCK; ++v) wl[v * DPQ_ROWS + lane] = row[c0 + v];
+    for (int v = part; v < DPQ_BLOCK; v += DPQ_LPR) wl[v * DPQ_ROWS + lane] = row[c0 + v];
+    __builtin_amdgcn_wave_barrier();                             // keeps the compiler from moving LDS accesses across
     // group parameters (Eq. 8 on the group's current weights): computed where the group starts, kept in the outputs
     const int g = c0 / a.G;
     const int og = a.perm ? a.perm[g * a.G] / a.G : g;           // the original group these columns belong to
@@ -93,8 +99,10 @@ __global__ void __launch_bounds__(DPQ_ROWS) dpq_block_kernel(DpqArgs a, int c0) 
         const float span = __fsub_rn(hi, lo);
         s = (span == 0.0f) ? 1.0f : __fdiv_rn(span, 15.0f);
         z = fminf(fmaxf(rintf(__fdiv_rn(-lo, s)), 0.0f), 15.0f);
-        a.scales[(int64_t)n * NG + og] = s;
-        a.zeros[(int64_t)n * NG + og] = (uint8_t)z;
+        if (part == 0) {
+            a.scales[(int64_t)n * NG + og] = s;
+            a.zeros[(int64_t)n * NG + og] = (uint8_t)z;
+        }
     } else {
         s = a.scales[(int64_t)n * NG + og];
         z = (float)a.zeros[(int64_t)n * NG + og];
@@ -108,10 +116,13 @@ __global__ void __launch_bounds__(DPQ_ROWS) dpq_block_kernel(DpqArgs a, int c0) 
         const float w_hat = __fmul_rn(w8_hat, sw);                                        // Eq. 11
         const float* urow = a.u + (int64_t)(c0 + q) * a.K + c0;                           // U[c0 + q, c0 + v]
         const float e = __fdiv_rn(__fsub_rn(w, w_hat), urow[q]);
-        a.err[(int64_t)n * DPQ_BLOCK + q] = e;
-        a.codes[(int64_t)n * a.K + (a.perm ? a.perm[c0 + q] : c0 + q)] = (uint8_t)uq;
-        for (int v = q + 1; v < DPQ_BLOCK; ++v)                                           // Eq. 12 inside the block
+        if (part == 0) {
+            a.err[(int64_t)n * DPQ_BLOCK + q] = e;
+            a.codes[(int64_t)n * a.K + (a.perm ? a.perm[c0 + q] : c0 + q)] = (uint8_t)uq;
+        }
+        for (int v = q + 1 + (part + DPQ_LPR - (q + 1) % DPQ_LPR) % DPQ_LPR; v < DPQ_BLOCK; v += DPQ_LPR)   // Eq. 12 inside the block
             wl[v * DPQ_ROWS + lane] = __fsub_rn(wl[v * DPQ_ROWS + lane], __fmul_rn(e, urow[v]));
+        __builtin_amdgcn_wave_barrier();
     }
 }
 
@@ -174,7 +185,7 @@ int launch_dpq_calibrate(const float* w, const float* u, const float* s_w, int p
     if (int e = launch_status()) return e;
     const unsigned row_groups = (unsigned)((N + DPQ_ROWS - 1) / DPQ_ROWS);
     for (int c0 = 0; c0 < K; c0 += DPQ_BLOCK) {
-        hipLaunchKernelGGL(dpq_block_kernel, dim3(row_groups), dim3(DPQ_ROWS), 0, st, a, c0);
+        hipLaunchKernelGGL(dpq_block_kernel, dim3(row_groups), dim3(DPQ_THREADS), 0, st, a, c0);
         if (int e = launch_status()) return e;
         const int64_t rest = K - c0 - DPQ_BLOCK;
         if (rest > 0) {
