@@ -172,6 +172,31 @@ def measured_ceilings(dev):
     return round(gbs, 1), round(copy_gbs, 1), round(tfl, 1)
 
 
+def plain_read_same_sizes(dev, sizes, copies, steps, warmup):
+    """What a kernel that only reads reaches on buffers of the decode sweep's sizes: the library's streaming-read probe
+    launched once per case on `sizes[j]` bytes, the same number of launches per HIP graph as the linear kernels, over
+    sixteen 64 MiB slots of a 1 GiB pool visited in turn.  Returns microseconds per launch."""
+    sink = torch.zeros(4, dtype=torch.float32, device=dev)
+    pool = torch.empty(1 << 30, dtype=torch.uint8, device=dev).fill_(1)
+    slot = 64 << 20
+
+    def reads(i):
+        for j, nb in enumerate(sizes):
+            at = ((i * len(sizes) + j) % 16) * slot
+            B.probe_stream_read(pool[at:at + min(slot, int(nb) // 256 * 256)], sink)
+
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        reads(0)
+        torch.cuda.synchronize()
+        graphs = [capture(lambda i=i: reads(i)) for i in range(copies)]
+        sec = time_graphs(graphs, steps, warmup)
+    torch.cuda.current_stream().wait_stream(side)
+    del graphs, pool
+    return sec / steps / len(sizes) * 1e6
+
+
 def block_latency(dev, steps, warmup):
     """Config 5: latency of the decoder-block linear stack per batch size, HIP graph replay."""
     from paper_2505_14638_amd.block import LAYERS, DecoderBlockLinears
@@ -282,7 +307,8 @@ def main():
 
     if not args.prefill_only:
         cases = [Case(2, L, m, dev, cfg["frac"], cfg["mult"]) for L in layers for m in (1, 4, 16)]
-        step_bytes = sum(alg_bytes(c.m, c.layer.k, c.layer.n) for c in cases)
+        case_bytes = [alg_bytes(c.m, c.layer.k, c.layer.n) for c in cases]
+        step_bytes = sum(case_bytes)
 
         def step(i):
             for j, c in enumerate(cases):
@@ -391,6 +417,12 @@ def main():
         result["measured_ceilings"] = {"stream_read_GBps": hbm, "copy_read_plus_write_GBps": copy,
                                        "mfma_e4m3_TFLOPs": mfma}
         result["roofline"]["frac_of_measured"] = round(result["roofline"]["achieved"] / hbm, 4)
+        if not args.eager and not args.prefill_only:
+            # the same comparison at the sizes of the sweep's layers (8.9-63 MB), where launch and ramp-up weigh as much
+            # as the transfer: time of the linear kernel against a kernel that only reads as many bytes
+            us = plain_read_same_sizes(dev, case_bytes, args.copies, args.steps, args.warmup)
+            result["roofline"]["plain_read_same_sizes_us_per_launch"] = round(us, 3)
+            result["roofline"]["frac_of_plain_read_same_sizes"] = round(us / result["roofline"]["avg_launch_us"], 4)
         if "prefill" in result:
             result["prefill"]["roofline"]["frac_of_measured"] = round(result["prefill"]["roofline"]["achieved"] / mfma, 4)
         del layers
