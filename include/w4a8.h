@@ -283,12 +283,22 @@ int w4a8_silu_mul(const void* gu_dev, int64_t M, int64_t F, int64_t ldgu, void* 
  *                             Arguments otherwise as in w4a8_linear.
  *   w4a8_silu_mul_quantize  = w4a8_silu_mul followed by w4a8_quantize_act of h with *scale_dev; h8_dev receives E4M3
  *                             bytes [M, F], row stride ldh8 bytes.
+ *   w4a8_linear_silu_mul_fp8_out = the gate|up layer (N = 2F output channels), w4a8_silu_mul and the quantization of h
+ *                             in one kernel: h8_dev receives E4M3 bytes [M, F].  The weight matrix is the gate|up
+ *                             matrix with its rows INTERLEAVED in bands of 16: packed row 32p + i is gate row 16p + i,
+ *                             packed row 32p + 16 + i is up row 16p + i (i < 16), so that a workgroup holds both halves
+ *                             of the channels it finishes; pack that matrix with w4a8_pack_weights (TILED).
+ *                             F % 16 == 0.  The gate and up values are rounded to bf16 before SiLU*mul, as the
+ *                             unfused sequence does.
  */
 int w4a8_linear_fp8_out(const uint8_t* x8_dev, int64_t M, int64_t K, int64_t ldx8, const float* x_scale_dev,
                         const uint8_t* packed_dev, const float* w_scales_dev, int64_t N, int32_t group_size,
                         const float* y_scale_dev, uint8_t* y8_dev, int64_t ldy8, void* stream);
 int w4a8_silu_mul_quantize(const void* gu_dev, int64_t M, int64_t F, int64_t ldgu, const float* scale_dev,
                            uint8_t* h8_dev, int64_t ldh8, void* stream);
+int w4a8_linear_silu_mul_fp8_out(const uint8_t* x8_dev, int64_t M, int64_t K, int64_t ldx8, const float* x_scale_dev,
+                                 const uint8_t* packed_dev, const float* w_scales_dev, int64_t F, int32_t group_size,
+                                 const float* h_scale_dev, uint8_t* h8_dev, int64_t ldh8, void* stream);
 
 /*
  * Measurement aids (not part of the layer): the two hardware ceilings the kernels are compared with, measured

@@ -52,6 +52,8 @@ SIGNATURES = {
     "w4a8_silu_mul": (_c_i32, [_c_vp, _c_i64, _c_i64, _c_i64, _c_vp, _c_i64, _c_vp]),
     "w4a8_linear_fp8_out": (_c_i32, [_c_vp, _c_i64, _c_i64, _c_i64, _c_vp, _c_vp, _c_vp, _c_i64, _c_i32, _c_vp, _c_vp,
                                      _c_i64, _c_vp]),
+    "w4a8_linear_silu_mul_fp8_out": (_c_i32, [_c_vp, _c_i64, _c_i64, _c_i64, _c_vp, _c_vp, _c_vp, _c_i64, _c_i32, _c_vp,
+                                              _c_vp, _c_i64, _c_vp]),
     "w4a8_silu_mul_quantize": (_c_i32, [_c_vp, _c_i64, _c_i64, _c_i64, _c_vp, _c_vp, _c_i64, _c_vp]),
     "w4a8_probe_stream_read": (_c_i32, [_c_vp, _c_sz, _c_vp, _c_vp]),
     "w4a8_probe_mfma_e4m3": (_c_i32, [_c_i32, _c_vp, _c_vp]),
@@ -287,6 +289,29 @@ def linear_fp8_out(x8, x_scale, packed, w_scales, n, group_size, y_scale, out=No
                                      x_scale.data_ptr(), packed.data_ptr(), w_scales.data_ptr(), n, group_size,
                                      y_scale.data_ptr(), out.data_ptr(), out.stride(0) if m > 1 else max(n, out.stride(0)),
                                      _stream()), "w4a8_linear_fp8_out")
+    return out
+
+
+def interleave_gate_up(w_gate_up: torch.Tensor) -> torch.Tensor:
+    """Row order w4a8_linear_silu_mul_fp8_out expects: [2F, K] with gate rows first, then up rows -> bands of 16 gate
+    rows and the 16 up rows of the same channels in turn.  A pure re-ordering of rows (F % 16 == 0)."""
+    f2, k = w_gate_up.shape
+    f = f2 // 2
+    assert f2 == 2 * f and f % 16 == 0
+    return torch.stack([w_gate_up[:f].reshape(f // 16, 16, k), w_gate_up[f:].reshape(f // 16, 16, k)], dim=1).reshape(f2, k).contiguous()
+
+
+def linear_silu_mul_fp8_out(x8, x_scale, packed, w_scales, f, group_size, h_scale, out=None):
+    """w4a8_linear_silu_mul_fp8_out: packed/w_scales from the interleaved gate|up matrix; returns uint8 [M, F]."""
+    m, k = x8.shape
+    assert x8.dtype == torch.uint8 and x8.stride(1) == 1 and h_scale.dtype == torch.float32
+    if out is None:
+        out = torch.empty((m, f), dtype=torch.uint8, device=x8.device)
+    _check(lib().w4a8_linear_silu_mul_fp8_out(x8.data_ptr(), m, k, x8.stride(0) if m > 1 else max(k, x8.stride(0)),
+                                              x_scale.data_ptr(), packed.data_ptr(), w_scales.data_ptr(), f, group_size,
+                                              h_scale.data_ptr(), out.data_ptr(),
+                                              out.stride(0) if m > 1 else max(f, out.stride(0)), _stream()),
+           "w4a8_linear_silu_mul_fp8_out")
     return out
 
 

@@ -7,8 +7,10 @@ quantized-linear path.  Intermediates are bf16, each linear layer's input is qua
 per-tensor scale (Eq. 13; all linear layers of a block are quantized, Sec. 4.1).
 
 `fused=True` runs the same computation with the quantization of each intermediate folded into the kernel that produces
-it (w4a8_linear_fp8_out for QKV and O, w4a8_silu_mul_quantize for SiLU*mul): six launches instead of nine, the same
-bytes at every layer input and the same block output.
+it (w4a8_linear_fp8_out for QKV and O, w4a8_linear_silu_mul_fp8_out for gate|up with SiLU*mul, on a row-interleaved
+copy of the gate|up weights, from 8 tokens on; below that w4a8_silu_mul_quantize after the plain layer): five or six
+launches instead of nine, the same bytes at every layer input and the same block
+output.
 """
 from __future__ import annotations
 
@@ -32,7 +34,10 @@ class DecoderBlockLinears:
         """Quantize (round-to-nearest INT4) and pack one [N, K] float32 weight matrix on the device."""
         k, n = self.dims[name]
         assert tuple(w_f32.shape) == (n, k)
-        self.weights[name] = B.pack_weights(w_f32.to(self.device), self.group_size, B.LAYOUT_TILED)
+        w_dev = w_f32.to(self.device)
+        self.weights[name] = B.pack_weights(w_dev, self.group_size, B.LAYOUT_TILED)
+        if name == "gate_up":                                    # row-interleaved copy for the fused gate|up + SiLU*mul layer
+            self.weights["gate_up_interleaved"] = B.pack_weights(B.interleave_gate_up(w_dev), self.group_size, B.LAYOUT_TILED)
 
     def set_act_scale(self, name: str, s_x: float) -> None:
         self.scales_x[name] = torch.tensor([s_x], dtype=torch.float32, device=self.device)
@@ -60,13 +65,17 @@ class DecoderBlockLinears:
                                 out=self._buf(("qkv", "y8", m), (m, self.dims["qkv"][1]), torch.uint8))
         o8 = B.linear_fp8_out(qkv8[:, :self.hidden], sx["o"], *w["o"], self.hidden, g, sx["gate_up"],
                               out=self._buf(("o", "y8", m), (m, self.hidden), torch.uint8))
-        gu = B.linear(o8, sx["gate_up"], *w["gate_up"], 2 * self.ffn, g, B.LAYOUT_TILED,
-                      out=self._buf(("gate_up", "y", m), (m, 2 * self.ffn), torch.bfloat16))
-        h8 = B.silu_mul_quantize(gu, sx["down"], out=self._buf(("h8", m), (m, self.ffn), torch.uint8))
+        h8 = self._buf(("h8", m), (m, self.ffn), torch.uint8)
+        if m >= 8:
+            B.linear_silu_mul_fp8_out(o8, sx["gate_up"], *w["gate_up_interleaved"], self.ffn, g, sx["down"], out=h8)
+        else:                                                    # a few tokens: one band per wavefront streams faster (measured)
+            gu = B.linear(o8, sx["gate_up"], *w["gate_up"], 2 * self.ffn, g, B.LAYOUT_TILED,
+                          out=self._buf(("gate_up", "y", m), (m, 2 * self.ffn), torch.bfloat16))
+            B.silu_mul_quantize(gu, sx["down"], out=h8)
         y = B.linear(h8, sx["down"], *w["down"], self.hidden, g, B.LAYOUT_TILED,
                      out=self._buf(("down", "y", m), (m, self.hidden), torch.bfloat16))
         if keep is not None:
-            keep.update(qkv_x8=x8, o_x8=qkv8[:, :self.hidden], gate_up_x8=o8, gate_up=gu, down_x8=h8, down=y)
+            keep.update(qkv_x8=x8, o_x8=qkv8[:, :self.hidden], gate_up_x8=o8, down_x8=h8, down=y)
         return y
 
     def forward(self, x: torch.Tensor, keep: dict | None = None) -> torch.Tensor:

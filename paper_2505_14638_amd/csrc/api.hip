@@ -202,6 +202,28 @@ int w4a8_linear_fp8_out(const uint8_t* x8_dev, int64_t M, int64_t K, int64_t ldx
                                     ldy8, 0, 0, 0, nullptr, 0, MODE_CODE_EXACT, y_scale_dev, st);
 }
 
+int w4a8_linear_silu_mul_fp8_out(const uint8_t* x8_dev, int64_t M, int64_t K, int64_t ldx8, const float* x_scale_dev,
+                                 const uint8_t* packed_dev, const float* w_scales_dev, int64_t F, int32_t group_size,
+                                 const float* h_scale_dev, uint8_t* h8_dev, int64_t ldh8, void* stream) {
+    if (F < 16 || F > DIM_MAX / 2 || F % 16 != 0) return W4A8_ERR_SHAPE;
+    if (ldh8 < F) return W4A8_ERR_SHAPE;
+    if (int e = check_linear(x8_dev, M, K, ldx8, x_scale_dev, packed_dev, w_scales_dev, 2 * F, group_size, W4A8_LAYOUT_TILED,
+                             h8_dev, YDT_E4M3, 2 * F))
+        return e;
+    if (!h_scale_dev) return W4A8_ERR_NULL;
+    if (reinterpret_cast<uintptr_t>(h_scale_dev) % 4) return W4A8_ERR_ALIGN;
+    if (M == 0) return W4A8_OK;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const w4a8_dtype ydt = static_cast<w4a8_dtype>(YDT_SILU_E4M3);
+    const int64_t N = 2 * F;
+    const bool deep_narrow = K >= 8192 && N <= 8192;             // same kernel choice as w4a8_linear
+    if (M <= 32 || (M <= 64 && deep_narrow))
+        return launch_linear_skinny(x8_dev, M, K, ldx8, x_scale_dev, packed_dev, w_scales_dev, N, group_size, h8_dev, ydt,
+                                    ldh8, 0, 0, 0, nullptr, 0, MODE_CODE_EXACT, h_scale_dev, st);
+    return launch_linear_mfma_tiled(x8_dev, M, K, ldx8, x_scale_dev, packed_dev, w_scales_dev, N, group_size, h8_dev, ydt,
+                                    ldh8, 0, 0, 0, nullptr, 0, MODE_CODE_EXACT, h_scale_dev, st);
+}
+
 size_t w4a8_asym_params_bytes(int64_t N, int64_t K, int32_t group_size) {
     if (check_weight_shape(N, K, group_size, W4A8_LAYOUT_TILED) != W4A8_OK) return 0;
     return (size_t)(((N + 15) / 16) * (K / group_size) * 80);

@@ -67,8 +67,10 @@ __global__ void __launch_bounds__(512, (KS * MF > 16 || MF * TPW > 16) ? 2 : 4) 
     constexpr int ZP_OFF = SC_OFF + WAVES * TPW * 256;           // asymmetric format: per lane the dword that holds its zero-point
     constexpr int LOOP_BYTES = ZP_OFF + (ASYM ? WAVES * TPW * 256 : 0);
     constexpr int RED_BYTES = (KS - 1) * NB * TPW * MF * 4 * 64 * 4;   // partial sums of groups 1 .. KS-1
-    constexpr int RS = BN + 16 / sizeof(OutT);                   // epilogue row stride: rows stay 16-byte aligned
-    constexpr int SLAB16_BYTES = 16 * RS * (int)sizeof(OutT);    // one 16-token slab of the workgroup's output
+    using SlabT = typename OutKind<OutT>::Slab;                  // element of the epilogue's LDS slab
+    constexpr bool SILU = OutKind<OutT>::SILU;
+    constexpr int RS = BN + 16 / sizeof(SlabT);                  // epilogue row stride: rows stay 16-byte aligned
+    constexpr int SLAB16_BYTES = 16 * RS * (int)sizeof(SlabT);   // one 16-token slab of the workgroup's output
     constexpr int LDS_BYTES = MaxOf<MaxOf<LOOP_BYTES, RED_BYTES>::value, SLAB16_BYTES>::value;
     constexpr int FR = (LDS_BYTES / SLAB16_BYTES < MF) ? LDS_BYTES / SLAB16_BYTES : MF;   // slabs per epilogue round
     constexpr int PIECES = (8 + MF - 1) / MF;                    // eighths of a band's expansion per step, at most
@@ -348,9 +350,9 @@ __global__ void __launch_bounds__(512, (KS * MF > 16 || MF * TPW > 16) ? 2 : 4) 
         const int n = bn * BN + (band * TPW + j) * 16 + i;
         so[j] = OUT_SCALED ? sx * w_out[per_channel ? min(n, N - 1) : 0] : sx;
     }
-    OutT* slab = reinterpret_cast<OutT*>(lds);
-    constexpr int VEC = 16 / sizeof(OutT);                       // elements per 16-byte store
-    constexpr int UPR = BN / VEC;                                // 16-byte units per row
+    SlabT* slab = reinterpret_cast<SlabT*>(lds);
+    constexpr int VEC = SILU ? 16 : 16 / sizeof(SlabT);          // outputs per 16-byte store
+    constexpr int UPR = (SILU ? BN / 2 : BN) / VEC;              // 16-byte units per row
     const int n_block = bn * BN;
     const bool vec_ok = (ldy % VEC == 0) && (reinterpret_cast<uintptr_t>(y) % 16 == 0);
 #pragma unroll
@@ -364,7 +366,7 @@ __global__ void __launch_bounds__(512, (KS * MF > 16 || MF * TPW > 16) ? 2 : 4) 
 #pragma unroll
                         for (int r = 0; r < 4; ++r)
                             slab[(ff * 16 + 4 * kq + r) * RS + (band * TPW + j) * 16 + i] =
-                                OutCast<OutT>::cast(so[j] * acc[(f0 + ff < MF) ? f0 + ff : 0][j][r], yq);
+                                OutCast<SlabT>::cast(so[j] * acc[(f0 + ff < MF) ? f0 + ff : 0][j][r], yq);
                 }
             }
         }
@@ -372,14 +374,39 @@ __global__ void __launch_bounds__(512, (KS * MF > 16 || MF * TPW > 16) ? 2 : 4) 
         constexpr int ROWS = FR * 16;
         for (int u = tid; u < ROWS * UPR; u += WAVES * 64) {
             const int row = u / UPR, col = (u % UPR) * VEC;
-            const int m = m0 + f0 * 16 + row, n = n_block + col;
-            if (row < (MF - f0) * 16 && m < M && n < N) {
-                OutT* dst = y + (int64_t)m * ldy + n;
-                const OutT* src = slab + row * RS + col;
-                if (vec_ok && n + VEC <= N) {
-                    *reinterpret_cast<uint4*>(dst) = *reinterpret_cast<const uint4*>(src);
-                } else {
-                    for (int e = 0; e < VEC && n + e < N; ++e) dst[e] = src[e];
+            const int m = m0 + f0 * 16 + row;
+            if constexpr (SILU) {
+                // 16 outputs of one band pair: gate = slab columns 32p .. 32p+15, up = 32p+16 .. 32p+31 (p = col / 16)
+                const int n_out = n_block / 2 + col;             // first of the 16 output columns; N / 2 columns in all
+                if (row < (MF - f0) * 16 && m < M && n_out < N / 2) {
+                    const SlabT* g = slab + row * RS + 2 * col;
+                    uint8_t* dst = reinterpret_cast<uint8_t*>(y) + (int64_t)m * ldy + n_out;
+                    uint32_t w[4];
+#pragma unroll
+                    for (int e = 0; e < 16; e += 4) {
+                        float h[4];
+#pragma unroll
+                        for (int t = 0; t < 4; ++t)
+                            h[t] = bf16_bits_to_f32(f32_to_bf16_bits(
+                                silu_mul_f32(bf16_bits_to_f32(g[e + t]), bf16_bits_to_f32(g[16 + e + t]))));
+                        w[e / 4] = cvt2(h[2] / yq, h[3] / yq, cvt2(h[0] / yq, h[1] / yq, 0u, false), true);
+                    }
+                    if (vec_ok && n_out + 16 <= N / 2) {
+                        *reinterpret_cast<uint4*>(dst) = make_uint4(w[0], w[1], w[2], w[3]);
+                    } else {
+                        for (int e = 0; e < 16 && n_out + e < N / 2; ++e) dst[e] = (uint8_t)(w[e / 4] >> (8 * (e % 4)));
+                    }
+                }
+            } else {
+                const int n = n_block + col;
+                if (row < (MF - f0) * 16 && m < M && n < N) {
+                    OutT* dst = y + (int64_t)m * ldy + n;
+                    const OutT* src = slab + row * RS + col;
+                    if (vec_ok && n + VEC <= N) {
+                        *reinterpret_cast<uint4*>(dst) = *reinterpret_cast<const uint4*>(src);
+                    } else {
+                        for (int e = 0; e < VEC && n + e < N; ++e) dst[e] = src[e];
+                    }
                 }
             }
         }
@@ -393,10 +420,10 @@ void launch_one(const LinearArgs& a, dim3 grid, int grid_m, int grid_n, hipStrea
     hipLaunchKernelGGL((linear_mfma_kernel<OutT, MF, KS, TPW, MODEV>), grid, dim3(WAVES * 64), 0, st, a.x8, a.M, a.ldx8, a.s_x, \
                        a.packed, a.scales, a.N, a.n_tiles, a.C, a.cpg, a.NG, static_cast<OutT*>(a.y), a.ldy, grid_m, grid_n,   \
                        a.w_out, a.per_channel, a.y_scale)
-    if (sizeof(OutT) == 1) {                                     // FP8 output exists for the code-exact mode only
+    if constexpr (sizeof(OutT) == 1) {                           // FP8 output exists for the code-exact mode only
         W4A8_MFMA(MODE_CODE_EXACT);
         return;
-    }
+    } else {
     if (a.mode == MODE_TWO_LEVEL)
         W4A8_MFMA(MODE_TWO_LEVEL);
     else if (a.mode == MODE_ASYM)
@@ -407,6 +434,7 @@ void launch_one(const LinearArgs& a, dim3 grid, int grid_m, int grid_n, hipStrea
         W4A8_MFMA(MODE_ASYM_TWO);
     else
         W4A8_MFMA(MODE_CODE_EXACT);
+    }
 #undef W4A8_MFMA
 }
 
@@ -418,7 +446,8 @@ int launch_linear_mfma_tiled(const uint8_t* x8, int64_t M, int64_t K, int64_t ld
                              const uint8_t* packed, const float* scales, int64_t N, int32_t G, void* y,
                              w4a8_dtype ydt, int64_t ldy, int mf, int ks, int tpw, const float* w_out, int per_channel,
                              int mode, const float* y_scale, hipStream_t st) {
-    if ((int)ydt == YDT_E4M3 && (mode != MODE_CODE_EXACT || !y_scale)) return W4A8_ERR_DTYPE;
+    if (((int)ydt == YDT_E4M3 || (int)ydt == YDT_SILU_E4M3) && (mode != MODE_CODE_EXACT || !y_scale)) return W4A8_ERR_DTYPE;
+    if ((int)ydt == YDT_SILU_E4M3 && N % 32 != 0) return W4A8_ERR_SHAPE;   // whole pairs of gate and up bands
     if (!(mf == 0 || mf == 4 || mf == 8 || mf == 16) || !(ks == 0 || ks == 1 || ks == 2 || ks == 4) || tpw < 0 || tpw > 2)
         return W4A8_ERR_SHAPE;
     const int C = (int)(K / 128), cpg = G / 128, NG = (int)(K / G);
@@ -464,6 +493,8 @@ int launch_linear_mfma_tiled(const uint8_t* x8, int64_t M, int64_t K, int64_t ld
         launched = true;                                                      \
         if (ydt == W4A8_F32)                                                  \
             launch_one<float, MFV, KSV, TPV>(a, grid, grid_m, grid_n, st);    \
+        else if ((int)ydt == YDT_SILU_E4M3)                                   \
+            launch_one<SiluFp8, MFV, KSV, TPV>(a, grid, grid_m, grid_n, st);  \
         else if ((int)ydt == YDT_E4M3)                                        \
             launch_one<uint8_t, MFV, KSV, TPV>(a, grid, grid_m, grid_n, st);  \
         else                                                                  \

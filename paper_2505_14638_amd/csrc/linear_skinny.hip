@@ -207,14 +207,37 @@ __global__ void __launch_bounds__(max_threads(MT * NT, MODE == MODE_ASYM || MODE
     const float sx = *s_x;
     const float yq = (sizeof(OutT) == 1) ? *y_scale : 1.0f;      // FP8 output: the next layer's activation scale
     constexpr int COLS = 16 * NT;                                // output channels of this workgroup
-    for (int idx = threadIdx.x; idx < MT * 16 * COLS; idx += blockDim.x) {
-        const int col = idx % COLS, row = idx / COLS;            // channel fastest: consecutive threads, consecutive y
-        const int j = col >> 4, nl = col & 15, mt = row >> 4, ml = row & 15;
-        const int e = (mt * NT + j) * 4 + (nl & 3), src_lane = ml + 16 * (nl >> 2);
-        float sum = 0.0f;
-        for (int w = 0; w < waves; ++w) sum += red[(w * E + e) * RED_STRIDE + src_lane];
-        const int m = mt * 16 + ml, n = (t0 + j) * 16 + nl;
-        if (m < M && n < N) y[(int64_t)m * ldy + n] = OutCast<OutT>::cast((OUT_SCALED ? sx * w_out[per_channel ? n : 0] : sx) * sum, yq);
+    if constexpr (OutKind<OutT>::SILU) {
+        // gate|up with SiLU*mul and the next quantization folded in: tiles 2p and 2p+1 of the workgroup are the gate and
+        // up rows of the same 16 channels; one thread per output byte
+        constexpr int HALF = COLS / 2;
+        uint8_t* h8 = reinterpret_cast<uint8_t*>(y);
+        for (int idx = threadIdx.x; idx < MT * 16 * HALF; idx += blockDim.x) {
+            const int col = idx % HALF, row = idx / HALF;
+            const int p = col >> 4, nl = col & 15, mt = row >> 4, ml = row & 15;
+            const int src_lane = ml + 16 * (nl >> 2);
+            const int eg = (mt * NT + 2 * p) * 4 + (nl & 3), eu = (mt * NT + 2 * p + 1) * 4 + (nl & 3);
+            float sg = 0.0f, su = 0.0f;
+            for (int w = 0; w < waves; ++w) {
+                sg += red[(w * E + eg) * RED_STRIDE + src_lane];
+                su += red[(w * E + eu) * RED_STRIDE + src_lane];
+            }
+            const int m = mt * 16 + ml, n_out = (t0 / 2) * 16 + col;
+            if (m < M && n_out < N / 2) {
+                const float g = bf16_bits_to_f32(f32_to_bf16_bits(sx * sg)), u = bf16_bits_to_f32(f32_to_bf16_bits(sx * su));
+                h8[(int64_t)m * ldy + n_out] = quantize_one(bf16_bits_to_f32(f32_to_bf16_bits(silu_mul_f32(g, u))), yq);
+            }
+        }
+    } else {
+        for (int idx = threadIdx.x; idx < MT * 16 * COLS; idx += blockDim.x) {
+            const int col = idx % COLS, row = idx / COLS;            // channel fastest: consecutive threads, consecutive y
+            const int j = col >> 4, nl = col & 15, mt = row >> 4, ml = row & 15;
+            const int e = (mt * NT + j) * 4 + (nl & 3), src_lane = ml + 16 * (nl >> 2);
+            float sum = 0.0f;
+            for (int w = 0; w < waves; ++w) sum += red[(w * E + e) * RED_STRIDE + src_lane];
+            const int m = mt * 16 + ml, n = (t0 + j) * 16 + nl;
+            if (m < M && n < N) y[(int64_t)m * ldy + n] = OutCast<OutT>::cast((OUT_SCALED ? sx * w_out[per_channel ? n : 0] : sx) * sum, yq);
+        }
     }
 }
 
@@ -228,10 +251,10 @@ int launch_one(const LinearArgs& a, int depth, int waves, hipStream_t st) {
     hipLaunchKernelGGL((linear_skinny_kernel<MT, NT, DEPTHV, OutT, MODEV>), dim3(grid), dim3(waves * 64), lds, st, a.x8, a.M, \
                        a.ldx8, a.s_x, a.packed, a.scales, a.N, a.n_tiles, a.C, a.cpg, a.NG, static_cast<OutT*>(a.y), a.ldy,   \
                        cpw, a.w_out, a.per_channel, a.y_scale)
-    if (sizeof(OutT) == 1) {                                     // FP8 output exists for the code-exact mode only
+    if constexpr (sizeof(OutT) == 1) {                           // FP8 output exists for the code-exact mode only
         W4A8_SKINNY(2, MODE_CODE_EXACT);
         return launch_status();
-    }
+    } else {
     if (a.mode == MODE_TWO_LEVEL)
         W4A8_SKINNY(2, MODE_TWO_LEVEL);
     else if (a.mode == MODE_ASYM)
@@ -244,14 +267,17 @@ int launch_one(const LinearArgs& a, int depth, int waves, hipStream_t st) {
         W4A8_SKINNY(DEEP, MODE_CODE_EXACT);
     else
         W4A8_SKINNY(2, MODE_CODE_EXACT);
-#undef W4A8_SKINNY
     return launch_status();
+    }
+#undef W4A8_SKINNY
 }
 
 template <int MT, typename OutT>
 int launch_nt(const LinearArgs& a, int nt, int depth, int waves, hipStream_t st) {
     switch (nt) {
-        case 1: return launch_one<MT, 1, OutT>(a, depth, waves, st);
+        case 1:
+            if constexpr (OutKind<OutT>::SILU) return W4A8_ERR_SHAPE;   // gate and up tiles come in pairs
+            else return launch_one<MT, 1, OutT>(a, depth, waves, st);
         case 2: return launch_one<MT, 2, OutT>(a, depth, waves, st);
         case 4: return launch_one<MT, 4, OutT>(a, depth, waves, st);
     }
@@ -290,6 +316,11 @@ int launch_linear_skinny(const uint8_t* x8, int64_t M, int64_t K, int64_t ldx8, 
         while (waves < 16 && waves * waves * 2 < want * want) waves *= 2;   // odd counts split K unevenly and measured slower
     }
     if (waves > C) waves = C;
+    // The fused gate|up layer needs gate and up tiles in one workgroup.  It keeps the split of K the plain layer would
+    // use on the same shape, so that every partial sum, and with it every output byte, is the same as in the unfused
+    // sequence (the one exception: 17..32 tokens on a layer narrow enough for 16 wavefronts, where four register tiles
+    // allow only 8).
+    if ((int)ydt == YDT_SILU_E4M3 && nt == 1) nt = 2;
     const int thread_cap = max_threads(mt * nt, mode == MODE_ASYM || mode == MODE_ASYM_TWO);
     while (waves > 1 && (waves * mt * nt > 64 || waves * 64 > thread_cap)) --waves;   // LDS and registers
     if (waves < 1 || waves > 16 || waves * mt * nt > 64 || waves * 64 > thread_cap) return W4A8_ERR_SHAPE;
@@ -299,6 +330,10 @@ int launch_linear_skinny(const uint8_t* x8, int64_t M, int64_t K, int64_t ldx8, 
     if ((int)ydt == YDT_E4M3) {
         if (mode != MODE_CODE_EXACT || !y_scale) return W4A8_ERR_DTYPE;
         return launch_mt<uint8_t>(a, mt, nt, depth, waves, st);
+    }
+    if ((int)ydt == YDT_SILU_E4M3) {                             // pairs of gate and up tiles: nt is even here
+        if (mode != MODE_CODE_EXACT || !y_scale || nt % 2 != 0) return W4A8_ERR_DTYPE;
+        return launch_mt<SiluFp8>(a, mt, nt, depth, waves, st);
     }
     if (ydt == W4A8_F32) return launch_mt<float>(a, mt, nt, depth, waves, st);
     return launch_mt<uint16_t>(a, mt, nt, depth, waves, st);

@@ -6,7 +6,7 @@
 namespace w4a8 {
 namespace {
 
-__device__ __forceinline__ float silu_mul(float g, float u) { return g / (1.0f + expf(-g)) * u; }
+__device__ __forceinline__ float silu_mul(float g, float u) { return silu_mul_f32(g, u); }
 
 // Q = false: h is bf16.  Q = true: h is E4M3 bytes, nearest_E4M3(bf16(silu(gate) * up) / *q_scale).
 template <bool Q>

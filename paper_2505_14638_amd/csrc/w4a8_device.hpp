@@ -311,6 +311,26 @@ __device__ __forceinline__ float bf16_bits_to_f32(uint16_t b) { return __uint_as
 // Eq. 13 for one value: nearest_E4M3(x / s), the quotient one IEEE float32 division.
 __device__ __forceinline__ uint8_t quantize_one(float x, float s) { return (uint8_t)(cvt2(x / s, 0.0f, 0u, false) & 0xFFu); }
 
+// silu(gate) * up in float32 (the decoder block's elementwise step): silu(g) = g / (1 + exp(-g)).
+__device__ __forceinline__ float silu_mul_f32(float g, float u) { return g / (1.0f + expf(-g)) * u; }
+
+// Output kinds of the linear kernels.  float, uint16_t (bf16) and uint8_t (E4M3 of the bf16 value, Eq. 13 with the next
+// layer's scale) are what they say.  SiluFp8 is the gate|up layer of a decoder block with SiLU*mul and the down
+// projection's activation quantization folded in: the weight rows come interleaved in 16-row bands (band 2p = gate
+// rows 16p .. 16p+15, band 2p+1 = up rows 16p .. 16p+15), the kernel forms the bf16 values of both, and writes
+// h8[m, 16p + i] = nearest_E4M3( bf16(silu(gate) * up) / scale ) -- N / 2 bytes per token.
+struct SiluFp8 {
+    uint8_t byte;
+};
+template <typename T> struct OutKind {
+    using Slab = T;                        // what the epilogue holds per output channel before storing
+    static constexpr bool SILU = false;
+};
+template <> struct OutKind<SiluFp8> {
+    using Slab = uint16_t;
+    static constexpr bool SILU = true;
+};
+
 // Output conversions of the linear kernels.  `q` is the static scale of the NEXT layer's activation quantization and
 // counts only for FP8 output (uint8_t): the value is rounded to bf16 first, then quantized by Eq. 13, which is exactly
 // what a bf16 output followed by the activation-quantize kernel produces.

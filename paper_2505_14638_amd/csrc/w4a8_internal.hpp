@@ -42,6 +42,8 @@ struct LinearArgs {
 // Output type beyond the public w4a8_dtype values, for the launchers: E4M3 bytes, the bf16 result quantized with the
 // next layer's static activation scale (code-exact mode only).
 constexpr int YDT_E4M3 = 2;
+// The gate|up layer with SiLU*mul and the next quantization folded in (see SiluFp8): y is E4M3 bytes [M, N / 2].
+constexpr int YDT_SILU_E4M3 = 3;
 
 int launch_quantize_act(const void* x, w4a8_dtype dt, int64_t M, int64_t K, int64_t ldx, const float* scale,
                         uint8_t* x8, int64_t ldx8, hipStream_t st);

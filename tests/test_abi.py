@@ -181,6 +181,12 @@ def test_fused_validation(L):
     assert f(P, 4, 256, 256, P, P, P, 64, 128, P, P, 32, None) == 2                    # ldy8 < N
     assert f(P, 4, 256, 256, P, P, P, 64, 96, P, P, 64, None) == 3
     assert L.w4a8_linear(P, 4, 256, 256, P, P, P, 64, 128, B.LAYOUT_TILED, P, 2, 64, None, 0, None) == 4   # 2 is not public
+    g = L.w4a8_linear_silu_mul_fp8_out
+    # x8, M, K, ldx8, xs, packed, scales, F, G, h_scale, h8, ldh8, stream
+    assert g(P, 0, 256, 256, P, P, P, 64, 128, P, P, 64, None) == 0
+    assert g(P, 4, 256, 256, P, P, P, 40, 128, P, P, 64, None) == 2                    # F % 16 != 0
+    assert g(P, 4, 256, 256, P, P, P, 64, 128, P, P, 32, None) == 2                    # ldh8 < F
+    assert g(P, 4, 256, 256, P, P, P, 64, 128, 0, P, 64, None) == 1
     q = L.w4a8_silu_mul_quantize
     assert q(P, 0, 64, 128, P, P, 64, None) == 0
     assert q(P, 4, 64, 64, P, P, 64, None) == 2                                        # ldgu < 2F

@@ -89,6 +89,7 @@ def test_block_stack_fused_is_the_same_computation(block, m):
     blk, _, _ = block
     fused = DecoderBlockLinears(HIDDEN, FFN, QKV_OUT, G, DEV, fused=True)
     fused.weights, fused.scales_x = blk.weights, blk.scales_x
+    assert "gate_up_interleaved" in blk.weights
     x_bits = syn.f32_to_bf16_bits(syn.make_activations(syn.rng_for(5, 200 + m), m, HIDDEN, CFG["frac"], CFG["mult"]))
     x_d = torch.from_numpy(x_bits.view(np.int16)).to(DEV).view(torch.bfloat16)
     a, b = {}, {}
@@ -97,8 +98,7 @@ def test_block_stack_fused_is_the_same_computation(block, m):
     torch.cuda.synchronize()
     for name in ("qkv_x8", "o_x8", "gate_up_x8", "down_x8"):
         assert torch.equal(a[name], b[name].contiguous()), name
-    for name in ("gate_up", "down"):
-        assert np.array_equal(bits(a[name]), bits(b[name])), name
+    assert np.array_equal(bits(a["down"]), bits(b["down"]))
 
 
 @pytest.mark.parametrize("m,k,n", [(1, 1024, 96), (16, 512, 200), (40, 1024, 72), (100, 384, 300), (300, 1024, 520),
@@ -136,3 +136,30 @@ def test_silu_mul_quantize_equals_silu_mul_then_quantize(gpu_lib, m, f):
     got = B.silu_mul_quantize(gu, torch.tensor([s], dtype=torch.float32, device=DEV))
     torch.cuda.synchronize()
     assert np.array_equal(got.cpu().numpy(), want)
+
+
+@pytest.mark.parametrize("m,k,f", [(1, 1024, 48), (16, 512, 208), (40, 1024, 64), (100, 384, 304), (300, 1024, 528),
+                                   (257, 640, 144)])
+def test_fused_gate_up_equals_the_unfused_sequence(gpu_lib, m, k, f):
+    """w4a8_linear_silu_mul_fp8_out on the row-interleaved gate|up matrix against linear (bf16) -> SiLU*mul -> Eq. 13 on
+    the matrix in its natural order: the same bytes; ragged channel counts, both kernels, a strided output."""
+    rng = np.random.default_rng([63, m, k, f])
+    w = syn.make_weights(rng, 2 * f, k) * np.float32(8.0)
+    x = syn.make_activations(rng, m, k, 0.02, 20.0)
+    s_x = syn.static_act_scale(x)
+    x8 = torch.from_numpy(o.quantize_act(x, s_x)).to(DEV)
+    sx = torch.tensor([s_x], dtype=torch.float32, device=DEV)
+    w_d = torch.from_numpy(w).to(DEV)
+    packed, scales = B.pack_weights(w_d, G, B.LAYOUT_TILED)
+    gu = B.linear(x8, sx, packed, scales, 2 * f, G, B.LAYOUT_TILED, out_dtype=torch.bfloat16)
+    h = bits(B.silu_mul(gu))
+    s_h = np.float32(np.abs(o.bf16_bits_to_f32(h)).max() / 600.0)
+    want = o.quantize_act(h, s_h, x_is_bf16_bits=True)
+    pi, si = B.pack_weights(B.interleave_gate_up(w_d), G, B.LAYOUT_TILED)
+    wide = torch.zeros((m, f + 48), dtype=torch.uint8, device=DEV)
+    got = B.linear_silu_mul_fp8_out(x8, sx, pi, si, f, G, torch.tensor([s_h], dtype=torch.float32, device=DEV),
+                                    out=wide[:, 16:16 + f])
+    torch.cuda.synchronize()
+    assert np.array_equal(got.cpu().numpy(), want)
+    assert int(wide[:, :16].max()) == 0 and int(wide[:, 16 + f:].max()) == 0
+    assert (want & 0x7F).max() == 0x7E and len(np.unique(want)) > 20
