@@ -241,14 +241,10 @@ __global__ void __launch_bounds__(512, (KS * MF > 16 || MF * TPW > 16) ? 2 : 4) 
                         uint32_t o;
                         if (TWO) {
                             o = (e & 1) ? two_level_half_fast<4>(src, tab[jb]) : two_level_half_fast<0>(src, tab[jb]);
-                            if (m8[jb])
-                                o = (e & 1) ? two_level_fix_minus_eight<4>(o, src, tab[jb])
-                                            : two_level_fix_minus_eight<0>(o, src, tab[jb]);
                         } else if (ASYM) {
                             o = (e & 1) ? asym_half<4>(src, atab[jb]) : asym_half<0>(src, atab[jb]);
                         } else {
                             o = (e & 1) ? sm_half_to_e4m3_fast<4>(src) : sm_half_to_e4m3_fast<0>(src);
-                            if (m8[jb]) o = sm_fix_minus_eight(o);   // wave-uniform, rare
                         }
                         keep_here(o);
                         next.op[jb][e] = (int)o;
@@ -266,6 +262,25 @@ __global__ void __launch_bounds__(512, (KS * MF > 16 || MF * TPW > 16) ? 2 : 4) 
                 acc[MF - 1][TPW - 1][1] = fmaf(sc, p_prev[1], acc[MF - 1][TPW - 1][1]);
                 acc[MF - 1][TPW - 1][2] = fmaf(sc, p_prev[2], acc[MF - 1][TPW - 1][2]);
                 acc[MF - 1][TPW - 1][3] = fmaf(sc, p_prev[3], acc[MF - 1][TPW - 1][3]);
+            }
+            // The -8 fix-up of the freshly expanded operand, for the bands whose next chunk is marked: here, after the
+            // steps, so that the step sequence above stays one basic block (a wave-uniform branch per piece of the
+            // expansion would cut it up, and the order of MFMAs, LDS reads and ALU work cannot be held across blocks).
+            if (!ASYM) {
+#pragma unroll
+                for (int j = 0; j < TPW; ++j) {
+                    if (m8[j]) {
+#pragma unroll
+                        for (int e = 0; e < 8; ++e) {
+                            const int d = e >> 1;
+                            const uint32_t src = d == 0 ? raw[j].x : d == 1 ? raw[j].y : d == 2 ? raw[j].z : raw[j].w;
+                            const uint32_t o = (uint32_t)next.op[j][e];
+                            next.op[j][e] = TWO ? (int)((e & 1) ? two_level_fix_minus_eight<4>(o, src, tab[j])
+                                                                : two_level_fix_minus_eight<0>(o, src, tab[j]))
+                                                : (int)sm_fix_minus_eight(o);
+                        }
+                    }
+                }
             }
         }
         __builtin_amdgcn_s_setprio(0);
