@@ -1,9 +1,9 @@
 // W4A8 linear layer for many tokens (the compute-bound regime of Sec. 1): an MFMA-tiled GEMM with the INT4 -> E4M3
 // expansion (Eq. 10) fused in front of the FP8 matrix unit.
 //
-// A workgroup of eight wavefronts computes 16*MF tokens x (128 / KS) channels of Y.  The wavefronts form KS groups
-// that split K between them: in every pass over the main loop group kg multiplies the 128-deep chunk c = KS * pass + kg.
-// Inside a group each wavefront owns one 16-channel weight band and all 16*MF tokens:
+// A workgroup of eight wavefronts computes 16*MF tokens x (128 * TPW / KS) channels of Y.  The wavefronts form KS
+// groups that split K between them: in every pass over the main loop group kg multiplies the 128-deep chunk
+// c = KS * pass + kg.  Inside a group each wavefront owns TPW 16-channel weight bands and all 16*MF tokens:
 //   - activations are the row operand and weights the column operand of the 16x16x128 MFMA, so a result lane holds
 //     one channel: its group scale is a single register, and every MFMA (started from a zero accumulator) is folded
 //     into the running sum with four FMAs against that scale -- group scales cannot be factored out of the sum over K;
@@ -16,7 +16,8 @@
 //     chunk is spread over the MFMAs of the current one, and two operand buffers alternate by pass parity, so nothing
 //     is copied;
 //   - each step issues the LDS reads of the next token block, then this block's MFMA, then the FMAs of the previous
-//     block (independent of the MFMA in flight);
+//     block (independent of the MFMA in flight); the steps of a pass form one basic block and run at raised wavefront
+//     priority;
 //   - the K-split groups add their partial sums through LDS, and the block of Y goes through LDS once more so that
 //     global stores are whole row segments.
 // Workgroups are numbered so that the ones resident on one XCD (one L2) at a time cover a compact rectangle of
