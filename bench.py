@@ -13,7 +13,8 @@ bytes = N*K/2 (codes) + 4*N*K/G (scales) + M*K (FP8 activations) + 2*M*N (bf16 o
 
 Also reported: `roofline` for the dominant kernel (the skinny linear kernel, timed alone with HIP events on the
 launch stream), `prefill` (TFLOP/s of the MFMA-tiled kernel over the prefill sweep, with its own roofline), and
-`cpu_baseline` (the CPU oracle timed on a bounded sample of the same workload).
+`cpu_baseline` (the CPU oracle timed on a bounded sample of the same workload); `block` (decoder-block latency),
+`weight_modes` (the other weight formats on one layer) and `calibration` (the offline DPQ + GAR step) are short extra legs.
 """
 import argparse
 import json
@@ -280,6 +281,47 @@ def weight_modes(dev):
     return {"metric": "weight formats on the gate|up layer (K = 4096, N = 28672), random codes", "by_case": out}
 
 
+def calibration(dev):
+    """Offline calibration on one Llama-3-8B-shaped layer (the O projection, 4096 x 4096): Group-Aware Reordering and
+    DPQ (Alg. 1) timed on the GPU, and the layer error of the calibrated weights against the same double quantization
+    without error compensation, both run through packing and the literal inference layer on 512 calibration tokens.
+    The Hessian X^T X, its dampening and Cholesky factors are dense linear algebra done with torch (float64)."""
+    n = k = 4096
+    t = 8192
+    rng = syn.rng_for(9, n, k)
+    w = torch.from_numpy(syn.make_weights(rng, n, k)).to(dev)
+    x = torch.from_numpy(syn.make_activations(rng, t, k, 0.01, 20.0)).to(dev)
+    x = x * torch.exp(torch.from_numpy(rng.uniform(-1.0, 1.0, size=k).astype(np.float32)).to(dev))[None, :]
+    s_x = (x.abs().max() / 448.0).reshape(1).to(torch.float32)
+    x8 = B.quantize_act(x, s_x)
+    s_w = (w.abs().amax(dim=1) / 448.0).to(torch.float32)
+    xd = x.double()
+    h = xd.T @ xd
+    t0, t1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    perm = B.gar_permutation(torch.diagonal(h).float().contiguous(), G)
+    hp = h[perm.long()][:, perm.long()]
+    hp = hp + torch.eye(k, device=dev, dtype=torch.float64) * (0.01 * torch.diagonal(hp).mean())
+    u = torch.linalg.cholesky(torch.cholesky_inverse(torch.linalg.cholesky(hp)), upper=True).float().contiguous()
+    B.dpq_calibrate(w, u, s_w, G, perm)                                  # untimed first run
+    torch.cuda.synchronize()
+    t0.record()
+    perm = B.gar_permutation(torch.diagonal(h).float().contiguous(), G)
+    cal = B.dpq_calibrate(w, u, s_w, G, perm)
+    t1.record()
+    torch.cuda.synchronize()
+    ms = t0.elapsed_time(t1)
+    plain = B.dpq_calibrate(w, torch.eye(k, device=dev), s_w, G)         # identity factor: no error reaches another weight
+    rows = x8[:512]
+    ref = (x[:512].double() @ w.double().T)
+    err = {}
+    for name, (codes, scales, zeros) in {"dpq_gar": cal, "uncompensated": plain}.items():
+        packed, params = B.pack_weights_asym(codes, G, scales, zeros)
+        y = B.linear_asym_two_level(rows, s_x, packed, params, s_w, n, G, out_dtype=torch.float32)
+        err[name] = float(((y.double() - ref) ** 2).sum())
+    return {"metric": "GAR + DPQ (Alg. 1) on a 4096 x 4096 layer, 8192 calibration tokens", "calibrate_ms": round(ms, 2),
+            "layer_error_ratio_vs_uncompensated": round(err["dpq_gar"] / err["uncompensated"], 4)}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -430,6 +472,7 @@ def main():
         if not args.no_block:
             result["block"] = block_latency(dev, 50, 5)
             result["weight_modes"] = weight_modes(dev)
+            result["calibration"] = calibration(dev)
     if not args.no_cpu and not args.prefill_only:
         result["cpu_baseline"] = cpu_baseline()
     print(json.dumps(result))
