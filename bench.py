@@ -281,6 +281,43 @@ def weight_modes(dev):
     return {"metric": "weight formats on the gate|up layer (K = 4096, N = 28672), random codes", "by_case": out}
 
 
+def decode_70b(dev, steps, warmup):
+    """Config 4's decode cases (Llama-3-70B shapes, M = 1 and 16): the linear kernel alone, HIP graph replay over two
+    rotating weight sets of random codes (428 MB each).  Layers of 34-235 MB, where launch and ramp-up weigh less."""
+    shapes = list(syn.LLAMA3_70B.values())
+    sets = []
+    for _ in range(2):
+        one = []
+        for (k, n) in shapes:
+            one.append((torch.randint(0, 256, (n * k // 2,), dtype=torch.uint8, device=dev),
+                        torch.rand(n * k // G, dtype=torch.float32, device=dev) * 0.01 + 0.001))
+        sets.append(one)
+    sx = torch.tensor([0.05], dtype=torch.float32, device=dev)
+    cases = []
+    for j, (k, n) in enumerate(shapes):
+        for m in (1, 16):
+            cases.append((j, m, k, n, torch.randint(0, 120, (m, k), dtype=torch.uint8, device=dev),
+                          torch.empty((m, n), dtype=torch.bfloat16, device=dev)))
+    total = sum(alg_bytes(m, k, n) for (_, m, k, n, _, _) in cases)
+
+    def run(i):
+        for (j, m, k, n, x8, y) in cases:
+            B.linear(x8, sx, sets[i % 2][j][0], sets[i % 2][j][1], n, G, B.LAYOUT_TILED, out=y)
+
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        run(0)
+        torch.cuda.synchronize()
+        graphs = [capture(lambda i=i: run(i)) for i in range(2)]
+        sec = time_graphs(graphs, steps, warmup) / steps
+    torch.cuda.current_stream().wait_stream(side)
+    gbs = total / sec / 1e9
+    return {"metric": "W4A8 linear effective HBM GB/s, decode cases of configs[3] (Llama-3-70B shapes, M in {1, 16})",
+            "value": round(gbs, 1), "unit": "GB/s", "frac_of_peak": round(gbs / HBM_PEAK_GBS, 4),
+            "us_per_launch": round(sec / len(cases) * 1e6, 2), "alg_bytes_per_launch": total // len(cases)}
+
+
 def calibration(dev):
     """Offline calibration on one Llama-3-8B-shaped layer (the O projection, 4096 x 4096): Group-Aware Reordering and
     DPQ (Alg. 1) timed on the GPU, and the layer error of the calibrated weights against the same double quantization
@@ -473,6 +510,8 @@ def main():
             result["block"] = block_latency(dev, 50, 5)
             result["weight_modes"] = weight_modes(dev)
             result["calibration"] = calibration(dev)
+            result["decode_70b"] = decode_70b(dev, 20, 3)
+            result["decode_70b"]["frac_of_measured"] = round(result["decode_70b"]["value"] / hbm, 4)
     if not args.no_cpu and not args.prefill_only:
         result["cpu_baseline"] = cpu_baseline()
     print(json.dumps(result))
