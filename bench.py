@@ -281,7 +281,7 @@ def weight_modes(dev):
     return {"metric": "weight formats on the gate|up layer (K = 4096, N = 28672), random codes", "by_case": out}
 
 
-def decode_70b(dev, steps, warmup):
+def llama70b(dev, steps, warmup):
     """Config 4's decode cases (Llama-3-70B shapes, M = 1 and 16): the linear kernel alone, HIP graph replay over two
     rotating weight sets of random codes (428 MB each).  Layers of 34-235 MB, where launch and ramp-up weigh less."""
     shapes = list(syn.LLAMA3_70B.values())
@@ -313,9 +313,30 @@ def decode_70b(dev, steps, warmup):
         sec = time_graphs(graphs, steps, warmup) / steps
     torch.cuda.current_stream().wait_stream(side)
     gbs = total / sec / 1e9
-    return {"metric": "W4A8 linear effective HBM GB/s, decode cases of configs[3] (Llama-3-70B shapes, M in {1, 16})",
+    # the prefill cases of the same config (M = 4096), eager launches after untimed ones
+    flop, psec = 0.0, 0.0
+    x8 = torch.randint(0, 120, (4096, max(k for (k, _) in shapes)), dtype=torch.uint8, device=dev)
+    t0, t1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    for j, (k, n) in enumerate(shapes):
+        y = torch.empty((4096, n), dtype=torch.bfloat16, device=dev)
+        xs = x8[:, :k]
+        for i in range(3):
+            B.linear(xs, sx, sets[i % 2][j][0], sets[i % 2][j][1], n, G, B.LAYOUT_TILED, out=y)
+        torch.cuda.synchronize()
+        t0.record()
+        for i in range(3):
+            B.linear(xs, sx, sets[i % 2][j][0], sets[i % 2][j][1], n, G, B.LAYOUT_TILED, out=y)
+        t1.record()
+        torch.cuda.synchronize()
+        psec += t0.elapsed_time(t1) * 1e-3 / 3
+        flop += 2.0 * 4096 * k * n
+        del y
+    tfl = flop / psec / 1e12
+    return {"metric": "W4A8 linear on configs[3] (Llama-3-70B shapes): effective HBM GB/s of the decode cases (M in {1, 16}) "
+                      "and TFLOP/s of the prefill cases (M = 4096)",
             "value": round(gbs, 1), "unit": "GB/s", "frac_of_peak": round(gbs / HBM_PEAK_GBS, 4),
-            "us_per_launch": round(sec / len(cases) * 1e6, 2), "alg_bytes_per_launch": total // len(cases)}
+            "us_per_launch": round(sec / len(cases) * 1e6, 2), "alg_bytes_per_launch": total // len(cases),
+            "prefill_tflops": round(tfl, 1), "prefill_frac_of_peak": round(tfl / FP8_PEAK_TFLOPS, 4)}
 
 
 def calibration(dev):
@@ -510,8 +531,8 @@ def main():
             result["block"] = block_latency(dev, 50, 5)
             result["weight_modes"] = weight_modes(dev)
             result["calibration"] = calibration(dev)
-            result["decode_70b"] = decode_70b(dev, 20, 3)
-            result["decode_70b"]["frac_of_measured"] = round(result["decode_70b"]["value"] / hbm, 4)
+            result["llama70b"] = llama70b(dev, 20, 3)
+            result["llama70b"]["frac_of_measured"] = round(result["llama70b"]["value"] / hbm, 4)
     if not args.no_cpu and not args.prefill_only:
         result["cpu_baseline"] = cpu_baseline()
     print(json.dumps(result))
