@@ -91,6 +91,15 @@ int w4a8_quantize_act(const void* x_dev, w4a8_dtype x_dtype, int64_t M, int64_t 
                       const float* scale_dev, uint8_t* x8_dev, int64_t ldx8, void* stream);
 
 /*
+ * Calibration of the static activation scale (Eq. 13: s_x = max|X| / Z_max over calibration data, offline).
+ *   w4a8_act_amax             folds max|X| of one batch, X [M, K] float32 or bf16 with row stride ldx elements, into
+ *                             *amax_dev (a float32 the caller has set to 0 before the first batch; NaNs are skipped)
+ *   w4a8_act_scale_from_amax  writes *scale_dev = *amax_dev / 448 (one float32 division; 1 when the maximum is 0)
+ */
+int w4a8_act_amax(const void* x_dev, w4a8_dtype x_dtype, int64_t M, int64_t K, int64_t ldx, float* amax_dev, void* stream);
+int w4a8_act_scale_from_amax(const float* amax_dev, float* scale_dev, void* stream);
+
+/*
  * Weight packing (offline with respect to inference; part of the boundary because the packed bytes are
  * compared bit for bit).  Writes w4a8_packed_bytes() bytes to packed_dev and w4a8_scales_count() floats to
  * scales_dev in `layout`.  src_scales_dev is read only for W4A8_SRC_I8_CODES (NULL otherwise).

@@ -25,6 +25,8 @@ SIGNATURES = {
     "w4a8_packed_bytes": (_c_sz, [_c_i64, _c_i64, _c_i32]),
     "w4a8_scales_count": (_c_sz, [_c_i64, _c_i64, _c_i32, _c_i32]),
     "w4a8_quantize_act": (_c_i32, [_c_vp, _c_i32, _c_i64, _c_i64, _c_i64, _c_vp, _c_vp, _c_i64, _c_vp]),
+    "w4a8_act_amax": (_c_i32, [_c_vp, _c_i32, _c_i64, _c_i64, _c_i64, _c_vp, _c_vp]),
+    "w4a8_act_scale_from_amax": (_c_i32, [_c_vp, _c_vp, _c_vp]),
     "w4a8_pack_weights": (_c_i32, [_c_vp, _c_i32, _c_vp, _c_i64, _c_i64, _c_i32, _c_i32, _c_vp, _c_vp, _c_vp]),
     "w4a8_linear_workspace_bytes": (_c_sz, [_c_i64, _c_i64, _c_i64, _c_i32]),
     "w4a8_linear": (_c_i32, [_c_vp, _c_i64, _c_i64, _c_i64, _c_vp, _c_vp, _c_vp, _c_i64, _c_i32, _c_i32, _c_vp,
@@ -124,6 +126,21 @@ def quantize_act(x: torch.Tensor, scale: torch.Tensor, out: torch.Tensor | None 
                                    scale.data_ptr(), out.data_ptr(), out.stride(0) if m > 1 else max(k, out.stride(0)),
                                    _stream()), "w4a8_quantize_act")
     return out
+
+
+def calibrate_act_scale(batches) -> torch.Tensor:
+    """Static activation scale (Eq. 13) over an iterable of [M, K] float32/bf16 device tensors: max|X| / 448."""
+    amax = scale = None
+    for x in batches:
+        if amax is None:
+            amax = torch.zeros(1, dtype=torch.float32, device=x.device)
+            scale = torch.empty(1, dtype=torch.float32, device=x.device)
+        m, k = x.shape
+        assert x.stride(1) == 1
+        _check(lib().w4a8_act_amax(x.data_ptr(), _dtype_code(x), m, k, x.stride(0) if m > 1 else max(k, x.stride(0)),
+                                   amax.data_ptr(), _stream()), "w4a8_act_amax")
+    _check(lib().w4a8_act_scale_from_amax(amax.data_ptr(), scale.data_ptr(), _stream()), "w4a8_act_scale_from_amax")
+    return scale
 
 
 def pack_weights(src: torch.Tensor, group_size: int, layout: int, src_scales: torch.Tensor | None = None,

@@ -66,6 +66,22 @@ int w4a8_quantize_act(const void* x_dev, w4a8_dtype x_dtype, int64_t M, int64_t 
     return launch_quantize_act(x_dev, x_dtype, M, K, ldx, scale_dev, x8_dev, ldx8, static_cast<hipStream_t>(stream));
 }
 
+int w4a8_act_amax(const void* x_dev, w4a8_dtype x_dtype, int64_t M, int64_t K, int64_t ldx, float* amax_dev, void* stream) {
+    if (!valid_dtype(x_dtype)) return W4A8_ERR_DTYPE;
+    if (M < 0 || K < 1 || M > DIM_MAX || K > DIM_MAX || ldx < K) return W4A8_ERR_SHAPE;
+    if (!x_dev || !amax_dev) return W4A8_ERR_NULL;
+    if (reinterpret_cast<uintptr_t>(x_dev) % (x_dtype == W4A8_F32 ? 4 : 2) || reinterpret_cast<uintptr_t>(amax_dev) % 4)
+        return W4A8_ERR_ALIGN;
+    if (M == 0) return W4A8_OK;
+    return launch_act_amax(x_dev, x_dtype, M, K, ldx, amax_dev, static_cast<hipStream_t>(stream));
+}
+
+int w4a8_act_scale_from_amax(const float* amax_dev, float* scale_dev, void* stream) {
+    if (!amax_dev || !scale_dev) return W4A8_ERR_NULL;
+    if (reinterpret_cast<uintptr_t>(amax_dev) % 4 || reinterpret_cast<uintptr_t>(scale_dev) % 4) return W4A8_ERR_ALIGN;
+    return launch_act_scale(amax_dev, scale_dev, static_cast<hipStream_t>(stream));
+}
+
 int w4a8_pack_weights(const void* src_dev, w4a8_src src_kind, const float* src_scales_dev, int64_t N, int64_t K,
                       int32_t group_size, w4a8_layout layout, uint8_t* packed_dev, float* scales_dev, void* stream) {
     if (src_kind != W4A8_SRC_F32_RTN && src_kind != W4A8_SRC_I8_CODES && src_kind != W4A8_SRC_F32_RTN_POW2)

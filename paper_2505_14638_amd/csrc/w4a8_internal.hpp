@@ -47,6 +47,8 @@ constexpr int YDT_SILU_E4M3 = 3;
 
 int launch_quantize_act(const void* x, w4a8_dtype dt, int64_t M, int64_t K, int64_t ldx, const float* scale,
                         uint8_t* x8, int64_t ldx8, hipStream_t st);
+int launch_act_amax(const void* x, w4a8_dtype dt, int64_t M, int64_t K, int64_t ldx, float* amax, hipStream_t st);
+int launch_act_scale(const float* amax, float* scale, hipStream_t st);
 int launch_pack_weights(const void* src, w4a8_src kind, const float* src_scales, int64_t N, int64_t K, int32_t G,
                         w4a8_layout layout, uint8_t* packed, float* scales, hipStream_t st);
 // asymmetric format (tiled storage): src = float32 weights (W4A8_SRC_F32_RTN) or unsigned codes with their scales and

@@ -66,6 +66,15 @@ def test_quantize_act_validation(L):
     assert f(P, B.F32, 0, 64, 64, P, P, 64, None) == 0                  # M == 0: no-op
 
 
+def test_act_scale_validation(L):
+    f = L.w4a8_act_amax
+    assert f(P, B.F32, 0, 64, 64, P, None) == 0
+    assert f(0, B.F32, 4, 64, 64, P, None) == 1 and f(P, B.F32, 4, 64, 64, 0, None) == 1
+    assert f(P, 9, 4, 64, 64, P, None) == 4 and f(P, B.F32, 4, 64, 32, P, None) == 2
+    assert f(P + 2, B.F32, 4, 64, 64, P, None) == 6
+    assert L.w4a8_act_scale_from_amax(0, P, None) == 1 and L.w4a8_act_scale_from_amax(P, P + 1, None) == 6
+
+
 def test_pack_validation(L):
     f = L.w4a8_pack_weights
     assert f(P, B.SRC_F32_RTN, 0, 16, 256, 128, B.LAYOUT_TILED, 0, P, None) == 1

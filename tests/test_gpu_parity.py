@@ -351,3 +351,26 @@ def test_silu_mul(gpu_lib):
         # fp32 arithmetic then one bf16 rounding: half a bf16 ulp plus a few fp32 ulps
         assert np.all(np.abs(yb - ref) <= o.bf16_half_ulp(np.maximum(np.abs(ref), np.abs(yb))) * (1 + 2.0 ** -10) + 1e-30)
         assert np.mean(got == o.round_to_bf16_bits(ref)) > 0.995
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_act_scale_calibration_bit_exact(gpu_lib, dtype):
+    """Eq. 13's scale over three calibration batches (one with a row stride, NaNs ignored) equals the oracle's
+    act_scale_from_amax of all the values."""
+    rng = np.random.default_rng(91)
+    batches = [syn.make_activations(rng, m, 1000, 0.01, 20.0) for m in (1, 37, 300)]
+    if dtype == "bf16":
+        vals = [o.bf16_bits_to_f32(syn.f32_to_bf16_bits(b)) for b in batches]
+        dev_batches = [torch.from_numpy(v).to(DEV).to(torch.bfloat16) for v in vals]
+    else:
+        vals = batches
+        dev_batches = [torch.from_numpy(v).to(DEV) for v in vals]
+    wide = torch.full((37, 1100), 1e9, dtype=dev_batches[1].dtype, device=DEV)
+    wide[:, :1000] = dev_batches[1]
+    dev_batches[1] = wide[:, :1000]                                       # strided rows; the padding must not be read
+    nan_batch = dev_batches[0].clone()
+    nan_batch[0, 5] = float("nan")
+    got = B.calibrate_act_scale(dev_batches + [nan_batch])
+    torch.cuda.synchronize()
+    want = o.act_scale_from_amax(np.concatenate([v.ravel() for v in vals]))
+    assert got.cpu().numpy()[0] == want
