@@ -233,3 +233,17 @@ def test_binding_fails_loudly_without_library(monkeypatch, tmp_path):
     monkeypatch.setattr(B, "LIB_PATH", str(tmp_path / "missing.so"))
     with pytest.raises(RuntimeError, match="no fallback"):
         B.lib()
+
+
+def test_interleave_gate_up_row_order():
+    """The row order the fused gate|up layer expects: bands of 16 gate rows followed by the 16 up rows of the same
+    channels (host-side re-ordering; runs on CPU tensors)."""
+    import torch
+    f, k = 48, 8
+    w = torch.arange(2 * f * k, dtype=torch.float32).reshape(2 * f, k)
+    wi = B.interleave_gate_up(w)
+    assert wi.shape == w.shape
+    for p in range(f // 16):
+        for i in range(16):
+            assert torch.equal(wi[32 * p + i], w[16 * p + i])               # gate row 16p + i
+            assert torch.equal(wi[32 * p + 16 + i], w[f + 16 * p + i])      # up row 16p + i
