@@ -245,6 +245,11 @@ int w4a8_dequant_weights_asym_two_level(const uint8_t* packed_dev, const void* p
  * Offline calibration (not part of inference; its outputs are the inputs of w4a8_pack_weights_asym with
  * W4A8_SRC_I8_CODES and of w4a8_linear_asym_two_level).
  *
+ * w4a8_hessian_accumulate: H += X^T X for one batch of calibration activations (the Hessian of the layer-wise
+ * objective, Eq. 5, App. A.2).  x_dev: X [T, K] float32 or bf16, row stride ldx elements; h_dev: float32 [K, K]
+ * row-major, in/out (set to 0 before the first batch); float32 accumulation.  K <= 65536.  Dampening (Sec. 3.3) and the
+ * Cholesky factorizations that lead from H to the factor U below are dense linear algebra left to a library.
+ *
  * w4a8_gar_permutation: Group-Aware Reordering (Sec. 3.2, App. A.3).  h_diag_dev: the K diagonal entries of the layer's
  * Hessian X^T X.  perm_dev receives K int32: position i of the reordered tensor holds original column perm[i]; columns
  * keep their group, inside a group they are ordered by descending diagonal entry, whole groups by the descending
@@ -268,6 +273,8 @@ int w4a8_dequant_weights_asym_two_level(const uint8_t* packed_dev, const void* p
  * step is one float32 operation, so the result is reproducible bit for bit.  The MSE search over scales that Sec. 3.3
  * mentions is not included (the paper gives no search grid).  K % 128 == 0, group_size % 128 == 0.
  */
+int w4a8_hessian_accumulate(const void* x_dev, w4a8_dtype x_dtype, int64_t T, int64_t K, int64_t ldx, float* h_dev,
+                            void* stream);
 int w4a8_gar_permutation(const float* h_diag_dev, int64_t K, int32_t group_size, int32_t* perm_dev, void* stream);
 size_t w4a8_dpq_workspace_bytes(int64_t N, int64_t K);
 int w4a8_dpq_calibrate(const float* w_dev, const float* u_factor_dev, const float* w_scale_dev, int32_t per_channel,

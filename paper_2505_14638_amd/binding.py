@@ -47,6 +47,7 @@ SIGNATURES = {
     "w4a8_linear_asym_two_level": (_c_i32, [_c_vp, _c_i64, _c_i64, _c_i64, _c_vp, _c_vp, _c_vp, _c_vp, _c_i32, _c_i64,
                                             _c_i32, _c_vp, _c_i32, _c_i64, _c_vp]),
     "w4a8_dequant_weights_asym_two_level": (_c_i32, [_c_vp, _c_vp, _c_i64, _c_i64, _c_i32, _c_vp, _c_vp]),
+    "w4a8_hessian_accumulate": (_c_i32, [_c_vp, _c_i32, _c_i64, _c_i64, _c_i64, _c_vp, _c_vp]),
     "w4a8_gar_permutation": (_c_i32, [_c_vp, _c_i64, _c_i32, _c_vp, _c_vp]),
     "w4a8_dpq_workspace_bytes": (_c_sz, [_c_i64, _c_i64]),
     "w4a8_dpq_calibrate": (_c_i32, [_c_vp, _c_vp, _c_vp, _c_i32, _c_vp, _c_i64, _c_i64, _c_i32, _c_vp, _c_vp, _c_vp, _c_vp,
@@ -342,6 +343,18 @@ def silu_mul_quantize(gu: torch.Tensor, scale: torch.Tensor, out: torch.Tensor |
                                         scale.data_ptr(), out.data_ptr(), out.stride(0) if m > 1 else max(f, out.stride(0)),
                                         _stream()), "w4a8_silu_mul_quantize")
     return out
+
+
+def hessian_accumulate(x: torch.Tensor, h: torch.Tensor | None = None) -> torch.Tensor:
+    """w4a8_hessian_accumulate: h (float32 [K, K], created as zeros when None) += x^T x for x [T, K] float32/bf16."""
+    t, k = x.shape
+    assert x.stride(1) == 1
+    if h is None:
+        h = torch.zeros((k, k), dtype=torch.float32, device=x.device)
+    assert h.dtype == torch.float32 and h.is_contiguous() and tuple(h.shape) == (k, k)
+    _check(lib().w4a8_hessian_accumulate(x.data_ptr(), _dtype_code(x), t, k, x.stride(0) if t > 1 else max(k, x.stride(0)),
+                                         h.data_ptr(), _stream()), "w4a8_hessian_accumulate")
+    return h
 
 
 def gar_permutation(h_diag: torch.Tensor, group_size: int) -> torch.Tensor:

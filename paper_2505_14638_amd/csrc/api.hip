@@ -319,6 +319,17 @@ int w4a8_dequant_weights_asym_two_level(const uint8_t* packed_dev, const void* p
     return dequant_asym(packed_dev, params8_dev, N, K, group_size, w8_dev, 1, stream);
 }
 
+int w4a8_hessian_accumulate(const void* x_dev, w4a8_dtype x_dtype, int64_t T, int64_t K, int64_t ldx, float* h_dev,
+                            void* stream) {
+    if (!valid_dtype(x_dtype)) return W4A8_ERR_DTYPE;
+    if (T < 0 || K < 1 || T > DIM_MAX || K > 65536 || ldx < K) return W4A8_ERR_SHAPE;
+    if (!x_dev || !h_dev) return W4A8_ERR_NULL;
+    if (reinterpret_cast<uintptr_t>(x_dev) % (x_dtype == W4A8_F32 ? 4 : 2) || reinterpret_cast<uintptr_t>(h_dev) % 4)
+        return W4A8_ERR_ALIGN;
+    if (T == 0) return W4A8_OK;
+    return launch_hessian_accumulate(x_dev, x_dtype, T, K, ldx, h_dev, static_cast<hipStream_t>(stream));
+}
+
 int w4a8_gar_permutation(const float* h_diag_dev, int64_t K, int32_t group_size, int32_t* perm_dev, void* stream) {
     if (int e = check_weight_shape(1, K, group_size, W4A8_LAYOUT_TILED)) return e;
     if (!h_diag_dev || !perm_dev) return W4A8_ERR_NULL;

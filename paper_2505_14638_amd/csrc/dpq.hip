@@ -26,6 +26,9 @@ __device__ __forceinline__ float fp8_value(float t) {
     return __builtin_amdgcn_cvt_f32_fp8(b, 0);
 }
 
+__device__ __forceinline__ float load_as_float(const float* p) { return *p; }
+__device__ __forceinline__ float load_as_float(const uint16_t* p) { return bf16_bits_to_f32(*p); }
+
 // position i of the reordered tensor holds original column perm[i]: inside a group by descending diagonal, groups
 // by descending maximum; ties keep the lower original index first.  One thread per column.
 __global__ void __launch_bounds__(256) gar_permutation_kernel(const float* __restrict__ d, int K, int G, int32_t* __restrict__ perm) {
@@ -165,7 +168,58 @@ __global__ void __launch_bounds__(256) dpq_lazy_update_kernel(DpqArgs a, int c0)
             if (r0 + tr + i < a.N && v0 + tc + j < a.K) a.work[(int64_t)(r0 + tr + i) * a.K + v0 + tc + j] = w[i][j];
 }
 
+// H += X^T X for one batch of calibration activations X [T, K] (the Hessian of the layer-wise objective, Eq. 5 and
+// App. A.2).  A workgroup of 256 threads owns a 64 x 64 tile of H, a thread 4 x 4 of it; 32 tokens at a time are staged
+// in LDS for the tile's rows and columns.  float32 accumulation.
+template <typename InT>
+__global__ void __launch_bounds__(256) hessian_accumulate_kernel(const InT* __restrict__ x, int64_t T, int64_t K, int64_t ldx,
+                                                                 float* __restrict__ h) {
+    __shared__ float xi[32 * 64], xj[32 * 64];                   // xi[t * 64 + r]: token t, feature i0 + r
+    const int tid = threadIdx.x;
+    const int64_t i0 = (int64_t)blockIdx.y * 64, j0 = (int64_t)blockIdx.x * 64;
+    const int tr = (tid >> 4) * 4, tc = (tid & 15) * 4;
+    float acc[4][4] = {};
+    for (int64_t t0 = 0; t0 < T; t0 += 32) {
+        for (int idx = tid; idx < 32 * 64; idx += 256) {
+            const int c = idx & 63, t = idx >> 6;                // consecutive threads, consecutive features: coalesced
+            const bool row_ok = t0 + t < T;
+            float a = 0.0f, b = 0.0f;
+            if (row_ok && i0 + c < K) a = load_as_float(x + (t0 + t) * ldx + i0 + c);
+            if (row_ok && j0 + c < K) b = load_as_float(x + (t0 + t) * ldx + j0 + c);
+            xi[idx] = a;
+            xj[idx] = b;
+        }
+        __syncthreads();
+#pragma unroll 8
+        for (int t = 0; t < 32; ++t) {
+            const float4 a = *reinterpret_cast<const float4*>(&xi[t * 64 + tr]);
+            const float4 b = *reinterpret_cast<const float4*>(&xj[t * 64 + tc]);
+            const float av[4] = {a.x, a.y, a.z, a.w}, bv[4] = {b.x, b.y, b.z, b.w};
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) acc[i][j] = fmaf(av[i], bv[j], acc[i][j]);
+        }
+        __syncthreads();
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            if (i0 + tr + i < K && j0 + tc + j < K) h[(i0 + tr + i) * K + j0 + tc + j] += acc[i][j];
+}
+
 }  // namespace
+
+int launch_hessian_accumulate(const void* x, w4a8_dtype dt, int64_t T, int64_t K, int64_t ldx, float* h, hipStream_t st) {
+    const dim3 grid((unsigned)((K + 63) / 64), (unsigned)((K + 63) / 64));
+    if (dt == W4A8_F32)
+        hipLaunchKernelGGL(hessian_accumulate_kernel<float>, grid, dim3(256), 0, st, static_cast<const float*>(x), T, K, ldx, h);
+    else
+        hipLaunchKernelGGL(hessian_accumulate_kernel<uint16_t>, grid, dim3(256), 0, st, static_cast<const uint16_t*>(x), T, K,
+                           ldx, h);
+    return launch_status();
+}
 
 int launch_gar_permutation(const float* hdiag, int64_t K, int32_t G, int32_t* perm, hipStream_t st) {
     hipLaunchKernelGGL(gar_permutation_kernel, dim3((unsigned)((K + 255) / 256)), dim3(256), 0, st, hdiag, (int)K, (int)G, perm);

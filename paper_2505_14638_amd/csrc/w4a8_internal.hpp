@@ -75,6 +75,7 @@ int launch_linear_mfma_tiled(const uint8_t* x8, int64_t M, int64_t K, int64_t ld
                              w4a8_dtype ydt, int64_t ldy, int mf, int ks, int tpw, const float* w_out, int per_channel,
                              int mode, const float* y_scale, hipStream_t st);
 // q_scale != nullptr: h is E4M3 bytes, the bf16 result quantized with *q_scale (Eq. 13)
+int launch_hessian_accumulate(const void* x, w4a8_dtype dt, int64_t T, int64_t K, int64_t ldx, float* h, hipStream_t st);
 int launch_gar_permutation(const float* hdiag, int64_t K, int32_t G, int32_t* perm, hipStream_t st);
 // workspace: (N * K + N * 128) floats
 int launch_dpq_calibrate(const float* w, const float* u, const float* s_w, int per_channel, const int32_t* perm,

@@ -204,6 +204,9 @@ def test_fused_validation(L):
 
 
 def test_calibration_validation(L):
+    ha = L.w4a8_hessian_accumulate
+    assert ha(P, B.F32, 0, 64, 64, P, None) == 0
+    assert ha(0, B.F32, 4, 64, 64, P, None) == 1 and ha(P, B.F32, 4, 64, 32, P, None) == 2 and ha(P, 5, 4, 64, 64, P, None) == 4
     gp = L.w4a8_gar_permutation
     assert gp(0, 256, 128, P, None) == 1 and gp(P, 256, 128, 0, None) == 1
     assert gp(P, 200, 200, P, None) == 5 and gp(P, 256, 64, P, None) == 3

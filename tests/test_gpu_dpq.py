@@ -92,3 +92,25 @@ def test_calibrated_weights_through_packing_and_inference(gpu_lib):
         errs[name] = float(np.linalg.norm(y - full) ** 2)
     print(f"  layer error on the calibration inputs: uncompensated {errs['plain']:.4e}, DPQ + GAR {errs['dpq_gar']:.4e}", flush=True)
     assert errs["dpq_gar"] < 0.9 * errs["plain"]
+
+
+@pytest.mark.parametrize("t,k,dtype", [(1, 64, "f32"), (100, 200, "f32"), (1000, 384, "bf16"), (4096, 1024, "f32")])
+def test_hessian_accumulate(gpu_lib, t, k, dtype):
+    """H = X^T X over two batches (float32 accumulation on the GPU) against the float64 product of the same values:
+    each entry within 2e-5 of sqrt(H_ii H_jj) (about a hundred float32 roundings of terms no larger than that)."""
+    rng = np.random.default_rng([84, t, k])
+    x = calibration_inputs(rng, 2 * t, k).astype(np.float32)
+    if dtype == "bf16":
+        x = o.bf16_bits_to_f32(syn.f32_to_bf16_bits(x))
+        xd = torch.from_numpy(x).to(DEV).to(torch.bfloat16)
+    else:
+        xd = torch.from_numpy(x).to(DEV)
+    wide = torch.full((t, k + 7), 1e6, dtype=xd.dtype, device=DEV)
+    wide[:, :k] = xd[t:]
+    h = B.hessian_accumulate(xd[:t])
+    h = B.hessian_accumulate(wide[:, :k], h)                              # second batch with a row stride
+    got = host(h).astype(np.float64)
+    want = x.astype(np.float64).T @ x.astype(np.float64)
+    d = np.sqrt(np.diag(want))
+    assert np.all(np.abs(got - want) <= 2e-5 * np.outer(d, d) + 1e-30)
+    assert np.array_equal(got, got.T)                                     # the same products in the same order
