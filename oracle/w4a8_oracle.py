@@ -555,7 +555,15 @@ def hessian_inverse_factor(x, damp: float = 0.01) -> np.ndarray:
     Hessian restricted to the not-yet-quantized weights q, q+1, ..., divided by its diagonal entry -- the factor of
     Eq. 12 -- which is the reason Sec. 3.3 gives for using the Cholesky decomposition.  float64 throughout; x is [T, K]."""
     x = np.asarray(x, dtype=np.float64)
-    h = x.T @ x
+    return hessian_inverse_factor_from_h(x.T @ x, damp)
+
+
+def hessian_inverse_factor_from_h(h, damp: float = 0.01, perm=None) -> np.ndarray:
+    """hessian_inverse_factor for a Hessian that has already been formed: h is H = X^T X [K, K] (symmetric).  With
+    `perm` (Sec. 3.2) the factor is that of the reordered columns, i.e. of H[perm][:, perm]."""
+    h = np.asarray(h, dtype=np.float64)
+    if perm is not None:
+        h = h[np.ix_(perm, perm)]
     h = h + np.eye(h.shape[0]) * (damp * np.mean(np.diag(h)))
     hinv = np.linalg.inv(h)
     return np.linalg.cholesky(hinv).T.copy()                # lower factor L with H^-1 = L L^T; U = L^T

@@ -37,6 +37,28 @@ def test_factor_rows_are_the_update_coefficients_of_eq12():
         assert np.isclose(u[q, q] ** 2, sub[0, 0], rtol=1e-9)
 
 
+def test_factor_from_a_formed_hessian_by_another_route():
+    """H^-1 = U^T U with U upper triangular and a positive diagonal has one solution.  A route that never inverts H:
+    the lower Cholesky factor L of the index-reversed dampened Hessian gives H = R R^T with R = (L reversed) upper
+    triangular, and U = R^-1.  With a permutation the Hessian is that of the reordered columns."""
+    rng = np.random.default_rng(74)
+    k = 24
+    x = correlated_inputs(rng, 200, k)
+    h = x.T @ x
+    perm = rng.permutation(k)
+    for p in (None, perm):
+        u = o.hessian_inverse_factor_from_h(h, damp=0.02, perm=p)
+        hp = h if p is None else h[p][:, p]
+        hd = hp + np.eye(k) * 0.02 * np.trace(hp) / k
+        low = np.linalg.cholesky(hd[::-1, ::-1])
+        r = low[::-1, ::-1]
+        assert np.allclose(r, np.triu(r)) and np.allclose(r @ r.T, hd, rtol=1e-12)
+        assert np.allclose(u, np.linalg.inv(r), rtol=1e-8, atol=1e-12)
+        assert np.all(np.diag(u) > 0) and np.allclose(u, np.triu(u))
+        assert np.allclose(u.T @ u @ hd, np.eye(k), atol=1e-8)
+    assert np.array_equal(o.hessian_inverse_factor(x, 0.02), o.hessian_inverse_factor_from_h(h, 0.02))
+
+
 def test_without_interactions_dpq_is_plain_double_quantization():
     """With U = I no error reaches another weight, and Alg. 1 reduces to its quantization steps alone: FP8 rounding
     (Eq. 7) followed by the asymmetric quantizer of Eq. 8-9 on the FP8 values -- the oracle's separately pinned
