@@ -343,8 +343,7 @@ def calibration(dev):
     """Offline calibration on one Llama-3-8B-shaped layer (the O projection, 4096 x 4096): Group-Aware Reordering and
     DPQ (Alg. 1) timed on the GPU, and the layer error of the calibrated weights against the same double quantization
     without error compensation, both run through packing and the literal inference layer on 512 calibration tokens.
-    The Hessian comes from w4a8_hessian_accumulate; its dampening and Cholesky factors are dense linear algebra done with
-    torch (float64)."""
+    The Hessian comes from w4a8_hessian_accumulate, the factor U of Eq. 12 from w4a8_hessian_inverse_factor."""
     n = k = 4096
     t = 8192
     rng = syn.rng_for(9, n, k)
@@ -362,15 +361,21 @@ def calibration(dev):
     t1.record()
     torch.cuda.synchronize()
     hessian_ms = t0.elapsed_time(t1)
-    h = h32.double()
-    perm = B.gar_permutation(torch.diagonal(h).float().contiguous(), G)
-    hp = h[perm.long()][:, perm.long()]
-    hp = hp + torch.eye(k, device=dev, dtype=torch.float64) * (0.01 * torch.diagonal(hp).mean())
-    u = torch.linalg.cholesky(torch.cholesky_inverse(torch.linalg.cholesky(hp)), upper=True).float().contiguous()
+    h_diag = torch.diagonal(h32).contiguous()
+    perm = B.gar_permutation(h_diag, G)
+    B.hessian_inverse_factor(h32, 0.01, perm)                            # untimed first run
+    torch.cuda.synchronize()
+    t0.record()
+    u, info = B.hessian_inverse_factor(h32, 0.01, perm)
+    t1.record()
+    torch.cuda.synchronize()
+    factor_ms = t0.elapsed_time(t1)
+    if int(info.item()) != 0:
+        raise RuntimeError(f"calibration: the dampened Hessian is not positive definite (info = {int(info.item())})")
     B.dpq_calibrate(w, u, s_w, G, perm)                                  # untimed first run
     torch.cuda.synchronize()
     t0.record()
-    perm = B.gar_permutation(torch.diagonal(h).float().contiguous(), G)
+    perm = B.gar_permutation(h_diag, G)
     cal = B.dpq_calibrate(w, u, s_w, G, perm)
     t1.record()
     torch.cuda.synchronize()
@@ -383,8 +388,9 @@ def calibration(dev):
         packed, params = B.pack_weights_asym(codes, G, scales, zeros)
         y = B.linear_asym_two_level(rows, s_x, packed, params, s_w, n, G, out_dtype=torch.float32)
         err[name] = float(((y.double() - ref) ** 2).sum())
-    return {"metric": "Hessian X^T X, then GAR + DPQ (Alg. 1), on a 4096 x 4096 layer with 8192 calibration tokens",
+    return {"metric": "Hessian X^T X, its factor U, then GAR + DPQ (Alg. 1), on a 4096 x 4096 layer with 8192 calibration tokens",
             "hessian_ms": round(hessian_ms, 2), "hessian_tflops_f32": round(2.0 * t * k * k / hessian_ms / 1e9, 1),
+            "factor_ms": round(factor_ms, 2),
             "calibrate_ms": round(ms, 2),
             "layer_error_ratio_vs_uncompensated": round(err["dpq_gar"] / err["uncompensated"], 4)}
 

@@ -247,8 +247,19 @@ int w4a8_dequant_weights_asym_two_level(const uint8_t* packed_dev, const void* p
  *
  * w4a8_hessian_accumulate: H += X^T X for one batch of calibration activations (the Hessian of the layer-wise
  * objective, Eq. 5, App. A.2).  x_dev: X [T, K] float32 or bf16, row stride ldx elements; h_dev: float32 [K, K]
- * row-major, in/out (set to 0 before the first batch); float32 accumulation.  K <= 65536.  Dampening (Sec. 3.3) and the
- * Cholesky factorizations that lead from H to the factor U below are dense linear algebra left to a library.
+ * row-major, in/out (set to 0 before the first batch); float32 accumulation.  K <= 65536.
+ *
+ * w4a8_hessian_inverse_factor: dampening and Cholesky factorization (Sec. 3.3): from H to the matrix U that
+ * w4a8_dpq_calibrate takes.  H_d = P^T H P + damp * mean(diag H) * I, with P the reordering of perm_dev (Sec. 3.2;
+ * NULL: none), i.e. H_d[i, j] = H[perm[i], perm[j]] + ...; u_factor_dev receives float32 [K, K] row-major: the
+ * upper-triangular U with positive diagonal and H_d^-1 = U^T U, zeros below the diagonal.  Computed in float64 (a
+ * Cholesky factorization of the index-reversed H_d and the inverse of its factor; H_d^-1 itself is never formed).
+ *   h_dev          float32 [K, K], symmetric (not modified)
+ *   damp           the dampening fraction, >= 0 (GPTQ's customary 0.01)
+ *   workspace_dev  w4a8_hessian_factor_workspace_bytes(K) bytes, 16-byte aligned
+ *   info_dev       out, one int32: 0, or 1 + the index (counted from the END of the reordered columns) of the first
+ *                  pivot that was not positive -- H_d is then not positive definite and U holds no usable values
+ * K % 128 == 0, K <= 32768.
  *
  * w4a8_gar_permutation: Group-Aware Reordering (Sec. 3.2, App. A.3).  h_diag_dev: the K diagonal entries of the layer's
  * Hessian X^T X.  perm_dev receives K int32: position i of the reordered tensor holds original column perm[i]; columns
@@ -276,6 +287,9 @@ int w4a8_dequant_weights_asym_two_level(const uint8_t* packed_dev, const void* p
 int w4a8_hessian_accumulate(const void* x_dev, w4a8_dtype x_dtype, int64_t T, int64_t K, int64_t ldx, float* h_dev,
                             void* stream);
 int w4a8_gar_permutation(const float* h_diag_dev, int64_t K, int32_t group_size, int32_t* perm_dev, void* stream);
+size_t w4a8_hessian_factor_workspace_bytes(int64_t K);
+int w4a8_hessian_inverse_factor(const float* h_dev, int64_t K, double damp, const int32_t* perm_dev, void* workspace_dev,
+                                size_t workspace_bytes, float* u_factor_dev, int32_t* info_dev, void* stream);
 size_t w4a8_dpq_workspace_bytes(int64_t N, int64_t K);
 int w4a8_dpq_calibrate(const float* w_dev, const float* u_factor_dev, const float* w_scale_dev, int32_t per_channel,
                        const int32_t* perm_dev, int64_t N, int64_t K, int32_t group_size, uint8_t* codes_dev,

@@ -50,6 +50,8 @@ SIGNATURES = {
     "w4a8_hessian_accumulate": (_c_i32, [_c_vp, _c_i32, _c_i64, _c_i64, _c_i64, _c_vp, _c_vp]),
     "w4a8_gar_permutation": (_c_i32, [_c_vp, _c_i64, _c_i32, _c_vp, _c_vp]),
     "w4a8_dpq_workspace_bytes": (_c_sz, [_c_i64, _c_i64]),
+    "w4a8_hessian_factor_workspace_bytes": (_c_sz, [_c_i64]),
+    "w4a8_hessian_inverse_factor": (_c_i32, [_c_vp, _c_i64, ctypes.c_double, _c_vp, _c_vp, _c_sz, _c_vp, _c_vp, _c_vp]),
     "w4a8_dpq_calibrate": (_c_i32, [_c_vp, _c_vp, _c_vp, _c_i32, _c_vp, _c_i64, _c_i64, _c_i32, _c_vp, _c_vp, _c_vp, _c_vp,
                                     _c_sz, _c_vp]),
     "w4a8_silu_mul": (_c_i32, [_c_vp, _c_i64, _c_i64, _c_i64, _c_vp, _c_i64, _c_vp]),
@@ -355,6 +357,24 @@ def hessian_accumulate(x: torch.Tensor, h: torch.Tensor | None = None) -> torch.
     _check(lib().w4a8_hessian_accumulate(x.data_ptr(), _dtype_code(x), t, k, x.stride(0) if t > 1 else max(k, x.stride(0)),
                                          h.data_ptr(), _stream()), "w4a8_hessian_accumulate")
     return h
+
+
+def hessian_inverse_factor(h: torch.Tensor, damp: float = 0.01, perm: torch.Tensor | None = None):
+    """w4a8_hessian_inverse_factor: h float32 [K, K] -> (U float32 [K, K], info int32 [1]); info stays on the device
+    (0 = success), so the call does not synchronize."""
+    k = h.shape[0]
+    assert h.dtype == torch.float32 and h.is_contiguous() and tuple(h.shape) == (k, k)
+    assert perm is None or (perm.dtype == torch.int32 and perm.is_contiguous() and perm.numel() == k)
+    nbytes = lib().w4a8_hessian_factor_workspace_bytes(k)
+    if nbytes == 0:
+        raise ValueError(f"w4a8_hessian_inverse_factor: unsupported K = {k}")
+    ws = torch.empty(nbytes, dtype=torch.uint8, device=h.device)
+    u = torch.empty((k, k), dtype=torch.float32, device=h.device)
+    info = torch.empty(1, dtype=torch.int32, device=h.device)
+    _check(lib().w4a8_hessian_inverse_factor(h.data_ptr(), k, float(damp), perm.data_ptr() if perm is not None else None,
+                                             ws.data_ptr(), nbytes, u.data_ptr(), info.data_ptr(), _stream()),
+           "w4a8_hessian_inverse_factor")
+    return u, info
 
 
 def gar_permutation(h_diag: torch.Tensor, group_size: int) -> torch.Tensor:

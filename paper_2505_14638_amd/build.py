@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libw4a8.so")
 SOURCES = ["api.hip", "quantize_act.hip", "pack_weights.hip", "linear_canonical.hip", "linear_skinny.hip",
-           "linear_mfma.hip", "silu_mul.hip", "probe.hip", "dpq.hip"]
+           "linear_mfma.hip", "silu_mul.hip", "probe.hip", "dpq.hip", "hessian_factor.hip"]
 # packed fp32 instructions are switched off for all device code (scalar fp32 only)
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]

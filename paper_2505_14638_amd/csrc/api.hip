@@ -337,6 +337,24 @@ int w4a8_gar_permutation(const float* h_diag_dev, int64_t K, int32_t group_size,
     return launch_gar_permutation(h_diag_dev, K, group_size, perm_dev, static_cast<hipStream_t>(stream));
 }
 
+size_t w4a8_hessian_factor_workspace_bytes(int64_t K) {
+    if (K < 128 || K % 128 != 0 || K > 32768) return 0;
+    return hessian_factor_workspace_bytes(K);
+}
+
+int w4a8_hessian_inverse_factor(const float* h_dev, int64_t K, double damp, const int32_t* perm_dev, void* workspace_dev,
+                                size_t workspace_bytes, float* u_factor_dev, int32_t* info_dev, void* stream) {
+    if (K < 128 || K % 128 != 0 || K > 32768) return W4A8_ERR_SHAPE;
+    if (!(damp >= 0.0) || !(damp <= 1.0e6)) return W4A8_ERR_SHAPE;
+    if (!h_dev || !workspace_dev || !u_factor_dev || !info_dev) return W4A8_ERR_NULL;
+    if (reinterpret_cast<uintptr_t>(h_dev) % 4 || reinterpret_cast<uintptr_t>(u_factor_dev) % 4 ||
+        reinterpret_cast<uintptr_t>(perm_dev) % 4 || reinterpret_cast<uintptr_t>(info_dev) % 4 || !aligned16(workspace_dev))
+        return W4A8_ERR_ALIGN;
+    if (workspace_bytes < w4a8_hessian_factor_workspace_bytes(K)) return W4A8_ERR_WORKSPACE;
+    return launch_hessian_inverse_factor(h_dev, K, damp, perm_dev, workspace_dev, u_factor_dev, info_dev,
+                                         static_cast<hipStream_t>(stream));
+}
+
 size_t w4a8_dpq_workspace_bytes(int64_t N, int64_t K) {
     if (check_nk(N, K, W4A8_LAYOUT_TILED) != W4A8_OK) return 0;
     return (size_t)(N * K + N * 128) * sizeof(float);

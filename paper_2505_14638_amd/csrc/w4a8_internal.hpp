@@ -77,6 +77,10 @@ int launch_linear_mfma_tiled(const uint8_t* x8, int64_t M, int64_t K, int64_t ld
 // q_scale != nullptr: h is E4M3 bytes, the bf16 result quantized with *q_scale (Eq. 13)
 int launch_hessian_accumulate(const void* x, w4a8_dtype dt, int64_t T, int64_t K, int64_t ldx, float* h, hipStream_t st);
 int launch_gar_permutation(const float* hdiag, int64_t K, int32_t G, int32_t* perm, hipStream_t st);
+// U = upper Cholesky factor of the inverse dampened (and reordered) Hessian; workspace: hessian_factor_workspace_bytes(K)
+size_t hessian_factor_workspace_bytes(int64_t K);
+int launch_hessian_inverse_factor(const float* h, int64_t K, double damp, const int32_t* perm, void* workspace, float* u,
+                                  int32_t* info, hipStream_t st);
 // workspace: (N * K + N * 128) floats
 int launch_dpq_calibrate(const float* w, const float* u, const float* s_w, int per_channel, const int32_t* perm,
                          int64_t N, int64_t K, int32_t G, uint8_t* codes, float* scales, uint8_t* zeros, void* workspace,

@@ -211,6 +211,15 @@ def test_calibration_validation(L):
     assert gp(0, 256, 128, P, None) == 1 and gp(P, 256, 128, 0, None) == 1
     assert gp(P, 200, 200, P, None) == 5 and gp(P, 256, 64, P, None) == 3
     assert L.w4a8_dpq_workspace_bytes(10, 256) == (10 * 256 + 10 * 128) * 4
+    hf = L.w4a8_hessian_inverse_factor
+    nb = L.w4a8_hessian_factor_workspace_bytes(256)
+    assert nb == (2 * 256 * 256 + 256 * 64 + 2) * 8 and L.w4a8_hessian_factor_workspace_bytes(200) == 0
+    # h, K, damp, perm, workspace, bytes, u, info, stream
+    assert hf(0, 256, 0.01, 0, P, nb, P, P, None) == 1 and hf(P, 256, 0.01, 0, P, nb, P, 0, None) == 1
+    assert hf(P, 200, 0.01, 0, P, nb, P, P, None) == 2 and hf(P, 256, -1.0, 0, P, nb, P, P, None) == 2
+    assert hf(P, 256, float("nan"), 0, P, nb, P, P, None) == 2
+    assert hf(P, 256, 0.01, P + 2, P, nb, P, P, None) == 6 and hf(P, 256, 0.01, 0, P + 8, nb, P, P, None) == 6
+    assert hf(P, 256, 0.01, 0, P, nb - 1, P, P, None) == 7
     f = L.w4a8_dpq_calibrate
     # w, u, s_w, per_channel, perm, N, K, G, codes, scales, zeros, workspace, bytes, stream
     ok = L.w4a8_dpq_workspace_bytes(16, 256)

@@ -114,3 +114,65 @@ def test_hessian_accumulate(gpu_lib, t, k, dtype):
     d = np.sqrt(np.diag(want))
     assert np.all(np.abs(got - want) <= 2e-5 * np.outer(d, d) + 1e-30)
     assert np.array_equal(got, got.T)                                     # the same products in the same order
+
+
+@pytest.mark.parametrize("k,reorder,damp", [(128, False, 0.01), (512, True, 0.01), (1024, True, 0.05), (1152, False, 0.01)])
+def test_hessian_inverse_factor(gpu_lib, k, reorder, damp):
+    """Dampening + Cholesky (Sec. 3.3) on the GPU (float64 inside) against the oracle's float64 route through the
+    explicit inverse, from the same float32 Hessian: float32 rounding of the result plus a conditioning allowance."""
+    rng = np.random.default_rng([85, k])
+    x = calibration_inputs(rng, 2 * k, k)
+    h = (x.T @ x).astype(np.float32)
+    h = np.maximum(h, h.T)                                                # symmetric after the rounding to float32
+    perm = o.gar_permutation(np.diag(h), 128) if reorder else None
+    want = o.hessian_inverse_factor_from_h(h, damp, perm)
+    u, info = B.hessian_inverse_factor(dev(h), damp, dev(perm.astype(np.int32)) if reorder else None)
+    got = host(u).astype(np.float64)
+    assert int(host(info)[0]) == 0
+    assert np.all(np.tril(got, -1) == 0.0) and np.all(np.diag(got) > 0)
+    assert np.all(np.abs(got - want) <= 2.0 ** -23 * np.abs(want) + 1e-9 * np.abs(want).max())
+    hd = (h if perm is None else h[perm][:, perm]).astype(np.float64)
+    hd = hd + np.eye(k) * damp * np.trace(hd) / k
+    assert np.abs(got.T @ got @ hd - np.eye(k)).max() < 1e-3            # float32 entries of U: ~cond * 2^-24
+
+
+def test_hessian_inverse_factor_reports_a_matrix_that_is_not_positive_definite(gpu_lib):
+    k = 256
+    h = np.eye(k, dtype=np.float32)
+    h[100, 100] = -1.0
+    _, info = B.hessian_inverse_factor(dev(h), 0.0)
+    assert int(host(info)[0]) == k - 100                                  # 1 + index counted from the end: 155 + 1
+
+
+def test_calibration_pipeline_on_the_gpu(gpu_lib):
+    """Activations -> Hessian -> reordering -> factor -> Alg. 1, every step on the GPU, against the oracle run on the
+    GPU's float32 Hessian: the permutation is identical; the factor agrees to float32 rounding, so all but a few codes
+    (a decision next to a tie can flip, and its compensation moves a few later ones) are identical and the layer error
+    is the same."""
+    rng = np.random.default_rng(86)
+    n, k, g, t = 64, 512, 128, 2048
+    w = syn.make_weights(rng, n, k)
+    x = calibration_inputs(rng, t, k).astype(np.float32)
+    s_w = (np.abs(w).max(axis=1) / np.float32(448.0)).astype(np.float32)
+    h_d = B.hessian_accumulate(dev(x))
+    perm_d = B.gar_permutation(torch.diagonal(h_d).contiguous(), g)
+    u_d, info = B.hessian_inverse_factor(h_d, 0.01, perm_d)
+    codes, scales, zeros = (host(a) for a in B.dpq_calibrate(dev(w), u_d, dev(s_w), g, perm_d))
+    assert int(host(info)[0]) == 0
+    h = host(h_d)
+    perm = o.gar_permutation(np.diag(h), g)
+    assert np.array_equal(host(perm_d), perm)
+    u = o.hessian_inverse_factor_from_h(h, 0.01, perm).astype(np.float32)
+    want = o.dpq_quantize(w, u, s_w, g, perm=perm)
+    same = float(np.mean(codes == want[0]))
+    print(f"  codes identical to the oracle's: {same:.5f}", flush=True)
+    assert same > 0.995 and np.mean(zeros == want[2]) > 0.99
+
+    def layer_error(c, s, z):
+        _, w8 = o.linear_ref_asym_paper_literal(np.zeros((1, k), np.uint8), 1.0, c, z, s, np.ones(n), g)
+        return float(np.linalg.norm((w.astype(np.float64) - o.e4m3_decode(w8) * s_w.astype(np.float64)[:, None]) @ x.T.astype(np.float64)) ** 2)
+    e_gpu, e_ref = layer_error(codes, scales, zeros), layer_error(*want)
+    plain = o.dpq_quantize(w, np.eye(k, dtype=np.float32), s_w, g)
+    e_plain = layer_error(*plain)
+    print(f"  layer error: GPU pipeline {e_gpu:.4e}, oracle {e_ref:.4e}, uncompensated {e_plain:.4e}", flush=True)
+    assert abs(e_gpu - e_ref) < 0.02 * e_ref and e_gpu < 0.9 * e_plain
