@@ -173,6 +173,29 @@ def measured_ceilings(dev):
     return round(gbs, 1), round(copy_gbs, 1), round(tfl, 1)
 
 
+def library_fp8_gemm_seconds(x8, n, reps):
+    """Seconds per call of the vendor library's FP8 GEMM (through torch._scaled_mm) for activations x8 [M, K] (E4M3 bytes)
+    against random FP8 weights [N, K], bf16 output; None where this torch build has no such GEMM.  A measured reference
+    for what a dense FP8 contraction reaches on this machine -- it is not part of the W4A8 path."""
+    try:
+        a = x8.view(torch.float8_e4m3fn)
+        w = torch.randint(0, 120, (n, x8.shape[1]), dtype=torch.uint8, device=x8.device).view(torch.float8_e4m3fn)
+        one = torch.ones((), dtype=torch.float32, device=x8.device)
+        run = lambda: torch._scaled_mm(a, w.t(), scale_a=one, scale_b=one, out_dtype=torch.bfloat16)
+        for _ in range(max(2, reps)):
+            run()
+        torch.cuda.synchronize()
+        t0, t1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        t0.record()
+        for _ in range(reps):
+            run()
+        t1.record()
+        torch.cuda.synchronize()
+        return t0.elapsed_time(t1) * 1e-3 / reps
+    except Exception:                                                    # noqa: BLE001 - any refusal means "not available"
+        return None
+
+
 def plain_read_same_sizes(dev, sizes, copies, steps, warmup):
     """What a kernel that only reads reaches on buffers of the decode sweep's sizes: the library's streaming-read probe
     launched once per case on `sizes[j]` bytes, the same number of launches per HIP graph as the linear kernels, over
@@ -469,6 +492,7 @@ def main():
     if not args.no_prefill:
         pcfg = syn.CONFIGS[3]
         per_shape, tot_flop, tot_sec, tot_sec_p2, tot_bytes = [], 0.0, 0.0, 0.0, 0
+        tot_sec_lib = 0.0                                                # None once the library GEMM is unavailable
         for L in layers:
             # the same codes with every group scale rounded up to a power of two, for the block-scaled variant
             p2 = [torch.exp2(torch.ceil(torch.log2(sc.abs()))) for (_, sc) in L.sets]
@@ -506,6 +530,11 @@ def main():
                 per_shape.append({"M": m, "K": L.k, "N": L.n, "us": round(s * 1e6, 2), "tflops": round(flop / s / 1e12, 1)})
                 if not args.no_pow2:
                     per_shape[-1]["pow2_tflops"] = round(flop / s2 / 1e12, 1)
+                if tot_sec_lib is not None and not args.no_pow2:
+                    s3 = library_fp8_gemm_seconds(c.x8, L.n, reps)
+                    tot_sec_lib = None if s3 is None else tot_sec_lib + s3
+                    if s3 is not None:
+                        per_shape[-1]["library_fp8_gemm_tflops"] = round(flop / s3 / 1e12, 1)
                 tot_flop += flop
                 tot_sec += s
                 tot_sec_p2 += 0.0 if args.no_pow2 else s2
@@ -526,6 +555,14 @@ def main():
                                                        "to powers of two and applied by the block-scaled MFMA)",
                                              "value": round(tfl2, 1), "unit": "TFLOP/s",
                                              "frac": round(tfl2 / FP8_PEAK_TFLOPS, 4)}
+
+        if not args.no_pow2 and tot_sec_lib:
+            tfl3 = tot_flop / tot_sec_lib / 1e12
+            result["prefill"]["library_fp8_gemm"] = {
+                "metric": "context, not the product path: the vendor library's dense FP8 x FP8 GEMM (torch._scaled_mm) on "
+                          "the same shapes and activations, weights already expanded to FP8 in HBM, one output scale",
+                "value": round(tfl3, 1), "unit": "TFLOP/s", "w4a8_linear_frac_of_it": round(tfl / tfl3, 4),
+                "w4a8_linear_pow2_frac_of_it": round(tfl2 / tfl3, 4)}
 
     if not args.prefill_only:
         hbm, copy, mfma = measured_ceilings(dev)
