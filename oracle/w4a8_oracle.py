@@ -582,7 +582,7 @@ def gar_permutation(h_diag, group_size: int) -> np.ndarray:
     return (order[:, None] * group_size + inside[order]).reshape(k).astype(np.int64)
 
 
-def dpq_quantize(w, u_factor, s_w, group_size: int, perm=None):
+def dpq_quantize(w, u_factor, s_w, group_size: int, perm=None, mse_grid: int = 0, mse_max_shrink: float = 0.8):
     """Dual Precision Quantization, Alg. 1, for all rows at once.  `w` is W16 [N, K]; `u_factor` the matrix of
     hessian_inverse_factor for the (reordered, if `perm` is given) columns; `s_w` the BF16 -> FP8 scale of Eq. 6, one
     per row or a single one.  Columns are visited in the order perm[0], perm[1], ... (GAR; identity when perm is None)
@@ -599,6 +599,12 @@ def dpq_quantize(w, u_factor, s_w, group_size: int, perm=None):
         w_hat  = w8_hat * s_w                                     Eq. 11
         err    = (w - w_hat) / U[q, q]
         w_v    = w_v - err * U[q, v]  for every later column v    Eq. 12
+    With mse_grid > 1 the group parameters come from the search of Sec. 3.3 (the paper names the search, not its grid;
+    this is the reading taken here): candidate i = 0 .. mse_grid - 1 shrinks the range to p_i * [min W8, max W8],
+    p_i = 1 - i * (mse_max_shrink / mse_grid), derives (s, z) from it as above, and is scored by
+    sum_k (w8_k - w8_hat_k)^2 over the group's current weights, w8_hat being what inference will see (Eq. 9 with its
+    clipping to [0, 15], then Eq. 10); the sum runs over k in visiting order in float32, and the first candidate with
+    the smallest score wins.  Candidate 0 is Eq. 8 itself.
     Returns (codes uint8 [N, K], scales float32 [N, K/G] in the FP8 domain, zero-points uint8 [N, K/G])."""
     w = np.array(w, dtype=np.float32, copy=True)
     n, k = w.shape
@@ -614,14 +620,33 @@ def dpq_quantize(w, u_factor, s_w, group_size: int, perm=None):
     def to_fp8_value(t):
         return e4m3_decode(e4m3_encode(t)).astype(np.float32)
 
+    def group_params(lo, hi):
+        span = (hi - lo).astype(np.float32)
+        s_ = np.where(span == 0, np.float32(1.0), (span / np.float32(15.0)).astype(np.float32)).astype(np.float32)
+        return s_, np.clip(np.rint(((-lo) / s_).astype(np.float32)), 0, 15).astype(np.float32)
+
     for g in range(k // group_size):
         q0 = g * group_size
         w8g = to_fp8_value((w[:, q0:q0 + group_size] / s_w[:, None]).astype(np.float32))
         lo = np.minimum(w8g.min(axis=1), np.float32(0.0)).astype(np.float32)
         hi = np.maximum(w8g.max(axis=1), np.float32(0.0)).astype(np.float32)
-        span = (hi - lo).astype(np.float32)
-        s = np.where(span == 0, np.float32(1.0), (span / np.float32(15.0)).astype(np.float32)).astype(np.float32)
-        z = np.clip(np.rint(((-lo) / s).astype(np.float32)), 0, 15).astype(np.float32)
+        s, z = group_params(lo, hi)
+        if mse_grid > 1:
+            shrink_step = np.float32(np.float32(mse_max_shrink) / np.float32(mse_grid))
+            best = np.full(n, np.inf, dtype=np.float32)
+            for i in range(mse_grid):
+                p_i = np.float32(np.float32(1.0) - np.float32(np.float32(i) * shrink_step))
+                s_i, z_i = group_params((p_i * lo).astype(np.float32), (p_i * hi).astype(np.float32))
+                score = np.zeros(n, dtype=np.float32)
+                for j in range(group_size):
+                    w8 = w8g[:, j]
+                    uq = np.clip(np.rint(((w8 / s_i).astype(np.float32) + z_i).astype(np.float32)), 0, 15).astype(np.float32)
+                    d = (w8 - to_fp8_value(((uq - z_i).astype(np.float32) * s_i).astype(np.float32))).astype(np.float32)
+                    score = (score + (d * d).astype(np.float32)).astype(np.float32)
+                better = score < best
+                best = np.where(better, score, best)
+                s = np.where(better, s_i, s).astype(np.float32)
+                z = np.where(better, z_i, z).astype(np.float32)
         for q in range(q0, q0 + group_size):
             wq = w[:, q].copy()
             w8 = to_fp8_value((wq / s_w).astype(np.float32))

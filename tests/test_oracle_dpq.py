@@ -162,3 +162,77 @@ def test_gar_permutation_hand_example_and_structure():
     assert np.all(blocks // 128 == (blocks[:, :1] // 128))                # every visited group is one original group
     assert np.all(np.diff(d[blocks], axis=1) <= 0)                        # descending inside a group
     assert np.all(np.diff(d[blocks[:, 0]]) <= 0)                          # groups by descending maximum
+
+
+def group_mse(w, codes, scales, zeros, s_w, g):
+    """Per (row, group): sum (W8 - W8_hat)^2 with W8 = the FP8 values of W / s_w (Eq. 7) and W8_hat what inference
+    computes from the stored codes (Eq. 10), through the separately pinned literal dequantization."""
+    n, k = w.shape
+    _, w8_hat = o.linear_ref_asym_paper_literal(np.zeros((1, k), np.uint8), 1.0, codes, zeros, scales, np.ones(n), g)
+    w8 = o.e4m3_decode(o.e4m3_encode((w / np.asarray(s_w, np.float32).reshape(-1, 1)).astype(np.float32)))
+    d = (w8 - o.e4m3_decode(w8_hat)) ** 2
+    return d.reshape(n, k // g, g).sum(axis=2)
+
+
+def test_mse_scale_search_never_raises_a_groups_own_error_and_helps_with_outliers():
+    """Sec. 3.3's search, with U = I so that groups do not interact: the parameters it picks give every (row, group) an
+    error no larger than Eq. 8's own range does (candidate 0 is that range), strictly smaller where a lone outlier
+    stretches the range; without a grid it is Eq. 8."""
+    rng = np.random.default_rng(75)
+    n, k, g = 12, 256, 64
+    w = syn.make_weights(rng, n, k)
+    w[np.arange(n), rng.integers(0, k, n)] *= 6.0                          # one outlier per row
+    s_w = (np.abs(w).max(axis=1) / np.float32(448.0)).astype(np.float32)
+    eye = np.eye(k, dtype=np.float32)
+    plain = o.dpq_quantize(w, eye, s_w, g)
+    for same in (o.dpq_quantize(w, eye, s_w, g, mse_grid=0), o.dpq_quantize(w, eye, s_w, g, mse_grid=1)):
+        assert all(np.array_equal(a, b) for a, b in zip(plain, same))
+    searched = o.dpq_quantize(w, eye, s_w, g, mse_grid=40, mse_max_shrink=0.8)
+    e0, e1 = group_mse(w, *plain, s_w, g), group_mse(w, *searched, s_w, g)
+    assert np.all(e1 <= e0 * (1 + 1e-6))
+    assert np.mean(e1 < 0.9 * e0) > 0.2                                   # the groups that hold an outlier, at least
+    assert np.all(searched[1] <= plain[1])                                # shrunk ranges only
+
+
+def test_mse_scale_search_picks_the_best_candidate_by_brute_force():
+    """Every candidate range of the grid, scored independently in float64 from the definition (shrink the range, Eq. 8,
+    Eq. 9 with clipping, Eq. 10 on the FP8 grid): the oracle's choice has the smallest score, and is the first such."""
+    rng = np.random.default_rng(76)
+    n, k, g, grid, shrink = 12, 64, 32, 16, 0.6
+    w = (rng.standard_normal((n, k)) * 0.02).astype(np.float32)
+    w[:, 5] *= 4.0
+    s_w = np.float32(2.0 ** -11)
+    _, scales, zeros = o.dpq_quantize(w, np.eye(k, dtype=np.float32), s_w, g, mse_grid=grid, mse_max_shrink=shrink)
+    w8 = o.e4m3_decode(o.e4m3_encode((w / s_w).astype(np.float32)))
+    checked = 0
+    for r in range(n):
+        for gi in range(k // g):
+            v = w8[r, gi * g:(gi + 1) * g]
+            lo, hi = min(v.min(), 0.0), max(v.max(), 0.0)
+            zr = -lo * 15.0 / (hi - lo)                                   # the zero-point before rounding, the same for every candidate
+            if abs(zr - np.floor(zr) - 0.5) < 1e-3:
+                continue                                                  # a tie that float32 and float64 may round apart
+            scores, params = [], []
+            for i in range(grid):
+                p = 1.0 - i * shrink / grid
+                s = (p * hi - p * lo) / 15.0
+                z = float(np.clip(np.rint(-p * lo / s), 0, 15))
+                u = np.clip(np.rint(v / s + z), 0, 15)
+                back = o.e4m3_decode(o.e4m3_encode(((u - z) * s).astype(np.float32)))
+                scores.append(float(np.sum((v - back) ** 2)))
+                params.append((s, z))
+            order = np.argsort(scores, kind="stable")
+            if scores[order[1]] - scores[order[0]] < 1e-4 * max(scores[order[0]], 1e-12):
+                continue                                                  # float32 and float64 scores may rank a near-tie apart
+            s_best, z_best = params[order[0]]
+            assert np.isclose(scales[r, gi], s_best, rtol=1e-6) and zeros[r, gi] == z_best
+            checked += 1
+    assert checked >= 8
+
+
+def test_mse_scale_search_keeps_a_range_that_is_already_exact():
+    """Weights whose FP8 values are the sixteen levels 0..15 of a unit grid: Eq. 8's own range reproduces them exactly
+    (score 0), and the first candidate with the smallest score is that one -- s = 1, z = 0."""
+    w = np.tile(np.arange(16, dtype=np.float32), (3, 8))                   # [3, 128], values exact in E4M3
+    _, scales, zeros = o.dpq_quantize(w, np.eye(128, dtype=np.float32), np.float32(1.0), 128, mse_grid=25)
+    assert np.all(scales == 1.0) and np.all(zeros == 0)
