@@ -403,11 +403,16 @@ def calibration(dev):
     t1.record()
     torch.cuda.synchronize()
     ms = t0.elapsed_time(t1)
+    t0.record()
+    cal_mse = B.dpq_calibrate(w, u, s_w, G, perm, mse_grid=20, mse_max_shrink=0.8)   # with the scale search of Sec. 3.3
+    t1.record()
+    torch.cuda.synchronize()
+    ms_mse = t0.elapsed_time(t1)
     plain = B.dpq_calibrate(w, torch.eye(k, device=dev), s_w, G)         # identity factor: no error reaches another weight
     rows = x8[:512]
     ref = (x[:512].double() @ w.double().T)
     err = {}
-    for name, (codes, scales, zeros) in {"dpq_gar": cal, "uncompensated": plain}.items():
+    for name, (codes, scales, zeros) in {"dpq_gar": cal, "dpq_gar_mse": cal_mse, "uncompensated": plain}.items():
         packed, params = B.pack_weights_asym(codes, G, scales, zeros)
         y = B.linear_asym_two_level(rows, s_x, packed, params, s_w, n, G, out_dtype=torch.float32)
         err[name] = float(((y.double() - ref) ** 2).sum())
@@ -415,7 +420,9 @@ def calibration(dev):
             "hessian_ms": round(hessian_ms, 2), "hessian_tflops_f32": round(2.0 * t * k * k / hessian_ms / 1e9, 1),
             "factor_ms": round(factor_ms, 2),
             "calibrate_ms": round(ms, 2),
-            "layer_error_ratio_vs_uncompensated": round(err["dpq_gar"] / err["uncompensated"], 4)}
+            "calibrate_with_scale_search_ms": round(ms_mse, 2),
+            "layer_error_ratio_vs_uncompensated": round(err["dpq_gar"] / err["uncompensated"], 4),
+            "layer_error_ratio_with_scale_search": round(err["dpq_gar_mse"] / err["uncompensated"], 4)}
 
 
 def main():

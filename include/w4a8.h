@@ -281,8 +281,8 @@ int w4a8_dequant_weights_asym_two_level(const uint8_t* packed_dev, const void* p
  * per weight, in visiting order: w8 = val(nearest_E4M3(w / s_w)) (Eq. 7); u = clamp(round(w8 / s + z), 0, 15) (Eq. 9);
  * w8_hat = val(nearest_E4M3((u - z) * s)) (Eq. 10, on the grid, as inference computes it); w_hat = w8_hat * s_w
  * (Eq. 11); err = (w - w_hat) / U[q,q]; every later weight w_v of the row becomes w_v - err * U[q,v] (Eq. 12).  Each
- * step is one float32 operation, so the result is reproducible bit for bit.  The MSE search over scales that Sec. 3.3
- * mentions is not included (the paper gives no search grid).  K % 128 == 0, group_size % 128 == 0.
+ * step is one float32 operation, so the result is reproducible bit for bit.  The search over scales that Sec. 3.3
+ * mentions is in w4a8_dpq_calibrate_mse.  K % 128 == 0, group_size % 128 == 0.
  */
 int w4a8_hessian_accumulate(const void* x_dev, w4a8_dtype x_dtype, int64_t T, int64_t K, int64_t ldx, float* h_dev,
                             void* stream);
@@ -294,6 +294,17 @@ size_t w4a8_dpq_workspace_bytes(int64_t N, int64_t K);
 int w4a8_dpq_calibrate(const float* w_dev, const float* u_factor_dev, const float* w_scale_dev, int32_t per_channel,
                        const int32_t* perm_dev, int64_t N, int64_t K, int32_t group_size, uint8_t* codes_dev,
                        float* scales8_dev, uint8_t* zeros_dev, void* workspace_dev, size_t workspace_bytes, void* stream);
+/* w4a8_dpq_calibrate with the per-group scale search of Sec. 3.3 (the paper names the search, not its grid; this is
+ * the reading built here).  At the start of a group, candidate i = 0 .. mse_grid - 1 shrinks the range of Eq. 8 to
+ * p_i * [min W8, max W8], p_i = 1 - i * (mse_max_shrink / mse_grid) (float32), derives (s, z) from it, and is scored by
+ * sum_k (w8_k - w8_hat_k)^2 over the group's current weights -- w8_hat as inference will see it (Eq. 9 with its
+ * clipping to [0, 15], then Eq. 10) -- summed in float32 in visiting order; the first candidate with the smallest score
+ * gives the group's parameters.  Candidate 0 is Eq. 8 itself; mse_grid <= 1 is w4a8_dpq_calibrate.
+ * 0 <= mse_grid <= 1024, 0 <= mse_max_shrink < 1. */
+int w4a8_dpq_calibrate_mse(const float* w_dev, const float* u_factor_dev, const float* w_scale_dev, int32_t per_channel,
+                           const int32_t* perm_dev, int64_t N, int64_t K, int32_t group_size, int32_t mse_grid,
+                           float mse_max_shrink, uint8_t* codes_dev, float* scales8_dev, uint8_t* zeros_dev,
+                           void* workspace_dev, size_t workspace_bytes, void* stream);
 
 /*
  * Elementwise step of the decoder-block linear stack (all linear layers of a block are quantized, Sec. 4.1;

@@ -54,6 +54,8 @@ SIGNATURES = {
     "w4a8_hessian_inverse_factor": (_c_i32, [_c_vp, _c_i64, ctypes.c_double, _c_vp, _c_vp, _c_sz, _c_vp, _c_vp, _c_vp]),
     "w4a8_dpq_calibrate": (_c_i32, [_c_vp, _c_vp, _c_vp, _c_i32, _c_vp, _c_i64, _c_i64, _c_i32, _c_vp, _c_vp, _c_vp, _c_vp,
                                     _c_sz, _c_vp]),
+    "w4a8_dpq_calibrate_mse": (_c_i32, [_c_vp, _c_vp, _c_vp, _c_i32, _c_vp, _c_i64, _c_i64, _c_i32, _c_i32, ctypes.c_float,
+                                        _c_vp, _c_vp, _c_vp, _c_vp, _c_sz, _c_vp]),
     "w4a8_silu_mul": (_c_i32, [_c_vp, _c_i64, _c_i64, _c_i64, _c_vp, _c_i64, _c_vp]),
     "w4a8_linear_fp8_out": (_c_i32, [_c_vp, _c_i64, _c_i64, _c_i64, _c_vp, _c_vp, _c_vp, _c_i64, _c_i32, _c_vp, _c_vp,
                                      _c_i64, _c_vp]),
@@ -387,9 +389,10 @@ def gar_permutation(h_diag: torch.Tensor, group_size: int) -> torch.Tensor:
 
 
 def dpq_calibrate(w: torch.Tensor, u_factor: torch.Tensor, w_scale: torch.Tensor, group_size: int,
-                  perm: torch.Tensor | None = None):
-    """w4a8_dpq_calibrate.  w float32 [N, K]; u_factor float32 [K, K] (of the reordered columns when perm is given);
-    w_scale float32 with N elements or one.  Returns (codes uint8 [N, K], scales8 float32 [N, K/G], zeros uint8 [N, K/G])."""
+                  perm: torch.Tensor | None = None, mse_grid: int = 0, mse_max_shrink: float = 0.8):
+    """w4a8_dpq_calibrate (mse_grid <= 1) / w4a8_dpq_calibrate_mse.  w float32 [N, K]; u_factor float32 [K, K] (of the
+    reordered columns when perm is given); w_scale float32 with N elements or one.  Returns (codes uint8 [N, K],
+    scales8 float32 [N, K/G], zeros uint8 [N, K/G])."""
     n, k = w.shape
     assert w.dtype == torch.float32 and w.is_contiguous() and u_factor.dtype == torch.float32 and u_factor.is_contiguous()
     assert tuple(u_factor.shape) == (k, k) and w_scale.dtype == torch.float32 and w_scale.numel() in (1, n)
@@ -400,10 +403,16 @@ def dpq_calibrate(w: torch.Tensor, u_factor: torch.Tensor, w_scale: torch.Tensor
     zeros = torch.empty((n, k // group_size), dtype=torch.uint8, device=dev)
     nbytes = lib().w4a8_dpq_workspace_bytes(n, k)
     work = torch.empty(max(nbytes, 16), dtype=torch.uint8, device=dev)
-    _check(lib().w4a8_dpq_calibrate(w.data_ptr(), u_factor.data_ptr(), w_scale.data_ptr(), 1 if w_scale.numel() > 1 else 0,
-                                    perm.data_ptr() if perm is not None else 0, n, k, group_size, codes.data_ptr(),
-                                    scales.data_ptr(), zeros.data_ptr(), work.data_ptr(), nbytes, _stream()),
-           "w4a8_dpq_calibrate")
+    per_channel = 1 if w_scale.numel() > 1 else 0
+    perm_ptr = perm.data_ptr() if perm is not None else 0
+    if mse_grid > 1:
+        _check(lib().w4a8_dpq_calibrate_mse(w.data_ptr(), u_factor.data_ptr(), w_scale.data_ptr(), per_channel, perm_ptr, n, k,
+                                            group_size, mse_grid, mse_max_shrink, codes.data_ptr(), scales.data_ptr(),
+                                            zeros.data_ptr(), work.data_ptr(), nbytes, _stream()), "w4a8_dpq_calibrate_mse")
+    else:
+        _check(lib().w4a8_dpq_calibrate(w.data_ptr(), u_factor.data_ptr(), w_scale.data_ptr(), per_channel, perm_ptr, n, k,
+                                        group_size, codes.data_ptr(), scales.data_ptr(), zeros.data_ptr(), work.data_ptr(),
+                                        nbytes, _stream()), "w4a8_dpq_calibrate")
     return codes, scales, zeros
 
 

@@ -16,7 +16,9 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-u
 # linear_mfma.hip orders MFMAs, LDS reads and ALU work step by step; the backend's sinking pass otherwise moves the MFMAs
 # of the modes that accumulate inside the matrix unit past the branches of a pass to its end, where all of the pass's
 # activation operands are live at once and spill
-EXTRA_FLAGS = {"linear_mfma.hip": ["-mllvm", "-disable-machine-sink"]}
+# dpq.hip: Alg. 1 is specified as a sequence of single float32 operations (its integer decisions must be reproducible
+# bit for bit), so a product must never be contracted with the sum or difference that consumes it
+EXTRA_FLAGS = {"linear_mfma.hip": ["-mllvm", "-disable-machine-sink"], "dpq.hip": ["-ffp-contract=off"]}
 
 
 def build(verbose: bool = False) -> str:

@@ -363,7 +363,17 @@ size_t w4a8_dpq_workspace_bytes(int64_t N, int64_t K) {
 int w4a8_dpq_calibrate(const float* w_dev, const float* u_factor_dev, const float* w_scale_dev, int32_t per_channel,
                        const int32_t* perm_dev, int64_t N, int64_t K, int32_t group_size, uint8_t* codes_dev,
                        float* scales8_dev, uint8_t* zeros_dev, void* workspace_dev, size_t workspace_bytes, void* stream) {
+    return w4a8_dpq_calibrate_mse(w_dev, u_factor_dev, w_scale_dev, per_channel, perm_dev, N, K, group_size, 0, 0.0f,
+                                  codes_dev, scales8_dev, zeros_dev, workspace_dev, workspace_bytes, stream);
+}
+
+int w4a8_dpq_calibrate_mse(const float* w_dev, const float* u_factor_dev, const float* w_scale_dev, int32_t per_channel,
+                           const int32_t* perm_dev, int64_t N, int64_t K, int32_t group_size, int32_t mse_grid,
+                           float mse_max_shrink, uint8_t* codes_dev, float* scales8_dev, uint8_t* zeros_dev,
+                           void* workspace_dev, size_t workspace_bytes, void* stream) {
     if (int e = check_weight_shape(N, K, group_size, W4A8_LAYOUT_TILED)) return e;
+    if (mse_grid < 0 || mse_grid > 1024) return W4A8_ERR_SHAPE;
+    if (mse_grid > 1 && !(mse_max_shrink >= 0.0f && mse_max_shrink < 1.0f)) return W4A8_ERR_SHAPE;
     if (per_channel != 0 && per_channel != 1) return W4A8_ERR_DTYPE;
     if (!w_dev || !u_factor_dev || !w_scale_dev || !codes_dev || !scales8_dev || !zeros_dev || !workspace_dev) return W4A8_ERR_NULL;
     if (reinterpret_cast<uintptr_t>(w_dev) % 4 || reinterpret_cast<uintptr_t>(u_factor_dev) % 4 ||
@@ -372,7 +382,8 @@ int w4a8_dpq_calibrate(const float* w_dev, const float* u_factor_dev, const floa
         return W4A8_ERR_ALIGN;
     if (workspace_bytes < w4a8_dpq_workspace_bytes(N, K)) return W4A8_ERR_WORKSPACE;
     return launch_dpq_calibrate(w_dev, u_factor_dev, w_scale_dev, per_channel, perm_dev, N, K, group_size, codes_dev,
-                                scales8_dev, zeros_dev, workspace_dev, static_cast<hipStream_t>(stream));
+                                scales8_dev, zeros_dev, workspace_dev, mse_grid, mse_max_shrink,
+                                static_cast<hipStream_t>(stream));
 }
 
 int w4a8_silu_mul(const void* gu_dev, int64_t M, int64_t F, int64_t ldgu, void* h_dev, int64_t ldh, void* stream) {

@@ -72,7 +72,16 @@ struct DpqArgs {
     float* scales;                // [N, K / G], original group order
     uint8_t* zeros;               // [N, K / G]
     float* err;                   // [N, 128] errors of the current block
+    int mse_grid;                 // candidates of the scale search (Sec. 3.3); <= 1: none
+    float shrink_step;            // max_shrink / mse_grid
 };
+
+// Eq. 8 for a range [lo, hi] that contains zero: s = (hi - lo) / 15 (1 for an empty range), z = round(-lo / s)
+__device__ __forceinline__ void group_params(float lo, float hi, float& s, float& z) {
+    const float span = __fsub_rn(hi, lo);
+    s = (span == 0.0f) ? 1.0f : __fdiv_rn(span, 15.0f);
+    z = fminf(fmaxf(rintf(__fdiv_rn(-lo, s)), 0.0f), 15.0f);
+}
 
 // One block of 128 columns starting at c0.  The DPQ_LPR lanes of a row sit next to each other in one wavefront and
 // share the row's 128 weights through LDS; a wavefront executes its LDS accesses in program order, so a lane's update
@@ -99,9 +108,36 @@ __global__ void __launch_bounds__(DPQ_THREADS) dpq_block_kernel(DpqArgs a, int c
             lo = fminf(lo, w8);
             hi = fmaxf(hi, w8);
         }
-        const float span = __fsub_rn(hi, lo);
-        s = (span == 0.0f) ? 1.0f : __fdiv_rn(span, 15.0f);
-        z = fminf(fmaxf(rintf(__fdiv_rn(-lo, s)), 0.0f), 15.0f);
+        group_params(lo, hi, s, z);
+        if (a.mse_grid > 1) {
+            // The scale search of Sec. 3.3: candidate i shrinks the range by p_i = 1 - i * shrink_step and is scored by
+            // the squared error, on the FP8 values, of what inference will reconstruct (Eq. 9 with clipping, Eq. 10);
+            // float32 sums over the group in visiting order.  The row's lanes share the candidates (i % DPQ_LPR) and
+            // then agree on the smallest score, the lowest index among equals -- the first minimum of a sequential scan.
+            float best = __builtin_inff(), bs = s, bz = z;
+            int best_i = a.mse_grid;
+            for (int i = part; i < a.mse_grid; i += DPQ_LPR) {
+                const float p = __fsub_rn(1.0f, __fmul_rn((float)i, a.shrink_step));
+                float si, zi;
+                group_params(__fmul_rn(p, lo), __fmul_rn(p, hi), si, zi);
+                float score = 0.0f;
+                for (int j = 0; j < a.G; ++j) {
+                    const float w8 = fp8_value(__fdiv_rn(row[c0 + j], sw));
+                    const float uq = fminf(fmaxf(rintf(__fadd_rn(__fdiv_rn(w8, si), zi)), 0.0f), 15.0f);
+                    const float d = __fsub_rn(w8, fp8_value(__fmul_rn(__fsub_rn(uq, zi), si)));
+                    score = __fadd_rn(score, __fmul_rn(d, d));
+                }
+                if (score < best) { best = score; best_i = i; bs = si; bz = zi; }
+            }
+#pragma unroll
+            for (int m = 1; m < DPQ_LPR; m <<= 1) {
+                const float ob = __shfl_xor(best, m), os = __shfl_xor(bs, m), oz = __shfl_xor(bz, m);
+                const int oi = __shfl_xor(best_i, m);
+                if (ob < best || (ob == best && oi < best_i)) { best = ob; best_i = oi; bs = os; bz = oz; }
+            }
+            s = bs;
+            z = bz;
+        }
         if (part == 0) {
             a.scales[(int64_t)n * NG + og] = s;
             a.zeros[(int64_t)n * NG + og] = (uint8_t)z;
@@ -228,8 +264,10 @@ int launch_gar_permutation(const float* hdiag, int64_t K, int32_t G, int32_t* pe
 
 int launch_dpq_calibrate(const float* w, const float* u, const float* s_w, int per_channel, const int32_t* perm,
                          int64_t N, int64_t K, int32_t G, uint8_t* codes, float* scales, uint8_t* zeros, void* workspace,
-                         hipStream_t st) {
+                         int mse_grid, float mse_max_shrink, hipStream_t st) {
     DpqArgs a;
+    a.mse_grid = mse_grid;
+    a.shrink_step = mse_grid > 1 ? mse_max_shrink / (float)mse_grid : 0.0f;
     a.work = static_cast<float*>(workspace);
     a.err = a.work + N * K;
     a.u = u; a.s_w = s_w; a.per_channel = per_channel; a.perm = perm;

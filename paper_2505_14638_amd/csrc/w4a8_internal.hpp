@@ -84,7 +84,7 @@ int launch_hessian_inverse_factor(const float* h, int64_t K, double damp, const 
 // workspace: (N * K + N * 128) floats
 int launch_dpq_calibrate(const float* w, const float* u, const float* s_w, int per_channel, const int32_t* perm,
                          int64_t N, int64_t K, int32_t G, uint8_t* codes, float* scales, uint8_t* zeros, void* workspace,
-                         hipStream_t st);
+                         int mse_grid, float mse_max_shrink, hipStream_t st);
 int launch_silu_mul(const void* gu, int64_t M, int64_t F, int64_t ldgu, void* h, int64_t ldh, const float* q_scale,
                     hipStream_t st);
 

@@ -230,6 +230,14 @@ def test_calibration_validation(L):
     assert f(P, P, P, 1, 0, 16, 200, 200, P, P, P, P, ok, None) == 5
     assert f(P, P, P, 1, P + 2, 16, 256, 128, P, P, P, P, ok, None) == 6
     assert f(P, P, P, 1, 0, 16, 256, 128, P, P, P, P, ok - 1, None) == 7
+    fm = L.w4a8_dpq_calibrate_mse
+    # w, u, s_w, per_channel, perm, N, K, G, mse_grid, mse_max_shrink, codes, scales, zeros, workspace, bytes, stream
+    assert fm(P, P, P, 1, 0, 16, 256, 128, 20, 0.8, P, P, P, P, ok - 1, None) == 7
+    assert fm(P, P, P, 1, 0, 16, 256, 128, -1, 0.8, P, P, P, P, ok, None) == 2
+    assert fm(P, P, P, 1, 0, 16, 256, 128, 2000, 0.8, P, P, P, P, ok, None) == 2
+    assert fm(P, P, P, 1, 0, 16, 256, 128, 20, 1.0, P, P, P, P, ok, None) == 2
+    assert fm(P, P, P, 1, 0, 16, 256, 128, 20, float("nan"), P, P, P, P, ok, None) == 2
+    assert fm(0, P, P, 1, 0, 16, 256, 128, 20, 0.5, P, P, P, P, ok, None) == 1
 
 
 def test_other_validation(L):

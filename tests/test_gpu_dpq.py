@@ -63,6 +63,28 @@ def test_dpq_bit_exact(gpu_lib, n, k, g, per_channel, reorder):
     assert np.mean(codes != plain[0]) > 0.05
 
 
+@pytest.mark.parametrize("n,k,g,grid,shrink,reorder", [(40, 256, 128, 20, 0.8, False), (70, 512, 256, 37, 0.5, True),
+                                                        (33, 384, 128, 5, 0.9, True), (17, 256, 128, 2, 0.3, False)])
+def test_dpq_with_the_mse_scale_search_bit_exact(gpu_lib, n, k, g, grid, shrink, reorder):
+    """Alg. 1 with the scale search of Sec. 3.3: candidates split over the lanes of a row on the GPU, scanned one after
+    the other in the oracle -- the same float32 scores, the same first minimum, the same codes and parameters."""
+    rng = np.random.default_rng([87, n, k, g])
+    w = syn.make_weights(rng, n, k)
+    w[np.arange(n), rng.integers(0, k, n)] *= 5.0                          # a stretched range in one group per row
+    x = calibration_inputs(rng, 2 * k, k)
+    perm = o.gar_permutation(np.diag(x.T @ x), g) if reorder else None
+    u = o.hessian_inverse_factor(x[:, perm] if reorder else x).astype(np.float32)
+    s_w = (np.abs(w).max(axis=1) / np.float32(448.0)).astype(np.float32)
+    want = o.dpq_quantize(w, u, s_w, g, perm=perm, mse_grid=grid, mse_max_shrink=shrink)
+    got = B.dpq_calibrate(dev(w), dev(u), dev(s_w), g, dev(perm.astype(np.int32)) if reorder else None, mse_grid=grid,
+                          mse_max_shrink=shrink)
+    codes, scales, zeros = (host(t) for t in got)
+    assert np.array_equal(scales, want[1]) and np.array_equal(zeros, want[2])
+    assert np.array_equal(codes, want[0])
+    plain = o.dpq_quantize(w, u, s_w, g, perm=perm)
+    assert np.mean(scales != plain[1]) > 0.1                               # the search did move scales
+
+
 def test_calibrated_weights_through_packing_and_inference(gpu_lib):
     """Calibration -> w4a8_pack_weights_asym -> w4a8_linear_asym_two_level: the layer on calibrated weights is closer
     to the unquantized layer, on the calibration inputs, than the layer on uncompensated weights; and the inference
