@@ -19,7 +19,6 @@ namespace {
 
 constexpr int TB = 64;              // tile edge
 constexpr int KS = 16;              // depth of one staged slice
-constexpr int MS = TB + 2;          // row stride of the diagonal-tile kernel's array
 
 // scalars[0] = damp * mean(diag(H)); *info = 0.  One workgroup; a fixed summation order.
 __global__ void __launch_bounds__(256) damp_term_kernel(const float* __restrict__ h, int n, double damp, double* __restrict__ scalars,
@@ -52,49 +51,89 @@ __global__ void __launch_bounds__(256) gather_reversed_kernel(const float* __res
     a[u] = v;
 }
 
-// Diagonal tile kb: a[kb, kb] <- its lower Cholesky factor L (zeros above the diagonal); dinv[kb] <- L^-1, row-major
+// Diagonal tile kb: a[kb, kb] <- its lower Cholesky factor L (zeros above the diagonal); dinv[kb] <- V = L^-1, row-major
 // 64 x 64 (zeros above the diagonal).  A pivot that is not positive is reported through *info (1 + its index in the
 // reversed order, first failure only); the results are then not finite.
-// One array holds both triangles: L(r, c), c <= r, at m[r][c]; V(i, c) = L^-1(i, c), i >= c, at m[c][i + 1].
+// The tile lives in registers, 4 x 4 per thread (thread (ty, tx) = (t / 16, t % 16) owns rows 4 ty.., columns 4 tx..),
+// and so does S, which starts as the identity and ends as V.  Step j: the owners of column j scale it by the pivot's
+// root (column j of L), the owners of row j of S divide it by the same (row j of V); both go through LDS to everyone,
+// who then take L[r, j] L[c, j] off their part of the tile and L[r, j] V[j, c] off their part of S.
 __global__ void __launch_bounds__(256) factor_diagonal_kernel(double* __restrict__ a, int n, int kb, double* __restrict__ dinv,
                                                               int32_t* __restrict__ info) {
-    __shared__ double m[TB * MS];
-    const int t = threadIdx.x;
+    __shared__ __attribute__((aligned(16))) double lcol[TB], vrow[TB];
+    __shared__ double pivot;
+    const int t = threadIdx.x, ty = t >> 4, tx = t & 15;
     double* tile = a + ((int64_t)kb * TB) * n + (int64_t)kb * TB;
-    for (int idx = t; idx < TB * TB; idx += 256) {
-        const int r = idx / TB, c = idx % TB;
-        if (c <= r) m[r * MS + c] = tile[(int64_t)r * n + c];
-    }
-    __syncthreads();
-    for (int j = 0; j < TB; ++j) {
-        const double d = m[j * MS + j];
-        if (t == 0 && !(d > 0.0) && *info == 0) *info = kb * TB + j + 1;
-        const double s = sqrt(d);
-        __syncthreads();                                         // everyone has read the pivot
-        if (t >= j && t < TB) m[t * MS + j] = (t == j) ? s : m[t * MS + j] / s;
-        __syncthreads();
-        for (int idx = t; idx < TB * TB; idx += 256) {
-            const int r = idx / TB, c = idx % TB;
-            if (c > j && c <= r) m[r * MS + c] -= m[r * MS + j] * m[c * MS + j];
+    double A[4][4], S[4][4];
+#pragma unroll
+    for (int rr = 0; rr < 4; ++rr)
+#pragma unroll
+        for (int cc = 0; cc < 4; ++cc) {
+            const int r = 4 * ty + rr, c = 4 * tx + cc;
+            A[rr][cc] = (c <= r) ? tile[(int64_t)r * n + c] : 0.0;
+            S[rr][cc] = (r == c) ? 1.0 : 0.0;
         }
-        __syncthreads();
-    }
-    if (t < TB) {                                                // column t of V by forward substitution
-        const int c = t;
-        m[c * MS + c + 1] = 1.0 / m[c * MS + c];
-        for (int i = c + 1; i < TB; ++i) {
-            double s = 0.0;
-            for (int k = c; k < i; ++k) s += m[i * MS + k] * m[c * MS + k + 1];
-            m[c * MS + i + 1] = -s / m[i * MS + i];
+    if (t == 0) pivot = A[0][0];
+    __syncthreads();
+    for (int jb = 0; jb < TB / 4; ++jb) {
+#pragma unroll
+        for (int jj = 0; jj < 4; ++jj) {
+            const int j = 4 * jb + jj;
+            const double d = pivot;
+            if (t == 0 && !(d > 0.0) && *info == 0) *info = kb * TB + j + 1;
+            const double s = sqrt(d), rs = 1.0 / s;              // one division per step; the scalings below multiply
+            if (tx == jb) {                                      // owners of column j
+#pragma unroll
+                for (int rr = 0; rr < 4; ++rr) {
+                    const int r = 4 * ty + rr;
+                    if (r >= j) {
+                        A[rr][jj] = (r == j) ? s : A[rr][jj] * rs;
+                        lcol[r] = A[rr][jj];
+                    }
+                }
+            }
+            if (ty == jb) {                                      // owners of row j of S
+#pragma unroll
+                for (int cc = 0; cc < 4; ++cc) {
+                    const int c = 4 * tx + cc;
+                    if (c <= j) {
+                        S[jj][cc] *= rs;
+                        vrow[c] = S[jj][cc];
+                    }
+                }
+            }
+            __syncthreads();
+#pragma unroll
+            for (int rr = 0; rr < 4; ++rr) {
+                const int r = 4 * ty + rr;
+                if (r > j) {
+                    const double lr = lcol[r];
+#pragma unroll
+                    for (int cc = 0; cc < 4; ++cc) {
+                        const int c = 4 * tx + cc;
+                        if (c > j && c <= r) A[rr][cc] -= lr * lcol[c];
+                        if (c <= j) S[rr][cc] -= lr * vrow[c];
+                    }
+                }
+            }
+            // the owner of the next pivot hands it on
+            if (jj < 3) {
+                if (ty == jb && tx == jb) pivot = A[(jj + 1) & 3][(jj + 1) & 3];
+            } else {
+                if (ty == jb + 1 && tx == jb + 1) pivot = A[0][0];
+            }
+            __syncthreads();
         }
     }
-    __syncthreads();
     double* dv = dinv + (int64_t)kb * TB * TB;
-    for (int idx = t; idx < TB * TB; idx += 256) {
-        const int r = idx / TB, c = idx % TB;
-        tile[(int64_t)r * n + c] = (c <= r) ? m[r * MS + c] : 0.0;
-        dv[idx] = (c <= r) ? m[c * MS + r + 1] : 0.0;
-    }
+#pragma unroll
+    for (int rr = 0; rr < 4; ++rr)
+#pragma unroll
+        for (int cc = 0; cc < 4; ++cc) {
+            const int r = 4 * ty + rr, c = 4 * tx + cc;
+            tile[(int64_t)r * n + c] = (c <= r) ? A[rr][cc] : 0.0;
+            dv[r * TB + c] = (c <= r) ? S[rr][cc] : 0.0;
+        }
 }
 
 // acc[i][j] += sum over k < depth of A(4 ty + i, k) * B(k, 4 tx + j) for a 64 x 64 tile, thread (ty, tx) = (t / 16,
