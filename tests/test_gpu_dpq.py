@@ -198,3 +198,33 @@ def test_calibration_pipeline_on_the_gpu(gpu_lib):
     e_plain = layer_error(*plain)
     print(f"  layer error: GPU pipeline {e_gpu:.4e}, oracle {e_ref:.4e}, uncompensated {e_plain:.4e}", flush=True)
     assert abs(e_gpu - e_ref) < 0.02 * e_ref and e_gpu < 0.9 * e_plain
+
+
+def test_calibration_at_the_size_bench_times_sampled_rows(gpu_lib):
+    """A 4096 x 4096 layer with 8192 calibration tokens, the shapes of bench.py's calibration leg.  The factor from the
+    GPU against the oracle's at full size; then Alg. 1 with GAR and the scale search on all 4096 rows on the GPU against
+    the oracle on 12 sampled rows (rows are independent), bit for bit, both on the oracle's factor."""
+    rng = np.random.default_rng(88)
+    n = k = 4096
+    g, t = 128, 8192
+    print("  inputs", flush=True)
+    w = syn.make_weights(rng, n, k)
+    x = syn.make_activations(rng, t, k, 0.01, 20.0) * np.exp(rng.uniform(-1.0, 1.0, size=k)).astype(np.float32)[None, :]
+    s_w = (np.abs(w).max(axis=1) / np.float32(448.0)).astype(np.float32)
+    h_d = B.hessian_accumulate(dev(x.astype(np.float32)))
+    perm_d = B.gar_permutation(torch.diagonal(h_d).contiguous(), g)
+    u_d, info = B.hessian_inverse_factor(h_d, 0.01, perm_d)
+    h, perm = host(h_d), host(perm_d)
+    assert int(host(info)[0]) == 0 and np.array_equal(perm, o.gar_permutation(np.diag(h), g))
+    print("  oracle factor", flush=True)
+    u = o.hessian_inverse_factor_from_h(h, 0.01, perm)
+    got_u = host(u_d).astype(np.float64)
+    assert np.all(np.abs(got_u - u) <= 2.0 ** -23 * np.abs(u) + 1e-9 * np.abs(u).max())
+    u32 = u.astype(np.float32)
+    print("  Alg. 1 on the GPU", flush=True)
+    codes, scales, zeros = (host(a) for a in B.dpq_calibrate(dev(w), dev(u32), dev(s_w), g, perm_d, mse_grid=8, mse_max_shrink=0.6))
+    rows = np.sort(np.concatenate([[0, n - 1], rng.choice(n - 2, 10, replace=False) + 1]))
+    print("  Alg. 1 in the oracle, 12 rows", flush=True)
+    want = o.dpq_quantize(w[rows], u32, s_w[rows], g, perm=perm, mse_grid=8, mse_max_shrink=0.6)
+    assert np.array_equal(scales[rows], want[1]) and np.array_equal(zeros[rows], want[2])
+    assert np.array_equal(codes[rows], want[0])
