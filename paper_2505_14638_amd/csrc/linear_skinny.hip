@@ -5,9 +5,12 @@
 // contiguous run of 128-deep chunks, which is contiguous memory in the tiled format) and their partial results
 // are summed through LDS.  Per chunk a wavefront issues one 16-byte load per lane and tile (the 1 KiB tile is read
 // fully coalesced), expands the sign-magnitude nibbles to E4M3 in registers (Eq. 10; four ALU ops per four weights,
-// plus a fix-up for -8 on chunks whose scales the packer has marked) and feeds them as the A operand of one
-// 16x16x128 FP8 MFMA per (tile, 16-token block); the activations are the B operand, loaded straight from global
-// memory (they are small and stay in cache).  The chunk's partial product is scaled by the group scale in fp32.
+// plus a fix-up for -8 on chunks whose scales the packer has marked) and feeds them as the column operand of one
+// 16x16x128 FP8 MFMA per (tile, 16-token block); the activations are the row operand, loaded straight from global
+// memory (they are small and stay in cache).  A result lane therefore holds ONE channel (and four tokens): the
+// chunk's partial product is scaled in fp32 by a group scale that is a single 4-byte load per lane -- the vector
+// memory path returns 64 bytes per clock to a compute unit whatever the addresses, so a float4 of scales per lane
+// (what the other operand order needs) costs it as much as the kilobyte of nibbles does.
 // Several chunks' loads are in flight ahead of the current chunk's arithmetic.
 #include "w4a8_device.hpp"
 #include "w4a8_internal.hpp"
@@ -20,9 +23,9 @@ constexpr int RED_STRIDE = 65;      // floats per (wave, register) row in LDS: 6
 template <int MT, int NT>
 struct ChunkLoads {
     uint4 w[NT];          // packed nibbles: this lane's slot of each tile
-    float4 s[NT];         // group scales of the four output channels this lane accumulates
+    float s[NT];          // group scale of the lane's channel (the one whose nibbles it expands and whose results it holds)
     uint4 x[MT][2];       // 32 activation bytes per 16-token block
-    uint32_t z[NT];       // asymmetric format: the zero-point bytes of the four output channels this lane accumulates
+    uint32_t z[NT];       // asymmetric format: the zero-point of the lane's channel
 };
 
 // larger register tiles run with fewer wavefronts per workgroup (the launcher enforces it), which raises the
@@ -68,7 +71,7 @@ __global__ void __launch_bounds__(max_threads(MT * NT, MODE == MODE_ASYM || MODE
         wbase[j] = packed + ((int64_t)t * C + c_begin) * 1024;
         sbase[j] = reinterpret_cast<const uint8_t*>(scales) + (int64_t)t * NG * REC;
     }
-    const uint32_t woff = lane * 16, soff = kq * 16;
+    const uint32_t woff = lane * 16, soff = i * 4;
     const uint8_t* xp[MT];
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) {
@@ -81,12 +84,8 @@ __global__ void __launch_bounds__(max_threads(MT * NT, MODE == MODE_ASYM || MODE
 #pragma unroll
         for (int j = 0; j < NT; ++j) {
             L.w[j] = *reinterpret_cast<const uint4*>(wbase[j] + woff);
-            if (TWO || POW2 || ASYM2)                           // the scale of the channel whose nibbles this lane expands
-                L.s[j] = make_float4(*reinterpret_cast<const float*>(sbase[j] + (int64_t)g * REC + i * 4), 0.f, 0.f, 0.f);
-            else
-                L.s[j] = *reinterpret_cast<const float4*>(sbase[j] + (int64_t)g * REC + soff);
-            L.z[j] = ASYM ? *reinterpret_cast<const uint32_t*>(sbase[j] + (int64_t)g * REC + 64 + kq * 4)
-                          : ASYM2 ? (uint32_t)sbase[j][(int64_t)g * REC + 64 + i] : 0u;   // ASYM2: the expanding channel's own
+            L.s[j] = *reinterpret_cast<const float*>(sbase[j] + (int64_t)g * REC + soff);
+            L.z[j] = (ASYM || ASYM2) ? (uint32_t)sbase[j][(int64_t)g * REC + 64 + i] : 0u;
             wbase[j] += 1024;
         }
 #pragma unroll
@@ -111,26 +110,25 @@ __global__ void __launch_bounds__(max_threads(MT * NT, MODE == MODE_ASYM || MODE
             const uint4 a = L.x[mt][0], b = L.x[mt][1];
             xop[mt] = v8i{(int)a.x, (int)a.y, (int)a.z, (int)a.w, (int)b.x, (int)b.y, (int)b.z, (int)b.w};
         }
-        // asymmetric format: sum_k x over the chunk, per token, from an MFMA against an operand of ones (every row of
-        // the result is that sum)
-        float xs[MT];
+        // asymmetric format: sum_k x over the chunk, per token, from an MFMA against an operand of ones (every column
+        // of the result is that sum: the lane gets the sums of its own four tokens)
+        v4f xs[MT];
         if (ASYM) {
             const v8i ones = v8i{0x38383838, 0x38383838, 0x38383838, 0x38383838, 0x38383838, 0x38383838, 0x38383838, 0x38383838};
 #pragma unroll
-            for (int mt = 0; mt < MT; ++mt) xs[mt] = mfma_16x16x128_e4m3(ones, xop[mt], v4f{0.f, 0.f, 0.f, 0.f})[0];
+            for (int mt = 0; mt < MT; ++mt) xs[mt] = mfma_16x16x128_e4m3(xop[mt], ones, v4f{0.f, 0.f, 0.f, 0.f});
         }
 #pragma unroll
         for (int j = 0; j < NT; ++j) {
-            const float4 s = L.s[j];
+            const float s = L.s[j];
             // a marked scale (sign bit) on any of the band's 16 channels: this chunk's tile may hold -8
-            const bool m8 = !ASYM && !ASYM2 && any_marked(__uint_as_float(__float_as_uint(s.x) | __float_as_uint(s.y) |
-                                                                __float_as_uint(s.z) | __float_as_uint(s.w)));
+            const bool m8 = !ASYM && !ASYM2 && any_marked(s);
             v8i wop;
             if (TWO) {
-                const MagTable tab = two_level_table(s.x);
+                const MagTable tab = two_level_table(s);
                 wop = m8 ? slot_to_operand_two_level<true>(L.w[j], tab) : slot_to_operand_two_level<false>(L.w[j], tab);
             } else if (ASYM2) {
-                wop = slot_to_operand_asym(L.w[j], asym_two_level_table(L.z[j], s.x));
+                wop = slot_to_operand_asym(L.w[j], asym_two_level_table(L.z[j], s));
             } else if (ASYM) {
                 wop = slot_to_operand_half_offset(L.w[j]);       // code - 7.5
             } else {
@@ -143,25 +141,26 @@ __global__ void __launch_bounds__(max_threads(MT * NT, MODE == MODE_ASYM || MODE
 #pragma unroll
             for (int mt = 0; mt < MT; ++mt) {
                 if (TWO || ASYM2) {
-                    acc[mt][j] = mfma_16x16x128_e4m3(wop, xop[mt], acc[mt][j]);
+                    acc[mt][j] = mfma_16x16x128_e4m3(xop[mt], wop, acc[mt][j]);
                     continue;
                 }
                 if (POW2) {
-                    acc[mt][j] = mfma_16x16x128_e4m3_scaled(wop, xop[mt], acc[mt][j], e8m0_of(s.x), E8M0_ONE);
+                    acc[mt][j] = mfma_16x16x128_e4m3_scaled(xop[mt], wop, acc[mt][j], E8M0_ONE, e8m0_of(s));
                     continue;
                 }
-                v4f p = mfma_16x16x128_e4m3(wop, xop[mt], v4f{0.f, 0.f, 0.f, 0.f});
+                v4f p = mfma_16x16x128_e4m3(xop[mt], wop, v4f{0.f, 0.f, 0.f, 0.f});
                 if (ASYM) {                                      // sum x (u - z) = sum x (u - 7.5) + (7.5 - z) sum x
-                    const uint32_t z = L.z[j];
-                    p[0] = fmaf(7.5f - (float)(z & 0xFFu), xs[mt], p[0]);
-                    p[1] = fmaf(7.5f - (float)((z >> 8) & 0xFFu), xs[mt], p[1]);
-                    p[2] = fmaf(7.5f - (float)((z >> 16) & 0xFFu), xs[mt], p[2]);
-                    p[3] = fmaf(7.5f - (float)(z >> 24), xs[mt], p[3]);
+                    const float zf = 7.5f - (float)L.z[j];
+                    p[0] = fmaf(zf, xs[mt][0], p[0]);
+                    p[1] = fmaf(zf, xs[mt][1], p[1]);
+                    p[2] = fmaf(zf, xs[mt][2], p[2]);
+                    p[3] = fmaf(zf, xs[mt][3], p[3]);
                 }
-                acc[mt][j][0] = fmaf(fabsf(s.x), p[0], acc[mt][j][0]);
-                acc[mt][j][1] = fmaf(fabsf(s.y), p[1], acc[mt][j][1]);
-                acc[mt][j][2] = fmaf(fabsf(s.z), p[2], acc[mt][j][2]);
-                acc[mt][j][3] = fmaf(fabsf(s.w), p[3], acc[mt][j][3]);
+                const float sa = fabsf(s);                       // the sign bit is the packer's mark, not part of the scale
+                acc[mt][j][0] = fmaf(sa, p[0], acc[mt][j][0]);
+                acc[mt][j][1] = fmaf(sa, p[1], acc[mt][j][1]);
+                acc[mt][j][2] = fmaf(sa, p[2], acc[mt][j][2]);
+                acc[mt][j][3] = fmaf(sa, p[3], acc[mt][j][3]);
             }
         }
     };
@@ -215,8 +214,8 @@ __global__ void __launch_bounds__(max_threads(MT * NT, MODE == MODE_ASYM || MODE
         for (int idx = threadIdx.x; idx < MT * 16 * HALF; idx += blockDim.x) {
             const int col = idx % HALF, row = idx / HALF;
             const int p = col >> 4, nl = col & 15, mt = row >> 4, ml = row & 15;
-            const int src_lane = ml + 16 * (nl >> 2);
-            const int eg = (mt * NT + 2 * p) * 4 + (nl & 3), eu = (mt * NT + 2 * p + 1) * 4 + (nl & 3);
+            const int src_lane = nl + 16 * (ml >> 2);            // lane = channel + 16 * (token / 4), register = token % 4
+            const int eg = (mt * NT + 2 * p) * 4 + (ml & 3), eu = (mt * NT + 2 * p + 1) * 4 + (ml & 3);
             float sg = 0.0f, su = 0.0f;
             for (int w = 0; w < waves; ++w) {
                 sg += red[(w * E + eg) * RED_STRIDE + src_lane];
@@ -232,7 +231,7 @@ __global__ void __launch_bounds__(max_threads(MT * NT, MODE == MODE_ASYM || MODE
         for (int idx = threadIdx.x; idx < MT * 16 * COLS; idx += blockDim.x) {
             const int col = idx % COLS, row = idx / COLS;            // channel fastest: consecutive threads, consecutive y
             const int j = col >> 4, nl = col & 15, mt = row >> 4, ml = row & 15;
-            const int e = (mt * NT + j) * 4 + (nl & 3), src_lane = ml + 16 * (nl >> 2);
+            const int e = (mt * NT + j) * 4 + (ml & 3), src_lane = nl + 16 * (ml >> 2);   // lane = channel + 16 * (token / 4)
             float sum = 0.0f;
             for (int w = 0; w < waves; ++w) sum += red[(w * E + e) * RED_STRIDE + src_lane];
             const int m = mt * 16 + ml, n = (t0 + j) * 16 + nl;
