@@ -228,3 +228,24 @@ def test_calibration_at_the_size_bench_times_sampled_rows(gpu_lib):
     want = o.dpq_quantize(w[rows], u32, s_w[rows], g, perm=perm, mse_grid=8, mse_max_shrink=0.6)
     assert np.array_equal(scales[rows], want[1]) and np.array_equal(zeros[rows], want[2])
     assert np.array_equal(codes[rows], want[0])
+
+
+def test_hessian_inverse_factor_special_cases(gpu_lib):
+    """A diagonal Hessian without dampening has the closed form U = diag(1 / sqrt(h_ii)); the identity permutation is
+    the same as none; a reversal of the columns gives the factor of the reversed matrix."""
+    rng = np.random.default_rng(89)
+    k = 256
+    d = rng.uniform(0.5, 4.0, k).astype(np.float32)
+    u, info = B.hessian_inverse_factor(dev(np.diag(d)), 0.0)
+    assert int(host(info)[0]) == 0
+    assert np.allclose(host(u), np.diag(1.0 / np.sqrt(d.astype(np.float64))), rtol=2e-7, atol=0)
+    x = calibration_inputs(rng, 2 * k, k)
+    h = (x.T @ x).astype(np.float32)
+    h = np.maximum(h, h.T)
+    u0 = host(B.hessian_inverse_factor(dev(h), 0.01)[0])
+    u1 = host(B.hessian_inverse_factor(dev(h), 0.01, dev(np.arange(k, dtype=np.int32)))[0])
+    assert np.array_equal(u0, u1)
+    rev = np.arange(k - 1, -1, -1, dtype=np.int32)
+    u2 = host(B.hessian_inverse_factor(dev(h), 0.01, dev(rev))[0])
+    u3 = host(B.hessian_inverse_factor(dev(np.ascontiguousarray(h[::-1, ::-1])), 0.01)[0])
+    assert np.array_equal(u2, u3)
