@@ -438,6 +438,7 @@ def main():
     ap.add_argument("--prefill-only", action="store_true", help="profiling aid: run only the prefill sweep")
     ap.add_argument("--eager", action="store_true", help="profiling aid: launch the decode sweep kernel by kernel "
                     "instead of replaying HIP graphs (for hardware-counter runs)")
+    ap.add_argument("--calibration-only", action="store_true", help="profiling aid: run only the offline-calibration leg")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
@@ -446,6 +447,9 @@ def main():
     B.lib()
     dev = "cuda:0"
     torch.cuda.set_device(0)
+    if args.calibration_only:
+        print(json.dumps({"calibration": calibration(dev)}))
+        return
     cfg = syn.CONFIGS[2]
     layers = [Layer(2, i, k, n, args.copies, dev) for i, (k, n) in enumerate(syn.LLAMA3_8B.values())]
     result = {}

@@ -4,7 +4,7 @@
 // Alg. 1 walks along a row: quantize one weight (FP8, then INT4, Eq. 7-9), dequantize it the way inference will
 // (Eq. 10-11), and push the error onto every later weight of the row through the Hessian factor U (Eq. 12; U is the
 // upper Cholesky factor of the inverse Hessian, Sec. 3.3).  Rows are independent, columns strictly sequential.  The
-// work is arranged in blocks of 128 columns: inside a block eight lanes of one wavefront own one row (each takes
+// work is arranged in blocks of 128 columns: inside a block 32 lanes of one wavefront own one row (each takes
 // the quantization step itself and applies the error to its share of the rest of the block); the columns right of
 // the block receive the block's 128 errors afterwards, in one tiled pass over the matrix.  Every weight still sees the same float32 operations in the same order as in the plain
 // column-by-column statement (w <- w - err_q * U[q, v] for q ascending, product and difference rounded separately),
@@ -16,9 +16,6 @@ namespace w4a8 {
 namespace {
 
 constexpr int DPQ_BLOCK = 128;      // columns per block
-constexpr int DPQ_THREADS = 128;    // threads per workgroup of the block kernel
-constexpr int DPQ_LPR = 8;          // lanes per row (neighbours in one wavefront)
-constexpr int DPQ_ROWS = DPQ_THREADS / DPQ_LPR;   // rows per workgroup
 
 // val(nearest_Z(t)): the E4M3 value nearest to t (ties to even, saturating), as a float32
 __device__ __forceinline__ float fp8_value(float t) {
@@ -87,8 +84,21 @@ __device__ __forceinline__ void group_params(float lo, float hi, float& s, float
 // share the row's 128 weights through LDS; a wavefront executes its LDS accesses in program order, so a lane's update
 // of a column is in place before every lane of the row reads that column in a later step -- no barrier is needed.
 // All lanes of a row take the (identical) quantization step; lane p updates the columns v with v % DPQ_LPR == p.
+// DPQ_LPR lanes per row: more lanes shorten a step (fewer columns to update per lane) but repeat the quantization
+// arithmetic on every one of them, so many lanes suit few rows and few lanes many rows.
+// The 128 steps are strictly sequential.  STAGE_U: the block's corner of U is staged in LDS once (64 KiB), so that no
+// step waits for a global load -- right when there are few rows and nothing else to run meanwhile; with many rows
+// the loads stay global and many small workgroups per compute unit hide them instead (64 KiB of LDS would leave two).
+template <int DPQ_LPR, bool STAGE_U, int DPQ_THREADS>
 __global__ void __launch_bounds__(DPQ_THREADS) dpq_block_kernel(DpqArgs a, int c0) {
+    constexpr int DPQ_ROWS = DPQ_THREADS / DPQ_LPR;              // rows per workgroup
     __shared__ float wl[DPQ_BLOCK * DPQ_ROWS];                   // wl[v * DPQ_ROWS + r]: column c0 + v of row r of the workgroup
+    __shared__ float ul[STAGE_U ? DPQ_BLOCK * DPQ_BLOCK : 1];    // ul[q * 128 + v] = U[c0 + q, c0 + v]
+    if (STAGE_U) {
+        for (int idx = threadIdx.x; idx < DPQ_BLOCK * DPQ_BLOCK; idx += DPQ_THREADS)
+            ul[idx] = a.u[(int64_t)(c0 + idx / DPQ_BLOCK) * a.K + c0 + idx % DPQ_BLOCK];
+        __syncthreads();
+    }
     const int lane = threadIdx.x / DPQ_LPR, part = threadIdx.x % DPQ_LPR;
     const int n = blockIdx.x * DPQ_ROWS + lane;
     if (n >= a.N) return;                                        // whole rows leave together
@@ -102,11 +112,16 @@ __global__ void __launch_bounds__(DPQ_THREADS) dpq_block_kernel(DpqArgs a, int c
     const int og = a.perm ? a.perm[g * a.G] / a.G : g;           // the original group these columns belong to
     float s, z;
     if (c0 % a.G == 0) {
-        float lo = 0.0f, hi = 0.0f;
-        for (int j = 0; j < a.G; ++j) {
+        float lo = 0.0f, hi = 0.0f;                              // minimum and maximum: any order gives the same result
+        for (int j = part; j < a.G; j += DPQ_LPR) {
             const float w8 = fp8_value(__fdiv_rn(row[c0 + j], sw));
             lo = fminf(lo, w8);
             hi = fmaxf(hi, w8);
+        }
+#pragma unroll
+        for (int m = 1; m < DPQ_LPR; m <<= 1) {
+            lo = fminf(lo, __shfl_xor(lo, m));
+            hi = fmaxf(hi, __shfl_xor(hi, m));
         }
         group_params(lo, hi, s, z);
         if (a.mse_grid > 1) {
@@ -153,7 +168,7 @@ __global__ void __launch_bounds__(DPQ_THREADS) dpq_block_kernel(DpqArgs a, int c
         const float uq = fminf(fmaxf(rintf(t), 0.0f), 15.0f);                             // Eq. 9
         const float w8_hat = fp8_value(__fmul_rn(__fsub_rn(uq, z), s));                   // Eq. 10
         const float w_hat = __fmul_rn(w8_hat, sw);                                        // Eq. 11
-        const float* urow = a.u + (int64_t)(c0 + q) * a.K + c0;                           // U[c0 + q, c0 + v]
+        const float* urow = STAGE_U ? ul + q * DPQ_BLOCK : a.u + (int64_t)(c0 + q) * a.K + c0;   // U[c0 + q, c0 + v]
         const float e = __fdiv_rn(__fsub_rn(w, w_hat), urow[q]);
         if (part == 0) {
             a.err[(int64_t)n * DPQ_BLOCK + q] = e;
@@ -275,9 +290,17 @@ int launch_dpq_calibrate(const float* w, const float* u, const float* s_w, int p
     a.codes = codes; a.scales = scales; a.zeros = zeros;
     hipLaunchKernelGGL(dpq_gather_kernel, dim3((unsigned)((N * K + 255) / 256)), dim3(256), 0, st, w, perm, N, K, a.work);
     if (int e = launch_status()) return e;
-    const unsigned row_groups = (unsigned)((N + DPQ_ROWS - 1) / DPQ_ROWS);
+    const int lpr = N <= 8192 ? 32 : N <= 16384 ? 16 : 8;        // lanes per row: about a quarter to half of the chip's lanes
+    const int threads = lpr == 8 ? 128 : 256;
+    const int rows_per_wg = threads / lpr;
+    const unsigned row_groups = (unsigned)((N + rows_per_wg - 1) / rows_per_wg);
     for (int c0 = 0; c0 < K; c0 += DPQ_BLOCK) {
-        hipLaunchKernelGGL(dpq_block_kernel, dim3(row_groups), dim3(DPQ_THREADS), 0, st, a, c0);
+        if (lpr == 32)
+            hipLaunchKernelGGL((dpq_block_kernel<32, true, 256>), dim3(row_groups), dim3(256), 0, st, a, c0);
+        else if (lpr == 16)
+            hipLaunchKernelGGL((dpq_block_kernel<16, true, 256>), dim3(row_groups), dim3(256), 0, st, a, c0);
+        else
+            hipLaunchKernelGGL((dpq_block_kernel<8, false, 128>), dim3(row_groups), dim3(128), 0, st, a, c0);
         if (int e = launch_status()) return e;
         const int64_t rest = K - c0 - DPQ_BLOCK;
         if (rest > 0) {
