@@ -249,3 +249,22 @@ def test_hessian_inverse_factor_special_cases(gpu_lib):
     u2 = host(B.hessian_inverse_factor(dev(h), 0.01, dev(rev))[0])
     u3 = host(B.hessian_inverse_factor(dev(np.ascontiguousarray(h[::-1, ::-1])), 0.01)[0])
     assert np.array_equal(u2, u3)
+
+
+@pytest.mark.parametrize("n", [9000, 17000])
+def test_dpq_many_rows_sampled(gpu_lib, n):
+    """Layers with more than 8192 / 16384 rows run the block kernel with 16 / 8 lanes per row (and, beyond 16384, with U
+    read from global memory): the same bits as the oracle on sampled rows, scale search included."""
+    rng = np.random.default_rng([90, n])
+    k, g = 256, 128
+    w = syn.make_weights(rng, n, k)
+    x = calibration_inputs(rng, 2 * k, k)
+    perm = o.gar_permutation(np.diag(x.T @ x), g)
+    u = o.hessian_inverse_factor(x[:, perm]).astype(np.float32)
+    s_w = (np.abs(w).max(axis=1) / np.float32(448.0)).astype(np.float32)
+    got = B.dpq_calibrate(dev(w), dev(u), dev(s_w), g, dev(perm.astype(np.int32)), mse_grid=6, mse_max_shrink=0.5)
+    codes, scales, zeros = (host(t) for t in got)
+    rows = np.sort(np.concatenate([[0, n - 1], rng.choice(n - 2, 30, replace=False) + 1]))
+    want = o.dpq_quantize(w[rows], u, s_w[rows], g, perm=perm, mse_grid=6, mse_max_shrink=0.5)
+    assert np.array_equal(scales[rows], want[1]) and np.array_equal(zeros[rows], want[2])
+    assert np.array_equal(codes[rows], want[0])
