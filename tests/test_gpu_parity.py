@@ -174,6 +174,8 @@ def test_config1_single_layer(gpu_lib):
     (7, 1024, 96, 128, (0, 1, 1)), (7, 1024, 96, 128, (0, 2, 3)), (20, 1024, 96, 128, (0, 4, 2)),
     (50, 2048, 144, 128, (0, 4, 4)), (33, 2048, 64, 128, (0, 1, 8)), (16, 2048, 64, 128, (0, 1, 16 + 2 * 256)),
     (3, 4096, 32, 128, (0, 1, 3 + 4 * 256)),
+    # very wide layers from 17 tokens on: four bands per wavefront by default, the last workgroup short of bands
+    (20, 256, 16400, 128, None), (32, 128, 16424, 128, None),
     # MFMA-tiled kernel: (path 1, 16-token blocks per workgroup, K-split groups); chunk counts that are not multiples
     # of the split (K = 384, 640, 1152), one-chunk K, group sizes spanning several chunks
     (9, 384, 40, 128, (1, 0, 0)), (9, 384, 40, 128, (1, 4, 1)), (129, 256, 272, 128, (1, 0, 0)),
