@@ -54,6 +54,9 @@ __global__ void __launch_bounds__(max_threads(MT * NT, MODE == MODE_ASYM || MODE
     constexpr bool OUT_SCALED = TWO || ASYM2;                    // output scaled by s_x * w_out[n]
     constexpr int REC = (ASYM || ASYM2) ? ASYM_RECORD_BYTES : 64;   // bytes of scales (and zero-points) per tile and group
     extern __shared__ float red[];
+    // the output scales are only needed at the very end; asked for here, their (possibly cold) loads are long back by then
+    const float sx = *s_x;
+    const float yq = (sizeof(OutT) == 1) ? *y_scale : 1.0f;      // FP8 output: the next layer's activation scale
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);     // wave-uniform: keeps the loop scalar
     const int waves = blockDim.x >> 6;
@@ -203,8 +206,6 @@ __global__ void __launch_bounds__(max_threads(MT * NT, MODE == MODE_ASYM || MODE
             for (int r = 0; r < 4; ++r) red[(wave * E + (mt * NT + j) * 4 + r) * RED_STRIDE + lane] = acc[mt][j][r];
     __syncthreads();
 
-    const float sx = *s_x;
-    const float yq = (sizeof(OutT) == 1) ? *y_scale : 1.0f;      // FP8 output: the next layer's activation scale
     constexpr int COLS = 16 * NT;                                // output channels of this workgroup
     if constexpr (OutKind<OutT>::SILU) {
         // gate|up with SiLU*mul and the next quantization folded in: tiles 2p and 2p+1 of the workgroup are the gate and
