@@ -306,7 +306,7 @@ int launch_linear_skinny(const uint8_t* x8, int64_t M, int64_t K, int64_t ldx8, 
     // Launch shape, from sweeps over the Llama-3-8B/70B layer shapes:
     //  - two bands per wavefront when the activation operand is wide enough to be worth sharing (M > 8 on layers
     //    with enough bands) or when the layer is large enough that fewer, longer-running workgroups ramp better;
-    //  - split K over as many wavefronts (a power of two) as it takes to have ~8192 (~2560 for M > 8) of them in flight.
+    //  - split K over as many wavefronts (a power of two) as it takes to have ~8192 (~2400 for M > 8) of them in flight.
     //  - four bands per wavefront from 17 tokens on when the layer is very wide (every chunk of activations a wavefront
     //    loads is then 2 KB or more, against 1 KB of nibbles per band), with fewer, longer-running wavefronts.
     const bool wide_many = M > 16 && n_tiles >= 1024;
@@ -314,10 +314,12 @@ int launch_linear_skinny(const uint8_t* x8, int64_t M, int64_t K, int64_t ldx8, 
     if (nt != 1 && nt != 2 && nt != 4) return W4A8_ERR_SHAPE;
     if (waves == 0) {
         const int grid = (n_tiles + nt - 1) / nt;
-        const int target = (wide_many && nt == 4) ? (M > 32 ? 896 : 2048) : M > 8 ? 2560 : 8192;
-        const int want = (target + grid - 1) / grid;
+        const int target = (wide_many && nt == 4) ? (M > 32 ? 896 : 2048) : M > 8 ? 2400 : 8192;
+        const float want = (float)target / (float)grid;
         waves = 2;                                               // the power of two nearest to `want` (ratio-wise), 2..16:
-        while (waves < 16 && waves * waves * 2 < want * want) waves *= 2;   // odd counts split K unevenly and measured slower
+        while (waves < 16 && (float)(waves * waves * 2) < want * want) waves *= 2;
+        // ... and no wavefront streams more than 64 KB of nibbles (the largest layers want more of them in flight)
+        while (waves < 16 && (int64_t)n_tiles * C * 1024 > (int64_t)grid * waves * 65536) waves *= 2;   // odd counts split K unevenly and measured slower
     }
     if (waves > C) waves = C;
     // The fused gate|up layer needs gate and up tiles in one workgroup.  It keeps the split of K the plain layer would
