@@ -133,6 +133,21 @@ int w4a8_linear(const uint8_t* x8_dev, int64_t M, int64_t K, int64_t ldx8, const
                 void* workspace_dev, size_t workspace_bytes, void* stream);
 
 /*
+ * w4a8_quantize_act and w4a8_linear in one launch, for few tokens (the memory-bound regime, where a separate
+ * quantization kernel costs a launch and a round trip of the activations): Y = w4a8_linear(w4a8_quantize_act(X)).
+ * Every workgroup quantizes all of X into on-chip memory while its first weights are on their way, with the same
+ * single float32 division and rounding per element (Eq. 13), so the codes, and with them Y, are identical bit for bit
+ * to the two calls.  x_dev: float32 or bf16 [M, K], row stride ldx elements, 16-byte aligned, ldx a multiple of 4
+ * (float32) or 8 (bf16).  x8_out_dev: NULL, or where the FP8 codes are also written, [M, K] bytes with row stride K,
+ * 16-byte aligned.  Tiled layout; 1 <= M <= 16 and M * K <= 65536 (W4A8_ERR_SHAPE otherwise: make the two calls);
+ * everything else as in w4a8_linear.
+ */
+int w4a8_linear_quantize_in(const void* x_dev, w4a8_dtype x_dtype, int64_t M, int64_t K, int64_t ldx,
+                            const float* x_scale_dev, const uint8_t* packed_dev, const float* w_scales_dev, int64_t N,
+                            int32_t group_size, void* y_dev, w4a8_dtype y_dtype, int64_t ldy, uint8_t* x8_out_dev,
+                            void* stream);
+
+/*
  * Same as w4a8_linear for W4A8_LAYOUT_TILED with the launch shape chosen by the caller; for tuning sweeps.
  *   path    0 = skinny (M <= 64), 1 = MFMA-tiled
  *   param0  skinny: n-tiles (of 16 rows) per wave, 1, 2 or 4.   tiled: 16-token blocks per workgroup, 4, 8 or 16

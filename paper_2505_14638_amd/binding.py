@@ -56,6 +56,8 @@ SIGNATURES = {
                                     _c_sz, _c_vp]),
     "w4a8_dpq_calibrate_mse": (_c_i32, [_c_vp, _c_vp, _c_vp, _c_i32, _c_vp, _c_i64, _c_i64, _c_i32, _c_i32, ctypes.c_float,
                                         _c_vp, _c_vp, _c_vp, _c_vp, _c_sz, _c_vp]),
+    "w4a8_linear_quantize_in": (_c_i32, [_c_vp, _c_i32, _c_i64, _c_i64, _c_i64, _c_vp, _c_vp, _c_vp, _c_i64, _c_i32, _c_vp,
+                                         _c_i32, _c_i64, _c_vp, _c_vp]),
     "w4a8_silu_mul": (_c_i32, [_c_vp, _c_i64, _c_i64, _c_i64, _c_vp, _c_i64, _c_vp]),
     "w4a8_linear_fp8_out": (_c_i32, [_c_vp, _c_i64, _c_i64, _c_i64, _c_vp, _c_vp, _c_vp, _c_i64, _c_i32, _c_vp, _c_vp,
                                      _c_i64, _c_vp]),
@@ -178,6 +180,21 @@ def linear(x8: torch.Tensor, x_scale: torch.Tensor, packed: torch.Tensor, w_scal
                              packed.data_ptr(), w_scales.data_ptr(), n, group_size, layout, out.data_ptr(),
                              _dtype_code(out), out.stride(0) if m > 1 else max(n, out.stride(0)), 0, 0, _stream()),
            "w4a8_linear")
+    return out
+
+
+def linear_quantize_in(x, x_scale, packed, w_scales, n, group_size, out=None, out_dtype=torch.bfloat16, x8_out=None):
+    """w4a8_linear_quantize_in: activations x float32/bf16 [M, K] (M <= 16, M * K <= 65536), quantized inside the layer."""
+    m, k = x.shape
+    assert x.stride(1) == 1
+    if out is None:
+        out = torch.empty((m, n), dtype=out_dtype, device=x.device)
+    assert x8_out is None or (x8_out.dtype == torch.uint8 and x8_out.is_contiguous() and tuple(x8_out.shape) == (m, k))
+    _check(lib().w4a8_linear_quantize_in(x.data_ptr(), _dtype_code(x), m, k, x.stride(0) if m > 1 else max(k, x.stride(0)),
+                                         x_scale.data_ptr(), packed.data_ptr(), w_scales.data_ptr(), n, group_size,
+                                         out.data_ptr(), _dtype_code(out), out.stride(0) if m > 1 else max(n, out.stride(0)),
+                                         x8_out.data_ptr() if x8_out is not None else None, _stream()),
+           "w4a8_linear_quantize_in")
     return out
 
 

@@ -144,6 +144,25 @@ int w4a8_linear_two_level(const uint8_t* x8_dev, int64_t M, int64_t K, int64_t l
                                     y_dtype, ldy, 0, 0, 0, w_out_scales_dev, per_channel, MODE_TWO_LEVEL, nullptr, st);
 }
 
+int w4a8_linear_quantize_in(const void* x_dev, w4a8_dtype x_dtype, int64_t M, int64_t K, int64_t ldx,
+                            const float* x_scale_dev, const uint8_t* packed_dev, const float* w_scales_dev, int64_t N,
+                            int32_t group_size, void* y_dev, w4a8_dtype y_dtype, int64_t ldy, uint8_t* x8_out_dev,
+                            void* stream) {
+    if (!valid_dtype(x_dtype) || !valid_dtype(y_dtype)) return W4A8_ERR_DTYPE;
+    if (M < 0 || M > 16) return W4A8_ERR_SHAPE;
+    if (int e = check_weight_shape(N, K, group_size, W4A8_LAYOUT_TILED)) return e;
+    if (M * K > 65536 || ldx < K || ldy < N) return W4A8_ERR_SHAPE;
+    if (!x_dev || !x_scale_dev || !packed_dev || !w_scales_dev || !y_dev) return W4A8_ERR_NULL;
+    if (!aligned16(x_dev) || ldx % (x_dtype == W4A8_F32 ? 4 : 8) != 0 || !aligned16(packed_dev) || !aligned16(w_scales_dev) ||
+        !aligned16(x8_out_dev) || reinterpret_cast<uintptr_t>(x_scale_dev) % 4 ||
+        reinterpret_cast<uintptr_t>(y_dev) % (y_dtype == W4A8_F32 ? 4 : 2))
+        return W4A8_ERR_ALIGN;
+    if (M == 0) return W4A8_OK;
+    return launch_linear_skinny(static_cast<const uint8_t*>(x_dev), M, K, ldx, x_scale_dev, packed_dev, w_scales_dev, N,
+                                group_size, y_dev, y_dtype, ldy, 0, 0, 0, nullptr, 0, MODE_CODE_EXACT, nullptr,
+                                static_cast<hipStream_t>(stream), x_dtype == W4A8_F32 ? 1 : 2, x8_out_dev);
+}
+
 int w4a8_linear_variant(const uint8_t* x8_dev, int64_t M, int64_t K, int64_t ldx8, const float* x_scale_dev,
                         const uint8_t* packed_dev, const float* w_scales_dev, int64_t N, int32_t group_size,
                         void* y_dev, w4a8_dtype y_dtype, int64_t ldy, int32_t path, int32_t param0, int32_t param1,

@@ -43,12 +43,17 @@ constexpr int max_threads(int tiles, bool asym = false) {
 // zero-points; MODE_ASYM_TWO: the same records with FP8-domain scales, the weight operand is
 // nearest_E4M3((code - zero_point) * s8[n,g]), accumulation and output scale as in MODE_TWO_LEVEL.  MODE_POW2: signed codes, the group scale is a power of two that the matrix unit applies itself
 // (block-scaled MFMA); the sum over the wavefront's share of K stays in the MFMA accumulator.
-template <int MT, int NT, int DEPTH, typename OutT, int MODE>
+// XQ != 0 (few tokens, M * K <= 64 KiB): the activation quantization of Eq. 13 is folded in.  `x8` then is the float32
+// (XQ = 1) or bf16 (XQ = 2) activation matrix itself, row stride ldx8 ELEMENTS; every workgroup quantizes all of it into
+// LDS while its first weight loads are in flight (the same single float32 division and rounding per element as the
+// stand-alone kernel), and the main loop takes its activation operands from there.  Workgroup 0 also writes the
+// codes to x8_out (row stride K) when that is not null.
+template <int MT, int NT, int DEPTH, typename OutT, int MODE, int XQ>
 __global__ void __launch_bounds__(max_threads(MT * NT, MODE == MODE_ASYM || MODE == MODE_ASYM_TWO)) linear_skinny_kernel(
     const uint8_t* __restrict__ x8, int M, int64_t ldx8, const float* __restrict__ s_x,
     const uint8_t* __restrict__ packed, const float* __restrict__ scales, int N, int n_tiles, int C, int cpg, int NG,
     OutT* __restrict__ y, int64_t ldy, int cpw, const float* __restrict__ w_out, int per_channel,
-    const float* __restrict__ y_scale) {
+    const float* __restrict__ y_scale, uint8_t* __restrict__ x8_out) {
     constexpr bool ASYM2 = MODE == MODE_ASYM_TWO;                // asymmetric records, two-level bytes, sum kept in the MFMA
     constexpr bool TWO = MODE == MODE_TWO_LEVEL, ASYM = MODE == MODE_ASYM, POW2 = MODE == MODE_POW2;
     constexpr bool OUT_SCALED = TWO || ASYM2;                    // output scaled by s_x * w_out[n]
@@ -75,15 +80,32 @@ __global__ void __launch_bounds__(max_threads(MT * NT, MODE == MODE_ASYM || MODE
         sbase[j] = reinterpret_cast<const uint8_t*>(scales) + (int64_t)t * NG * REC;
     }
     const uint32_t woff = lane * 16, soff = i * 4;
-    const uint8_t* xp[MT];
+    const uint8_t* xp[MT];                                       // XQ == 0: the lane's activation bytes in global memory
+    uint32_t xo[MT];                                             // XQ != 0: their offset in the LDS copy, [M][K] bytes
+    uint8_t* xl = reinterpret_cast<uint8_t*>(red);
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) {
         const int m = min(mt * 16 + i, M - 1);                   // rows past the end reload the last one; not stored
         xp[mt] = x8 + (int64_t)m * ldx8 + kq * 32 + (int64_t)c_begin * 128;
+        xo[mt] = (uint32_t)m * (uint32_t)(C * 128) + kq * 32 + c_begin * 128;
     }
     int g = c_begin / cpg, g_left = cpg - (c_begin - g * cpg);   // current group and chunks left in it
 
-    auto load_chunk = [&](ChunkLoads<MT, NT>& L) {
+    auto load_x = [&](ChunkLoads<MT, NT>& L) {
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) {
+            if (XQ) {
+                L.x[mt][0] = *reinterpret_cast<const uint4*>(xl + xo[mt]);
+                L.x[mt][1] = *reinterpret_cast<const uint4*>(xl + xo[mt] + 16);
+                xo[mt] += 128;
+            } else {
+                L.x[mt][0] = *reinterpret_cast<const uint4*>(xp[mt]);
+                L.x[mt][1] = *reinterpret_cast<const uint4*>(xp[mt] + 16);
+                xp[mt] += 128;
+            }
+        }
+    };
+    auto load_ws = [&](ChunkLoads<MT, NT>& L) {
 #pragma unroll
         for (int j = 0; j < NT; ++j) {
             L.w[j] = *reinterpret_cast<const uint4*>(wbase[j] + woff);
@@ -91,13 +113,11 @@ __global__ void __launch_bounds__(max_threads(MT * NT, MODE == MODE_ASYM || MODE
             L.z[j] = (ASYM || ASYM2) ? (uint32_t)sbase[j][(int64_t)g * REC + 64 + i] : 0u;
             wbase[j] += 1024;
         }
-#pragma unroll
-        for (int mt = 0; mt < MT; ++mt) {
-            L.x[mt][0] = *reinterpret_cast<const uint4*>(xp[mt]);
-            L.x[mt][1] = *reinterpret_cast<const uint4*>(xp[mt] + 16);
-            xp[mt] += 128;
-        }
         if (--g_left == 0) { ++g; g_left = cpg; }
+    };
+    auto load_chunk = [&](ChunkLoads<MT, NT>& L) {
+        load_ws(L);
+        load_x(L);
     };
 
     v4f acc[MT][NT];
@@ -174,9 +194,34 @@ __global__ void __launch_bounds__(max_threads(MT * NT, MODE == MODE_ASYM || MODE
     // chunks, whose refills fall off the end of the wavefront's K range, run in a separate tail.
     {
         ChunkLoads<MT, NT> ring[DEPTH];
+        if (XQ) {
 #pragma unroll
-        for (int d = 0; d < DEPTH; ++d)
-            if (c_begin + d < c_end) load_chunk(ring[d]);
+            for (int d = 0; d < DEPTH; ++d)
+                if (c_begin + d < c_end) load_ws(ring[d]);       // the first weights are on their way ...
+            // ... while the workgroup quantizes the activations (Eq. 13), 16 elements per thread and turn
+            const int k16 = C * 8;                               // 16-element units per row
+            for (int u = threadIdx.x; u < M * k16; u += blockDim.x) {
+                const int m = u / k16, k = (u - m * k16) * 16;
+                float v[16];
+                if (XQ == 1) Load16<float>::load(reinterpret_cast<const float*>(x8) + (int64_t)m * ldx8 + k, v);
+                else Load16<uint16_t>::load(reinterpret_cast<const uint16_t*>(x8) + (int64_t)m * ldx8 + k, v);
+                uint4 o;
+                o.x = quant4(v[0], v[1], v[2], v[3], sx);
+                o.y = quant4(v[4], v[5], v[6], v[7], sx);
+                o.z = quant4(v[8], v[9], v[10], v[11], sx);
+                o.w = quant4(v[12], v[13], v[14], v[15], sx);
+                *reinterpret_cast<uint4*>(xl + (uint32_t)m * (uint32_t)(C * 128) + k) = o;
+                if (x8_out != nullptr && blockIdx.x == 0) *reinterpret_cast<uint4*>(x8_out + (int64_t)m * (C * 128) + k) = o;
+            }
+            __syncthreads();
+#pragma unroll
+            for (int d = 0; d < DEPTH; ++d)
+                if (c_begin + d < c_end) load_x(ring[d]);
+        } else {
+#pragma unroll
+            for (int d = 0; d < DEPTH; ++d)
+                if (c_begin + d < c_end) load_chunk(ring[d]);
+        }
         int c = c_begin;
         for (; c + 2 * DEPTH <= c_end; c += DEPTH) {
 #pragma unroll
@@ -196,6 +241,7 @@ __global__ void __launch_bounds__(max_threads(MT * NT, MODE == MODE_ASYM || MODE
         }
     }
 
+    if (XQ) __syncthreads();                                     // the partial sums below reuse the activations' LDS
     // sum the wavefronts' partials through LDS: red[wave][e = (mt*NT + j)*4 + r][lane]
     constexpr int E = MT * NT * 4;
 #pragma unroll
@@ -247,10 +293,23 @@ int launch_one(const LinearArgs& a, int depth, int waves, hipStream_t st) {
     const int cpw = (a.C + waves - 1) / waves;
     const size_t lds = (size_t)waves * MT * NT * 4 * RED_STRIDE * sizeof(float);
     constexpr int DEEP = (MT * NT == 1) ? 4 : 2;                 // deeper ring while the registers allow it
-#define W4A8_SKINNY(DEPTHV, MODEV)                                                                                        \
-    hipLaunchKernelGGL((linear_skinny_kernel<MT, NT, DEPTHV, OutT, MODEV>), dim3(grid), dim3(waves * 64), lds, st, a.x8, a.M, \
-                       a.ldx8, a.s_x, a.packed, a.scales, a.N, a.n_tiles, a.C, a.cpg, a.NG, static_cast<OutT*>(a.y), a.ldy,   \
-                       cpw, a.w_out, a.per_channel, a.y_scale)
+#define W4A8_SKINNY_X(DEPTHV, MODEV, XQV, LDSV)                                                                              \
+    hipLaunchKernelGGL((linear_skinny_kernel<MT, NT, DEPTHV, OutT, MODEV, XQV>), dim3(grid), dim3(waves * 64), LDSV, st, a.x8,   \
+                       a.M, a.ldx8, a.s_x, a.packed, a.scales, a.N, a.n_tiles, a.C, a.cpg, a.NG, static_cast<OutT*>(a.y), a.ldy, \
+                       cpw, a.w_out, a.per_channel, a.y_scale, a.x8_out)
+#define W4A8_SKINNY(DEPTHV, MODEV) W4A8_SKINNY_X(DEPTHV, MODEV, 0, lds)
+    if (a.xq != 0) {                                             // activation quantization folded in: few tokens, plain outputs
+        if constexpr (MT == 1 && NT <= 2 && sizeof(OutT) > 1) {
+            if (a.mode != MODE_CODE_EXACT) return W4A8_ERR_SHAPE;
+            const size_t xbytes = (size_t)a.M * a.C * 128;
+            const size_t both = lds > xbytes ? lds : xbytes;
+            if (a.xq == 1) W4A8_SKINNY_X(2, MODE_CODE_EXACT, 1, both);
+            else W4A8_SKINNY_X(2, MODE_CODE_EXACT, 2, both);
+            return launch_status();
+        } else {
+            return W4A8_ERR_SHAPE;
+        }
+    }
     if constexpr (sizeof(OutT) == 1) {                           // FP8 output exists for the code-exact mode only
         W4A8_SKINNY(2, MODE_CODE_EXACT);
         return launch_status();
@@ -270,6 +329,7 @@ int launch_one(const LinearArgs& a, int depth, int waves, hipStream_t st) {
     return launch_status();
     }
 #undef W4A8_SKINNY
+#undef W4A8_SKINNY_X
 }
 
 template <int MT, typename OutT>
@@ -298,8 +358,9 @@ int launch_mt(const LinearArgs& a, int mt, int nt, int depth, int waves, hipStre
 int launch_linear_skinny(const uint8_t* x8, int64_t M, int64_t K, int64_t ldx8, const float* s_x,
                          const uint8_t* packed, const float* scales, int64_t N, int32_t G, void* y, w4a8_dtype ydt,
                          int64_t ldy, int nt, int waves, int depth, const float* w_out, int per_channel, int mode,
-                         const float* y_scale, hipStream_t st) {
+                         const float* y_scale, hipStream_t st, int xq, uint8_t* x8_out) {
     if (M < 1 || M > 64) return W4A8_ERR_SHAPE;
+    if (xq != 0 && (M > 16 || M * K > 65536 || mode != MODE_CODE_EXACT)) return W4A8_ERR_SHAPE;
     const int C = (int)(K / 128), cpg = G / 128, NG = (int)(K / G);
     const int n_tiles = (int)((N + 15) / 16);
     const int mt = (M <= 16) ? 1 : (M <= 32) ? 2 : 4;
@@ -311,6 +372,7 @@ int launch_linear_skinny(const uint8_t* x8, int64_t M, int64_t K, int64_t ldx8, 
     //    loads is then 2 KB or more, against 1 KB of nibbles per band), with fewer, longer-running wavefronts.
     const bool wide_many = M > 16 && n_tiles >= 1024;
     if (nt == 0) nt = wide_many ? 4 : ((M > 8 && n_tiles >= 384) || (int64_t)n_tiles * C >= 100000) ? 2 : 1;
+    if (xq != 0 && nt > 2) return W4A8_ERR_SHAPE;
     if (nt != 1 && nt != 2 && nt != 4) return W4A8_ERR_SHAPE;
     if (waves == 0) {
         const int grid = (n_tiles + nt - 1) / nt;
@@ -332,7 +394,8 @@ int launch_linear_skinny(const uint8_t* x8, int64_t M, int64_t K, int64_t ldx8, 
     if (waves < 1 || waves > 16 || waves * mt * nt > 64 || waves * 64 > thread_cap) return W4A8_ERR_SHAPE;
     if (depth == 0) depth = 2;                                   // deeper rings cost occupancy and measured no faster
     if (depth != 2 && depth != 4) return W4A8_ERR_SHAPE;
-    const LinearArgs a{x8, (int)M, ldx8, s_x, packed, scales, (int)N, n_tiles, C, cpg, NG, y, ldy, w_out, per_channel, mode, y_scale};
+    const LinearArgs a{x8, (int)M, ldx8, s_x, packed, scales, (int)N, n_tiles, C, cpg, NG, y, ldy, w_out, per_channel, mode, y_scale,
+                       xq, x8_out};
     if ((int)ydt == YDT_E4M3) {
         if (mode != MODE_CODE_EXACT || !y_scale) return W4A8_ERR_DTYPE;
         return launch_mt<uint8_t>(a, mt, nt, depth, waves, st);

@@ -6,41 +6,6 @@
 namespace w4a8 {
 namespace {
 
-__device__ __forceinline__ uint32_t quant4(float a, float b, float c, float d, float s) {
-    // IEEE float32 division (correctly rounded), then one rounding onto the E4M3 grid
-    uint32_t r = cvt2(a / s, b / s, 0u, false);
-    return cvt2(c / s, d / s, r, true);
-}
-
-template <typename InT> struct Load16;   // 16 consecutive elements -> 16 floats
-template <> struct Load16<float> {
-    static __device__ __forceinline__ void load(const float* p, float (&v)[16]) {
-        const float4* q = reinterpret_cast<const float4*>(p);
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const float4 t = q[i];
-            v[4 * i] = t.x; v[4 * i + 1] = t.y; v[4 * i + 2] = t.z; v[4 * i + 3] = t.w;
-        }
-    }
-    static __device__ __forceinline__ float one(const float* p) { return *p; }
-};
-template <> struct Load16<uint16_t> {
-    static __device__ __forceinline__ void load(const uint16_t* p, float (&v)[16]) {
-        const uint4* q = reinterpret_cast<const uint4*>(p);
-#pragma unroll
-        for (int i = 0; i < 2; ++i) {
-            const uint4 t = q[i];
-            const uint32_t w[4] = {t.x, t.y, t.z, t.w};
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                v[8 * i + 2 * j] = __uint_as_float(w[j] << 16);
-                v[8 * i + 2 * j + 1] = __uint_as_float(w[j] & 0xFFFF0000u);
-            }
-        }
-    }
-    static __device__ __forceinline__ float one(const uint16_t* p) { return bf16_bits_to_f32(*p); }
-};
-
 template <typename InT>
 __global__ void __launch_bounds__(256) quantize_act_vec_kernel(const InT* __restrict__ x, int64_t M, int64_t K16,
                                                                int64_t ldx, const float* __restrict__ scale,

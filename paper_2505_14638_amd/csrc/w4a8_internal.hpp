@@ -37,6 +37,8 @@ struct LinearArgs {
     int per_channel;
     int mode;                        // a WeightMode
     const float* y_scale;            // FP8 output only: the static scale the output is quantized with (Eq. 13)
+    int xq = 0;                      // skinny kernel: x8 is the float32 (1) / bf16 (2) activation matrix, quantized in the kernel
+    uint8_t* x8_out = nullptr;       // ... and where its codes go as well (row stride K), or null
 };
 
 // Output type beyond the public w4a8_dtype values, for the launchers: E4M3 bytes, the bf16 result quantized with the
@@ -68,7 +70,7 @@ int launch_linear_canonical(const uint8_t* x8, int64_t M, int64_t K, int64_t ldx
 int launch_linear_skinny(const uint8_t* x8, int64_t M, int64_t K, int64_t ldx8, const float* s_x,
                          const uint8_t* packed, const float* scales, int64_t N, int32_t G, void* y, w4a8_dtype ydt,
                          int64_t ldy, int nt, int waves, int depth, const float* w_out, int per_channel, int mode,
-                         const float* y_scale, hipStream_t st);
+                         const float* y_scale, hipStream_t st, int xq = 0, uint8_t* x8_out = nullptr);
 // mf = 16-token blocks per workgroup, ks = K-split groups per workgroup, tpw = weight bands per wavefront; 0: chosen
 int launch_linear_mfma_tiled(const uint8_t* x8, int64_t M, int64_t K, int64_t ldx8, const float* s_x,
                              const uint8_t* packed, const float* scales, int64_t N, int32_t G, void* y,

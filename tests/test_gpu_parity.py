@@ -376,3 +376,37 @@ def test_act_scale_calibration_bit_exact(gpu_lib, dtype):
     torch.cuda.synchronize()
     want = o.act_scale_from_amax(np.concatenate([v.ravel() for v in vals]))
     assert got.cpu().numpy()[0] == want
+
+
+@pytest.mark.parametrize("m,k,n,dtype", [(1, 1024, 96, "f32"), (4, 512, 200, "bf16"), (16, 4096, 48, "f32"), (3, 14336, 40, "bf16"),
+                                         (1, 4096, 6144, "bf16"), (4, 14336, 4096, "f32"), (9, 256, 520, "f32")])
+def test_linear_quantize_in_equals_the_two_calls(gpu_lib, m, k, n, dtype):
+    """w4a8_linear_quantize_in: the FP8 codes it produces are the oracle's (Eq. 13), and its output is, bit for bit, that
+    of w4a8_quantize_act followed by w4a8_linear; activations with a row stride, float32 and bf16, both output types."""
+    rng = np.random.default_rng([31, m, k, n])
+    w = syn.make_weights(rng, n, k)
+    x = syn.make_activations(rng, m, k, 0.02, 20.0)
+    x[0, :4] = [1e9, -1e9, 0.0, -0.0]                                     # saturation and signed zero on the way
+    s_x = syn.static_act_scale(x[:, 4:]) if k > 4 else np.float32(1.0)
+    sx_d = dev(np.array([s_x], dtype=np.float32))
+    packed, scales = B.pack_weights(dev(w), 128, B.LAYOUT_TILED)
+    if dtype == "bf16":
+        xb = syn.f32_to_bf16_bits(x)
+        want8 = o.quantize_act(xb, s_x, x_is_bf16_bits=True)
+        wide = torch.zeros((m, k + 64), dtype=torch.bfloat16, device=DEV)
+        wide[:, :k] = torch.from_numpy(xb.view(np.int16)).to(DEV).view(torch.bfloat16)
+    else:
+        want8 = o.quantize_act(x, s_x)
+        wide = torch.zeros((m, k + 64), dtype=torch.float32, device=DEV)
+        wide[:, :k] = torch.from_numpy(x).to(DEV)
+    x_d = wide[:, :k]
+    x8 = B.quantize_act(x_d, sx_d)
+    for out_dtype in (torch.float32, torch.bfloat16):
+        two = B.linear(x8, sx_d, packed, scales, n, 128, B.LAYOUT_TILED, out_dtype=out_dtype)
+        codes = torch.zeros((m, k), dtype=torch.uint8, device=DEV)
+        one = B.linear_quantize_in(x_d, sx_d, packed, scales, n, 128, out_dtype=out_dtype, x8_out=codes)
+        torch.cuda.synchronize()
+        assert np.array_equal(codes.cpu().numpy(), want8)
+        it = torch.int32 if out_dtype == torch.float32 else torch.int16
+        assert torch.equal(one.view(it), two.view(it))
+    assert np.array_equal(x8.cpu().numpy(), want8)
