@@ -517,7 +517,7 @@ def main():
             "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 5),
             "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "fp8_e4m3", "data": "synthetic",
             "config": {"workload": "configs[1]: decode sweep, Llama-3-8B shapes, M in {1,4,16} x 4 (K,N), INT4 g128 "
-                                   "weights, FP8 e4m3 activations, bf16 out; step = 12 x (quantize_act + linear)",
+                                   "weights, FP8 e4m3 activations, bf16 out; step = activation quantization + linear for each of the 12 cases",
                        "weight_sets": args.copies, "launch": "eager" if args.eager else "HIP graph replay",
                        "step_form": "w4a8_linear_quantize_in for the single-token cases, quantize_act + linear for the others"
                                     if fused_sec is not None and fused_sec <= sec else "12 x (quantize_act + linear)",
