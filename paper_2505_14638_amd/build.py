@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libw4a8.so")
 SOURCES = ["api.hip", "quantize_act.hip", "pack_weights.hip", "linear_canonical.hip", "linear_skinny.hip",
-           "linear_mfma.hip", "silu_mul.hip", "probe.hip", "dpq.hip", "hessian_factor.hip"]
+           "linear_mfma.hip", "linear_mfma2d.hip", "silu_mul.hip", "probe.hip", "dpq.hip", "hessian_factor.hip"]
 # packed fp32 instructions are switched off for all device code (scalar fp32 only)
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
@@ -18,7 +18,8 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-u
 # activation operands are live at once and spill
 # dpq.hip: Alg. 1 is specified as a sequence of single float32 operations (its integer decisions must be reproducible
 # bit for bit), so a product must never be contracted with the sum or difference that consumes it
-EXTRA_FLAGS = {"linear_mfma.hip": ["-mllvm", "-disable-machine-sink"], "dpq.hip": ["-ffp-contract=off"]}
+EXTRA_FLAGS = {"linear_mfma.hip": ["-mllvm", "-disable-machine-sink"],
+               "linear_mfma2d.hip": ["-mllvm", "-disable-machine-sink"], "dpq.hip": ["-ffp-contract=off"]}
 
 
 def build(verbose: bool = False) -> str:
