@@ -183,7 +183,7 @@ int w4a8_linear_variant(const uint8_t* x8_dev, int64_t M, int64_t K, int64_t ldx
                                         y_dtype, ldy, param0, param1 & 0xFF, param1 >> 8, nullptr, 0, MODE_CODE_EXACT, nullptr, st);
     if (path == 2 || path == 2 + 16 * MODE_POW2)
         return launch_linear_mfma2d(x8_dev, M, K, ldx8, x_scale_dev, packed_dev, w_scales_dev, N, group_size, y_dev, y_dtype,
-                                    ldy, param0, param1, path >> 4, nullptr, st);
+                                    ldy, param0, param1 & 0xFF, param1 >> 8, path >> 4, nullptr, st);
     return W4A8_ERR_SHAPE;
 }
 

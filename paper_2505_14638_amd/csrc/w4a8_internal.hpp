@@ -77,11 +77,12 @@ int launch_linear_mfma_tiled(const uint8_t* x8, int64_t M, int64_t K, int64_t ld
                              w4a8_dtype ydt, int64_t ldy, int mf, int ks, int tpw, const float* w_out, int per_channel,
                              int mode, const float* y_scale, hipStream_t st);
 // Second tiling of the many-token kernel (2-D grid of wavefronts, expansion shared through LDS).  cfg: a tile of
-// mfma2d_tile; group_m = token blocks per super-column of the block order (0: chosen); mode: MODE_CODE_EXACT or MODE_POW2.
+// mfma2d_tile; group_m = token blocks per super-column of the block order (0: chosen); workgroups = size of the
+// persistent grid (0: one per compute unit); mode: MODE_CODE_EXACT or MODE_POW2.
 bool mfma2d_tile(int cfg, int& bm, int& bn);
 int launch_linear_mfma2d(const uint8_t* x8, int64_t M, int64_t K, int64_t ldx8, const float* s_x, const uint8_t* packed,
                          const float* scales, int64_t N, int32_t G, void* y, w4a8_dtype ydt, int64_t ldy, int cfg,
-                         int group_m, int mode, const float* y_scale, hipStream_t st);
+                         int group_m, int workgroups, int mode, const float* y_scale, hipStream_t st);
 // q_scale != nullptr: h is E4M3 bytes, the bf16 result quantized with *q_scale (Eq. 13)
 int launch_hessian_accumulate(const void* x, w4a8_dtype dt, int64_t T, int64_t K, int64_t ldx, float* h, hipStream_t st);
 int launch_gar_permutation(const float* hdiag, int64_t K, int32_t G, int32_t* perm, hipStream_t st);
