@@ -109,7 +109,13 @@ int w4a8_pack_weights(const void* src_dev, w4a8_src src_kind, const float* src_s
                       int64_t N, int64_t K, int32_t group_size, w4a8_layout layout,
                       uint8_t* packed_dev, float* scales_dev, void* stream);
 
-/* Bytes of scratch w4a8_linear needs for these sizes (currently always 0: reductions stay on chip). */
+/*
+ * Bytes of device scratch with which w4a8_linear runs these sizes fastest (tiled layout); 0 for most shapes.
+ * Non-zero where the layer has few output tiles and a deep K (Sec. 1: between the memory-bound and the compute-bound
+ * regime -- some 64 to 512 tokens on the layers of a decoder): K is then multiplied in several ranges by different
+ * workgroups, whose float32 partial sums (ranges x M x round_up(N, 64) floats) pass through the scratch and are
+ * added in the order of the ranges by a second launch, so the result does not depend on timing.
+ */
 size_t w4a8_linear_workspace_bytes(int64_t M, int64_t K, int64_t N, int32_t group_size);
 
 /*
@@ -122,7 +128,10 @@ size_t w4a8_linear_workspace_bytes(int64_t M, int64_t K, int64_t N, int32_t grou
  *   x_scale_dev   one float32 on the device: s_x
  *   packed_dev, w_scales_dev   as written by w4a8_pack_weights for the same N, K, group_size, layout
  *   y_dev         out [M, N], float32 or bf16 (round to nearest even), row stride ldy elements
- *   workspace_dev may be NULL when w4a8_linear_workspace_bytes() is 0
+ *   workspace_dev NULL: the layer runs without scratch (slower where w4a8_linear_workspace_bytes() is not 0, same
+ *                 tolerance).  Not NULL: 16-byte aligned device memory of workspace_bytes bytes, which must be at least
+ *                 w4a8_linear_workspace_bytes() for these sizes (W4A8_ERR_WORKSPACE otherwise); its contents are
+ *                 scratch, owned by the call until the stream work completes.
  * Kernel choice depends only on (M, K, N, layout): up to 32 tokens (64 for K >= 8192 with N <= 8192) take the
  * bandwidth-bound skinny path, larger M the MFMA-tiled path; CANONICAL always takes a plain reference-speed kernel.
  * M == 0 is a no-op.
@@ -146,22 +155,6 @@ int w4a8_linear_quantize_in(const void* x_dev, w4a8_dtype x_dtype, int64_t M, in
                             const float* x_scale_dev, const uint8_t* packed_dev, const float* w_scales_dev, int64_t N,
                             int32_t group_size, void* y_dev, w4a8_dtype y_dtype, int64_t ldy, uint8_t* x8_out_dev,
                             void* stream);
-
-/*
- * Same as w4a8_linear for W4A8_LAYOUT_TILED with the launch shape chosen by the caller; for tuning sweeps.
- *   path    0 = skinny (M <= 64), 1 = MFMA-tiled
- *   param0  skinny: n-tiles (of 16 rows) per wave, 1, 2 or 4.   tiled: 16-token blocks per workgroup, 4, 8 or 16
- *           (the workgroup covers 16 * param0 tokens); 0 = chosen from the shape
- *   param1  skinny: waves per workgroup (K is split across them), 1..16, plus 256 * chunks in flight per wave
- *           (0 auto, 2 or 4).   tiled: K-split groups per workgroup (1, 2 or 4; 0 = chosen) plus 256 * weight bands
- *           per wavefront (1 or 2; 0 = chosen): the workgroup covers 128 * bands / groups channels.  Built shapes
- *           (blocks, groups, bands): (16,1,1) (8,1,1) (8,2,1) (4,1,1) (4,2,1) (4,4,1) (16,1,2)
- * Unsupported combinations return W4A8_ERR_SHAPE.
- */
-int w4a8_linear_variant(const uint8_t* x8_dev, int64_t M, int64_t K, int64_t ldx8, const float* x_scale_dev,
-                        const uint8_t* packed_dev, const float* w_scales_dev, int64_t N, int32_t group_size,
-                        void* y_dev, w4a8_dtype y_dtype, int64_t ldy, int32_t path, int32_t param0,
-                        int32_t param1, void* stream);
 
 /*
  * Test hook for Eq. 10: writes the E4M3 byte the fused kernels feed to the matrix unit for every code,
@@ -355,19 +348,6 @@ int w4a8_silu_mul_quantize(const void* gu_dev, int64_t M, int64_t F, int64_t ldg
 int w4a8_linear_silu_mul_fp8_out(const uint8_t* x8_dev, int64_t M, int64_t K, int64_t ldx8, const float* x_scale_dev,
                                  const uint8_t* packed_dev, const float* w_scales_dev, int64_t F, int32_t group_size,
                                  const float* h_scale_dev, uint8_t* h8_dev, int64_t ldh8, void* stream);
-
-/*
- * Measurement aids (not part of the layer): the two hardware ceilings the kernels are compared with, measured
- * on the device at hand.  Time the calls with events on `stream`.
- *   w4a8_probe_stream_read  loads every 16 bytes of buf_dev[0 .. bytes) once; bytes / time is the achievable HBM
- *                           read bandwidth when `bytes` is far larger than the caches.  sink_dev: 4 bytes, scratch.
- *   w4a8_probe_mfma_e4m3    issues back-to-back 16x16x128 E4M3 MFMAs on independent accumulators from two
- *                           workgroups per compute unit; w4a8_probe_mfma_flop(iters) / time is the achievable dense
- *                           FP8 MFMA rate.  sink_dev: 4 bytes, scratch.  1 <= iters <= 2^20.
- */
-int w4a8_probe_stream_read(const void* buf_dev, size_t bytes, uint32_t* sink_dev, void* stream);
-int w4a8_probe_mfma_e4m3(int32_t iters, float* sink_dev, void* stream);
-double w4a8_probe_mfma_flop(int32_t iters);
 
 /* Static, NUL-terminated description of a status value. */
 const char* w4a8_status_string(int status);

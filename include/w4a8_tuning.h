@@ -1,0 +1,63 @@
+/*
+ * w4a8_tuning.h -- tuning and measurement entry points of libw4a8.so.  They are not steps of the layer: the calls of
+ * the W4A8 linear layer proper are declared in w4a8.h, whose conventions (status codes, device pointers, streams)
+ * apply here too.
+ */
+#ifndef W4A8_TUNING_H
+#define W4A8_TUNING_H
+
+#include "w4a8.h"
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/*
+ * Same as w4a8_linear for W4A8_LAYOUT_TILED with the launch shape chosen by the caller; for tuning sweeps.
+ *   path    0 = skinny (M <= 64), 1 = MFMA-tiled (first tiling: one weight band per wavefront),
+ *           2 = MFMA-tiled, second tiling (2-D grid of wavefronts, persistent workgroups); 2 + 48 = the same through the
+ *           block-scaled MFMA (power-of-two group scales, as w4a8_linear_pow2)
+ *   param0  skinny: n-tiles (of 16 rows) per wave, 1, 2 or 4.   tiled: 16-token blocks per workgroup, 4, 8 or 16
+ *           (the workgroup covers 16 * param0 tokens); 0 = chosen from the shape
+ *   param1  skinny: waves per workgroup (K is split across them), 1..16, plus 256 * chunks in flight per wave
+ *           (0 auto, 2 or 4).   tiled: K-split groups per workgroup (1, 2 or 4; 0 = chosen) plus 256 * weight bands
+ *           per wavefront (1 or 2; 0 = chosen): the workgroup covers 128 * bands / groups channels.  Built shapes
+ *           (blocks, groups, bands): (16,1,1) (8,1,1) (8,2,1) (4,1,1) (4,2,1) (4,4,1) (16,1,2)
+ *           path 2: param0 = workgroup tile, 0: 512 x 128, 1: 256 x 256, 2: 256 x 128, 3: 128 x 256, 5: 128 x 128 tokens x
+ *           channels (eight wavefronts), 4: 256 x 128 with four wavefronts (two workgroups per compute unit);
+ *           param1 = token blocks per super-column of the tile order (0 = chosen) plus 256 * workgroups (0 = chosen)
+ * Unsupported combinations return W4A8_ERR_SHAPE.
+ */
+int w4a8_linear_variant(const uint8_t* x8_dev, int64_t M, int64_t K, int64_t ldx8, const float* x_scale_dev,
+                        const uint8_t* packed_dev, const float* w_scales_dev, int64_t N, int32_t group_size,
+                        void* y_dev, w4a8_dtype y_dtype, int64_t ldy, int32_t path, int32_t param0,
+                        int32_t param1, void* stream);
+
+/*
+ * The second tiling with K multiplied in `ksplit` ranges by different workgroups (what w4a8_linear does with a
+ * workspace on the shapes w4a8_linear_workspace_bytes() names), tile and split chosen by the caller.  workspace_dev:
+ * 16-byte aligned, at least ksplit * M * round_up(N, 64) * 4 bytes (W4A8_ERR_WORKSPACE otherwise).  tile as param0 of
+ * path 2 above; 2 <= ksplit <= K / 128.
+ */
+int w4a8_linear_splitk_variant(const uint8_t* x8_dev, int64_t M, int64_t K, int64_t ldx8, const float* x_scale_dev,
+                               const uint8_t* packed_dev, const float* w_scales_dev, int64_t N, int32_t group_size,
+                               void* y_dev, w4a8_dtype y_dtype, int64_t ldy, int32_t tile, int32_t ksplit,
+                               void* workspace_dev, size_t workspace_bytes, void* stream);
+
+/*
+ * Measurement aids (not part of the layer): the two hardware ceilings the kernels are compared with, measured
+ * on the device at hand.  Time the calls with events on `stream`.
+ *   w4a8_probe_stream_read  loads every 16 bytes of buf_dev[0 .. bytes) once; bytes / time is the achievable HBM
+ *                           read bandwidth when `bytes` is far larger than the caches.  sink_dev: 4 bytes, scratch.
+ *   w4a8_probe_mfma_e4m3    issues back-to-back 16x16x128 E4M3 MFMAs on independent accumulators from two
+ *                           workgroups per compute unit; w4a8_probe_mfma_flop(iters) / time is the achievable dense
+ *                           FP8 MFMA rate.  sink_dev: 4 bytes, scratch.  1 <= iters <= 2^20.
+ */
+int w4a8_probe_stream_read(const void* buf_dev, size_t bytes, uint32_t* sink_dev, void* stream);
+int w4a8_probe_mfma_e4m3(int32_t iters, float* sink_dev, void* stream);
+double w4a8_probe_mfma_flop(int32_t iters);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* W4A8_TUNING_H */

@@ -33,6 +33,8 @@ SIGNATURES = {
                              _c_i32, _c_i64, _c_vp, _c_sz, _c_vp]),
     "w4a8_linear_variant": (_c_i32, [_c_vp, _c_i64, _c_i64, _c_i64, _c_vp, _c_vp, _c_vp, _c_i64, _c_i32, _c_vp,
                                      _c_i32, _c_i64, _c_i32, _c_i32, _c_i32, _c_vp]),
+    "w4a8_linear_splitk_variant": (_c_i32, [_c_vp, _c_i64, _c_i64, _c_i64, _c_vp, _c_vp, _c_vp, _c_i64, _c_i32, _c_vp,
+                                            _c_i32, _c_i64, _c_i32, _c_i32, _c_vp, _c_sz, _c_vp]),
     "w4a8_dequant_weights": (_c_i32, [_c_vp, _c_i64, _c_i64, _c_i32, _c_vp, _c_vp]),
     "w4a8_linear_two_level": (_c_i32, [_c_vp, _c_i64, _c_i64, _c_i64, _c_vp, _c_vp, _c_vp, _c_vp, _c_i32, _c_i64, _c_i32,
                                        _c_vp, _c_i32, _c_i64, _c_vp]),
@@ -169,17 +171,34 @@ def pack_weights(src: torch.Tensor, group_size: int, layout: int, src_scales: to
     return packed[:nbytes], scales[:nscales]
 
 
+def linear_workspace_bytes(m: int, k: int, n: int, group_size: int) -> int:
+    return lib().w4a8_linear_workspace_bytes(m, k, n, group_size)
+
+
 def linear(x8: torch.Tensor, x_scale: torch.Tensor, packed: torch.Tensor, w_scales: torch.Tensor, n: int,
            group_size: int, layout: int, out_dtype: torch.dtype = torch.bfloat16,
-           out: torch.Tensor | None = None) -> torch.Tensor:
+           out: torch.Tensor | None = None, workspace: torch.Tensor | None = None) -> torch.Tensor:
+    """w4a8_linear; `workspace`: a uint8 device tensor of at least linear_workspace_bytes(m, k, n, group_size) bytes, or
+    None to run without scratch."""
     m, k = x8.shape
     assert x8.dtype == torch.uint8 and x8.stride(1) == 1
     if out is None:
         out = torch.empty((m, n), dtype=out_dtype, device=x8.device)
+    ws_ptr, ws_bytes = (workspace.data_ptr(), workspace.numel() * workspace.element_size()) if workspace is not None else (0, 0)
     _check(lib().w4a8_linear(x8.data_ptr(), m, k, x8.stride(0) if m > 1 else max(k, x8.stride(0)), x_scale.data_ptr(),
                              packed.data_ptr(), w_scales.data_ptr(), n, group_size, layout, out.data_ptr(),
-                             _dtype_code(out), out.stride(0) if m > 1 else max(n, out.stride(0)), 0, 0, _stream()),
-           "w4a8_linear")
+                             _dtype_code(out), out.stride(0) if m > 1 else max(n, out.stride(0)), ws_ptr, ws_bytes,
+                             _stream()), "w4a8_linear")
+    return out
+
+
+def linear_splitk_variant(x8, x_scale, packed, w_scales, n, group_size, out, tile: int, ksplit: int, workspace: torch.Tensor):
+    m, k = x8.shape
+    _check(lib().w4a8_linear_splitk_variant(x8.data_ptr(), m, k, x8.stride(0) if m > 1 else max(k, x8.stride(0)),
+                                            x_scale.data_ptr(), packed.data_ptr(), w_scales.data_ptr(), n, group_size,
+                                            out.data_ptr(), _dtype_code(out), out.stride(0) if m > 1 else max(n, out.stride(0)),
+                                            tile, ksplit, workspace.data_ptr(), workspace.numel() * workspace.element_size(),
+                                            _stream()), "w4a8_linear_splitk_variant")
     return out
 
 

@@ -9,6 +9,10 @@ namespace {
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 inline bool valid_dtype(int d) { return d == W4A8_F32 || d == W4A8_BF16; }
 inline bool valid_layout(int l) { return l == W4A8_LAYOUT_CANONICAL || l == W4A8_LAYOUT_TILED; }
+// Few tokens: the skinny kernel streams the weights once with K split across wavefronts.  From 33 tokens on the
+// MFMA-tiled kernels (activations staged once per workgroup, nibble expansion shared by several token blocks) are
+// faster, except for deep, narrow layers, where the skinny kernel's finer split of K still wins up to 64 tokens.
+inline bool takes_skinny_path(int64_t M, int64_t K, int64_t N) { return M <= 32 || (M <= 64 && K >= 8192 && N <= 8192); }
 constexpr int64_t DIM_MAX = (int64_t)1 << 30;      // keeps every 32-bit tile / chunk index in range
 
 int check_nk(int64_t N, int64_t K, int layout) {
@@ -95,30 +99,40 @@ int w4a8_pack_weights(const void* src_dev, w4a8_src src_kind, const float* src_s
                                static_cast<hipStream_t>(stream));
 }
 
-size_t w4a8_linear_workspace_bytes(int64_t, int64_t, int64_t, int32_t) { return 0; }
+size_t w4a8_linear_workspace_bytes(int64_t M, int64_t K, int64_t N, int32_t group_size) {
+    if (M < 1 || M > DIM_MAX || check_weight_shape(N, K, group_size, W4A8_LAYOUT_TILED) != W4A8_OK) return 0;
+    if (takes_skinny_path(M, K, N)) return 0;
+    int cfg, ksplit;
+    mfma2d_choose_ksplit(M, K, N, cfg, ksplit);
+    return mfma2d_splitk_bytes(M, N, ksplit);
+}
 
 int w4a8_linear(const uint8_t* x8_dev, int64_t M, int64_t K, int64_t ldx8, const float* x_scale_dev,
                 const uint8_t* packed_dev, const float* w_scales_dev, int64_t N, int32_t group_size,
                 w4a8_layout layout, void* y_dev, w4a8_dtype y_dtype, int64_t ldy, void* workspace_dev,
                 size_t workspace_bytes, void* stream) {
-    (void)workspace_dev;
-    (void)workspace_bytes;
     if (!valid_dtype(y_dtype)) return W4A8_ERR_DTYPE;
     if (int e = check_linear(x8_dev, M, K, ldx8, x_scale_dev, packed_dev, w_scales_dev, N, group_size, layout, y_dev,
                              y_dtype, ldy))
         return e;
+    int ksplit = 0, split_cfg = 0;
+    if (workspace_dev != nullptr) {
+        if (!aligned16(workspace_dev)) return W4A8_ERR_ALIGN;
+        const size_t need = layout == W4A8_LAYOUT_TILED ? w4a8_linear_workspace_bytes(M, K, N, group_size) : 0;
+        if (workspace_bytes < need) return W4A8_ERR_WORKSPACE;
+        if (need > 0) mfma2d_choose_ksplit(M, K, N, split_cfg, ksplit);
+    }
     if (M == 0) return W4A8_OK;
     hipStream_t st = static_cast<hipStream_t>(stream);
     if (layout == W4A8_LAYOUT_CANONICAL)
         return launch_linear_canonical(x8_dev, M, K, ldx8, x_scale_dev, packed_dev, w_scales_dev, N, group_size, y_dev,
                                        y_dtype, ldy, st);
-    // Few tokens: the skinny kernel streams the weights once with K split across wavefronts.  From 33 tokens on the
-    // MFMA-tiled kernel (activations staged once per workgroup, nibble expansion shared by several token blocks) is
-    // faster, except for deep, narrow layers, where the skinny kernel's finer split of K still wins up to 64 tokens.
-    const bool deep_narrow = K >= 8192 && N <= 8192;
-    if (M <= 32 || (M <= 64 && deep_narrow))
+    if (takes_skinny_path(M, K, N))
         return launch_linear_skinny(x8_dev, M, K, ldx8, x_scale_dev, packed_dev, w_scales_dev, N, group_size, y_dev,
                                     y_dtype, ldy, 0, 0, 0, nullptr, 0, MODE_CODE_EXACT, nullptr, st);
+    if (ksplit > 1)                                              // few tiles, deep K: K ranges across workgroups
+        return launch_linear_mfma2d(x8_dev, M, K, ldx8, x_scale_dev, packed_dev, w_scales_dev, N, group_size, y_dev, y_dtype,
+                                    ldy, split_cfg, 0, 0, MODE_CODE_EXACT, nullptr, st, ksplit, workspace_dev);
     return launch_linear_mfma_tiled(x8_dev, M, K, ldx8, x_scale_dev, packed_dev, w_scales_dev, N, group_size, y_dev,
                                     y_dtype, ldy, 0, 0, 0, nullptr, 0, MODE_CODE_EXACT, nullptr, st);
 }
@@ -136,8 +150,7 @@ int w4a8_linear_two_level(const uint8_t* x8_dev, int64_t M, int64_t K, int64_t l
     if (per_channel != 0 && per_channel != 1) return W4A8_ERR_DTYPE;
     if (M == 0) return W4A8_OK;
     hipStream_t st = static_cast<hipStream_t>(stream);
-    const bool deep_narrow = K >= 8192 && N <= 8192;             // same kernel choice as w4a8_linear
-    if (M <= 32 || (M <= 64 && deep_narrow))
+    if (takes_skinny_path(M, K, N))                              // same kernel choice as w4a8_linear
         return launch_linear_skinny(x8_dev, M, K, ldx8, x_scale_dev, packed_dev, w_scales8_dev, N, group_size, y_dev,
                                     y_dtype, ldy, 0, 0, 0, w_out_scales_dev, per_channel, MODE_TWO_LEVEL, nullptr, st);
     return launch_linear_mfma_tiled(x8_dev, M, K, ldx8, x_scale_dev, packed_dev, w_scales8_dev, N, group_size, y_dev,
@@ -187,6 +200,22 @@ int w4a8_linear_variant(const uint8_t* x8_dev, int64_t M, int64_t K, int64_t ldx
     return W4A8_ERR_SHAPE;
 }
 
+int w4a8_linear_splitk_variant(const uint8_t* x8_dev, int64_t M, int64_t K, int64_t ldx8, const float* x_scale_dev,
+                               const uint8_t* packed_dev, const float* w_scales_dev, int64_t N, int32_t group_size,
+                               void* y_dev, w4a8_dtype y_dtype, int64_t ldy, int32_t tile, int32_t ksplit,
+                               void* workspace_dev, size_t workspace_bytes, void* stream) {
+    if (!valid_dtype(y_dtype)) return W4A8_ERR_DTYPE;
+    if (int e = check_linear(x8_dev, M, K, ldx8, x_scale_dev, packed_dev, w_scales_dev, N, group_size,
+                             W4A8_LAYOUT_TILED, y_dev, y_dtype, ldy))
+        return e;
+    if (ksplit < 2 || ksplit > K / 128 || M < 1) return W4A8_ERR_SHAPE;
+    if (!workspace_dev) return W4A8_ERR_NULL;
+    if (!aligned16(workspace_dev)) return W4A8_ERR_ALIGN;
+    if (workspace_bytes < mfma2d_splitk_bytes(M, N, ksplit)) return W4A8_ERR_WORKSPACE;
+    return launch_linear_mfma2d(x8_dev, M, K, ldx8, x_scale_dev, packed_dev, w_scales_dev, N, group_size, y_dev, y_dtype, ldy,
+                                tile, 0, 0, MODE_CODE_EXACT, nullptr, static_cast<hipStream_t>(stream), ksplit, workspace_dev);
+}
+
 int w4a8_dequant_weights(const uint8_t* packed_dev, int64_t N, int64_t K, w4a8_layout layout, uint8_t* w8_dev,
                          void* stream) {
     if (int e = check_nk(N, K, layout)) return e;
@@ -213,8 +242,7 @@ int w4a8_linear_pow2(const uint8_t* x8_dev, int64_t M, int64_t K, int64_t ldx8, 
         return e;
     if (M == 0) return W4A8_OK;
     hipStream_t st = static_cast<hipStream_t>(stream);
-    const bool deep_narrow = K >= 8192 && N <= 8192;             // same kernel choice as w4a8_linear
-    if (M <= 32 || (M <= 64 && deep_narrow))
+    if (takes_skinny_path(M, K, N))                              // same kernel choice as w4a8_linear
         return launch_linear_skinny(x8_dev, M, K, ldx8, x_scale_dev, packed_dev, w_scales_dev, N, group_size, y_dev,
                                     y_dtype, ldy, 0, 0, 0, nullptr, 0, MODE_POW2, nullptr, st);
     return launch_linear_mfma_tiled(x8_dev, M, K, ldx8, x_scale_dev, packed_dev, w_scales_dev, N, group_size, y_dev,
@@ -232,8 +260,7 @@ int w4a8_linear_fp8_out(const uint8_t* x8_dev, int64_t M, int64_t K, int64_t ldx
     if (M == 0) return W4A8_OK;
     hipStream_t st = static_cast<hipStream_t>(stream);
     const w4a8_dtype ydt = static_cast<w4a8_dtype>(YDT_E4M3);
-    const bool deep_narrow = K >= 8192 && N <= 8192;             // same kernel choice as w4a8_linear
-    if (M <= 32 || (M <= 64 && deep_narrow))
+    if (takes_skinny_path(M, K, N))                              // same kernel choice as w4a8_linear
         return launch_linear_skinny(x8_dev, M, K, ldx8, x_scale_dev, packed_dev, w_scales_dev, N, group_size, y8_dev, ydt,
                                     ldy8, 0, 0, 0, nullptr, 0, MODE_CODE_EXACT, y_scale_dev, st);
     return launch_linear_mfma_tiled(x8_dev, M, K, ldx8, x_scale_dev, packed_dev, w_scales_dev, N, group_size, y8_dev, ydt,
@@ -254,8 +281,7 @@ int w4a8_linear_silu_mul_fp8_out(const uint8_t* x8_dev, int64_t M, int64_t K, in
     hipStream_t st = static_cast<hipStream_t>(stream);
     const w4a8_dtype ydt = static_cast<w4a8_dtype>(YDT_SILU_E4M3);
     const int64_t N = 2 * F;
-    const bool deep_narrow = K >= 8192 && N <= 8192;             // same kernel choice as w4a8_linear
-    if (M <= 32 || (M <= 64 && deep_narrow))
+    if (takes_skinny_path(M, K, N))                              // same kernel choice as w4a8_linear
         return launch_linear_skinny(x8_dev, M, K, ldx8, x_scale_dev, packed_dev, w_scales_dev, N, group_size, h8_dev, ydt,
                                     ldh8, 0, 0, 0, nullptr, 0, MODE_CODE_EXACT, h_scale_dev, st);
     return launch_linear_mfma_tiled(x8_dev, M, K, ldx8, x_scale_dev, packed_dev, w_scales_dev, N, group_size, h8_dev, ydt,
@@ -291,8 +317,7 @@ int w4a8_linear_asym(const uint8_t* x8_dev, int64_t M, int64_t K, int64_t ldx8, 
         return e;
     if (M == 0) return W4A8_OK;
     hipStream_t st = static_cast<hipStream_t>(stream);
-    const bool deep_narrow = K >= 8192 && N <= 8192;             // same kernel choice as w4a8_linear
-    if (M <= 32 || (M <= 64 && deep_narrow))
+    if (takes_skinny_path(M, K, N))                              // same kernel choice as w4a8_linear
         return launch_linear_skinny(x8_dev, M, K, ldx8, x_scale_dev, packed_dev, params, N, group_size, y_dev, y_dtype, ldy,
                                     0, 0, 0, nullptr, 0, MODE_ASYM, nullptr, st);
     return launch_linear_mfma_tiled(x8_dev, M, K, ldx8, x_scale_dev, packed_dev, params, N, group_size, y_dev, y_dtype, ldy,
@@ -313,8 +338,7 @@ int w4a8_linear_asym_two_level(const uint8_t* x8_dev, int64_t M, int64_t K, int6
     if (per_channel != 0 && per_channel != 1) return W4A8_ERR_DTYPE;
     if (M == 0) return W4A8_OK;
     hipStream_t st = static_cast<hipStream_t>(stream);
-    const bool deep_narrow = K >= 8192 && N <= 8192;             // same kernel choice as w4a8_linear
-    if (M <= 32 || (M <= 64 && deep_narrow))
+    if (takes_skinny_path(M, K, N))                              // same kernel choice as w4a8_linear
         return launch_linear_skinny(x8_dev, M, K, ldx8, x_scale_dev, packed_dev, params, N, group_size, y_dev, y_dtype, ldy,
                                     0, 0, 0, w_out_scales_dev, per_channel, MODE_ASYM_TWO, nullptr, st);
     return launch_linear_mfma_tiled(x8_dev, M, K, ldx8, x_scale_dev, packed_dev, params, N, group_size, y_dev, y_dtype, ldy,

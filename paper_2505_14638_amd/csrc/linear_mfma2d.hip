@@ -73,7 +73,8 @@ template <typename OutT, int WGM, int WGN, int WM, int WN, int MODE>
 __global__ void __launch_bounds__(64 * WGM * WGN, 2) linear_mfma2d_kernel(
     const uint8_t* __restrict__ x8, int M, int64_t ldx8, const float* __restrict__ s_x,
     const uint8_t* __restrict__ packed, const float* __restrict__ scales, int N, int n_tiles, int C, int cpg, int NG,
-    OutT* __restrict__ y, int64_t ldy, int grid_m, int grid_n, int group_m, const float* __restrict__ y_scale) {
+    OutT* __restrict__ y, int64_t ldy, int grid_m, int grid_n, int group_m, const float* __restrict__ y_scale, int ksplit,
+    int cps, int64_t split_stride) {
     constexpr int WAVES = WGM * WGN, THREADS = 64 * WAVES;
     static_assert(WAVES == 8 || WAVES == 4, "one workgroup of eight wavefronts per compute unit, or two of four");
     static_assert(WN % WGM == 0, "every wavefront expands whole bands of its own");
@@ -112,15 +113,18 @@ __global__ void __launch_bounds__(64 * WGM * WGN, 2) linear_mfma2d_kernel(
 
     // This workgroup's tiles: consecutive workgroup ids go round-robin to the eight XCDs; XCD x owns the contiguous range
     // [x * per_xcd, (x + 1) * per_xcd) of the virtual tile order, and its workgroups take every nx-th tile of it.
-    const int total = grid_m * grid_n;
+    // With ksplit > 1 a unit of work is (K range, tile): unit u multiplies chunks [u / tiles * cps, + cps) of tile
+    // u % tiles and stores its float32 partial sums, unscaled, at y + (u / tiles) * split_stride (the workspace).
+    const int tiles = grid_m * grid_n;
+    const int total = tiles * ksplit;
     const int nx = gridDim.x / XCDS2;
     const int per_xcd = (total + XCDS2 - 1) / XCDS2;
     const int v_end = min(total, (int)(blockIdx.x % XCDS2 + 1) * per_xcd);
     int v = (int)(blockIdx.x % XCDS2) * per_xcd + (int)(blockIdx.x / XCDS2);
     if (v >= v_end) return;
 
-    // state of the tile whose loads are being issued (the main loop's tile)
-    int m0 = 0, bn = 0;
+    // state of the unit whose loads are being issued (the main loop's unit)
+    int m0 = 0, bn = 0, split = 0, c_begin = 0, c_end = C;
     const uint8_t* sbase[WN];                                    // scales of the wavefront's bands: + g * 64 + i * 4
     const uint8_t* ebase[EPW];                                   // nibbles of the bands it expands: + c * 1024 + lane * 16
     const uint8_t* xrow0 = x8;
@@ -130,7 +134,11 @@ __global__ void __launch_bounds__(64 * WGM * WGN, 2) linear_mfma2d_kernel(
     // row r (0..15) sits in page r / 8 at slot (r % 8) * 8 + (sg ^ (r % 8) ^ (r / 8)): one copy instruction fills a
     // page from eight whole 128-byte row segments, and the two ds_read_b128 of an operand are free of bank conflicts.
     // A wavefront copies pages wave * DPW .. + DPW - 1; page d holds rows 8 (d % 2) .. + 7 of block d / 2.
-    auto set_tile = [&](int vt) {
+    auto set_tile = [&](int unit) {
+        split = unit / tiles;
+        const int vt = unit - split * tiles;
+        c_begin = split * cps;
+        c_end = min(C, c_begin + cps);
         const int group = vt / (group_m * grid_n);
         const int first_m = group * group_m;
         const int rows_in_group = min(group_m, grid_m - first_m);
@@ -190,15 +198,15 @@ __global__ void __launch_bounds__(64 * WGM * WGN, 2) linear_mfma2d_kernel(
     // expand cur.raw (chunk c + 1) into the other stage, copy the activations of chunk c + 1 there, and load the scales
     // of chunk c + 1 and the nibbles of chunk c + 2 into nxt.
     auto chunk = [&](int c, Set& cur, Set& nxt) {
-        const int buf = c & 1;
+        const int buf = (c - c_begin) & 1;
         // what the previous chunk loaded is touched here, straight after the wait for all loads at that chunk's end
 #pragma unroll
         for (int j = 0; j < WN; ++j) asm volatile("" : "+v"(cur.s[j]));
 #pragma unroll
         for (int t = 0; t < EPW; ++t) asm volatile("" : "+v"(cur.raw[t]));   // as one 128-bit value: it stays in the registers it was loaded into
-        const int cn = min(c + 1, C - 1);                        // after the last chunk: copied again, never read
-        if (c + 1 < C) load_scales(nxt, c + 1);
-        if (c + 2 < C) load_raw(nxt, c + 2);
+        const int cn = min(c + 1, c_end - 1);                    // after the last chunk: copied again, never read
+        if (c + 1 < c_end) load_scales(nxt, c + 1);
+        if (c + 2 < c_end) load_raw(nxt, c + 2);
 
         __builtin_amdgcn_s_setprio(1);
         // the wavefront's weight operands of this chunk
@@ -292,13 +300,14 @@ __global__ void __launch_bounds__(64 * WGM * WGN, 2) linear_mfma2d_kernel(
     u32x4 raw0[EPW];
     auto start_issue = [&]() {
 #pragma unroll
-        for (int q = 0; q < DPW; ++q) stage_page(0, 0, q);
+        for (int q = 0; q < DPW; ++q) stage_page(c_begin, 0, q);
 #pragma unroll
-        for (int t = 0; t < EPW; ++t) raw0[t] = *reinterpret_cast<const W4A8_GLOBAL u32x4*>(uniform(ebase[t]) + woff);
-        load_scales(sa, 0);
+        for (int t = 0; t < EPW; ++t)
+            raw0[t] = *reinterpret_cast<const W4A8_GLOBAL u32x4*>(uniform(ebase[t] + (int64_t)c_begin * 1024) + woff);
+        load_scales(sa, c_begin);
 #pragma unroll
         for (int t = 0; t < EPW; ++t) sa.raw[t] = u32x4{0u, 0u, 0u, 0u};
-        if (1 < C) load_raw(sa, 1);
+        if (c_begin + 1 < c_end) load_raw(sa, c_begin + 1);
     };
     // second half: chunk 0's weight operands, expanded from registers, into stage 0; then everything has landed
     auto start_finish = [&]() {
@@ -312,13 +321,14 @@ __global__ void __launch_bounds__(64 * WGM * WGN, 2) linear_mfma2d_kernel(
         lds_dma_wait_all();
     };
 
-    const float sx = *s_x;
+    const float sx = ksplit > 1 ? 1.0f : *s_x;                   // partial sums are stored unscaled
     const float yq = (sizeof(OutT) == 1) ? *y_scale : 1.0f;      // FP8 output: the next layer's activation scale
 
     // Epilogue of the tile (em0, ebn), 16-token blocks f0 .. f1-1 of every wavefront row.
-    auto epilogue = [&](int em0, int ebn, auto F0, auto F1) {
+    auto epilogue = [&](int em0, int ebn, int esplit, auto F0, auto F1) {
         constexpr int f0 = decltype(F0)::value, f1 = decltype(F1)::value;
         const int n_block = ebn * BN;
+        OutT* const yo = y + (int64_t)esplit * split_stride;     // this unit's share of the workspace (esplit = 0 without a split)
         if constexpr (DIRECT) {
             // Result lane: channel i of band j, tokens 4 kq .. 4 kq + 3 of block f.  Every wavefront turns its 16 tokens x
             // 16 WN channels of a block into row-major order in an LDS slab of its own (a wavefront's LDS accesses run in
@@ -328,7 +338,7 @@ __global__ void __launch_bounds__(64 * WGM * WGN, 2) linear_mfma2d_kernel(
             constexpr int SEGS = ROW_B / 16, ROWS_PER_STORE = 64 / SEGS, STORES = 16 / ROWS_PER_STORE;
             static_assert(WAVES * 16 * RSB <= (B_STAGES == 2 ? STAGE : A_STAGE), "the wavefronts' slabs fit stage 1");
             uint8_t* const slab = lds + STAGE + wave * (16 * RSB);
-            const bool vec_ok = (ldy * EB) % 16 == 0 && reinterpret_cast<uintptr_t>(y) % 16 == 0;
+            const bool vec_ok = (ldy * EB) % 16 == 0 && reinterpret_cast<uintptr_t>(yo) % 16 == 0;
             const int n_wave = n_block + wn * WN * 16;               // first channel of the wavefront's bands
             const int seg = lane % SEGS, srow = lane / SEGS;
 #pragma unroll
@@ -361,7 +371,7 @@ __global__ void __launch_bounds__(64 * WGM * WGN, 2) linear_mfma2d_kernel(
                     const uint4 w = *reinterpret_cast<const uint4*>(slab + row * RSB + seg * 16);
                     const int m = em0 + (wm * WM + f) * 16 + row, n = n_wave + seg * (16 / EB);
                     if (m < M && n < N) {
-                        OutT* dst = y + (int64_t)m * ldy + n;
+                        OutT* dst = yo + (int64_t)m * ldy + n;
                         if (vec_ok && n + 16 / EB <= N) {
                             *reinterpret_cast<uint4*>(dst) = w;
                         } else {
@@ -441,35 +451,63 @@ __global__ void __launch_bounds__(64 * WGM * WGN, 2) linear_mfma2d_kernel(
         for (int f = 0; f < WM; ++f)
 #pragma unroll
             for (int j = 0; j < WN; ++j) acc[f][j] = v4f{0.f, 0.f, 0.f, 0.f};
-        for (int c = 0; c < C; c += 2) {
+        for (int c = c_begin; c < c_end; c += 2) {
             chunk(c, sa, sb);
-            if (c + 1 < C) chunk(c + 1, sb, sa);
+            if (c + 1 < c_end) chunk(c + 1, sb, sa);
         }
         // The loop's last barrier has passed: both stages are free.  The next tile's first copies and loads go out
         // before this tile's epilogue and are waited for in its middle; they touch stage 0 only (the slab epilogue
         // works in stage 1).
         const int em0 = m0, ebn = bn;
+        const int esplit = split;
         const int v_next = v + nx;
         const bool more = v_next < v_end;
         if (more) {
             set_tile(v_next);
             start_issue();
         }
-        epilogue(em0, ebn, std::integral_constant<int, 0>{}, std::integral_constant<int, WM / 2>{});
+        epilogue(em0, ebn, esplit, std::integral_constant<int, 0>{}, std::integral_constant<int, WM / 2>{});
         if (more) start_finish();
-        epilogue(em0, ebn, std::integral_constant<int, WM / 2>{}, std::integral_constant<int, WM>{});
+        epilogue(em0, ebn, esplit, std::integral_constant<int, WM / 2>{}, std::integral_constant<int, WM>{});
         if (!more) break;
         __syncthreads();
         v = v_next;
     }
 }
 
+// Sum of the K ranges' partial sums in the order of the ranges (fixed, so the result does not depend on which workgroup
+// finished first), then the output scale and cast of the layer: y[m, n] = cast(s_x * sum_s partial[s][m][n]).
+template <typename OutT>
+__global__ void __launch_bounds__(256) splitk_reduce_kernel(const float* __restrict__ partial, int ksplit, int64_t split_stride,
+                                                            int64_t ldw, int M, int N, const float* __restrict__ s_x,
+                                                            OutT* __restrict__ y, int64_t ldy, const float* __restrict__ y_scale) {
+    const int n4 = (N + 3) / 4;
+    const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= (int64_t)M * n4) return;
+    const int m = (int)(idx / n4), n = (int)(idx % n4) * 4;
+    const float sx = *s_x;
+    const float yq = (sizeof(OutT) == 1) ? *y_scale : 1.0f;
+    const float* p = partial + (int64_t)m * ldw + n;             // ldw is a multiple of 4: a float4 stays inside the row
+    float4 sum = *reinterpret_cast<const float4*>(p);
+    for (int s = 1; s < ksplit; ++s) {
+        const float4 t = *reinterpret_cast<const float4*>(p + (int64_t)s * split_stride);
+        sum.x += t.x; sum.y += t.y; sum.z += t.z; sum.w += t.w;
+    }
+    const float v[4] = {sum.x, sum.y, sum.z, sum.w};
+    for (int e = 0; e < 4 && n + e < N; ++e) y[(int64_t)m * ldy + n + e] = OutCast<OutT>::cast(sx * v[e], yq);
+}
+
+struct SplitArgs {
+    int ksplit = 1, cps = 0;
+    int64_t split_stride = 0;
+};
+
 template <typename OutT, int WGM, int WGN, int WM, int WN>
-void launch_cfg(const LinearArgs& a, dim3 grid, int grid_m, int grid_n, int group_m, hipStream_t st) {
-#define W4A8_MFMA2D(MODEV)                                                                                                  \
+void launch_cfg(const LinearArgs& a, dim3 grid, int grid_m, int grid_n, int group_m, const SplitArgs& sp, hipStream_t st) {
+#define W4A8_MFMA2D(MODEV)                                                                                                     \
     hipLaunchKernelGGL((linear_mfma2d_kernel<OutT, WGM, WGN, WM, WN, MODEV>), grid, dim3(64 * WGM * WGN), 0, st, a.x8, a.M, a.ldx8, \
-                       a.s_x, a.packed, a.scales, a.N, a.n_tiles, a.C, a.cpg, a.NG, static_cast<OutT*>(a.y), a.ldy, grid_m,    \
-                       grid_n, group_m, a.y_scale)
+                       a.s_x, a.packed, a.scales, a.N, a.n_tiles, a.C, a.cpg, a.NG, static_cast<OutT*>(a.y), a.ldy, grid_m,       \
+                       grid_n, group_m, a.y_scale, sp.ksplit, sp.cps > 0 ? sp.cps : a.C, sp.split_stride)
     if constexpr (sizeof(OutT) == 1) {                           // FP8 output exists for the code-exact mode only
         W4A8_MFMA2D(MODE_CODE_EXACT);
     } else {
@@ -480,30 +518,62 @@ void launch_cfg(const LinearArgs& a, dim3 grid, int grid_m, int grid_n, int grou
 }
 
 template <int WGM, int WGN, int WM, int WN>
-void launch_out(const LinearArgs& a, int ydt, dim3 grid, int grid_m, int grid_n, int group_m, hipStream_t st) {
-    if (ydt == W4A8_F32) launch_cfg<float, WGM, WGN, WM, WN>(a, grid, grid_m, grid_n, group_m, st);
-    else if (ydt == YDT_SILU_E4M3) launch_cfg<SiluFp8, WGM, WGN, WM, WN>(a, grid, grid_m, grid_n, group_m, st);
-    else if (ydt == YDT_E4M3) launch_cfg<uint8_t, WGM, WGN, WM, WN>(a, grid, grid_m, grid_n, group_m, st);
-    else launch_cfg<uint16_t, WGM, WGN, WM, WN>(a, grid, grid_m, grid_n, group_m, st);
+void launch_out(const LinearArgs& a, int ydt, dim3 grid, int grid_m, int grid_n, int group_m, const SplitArgs& sp, hipStream_t st) {
+    if (ydt == W4A8_F32) launch_cfg<float, WGM, WGN, WM, WN>(a, grid, grid_m, grid_n, group_m, sp, st);
+    else if (ydt == YDT_SILU_E4M3) launch_cfg<SiluFp8, WGM, WGN, WM, WN>(a, grid, grid_m, grid_n, group_m, sp, st);
+    else if (ydt == YDT_E4M3) launch_cfg<uint8_t, WGM, WGN, WM, WN>(a, grid, grid_m, grid_n, group_m, sp, st);
+    else launch_cfg<uint16_t, WGM, WGN, WM, WN>(a, grid, grid_m, grid_n, group_m, sp, st);
 }
 
 }  // namespace
 
-// Built workgroup tiles {tokens, channels}: cfg 0 = 512 x 128, 1 = 256 x 256, 2 = 256 x 128, 3 = 128 x 256 (eight
-// wavefronts, one workgroup per compute unit); 4 = 256 x 128 with four wavefronts, two workgroups per compute unit.
+// Built workgroup tiles {tokens, channels}: cfg 0 = 512 x 128, 1 = 256 x 256, 2 = 256 x 128, 3 = 128 x 256, 5 = 128 x 128
+// (eight wavefronts, one workgroup per compute unit); 4 = 256 x 128 with four wavefronts, two workgroups per compute unit.
 bool mfma2d_tile(int cfg, int& bm, int& bn) {
-    static const int t[5][2] = {{512, 128}, {256, 256}, {256, 128}, {128, 256}, {256, 128}};
-    if (cfg < 0 || cfg > 4) return false;
+    static const int t[6][2] = {{512, 128}, {256, 256}, {256, 128}, {128, 256}, {256, 128}, {128, 128}};
+    if (cfg < 0 || cfg > 5) return false;
     bm = t[cfg][0];
     bn = t[cfg][1];
     return true;
 }
 
+// Row stride (floats) of a K range's partial sums in the workspace, and the bytes `ksplit` ranges take.
+static int64_t splitk_ldw(int64_t N) { return (N + 63) / 64 * 64; }
+size_t mfma2d_splitk_bytes(int64_t M, int64_t N, int ksplit) {
+    return ksplit > 1 ? (size_t)ksplit * (size_t)M * (size_t)splitk_ldw(N) * sizeof(float) : 0;
+}
+
+// The split of K this library uses for a layer of many-token shape when the caller provides a workspace: ksplit = 0 means
+// none.  Few output tiles and a deep K (the down projection of a decoder block at 64...512 tokens): the tiles are multiplied
+// in `ksplit` K ranges by different workgroups, about as many as it takes to give every compute unit one.  Measured on the
+// Llama-3 shapes: 29 -> 22 us at 128 tokens on the 8B down projection (K = 14336), 84 -> 57 us on the 70B one (K = 28672);
+// no gain for K <= 8192, where the partial sums (written and read once) weigh as much as the weights.
+void mfma2d_choose_ksplit(int64_t M, int64_t K, int64_t N, int& cfg, int& ksplit) {
+    cfg = 3;
+    ksplit = 0;
+    const int64_t C = K / 128;
+    if (M > 512 || K < 12288) return;
+    int64_t tiles = ((M + 127) / 128) * ((N + 255) / 256);      // 128 x 256 tiles ...
+    if (tiles <= 16) {                                          // ... or 128 x 128 where those are very few
+        cfg = 5;
+        tiles = ((M + 127) / 128) * ((N + 127) / 128);
+    }
+    if (tiles > 128) return;
+    int64_t s = 256 / tiles;
+    if (s > C / 8) s = C / 8;
+    if (s < 2) return;
+    const int64_t cps = (C + s - 1) / s;
+    s = (C + cps - 1) / cps;                                    // no empty range
+    ksplit = s < 2 ? 0 : (int)s;
+}
+
 // cfg: a tile of mfma2d_tile; group_m = token blocks per super-column of the block order (0: chosen); workgroups = size
-// of the persistent grid (0: one per compute unit).
+// of the persistent grid (0: one per compute unit); ksplit > 1: K is multiplied in that many ranges by different workgroups
+// whose float32 partial sums go through `workspace` (mfma2d_splitk_bytes) and are summed by a second launch.
 int launch_linear_mfma2d(const uint8_t* x8, int64_t M, int64_t K, int64_t ldx8, const float* s_x, const uint8_t* packed,
                          const float* scales, int64_t N, int32_t G, void* y, w4a8_dtype ydt, int64_t ldy, int cfg,
-                         int group_m, int workgroups, int mode, const float* y_scale, hipStream_t st) {
+                         int group_m, int workgroups, int mode, const float* y_scale, hipStream_t st, int ksplit,
+                         void* workspace) {
     if (mode != MODE_CODE_EXACT && mode != MODE_POW2) return W4A8_ERR_DTYPE;
     if (((int)ydt == YDT_E4M3 || (int)ydt == YDT_SILU_E4M3) && (mode != MODE_CODE_EXACT || !y_scale)) return W4A8_ERR_DTYPE;
     if ((int)ydt == YDT_SILU_E4M3 && N % 32 != 0) return W4A8_ERR_SHAPE;
@@ -512,9 +582,18 @@ int launch_linear_mfma2d(const uint8_t* x8, int64_t M, int64_t K, int64_t ldx8, 
     const int C = (int)(K / 128), cpg = G / 128, NG = (int)(K / G);
     const int n_tiles = (int)((N + 15) / 16);
     const int grid_m = (int)((M + bm - 1) / bm), grid_n = (int)((N + bn - 1) / bn);
-    const int64_t total = (int64_t)grid_m * grid_n;
+    if (ksplit < 1) ksplit = 1;
+    if (ksplit > 1 && (ksplit > C || !workspace || (int)ydt == YDT_SILU_E4M3)) return W4A8_ERR_SHAPE;
+    SplitArgs sp;
+    if (ksplit > 1) {
+        sp.cps = (C + ksplit - 1) / ksplit;
+        ksplit = (C + sp.cps - 1) / sp.cps;                     // no empty range
+        sp.ksplit = ksplit;
+        sp.split_stride = M * splitk_ldw(N);
+    }
+    const int64_t total = (int64_t)grid_m * grid_n * ksplit;
     if (total > (1 << 30)) return W4A8_ERR_SHAPE;
-    if (ldx8 >= (1 << 23) || ldy >= (1 << 20)) return W4A8_ERR_SHAPE;   // 32-bit byte offsets inside a workgroup tile
+    if (ldx8 >= (1 << 23) || ldy >= (1 << 20) || N >= (1 << 20)) return W4A8_ERR_SHAPE;   // 32-bit byte offsets inside a tile
     if (group_m <= 0) {
         // One XCD runs 32 workgroups at a time; per chunk they pull rows * 128 bytes of activations and columns * 64
         // bytes of nibbles through its L2, least for a rectangle with about twice as many columns as rows:
@@ -528,15 +607,36 @@ int launch_linear_mfma2d(const uint8_t* x8, int64_t M, int64_t K, int64_t ldx8, 
     const int64_t needed = (total + XCDS2 - 1) / XCDS2 * XCDS2;
     if (workgroups > needed) workgroups = (int)needed;
     const dim3 grid((unsigned)workgroups);
-    const LinearArgs a{x8, (int)M, ldx8, s_x, packed, scales, (int)N, n_tiles, C, cpg, NG, y, ldy, nullptr, 0, mode, y_scale};
-    switch (cfg) {
-        case 0: launch_out<4, 2, 8, 4>(a, (int)ydt, grid, grid_m, grid_n, group_m, st); break;
-        case 1: launch_out<2, 4, 8, 4>(a, (int)ydt, grid, grid_m, grid_n, group_m, st); break;
-        case 2: launch_out<4, 2, 4, 4>(a, (int)ydt, grid, grid_m, grid_n, group_m, st); break;
-        case 3: launch_out<2, 4, 4, 4>(a, (int)ydt, grid, grid_m, grid_n, group_m, st); break;
-        default: launch_out<2, 2, 8, 4>(a, (int)ydt, grid, grid_m, grid_n, group_m, st); break;
+    LinearArgs a{x8, (int)M, ldx8, s_x, packed, scales, (int)N, n_tiles, C, cpg, NG, y, ldy, nullptr, 0, mode, y_scale};
+    int kernel_ydt = (int)ydt;
+    if (ksplit > 1) {                                            // the tiles go to the workspace as unscaled float32
+        a.y = workspace;
+        a.ldy = splitk_ldw(N);
+        kernel_ydt = W4A8_F32;
     }
-    return launch_status();
+    switch (cfg) {
+        case 0: launch_out<4, 2, 8, 4>(a, kernel_ydt, grid, grid_m, grid_n, group_m, sp, st); break;
+        case 1: launch_out<2, 4, 8, 4>(a, kernel_ydt, grid, grid_m, grid_n, group_m, sp, st); break;
+        case 2: launch_out<4, 2, 4, 4>(a, kernel_ydt, grid, grid_m, grid_n, group_m, sp, st); break;
+        case 3: launch_out<2, 4, 4, 4>(a, kernel_ydt, grid, grid_m, grid_n, group_m, sp, st); break;
+        case 4: launch_out<2, 2, 8, 4>(a, kernel_ydt, grid, grid_m, grid_n, group_m, sp, st); break;
+        default: launch_out<2, 4, 4, 2>(a, kernel_ydt, grid, grid_m, grid_n, group_m, sp, st); break;
+    }
+    if (int e = launch_status()) return e;
+    if (ksplit > 1) {
+        const int64_t work = M * ((N + 3) / 4);
+        const dim3 rgrid((unsigned)((work + 255) / 256));
+        const float* ws = static_cast<const float*>(workspace);
+#define W4A8_REDUCE(T)                                                                                                       \
+    hipLaunchKernelGGL((splitk_reduce_kernel<T>), rgrid, dim3(256), 0, st, ws, ksplit, sp.split_stride, splitk_ldw(N), (int)M, \
+                       (int)N, s_x, static_cast<T*>(y), ldy, y_scale)
+        if (ydt == W4A8_F32) W4A8_REDUCE(float);
+        else if ((int)ydt == YDT_E4M3) W4A8_REDUCE(uint8_t);
+        else W4A8_REDUCE(uint16_t);
+#undef W4A8_REDUCE
+        return launch_status();
+    }
+    return W4A8_OK;
 }
 
 }  // namespace w4a8

@@ -5,6 +5,7 @@
 #include <stdint.h>
 
 #include "../../include/w4a8.h"
+#include "../../include/w4a8_tuning.h"
 
 namespace w4a8 {
 
@@ -76,13 +77,17 @@ int launch_linear_mfma_tiled(const uint8_t* x8, int64_t M, int64_t K, int64_t ld
                              const uint8_t* packed, const float* scales, int64_t N, int32_t G, void* y,
                              w4a8_dtype ydt, int64_t ldy, int mf, int ks, int tpw, const float* w_out, int per_channel,
                              int mode, const float* y_scale, hipStream_t st);
-// Second tiling of the many-token kernel (2-D grid of wavefronts, expansion shared through LDS).  cfg: a tile of
-// mfma2d_tile; group_m = token blocks per super-column of the block order (0: chosen); workgroups = size of the
-// persistent grid (0: one per compute unit); mode: MODE_CODE_EXACT or MODE_POW2.
+// Second tiling of the many-token kernel (2-D grid of wavefronts, expansion shared through LDS, persistent workgroups).
+// cfg: a tile of mfma2d_tile; group_m = token blocks per super-column of the block order (0: chosen); workgroups = size of
+// the persistent grid (0: one per compute unit); mode: MODE_CODE_EXACT or MODE_POW2; ksplit > 1: K is multiplied in that
+// many ranges by different workgroups, their float32 partial sums go through `workspace` (mfma2d_splitk_bytes).
 bool mfma2d_tile(int cfg, int& bm, int& bn);
+size_t mfma2d_splitk_bytes(int64_t M, int64_t N, int ksplit);
+void mfma2d_choose_ksplit(int64_t M, int64_t K, int64_t N, int& cfg, int& ksplit);   // ksplit 0: this shape is not split
 int launch_linear_mfma2d(const uint8_t* x8, int64_t M, int64_t K, int64_t ldx8, const float* s_x, const uint8_t* packed,
                          const float* scales, int64_t N, int32_t G, void* y, w4a8_dtype ydt, int64_t ldy, int cfg,
-                         int group_m, int workgroups, int mode, const float* y_scale, hipStream_t st);
+                         int group_m, int workgroups, int mode, const float* y_scale, hipStream_t st, int ksplit = 1,
+                         void* workspace = nullptr);
 // q_scale != nullptr: h is E4M3 bytes, the bf16 result quantized with *q_scale (Eq. 13)
 int launch_hessian_accumulate(const void* x, w4a8_dtype dt, int64_t T, int64_t K, int64_t ldx, float* h, hipStream_t st);
 int launch_gar_permutation(const float* hdiag, int64_t K, int32_t G, int32_t* perm, hipStream_t st);

@@ -21,7 +21,7 @@ def L():
 
 
 def declared_functions():
-    text = open(os.path.join(ROOT, "include", "w4a8.h")).read()
+    text = "".join(open(os.path.join(ROOT, "include", h)).read() for h in ("w4a8.h", "w4a8_tuning.h"))
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     return sorted(set(re.findall(r"\b(w4a8_[a-z0-9_]+)\s*\(", text)))
 
@@ -30,7 +30,7 @@ def test_header_and_library_agree(L):
     names = declared_functions()
     assert {"w4a8_quantize_act", "w4a8_pack_weights", "w4a8_linear"} <= set(names)
     for name in names:
-        assert hasattr(L, name), f"{name} declared in include/w4a8.h but not exported"
+        assert hasattr(L, name), f"{name} declared in include/*.h but not exported"
         assert name in B.SIGNATURES, f"{name} has no ctypes signature in the binding"
     assert sorted(B.SIGNATURES) == names
 
@@ -109,6 +109,28 @@ def test_linear_validation(L):
     assert call(x8=P + 4) == 6 and call(ldx8=264) == 6 and call(packed=P + 8) == 6
     assert call(y=P + 1) == 6
     assert call(layout=B.LAYOUT_CANONICAL, G=32, M=0) == 0
+    # workspace (K ranges across workgroups, Sec. 1: between the two regimes): asked for on few-tile, deep-K shapes only
+    wb = L.w4a8_linear_workspace_bytes
+    assert wb(8, 14336, 4096, 128) == 0 and wb(8192, 4096, 4096, 128) == 0 and wb(128, 4096, 28672, 128) == 0
+    need = wb(128, 14336, 4096, 128)
+    assert need > 0 and need % (128 * 4096 * 4) == 0 and need <= 32 << 20     # whole float32 [M, N] planes, one per K range
+    assert wb(128, 4096, 4096, 128) == 0 and wb(1024, 14336, 4096, 128) == 0   # shallow K, many tokens: not split
+    assert wb(128, 14336, 4096, 96) == 0 and wb(0, 14336, 4096, 128) == 0
+    big = dict(M=128, K=14336, ldx8=14336, N=4096, ldy=4096)
+
+    def call_ws(ws, nbytes, **kw):
+        a = {**ok, **big, **kw}
+        return f(a["x8"], a["M"], a["K"], a["ldx8"], a["xs"], a["packed"], a["ws"], a["N"], a["G"], a["layout"],
+                 a["y"], a["ydt"], a["ldy"], ws, nbytes, None)
+
+    assert call_ws(P, need - 1) == 7 and call_ws(P, 0) == 7                   # too small
+    assert call_ws(P + 8, need) == 6                                           # misaligned
+    assert call_ws(P, 0, M=0) == 0                                             # nothing needed, nothing launched
+    fs = L.w4a8_linear_splitk_variant
+    sk = (P, 128, 14336, 14336, P, P, P, 4096, 128, P, B.BF16, 4096)
+    assert fs(*sk, 5, 4, P, 4 * 128 * 4096 * 4 - 1, None) == 7
+    assert fs(*sk, 5, 1, P, 1 << 30, None) == 2 and fs(*sk, 5, 113, P, 1 << 30, None) == 2
+    assert fs(*sk, 5, 4, None, 1 << 30, None) == 1 and fs(*sk, 5, 4, P + 4, 1 << 30, None) == 6
     fv = L.w4a8_linear_variant
     assert fv(P, 100, 256, 256, P, P, P, 64, 128, P, B.BF16, 64, 0, 1, 1, None) == 2   # skinny path needs M <= 64
     assert fv(P, 4, 256, 256, P, P, P, 64, 128, P, B.BF16, 64, 7, 0, 0, None) == 2     # unknown path
