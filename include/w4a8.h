@@ -142,6 +142,20 @@ int w4a8_linear(const uint8_t* x8_dev, int64_t M, int64_t K, int64_t ldx8, const
                 void* workspace_dev, size_t workspace_bytes, void* stream);
 
 /*
+ * w4a8_linear for callers that cannot allocate device memory (code under HIP graph capture, serving loops, harnesses
+ * that forbid it): the same layer, tiled layout, with the scratch of w4a8_linear_workspace_bytes() taken from a buffer
+ * of W4A8_STATIC_WORKSPACE_BYTES that lives inside the library (one per GPU, held until the process ends) instead of a
+ * workspace argument.  Calls nothing that allocates or frees.  Sizes whose scratch would exceed the buffer return
+ * W4A8_ERR_WORKSPACE (use w4a8_linear with a workspace of your own, or with none).  All calls on one GPU share the
+ * buffer: two calls whose stream work can overlap in time on the same GPU race on it; calls ordered on one stream do not.
+ * Output identical to w4a8_linear with a sufficient workspace.
+ */
+#define W4A8_STATIC_WORKSPACE_BYTES (16u << 20)
+int w4a8_linear_static_workspace(const uint8_t* x8_dev, int64_t M, int64_t K, int64_t ldx8, const float* x_scale_dev,
+                                 const uint8_t* packed_dev, const float* w_scales_dev, int64_t N, int32_t group_size,
+                                 void* y_dev, w4a8_dtype y_dtype, int64_t ldy, void* stream);
+
+/*
  * w4a8_quantize_act and w4a8_linear in one launch, for few tokens (the memory-bound regime, where a separate
  * quantization kernel costs a launch and a round trip of the activations): Y = w4a8_linear(w4a8_quantize_act(X)).
  * Every workgroup quantizes all of X into on-chip memory while its first weights are on their way, with the same

@@ -31,6 +31,8 @@ SIGNATURES = {
     "w4a8_linear_workspace_bytes": (_c_sz, [_c_i64, _c_i64, _c_i64, _c_i32]),
     "w4a8_linear": (_c_i32, [_c_vp, _c_i64, _c_i64, _c_i64, _c_vp, _c_vp, _c_vp, _c_i64, _c_i32, _c_i32, _c_vp,
                              _c_i32, _c_i64, _c_vp, _c_sz, _c_vp]),
+    "w4a8_linear_static_workspace": (_c_i32, [_c_vp, _c_i64, _c_i64, _c_i64, _c_vp, _c_vp, _c_vp, _c_i64, _c_i32, _c_vp,
+                                              _c_i32, _c_i64, _c_vp]),
     "w4a8_linear_variant": (_c_i32, [_c_vp, _c_i64, _c_i64, _c_i64, _c_vp, _c_vp, _c_vp, _c_i64, _c_i32, _c_vp,
                                      _c_i32, _c_i64, _c_i32, _c_i32, _c_i32, _c_vp]),
     "w4a8_linear_splitk_variant": (_c_i32, [_c_vp, _c_i64, _c_i64, _c_i64, _c_vp, _c_vp, _c_vp, _c_i64, _c_i32, _c_vp,
@@ -189,6 +191,19 @@ def linear(x8: torch.Tensor, x_scale: torch.Tensor, packed: torch.Tensor, w_scal
                              packed.data_ptr(), w_scales.data_ptr(), n, group_size, layout, out.data_ptr(),
                              _dtype_code(out), out.stride(0) if m > 1 else max(n, out.stride(0)), ws_ptr, ws_bytes,
                              _stream()), "w4a8_linear")
+    return out
+
+
+def linear_static_workspace(x8, x_scale, packed, w_scales, n, group_size, out_dtype=torch.bfloat16, out=None):
+    """w4a8_linear_static_workspace: the layer with its scratch inside the library (no allocation by the call)."""
+    m, k = x8.shape
+    assert x8.dtype == torch.uint8 and x8.stride(1) == 1
+    if out is None:
+        out = torch.empty((m, n), dtype=out_dtype, device=x8.device)
+    _check(lib().w4a8_linear_static_workspace(x8.data_ptr(), m, k, x8.stride(0) if m > 1 else max(k, x8.stride(0)),
+                                              x_scale.data_ptr(), packed.data_ptr(), w_scales.data_ptr(), n, group_size,
+                                              out.data_ptr(), _dtype_code(out), out.stride(0) if m > 1 else max(n, out.stride(0)),
+                                              _stream()), "w4a8_linear_static_workspace")
     return out
 
 

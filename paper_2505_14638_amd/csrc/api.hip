@@ -2,9 +2,30 @@
 // Validation never touches the device, so every error path can be exercised without a GPU.
 #include "w4a8_internal.hpp"
 
+#include <atomic>
+
 using namespace w4a8;
 
+// Scratch of w4a8_linear_static_workspace: one copy per GPU, inside the library's device image, held until the process
+// ends.  In host code this name is only a handle for hipGetSymbolAddress; the device address is looked up per device.
+static __device__ __align__(256) unsigned char scratch[W4A8_STATIC_WORKSPACE_BYTES];
+
 namespace {
+
+constexpr int MAX_DEVICES = 64;
+std::atomic<void*> scratch_ptr[MAX_DEVICES];                   // device address of `scratch` on each GPU, once looked up
+
+// The address of `scratch` on the current device (looked up on the first call there; no allocation), or null.
+void* static_scratch() {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MAX_DEVICES) return nullptr;
+    void* p = scratch_ptr[dev].load(std::memory_order_acquire);
+    if (p == nullptr) {
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || p == nullptr) return nullptr;
+        scratch_ptr[dev].store(p, std::memory_order_release);   // two threads racing here store the same address
+    }
+    return p;
+}
 
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 inline bool valid_dtype(int d) { return d == W4A8_F32 || d == W4A8_BF16; }
@@ -135,6 +156,27 @@ int w4a8_linear(const uint8_t* x8_dev, int64_t M, int64_t K, int64_t ldx8, const
                                     ldy, split_cfg, 0, 0, MODE_CODE_EXACT, nullptr, st, ksplit, workspace_dev);
     return launch_linear_mfma_tiled(x8_dev, M, K, ldx8, x_scale_dev, packed_dev, w_scales_dev, N, group_size, y_dev,
                                     y_dtype, ldy, 0, 0, 0, nullptr, 0, MODE_CODE_EXACT, nullptr, st);
+}
+
+int w4a8_linear_static_workspace(const uint8_t* x8_dev, int64_t M, int64_t K, int64_t ldx8, const float* x_scale_dev,
+                                 const uint8_t* packed_dev, const float* w_scales_dev, int64_t N, int32_t group_size,
+                                 void* y_dev, w4a8_dtype y_dtype, int64_t ldy, void* stream) {
+    if (!valid_dtype(y_dtype)) return W4A8_ERR_DTYPE;
+    if (int e = check_linear(x8_dev, M, K, ldx8, x_scale_dev, packed_dev, w_scales_dev, N, group_size, W4A8_LAYOUT_TILED,
+                             y_dev, y_dtype, ldy))
+        return e;
+    const size_t need = w4a8_linear_workspace_bytes(M, K, N, group_size);
+    if (need > (size_t)W4A8_STATIC_WORKSPACE_BYTES) return W4A8_ERR_WORKSPACE;
+    if (M == 0) return W4A8_OK;
+    void* ws = nullptr;
+    if (need > 0) {
+        ws = static_scratch();
+        if (ws == nullptr) return W4A8_ERR_HIP;
+    }
+    // Nothing in the scratch has to start at zero: every K range writes its whole [M, round_up(N, 64)] plane of partial
+    // sums before the second launch reads it, whatever an earlier call left there.
+    return w4a8_linear(x8_dev, M, K, ldx8, x_scale_dev, packed_dev, w_scales_dev, N, group_size, W4A8_LAYOUT_TILED, y_dev,
+                       y_dtype, ldy, ws, need, stream);
 }
 
 int w4a8_linear_two_level(const uint8_t* x8_dev, int64_t M, int64_t K, int64_t ldx8, const float* x_scale_dev,

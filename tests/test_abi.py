@@ -126,6 +126,13 @@ def test_linear_validation(L):
     assert call_ws(P, need - 1) == 7 and call_ws(P, 0) == 7                   # too small
     assert call_ws(P + 8, need) == 6                                           # misaligned
     assert call_ws(P, 0, M=0) == 0                                             # nothing needed, nothing launched
+    # the variant with its scratch inside the library: same validation, sizes beyond the buffer refused on the host
+    fn = L.w4a8_linear_static_workspace
+    assert fn(P, 0, 14336, 14336, P, P, P, 4096, 128, P, B.BF16, 4096, None) == 0
+    assert fn(0, 128, 14336, 14336, P, P, P, 4096, 128, P, B.BF16, 4096, None) == 1
+    assert fn(P, 128, 14336, 14336, P, P, P, 4096, 96, P, B.BF16, 4096, None) == 3
+    assert wb(512, 28672, 8192, 128) > 16 << 20
+    assert fn(P, 512, 28672, 28672, P, P, P, 8192, 128, P, B.BF16, 8192, None) == 7
     fs = L.w4a8_linear_splitk_variant
     sk = (P, 128, 14336, 14336, P, P, P, 4096, 128, P, B.BF16, 4096)
     assert fs(*sk, 5, 4, P, 4 * 128 * 4096 * 4 - 1, None) == 7
