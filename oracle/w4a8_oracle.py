@@ -149,7 +149,7 @@ def bf16_half_ulp(x) -> np.ndarray:
     """Half of the bf16 spacing at |x| (float64): the most a correct bf16 rounding may move x."""
     a = np.abs(np.asarray(x, dtype=np.float64))
     with np.errstate(divide="ignore"):
-        e = np.floor(np.log2(np.where(a > 0, a, 1.0)))
+        e = np.floor(np.log2(np.where(a > 0, a, 2.0 ** -126)))   # at zero: the subnormal spacing, like everything below 2^-126
     e = np.maximum(e, -126.0)
     return np.ldexp(1.0, (e - 8).astype(np.int64))
 

@@ -158,3 +158,23 @@ def test_bf16_rounding_helper():
     # 1 + 2^-8 is halfway between 1 and 1 + 2^-7: goes to the even mantissa (1.0); 1 + 3*2^-8 -> 1 + 2^-6
     assert o.round_to_bf16_bits(np.array([1 + 2.0 ** -8]))[0] == 0x3F80
     assert o.round_to_bf16_bits(np.array([1 + 3 * 2.0 ** -8]))[0] == 0x3F82
+
+
+def test_bf16_half_ulp_exact_values():
+    """bf16_half_ulp pinned from both sides (a value twice or half as large fails): hand values at the ends of a binade,
+    in the subnormal range, and for every finite bf16 pattern exactly half the distance to the next pattern away from
+    zero (bf16 has 8 significant bits: spacing 2^(e-7) in [2^e, 2^(e+1)), 2^-133 below 2^-126)."""
+    assert o.bf16_half_ulp(1.0) == 2.0 ** -8
+    assert o.bf16_half_ulp(np.nextafter(2.0, 0.0)) == 2.0 ** -8            # still the binade of 1.0
+    assert o.bf16_half_ulp(2.0) == 2.0 ** -7
+    assert o.bf16_half_ulp(-3.0) == 2.0 ** -7
+    assert o.bf16_half_ulp(448.0) == 2.0 ** 0                                # 448 = 1.75 * 2^8: spacing 2, half of it 1
+    assert o.bf16_half_ulp(2.0 ** -126) == 2.0 ** -134                      # smallest normal
+    assert o.bf16_half_ulp(2.0 ** -130) == 2.0 ** -134 and o.bf16_half_ulp(0.0) == 2.0 ** -134   # subnormals: fixed spacing 2^-133
+    bits = np.arange(0x7F7F, dtype=np.uint16)                                # 0 .. the pattern before the largest finite one
+    x = o.bf16_bits_to_f32(bits).astype(np.float64)
+    nxt = o.bf16_bits_to_f32(bits + np.uint16(1)).astype(np.float64)
+    assert np.array_equal(o.bf16_half_ulp(x), (nxt - x) / 2)
+    assert np.array_equal(o.bf16_half_ulp(-x), (nxt - x) / 2)
+    # strictly inside a binade the value does not change; it doubles exactly at a power of two
+    assert o.bf16_half_ulp(1.9999) == o.bf16_half_ulp(1.0001) == 2.0 ** -8
