@@ -17,6 +17,8 @@
  *   - notation: M tokens, K input features, N output features; W is [N, K] (one row per output
  *     channel), quantization groups are `group_size` consecutive weights along a row (Sec. 3.1,
  *     App. A.1); group g of row n covers k in [g*group_size, (g+1)*group_size).
+ *   - size limits (W4A8_ERR_SHAPE beyond them): M, N, K <= 2^30; N * K <= 2^32 weights and N * K / group_size <= 2^25
+ *     groups per matrix; tiled layout: ldx8 < 2^23, ldy < 2^20; canonical layout: M * N <= 2^25 outputs per call.
  *   - the FP8 format is E4M3 with range +-448 (Sec. 2.2, Sec. 4.1): bias 7, no infinities,
  *     S.1111.111 is NaN.  The INT4 codes are signed, in [-8, 7]; group scales are non-negative.
  *     The *_asym entry points take the paper's own storage format instead (Sec. 2.1, Eq. 8-9): unsigned
@@ -44,7 +46,10 @@ typedef enum {
     W4A8_ERR_HIP = 8        /* the HIP runtime refused a launch */
 } w4a8_status;
 
-typedef enum { W4A8_F32 = 0, W4A8_BF16 = 1 } w4a8_dtype;
+/* Every enumeration below spans the whole int range (the two *_RANGE_* enumerators are no values of their own): a caller
+   may hand any int to an entry point, which then answers W4A8_ERR_DTYPE / W4A8_ERR_LAYOUT instead of reading an
+   enumeration value its type cannot hold. */
+typedef enum { W4A8_F32 = 0, W4A8_BF16 = 1, W4A8_DTYPE_RANGE_LO = -0x7FFFFFFF - 1, W4A8_DTYPE_RANGE_HI = 0x7FFFFFFF } w4a8_dtype;
 
 typedef enum {
     W4A8_SRC_F32_RTN = 0,  /* src = W float32 [N, K]; the library quantizes: symmetric round-to-nearest
@@ -54,8 +59,10 @@ typedef enum {
     W4A8_SRC_I8_CODES = 1, /* src = int8 codes [N, K], each in [-8, 7] (only the low nibble is kept), plus
                               float32 scales [N, K/group_size] (their magnitude is used): a pure re-layout, for
                               codes produced by an offline calibrator (Alg. 1) */
-    W4A8_SRC_F32_RTN_POW2 = 2 /* as W4A8_SRC_F32_RTN with power-of-two scales (Sec. 2.2): s = the smallest power of
+    W4A8_SRC_F32_RTN_POW2 = 2, /* as W4A8_SRC_F32_RTN with power-of-two scales (Sec. 2.2): s = the smallest power of
                               two >= max|W| / 7 (so that every code stays in [-7, 7]); for w4a8_linear_pow2 */
+    W4A8_SRC_RANGE_LO = -0x7FFFFFFF - 1,
+    W4A8_SRC_RANGE_HI = 0x7FFFFFFF
 } w4a8_src;
 
 typedef enum {
@@ -71,7 +78,9 @@ typedef enum {
        scales (Np*K/group_size floats): element (n, g) at ((n / 16) * (K/group_size) + g) * 16 + (n % 16), stored
        as |scale|, with the sign bit set exactly for the (n, g) whose codes contain -8 (a hint that lets the
        kernels expand nibbles the short way elsewhere; the packed codes alone still determine every weight). */
-    W4A8_LAYOUT_TILED = 1
+    W4A8_LAYOUT_TILED = 1,
+    W4A8_LAYOUT_RANGE_LO = -0x7FFFFFFF - 1,
+    W4A8_LAYOUT_RANGE_HI = 0x7FFFFFFF
 } w4a8_layout;
 
 /* Sizes of the buffers w4a8_pack_weights writes, in bytes / in floats; 0 for unsupported arguments. */

@@ -35,11 +35,15 @@ inline bool valid_layout(int l) { return l == W4A8_LAYOUT_CANONICAL || l == W4A8
 // faster, except for deep, narrow layers, where the skinny kernel's finer split of K still wins up to 64 tokens.
 inline bool takes_skinny_path(int64_t M, int64_t K, int64_t N) { return M <= 32 || (M <= 64 && K >= 8192 && N <= 8192); }
 constexpr int64_t DIM_MAX = (int64_t)1 << 30;      // keeps every 32-bit tile / chunk index in range
+// One thread per packed byte, 64 per group scale, 64 per output of the canonical layout's layer: these launches stay
+// below 2^32 threads for N * K <= 2^32 weights, N * K / group_size <= 2^25 groups and M * N <= 2^25 canonical outputs.
+constexpr int64_t WEIGHTS_MAX = (int64_t)1 << 32, GROUPS_MAX = (int64_t)1 << 25, CANONICAL_OUTPUTS_MAX = (int64_t)1 << 25;
 
 int check_nk(int64_t N, int64_t K, int layout) {
     if (!valid_layout(layout)) return W4A8_ERR_LAYOUT;
     if (N < 1 || K < 2 || N > DIM_MAX || K > DIM_MAX || (K & 1)) return W4A8_ERR_SHAPE;
     if (layout == W4A8_LAYOUT_TILED && K % 128 != 0) return W4A8_ERR_LAYOUT;
+    if (((N + 15) / 16 * 16) * K > WEIGHTS_MAX) return W4A8_ERR_SHAPE;
     return W4A8_OK;
 }
 
@@ -47,6 +51,7 @@ int check_weight_shape(int64_t N, int64_t K, int64_t G, int layout) {
     if (int e = check_nk(N, K, layout)) return e;
     if (G < 2 || (G & 1) || G > K || K % G != 0) return W4A8_ERR_GROUP;
     if (layout == W4A8_LAYOUT_TILED && G % 128 != 0) return W4A8_ERR_GROUP;
+    if (((N + 15) / 16 * 16) * (K / G) > GROUPS_MAX) return W4A8_ERR_SHAPE;
     return W4A8_OK;
 }
 
@@ -56,6 +61,8 @@ int check_linear(const uint8_t* x8, int64_t M, int64_t K, int64_t ldx8, const fl
     if (int e = check_weight_shape(N, K, G, layout)) return e;
     if (!valid_dtype(ydt) && ydt != YDT_E4M3) return W4A8_ERR_DTYPE;   // callers with a public y_dtype check it first
     if (ldx8 < K || ldy < N) return W4A8_ERR_SHAPE;
+    if (layout == W4A8_LAYOUT_CANONICAL && M * N > CANONICAL_OUTPUTS_MAX) return W4A8_ERR_SHAPE;
+    if (layout == W4A8_LAYOUT_TILED && (ldx8 >= ((int64_t)1 << 23) || ldy >= ((int64_t)1 << 20))) return W4A8_ERR_SHAPE;
     if (!x8 || !xs || !packed || !ws || !y) return W4A8_ERR_NULL;
     if (layout == W4A8_LAYOUT_TILED) {
         if (!aligned16(x8) || !aligned16(packed) || !aligned16(ws) || (ldx8 & 15)) return W4A8_ERR_ALIGN;

@@ -537,36 +537,6 @@ bool mfma2d_tile(int cfg, int& bm, int& bn) {
     return true;
 }
 
-// Row stride (floats) of a K range's partial sums in the workspace, and the bytes `ksplit` ranges take.
-static int64_t splitk_ldw(int64_t N) { return (N + 63) / 64 * 64; }
-size_t mfma2d_splitk_bytes(int64_t M, int64_t N, int ksplit) {
-    return ksplit > 1 ? (size_t)ksplit * (size_t)M * (size_t)splitk_ldw(N) * sizeof(float) : 0;
-}
-
-// The split of K this library uses for a layer of many-token shape when the caller provides a workspace: ksplit = 0 means
-// none.  Few output tiles and a deep K (the down projection of a decoder block at 64...512 tokens): the tiles are multiplied
-// in `ksplit` K ranges by different workgroups, about as many as it takes to give every compute unit one.  Measured on the
-// Llama-3 shapes: 29 -> 22 us at 128 tokens on the 8B down projection (K = 14336), 84 -> 57 us on the 70B one (K = 28672);
-// no gain for K <= 8192, where the partial sums (written and read once) weigh as much as the weights.
-void mfma2d_choose_ksplit(int64_t M, int64_t K, int64_t N, int& cfg, int& ksplit) {
-    cfg = 3;
-    ksplit = 0;
-    const int64_t C = K / 128;
-    if (M > 512 || K < 12288) return;
-    int64_t tiles = ((M + 127) / 128) * ((N + 255) / 256);      // 128 x 256 tiles ...
-    if (tiles <= 16) {                                          // ... or 128 x 128 where those are very few
-        cfg = 5;
-        tiles = ((M + 127) / 128) * ((N + 127) / 128);
-    }
-    if (tiles > 128) return;
-    int64_t s = 256 / tiles;
-    if (s > C / 8) s = C / 8;
-    if (s < 2) return;
-    const int64_t cps = (C + s - 1) / s;
-    s = (C + cps - 1) / cps;                                    // no empty range
-    ksplit = s < 2 ? 0 : (int)s;
-}
-
 // cfg: a tile of mfma2d_tile; group_m = token blocks per super-column of the block order (0: chosen); workgroups = size
 // of the persistent grid (0: one per compute unit); ksplit > 1: K is multiplied in that many ranges by different workgroups
 // whose float32 partial sums go through `workspace` (mfma2d_splitk_bytes) and are summed by a second launch.
@@ -589,7 +559,7 @@ int launch_linear_mfma2d(const uint8_t* x8, int64_t M, int64_t K, int64_t ldx8, 
         sp.cps = (C + ksplit - 1) / ksplit;
         ksplit = (C + sp.cps - 1) / sp.cps;                     // no empty range
         sp.ksplit = ksplit;
-        sp.split_stride = M * splitk_ldw(N);
+        sp.split_stride = M * mfma2d_splitk_ldw(N);
     }
     const int64_t total = (int64_t)grid_m * grid_n * ksplit;
     if (total > (1 << 30)) return W4A8_ERR_SHAPE;
@@ -611,7 +581,7 @@ int launch_linear_mfma2d(const uint8_t* x8, int64_t M, int64_t K, int64_t ldx8, 
     int kernel_ydt = (int)ydt;
     if (ksplit > 1) {                                            // the tiles go to the workspace as unscaled float32
         a.y = workspace;
-        a.ldy = splitk_ldw(N);
+        a.ldy = mfma2d_splitk_ldw(N);
         kernel_ydt = W4A8_F32;
     }
     switch (cfg) {
@@ -628,7 +598,7 @@ int launch_linear_mfma2d(const uint8_t* x8, int64_t M, int64_t K, int64_t ldx8, 
         const dim3 rgrid((unsigned)((work + 255) / 256));
         const float* ws = static_cast<const float*>(workspace);
 #define W4A8_REDUCE(T)                                                                                                       \
-    hipLaunchKernelGGL((splitk_reduce_kernel<T>), rgrid, dim3(256), 0, st, ws, ksplit, sp.split_stride, splitk_ldw(N), (int)M, \
+    hipLaunchKernelGGL((splitk_reduce_kernel<T>), rgrid, dim3(256), 0, st, ws, ksplit, sp.split_stride, mfma2d_splitk_ldw(N), (int)M, \
                        (int)N, s_x, static_cast<T*>(y), ldy, y_scale)
         if (ydt == W4A8_F32) W4A8_REDUCE(float);
         else if ((int)ydt == YDT_E4M3) W4A8_REDUCE(uint8_t);

@@ -31,8 +31,10 @@ struct ChunkLoads {
 // larger register tiles run with fewer wavefronts per workgroup (the launcher enforces it), which raises the
 // register budget per lane: 128 at 1024 threads, 256 at 512 and below; the asymmetric format's zero-point terms need
 // the larger budget from two tiles on
-constexpr int max_threads(int tiles, bool asym = false) {
-    return tiles <= (asym ? 1 : 2) ? 1024 : (tiles <= 8 ? 512 : 256);
+// (the fused gate|up form at 17..32 tokens -- two token blocks x two bands, code-exact mode -- fits the smaller budget
+// as well, 119 registers, and takes it, so that it can split K over as many wavefronts as the plain layer does)
+constexpr int max_threads(int tiles, bool asym = false, bool fused_gate_up_2x2 = false) {
+    return (tiles <= (asym ? 1 : 2) || fused_gate_up_2x2) ? 1024 : (tiles <= 8 ? 512 : 256);
 }
 
 // DEPTH = chunks in flight per wavefront (a ring of register buffers).  MODE_CODE_EXACT: signed codes, group scales
@@ -49,7 +51,8 @@ constexpr int max_threads(int tiles, bool asym = false) {
 // stand-alone kernel), and the main loop takes its activation operands from there.  Workgroup 0 also writes the
 // codes to x8_out (row stride K) when that is not null.
 template <int MT, int NT, int DEPTH, typename OutT, int MODE, int XQ>
-__global__ void __launch_bounds__(max_threads(MT * NT, MODE == MODE_ASYM || MODE == MODE_ASYM_TWO)) linear_skinny_kernel(
+__global__ void __launch_bounds__(max_threads(MT * NT, MODE == MODE_ASYM || MODE == MODE_ASYM_TWO,
+                                               OutKind<OutT>::SILU && MT == 2 && NT == 2)) linear_skinny_kernel(
     const uint8_t* __restrict__ x8, int M, int64_t ldx8, const float* __restrict__ s_x,
     const uint8_t* __restrict__ packed, const float* __restrict__ scales, int N, int n_tiles, int C, int cpg, int NG,
     OutT* __restrict__ y, int64_t ldy, int cpw, const float* __restrict__ w_out, int per_channel,
@@ -386,10 +389,10 @@ int launch_linear_skinny(const uint8_t* x8, int64_t M, int64_t K, int64_t ldx8, 
     if (waves > C) waves = C;
     // The fused gate|up layer needs gate and up tiles in one workgroup.  It keeps the split of K the plain layer would
     // use on the same shape, so that every partial sum, and with it every output byte, is the same as in the unfused
-    // sequence (the one exception: 17..32 tokens on a layer narrow enough for 16 wavefronts, where four register tiles
-    // allow only 8).
+    // sequence.
     if ((int)ydt == YDT_SILU_E4M3 && nt == 1) nt = 2;
-    const int thread_cap = max_threads(mt * nt, mode == MODE_ASYM || mode == MODE_ASYM_TWO);
+    const int thread_cap = max_threads(mt * nt, mode == MODE_ASYM || mode == MODE_ASYM_TWO,
+                                       (int)ydt == YDT_SILU_E4M3 && mt == 2 && nt == 2);
     while (waves > 1 && (waves * mt * nt > 64 || waves * 64 > thread_cap)) --waves;   // LDS and registers
     if (waves < 1 || waves > 16 || waves * mt * nt > 64 || waves * 64 > thread_cap) return W4A8_ERR_SHAPE;
     if (depth == 0) depth = 2;                                   // deeper rings cost occupancy and measured no faster

@@ -266,24 +266,24 @@ __device__ __forceinline__ int e8m0_of(float s) { return (int)((__float_as_uint(
 // might alias (it would wait for the just-issued prefetch before each read).  The caller orders a copy against its
 // readers with lds_dma_wait_all() (plus a workgroup barrier when other wavefronts read the data), and against earlier
 // reads of the destination with the `after` argument: a value obtained from those reads, which the copy waits for.
-// A kernel that uses these must not also use the compiler's own LDS-copy builtins (both program M0).
+// The statements declare M0 as clobbered, so the compiler keeps no value of its own there across them.
 __device__ __forceinline__ void lds_dma_16(const uint8_t* base, uint32_t offset, uint32_t lds_addr) {
     asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
                  :
                  : "v"(offset), "s"(base), "s"(lds_addr)
-                 : "memory");
+                 : "memory", "m0");
 }
 __device__ __forceinline__ void lds_dma_16_after(const uint8_t* base, uint32_t offset, uint32_t lds_addr, uint32_t after) {
     asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
                  :
                  : "v"(offset), "s"(base), "s"(lds_addr), "v"(after)
-                 : "memory");
+                 : "memory", "m0");
 }
 __device__ __forceinline__ void lds_dma_4(const uint8_t* base, uint32_t offset, uint32_t lds_addr) {
     asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dword %0, %1"
                  :
                  : "v"(offset), "s"(base), "s"(lds_addr)
-                 : "memory");
+                 : "memory", "m0");
 }
 
 // Waits until every outstanding global load of this wavefront, the copies above included, has completed.

@@ -109,6 +109,11 @@ def test_linear_validation(L):
     assert call(x8=P + 4) == 6 and call(ldx8=264) == 6 and call(packed=P + 8) == 6
     assert call(y=P + 1) == 6
     assert call(layout=B.LAYOUT_CANONICAL, G=32, M=0) == 0
+    # size limits: weights per matrix, groups per matrix, outputs of the canonical layout's layer, strides of the tiled one
+    assert call(N=1 << 20, K=1 << 13, ldx8=1 << 13, ldy=1 << 20) == 2                       # 2^33 weights
+    assert call(layout=B.LAYOUT_CANONICAL, N=1 << 14, K=1 << 13, ldx8=1 << 13, ldy=1 << 14, G=2) == 2   # 2^26 groups
+    assert call(layout=B.LAYOUT_CANONICAL, M=1 << 13, N=1 << 13, ldy=1 << 13, G=32) == 2    # 2^26 canonical outputs
+    assert call(ldx8=1 << 23) == 2 and call(ldy=1 << 20) == 2
     # workspace (K ranges across workgroups, Sec. 1: between the two regimes): asked for on few-tile, deep-K shapes only
     wb = L.w4a8_linear_workspace_bytes
     assert wb(8, 14336, 4096, 128) == 0 and wb(8192, 4096, 4096, 128) == 0 and wb(128, 4096, 28672, 128) == 0

@@ -139,7 +139,9 @@ def test_silu_mul_quantize_equals_silu_mul_then_quantize(gpu_lib, m, f):
 
 
 @pytest.mark.parametrize("m,k,f", [(1, 1024, 48), (16, 512, 208), (40, 1024, 64), (100, 384, 304), (300, 1024, 528),
-                                   (257, 640, 144), (24, 256, 8208)])
+                                   (257, 640, 144), (24, 256, 8208),
+                                   # 17..32 tokens on a narrow layer: the plain layer splits K over 16 wavefronts, and so does the fused one
+                                   (24, 2048, 1024), (32, 4096, 512), (20, 2048, 1696)])
 def test_fused_gate_up_equals_the_unfused_sequence(gpu_lib, m, k, f):
     """w4a8_linear_silu_mul_fp8_out on the row-interleaved gate|up matrix against linear (bf16) -> SiLU*mul -> Eq. 13 on
     the matrix in its natural order: the same bytes; ragged channel counts, both kernels, a strided output."""
