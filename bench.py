@@ -10,6 +10,7 @@ replayed as HIP graphs so that the host's launch cost does not bound microsecond
 
 `value` = algorithmic bytes of the 12 linear layers / step time, where per layer
 bytes = N*K/2 (codes) + 4*N*K/G (scales) + M*K (FP8 activations) + 2*M*N (bf16 output).
+Every timed leg is repeated REPEATS times; the median is reported, with the minimum and the maximum next to it.
 
 Also reported: `roofline` for the dominant kernel (the skinny linear kernel, timed alone with HIP events on the
 launch stream), `prefill` (TFLOP/s of the MFMA-tiled kernel over the prefill sweep, with its own roofline), and
@@ -31,6 +32,7 @@ import torch
 from paper_2505_14638_amd import binding as B
 from paper_2505_14638_amd import synthetic as syn
 
+REPEATS = 5                    # timed repetitions per leg: the median is the figure, min and max its spread
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
 FP8_PEAK_TFLOPS = 5000.0       # MI355X dense FP8 MFMA
 G = 128
@@ -68,13 +70,15 @@ class Case:
         self.x = torch.from_numpy(x).to(dev)
         self.x8 = torch.empty((m, layer.k), dtype=torch.uint8, device=dev)
         self.y = torch.empty((m, layer.n), dtype=torch.bfloat16, device=dev)
+        need = B.linear_workspace_bytes(m, layer.k, layer.n, G)          # scratch for K ranges across workgroups, where asked for
+        self.ws = torch.empty(need, dtype=torch.uint8, device=dev) if need else None
 
     def quantize(self):
         B.quantize_act(self.x, self.s_x, out=self.x8)
 
     def linear(self, s):
         packed, scales = self.layer.sets[s % len(self.layer.sets)]
-        B.linear(self.x8, self.s_x, packed, scales, self.layer.n, G, B.LAYOUT_TILED, out=self.y)
+        B.linear(self.x8, self.s_x, packed, scales, self.layer.n, G, B.LAYOUT_TILED, out=self.y, workspace=self.ws)
 
     def fusable(self):
         """Where folding the activation quantization into the layer (w4a8_linear_quantize_in) pays: a single token.  Every
@@ -105,7 +109,7 @@ class Eager:
         self.replay = fn
 
 
-def time_graphs(graphs, reps, warmup):
+def time_graphs_once(graphs, reps, warmup):
     """Replay graphs round-robin `reps` times after `warmup`; returns seconds for the timed replays."""
     for i in range(warmup):
         graphs[i % len(graphs)].replay()
@@ -117,6 +121,39 @@ def time_graphs(graphs, reps, warmup):
     t1.record()
     torch.cuda.synchronize()
     return t0.elapsed_time(t1) * 1e-3
+
+
+def spread(vals):
+    """(median, min, max) of the repetitions of one leg."""
+    v = sorted(vals)
+    return v[len(v) // 2], v[0], v[-1]
+
+
+def time_graphs(graphs, reps, warmup, repeats=REPEATS):
+    """REPEATS timed regions of `reps` replays each (warm-up before the first); seconds of the median region."""
+    vals = [time_graphs_once(graphs, reps, warmup if r == 0 else 0) for r in range(repeats)]
+    return spread(vals)[0]
+
+
+def time_graphs_spread(graphs, reps, warmup, repeats=REPEATS):
+    return spread([time_graphs_once(graphs, reps, warmup if r == 0 else 0) for r in range(repeats)])
+
+
+def time_launches(run, reps, repeats=REPEATS):
+    """Eager launches: `reps` untimed ones first, then REPEATS timed regions of `reps`; (median, min, max) seconds per launch."""
+    for i in range(max(2, reps)):
+        run(i)
+    torch.cuda.synchronize()
+    t0, t1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    vals = []
+    for _ in range(repeats):
+        t0.record()
+        for i in range(reps):
+            run(i)
+        t1.record()
+        torch.cuda.synchronize()
+        vals.append(t0.elapsed_time(t1) * 1e-3 / reps)
+    return spread(vals)
 
 
 def cpu_baseline(min_seconds=10.0):
@@ -187,7 +224,7 @@ def measured_ceilings(dev):
     return round(gbs, 1), round(copy_gbs, 1), round(tfl, 1)
 
 
-def library_fp8_gemm_seconds(x8, n, reps):
+def library_fp8_gemm_seconds(x8, n, reps):  # noqa: C901
     """Seconds per call of the vendor library's FP8 GEMM (through torch._scaled_mm) for activations x8 [M, K] (E4M3 bytes)
     against random FP8 weights [N, K], bf16 output; None where this torch build has no such GEMM.  A measured reference
     for what a dense FP8 contraction reaches on this machine -- it is not part of the W4A8 path."""
@@ -235,99 +272,202 @@ def plain_read_same_sizes(dev, sizes, copies, steps, warmup):
     return sec / steps / len(sizes) * 1e6
 
 
-def block_latency(dev, steps, warmup):
-    """Config 5: latency of the decoder-block linear stack per batch size, HIP graph replay."""
+class WeightViews:
+    """One packed [n_total, K] weight matrix that layers of N rows are sliced from: in the tiled format the bands of 16
+    rows are contiguous, so rows [i N, (i + 1) N) of the big matrix are the packed codes and scales of a layer of their
+    own.  Enough slices to keep the weights of consecutive launches out of the 256 MB last-level cache."""
+
+    def __init__(self, k, n_total, dev, seed):
+        self.k, self.n_total = k, n_total
+        gen = torch.Generator(device=dev).manual_seed(seed)
+        packed, scales = [], []
+        step = 16384
+        for r0 in range(0, n_total, step):                               # packed in pieces: the float32 source of one piece at a time
+            w = torch.randn((min(step, n_total - r0), k), generator=gen, device=dev) * 0.02
+            p_, s_ = B.pack_weights(w, G, B.LAYOUT_TILED)
+            packed.append(p_)
+            scales.append(s_)
+            del w
+        self.packed, self.scales = torch.cat(packed), torch.cat(scales)
+        torch.cuda.synchronize()
+
+    def count(self, n):
+        return self.n_total // n
+
+    def view(self, i, n):
+        pb, sc = n * self.k // 2, n * self.k // G
+        return self.packed[i * pb:(i + 1) * pb], self.scales[i * sc:(i + 1) * sc]
+
+
+def decode_cases(dev):
+    """Per-case rows of the decode shapes (configs[1]: Llama-3-8B, configs[3]: Llama-3-70B at M = 1 and 16): the linear
+    kernel alone on weights that come from HBM (a HIP graph of one launch per weight slice, >= 500 MB of distinct
+    weights per case), the launch shape the library chooses, and the best of the built launch shapes timed the same way."""
+    pools = [(4096, 286720, [6144, 4096, 28672], (1, 4, 16), "8B"), (14336, 81920, [4096], (1, 4, 16), "8B"),
+             (8192, 172032, [10240, 8192, 57344], (1, 16), "70B"), (28672, 40960, [8192], (1, 16), "70B")]
+    rows = []
+    sx = torch.tensor([0.05], dtype=torch.float32, device=dev)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    for (k, n_total, ns, ms, model) in pools:
+        pool = WeightViews(k, n_total, dev, seed=k)
+        for n in ns:
+            views = [pool.view(i, n) for i in range(pool.count(n))]
+            layer_bytes = n * k // 2 + 4 * n * k // G
+            for m in ms:
+                x8 = torch.randint(0, 120, (m, k), dtype=torch.uint8, device=dev)
+                y = torch.empty((m, n), dtype=torch.bfloat16, device=dev)
+                reps = max(2, int(2e-3 / (len(views) * layer_bytes / 4e12)))      # about 2 ms per timed region
+
+                def timed(launch):
+                    with torch.cuda.stream(side):
+                        launch(*views[0])
+                        torch.cuda.synchronize()
+                        g = capture(lambda: [launch(p_, s_) for (p_, s_) in views])
+                        med, lo, hi = time_graphs_spread([g], reps, reps)            # one untimed region first: clocks ramp up under load
+                    del g
+                    return [t / (reps * len(views)) for t in (med, lo, hi)]
+
+                shape = B.linear_launch_shape(m, k, n, G)
+                best, best_shape = None, None
+                for nt in (1, 2, 4):
+                    for waves in (2, 4, 8, 16):
+                        for depth in (0, 4):
+                            p1 = waves | (depth << 8)
+                            if depth == 4 and (m > 1 or nt > 1):
+                                continue                                     # the deeper ring is built for one band and one token block
+                            try:
+                                t = timed(lambda p_, s_: B.linear_variant(x8, sx, p_, s_, n, G, y, 0, nt, p1))[0]
+                            except B.W4A8Error:
+                                continue                                     # a combination that is not built
+                            if best is None or t < best:
+                                best, best_shape = t, [0, nt, waves | ((depth or 2) << 8)]
+                # the library's own choice last, like the variants after untimed launches of the same kind
+                med, lo, hi = timed(lambda p_, s_: B.linear(x8, sx, p_, s_, n, G, B.LAYOUT_TILED, out=y))
+                if med < best:
+                    best, best_shape = med, list(shape[:3])
+                nbytes = alg_bytes(m, k, n)
+                rows.append({"model": model, "M": m, "K": k, "N": n, "us": round(med * 1e6, 2), "us_min": round(lo * 1e6, 2),
+                             "us_max": round(hi * 1e6, 2), "GBps": round(nbytes / med / 1e9, 1),
+                             "frac_of_peak": round(nbytes / med / 1e9 / HBM_PEAK_GBS, 4), "launch_shape": list(shape[:3]),
+                             "best_variant": best_shape, "best_variant_us": round(best * 1e6, 2),
+                             "default_over_best": round(med / best, 3), "weight_slices": len(views)})
+                del x8, y
+        del pool, views
+        torch.cuda.empty_cache()
+    torch.cuda.current_stream().wait_stream(side)
+    worst = max(r["default_over_best"] for r in rows)
+    tot_b = sum(alg_bytes(r["M"], r["K"], r["N"]) for r in rows)
+    tot_t = sum(r["us"] for r in rows) * 1e-6
+    return {"metric": "the few-token linear kernel per decode case, weights from HBM (one launch per weight slice in a HIP "
+                      "graph, >= 500 MB of distinct weights per case); launch_shape / best_variant = (path, param0, param1) "
+                      "of w4a8_linear_variant, param1 = wavefronts + 256 * chunks in flight",
+            "rows": rows, "worst_default_over_best": worst, "byte_weighted_GBps": round(tot_b / tot_t / 1e9, 1),
+            "byte_weighted_frac_of_peak": round(tot_b / tot_t / 1e9 / HBM_PEAK_GBS, 4), "repeats": REPEATS}
+
+
+def block_latency(dev, steps, warmup, sets=3):
+    """Config 5: latency of the decoder-block linear stack per batch size, HIP graph replay over `sets` rotating weight
+    sets (3 x 116 MB: beyond the 256 MB last-level cache, so the weights come from HBM); the figure with one weight set
+    (partly served by that cache) is kept next to it, labelled."""
     from paper_2505_14638_amd.block import LAYERS, DecoderBlockLinears
     cfg = syn.CONFIGS[5]
-    blk = DecoderBlockLinears(cfg["hidden"], cfg["ffn"], syn.LLAMA3_8B["qkv"][1], cfg["group"], dev)
-    for idx, name in enumerate(LAYERS):
-        k, n = blk.dims[name]
-        blk.load_layer(name, torch.from_numpy(syn.make_weights(syn.rng_for(5, idx), n, k)))
-    for name, s in zip(LAYERS, (0.19, 0.012, 0.004, 0.0006)):          # typical static scales of this block
-        blk.set_act_scale(name, s)
-    fused = DecoderBlockLinears(cfg["hidden"], cfg["ffn"], syn.LLAMA3_8B["qkv"][1], cfg["group"], dev, fused=True)
-    fused.weights, fused.scales_x = blk.weights, blk.scales_x
-    out, out_fused = {}, {}
+    blocks, fused_blocks = [], []
+    for c in range(sets):
+        blk = DecoderBlockLinears(cfg["hidden"], cfg["ffn"], syn.LLAMA3_8B["qkv"][1], cfg["group"], dev)
+        for idx, name in enumerate(LAYERS):
+            k, n = blk.dims[name]
+            blk.load_layer(name, torch.from_numpy(syn.make_weights(syn.rng_for(5, idx, c), n, k)))
+        for name, s in zip(LAYERS, (0.19, 0.012, 0.004, 0.0006)):      # typical static scales of this block
+            blk.set_act_scale(name, s)
+        fused = DecoderBlockLinears(cfg["hidden"], cfg["ffn"], syn.LLAMA3_8B["qkv"][1], cfg["group"], dev, fused=True)
+        fused.weights, fused.scales_x = blk.weights, blk.scales_x
+        blocks.append(blk)
+        fused_blocks.append(fused)
+    out = {"by_batch": {}, "fused_by_batch": {}, "fused_spread": {}, "one_weight_set_by_batch": {}, "one_weight_set_fused_by_batch": {}}
     for m in cfg["batches"]:
         x = syn.make_activations(syn.rng_for(5, 200 + m), m, cfg["hidden"], cfg["frac"], cfg["mult"])
         x_d = torch.from_numpy(x).to(dev).to(torch.bfloat16)
         side = torch.cuda.Stream()
         side.wait_stream(torch.cuda.current_stream())
         with torch.cuda.stream(side):
-            blk.forward(x_d)
-            torch.cuda.synchronize()
-            g = capture(lambda: blk.forward(x_d))
-            sec = time_graphs([g], steps, warmup)
-            fused.forward(x_d)
-            torch.cuda.synchronize()
-            gf = capture(lambda: fused.forward(x_d))
-            sec_f = time_graphs([gf], steps, warmup)
-        out[str(m)] = round(sec / steps * 1e6, 2)
-        out_fused[str(m)] = round(sec_f / steps * 1e6, 2)
+            for group, key, key1 in ((blocks, "by_batch", "one_weight_set_by_batch"),
+                                     (fused_blocks, "fused_by_batch", "one_weight_set_fused_by_batch")):
+                graphs = []
+                for blk in group:
+                    blk.forward(x_d)
+                    torch.cuda.synchronize()
+                    graphs.append(capture(lambda blk=blk: blk.forward(x_d)))
+                med, lo, hi = time_graphs_spread(graphs, steps, warmup)
+                out[key][str(m)] = round(med / steps * 1e6, 2)
+                if key == "fused_by_batch":
+                    out["fused_spread"][str(m)] = [round(lo / steps * 1e6, 2), round(hi / steps * 1e6, 2)]
+                out[key1][str(m)] = round(time_graphs(graphs[:1], steps, warmup) / steps * 1e6, 2)
+                del graphs
+        torch.cuda.current_stream().wait_stream(side)
     return {"metric": "decoder-block linear stack latency (config 5: QKV, O, gate|up, SiLU*mul, down; hidden 4096, "
-                      "FFN 14336)", "unit": "us per block", "by_batch": out, "fused_by_batch": out_fused,
+                      "FFN 14336)", "unit": "us per block", "weight_sets": sets, "repeats": REPEATS, **out,
             "fused": "same outputs with each intermediate's FP8 quantization folded into the kernel that produces it "
                      "(6 launches instead of 9)",
-            "note": "one weight set, so at small batch part of the 116 MB of weights is served by the 256 MB cache"}
+            "note": "by_batch / fused_by_batch rotate over the weight sets (weights from HBM); one_weight_set_* replay one "
+                    "set, part of whose 116 MB is then served by the 256 MB last-level cache"}
 
 
 def weight_modes(dev):
-    """The other weight formats of the library on two shapes (gate|up at M = 1 and M = 8192): same measurement as the
-    main legs, eager launches over six rotating weight sets (decode) or one (prefill)."""
+    """The other weight formats of the library on two shapes (gate|up at M = 1 and M = 8192), every buffer made by the
+    library's packers from seeded float32 weights, so the timed launches compute the layer: eager launches over six
+    rotating weight sets (decode: 6 x 62 MB) or one (prefill); median of REPEATS."""
     k, n = syn.LLAMA3_8B["gate_up"]
-    nt = (n + 15) // 16
     out = {}
+    gen = torch.Generator(device=dev).manual_seed(20250514)
     for m in (1, 8192):
         sets = 6 if m == 1 else 1
         x8 = torch.randint(0, 120, (m, k), dtype=torch.uint8, device=dev)
         sx = torch.tensor([0.1], dtype=torch.float32, device=dev)
         y = torch.empty((m, n), dtype=torch.bfloat16, device=dev)
-        packed = [torch.randint(0, 256, (n * k // 2,), dtype=torch.uint8, device=dev) for _ in range(sets)]
-        s32 = [torch.rand(nt * 16 * k // G, dtype=torch.float32, device=dev) * 0.01 + 0.005 for _ in range(sets)]
-        s8 = [sc * 400.0 for sc in s32]                                    # FP8-domain group scales, products up to ~56
-        sp2 = [torch.exp2(torch.ceil(torch.log2(sc))) for sc in s32]
-        w_out = torch.rand(n, dtype=torch.float32, device=dev) * 1e-3
-        params = []
-        for i in range(sets):
-            rec = torch.zeros((nt * (k // G), 80), dtype=torch.uint8, device=dev)
-            rec[:, :64] = s32[i].view(-1, 16).view(torch.uint8)
-            rec[:, 64:] = torch.randint(0, 16, (nt * (k // G), 16), dtype=torch.uint8, device=dev)
-            params.append(rec.reshape(-1))
+        sym, p2, asym, two = [], [], [], []
+        for _ in range(sets):
+            w = torch.randn((n, k), generator=gen, device=dev) * 0.02
+            sym.append(B.pack_weights(w, G, B.LAYOUT_TILED))                  # signed codes, float32 group scales (Eq. 1 symmetric)
+            p2.append(B.pack_weights(w, G, B.LAYOUT_TILED, pow2=True))        # the same with power-of-two scales (Sec. 2.2)
+            asym.append(B.pack_weights_asym(w, G))                            # unsigned codes, zero-points (Eq. 8-9)
+            packed, scales = sym[-1]
+            two.append((packed, scales.abs() * 400.0))                        # FP8-domain group scales (Eq. 8): products up to ~56
+            del w
+        w_out = torch.rand(n, generator=gen, dtype=torch.float32, device=dev) * 1e-3
         calls = {
-            "code_exact": lambda i: B.linear(x8, sx, packed[i], s32[i], n, G, B.LAYOUT_TILED, out=y),
-            "two_level": lambda i: B.linear_two_level(x8, sx, packed[i], s8[i], w_out, n, G, out=y),
-            "asym": lambda i: B.linear_asym(x8, sx, packed[i], params[i], n, G, out=y),
-            "pow2": lambda i: B.linear_pow2(x8, sx, packed[i], sp2[i], n, G, out=y),
+            "code_exact": lambda i: B.linear(x8, sx, *sym[i % sets], n, G, B.LAYOUT_TILED, out=y),
+            "two_level": lambda i: B.linear_two_level(x8, sx, *two[i % sets], w_out, n, G, out=y),
+            "asym": lambda i: B.linear_asym(x8, sx, *asym[i % sets], n, G, out=y),
+            "pow2": lambda i: B.linear_pow2(x8, sx, *p2[i % sets], n, G, out=y),
         }
         reps = 60 if m == 1 else 10
         row = {}
         for name, fn in calls.items():
-            for i in range(reps):
-                fn(i % sets)
-            torch.cuda.synchronize()
-            t0, t1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            t0.record()
-            for i in range(reps):
-                fn(i % sets)
-            t1.record()
-            torch.cuda.synchronize()
-            sec = t0.elapsed_time(t1) * 1e-3 / reps
+            sec = time_launches(fn, reps)[0]
             extra = n * k // G if name == "asym" else 0                   # zero-point bytes
             row[name] = round((alg_bytes(m, k, n) + extra) / sec / 1e9, 1) if m == 1 else round(2.0 * m * k * n / sec / 1e12, 1)
         out[f"M={m}"] = {"unit": "GB/s" if m == 1 else "TFLOP/s", **row}
-    return {"metric": "weight formats on the gate|up layer (K = 4096, N = 28672), random codes", "by_case": out}
+        del sym, p2, asym, two
+        torch.cuda.empty_cache()
+    return {"metric": "weight formats on the gate|up layer (K = 4096, N = 28672), weights packed by the library", "repeats": REPEATS,
+            "by_case": out}
 
 
 def llama70b(dev, steps, warmup):
-    """Config 4's decode cases (Llama-3-70B shapes, M = 1 and 16): the linear kernel alone, HIP graph replay over two
-    rotating weight sets of random codes (428 MB each).  Layers of 34-235 MB, where launch and ramp-up weigh less."""
+    """Config 4 (Llama-3-70B shapes): the decode cases (M = 1 and 16) as one HIP graph per weight set, two rotating sets
+    (428 MB each) packed by the library from seeded float32 weights; the prefill cases (M = 4096) as eager launches.
+    Per-case rows of the decode cases, with weights from HBM for every single case, are in `decode_cases`."""
     shapes = list(syn.LLAMA3_70B.values())
+    gen = torch.Generator(device=dev).manual_seed(70)
     sets = []
     for _ in range(2):
         one = []
         for (k, n) in shapes:
-            one.append((torch.randint(0, 256, (n * k // 2,), dtype=torch.uint8, device=dev),
-                        torch.rand(n * k // G, dtype=torch.float32, device=dev) * 0.01 + 0.001))
+            parts = [B.pack_weights(torch.randn((min(16384, n - r0), k), generator=gen, device=dev) * 0.02, G, B.LAYOUT_TILED)
+                     for r0 in range(0, n, 16384)]                          # in pieces: 16-row bands are contiguous in the tiled format
+            one.append((torch.cat([p_ for (p_, _) in parts]), torch.cat([s_ for (_, s_) in parts])))
+            del parts
         sets.append(one)
     sx = torch.tensor([0.05], dtype=torch.float32, device=dev)
     cases = []
@@ -347,33 +487,27 @@ def llama70b(dev, steps, warmup):
         run(0)
         torch.cuda.synchronize()
         graphs = [capture(lambda i=i: run(i)) for i in range(2)]
-        sec = time_graphs(graphs, steps, warmup) / steps
+        med, lo, hi = [t / steps for t in time_graphs_spread(graphs, steps, warmup)]
     torch.cuda.current_stream().wait_stream(side)
-    gbs = total / sec / 1e9
+    gbs = total / med / 1e9
     # the prefill cases of the same config (M = 4096), eager launches after untimed ones
-    flop, psec = 0.0, 0.0
+    flop, psec, per_shape = 0.0, 0.0, []
     x8 = torch.randint(0, 120, (4096, max(k for (k, _) in shapes)), dtype=torch.uint8, device=dev)
-    t0, t1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     for j, (k, n) in enumerate(shapes):
         y = torch.empty((4096, n), dtype=torch.bfloat16, device=dev)
         xs = x8[:, :k]
-        for i in range(3):
-            B.linear(xs, sx, sets[i % 2][j][0], sets[i % 2][j][1], n, G, B.LAYOUT_TILED, out=y)
-        torch.cuda.synchronize()
-        t0.record()
-        for i in range(3):
-            B.linear(xs, sx, sets[i % 2][j][0], sets[i % 2][j][1], n, G, B.LAYOUT_TILED, out=y)
-        t1.record()
-        torch.cuda.synchronize()
-        psec += t0.elapsed_time(t1) * 1e-3 / 3
+        sec = time_launches(lambda i: B.linear(xs, sx, sets[i % 2][j][0], sets[i % 2][j][1], n, G, B.LAYOUT_TILED, out=y), 3)[0]
+        psec += sec
         flop += 2.0 * 4096 * k * n
+        per_shape.append({"M": 4096, "K": k, "N": n, "us": round(sec * 1e6, 1), "tflops": round(2.0 * 4096 * k * n / sec / 1e12, 1)})
         del y
     tfl = flop / psec / 1e12
     return {"metric": "W4A8 linear on configs[3] (Llama-3-70B shapes): effective HBM GB/s of the decode cases (M in {1, 16}) "
                       "and TFLOP/s of the prefill cases (M = 4096)",
-            "value": round(gbs, 1), "unit": "GB/s", "frac_of_peak": round(gbs / HBM_PEAK_GBS, 4),
-            "us_per_launch": round(sec / len(cases) * 1e6, 2), "alg_bytes_per_launch": total // len(cases),
-            "prefill_tflops": round(tfl, 1), "prefill_frac_of_peak": round(tfl / FP8_PEAK_TFLOPS, 4)}
+            "value": round(gbs, 1), "unit": "GB/s", "frac_of_peak": round(gbs / HBM_PEAK_GBS, 4), "repeats": REPEATS,
+            "GBps_min_max": [round(total / hi / 1e9, 1), round(total / lo / 1e9, 1)],
+            "us_per_launch": round(med / len(cases) * 1e6, 2), "alg_bytes_per_launch": total // len(cases),
+            "prefill_tflops": round(tfl, 1), "prefill_frac_of_peak": round(tfl / FP8_PEAK_TFLOPS, 4), "prefill_shapes": per_shape}
 
 
 def calibration(dev):
@@ -497,24 +631,27 @@ def main():
             else:
                 step_graphs = [capture(lambda i=i: step(i)) for i in range(args.copies)]
                 lin_graphs = [capture(lambda i=i: linears_only(i)) for i in range(args.copies)]
-            sec = time_graphs(step_graphs, args.steps, args.warmup)
-            lin_sec = time_graphs(lin_graphs, args.steps, args.warmup)
+            repeats = 1 if args.eager else REPEATS                      # counter runs: one pass
+            sec, sec_lo, sec_hi = time_graphs_spread(step_graphs, args.steps, args.warmup, repeats)
+            lin_sec, lin_lo, lin_hi = time_graphs_spread(lin_graphs, args.steps, args.warmup, repeats)
             fused_sec = None
             if not args.eager:
                 step_fused(0)
                 torch.cuda.synchronize()
                 fused_graphs = [capture(lambda i=i: step_fused(i)) for i in range(args.copies)]
-                fused_sec = time_graphs(fused_graphs, args.steps, args.warmup)
+                fused_sec, f_lo, f_hi = time_graphs_spread(fused_graphs, args.steps, args.warmup)
                 del fused_graphs
         two_kernel_gbs = step_bytes / (sec / args.steps) / 1e9
         if fused_sec is not None and fused_sec < sec:
-            sec = fused_sec                                              # the step as the library runs it fastest
+            sec, sec_lo, sec_hi = fused_sec, f_lo, f_hi                  # the step as the library runs it fastest
         ms_per_step = sec / args.steps * 1e3
         value = step_bytes / (sec / args.steps) / 1e9
         lin_gbs = step_bytes / (lin_sec / args.steps) / 1e9
         result.update({
             "metric": "W4A8 linear effective HBM GB/s (decode sweep)", "value": round(value, 1), "unit": "GB/s",
             "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 5),
+            "repeats": repeats, "ms_per_step_min": round(sec_lo / args.steps * 1e3, 5),
+            "ms_per_step_max": round(sec_hi / args.steps * 1e3, 5),
             "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "fp8_e4m3", "data": "synthetic",
             "config": {"workload": "configs[1]: decode sweep, Llama-3-8B shapes, M in {1,4,16} x 4 (K,N), INT4 g128 "
                                    "weights, FP8 e4m3 activations, bf16 out; step = activation quantization + linear for each of the 12 cases",
@@ -527,6 +664,8 @@ def main():
                          "traffic": SKINNY_TRAFFIC_BYTES_PER_LAUNCH.get(args.copies),
                          "kernel": "linear_skinny_kernel", "launches_per_step": len(cases),
                          "avg_launch_us": round(lin_sec / args.steps / len(cases) * 1e6, 3),
+                         "avg_launch_us_min_max": [round(lin_lo / args.steps / len(cases) * 1e6, 3),
+                                                   round(lin_hi / args.steps / len(cases) * 1e6, 3)],
                          "alg_bytes_per_launch": step_bytes // len(cases)},
         })
         del cases, step_graphs, lin_graphs
@@ -542,34 +681,20 @@ def main():
                 c = Case(3, L, m, dev, pcfg["frac"], pcfg["mult"])
                 c.quantize()
                 reps = max(3, min(50, int(2e13 / (2.0 * m * L.k * L.n))))
-                # untimed launches first, about as many as will be timed: building the inputs on the host leaves the GPU
-                # idle for seconds, and its clocks take some milliseconds of load to come back up
-                for i in range(max(2, reps)):
-                    c.linear(i)
-                torch.cuda.synchronize()
-                t0, t1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-                t0.record()
-                for i in range(reps):
-                    c.linear(i)
-                t1.record()
-                torch.cuda.synchronize()
-                s = t0.elapsed_time(t1) * 1e-3 / reps
+                # untimed launches first, as many as one timed region holds: building the inputs on the host leaves the
+                # GPU idle for seconds, and its clocks take some milliseconds of load to come back up
+                rep_count = 1 if args.no_pow2 else REPEATS               # counter runs (--no-pow2): one timed region
+                s, s_lo, s_hi = time_launches(lambda i: c.linear(i), reps, rep_count)
                 flop = 2.0 * m * L.k * L.n
 
                 def pow2(i):
                     B.linear_pow2(c.x8, c.s_x, L.sets[i % len(L.sets)][0], p2[i % len(p2)], L.n, G, out=c.y)
                 s2 = s
                 if not args.no_pow2:
-                    for i in range(max(2, reps)):
-                        pow2(i)
-                    torch.cuda.synchronize()
-                    t0.record()
-                    for i in range(reps):
-                        pow2(i)
-                    t1.record()
-                    torch.cuda.synchronize()
-                    s2 = t0.elapsed_time(t1) * 1e-3 / reps
-                per_shape.append({"M": m, "K": L.k, "N": L.n, "us": round(s * 1e6, 2), "tflops": round(flop / s / 1e12, 1)})
+                    s2 = time_launches(pow2, reps)[0]
+                per_shape.append({"M": m, "K": L.k, "N": L.n, "us": round(s * 1e6, 2), "tflops": round(flop / s / 1e12, 1),
+                                  "tflops_min_max": [round(flop / s_hi / 1e12, 1), round(flop / s_lo / 1e12, 1)],
+                                  "launch_shape": list(B.linear_launch_shape(m, L.k, L.n, G, c.ws is not None))})
                 if not args.no_pow2:
                     per_shape[-1]["pow2_tflops"] = round(flop / s2 / 1e12, 1)
                 if tot_sec_lib is not None and not args.no_pow2:
@@ -586,12 +711,13 @@ def main():
         tfl = tot_flop / tot_sec / 1e12
         tfl2 = tot_flop / tot_sec_p2 / 1e12 if tot_sec_p2 > 0 else 0.0
         result["prefill"] = {"metric": "W4A8 linear TFLOP/s (prefill sweep, configs[2])", "value": round(tfl, 1),
-                             "unit": "TFLOP/s", "shapes": per_shape,
+                             "unit": "TFLOP/s", "repeats": REPEATS, "shapes": per_shape,
                              "roofline": {"bound": "mfma", "achieved": round(tfl, 1), "peak": FP8_PEAK_TFLOPS,
                                           "unit": "TFLOP/s", "frac": round(tfl / FP8_PEAK_TFLOPS, 4),
                                           "traffic": PREFILL_TRAFFIC_BYTES_PER_LAUNCH,
                                           "alg_bytes_per_launch": tot_bytes // len(per_shape),
-                                          "kernel": "linear_mfma_kernel"}}
+                                          "kernel": "linear_mfma2d_kernel (the 2048- and 8192-token shapes and gate|up at 512); "
+                                                    "linear_mfma_kernel (the other 512-token shapes)"}}
         if not args.no_pow2:
             result["prefill"]["pow2_scales"] = {"metric": "the same sweep through w4a8_linear_pow2 (group scales rounded up "
                                                        "to powers of two and applied by the block-scaled MFMA)",
@@ -622,6 +748,7 @@ def main():
         del layers
         torch.cuda.empty_cache()
         if not args.no_block:
+            result["decode_cases"] = decode_cases(dev)
             result["block"] = block_latency(dev, 50, 5)
             result["weight_modes"] = weight_modes(dev)
             result["calibration"] = calibration(dev)

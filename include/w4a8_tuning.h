@@ -34,6 +34,14 @@ int w4a8_linear_variant(const uint8_t* x8_dev, int64_t M, int64_t K, int64_t ldx
                         int32_t param1, void* stream);
 
 /*
+ * The launch shape w4a8_linear chooses by itself for these sizes (tiled layout, bf16 output), in the terms of
+ * w4a8_linear_variant: shape4[0] = path (0, 1 or 2; 3 = the second tiling with K ranges across workgroups, taken only
+ * when the caller hands w4a8_linear a workspace -- with_workspace != 0), shape4[1] = param0, shape4[2] = param1,
+ * shape4[3] = K ranges (path 3, else 0).  shape4 is HOST memory, four int32.  Nothing is launched.
+ */
+int w4a8_linear_launch_shape(int64_t M, int64_t K, int64_t N, int32_t group_size, int32_t with_workspace, int32_t* shape4);
+
+/*
  * The second tiling with K multiplied in `ksplit` ranges by different workgroups (what w4a8_linear does with a
  * workspace on the shapes w4a8_linear_workspace_bytes() names), tile and split chosen by the caller.  workspace_dev:
  * 16-byte aligned, at least ksplit * M * round_up(N, 64) * 4 bytes (W4A8_ERR_WORKSPACE otherwise).  tile as param0 of

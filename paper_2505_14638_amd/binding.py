@@ -35,6 +35,7 @@ SIGNATURES = {
                                               _c_i32, _c_i64, _c_vp]),
     "w4a8_linear_variant": (_c_i32, [_c_vp, _c_i64, _c_i64, _c_i64, _c_vp, _c_vp, _c_vp, _c_i64, _c_i32, _c_vp,
                                      _c_i32, _c_i64, _c_i32, _c_i32, _c_i32, _c_vp]),
+    "w4a8_linear_launch_shape": (_c_i32, [_c_i64, _c_i64, _c_i64, _c_i32, _c_i32, _c_vp]),
     "w4a8_linear_splitk_variant": (_c_i32, [_c_vp, _c_i64, _c_i64, _c_i64, _c_vp, _c_vp, _c_vp, _c_i64, _c_i32, _c_vp,
                                             _c_i32, _c_i64, _c_i32, _c_i32, _c_vp, _c_sz, _c_vp]),
     "w4a8_dequant_weights": (_c_i32, [_c_vp, _c_i64, _c_i64, _c_i32, _c_vp, _c_vp]),
@@ -205,6 +206,14 @@ def linear_static_workspace(x8, x_scale, packed, w_scales, n, group_size, out_dt
                                               out.data_ptr(), _dtype_code(out), out.stride(0) if m > 1 else max(n, out.stride(0)),
                                               _stream()), "w4a8_linear_static_workspace")
     return out
+
+
+def linear_launch_shape(m: int, k: int, n: int, group_size: int, with_workspace: bool = False):
+    """(path, param0, param1, k_ranges) of the launch w4a8_linear chooses for these sizes (see w4a8_linear_variant)."""
+    out = (ctypes.c_int32 * 4)()
+    _check(lib().w4a8_linear_launch_shape(m, k, n, group_size, 1 if with_workspace else 0, ctypes.addressof(out)),
+           "w4a8_linear_launch_shape")
+    return tuple(int(v) for v in out)
 
 
 def linear_splitk_variant(x8, x_scale, packed, w_scales, n, group_size, out, tile: int, ksplit: int, workspace: torch.Tensor):

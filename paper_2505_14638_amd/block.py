@@ -29,6 +29,7 @@ class DecoderBlockLinears:
         self.weights = {}
         self.scales_x = {}
         self._buffers = {}
+        self._workspace = None                                   # scratch of w4a8_linear (K ranges across workgroups), grown on demand
 
     def load_layer(self, name: str, w_f32: torch.Tensor) -> None:
         """Quantize (round-to-nearest INT4) and pack one [N, K] float32 weight matrix on the device."""
@@ -49,13 +50,23 @@ class DecoderBlockLinears:
             self._buffers[key] = b
         return b
 
+    def _ws(self, name: str, m: int):
+        """The workspace w4a8_linear asks for on this layer at this batch size (None where it asks for none)."""
+        k, n = self.dims[name]
+        need = B.linear_workspace_bytes(m, k, n, self.group_size)
+        if need == 0:
+            return None
+        if self._workspace is None or self._workspace.numel() < need:
+            self._workspace = torch.empty(need, dtype=torch.uint8, device=self.device)
+        return self._workspace
+
     def _linear(self, name: str, x: torch.Tensor, m: int) -> torch.Tensor:
         k, n = self.dims[name]
         x8 = self._buf((name, "x8", m), (m, k), torch.uint8)
         y = self._buf((name, "y", m), (m, n), torch.bfloat16)
         B.quantize_act(x, self.scales_x[name], out=x8)
         packed, scales = self.weights[name]
-        B.linear(x8, self.scales_x[name], packed, scales, n, self.group_size, B.LAYOUT_TILED, out=y)
+        B.linear(x8, self.scales_x[name], packed, scales, n, self.group_size, B.LAYOUT_TILED, out=y, workspace=self._ws(name, m))
         return y
 
     def _forward_fused(self, x: torch.Tensor, keep: dict | None) -> torch.Tensor:
@@ -73,7 +84,7 @@ class DecoderBlockLinears:
                           out=self._buf(("gate_up", "y", m), (m, 2 * self.ffn), torch.bfloat16))
             B.silu_mul_quantize(gu, sx["down"], out=h8)
         y = B.linear(h8, sx["down"], *w["down"], self.hidden, g, B.LAYOUT_TILED,
-                     out=self._buf(("down", "y", m), (m, self.hidden), torch.bfloat16))
+                     out=self._buf(("down", "y", m), (m, self.hidden), torch.bfloat16), workspace=self._ws("down", m))
         if keep is not None:
             keep.update(qkv_x8=x8, o_x8=qkv8[:, :self.hidden], gate_up_x8=o8, down_x8=h8, down=y)
         return y

@@ -249,6 +249,39 @@ int w4a8_linear_variant(const uint8_t* x8_dev, int64_t M, int64_t K, int64_t ldx
     return W4A8_ERR_SHAPE;
 }
 
+int w4a8_linear_launch_shape(int64_t M, int64_t K, int64_t N, int32_t group_size, int32_t with_workspace, int32_t* shape4) {
+    if (!shape4) return W4A8_ERR_NULL;
+    if (M < 1 || M > DIM_MAX) return W4A8_ERR_SHAPE;
+    if (int e = check_weight_shape(N, K, group_size, W4A8_LAYOUT_TILED)) return e;
+    shape4[0] = shape4[1] = shape4[2] = shape4[3] = 0;
+    if (takes_skinny_path(M, K, N)) {
+        int nt = 0, waves = 0, depth = 0;
+        if (!skinny_launch_shape(M, K, N, W4A8_BF16, MODE_CODE_EXACT, 0, nt, waves, depth)) return W4A8_ERR_SHAPE;
+        shape4[1] = nt;
+        shape4[2] = waves | (depth << 8);
+        return W4A8_OK;
+    }
+    int cfg = 0, ksplit = 0;
+    if (with_workspace) mfma2d_choose_ksplit(M, K, N, cfg, ksplit);
+    if (ksplit > 1) {
+        shape4[0] = 3;
+        shape4[1] = cfg;
+        shape4[3] = ksplit;
+        return W4A8_OK;
+    }
+    int mf = 0, ks = 0, tpw = 0, cfg2d = -1;
+    if (!mfma_launch_shape(M, K, N, MODE_CODE_EXACT, mf, ks, tpw, cfg2d)) return W4A8_ERR_SHAPE;
+    if (cfg2d >= 0) {
+        shape4[0] = 2;
+        shape4[1] = cfg2d;
+    } else {
+        shape4[0] = 1;
+        shape4[1] = mf;
+        shape4[2] = ks | (tpw << 8);
+    }
+    return W4A8_OK;
+}
+
 int w4a8_linear_splitk_variant(const uint8_t* x8_dev, int64_t M, int64_t K, int64_t ldx8, const float* x_scale_dev,
                                const uint8_t* packed_dev, const float* w_scales_dev, int64_t N, int32_t group_size,
                                void* y_dev, w4a8_dtype y_dtype, int64_t ldy, int32_t tile, int32_t ksplit,

@@ -456,33 +456,28 @@ void launch_one(const LinearArgs& a, dim3 grid, int grid_m, int grid_n, hipStrea
 
 }  // namespace
 
-// mf = 16-token blocks per workgroup (4, 8 or 16), ks = K-split groups (1, 2 or 4), tpw = weight bands per wavefront
-// (1 or 2); 0 = chosen from the shape.
-int launch_linear_mfma_tiled(const uint8_t* x8, int64_t M, int64_t K, int64_t ldx8, const float* s_x,
-                             const uint8_t* packed, const float* scales, int64_t N, int32_t G, void* y,
-                             w4a8_dtype ydt, int64_t ldy, int mf, int ks, int tpw, const float* w_out, int per_channel,
-                             int mode, const float* y_scale, hipStream_t st) {
-    if (((int)ydt == YDT_E4M3 || (int)ydt == YDT_SILU_E4M3) && (mode != MODE_CODE_EXACT || !y_scale)) return W4A8_ERR_DTYPE;
-    if ((int)ydt == YDT_SILU_E4M3 && N % 32 != 0) return W4A8_ERR_SHAPE;   // whole pairs of gate and up bands
-    if (!(mf == 0 || mf == 4 || mf == 8 || mf == 16) || !(ks == 0 || ks == 1 || ks == 2 || ks == 4) || tpw < 0 || tpw > 2)
-        return W4A8_ERR_SHAPE;
-    const int C = (int)(K / 128), cpg = G / 128, NG = (int)(K / G);
+// Launch shape of the many-token kernels for a layer; requested values of mf / ks / tpw other than 0 are kept.
+// cfg2d >= 0 on return: the layer goes to the second tiling (linear_mfma2d.hip) with that workgroup tile.
+//  - Large grids in the code-exact and power-of-two modes go to the second tiling (a 2-D grid of wavefronts over
+//    256-token tiles, expansion shared through LDS, persistent workgroups): 256 x 256 tiles when they fill the 256
+//    compute units, 256 x 128 tiles in two workgroups per compute unit when those do, as long as padding the tokens to a
+//    multiple of 256 wastes less than a quarter.  Measured on the Llama-3 shapes: +5...12 % at 8192 tokens, +3...15 %
+//    at 2048; smaller grids stay with the first tiling.
+//  - First tiling: tall token blocks amortize the nibble expansion over more MFMAs; two bands per wavefront halve the
+//    LDS reads per MFMA (the activation operand is reused); K-splits shorten the dependent chain of passes (each waits
+//    for the copies of the next) when the grid is too small to fill the chip, at the price of a wider activation block
+//    to copy per pass.  Sweeps over the Llama-3 layer shapes are matched by: the first shape, in the list's order of
+//    preference, that yields about 1.5 workgroups per compute unit.
+bool mfma_launch_shape(int64_t M, int64_t K, int64_t N, int mode, int& mf, int& ks, int& tpw, int& cfg2d) {
+    cfg2d = -1;
+    const int C = (int)(K / 128);
     const int n_tiles = (int)((N + 15) / 16);
-    // Workgroup shape.  Tall token blocks amortize the nibble expansion over more MFMAs; two bands per wavefront halve
-    // the LDS reads per MFMA (the activation operand is reused); K-splits shorten the dependent chain of passes (each
-    // waits for the copies of the next) when the grid is too small to fill the chip, at the price of a wider activation
-    // block to copy per pass.  Sweeps over the Llama-3 layer shapes are matched by: the first shape, in this order of
-    // preference, that yields about 1.5 workgroups per compute unit.
-    // Large grids in the code-exact and power-of-two modes go to the second tiling (linear_mfma2d.hip: a 2-D grid of
-    // wavefronts over 256-token tiles, expansion shared through LDS, persistent workgroups): 256 x 256 tiles when they fill
-    // the 256 compute units, 256 x 128 tiles in two workgroups per compute unit when those do, as long as padding the
-    // tokens to a multiple of 256 wastes less than a quarter.  Measured on the Llama-3 shapes: +5...12 % at 8192 tokens,
-    // +3...15 % at 2048; smaller grids stay with the shapes below.
     if (mf == 0 && ks == 0 && tpw == 0 && (mode == MODE_CODE_EXACT || mode == MODE_POW2)) {
         const int64_t tm = (M + 255) / 256, t1 = tm * ((N + 255) / 256), t4 = tm * ((N + 127) / 128);
-        if (4 * M >= 3 * 256 * tm && (t1 >= 200 || t4 >= 200))
-            return launch_linear_mfma2d(x8, M, K, ldx8, s_x, packed, scales, N, G, y, ydt, ldy, t1 >= 200 ? 1 : 4, 0, 0, mode,
-                                        y_scale, st);
+        if (4 * M >= 3 * 256 * tm && (t1 >= 200 || t4 >= 200)) {
+            cfg2d = t1 >= 200 ? 1 : 4;
+            return true;
+        }
     }
     static const int cand[W4A8_MFMA_SHAPES][3] = W4A8_MFMA_SHAPE_LIST;
     if (mf == 0 || ks == 0 || tpw == 0) {
@@ -501,11 +496,30 @@ int launch_linear_mfma_tiled(const uint8_t* x8, int64_t M, int64_t K, int64_t ld
             if (groups >= 384) { pick = q; break; }
         }
         if (pick < 0) pick = fallback;
-        if (pick < 0) return W4A8_ERR_SHAPE;                     // a combination that is not built
+        if (pick < 0) return false;                              // a combination that is not built
         mf = cand[pick][0];
         ks = cand[pick][1];
         tpw = cand[pick][2];
     }
+    return true;
+}
+
+// mf = 16-token blocks per workgroup (4, 8 or 16), ks = K-split groups (1, 2 or 4), tpw = weight bands per wavefront
+// (1 or 2); 0 = chosen from the shape.
+int launch_linear_mfma_tiled(const uint8_t* x8, int64_t M, int64_t K, int64_t ldx8, const float* s_x,
+                             const uint8_t* packed, const float* scales, int64_t N, int32_t G, void* y,
+                             w4a8_dtype ydt, int64_t ldy, int mf, int ks, int tpw, const float* w_out, int per_channel,
+                             int mode, const float* y_scale, hipStream_t st) {
+    if (((int)ydt == YDT_E4M3 || (int)ydt == YDT_SILU_E4M3) && (mode != MODE_CODE_EXACT || !y_scale)) return W4A8_ERR_DTYPE;
+    if ((int)ydt == YDT_SILU_E4M3 && N % 32 != 0) return W4A8_ERR_SHAPE;   // whole pairs of gate and up bands
+    if (!(mf == 0 || mf == 4 || mf == 8 || mf == 16) || !(ks == 0 || ks == 1 || ks == 2 || ks == 4) || tpw < 0 || tpw > 2)
+        return W4A8_ERR_SHAPE;
+    const int C = (int)(K / 128), cpg = G / 128, NG = (int)(K / G);
+    const int n_tiles = (int)((N + 15) / 16);
+    int cfg2d = -1;
+    if (!mfma_launch_shape(M, K, N, mode, mf, ks, tpw, cfg2d)) return W4A8_ERR_SHAPE;
+    if (cfg2d >= 0)
+        return launch_linear_mfma2d(x8, M, K, ldx8, s_x, packed, scales, N, G, y, ydt, ldy, cfg2d, 0, 0, mode, y_scale, st);
     const int per_wg = (8 / ks) * tpw;
     const int grid_n = (n_tiles + per_wg - 1) / per_wg;
     const int grid_m = (int)((M + 16 * mf - 1) / (16 * mf));

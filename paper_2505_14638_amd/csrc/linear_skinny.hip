@@ -358,25 +358,22 @@ int launch_mt(const LinearArgs& a, int mt, int nt, int depth, int waves, hipStre
 
 }  // namespace
 
-int launch_linear_skinny(const uint8_t* x8, int64_t M, int64_t K, int64_t ldx8, const float* s_x,
-                         const uint8_t* packed, const float* scales, int64_t N, int32_t G, void* y, w4a8_dtype ydt,
-                         int64_t ldy, int nt, int waves, int depth, const float* w_out, int per_channel, int mode,
-                         const float* y_scale, hipStream_t st, int xq, uint8_t* x8_out) {
-    if (M < 1 || M > 64) return W4A8_ERR_SHAPE;
-    if (xq != 0 && (M > 16 || M * K > 65536 || mode != MODE_CODE_EXACT)) return W4A8_ERR_SHAPE;
-    const int C = (int)(K / 128), cpg = G / 128, NG = (int)(K / G);
+// Launch shape of the skinny kernel for a layer, from sweeps over the Llama-3-8B/70B layer shapes (requested values
+// other than 0 are kept):
+//  - two bands per wavefront when the activation operand is wide enough to be worth sharing (M > 8 on layers
+//    with enough bands) or when the layer is large enough that fewer, longer-running workgroups ramp better;
+//  - split K over as many wavefronts (a power of two) as it takes to have ~8192 (~2400 for M > 8) of them in flight;
+//  - four bands per wavefront from 17 tokens on when the layer is very wide (every chunk of activations a wavefront
+//    loads is then 2 KB or more, against 1 KB of nibbles per band), with fewer, longer-running wavefronts.
+// Returns false for a combination that is not built.
+bool skinny_launch_shape(int64_t M, int64_t K, int64_t N, int ydt, int mode, int xq, int& nt, int& waves, int& depth) {
+    const int C = (int)(K / 128);
     const int n_tiles = (int)((N + 15) / 16);
     const int mt = (M <= 16) ? 1 : (M <= 32) ? 2 : 4;
-    // Launch shape, from sweeps over the Llama-3-8B/70B layer shapes:
-    //  - two bands per wavefront when the activation operand is wide enough to be worth sharing (M > 8 on layers
-    //    with enough bands) or when the layer is large enough that fewer, longer-running workgroups ramp better;
-    //  - split K over as many wavefronts (a power of two) as it takes to have ~8192 (~2400 for M > 8) of them in flight.
-    //  - four bands per wavefront from 17 tokens on when the layer is very wide (every chunk of activations a wavefront
-    //    loads is then 2 KB or more, against 1 KB of nibbles per band), with fewer, longer-running wavefronts.
     const bool wide_many = M > 16 && n_tiles >= 1024;
     if (nt == 0) nt = wide_many ? 4 : ((M > 8 && n_tiles >= 384) || (int64_t)n_tiles * C >= 100000) ? 2 : 1;
-    if (xq != 0 && nt > 2) return W4A8_ERR_SHAPE;
-    if (nt != 1 && nt != 2 && nt != 4) return W4A8_ERR_SHAPE;
+    if (xq != 0 && nt > 2) return false;
+    if (nt != 1 && nt != 2 && nt != 4) return false;
     if (waves == 0) {
         const int grid = (n_tiles + nt - 1) / nt;
         const int target = (wide_many && nt == 4) ? (M > 32 ? 896 : 2048) : M > 8 ? 2400 : 8192;
@@ -390,13 +387,25 @@ int launch_linear_skinny(const uint8_t* x8, int64_t M, int64_t K, int64_t ldx8, 
     // The fused gate|up layer needs gate and up tiles in one workgroup.  It keeps the split of K the plain layer would
     // use on the same shape, so that every partial sum, and with it every output byte, is the same as in the unfused
     // sequence.
-    if ((int)ydt == YDT_SILU_E4M3 && nt == 1) nt = 2;
+    if (ydt == YDT_SILU_E4M3 && nt == 1) nt = 2;
     const int thread_cap = max_threads(mt * nt, mode == MODE_ASYM || mode == MODE_ASYM_TWO,
-                                       (int)ydt == YDT_SILU_E4M3 && mt == 2 && nt == 2);
+                                       ydt == YDT_SILU_E4M3 && mt == 2 && nt == 2);
     while (waves > 1 && (waves * mt * nt > 64 || waves * 64 > thread_cap)) --waves;   // LDS and registers
-    if (waves < 1 || waves > 16 || waves * mt * nt > 64 || waves * 64 > thread_cap) return W4A8_ERR_SHAPE;
+    if (waves < 1 || waves > 16 || waves * mt * nt > 64 || waves * 64 > thread_cap) return false;
     if (depth == 0) depth = 2;                                   // deeper rings cost occupancy and measured no faster
-    if (depth != 2 && depth != 4) return W4A8_ERR_SHAPE;
+    return depth == 2 || depth == 4;
+}
+
+int launch_linear_skinny(const uint8_t* x8, int64_t M, int64_t K, int64_t ldx8, const float* s_x,
+                         const uint8_t* packed, const float* scales, int64_t N, int32_t G, void* y, w4a8_dtype ydt,
+                         int64_t ldy, int nt, int waves, int depth, const float* w_out, int per_channel, int mode,
+                         const float* y_scale, hipStream_t st, int xq, uint8_t* x8_out) {
+    if (M < 1 || M > 64) return W4A8_ERR_SHAPE;
+    if (xq != 0 && (M > 16 || M * K > 65536 || mode != MODE_CODE_EXACT)) return W4A8_ERR_SHAPE;
+    const int C = (int)(K / 128), cpg = G / 128, NG = (int)(K / G);
+    const int n_tiles = (int)((N + 15) / 16);
+    const int mt = (M <= 16) ? 1 : (M <= 32) ? 2 : 4;
+    if (!skinny_launch_shape(M, K, N, (int)ydt, mode, xq, nt, waves, depth)) return W4A8_ERR_SHAPE;
     const LinearArgs a{x8, (int)M, ldx8, s_x, packed, scales, (int)N, n_tiles, C, cpg, NG, y, ldy, w_out, per_channel, mode, y_scale,
                        xq, x8_out};
     if ((int)ydt == YDT_E4M3) {

@@ -7,15 +7,24 @@
 namespace w4a8 {
 namespace {
 
+// Every wavefront reads runs of 8 KiB (eight independent 16-byte loads per lane in flight, each a whole KiB per
+// wavefront), runs dealt round-robin to the wavefronts of a grid sized to the chip (eight workgroups per compute unit).
+constexpr int STREAM_WORKGROUPS = 2048, STREAM_LOADS = 8;
+
 __global__ void __launch_bounds__(256) stream_read_kernel(const uint4* __restrict__ p, size_t n, uint32_t* sink) {
     uint32_t acc = 0;
-    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-    const size_t stride = (size_t)gridDim.x * blockDim.x;
-    for (; i + 3 * stride < n; i += 4 * stride) {
-        const uint4 a = p[i], b = p[i + stride], c = p[i + 2 * stride], d = p[i + 3 * stride];
-        acc += a.x ^ a.y ^ a.z ^ a.w ^ b.x ^ b.y ^ b.z ^ b.w ^ c.x ^ c.y ^ c.z ^ c.w ^ d.x ^ d.y ^ d.z ^ d.w;
+    const size_t lane = threadIdx.x & 63;
+    const size_t wave = (size_t)blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6), waves = (size_t)gridDim.x * (blockDim.x >> 6);
+    const size_t run = (size_t)STREAM_LOADS * 64;                // 16-byte units per run
+    size_t base = wave * run;
+    for (; base + run <= n; base += waves * run) {
+        uint4 v[STREAM_LOADS];
+#pragma unroll
+        for (int j = 0; j < STREAM_LOADS; ++j) v[j] = p[base + (size_t)j * 64 + lane];
+#pragma unroll
+        for (int j = 0; j < STREAM_LOADS; ++j) acc += v[j].x ^ v[j].y ^ v[j].z ^ v[j].w;
     }
-    for (; i < n; i += stride) {
+    for (size_t i = base + lane; i < n && i < base + run; i += 64) {   // the last, partial run
         const uint4 a = p[i];
         acc += a.x ^ a.y ^ a.z ^ a.w;
     }
@@ -55,7 +64,7 @@ extern "C" {
 int w4a8_probe_stream_read(const void* buf_dev, size_t bytes, uint32_t* sink_dev, void* stream) {
     if (!buf_dev || !sink_dev) return W4A8_ERR_NULL;
     if (bytes < 16 || reinterpret_cast<uintptr_t>(buf_dev) % 16) return W4A8_ERR_ALIGN;
-    hipLaunchKernelGGL(stream_read_kernel, dim3(16384), dim3(256), 0, static_cast<hipStream_t>(stream),
+    hipLaunchKernelGGL(stream_read_kernel, dim3(STREAM_WORKGROUPS), dim3(256), 0, static_cast<hipStream_t>(stream),
                        static_cast<const uint4*>(buf_dev), bytes / 16, sink_dev);
     return launch_status();
 }

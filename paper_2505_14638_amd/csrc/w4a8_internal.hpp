@@ -72,6 +72,9 @@ int launch_linear_skinny(const uint8_t* x8, int64_t M, int64_t K, int64_t ldx8, 
                          const uint8_t* packed, const float* scales, int64_t N, int32_t G, void* y, w4a8_dtype ydt,
                          int64_t ldy, int nt, int waves, int depth, const float* w_out, int per_channel, int mode,
                          const float* y_scale, hipStream_t st, int xq = 0, uint8_t* x8_out = nullptr);
+// The launch shapes the launchers choose by themselves (requested values other than 0 are kept); false: not built.
+bool skinny_launch_shape(int64_t M, int64_t K, int64_t N, int ydt, int mode, int xq, int& nt, int& waves, int& depth);
+bool mfma_launch_shape(int64_t M, int64_t K, int64_t N, int mode, int& mf, int& ks, int& tpw, int& cfg2d);
 // mf = 16-token blocks per workgroup, ks = K-split groups per workgroup, tpw = weight bands per wavefront; 0: chosen
 int launch_linear_mfma_tiled(const uint8_t* x8, int64_t M, int64_t K, int64_t ldx8, const float* s_x,
                              const uint8_t* packed, const float* scales, int64_t N, int32_t G, void* y,

@@ -67,6 +67,11 @@ int main() {
                                         256, 128, P, W4A8_BF16, 256, nullptr), W4A8_OK);
     EXPECT(w4a8_linear_splitk_variant((const uint8_t*)P, 128, 14336, 14336, (const float*)P, (const uint8_t*)P, (const float*)P, 4096,
                                       128, P, W4A8_BF16, 4096, 5, 4, P, (size_t)4 * 128 * 4096 * 4 - 1, nullptr), W4A8_ERR_WORKSPACE);
+    int32_t shape[4] = {9, 9, 9, 9};
+    EXPECT(w4a8_linear_launch_shape(128, 14336, 4096, 128, 1, shape), W4A8_OK);
+    EXPECT(shape[0], 3);
+    EXPECT(w4a8_linear_launch_shape(128, 14336, 4096, 128, 1, nullptr), W4A8_ERR_NULL);
+    EXPECT(w4a8_linear_launch_shape(128, 14336, 4096, 100, 1, shape), W4A8_ERR_GROUP);
     EXPECT(w4a8_linear_variant((const uint8_t*)P, 100, 256, 256, (const float*)P, (const uint8_t*)P, (const float*)P, 64, 128, P,
                                W4A8_BF16, 64, 0, 1, 1, nullptr), W4A8_ERR_SHAPE);
     EXPECT(w4a8_linear_quantize_in(P, W4A8_BF16, 17, 256, 256, (const float*)P, (const uint8_t*)P, (const float*)P, 64, 128, P,

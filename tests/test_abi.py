@@ -138,6 +138,12 @@ def test_linear_validation(L):
     assert fn(P, 128, 14336, 14336, P, P, P, 4096, 96, P, B.BF16, 4096, None) == 3
     assert wb(512, 28672, 8192, 128) > 16 << 20
     assert fn(P, 512, 28672, 28672, P, P, P, 8192, 128, P, B.BF16, 8192, None) == 7
+    # the launch shape the library chooses, as w4a8_linear_variant takes it
+    assert B.linear_launch_shape(1, 4096, 4096, 128) == (0, 1, 16 | (2 << 8), 0)
+    assert B.linear_launch_shape(8192, 4096, 4096, 128) == (2, 1, 0, 0) and B.linear_launch_shape(2048, 4096, 4096, 128) == (2, 4, 0, 0)
+    assert B.linear_launch_shape(512, 4096, 4096, 128)[0] == 1
+    assert B.linear_launch_shape(128, 14336, 4096, 128, True) == (3, 5, 0, 8) and B.linear_launch_shape(128, 14336, 4096, 128)[0] == 1
+    assert L.w4a8_linear_launch_shape(128, 14336, 4096, 128, 0, None) == 1 and L.w4a8_linear_launch_shape(0, 14336, 4096, 128, 0, P) == 2
     fs = L.w4a8_linear_splitk_variant
     sk = (P, 128, 14336, 14336, P, P, P, 4096, 128, P, B.BF16, 4096)
     assert fs(*sk, 5, 4, P, 4 * 128 * 4096 * 4 - 1, None) == 7
