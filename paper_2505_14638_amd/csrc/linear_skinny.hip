@@ -358,25 +358,39 @@ int launch_mt(const LinearArgs& a, int mt, int nt, int depth, int waves, hipStre
 
 }  // namespace
 
-// Launch shape of the skinny kernel for a layer, from sweeps over the Llama-3-8B/70B layer shapes (requested values
-// other than 0 are kept):
+// Launch shape of the skinny kernel for a layer, from sweeps over the Llama-3-8B/70B layer shapes with the weights coming
+// from HBM (requested values other than 0 are kept):
 //  - two bands per wavefront when the activation operand is wide enough to be worth sharing (M > 8 on layers
 //    with enough bands) or when the layer is large enough that fewer, longer-running workgroups ramp better;
-//  - split K over as many wavefronts (a power of two) as it takes to have ~8192 (~2400 for M > 8) of them in flight;
 //  - four bands per wavefront from 17 tokens on when the layer is very wide (every chunk of activations a wavefront
-//    loads is then 2 KB or more, against 1 KB of nibbles per band), with fewer, longer-running wavefronts.
+//    loads is then 2 KB or more, against 1 KB of nibbles per band), with fewer, longer-running wavefronts;
+//  - up to 16 tokens, a grid between one and two workgroups per compute unit (256 of them) leaves half of the chip with
+//    twice the work of the other half: one more doubling of the bands per wavefront brings it to at most one each;
+//  - split K over as many wavefronts (a power of two) as it takes to have ~16384 (~2400 for M > 8) of them in flight;
+//  - up to 8 tokens on long rows (K >= 8192) with more workgroups than the chip holds at once: eight wavefronts, each
+//    with four chunks in flight where that ring is built (a workgroup's wavefronts start one after the other, about
+//    60 ns apart, so half as many of them have their loads under way sooner).
+// The split of K (the number of wavefronts) never depends on the output type or on whether the activation quantization is
+// folded in: the fused forms add up the same partial sums in the same order as the plain layer and give the same bytes.
 // Returns false for a combination that is not built.
 bool skinny_launch_shape(int64_t M, int64_t K, int64_t N, int ydt, int mode, int xq, int& nt, int& waves, int& depth) {
     const int C = (int)(K / 128);
     const int n_tiles = (int)((N + 15) / 16);
     const int mt = (M <= 16) ? 1 : (M <= 32) ? 2 : 4;
     const bool wide_many = M > 16 && n_tiles >= 1024;
-    if (nt == 0) nt = wide_many ? 4 : ((M > 8 && n_tiles >= 384) || (int64_t)n_tiles * C >= 100000) ? 2 : 1;
-    if (xq != 0 && nt > 2) return false;
+    const bool auto_nt = nt == 0;
+    bool long_rows = false;
+    if (auto_nt) {
+        nt = wide_many ? 4 : ((M > 8 && n_tiles >= 384) || (int64_t)n_tiles * C >= 100000) ? 2 : 1;
+        const int grid = (n_tiles + nt - 1) / nt;
+        if (mt == 1 && grid > 256 && grid < 512 && nt < 4) nt *= 2;
+        long_rows = waves == 0 && nt == 1 && M <= 8 && C >= 64 && n_tiles >= 512;
+    }
     if (nt != 1 && nt != 2 && nt != 4) return false;
+    if (long_rows) waves = 8;
     if (waves == 0) {
         const int grid = (n_tiles + nt - 1) / nt;
-        const int target = (wide_many && nt == 4) ? (M > 32 ? 896 : 2048) : M > 8 ? 2400 : 8192;
+        const int target = (wide_many && nt == 4) ? (M > 32 ? 896 : 2048) : M > 8 ? 2400 : 16384;
         const float want = (float)target / (float)grid;
         waves = 2;                                               // the power of two nearest to `want` (ratio-wise), 2..16:
         while (waves < 16 && (float)(waves * waves * 2) < want * want) waves *= 2;
@@ -384,16 +398,20 @@ bool skinny_launch_shape(int64_t M, int64_t K, int64_t N, int ydt, int mode, int
         while (waves < 16 && (int64_t)n_tiles * C * 1024 > (int64_t)grid * waves * 65536) waves *= 2;   // odd counts split K unevenly and measured slower
     }
     if (waves > C) waves = C;
-    // The fused gate|up layer needs gate and up tiles in one workgroup.  It keeps the split of K the plain layer would
-    // use on the same shape, so that every partial sum, and with it every output byte, is the same as in the unfused
-    // sequence.
+    // The fused gate|up layer needs gate and up tiles in one workgroup.
     if (ydt == YDT_SILU_E4M3 && nt == 1) nt = 2;
     const int thread_cap = max_threads(mt * nt, mode == MODE_ASYM || mode == MODE_ASYM_TWO,
                                        ydt == YDT_SILU_E4M3 && mt == 2 && nt == 2);
     while (waves > 1 && (waves * mt * nt > 64 || waves * 64 > thread_cap)) --waves;   // LDS and registers
     if (waves < 1 || waves > 16 || waves * mt * nt > 64 || waves * 64 > thread_cap) return false;
-    if (depth == 0) depth = 2;                                   // deeper rings cost occupancy and measured no faster
-    return depth == 2 || depth == 4;
+    // the form that quantizes its own input is built for one or two bands: fewer bands, the same split of K
+    if (xq != 0 && nt > 2) {
+        if (!auto_nt) return false;
+        nt = 2;
+    }
+    const bool deep_built = mt == 1 && nt == 1 && xq == 0 && (ydt == (int)W4A8_BF16 || ydt == (int)W4A8_F32) && mode == MODE_CODE_EXACT;
+    if (depth == 0) depth = (long_rows && deep_built) ? 4 : 2;   // elsewhere deeper rings cost occupancy and measured no faster
+    return depth == 2 || (depth == 4 && deep_built);
 }
 
 int launch_linear_skinny(const uint8_t* x8, int64_t M, int64_t K, int64_t ldx8, const float* s_x,
