@@ -410,7 +410,7 @@ def block_latency(dev, steps, warmup, sets=3):
     return {"metric": "decoder-block linear stack latency (config 5: QKV, O, gate|up, SiLU*mul, down; hidden 4096, "
                       "FFN 14336)", "unit": "us per block", "weight_sets": sets, "repeats": REPEATS, **out,
             "fused": "same outputs with each intermediate's FP8 quantization folded into the kernel that produces it "
-                     "(6 launches instead of 9)",
+                     "and, up to 8 tokens, the quantization of the block input into the QKV layer (4 or 5 launches instead of 9)",
             "note": "by_batch / fused_by_batch rotate over the weight sets (weights from HBM); one_weight_set_* replay one "
                     "set, part of whose 116 MB is then served by the 256 MB last-level cache"}
 

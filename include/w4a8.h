@@ -362,10 +362,17 @@ int w4a8_silu_mul(const void* gu_dev, int64_t M, int64_t F, int64_t ldgu, void* 
  *                             of the channels it finishes; pack that matrix with w4a8_pack_weights (TILED).
  *                             F % 16 == 0.  The gate and up values are rounded to bf16 before SiLU*mul, as the
  *                             unfused sequence does.
+ *   w4a8_linear_quantize_in_fp8_out = w4a8_quantize_act of x followed by w4a8_linear_fp8_out, in one kernel: the form of
+ *                             w4a8_linear_quantize_in (same limits: M <= 16, M * K <= 65536; same x, x8_out arguments)
+ *                             whose output is quantized for the next layer like that of w4a8_linear_fp8_out.
  */
 int w4a8_linear_fp8_out(const uint8_t* x8_dev, int64_t M, int64_t K, int64_t ldx8, const float* x_scale_dev,
                         const uint8_t* packed_dev, const float* w_scales_dev, int64_t N, int32_t group_size,
                         const float* y_scale_dev, uint8_t* y8_dev, int64_t ldy8, void* stream);
+int w4a8_linear_quantize_in_fp8_out(const void* x_dev, w4a8_dtype x_dtype, int64_t M, int64_t K, int64_t ldx,
+                                    const float* x_scale_dev, const uint8_t* packed_dev, const float* w_scales_dev,
+                                    int64_t N, int32_t group_size, const float* y_scale_dev, uint8_t* y8_dev, int64_t ldy8,
+                                    uint8_t* x8_out_dev, void* stream);
 int w4a8_silu_mul_quantize(const void* gu_dev, int64_t M, int64_t F, int64_t ldgu, const float* scale_dev,
                            uint8_t* h8_dev, int64_t ldh8, void* stream);
 int w4a8_linear_silu_mul_fp8_out(const uint8_t* x8_dev, int64_t M, int64_t K, int64_t ldx8, const float* x_scale_dev,

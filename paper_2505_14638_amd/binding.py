@@ -63,6 +63,8 @@ SIGNATURES = {
                                         _c_vp, _c_vp, _c_vp, _c_vp, _c_sz, _c_vp]),
     "w4a8_linear_quantize_in": (_c_i32, [_c_vp, _c_i32, _c_i64, _c_i64, _c_i64, _c_vp, _c_vp, _c_vp, _c_i64, _c_i32, _c_vp,
                                          _c_i32, _c_i64, _c_vp, _c_vp]),
+    "w4a8_linear_quantize_in_fp8_out": (_c_i32, [_c_vp, _c_i32, _c_i64, _c_i64, _c_i64, _c_vp, _c_vp, _c_vp, _c_i64, _c_i32,
+                                                 _c_vp, _c_vp, _c_i64, _c_vp, _c_vp]),
     "w4a8_silu_mul": (_c_i32, [_c_vp, _c_i64, _c_i64, _c_i64, _c_vp, _c_i64, _c_vp]),
     "w4a8_linear_fp8_out": (_c_i32, [_c_vp, _c_i64, _c_i64, _c_i64, _c_vp, _c_vp, _c_vp, _c_i64, _c_i32, _c_vp, _c_vp,
                                      _c_i64, _c_vp]),
@@ -238,6 +240,23 @@ def linear_quantize_in(x, x_scale, packed, w_scales, n, group_size, out=None, ou
                                          out.data_ptr(), _dtype_code(out), out.stride(0) if m > 1 else max(n, out.stride(0)),
                                          x8_out.data_ptr() if x8_out is not None else None, _stream()),
            "w4a8_linear_quantize_in")
+    return out
+
+
+def linear_quantize_in_fp8_out(x, x_scale, packed, w_scales, n, group_size, y_scale, out=None, x8_out=None):
+    """w4a8_linear_quantize_in_fp8_out: x float32/bf16 [M, K] quantized inside the layer, output E4M3 bytes [M, N] for the next layer."""
+    m, k = x.shape
+    assert x.stride(1) == 1
+    if out is None:
+        out = torch.empty((m, n), dtype=torch.uint8, device=x.device)
+    assert out.dtype == torch.uint8 and out.stride(1) == 1
+    assert x8_out is None or (x8_out.dtype == torch.uint8 and x8_out.is_contiguous() and tuple(x8_out.shape) == (m, k))
+    _check(lib().w4a8_linear_quantize_in_fp8_out(x.data_ptr(), _dtype_code(x), m, k, x.stride(0) if m > 1 else max(k, x.stride(0)),
+                                                 x_scale.data_ptr(), packed.data_ptr(), w_scales.data_ptr(), n, group_size,
+                                                 y_scale.data_ptr(), out.data_ptr(),
+                                                 out.stride(0) if m > 1 else max(n, out.stride(0)),
+                                                 x8_out.data_ptr() if x8_out is not None else None, _stream()),
+           "w4a8_linear_quantize_in_fp8_out")
     return out
 
 

@@ -8,9 +8,9 @@ per-tensor scale (Eq. 13; all linear layers of a block are quantized, Sec. 4.1).
 
 `fused=True` runs the same computation with the quantization of each intermediate folded into the kernel that produces
 it (w4a8_linear_fp8_out for QKV and O, w4a8_linear_silu_mul_fp8_out for gate|up with SiLU*mul, on a row-interleaved
-copy of the gate|up weights, from 8 tokens on; below that w4a8_silu_mul_quantize after the plain layer): five or six
-launches instead of nine, the same bytes at every layer input and the same block
-output.
+copy of the gate|up weights) and, up to eight tokens, the quantization of the block input folded into the QKV layer
+(w4a8_linear_quantize_in_fp8_out): four or five launches instead of nine, the same bytes at every layer input and the
+same block output.
 """
 from __future__ import annotations
 
@@ -29,6 +29,7 @@ class DecoderBlockLinears:
         self.weights = {}
         self.scales_x = {}
         self._buffers = {}
+        self.quantize_in_up_to = 8                               # tokens up to which the QKV layer quantizes its own input
         self._workspace = None                                   # scratch of w4a8_linear (K ranges across workgroups), grown on demand
 
     def load_layer(self, name: str, w_f32: torch.Tensor) -> None:
@@ -71,18 +72,18 @@ class DecoderBlockLinears:
 
     def _forward_fused(self, x: torch.Tensor, keep: dict | None) -> torch.Tensor:
         m, g, sx, w = x.shape[0], self.group_size, self.scales_x, self.weights
-        x8 = B.quantize_act(x, sx["qkv"], out=self._buf(("qkv", "x8", m), (m, self.hidden), torch.uint8))
-        qkv8 = B.linear_fp8_out(x8, sx["qkv"], *w["qkv"], self.dims["qkv"][1], g, sx["o"],
-                                out=self._buf(("qkv", "y8", m), (m, self.dims["qkv"][1]), torch.uint8))
+        x8 = self._buf(("qkv", "x8", m), (m, self.hidden), torch.uint8)
+        qkv8 = self._buf(("qkv", "y8", m), (m, self.dims["qkv"][1]), torch.uint8)
+        if m <= self.quantize_in_up_to:                          # every workgroup quantizes x itself: one launch fewer
+            B.linear_quantize_in_fp8_out(x, sx["qkv"], *w["qkv"], self.dims["qkv"][1], g, sx["o"], out=qkv8,
+                                         x8_out=x8 if keep is not None else None)
+        else:
+            B.quantize_act(x, sx["qkv"], out=x8)
+            B.linear_fp8_out(x8, sx["qkv"], *w["qkv"], self.dims["qkv"][1], g, sx["o"], out=qkv8)
         o8 = B.linear_fp8_out(qkv8[:, :self.hidden], sx["o"], *w["o"], self.hidden, g, sx["gate_up"],
                               out=self._buf(("o", "y8", m), (m, self.hidden), torch.uint8))
         h8 = self._buf(("h8", m), (m, self.ffn), torch.uint8)
-        if m >= 8:
-            B.linear_silu_mul_fp8_out(o8, sx["gate_up"], *w["gate_up_interleaved"], self.ffn, g, sx["down"], out=h8)
-        else:                                                    # a few tokens: one band per wavefront streams faster (measured)
-            gu = B.linear(o8, sx["gate_up"], *w["gate_up"], 2 * self.ffn, g, B.LAYOUT_TILED,
-                          out=self._buf(("gate_up", "y", m), (m, 2 * self.ffn), torch.bfloat16))
-            B.silu_mul_quantize(gu, sx["down"], out=h8)
+        B.linear_silu_mul_fp8_out(o8, sx["gate_up"], *w["gate_up_interleaved"], self.ffn, g, sx["down"], out=h8)
         y = B.linear(h8, sx["down"], *w["down"], self.hidden, g, B.LAYOUT_TILED,
                      out=self._buf(("down", "y", m), (m, self.hidden), torch.bfloat16), workspace=self._ws("down", m))
         if keep is not None:

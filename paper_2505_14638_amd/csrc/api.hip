@@ -349,6 +349,25 @@ int w4a8_linear_fp8_out(const uint8_t* x8_dev, int64_t M, int64_t K, int64_t ldx
                                     ldy8, 0, 0, 0, nullptr, 0, MODE_CODE_EXACT, y_scale_dev, st);
 }
 
+int w4a8_linear_quantize_in_fp8_out(const void* x_dev, w4a8_dtype x_dtype, int64_t M, int64_t K, int64_t ldx,
+                                    const float* x_scale_dev, const uint8_t* packed_dev, const float* w_scales_dev,
+                                    int64_t N, int32_t group_size, const float* y_scale_dev, uint8_t* y8_dev, int64_t ldy8,
+                                    uint8_t* x8_out_dev, void* stream) {
+    if (!valid_dtype(x_dtype)) return W4A8_ERR_DTYPE;
+    if (M < 0 || M > 16) return W4A8_ERR_SHAPE;
+    if (int e = check_weight_shape(N, K, group_size, W4A8_LAYOUT_TILED)) return e;
+    if (M * K > 65536 || ldx < K || ldy8 < N) return W4A8_ERR_SHAPE;
+    if (!x_dev || !x_scale_dev || !packed_dev || !w_scales_dev || !y_scale_dev || !y8_dev) return W4A8_ERR_NULL;
+    if (!aligned16(x_dev) || ldx % (x_dtype == W4A8_F32 ? 4 : 8) != 0 || !aligned16(packed_dev) || !aligned16(w_scales_dev) ||
+        !aligned16(x8_out_dev) || reinterpret_cast<uintptr_t>(x_scale_dev) % 4 || reinterpret_cast<uintptr_t>(y_scale_dev) % 4)
+        return W4A8_ERR_ALIGN;
+    if (M == 0) return W4A8_OK;
+    return launch_linear_skinny(static_cast<const uint8_t*>(x_dev), M, K, ldx, x_scale_dev, packed_dev, w_scales_dev, N,
+                                group_size, y8_dev, static_cast<w4a8_dtype>(YDT_E4M3), ldy8, 0, 0, 0, nullptr, 0,
+                                MODE_CODE_EXACT, y_scale_dev, static_cast<hipStream_t>(stream), x_dtype == W4A8_F32 ? 1 : 2,
+                                x8_out_dev);
+}
+
 int w4a8_linear_silu_mul_fp8_out(const uint8_t* x8_dev, int64_t M, int64_t K, int64_t ldx8, const float* x_scale_dev,
                                  const uint8_t* packed_dev, const float* w_scales_dev, int64_t F, int32_t group_size,
                                  const float* h_scale_dev, uint8_t* h8_dev, int64_t ldh8, void* stream) {

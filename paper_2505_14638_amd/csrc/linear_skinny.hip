@@ -301,8 +301,8 @@ int launch_one(const LinearArgs& a, int depth, int waves, hipStream_t st) {
                        a.M, a.ldx8, a.s_x, a.packed, a.scales, a.N, a.n_tiles, a.C, a.cpg, a.NG, static_cast<OutT*>(a.y), a.ldy, \
                        cpw, a.w_out, a.per_channel, a.y_scale, a.x8_out)
 #define W4A8_SKINNY(DEPTHV, MODEV) W4A8_SKINNY_X(DEPTHV, MODEV, 0, lds)
-    if (a.xq != 0) {                                             // activation quantization folded in: few tokens, plain outputs
-        if constexpr (MT == 1 && NT <= 2 && sizeof(OutT) > 1) {
+    if (a.xq != 0) {                                             // activation quantization folded in: few tokens; float32, bf16 or FP8 outputs
+        if constexpr (MT == 1 && NT <= 2 && !OutKind<OutT>::SILU) {
             if (a.mode != MODE_CODE_EXACT) return W4A8_ERR_SHAPE;
             const size_t xbytes = (size_t)a.M * a.C * 128;
             const size_t both = lds > xbytes ? lds : xbytes;

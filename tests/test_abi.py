@@ -260,6 +260,24 @@ def test_linear_quantize_in_validation(L):
     assert f(P, B.F32, 4, 256, 256, P, P, P, 64, 96, P, B.BF16, 64, 0, None) == 3
 
 
+def test_linear_quantize_in_fp8_out_validation(L):
+    f = L.w4a8_linear_quantize_in_fp8_out
+    # x, x_dtype, M, K, ldx, x_scale, packed, w_scales, N, G, y_scale, y8, ldy8, x8_out, stream
+    assert f(P, B.BF16, 0, 256, 256, P, P, P, 64, 128, P, P, 64, 0, None) == 0
+    assert f(P, B.BF16, 17, 256, 256, P, P, P, 64, 128, P, P, 64, 0, None) == 2                  # more than 16 tokens
+    assert f(P, B.BF16, 16, 8192, 8192, P, P, P, 64, 128, P, P, 64, 0, None) == 2                # M * K > 65536
+    assert f(P, B.BF16, 4, 256, 128, P, P, P, 64, 128, P, P, 64, 0, None) == 2                   # ldx < K
+    assert f(P, B.BF16, 4, 256, 256, P, P, P, 64, 128, P, P, 32, 0, None) == 2                   # ldy8 < N
+    assert f(P, B.BF16, 4, 256, 260, P, P, P, 64, 128, P, P, 64, 0, None) == 6
+    assert f(P, B.BF16, 4, 256, 256, P, P, P, 64, 128, P + 2, P, 64, 0, None) == 6               # y_scale not 4-byte aligned
+    assert f(P, B.BF16, 4, 256, 256, P, P, P, 64, 128, P, P, 64, P + 8, None) == 6
+    assert f(P, B.BF16, 4, 256, 256, P, P, P, 64, 128, 0, P, 64, 0, None) == 1                   # no output scale
+    assert f(P, B.BF16, 4, 256, 256, P, P, P, 64, 128, P, 0, 64, 0, None) == 1
+    assert f(P, 7, 4, 256, 256, P, P, P, 64, 128, P, P, 64, 0, None) == 4
+    assert f(P, B.BF16, 4, 200, 200, P, P, P, 64, 128, P, P, 64, 0, None) == 5
+    assert f(P, B.BF16, 4, 256, 256, P, P, P, 64, 96, P, P, 64, 0, None) == 3
+
+
 def test_calibration_validation(L):
     ha = L.w4a8_hessian_accumulate
     assert ha(P, B.F32, 0, 64, 64, P, None) == 0

@@ -410,3 +410,15 @@ def test_linear_quantize_in_equals_the_two_calls(gpu_lib, m, k, n, dtype):
         it = torch.int32 if out_dtype == torch.float32 else torch.int16
         assert torch.equal(one.view(it), two.view(it))
     assert np.array_equal(x8.cpu().numpy(), want8)
+    # the form whose output is quantized for the next layer: the bytes of w4a8_quantize_act + w4a8_linear_fp8_out, which
+    # in turn are the oracle's quantization (Eq. 13) of the bf16 output above
+    y_scale = np.float32(max(float(two.abs().max()), 1e-3) / 448.0)
+    ys_d = dev(np.array([y_scale], dtype=np.float32))
+    two8 = B.linear_fp8_out(x8, sx_d, packed, scales, n, 128, ys_d)
+    codes = torch.zeros((m, k), dtype=torch.uint8, device=DEV)
+    wide8 = torch.zeros((m, n + 32), dtype=torch.uint8, device=DEV)
+    one8 = B.linear_quantize_in_fp8_out(x_d, sx_d, packed, scales, n, 128, ys_d, out=wide8[:, :n], x8_out=codes)
+    torch.cuda.synchronize()
+    assert np.array_equal(codes.cpu().numpy(), want8)
+    assert torch.equal(one8, two8) and int(wide8[:, n:].max()) == 0
+    assert np.array_equal(two8.cpu().numpy(), o.quantize_act(bf16_bits(two), y_scale, x_is_bf16_bits=True))
