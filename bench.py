@@ -40,7 +40,7 @@ G = 128
 # (profiles/linear_skinny_decode_sweep_hbm_traffic.txt): FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, the factors that make the
 # same counters read 1 GiB + 1 GiB for a plain 1 GiB device-to-device copy.  Counters cannot be read from inside a
 # timed run, so the figure is carried here and reported only for the workload it was measured on.
-SKINNY_TRAFFIC_BYTES_PER_LAUNCH = {4: 29.573e6}          # by --copies
+SKINNY_TRAFFIC_BYTES_PER_LAUNCH = {4: 29.589e6}          # by --copies
 # same for the prefill sweep (profiles/linear_mfma_prefill_sweep_hbm_traffic.txt): mean over its 12 shapes, one launch each
 PREFILL_TRAFFIC_BYTES_PER_LAUNCH = 295.4e6
 
