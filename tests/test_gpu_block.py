@@ -102,7 +102,12 @@ def test_block_stack_fused_is_the_same_computation(block, m):
 
 
 @pytest.mark.parametrize("m,k,n", [(1, 1024, 96), (16, 512, 200), (40, 1024, 72), (100, 384, 300), (300, 1024, 520),
-                                   (257, 640, 130)])
+                                   (257, 640, 130),
+                                   # shapes on which the plain layer's launch differs from the common one (eight wavefronts
+                                   # with four chunks in flight on long rows; one more doubling of the bands per wavefront
+                                   # on grids between one and two workgroups per compute unit): the FP8-output form has to
+                                   # split K the same way
+                                   (2, 8192, 8192), (8, 8192, 8192), (16, 1024, 10240), (3, 1024, 6144)])
 def test_linear_fp8_out_equals_linear_then_quantize(gpu_lib, m, k, n):
     """Ragged shapes on both kernels: the FP8 output equals the oracle's Eq. 13 applied to the bf16 output of the
     unfused layer; rows with a stride (a column slice of a wider buffer) included."""

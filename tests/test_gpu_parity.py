@@ -379,7 +379,12 @@ def test_act_scale_calibration_bit_exact(gpu_lib, dtype):
 
 
 @pytest.mark.parametrize("m,k,n,dtype", [(1, 1024, 96, "f32"), (4, 512, 200, "bf16"), (16, 4096, 48, "f32"), (3, 14336, 40, "bf16"),
-                                         (1, 4096, 6144, "bf16"), (4, 14336, 4096, "f32"), (9, 256, 520, "f32")])
+                                         (1, 4096, 6144, "bf16"), (4, 14336, 4096, "f32"), (9, 256, 520, "f32"),
+                                         # launch shapes that differ from the common one: long rows on many bands (the plain
+                                         # layer keeps four chunks in flight, this form two), grids between one and two
+                                         # workgroups per compute unit (the plain layer takes four bands per wavefront,
+                                         # this form two): the split of K has to stay the same
+                                         (8, 8192, 8192, "bf16"), (2, 8192, 10240, "f32"), (16, 1024, 10240, "bf16")])
 def test_linear_quantize_in_equals_the_two_calls(gpu_lib, m, k, n, dtype):
     """w4a8_linear_quantize_in: the FP8 codes it produces are the oracle's (Eq. 13), and its output is, bit for bit, that
     of w4a8_quantize_act followed by w4a8_linear; activations with a row stride, float32 and bf16, both output types."""
