@@ -32,8 +32,19 @@ inline bool valid_dtype(int d) { return d == W4A8_F32 || d == W4A8_BF16; }
 inline bool valid_layout(int l) { return l == W4A8_LAYOUT_CANONICAL || l == W4A8_LAYOUT_TILED; }
 // Few tokens: the skinny kernel streams the weights once with K split across wavefronts.  From 33 tokens on the
 // MFMA-tiled kernels (activations staged once per workgroup, nibble expansion shared by several token blocks) are
-// faster, except for deep, narrow layers, where the skinny kernel's finer split of K still wins up to 64 tokens.
-inline bool takes_skinny_path(int64_t M, int64_t K, int64_t N) { return M <= 32 || (M <= 64 && K >= 8192 && N <= 8192); }
+// faster, except for narrow layers, where the skinny kernel's finer split of K still wins: up to 64 tokens on layers
+// of at most 4096 channels and on deep ones (K >= 8192) of at most 8192, up to 48 tokens on up to 6144 channels
+// (measured on the Llama-3 layer shapes with the weights coming from HBM).
+inline bool takes_skinny_path(int64_t M, int64_t K, int64_t N) {
+    return M <= 32 || (M <= 64 && (N <= 4096 || (K >= 8192 && N <= 8192))) || (M <= 48 && N <= 6144);
+}
+// ... unless the caller brings a workspace and the layer is deep enough for K ranges across workgroups, which beat the
+// skinny kernel from 41 tokens on (Llama-3-8B down projection at 48 / 64 tokens: 24 / 29 us against 22)
+inline bool prefers_split_k(int64_t M, int64_t K, int64_t N) {
+    int cfg, ksplit;
+    mfma2d_choose_ksplit(M, K, N, cfg, ksplit);
+    return ksplit > 1 && M > 40;
+}
 constexpr int64_t DIM_MAX = (int64_t)1 << 30;      // keeps every 32-bit tile / chunk index in range
 // One thread per packed byte, 64 per group scale, 64 per output of the canonical layout's layer: these launches stay
 // below 2^32 threads for N * K <= 2^32 weights, N * K / group_size <= 2^25 groups and M * N <= 2^25 canonical outputs.
@@ -129,7 +140,7 @@ int w4a8_pack_weights(const void* src_dev, w4a8_src src_kind, const float* src_s
 
 size_t w4a8_linear_workspace_bytes(int64_t M, int64_t K, int64_t N, int32_t group_size) {
     if (M < 1 || M > DIM_MAX || check_weight_shape(N, K, group_size, W4A8_LAYOUT_TILED) != W4A8_OK) return 0;
-    if (takes_skinny_path(M, K, N)) return 0;
+    if (takes_skinny_path(M, K, N) && !prefers_split_k(M, K, N)) return 0;
     int cfg, ksplit;
     mfma2d_choose_ksplit(M, K, N, cfg, ksplit);
     return mfma2d_splitk_bytes(M, N, ksplit);
@@ -155,7 +166,7 @@ int w4a8_linear(const uint8_t* x8_dev, int64_t M, int64_t K, int64_t ldx8, const
     if (layout == W4A8_LAYOUT_CANONICAL)
         return launch_linear_canonical(x8_dev, M, K, ldx8, x_scale_dev, packed_dev, w_scales_dev, N, group_size, y_dev,
                                        y_dtype, ldy, st);
-    if (takes_skinny_path(M, K, N))
+    if (takes_skinny_path(M, K, N) && ksplit <= 1)
         return launch_linear_skinny(x8_dev, M, K, ldx8, x_scale_dev, packed_dev, w_scales_dev, N, group_size, y_dev,
                                     y_dtype, ldy, 0, 0, 0, nullptr, 0, MODE_CODE_EXACT, nullptr, st);
     if (ksplit > 1)                                              // few tiles, deep K: K ranges across workgroups
@@ -254,7 +265,7 @@ int w4a8_linear_launch_shape(int64_t M, int64_t K, int64_t N, int32_t group_size
     if (M < 1 || M > DIM_MAX) return W4A8_ERR_SHAPE;
     if (int e = check_weight_shape(N, K, group_size, W4A8_LAYOUT_TILED)) return e;
     shape4[0] = shape4[1] = shape4[2] = shape4[3] = 0;
-    if (takes_skinny_path(M, K, N)) {
+    if (takes_skinny_path(M, K, N) && !(with_workspace && prefers_split_k(M, K, N))) {
         int nt = 0, waves = 0, depth = 0;
         if (!skinny_launch_shape(M, K, N, W4A8_BF16, MODE_CODE_EXACT, 0, nt, waves, depth)) return W4A8_ERR_SHAPE;
         shape4[1] = nt;

@@ -121,6 +121,11 @@ def test_linear_validation(L):
     assert need > 0 and need % (128 * 4096 * 4) == 0 and need <= 32 << 20     # whole float32 [M, N] planes, one per K range
     assert wb(128, 4096, 4096, 128) == 0 and wb(1024, 14336, 4096, 128) == 0   # shallow K, many tokens: not split
     assert wb(128, 14336, 4096, 96) == 0 and wb(0, 14336, 4096, 128) == 0
+    # 41..64 tokens on a deep narrow layer: the few-token kernel without a workspace, K ranges across workgroups with one
+    assert wb(40, 14336, 4096, 128) == 0 and wb(48, 14336, 4096, 128) > 0 and wb(64, 4096, 4096, 128) == 0
+    assert B.linear_launch_shape(48, 14336, 4096, 128)[0] == 0 and B.linear_launch_shape(48, 14336, 4096, 128, True)[0] == 3
+    assert B.linear_launch_shape(64, 4096, 4096, 128)[0] == 0 and B.linear_launch_shape(64, 4096, 6144, 128)[0] == 1
+    assert B.linear_launch_shape(48, 4096, 6144, 128)[0] == 0 and B.linear_launch_shape(33, 4096, 28672, 128)[0] == 1
     big = dict(M=128, K=14336, ldx8=14336, N=4096, ldy=4096)
 
     def call_ws(ws, nbytes, **kw):

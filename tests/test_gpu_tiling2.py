@@ -141,9 +141,10 @@ def test_split_k_exact_integer_case_bit_for_bit(gpu_lib, tile, ksplit):
     assert np.array_equal(y32, want)
 
 
-@pytest.mark.parametrize("m", [96, 128, 400])
+@pytest.mark.parametrize("m", [48, 96, 128, 400])
 def test_linear_with_workspace_on_the_down_projection(gpu_lib, m):
-    """The Llama-3-8B down projection (K = 14336, N = 4096) at batch sizes where w4a8_linear asks for a workspace: sampled
+    """The Llama-3-8B down projection (K = 14336, N = 4096) at batch sizes where w4a8_linear asks for a workspace (from 41
+    tokens on; at 48 the layer without a workspace runs on the few-token kernel): sampled
     token rows x all channels against the oracle, bf16 == RNE(float32), and the same bits on a second call (the order
     of the ranges in the sum is fixed)."""
     k, n = syn.LLAMA3_8B["down"]
