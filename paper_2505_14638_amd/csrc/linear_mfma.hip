@@ -458,11 +458,16 @@ void launch_one(const LinearArgs& a, dim3 grid, int grid_m, int grid_n, hipStrea
 
 // Launch shape of the many-token kernels for a layer; requested values of mf / ks / tpw other than 0 are kept.
 // cfg2d >= 0 on return: the layer goes to the second tiling (linear_mfma2d.hip) with that workgroup tile.
-//  - Large grids in the code-exact and power-of-two modes go to the second tiling (a 2-D grid of wavefronts over
-//    256-token tiles, expansion shared through LDS, persistent workgroups): 256 x 256 tiles when they fill the 256
-//    compute units, 256 x 128 tiles in two workgroups per compute unit when those do, as long as padding the tokens to a
-//    multiple of 256 wastes less than a quarter.  Measured on the Llama-3 shapes: +5...12 % at 8192 tokens, +3...15 %
-//    at 2048; smaller grids stay with the first tiling.
+//  - In the code-exact and power-of-two modes the second tiling (a 2-D grid of wavefronts over 256-token tiles,
+//    expansion shared through LDS, persistent workgroups) competes with the first on estimated time.  A persistent
+//    workgroup needs a fixed time per tile, so what a grid costs is rounds x time per tile, and the last, partly filled
+//    round costs as much as a full one: 256 x 256 tiles (one workgroup per compute unit, 256 at a time), 256 x 128 tiles
+//    with eight wavefronts (256 at a time) or with four (two workgroups per compute unit, 512 at a time; a tile takes
+//    longer while two share the unit).  Times per tile in microseconds, C = K / 128 chunks, from medians on the
+//    Llama-3 layer shapes with the weights coming from HBM: 6 + 1.66 C, 5 + 1.08 C, 5 + 1.28 C alone and 5 + 1.875 C
+//    shared.  The first tiling is priced at 0.265 C + flops / 1.35 PFLOP/s.  Against the rule this replaces (256 x 256 or
+//    four-wavefront 256 x 128 tiles once they number 200): 640 tokens on gate|up 125 -> 104 us, 3072 / 4096 tokens on
+//    QKV 113 / 120 -> 101 / 108, 2048 tokens on the O projection 47 -> 42, 192...256 tokens on gate|up 48 -> 42.
 //  - First tiling: tall token blocks amortize the nibble expansion over more MFMAs; two bands per wavefront halve the
 //    LDS reads per MFMA (the activation operand is reused); K-splits shorten the dependent chain of passes (each waits
 //    for the copies of the next) when the grid is too small to fill the chip, at the price of a wider activation block
@@ -473,9 +478,17 @@ bool mfma_launch_shape(int64_t M, int64_t K, int64_t N, int mode, int& mf, int& 
     const int C = (int)(K / 128);
     const int n_tiles = (int)((N + 15) / 16);
     if (mf == 0 && ks == 0 && tpw == 0 && (mode == MODE_CODE_EXACT || mode == MODE_POW2)) {
-        const int64_t tm = (M + 255) / 256, t1 = tm * ((N + 255) / 256), t4 = tm * ((N + 127) / 128);
-        if (4 * M >= 3 * 256 * tm && (t1 >= 200 || t4 >= 200)) {
-            cfg2d = t1 >= 200 ? 1 : 4;
+        const int64_t tm = (M + 255) / 256, t1 = tm * ((N + 255) / 256), t2 = tm * ((N + 127) / 128);
+        const double c = (double)C;
+        const double e1 = (double)((t1 + 255) / 256) * (6.0 + 1.66 * c);
+        const double e2 = (double)((t2 + 255) / 256) * (5.0 + 1.08 * c);
+        const int64_t rem = t2 % 512;
+        const double e4 = (double)(t2 / 512) * (5.0 + 1.875 * c) +
+                          (rem == 0 ? 0.0 : rem <= 256 ? 5.0 + 1.28 * c : 5.0 + 1.875 * c);
+        const double first = 0.265 * c + 2.0 * (double)M * (double)K * (double)N / 1.35e9;
+        const double best = e1 < e2 ? (e1 < e4 ? e1 : e4) : (e2 < e4 ? e2 : e4);
+        if (best < first) {
+            cfg2d = best == e1 ? 1 : best == e2 ? 2 : 4;
             return true;
         }
     }

@@ -145,7 +145,7 @@ def test_linear_validation(L):
     assert fn(P, 512, 28672, 28672, P, P, P, 8192, 128, P, B.BF16, 8192, None) == 7
     # the launch shape the library chooses, as w4a8_linear_variant takes it
     assert B.linear_launch_shape(1, 4096, 4096, 128) == (0, 1, 16 | (2 << 8), 0)
-    assert B.linear_launch_shape(8192, 4096, 4096, 128) == (2, 1, 0, 0) and B.linear_launch_shape(2048, 4096, 4096, 128) == (2, 4, 0, 0)
+    assert B.linear_launch_shape(8192, 4096, 4096, 128) == (2, 1, 0, 0) and B.linear_launch_shape(2048, 4096, 4096, 128) == (2, 2, 0, 0) and B.linear_launch_shape(3072, 4096, 6144, 128) == (2, 4, 0, 0)
     assert B.linear_launch_shape(512, 4096, 4096, 128)[0] == 1
     assert B.linear_launch_shape(128, 14336, 4096, 128, True) == (3, 5, 0, 8) and B.linear_launch_shape(128, 14336, 4096, 128)[0] == 1
     assert L.w4a8_linear_launch_shape(128, 14336, 4096, 128, 0, None) == 1 and L.w4a8_linear_launch_shape(0, 14336, 4096, 128, 0, P) == 2
