@@ -42,6 +42,16 @@ int w4a8_linear_variant(const uint8_t* x8_dev, int64_t M, int64_t K, int64_t ldx
 int w4a8_linear_launch_shape(int64_t M, int64_t K, int64_t N, int32_t group_size, int32_t with_workspace, int32_t* shape4);
 
 /*
+ * The launch shape of the few-token kernel (path 0 above) for one of the forms that run on it, M <= 64:
+ *   form 0 = w4a8_linear (bf16 / float32 output), 1 = w4a8_linear_fp8_out, 2 = w4a8_linear_silu_mul_fp8_out (N = 2F, the
+ *   interleaved gate|up matrix), 3 = w4a8_linear_quantize_in, 4 = w4a8_linear_quantize_in_fp8_out.
+ * shape3[0] = weight bands per wavefront, shape3[1] = wavefronts per workgroup (the split of K), shape3[2] = chunks in
+ * flight per wavefront.  shape3 is HOST memory, three int32.  Nothing is launched.  The fused forms give the bytes of
+ * the sequences they replace because shape3[1] is the same for every form of a given (M, K, N); tests hold it to that.
+ */
+int w4a8_linear_few_token_shape(int64_t M, int64_t K, int64_t N, int32_t group_size, int32_t form, int32_t* shape3);
+
+/*
  * The second tiling with K multiplied in `ksplit` ranges by different workgroups (what w4a8_linear does with a
  * workspace on the shapes w4a8_linear_workspace_bytes() names), tile and split chosen by the caller.  workspace_dev:
  * 16-byte aligned, at least ksplit * M * round_up(N, 64) * 4 bytes (W4A8_ERR_WORKSPACE otherwise).  tile as param0 of

@@ -36,6 +36,7 @@ SIGNATURES = {
     "w4a8_linear_variant": (_c_i32, [_c_vp, _c_i64, _c_i64, _c_i64, _c_vp, _c_vp, _c_vp, _c_i64, _c_i32, _c_vp,
                                      _c_i32, _c_i64, _c_i32, _c_i32, _c_i32, _c_vp]),
     "w4a8_linear_launch_shape": (_c_i32, [_c_i64, _c_i64, _c_i64, _c_i32, _c_i32, _c_vp]),
+    "w4a8_linear_few_token_shape": (_c_i32, [_c_i64, _c_i64, _c_i64, _c_i32, _c_i32, _c_vp]),
     "w4a8_linear_splitk_variant": (_c_i32, [_c_vp, _c_i64, _c_i64, _c_i64, _c_vp, _c_vp, _c_vp, _c_i64, _c_i32, _c_vp,
                                             _c_i32, _c_i64, _c_i32, _c_i32, _c_vp, _c_sz, _c_vp]),
     "w4a8_dequant_weights": (_c_i32, [_c_vp, _c_i64, _c_i64, _c_i32, _c_vp, _c_vp]),
@@ -215,6 +216,17 @@ def linear_launch_shape(m: int, k: int, n: int, group_size: int, with_workspace:
     out = (ctypes.c_int32 * 4)()
     _check(lib().w4a8_linear_launch_shape(m, k, n, group_size, 1 if with_workspace else 0, ctypes.addressof(out)),
            "w4a8_linear_launch_shape")
+    return tuple(int(v) for v in out)
+
+
+FEW_TOKEN_FORMS = {"linear": 0, "fp8_out": 1, "silu_mul_fp8_out": 2, "quantize_in": 3, "quantize_in_fp8_out": 4}
+
+
+def linear_few_token_shape(m: int, k: int, n: int, group_size: int, form: str = "linear"):
+    """(bands per wavefront, wavefronts per workgroup = split of K, chunks in flight) of the few-token kernel for a form."""
+    out = (ctypes.c_int32 * 3)()
+    _check(lib().w4a8_linear_few_token_shape(m, k, n, group_size, FEW_TOKEN_FORMS[form], ctypes.addressof(out)),
+           "w4a8_linear_few_token_shape")
     return tuple(int(v) for v in out)
 
 

@@ -293,6 +293,21 @@ int w4a8_linear_launch_shape(int64_t M, int64_t K, int64_t N, int32_t group_size
     return W4A8_OK;
 }
 
+int w4a8_linear_few_token_shape(int64_t M, int64_t K, int64_t N, int32_t group_size, int32_t form, int32_t* shape3) {
+    if (!shape3) return W4A8_ERR_NULL;
+    if (M < 1 || M > 64 || form < 0 || form > 4) return W4A8_ERR_SHAPE;
+    if (int e = check_weight_shape(N, K, group_size, W4A8_LAYOUT_TILED)) return e;
+    if (form >= 3 && (M > 16 || M * K > 65536)) return W4A8_ERR_SHAPE;
+    if (form == 2 && N % 32 != 0) return W4A8_ERR_SHAPE;
+    const int ydt = form == 1 || form == 4 ? YDT_E4M3 : form == 2 ? YDT_SILU_E4M3 : (int)W4A8_BF16;
+    int nt = 0, waves = 0, depth = 0;
+    if (!skinny_launch_shape(M, K, N, ydt, MODE_CODE_EXACT, form >= 3 ? 2 : 0, nt, waves, depth)) return W4A8_ERR_SHAPE;
+    shape3[0] = nt;
+    shape3[1] = waves;
+    shape3[2] = depth;
+    return W4A8_OK;
+}
+
 int w4a8_linear_splitk_variant(const uint8_t* x8_dev, int64_t M, int64_t K, int64_t ldx8, const float* x_scale_dev,
                                const uint8_t* packed_dev, const float* w_scales_dev, int64_t N, int32_t group_size,
                                void* y_dev, w4a8_dtype y_dtype, int64_t ldy, int32_t tile, int32_t ksplit,

@@ -398,11 +398,15 @@ bool skinny_launch_shape(int64_t M, int64_t K, int64_t N, int ydt, int mode, int
         while (waves < 16 && (int64_t)n_tiles * C * 1024 > (int64_t)grid * waves * 65536) waves *= 2;   // odd counts split K unevenly and measured slower
     }
     if (waves > C) waves = C;
+    const bool asym = mode == MODE_ASYM || mode == MODE_ASYM_TWO;
+    // LDS and registers of the plain layer bound its wavefronts; every other form takes that count, or fewer where its
+    // own kernel holds fewer
+    const int plain_cap = max_threads(mt * nt, asym);
+    while (waves > 1 && (waves * mt * nt > 64 || waves * 64 > plain_cap)) --waves;
     // The fused gate|up layer needs gate and up tiles in one workgroup.
     if (ydt == YDT_SILU_E4M3 && nt == 1) nt = 2;
-    const int thread_cap = max_threads(mt * nt, mode == MODE_ASYM || mode == MODE_ASYM_TWO,
-                                       ydt == YDT_SILU_E4M3 && mt == 2 && nt == 2);
-    while (waves > 1 && (waves * mt * nt > 64 || waves * 64 > thread_cap)) --waves;   // LDS and registers
+    const int thread_cap = max_threads(mt * nt, asym, ydt == YDT_SILU_E4M3 && mt == 2 && nt == 2);
+    while (waves > 1 && (waves * mt * nt > 64 || waves * 64 > thread_cap)) --waves;
     if (waves < 1 || waves > 16 || waves * mt * nt > 64 || waves * 64 > thread_cap) return false;
     // the form that quantizes its own input is built for one or two bands: fewer bands, the same split of K
     if (xq != 0 && nt > 2) {

@@ -265,6 +265,35 @@ def test_linear_quantize_in_validation(L):
     assert f(P, B.F32, 4, 256, 256, P, P, P, 64, 96, P, B.BF16, 64, 0, None) == 3
 
 
+def test_few_token_forms_split_k_alike(L):
+    """The fused forms of the few-token kernel are byte-identical to the sequences they replace only if they add up the
+    same partial sums in the same order, i.e. split K over the same number of wavefronts as the plain layer on the same
+    (M, K, N).  Checked on the host over a grid of sizes (the launch-shape function launches nothing)."""
+    assert L.w4a8_linear_few_token_shape(1, 4096, 4096, 128, 0, None) == 1
+    assert L.w4a8_linear_few_token_shape(65, 4096, 4096, 128, 0, P) == 2 and L.w4a8_linear_few_token_shape(1, 4096, 4096, 128, 5, P) == 2
+    assert L.w4a8_linear_few_token_shape(17, 1024, 4096, 128, 3, P) == 2 and L.w4a8_linear_few_token_shape(1, 4096, 4080, 128, 2, P) == 2
+    assert B.linear_few_token_shape(1, 8192, 8192, 128) == (1, 8, 4) and B.linear_few_token_shape(1, 8192, 8192, 128, "fp8_out") == (1, 8, 2)
+    assert B.linear_few_token_shape(16, 8192, 10240, 128) == (4, 8, 2) and B.linear_few_token_shape(1, 4096, 6144, 128) == (2, 16, 2)
+    checked = 0
+    for k in (128, 512, 1024, 4096, 8192, 14336, 28672):
+        for n in (32, 96, 2048, 4096, 6144, 8192, 10240, 16384, 28672, 57344, 128256):
+            if (n + 15) // 16 * 16 * k > 1 << 32:
+                continue
+            for m in (1, 2, 4, 7, 8, 9, 15, 16, 17, 24, 32, 33, 48, 64):
+                nt, waves, depth = B.linear_few_token_shape(m, k, n, 128)
+                assert nt in (1, 2, 4) and 1 <= waves <= 16 and depth in (2, 4)
+                assert B.linear_few_token_shape(m, k, n, 128, "fp8_out")[1] == waves
+                if n % 32 == 0:
+                    nt_s, waves_s, _ = B.linear_few_token_shape(m, k, n, 128, "silu_mul_fp8_out")
+                    assert waves_s == waves and nt_s % 2 == 0
+                if m <= 16 and m * k <= 65536:
+                    for form in ("quantize_in", "quantize_in_fp8_out"):
+                        nt_q, waves_q, depth_q = B.linear_few_token_shape(m, k, n, 128, form)
+                        assert waves_q == waves and nt_q <= 2 and depth_q == 2
+                checked += 1
+    assert checked > 900
+
+
 def test_linear_quantize_in_fp8_out_validation(L):
     f = L.w4a8_linear_quantize_in_fp8_out
     # x, x_dtype, M, K, ldx, x_scale, packed, w_scales, N, G, y_scale, y8, ldy8, x8_out, stream

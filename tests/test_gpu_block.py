@@ -146,7 +146,12 @@ def test_silu_mul_quantize_equals_silu_mul_then_quantize(gpu_lib, m, f):
 @pytest.mark.parametrize("m,k,f", [(1, 1024, 48), (16, 512, 208), (40, 1024, 64), (100, 384, 304), (300, 1024, 528),
                                    (257, 640, 144), (24, 256, 8208),
                                    # 17..32 tokens on a narrow layer: the plain layer splits K over 16 wavefronts, and so does the fused one
-                                   (24, 2048, 1024), (32, 4096, 512), (20, 2048, 1696)])
+                                   (24, 2048, 1024), (32, 4096, 512), (20, 2048, 1696),
+                                   # ... and on one with 384..1023 bands, where the plain layer takes two bands per wavefront
+                                   # and is held to 8 wavefronts by its registers: so is the fused one
+                                   (24, 4096, 3072), (17, 2048, 4096),
+                                   # one token and a handful: the fused form is what the decoder block runs from one token on
+                                   (2, 4096, 14336), (8, 4096, 2048)])
 def test_fused_gate_up_equals_the_unfused_sequence(gpu_lib, m, k, f):
     """w4a8_linear_silu_mul_fp8_out on the row-interleaved gate|up matrix against linear (bf16) -> SiLU*mul -> Eq. 13 on
     the matrix in its natural order: the same bytes; ragged channel counts, both kernels, a strided output."""
