@@ -67,7 +67,10 @@ class DecoderBlockLinears:
         y = self._buf((name, "y", m), (m, n), torch.bfloat16)
         B.quantize_act(x, self.scales_x[name], out=x8)
         packed, scales = self.weights[name]
-        B.linear(x8, self.scales_x[name], packed, scales, n, self.group_size, B.LAYOUT_TILED, out=y, workspace=self._ws(name, m))
+        # only the last layer takes the workspace: the fused forms of the others take none, and with one w4a8_linear may add
+        # the ranges of K in another order than they do
+        ws = self._ws(name, m) if name == "down" else None
+        B.linear(x8, self.scales_x[name], packed, scales, n, self.group_size, B.LAYOUT_TILED, out=y, workspace=ws)
         return y
 
     def _forward_fused(self, x: torch.Tensor, keep: dict | None) -> torch.Tensor:
