@@ -294,6 +294,37 @@ def test_few_token_forms_split_k_alike(L):
     assert checked > 900
 
 
+def test_launch_shape_is_built_and_consistent_for_every_size(L):
+    """w4a8_linear's own choice over a grid of sizes: always a built combination (never W4A8_ERR_SHAPE for valid sizes),
+    K ranges across workgroups exactly where w4a8_linear_workspace_bytes() asks for a workspace, and the same launch with
+    and without a workspace everywhere else."""
+    second_tiling_tiles = {0, 1, 2, 3, 4, 5}
+    first_tiling = {(16, 1, 1), (8, 1, 1), (8, 2, 1), (4, 1, 1), (4, 2, 1), (4, 4, 1), (16, 1, 2)}
+    n_checked = 0
+    for k in (128, 1024, 4096, 8192, 14336, 28672):
+        for n in (16, 100, 4096, 6144, 10240, 28672, 57344):
+            for m in (1, 16, 17, 32, 33, 40, 41, 48, 49, 64, 65, 100, 128, 192, 256, 300, 512, 640, 1000, 2048, 3072, 8192, 20000):
+                plain = B.linear_launch_shape(m, k, n, 128)
+                with_ws = B.linear_launch_shape(m, k, n, 128, True)
+                need = L.w4a8_linear_workspace_bytes(m, k, n, 128)
+                for path, p0, p1, ranges in (plain, with_ws):
+                    assert path in (0, 1, 2, 3)
+                    if path == 0:
+                        assert m <= 64 and p0 in (1, 2, 4) and 1 <= (p1 & 0xFF) <= 16 and (p1 >> 8) in (2, 4)
+                    elif path == 1:
+                        assert (p0, p1 & 0xFF, p1 >> 8) in first_tiling
+                    else:
+                        assert p0 in second_tiling_tiles
+                    assert (ranges >= 2) == (path == 3) and (path != 3 or ranges <= k // 128)
+                assert plain[0] != 3 and (with_ws[0] == 3) == (need > 0)
+                if need == 0:
+                    assert with_ws == plain
+                else:
+                    assert need == with_ws[3] * m * ((n + 63) // 64 * 64) * 4
+                n_checked += 1
+    assert n_checked == 6 * 7 * 23
+
+
 def test_linear_quantize_in_fp8_out_validation(L):
     f = L.w4a8_linear_quantize_in_fp8_out
     # x, x_dtype, M, K, ldx, x_scale, packed, w_scales, N, G, y_scale, y8, ldy8, x8_out, stream
