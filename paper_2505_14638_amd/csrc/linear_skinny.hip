@@ -384,13 +384,16 @@ bool skinny_launch_shape(int64_t M, int64_t K, int64_t N, int ydt, int mode, int
         nt = wide_many ? 4 : ((M > 8 && n_tiles >= 384) || (int64_t)n_tiles * C >= 100000) ? 2 : 1;
         const int grid = (n_tiles + nt - 1) / nt;
         if (mt == 1 && grid > 256 && grid < 512 && nt < 4) nt *= 2;
-        long_rows = waves == 0 && nt == 1 && M <= 8 && C >= 64 && n_tiles >= 512;
+        long_rows = waves == 0 && nt == 1 && M <= 8 && C >= 64 && n_tiles >= 512 && mode == MODE_CODE_EXACT;
     }
     if (nt != 1 && nt != 2 && nt != 4) return false;
     if (long_rows) waves = 8;
     if (waves == 0) {
         const int grid = (n_tiles + nt - 1) / nt;
-        const int target = (wide_many && nt == 4) ? (M > 32 ? 896 : 2048) : M > 8 ? 2400 : 16384;
+        // (the two-level and power-of-two formats measured faster with half as many at few tokens: gate|up of
+        // Llama-3-8B at one token 4.4 against 4.0 TB/s and 4.7 against 4.4)
+        const bool many = mode == MODE_CODE_EXACT || mode == MODE_ASYM;
+        const int target = (wide_many && nt == 4) ? (M > 32 ? 896 : 2048) : M > 8 ? 2400 : many ? 16384 : 8192;
         const float want = (float)target / (float)grid;
         waves = 2;                                               // the power of two nearest to `want` (ratio-wise), 2..16:
         while (waves < 16 && (float)(waves * waves * 2) < want * want) waves *= 2;
