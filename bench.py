@@ -368,10 +368,11 @@ def decode_cases(dev):
             "byte_weighted_frac_of_peak": round(tot_b / tot_t / 1e9 / HBM_PEAK_GBS, 4), "repeats": REPEATS}
 
 
-def block_latency(dev, steps, warmup, sets=3):
+def block_latency(dev, steps, warmup, sets=4, stack=12):
     """Config 5: latency of the decoder-block linear stack per batch size, HIP graph replay over `sets` rotating weight
-    sets (3 x 116 MB: beyond the 256 MB last-level cache, so the weights come from HBM); the figure with one weight set
-    (partly served by that cache) is kept next to it, labelled."""
+    sets (4 x 116 MB: beyond the 256 MB last-level cache, so the weights come from HBM); the figure with one weight set
+    (partly served by that cache) is kept next to it, labelled.  `stack` consecutive blocks in ONE graph (as the blocks
+    of a model are replayed) give the per-block figure without a graph replay's own start-up."""
     from paper_2505_14638_amd.block import LAYERS, DecoderBlockLinears
     cfg = syn.CONFIGS[5]
     blocks, fused_blocks = [], []
@@ -386,7 +387,8 @@ def block_latency(dev, steps, warmup, sets=3):
         fused.weights, fused.scales_x = blk.weights, blk.scales_x
         blocks.append(blk)
         fused_blocks.append(fused)
-    out = {"by_batch": {}, "fused_by_batch": {}, "fused_spread": {}, "one_weight_set_by_batch": {}, "one_weight_set_fused_by_batch": {}}
+    out = {"by_batch": {}, "fused_by_batch": {}, "fused_spread": {}, "fused_in_a_stack_by_batch": {},
+           "one_weight_set_by_batch": {}, "one_weight_set_fused_by_batch": {}}
     for m in cfg["batches"]:
         x = syn.make_activations(syn.rng_for(5, 200 + m), m, cfg["hidden"], cfg["frac"], cfg["mult"])
         x_d = torch.from_numpy(x).to(dev).to(torch.bfloat16)
@@ -406,13 +408,19 @@ def block_latency(dev, steps, warmup, sets=3):
                     out["fused_spread"][str(m)] = [round(lo / steps * 1e6, 2), round(hi / steps * 1e6, 2)]
                 out[key1][str(m)] = round(time_graphs(graphs[:1], steps, warmup) / steps * 1e6, 2)
                 del graphs
+            g = capture(lambda: [fused_blocks[i % sets].forward(x_d) for i in range(stack)])
+            reps = max(3, steps // stack)
+            out["fused_in_a_stack_by_batch"][str(m)] = round(time_graphs_spread([g], reps, 2)[0] / (reps * stack) * 1e6, 2)
+            del g
         torch.cuda.current_stream().wait_stream(side)
     return {"metric": "decoder-block linear stack latency (config 5: QKV, O, gate|up, SiLU*mul, down; hidden 4096, "
                       "FFN 14336)", "unit": "us per block", "weight_sets": sets, "repeats": REPEATS, **out,
             "fused": "same outputs with each intermediate's FP8 quantization folded into the kernel that produces it "
                      "and, up to 8 tokens, the quantization of the block input into the QKV layer (4 or 5 launches instead of 9)",
-            "note": "by_batch / fused_by_batch rotate over the weight sets (weights from HBM); one_weight_set_* replay one "
-                    "set, part of whose 116 MB is then served by the 256 MB last-level cache"}
+            "note": "by_batch / fused_by_batch: one block per graph replay, rotating over the weight sets (weights from "
+                    "HBM); fused_in_a_stack_by_batch: %d consecutive fused blocks in one graph over the same rotating weight "
+                    "sets, per block (no graph start-up per block); one_weight_set_*: one set replayed, part of whose "
+                    "116 MB is then served by the 256 MB last-level cache" % stack}
 
 
 def weight_modes(dev):
