@@ -109,15 +109,41 @@ class Eager:
         self.replay = fn
 
 
+class Steps:
+    """The steps fn(0) .. fn(copies - 1) (one per weight set) as `copies` single-step graphs plus ONE graph that holds them
+    all in a row: a graph replay's own start-up (3-5 us here) is then paid once per `copies` steps.  run(n) replays
+    exactly n steps."""
+
+    def __init__(self, fn, copies, eager=False):
+        self.copies = copies
+        if eager:
+            self.singles = [Eager(lambda i=i: fn(i)) for i in range(copies)]
+            self.all = Eager(lambda: [fn(i) for i in range(copies)])
+        else:
+            self.singles = [capture(lambda i=i: fn(i)) for i in range(copies)]
+            self.all = capture(lambda: [fn(i) for i in range(copies)])
+
+    def run(self, n):
+        for _ in range(n // self.copies):
+            self.all.replay()
+        for i in range(n % self.copies):
+            self.singles[i].replay()
+
+
 def time_graphs_once(graphs, reps, warmup):
-    """Replay graphs round-robin `reps` times after `warmup`; returns seconds for the timed replays."""
-    for i in range(warmup):
-        graphs[i % len(graphs)].replay()
+    """Replay graphs round-robin `reps` times after `warmup` (a Steps object: exactly that many steps); returns seconds
+    for the timed replays."""
+    if isinstance(graphs, Steps):
+        replay = graphs.run
+    else:
+        def replay(n):
+            for i in range(n):
+                graphs[i % len(graphs)].replay()
+    replay(warmup)
     torch.cuda.synchronize()
     t0, t1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     t0.record()
-    for i in range(reps):
-        graphs[i % len(graphs)].replay()
+    replay(reps)
     t1.record()
     torch.cuda.synchronize()
     return t0.elapsed_time(t1) * 1e-3
@@ -265,7 +291,7 @@ def plain_read_same_sizes(dev, sizes, copies, steps, warmup):
     with torch.cuda.stream(side):
         reads(0)
         torch.cuda.synchronize()
-        graphs = [capture(lambda i=i: reads(i)) for i in range(copies)]
+        graphs = Steps(reads, copies)
         sec = time_graphs(graphs, steps, warmup)
     torch.cuda.current_stream().wait_stream(side)
     del graphs, pool
@@ -635,22 +661,20 @@ def main():
         with torch.cuda.stream(side):
             step(0)                                                     # eager run before capture
             torch.cuda.synchronize()
-            if args.eager:
-                step_graphs = [Eager(lambda i=i: step(i)) for i in range(args.copies)]
-                lin_graphs = [Eager(lambda i=i: linears_only(i)) for i in range(args.copies)]
-            else:
-                step_graphs = [capture(lambda i=i: step(i)) for i in range(args.copies)]
-                lin_graphs = [capture(lambda i=i: linears_only(i)) for i in range(args.copies)]
+            step_graphs = Steps(step, args.copies, args.eager)
+            lin_graphs = Steps(linears_only, args.copies, args.eager)
             repeats = 1 if args.eager else REPEATS                      # counter runs: one pass
             sec, sec_lo, sec_hi = time_graphs_spread(step_graphs, args.steps, args.warmup, repeats)
             lin_sec, lin_lo, lin_hi = time_graphs_spread(lin_graphs, args.steps, args.warmup, repeats)
             # the same launches over ONE weight set (109 MB: partly served by the 256 MB last-level cache), labelled as such
-            one_set_sec = time_graphs_spread(lin_graphs[:1], args.steps, args.warmup, repeats)[0]
+            one_set_graphs = Steps(lambda i: [c.linear(0) for c in cases], args.copies, args.eager)
+            one_set_sec = time_graphs_spread(one_set_graphs, args.steps, args.warmup, repeats)[0]
+            del one_set_graphs
             fused_sec = None
             if not args.eager:
                 step_fused(0)
                 torch.cuda.synchronize()
-                fused_graphs = [capture(lambda i=i: step_fused(i)) for i in range(args.copies)]
+                fused_graphs = Steps(step_fused, args.copies)
                 fused_sec, f_lo, f_hi = time_graphs_spread(fused_graphs, args.steps, args.warmup)
                 del fused_graphs
         two_kernel_gbs = step_bytes / (sec / args.steps) / 1e9
@@ -667,7 +691,7 @@ def main():
             "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "fp8_e4m3", "data": "synthetic",
             "config": {"workload": "configs[1]: decode sweep, Llama-3-8B shapes, M in {1,4,16} x 4 (K,N), INT4 g128 "
                                    "weights, FP8 e4m3 activations, bf16 out; step = activation quantization + linear for each of the 12 cases",
-                       "weight_sets": args.copies, "launch": "eager" if args.eager else "HIP graph replay",
+                       "weight_sets": args.copies, "launch": "eager" if args.eager else "HIP graph replay, %d steps (one per weight set) per graph" % args.copies,
                        "step_form": "w4a8_linear_quantize_in for the single-token cases, quantize_act + linear for the others"
                                     if fused_sec is not None and fused_sec <= sec else "12 x (quantize_act + linear)",
                        "two_kernel_step_GBps": round(two_kernel_gbs, 1)},
