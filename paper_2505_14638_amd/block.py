@@ -77,7 +77,7 @@ class DecoderBlockLinears:
         m, g, sx, w = x.shape[0], self.group_size, self.scales_x, self.weights
         x8 = self._buf(("qkv", "x8", m), (m, self.hidden), torch.uint8)
         qkv8 = self._buf(("qkv", "y8", m), (m, self.dims["qkv"][1]), torch.uint8)
-        if m <= self.quantize_in_up_to:                          # every workgroup quantizes x itself: one launch fewer
+        if m <= self.quantize_in_up_to and m * self.hidden <= 65536:   # every workgroup quantizes x itself: one launch fewer
             B.linear_quantize_in_fp8_out(x, sx["qkv"], *w["qkv"], self.dims["qkv"][1], g, sx["o"], out=qkv8,
                                          x8_out=x8 if keep is not None else None)
         else:
