@@ -81,9 +81,11 @@ class Case:
         B.linear(self.x8, self.s_x, packed, scales, self.layer.n, G, B.LAYOUT_TILED, out=self.y, workspace=self.ws)
 
     def fusable(self):
-        """Where folding the activation quantization into the layer (w4a8_linear_quantize_in) pays: a single token.  Every
-        workgroup quantizes all of X, so from four tokens on the separate kernel is the faster form (measured)."""
-        return self.m == 1
+        """Where folding the activation quantization into the layer (w4a8_linear_quantize_in) pays.  Every workgroup
+        quantizes all of X, so the work grows with tokens x workgroups per compute unit: measured faster at one token on
+        every layer, and up to four tokens on the layers that run one workgroup per compute unit (QKV 8.4 -> 7.9 us, O
+        projection 7.4 -> 6.6); slower on gate|up from two tokens on and on the down projection from four."""
+        return self.m == 1 or (self.m <= 4 and self.layer.k <= 4096 and self.layer.n <= 6144)
 
     def quantize_and_linear(self, s):
         """One pass of the path for this case: the fused launch where the library has one, else the two kernels."""
@@ -692,7 +694,7 @@ def main():
             "config": {"workload": "configs[1]: decode sweep, Llama-3-8B shapes, M in {1,4,16} x 4 (K,N), INT4 g128 "
                                    "weights, FP8 e4m3 activations, bf16 out; step = activation quantization + linear for each of the 12 cases",
                        "weight_sets": args.copies, "launch": "eager" if args.eager else "HIP graph replay, %d steps (one per weight set) per graph" % args.copies,
-                       "step_form": "w4a8_linear_quantize_in for the single-token cases, quantize_act + linear for the others"
+                       "step_form": "w4a8_linear_quantize_in for the single-token cases and for four tokens on QKV and O, quantize_act + linear for the others"
                                     if fused_sec is not None and fused_sec <= sec else "12 x (quantize_act + linear)",
                        "two_kernel_step_GBps": round(two_kernel_gbs, 1)},
             "roofline": {"bound": "hbm", "achieved": round(lin_gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
