@@ -121,7 +121,7 @@ int w4a8_pack_weights(const void* src_dev, w4a8_src src_kind, const float* src_s
 /*
  * Bytes of device scratch with which w4a8_linear runs these sizes fastest (tiled layout); 0 for most shapes.
  * Non-zero where the layer has few output tiles and a deep K (Sec. 1: between the memory-bound and the compute-bound
- * regime -- some 64 to 512 tokens on the layers of a decoder): K is then multiplied in several ranges by different
+ * regime -- some 41 to 512 tokens on the down projection of a decoder): K is then multiplied in several ranges by different
  * workgroups, whose float32 partial sums (ranges x M x round_up(N, 64) floats) pass through the scratch and are
  * added in the order of the ranges by a second launch, so the result does not depend on timing.
  */
@@ -141,9 +141,11 @@ size_t w4a8_linear_workspace_bytes(int64_t M, int64_t K, int64_t N, int32_t grou
  *                 tolerance).  Not NULL: 16-byte aligned device memory of workspace_bytes bytes, which must be at least
  *                 w4a8_linear_workspace_bytes() for these sizes (W4A8_ERR_WORKSPACE otherwise); its contents are
  *                 scratch, owned by the call until the stream work completes.
- * Kernel choice depends only on (M, K, N, layout): up to 32 tokens (64 for K >= 8192 with N <= 8192) take the
- * bandwidth-bound skinny path, larger M the MFMA-tiled path; CANONICAL always takes a plain reference-speed kernel.
- * M == 0 is a no-op.
+ * Kernel choice depends only on (M, K, N, layout) and on whether a workspace is given: up to 32 tokens (up to 64 on
+ * layers of at most 4096 channels, or of at most 8192 when K >= 8192; up to 48 on at most 6144 channels) take the
+ * bandwidth-bound few-token path, larger M the MFMA-tiled paths; with a workspace the shapes
+ * w4a8_linear_workspace_bytes() names (from 41 tokens on) run K in ranges across workgroups instead.  CANONICAL always
+ * takes a plain reference-speed kernel.  M == 0 is a no-op.
  */
 int w4a8_linear(const uint8_t* x8_dev, int64_t M, int64_t K, int64_t ldx8, const float* x_scale_dev,
                 const uint8_t* packed_dev, const float* w_scales_dev, int64_t N, int32_t group_size,
