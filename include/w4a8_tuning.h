@@ -34,6 +34,15 @@ int w4a8_linear_variant(const uint8_t* x8_dev, int64_t M, int64_t K, int64_t ldx
                         int32_t param1, void* stream);
 
 /*
+ * w4a8_linear_two_level on the second tiling with the workgroup tile chosen by the caller (tile, group_m_workgroups as
+ * param0 and param1 of path 2 above); arguments otherwise as in w4a8_linear_two_level.  For tests and tuning sweeps.
+ */
+int w4a8_linear_two_level_variant(const uint8_t* x8_dev, int64_t M, int64_t K, int64_t ldx8, const float* x_scale_dev,
+                                  const uint8_t* packed_dev, const float* w_scales8_dev, const float* w_out_scales_dev,
+                                  int32_t per_channel, int64_t N, int32_t group_size, void* y_dev, w4a8_dtype y_dtype,
+                                  int64_t ldy, int32_t tile, int32_t group_m_workgroups, void* stream);
+
+/*
  * The launch shape w4a8_linear chooses by itself for these sizes (tiled layout, bf16 output), in the terms of
  * w4a8_linear_variant: shape4[0] = path (0, 1 or 2; 3 = the second tiling with K ranges across workgroups, taken only
  * when the caller hands w4a8_linear a workspace -- with_workspace != 0), shape4[1] = param0, shape4[2] = param1,

@@ -42,6 +42,8 @@ SIGNATURES = {
     "w4a8_dequant_weights": (_c_i32, [_c_vp, _c_i64, _c_i64, _c_i32, _c_vp, _c_vp]),
     "w4a8_linear_two_level": (_c_i32, [_c_vp, _c_i64, _c_i64, _c_i64, _c_vp, _c_vp, _c_vp, _c_vp, _c_i32, _c_i64, _c_i32,
                                        _c_vp, _c_i32, _c_i64, _c_vp]),
+    "w4a8_linear_two_level_variant": (_c_i32, [_c_vp, _c_i64, _c_i64, _c_i64, _c_vp, _c_vp, _c_vp, _c_vp, _c_i32, _c_i64,
+                                               _c_i32, _c_vp, _c_i32, _c_i64, _c_i32, _c_i32, _c_vp]),
     "w4a8_dequant_weights_two_level": (_c_i32, [_c_vp, _c_vp, _c_i64, _c_i64, _c_i32, _c_vp, _c_vp]),
     "w4a8_linear_pow2": (_c_i32, [_c_vp, _c_i64, _c_i64, _c_i64, _c_vp, _c_vp, _c_vp, _c_i64, _c_i32, _c_vp, _c_i32,
                                   _c_i64, _c_vp]),
@@ -278,6 +280,19 @@ def linear_variant(x8, x_scale, packed, w_scales, n, group_size, out, path: int,
                                      x_scale.data_ptr(), packed.data_ptr(), w_scales.data_ptr(), n, group_size,
                                      out.data_ptr(), _dtype_code(out), out.stride(0) if m > 1 else max(n, out.stride(0)),
                                      path, param0, param1, _stream()), "w4a8_linear_variant")
+    return out
+
+
+def linear_two_level_variant(x8, x_scale, packed, w_scales8, w_out_scales, n, group_size, out, tile: int, param1: int = 0):
+    """w4a8_linear_two_level_variant: the two-level layer on a chosen tile of the second tiling."""
+    m, k = x8.shape
+    per_channel = 1 if w_out_scales.numel() > 1 else 0
+    assert w_out_scales.numel() in (1, n) and w_out_scales.dtype == torch.float32
+    _check(lib().w4a8_linear_two_level_variant(x8.data_ptr(), m, k, x8.stride(0) if m > 1 else max(k, x8.stride(0)),
+                                               x_scale.data_ptr(), packed.data_ptr(), w_scales8.data_ptr(),
+                                               w_out_scales.data_ptr(), per_channel, n, group_size, out.data_ptr(),
+                                               _dtype_code(out), out.stride(0) if m > 1 else max(n, out.stride(0)),
+                                               tile, param1, _stream()), "w4a8_linear_two_level_variant")
     return out
 
 

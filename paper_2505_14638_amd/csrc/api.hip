@@ -217,6 +217,24 @@ int w4a8_linear_two_level(const uint8_t* x8_dev, int64_t M, int64_t K, int64_t l
                                     y_dtype, ldy, 0, 0, 0, w_out_scales_dev, per_channel, MODE_TWO_LEVEL, nullptr, st);
 }
 
+int w4a8_linear_two_level_variant(const uint8_t* x8_dev, int64_t M, int64_t K, int64_t ldx8, const float* x_scale_dev,
+                                  const uint8_t* packed_dev, const float* w_scales8_dev, const float* w_out_scales_dev,
+                                  int32_t per_channel, int64_t N, int32_t group_size, void* y_dev, w4a8_dtype y_dtype,
+                                  int64_t ldy, int32_t tile, int32_t group_m_workgroups, void* stream) {
+    if (!valid_dtype(y_dtype)) return W4A8_ERR_DTYPE;
+    if (int e = check_linear(x8_dev, M, K, ldx8, x_scale_dev, packed_dev, w_scales8_dev, N, group_size,
+                             W4A8_LAYOUT_TILED, y_dev, y_dtype, ldy))
+        return e;
+    if (!w_out_scales_dev) return W4A8_ERR_NULL;
+    if (reinterpret_cast<uintptr_t>(w_out_scales_dev) % 4) return W4A8_ERR_ALIGN;
+    if (per_channel != 0 && per_channel != 1) return W4A8_ERR_DTYPE;
+    if (tile < 0 || group_m_workgroups < 0) return W4A8_ERR_SHAPE;
+    if (M == 0) return W4A8_OK;
+    return launch_linear_mfma2d(x8_dev, M, K, ldx8, x_scale_dev, packed_dev, w_scales8_dev, N, group_size, y_dev, y_dtype,
+                                ldy, tile, group_m_workgroups & 0xFF, group_m_workgroups >> 8, MODE_TWO_LEVEL, nullptr,
+                                static_cast<hipStream_t>(stream), 1, nullptr, w_out_scales_dev, per_channel);
+}
+
 int w4a8_linear_quantize_in(const void* x_dev, w4a8_dtype x_dtype, int64_t M, int64_t K, int64_t ldx,
                             const float* x_scale_dev, const uint8_t* packed_dev, const float* w_scales_dev, int64_t N,
                             int32_t group_size, void* y_dev, w4a8_dtype y_dtype, int64_t ldy, uint8_t* x8_out_dev,

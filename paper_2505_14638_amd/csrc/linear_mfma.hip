@@ -477,7 +477,7 @@ bool mfma_launch_shape(int64_t M, int64_t K, int64_t N, int mode, int& mf, int& 
     cfg2d = -1;
     const int C = (int)(K / 128);
     const int n_tiles = (int)((N + 15) / 16);
-    if (mf == 0 && ks == 0 && tpw == 0 && (mode == MODE_CODE_EXACT || mode == MODE_POW2)) {
+    if (mf == 0 && ks == 0 && tpw == 0 && (mode == MODE_CODE_EXACT || mode == MODE_POW2 || mode == MODE_TWO_LEVEL)) {
         const int64_t tm = (M + 255) / 256, t1 = tm * ((N + 255) / 256), t2 = tm * ((N + 127) / 128);
         const double c = (double)C;
         const double e1 = (double)((t1 + 255) / 256) * (6.0 + 1.66 * c);
@@ -532,7 +532,8 @@ int launch_linear_mfma_tiled(const uint8_t* x8, int64_t M, int64_t K, int64_t ld
     int cfg2d = -1;
     if (!mfma_launch_shape(M, K, N, mode, mf, ks, tpw, cfg2d)) return W4A8_ERR_SHAPE;
     if (cfg2d >= 0)
-        return launch_linear_mfma2d(x8, M, K, ldx8, s_x, packed, scales, N, G, y, ydt, ldy, cfg2d, 0, 0, mode, y_scale, st);
+        return launch_linear_mfma2d(x8, M, K, ldx8, s_x, packed, scales, N, G, y, ydt, ldy, cfg2d, 0, 0, mode, y_scale, st, 1, nullptr,
+                                    w_out, per_channel);
     const int per_wg = (8 / ks) * tpw;
     const int grid_n = (n_tiles + per_wg - 1) / per_wg;
     const int grid_m = (int)((M + 16 * mf - 1) / (16 * mf));

@@ -74,7 +74,7 @@ __global__ void __launch_bounds__(64 * WGM * WGN, 2) linear_mfma2d_kernel(
     const uint8_t* __restrict__ x8, int M, int64_t ldx8, const float* __restrict__ s_x,
     const uint8_t* __restrict__ packed, const float* __restrict__ scales, int N, int n_tiles, int C, int cpg, int NG,
     OutT* __restrict__ y, int64_t ldy, int grid_m, int grid_n, int group_m, const float* __restrict__ y_scale, int ksplit,
-    int cps, int64_t split_stride) {
+    int cps, int64_t split_stride, const float* __restrict__ w_out, int per_channel) {
     constexpr int WAVES = WGM * WGN, THREADS = 64 * WAVES;
     static_assert(WAVES == 8 || WAVES == 4, "one workgroup of eight wavefronts per compute unit, or two of four");
     static_assert(WN % WGM == 0, "every wavefront expands whole bands of its own");
@@ -83,8 +83,14 @@ __global__ void __launch_bounds__(64 * WGM * WGN, 2) linear_mfma2d_kernel(
     // and operand reads at the head of a chunk fall into the other's MFMA steps; they keep ONE stage of weight operands,
     // which costs a second barrier per chunk (all operand registers read before the next chunk's operands are written).
     constexpr int B_STAGES = WAVES == 8 ? 2 : 1;
-    static_assert(MODE == MODE_CODE_EXACT || MODE == MODE_POW2, "modes built for this tiling");
+    static_assert(MODE == MODE_CODE_EXACT || MODE == MODE_POW2 || MODE == MODE_TWO_LEVEL, "modes built for this tiling");
     constexpr bool POW2 = MODE == MODE_POW2;
+    // Two-level reading (Eq. 6-11 taken literally): `scales` are FP8-domain group scales, the weight operand is
+    // nearest_E4M3(code * s8[n, g]) -- formed by the wavefront that expands the band, which therefore loads the scales of
+    // the bands it expands, not of those it multiplies with -- the sum over all of K stays in the matrix unit and the
+    // output is scaled by s_x * w_out[n] (w_out[0] when per_channel is 0).
+    constexpr bool TWO = MODE == MODE_TWO_LEVEL;
+    constexpr bool SUM_IN_MFMA = POW2 || TWO;                    // no FMAs in the loop
     constexpr int BM = 16 * WM * WGM, BN = 16 * WN * WGN;
     constexpr int NBAND = WN * WGN;                              // weight bands of the workgroup tile
     constexpr int EPW = WN / WGM;                                // bands a wavefront expands per chunk
@@ -127,6 +133,7 @@ __global__ void __launch_bounds__(64 * WGM * WGN, 2) linear_mfma2d_kernel(
     int m0 = 0, bn = 0, split = 0, c_begin = 0, c_end = C;
     const uint8_t* sbase[WN];                                    // scales of the wavefront's bands: + g * 64 + i * 4
     const uint8_t* ebase[EPW];                                   // nibbles of the bands it expands: + c * 1024 + lane * 16
+    const uint8_t* esbase[EPW];                                  // two-level mode: their scales, + g * 64 + i * 4
     const uint8_t* xrow0 = x8;
     uint32_t xoff[DPW];                                          // lane's offset of page q from the tile's first row
     const uint32_t woff = lane * 16, soff = i * 4;
@@ -155,6 +162,7 @@ __global__ void __launch_bounds__(64 * WGM * WGN, 2) linear_mfma2d_kernel(
         for (int t = 0; t < EPW; ++t) {
             const int tt = min(bn * NBAND + wn * WN + wm * EPW + t, n_tiles - 1);
             ebase[t] = packed + (int64_t)tt * C * 1024;
+            esbase[t] = reinterpret_cast<const uint8_t*>(scales) + (int64_t)tt * NG * 64;
         }
         xrow0 = x8 + (int64_t)m0 * ldx8;
 #pragma unroll
@@ -177,14 +185,20 @@ __global__ void __launch_bounds__(64 * WGM * WGN, 2) linear_mfma2d_kernel(
     struct Set {
         float s[WN];                                             // group scales of the wavefront's bands
         u32x4 raw[EPW];                                          // nibbles of the bands it expands, one chunk further on
+        float es[EPW];                                           // two-level mode: the group scales that go with them
     };
     auto load_scales = [&](Set& S, int c) {
+        if (TWO) return;                                         // the multiplying wavefronts need no scales there
 #pragma unroll
         for (int j = 0; j < WN; ++j) S.s[j] = *reinterpret_cast<const W4A8_GLOBAL float*>(uniform(sbase[j] + (int64_t)(c / cpg) * 64) + soff);
     };
     auto load_raw = [&](Set& S, int c) {
 #pragma unroll
         for (int t = 0; t < EPW; ++t) S.raw[t] = *reinterpret_cast<const W4A8_GLOBAL u32x4*>(uniform(ebase[t] + (int64_t)c * 1024) + woff);
+        if (TWO) {
+#pragma unroll
+            for (int t = 0; t < EPW; ++t) S.es[t] = *reinterpret_cast<const W4A8_GLOBAL float*>(uniform(esbase[t] + (int64_t)(c / cpg) * 64) + soff);
+        }
     };
     // the finished operand of expanded band t (registers 4h .. 4h+3) into stage `buf`
     auto publish = [&](int buf, int t, int h, uint32_t a, uint32_t b, uint32_t c2, uint32_t d) {
@@ -200,10 +214,20 @@ __global__ void __launch_bounds__(64 * WGM * WGN, 2) linear_mfma2d_kernel(
     auto chunk = [&](int c, Set& cur, Set& nxt) {
         const int buf = (c - c_begin) & 1;
         // what the previous chunk loaded is touched here, straight after the wait for all loads at that chunk's end
+        if (!TWO) {
 #pragma unroll
-        for (int j = 0; j < WN; ++j) asm volatile("" : "+v"(cur.s[j]));
+            for (int j = 0; j < WN; ++j) asm volatile("" : "+v"(cur.s[j]));
+        }
 #pragma unroll
         for (int t = 0; t < EPW; ++t) asm volatile("" : "+v"(cur.raw[t]));   // as one 128-bit value: it stays in the registers it was loaded into
+        MagTable tab[EPW];                                       // two-level mode: nearest_E4M3(m * s8) for the lane's channel
+        if (TWO) {
+#pragma unroll
+            for (int t = 0; t < EPW; ++t) {
+                asm volatile("" : "+v"(cur.es[t]));
+                tab[t] = two_level_table(cur.es[t]);
+            }
+        }
         const int cn = min(c + 1, c_end - 1);                    // after the last chunk: copied again, never read
         if (c + 1 < c_end) load_scales(nxt, c + 1);
         if (c + 2 < c_end) load_raw(nxt, c + 2);
@@ -228,7 +252,7 @@ __global__ void __launch_bounds__(64 * WGM * WGN, 2) linear_mfma2d_kernel(
         }
 #pragma unroll
         for (int j = 0; j < WN; ++j) {
-            if (any_marked(cur.s[j])) {                          // wave-uniform, rare: the band's group holds a -8
+            if (!TWO && any_marked(cur.s[j])) {                  // wave-uniform, rare: the band's group holds a -8
 #pragma unroll
                 for (int e = 0; e < 8; ++e) bop[j][e] = (int)sm_fix_minus_eight((uint32_t)bop[j][e]);
             }
@@ -257,8 +281,9 @@ __global__ void __launch_bounds__(64 * WGM * WGN, 2) linear_mfma2d_kernel(
             // the copies of the next chunk's activations, one every few steps of the first half of the chunk
             if constexpr (st % DMA_EVERY == 0 && st / DMA_EVERY < DPW) stage_page(cn, buf ^ 1, st / DMA_EVERY);
             if (POW2) acc[f][j] = mfma_16x16x128_e4m3_scaled(xop, bop[j], acc[f][j], E8M0_ONE, e8m0_of(cur.s[j]));
-            const v4f p = POW2 ? v4f{0.f, 0.f, 0.f, 0.f} : mfma_16x16x128_e4m3(xop, bop[j], v4f{0.f, 0.f, 0.f, 0.f});
-            if constexpr (!POW2 && st > 1) {
+            if (TWO) acc[f][j] = mfma_16x16x128_e4m3(xop, bop[j], acc[f][j]);
+            const v4f p = SUM_IN_MFMA ? v4f{0.f, 0.f, 0.f, 0.f} : mfma_16x16x128_e4m3(xop, bop[j], v4f{0.f, 0.f, 0.f, 0.f});
+            if constexpr (!SUM_IN_MFMA && st > 1) {
                 fold(std::integral_constant<int, (st - 2) / WN>{}, std::integral_constant<int, (st - 2) % WN>{}, p_prev2);
                 keep_here(acc[(st - 2) / WN][(st - 2) % WN]);
             }
@@ -271,24 +296,38 @@ __global__ void __launch_bounds__(64 * WGM * WGN, 2) linear_mfma2d_kernel(
             constexpr int E = st / STEPS_PER_EIGHTH, t = E / 8, e = E % 8, d = e >> 1;
             if constexpr (EXPAND) {
                 const uint32_t src = cur.raw[t][d];
-                uint32_t o = (e & 1) ? sm_half_to_e4m3_fast<4>(src) : sm_half_to_e4m3_fast<0>(src);
+                uint32_t o;
+                if (TWO) o = (e & 1) ? two_level_half_fast<4>(src, tab[t]) : two_level_half_fast<0>(src, tab[t]);
+                else o = (e & 1) ? sm_half_to_e4m3_fast<4>(src) : sm_half_to_e4m3_fast<0>(src);
                 keep_here(o);
                 eop[t][e] = o;
                 if (e == 3) publish(buf ^ 1, t, 0, eop[t][0], eop[t][1], eop[t][2], eop[t][3]);
                 if (e == 7) publish(buf ^ 1, t, 1, eop[t][4], eop[t][5], eop[t][6], eop[t][7]);
             }
-            constexpr int ALU = ((POW2 || st < 2) ? 0 : 4) + (EXPAND ? 4 : 0);
+            constexpr int ALU = ((SUM_IN_MFMA || st < 2) ? 0 : 4) + (EXPAND ? 4 : 0);
             if (j == 0 && f + 1 < WM) __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);   // LDS reads of the next block
             __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                            // this step's MFMA
             __builtin_amdgcn_sched_group_barrier(0x002, ALU, 0);                          // ALU work independent of it
             if (EXPAND && (e == 3 || e == 7)) __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);   // the publishing LDS write
             __builtin_amdgcn_sched_barrier(0);
         });
-        if (!POW2) {
+        if (!SUM_IN_MFMA) {
             fold(std::integral_constant<int, (STEPS - 2) / WN>{}, std::integral_constant<int, (STEPS - 2) % WN>{}, p_prev2);
             fold(std::integral_constant<int, WM - 1>{}, std::integral_constant<int, WN - 1>{}, p_prev);
         }
         __builtin_amdgcn_s_setprio(0);
+        if (TWO) {
+            // a band whose group holds a -8 (marked by the packer, rare): its operand again, this time with the pattern
+            // 1000 put right -- after the steps, so that their instruction sequence stays one block
+#pragma unroll
+            for (int t = 0; t < EPW; ++t) {
+                if (any_marked(cur.es[t])) {
+                    const v8i o = slot_to_operand_two_level<true>(make_uint4(cur.raw[t][0], cur.raw[t][1], cur.raw[t][2], cur.raw[t][3]), tab[t]);
+                    publish(buf ^ 1, t, 0, (uint32_t)o[0], (uint32_t)o[1], (uint32_t)o[2], (uint32_t)o[3]);
+                    publish(buf ^ 1, t, 1, (uint32_t)o[4], (uint32_t)o[5], (uint32_t)o[6], (uint32_t)o[7]);
+                }
+            }
+        }
         lds_dma_wait_all();                                      // this wavefront's copies and loads have landed ...
         __syncthreads();                                         // ... and so have everyone's; the stages just read are free
     };
@@ -298,15 +337,23 @@ __global__ void __launch_bounds__(64 * WGM * WGN, 2) linear_mfma2d_kernel(
     // the compiler puts in front of their first uses leave the copies alone).
     Set sa, sb;
     u32x4 raw0[EPW];
+    float es0[EPW];                                              // two-level mode: scales of chunk 0's bands
     auto start_issue = [&]() {
 #pragma unroll
         for (int q = 0; q < DPW; ++q) stage_page(c_begin, 0, q);
 #pragma unroll
         for (int t = 0; t < EPW; ++t)
             raw0[t] = *reinterpret_cast<const W4A8_GLOBAL u32x4*>(uniform(ebase[t] + (int64_t)c_begin * 1024) + woff);
+        if (TWO) {
+#pragma unroll
+            for (int t = 0; t < EPW; ++t) es0[t] = *reinterpret_cast<const W4A8_GLOBAL float*>(uniform(esbase[t] + (int64_t)(c_begin / cpg) * 64) + soff);
+        }
         load_scales(sa, c_begin);
 #pragma unroll
-        for (int t = 0; t < EPW; ++t) sa.raw[t] = u32x4{0u, 0u, 0u, 0u};
+        for (int t = 0; t < EPW; ++t) {
+            sa.raw[t] = u32x4{0u, 0u, 0u, 0u};
+            sa.es[t] = 0.0f;
+        }
         if (c_begin + 1 < c_end) load_raw(sa, c_begin + 1);
     };
     // second half: chunk 0's weight operands, expanded from registers, into stage 0; then everything has landed
@@ -314,7 +361,7 @@ __global__ void __launch_bounds__(64 * WGM * WGN, 2) linear_mfma2d_kernel(
 #pragma unroll
         for (int t = 0; t < EPW; ++t) {
             const uint4 r = make_uint4(raw0[t][0], raw0[t][1], raw0[t][2], raw0[t][3]);
-            const v8i o = slot_to_operand<false>(r);
+            const v8i o = TWO ? slot_to_operand_two_level<true>(r, two_level_table(es0[t])) : slot_to_operand<false>(r);
             publish(0, t, 0, (uint32_t)o[0], (uint32_t)o[1], (uint32_t)o[2], (uint32_t)o[3]);
             publish(0, t, 1, (uint32_t)o[4], (uint32_t)o[5], (uint32_t)o[6], (uint32_t)o[7]);
         }
@@ -341,6 +388,10 @@ __global__ void __launch_bounds__(64 * WGM * WGN, 2) linear_mfma2d_kernel(
             const bool vec_ok = (ldy * EB) % 16 == 0 && reinterpret_cast<uintptr_t>(yo) % 16 == 0;
             const int n_wave = n_block + wn * WN * 16;               // first channel of the wavefront's bands
             const int seg = lane % SEGS, srow = lane / SEGS;
+            float so[WN];                                            // output scale of the lane's channel of band j
+#pragma unroll
+            for (int j = 0; j < WN; ++j)
+                so[j] = TWO ? sx * w_out[per_channel ? min(n_wave + j * 16 + i, N - 1) : 0] : sx;
 #pragma unroll
             for (int f = f0; f < f1; ++f) {
 #pragma unroll
@@ -352,7 +403,7 @@ __global__ void __launch_bounds__(64 * WGM * WGN, 2) linear_mfma2d_kernel(
                         typedef __bf16 b2 __attribute__((ext_vector_type(2)));
                         const bool odd = (i & 1) != 0;
                         const uint32_t sel_lo = odd ? 0x05040100u : 0x01000504u, sel_hi = odd ? 0x07060302u : 0x03020706u;
-                        const f2 t01 = {sx * acc[f][j][0], sx * acc[f][j][1]}, t23 = {sx * acc[f][j][2], sx * acc[f][j][3]};
+                        const f2 t01 = {so[j] * acc[f][j][0], so[j] * acc[f][j][1]}, t23 = {so[j] * acc[f][j][2], so[j] * acc[f][j][3]};
                         const b2 c01 = __builtin_convertvector(t01, b2), c23 = __builtin_convertvector(t23, b2);
                         const uint32_t a = *reinterpret_cast<const uint32_t*>(&c01), b = *reinterpret_cast<const uint32_t*>(&c23);
                         const uint32_t own = odd ? b : a, nb = from_pair_lane(odd ? a : b);
@@ -362,7 +413,7 @@ __global__ void __launch_bounds__(64 * WGM * WGN, 2) linear_mfma2d_kernel(
                     } else {
 #pragma unroll
                         for (int r = 0; r < 4; ++r)
-                            *reinterpret_cast<float*>(slab + (4 * kq + r) * RSB + (j * 16 + i) * 4) = sx * acc[f][j][r];
+                            *reinterpret_cast<float*>(slab + (4 * kq + r) * RSB + (j * 16 + i) * 4) = so[j] * acc[f][j][r];
                     }
                 }
 #pragma unroll
@@ -385,6 +436,7 @@ __global__ void __launch_bounds__(64 * WGM * WGN, 2) linear_mfma2d_kernel(
                 }
             }
         } else {
+            static_assert(!TWO || DIRECT, "the two-level mode has float32 and bf16 outputs only");
             // E4M3 outputs: per round the workgroup turns block f of every wavefront row into row-major order in LDS
             // (stage 1, which nothing else uses between two tiles) and stores whole row segments
             SlabT* slab = reinterpret_cast<SlabT*>(lds + STAGE);
@@ -507,11 +559,12 @@ void launch_cfg(const LinearArgs& a, dim3 grid, int grid_m, int grid_n, int grou
 #define W4A8_MFMA2D(MODEV)                                                                                                     \
     hipLaunchKernelGGL((linear_mfma2d_kernel<OutT, WGM, WGN, WM, WN, MODEV>), grid, dim3(64 * WGM * WGN), 0, st, a.x8, a.M, a.ldx8, \
                        a.s_x, a.packed, a.scales, a.N, a.n_tiles, a.C, a.cpg, a.NG, static_cast<OutT*>(a.y), a.ldy, grid_m,       \
-                       grid_n, group_m, a.y_scale, sp.ksplit, sp.cps > 0 ? sp.cps : a.C, sp.split_stride)
+                       grid_n, group_m, a.y_scale, sp.ksplit, sp.cps > 0 ? sp.cps : a.C, sp.split_stride, a.w_out, a.per_channel)
     if constexpr (sizeof(OutT) == 1) {                           // FP8 output exists for the code-exact mode only
         W4A8_MFMA2D(MODE_CODE_EXACT);
     } else {
         if (a.mode == MODE_POW2) W4A8_MFMA2D(MODE_POW2);
+        else if (a.mode == MODE_TWO_LEVEL) W4A8_MFMA2D(MODE_TWO_LEVEL);
         else W4A8_MFMA2D(MODE_CODE_EXACT);
     }
 #undef W4A8_MFMA2D
@@ -543,8 +596,9 @@ bool mfma2d_tile(int cfg, int& bm, int& bn) {
 int launch_linear_mfma2d(const uint8_t* x8, int64_t M, int64_t K, int64_t ldx8, const float* s_x, const uint8_t* packed,
                          const float* scales, int64_t N, int32_t G, void* y, w4a8_dtype ydt, int64_t ldy, int cfg,
                          int group_m, int workgroups, int mode, const float* y_scale, hipStream_t st, int ksplit,
-                         void* workspace) {
-    if (mode != MODE_CODE_EXACT && mode != MODE_POW2) return W4A8_ERR_DTYPE;
+                         void* workspace, const float* w_out, int per_channel) {
+    if (mode != MODE_CODE_EXACT && mode != MODE_POW2 && mode != MODE_TWO_LEVEL) return W4A8_ERR_DTYPE;
+    if (mode == MODE_TWO_LEVEL && (!w_out || ksplit > 1 || ((int)ydt != W4A8_F32 && (int)ydt != W4A8_BF16))) return W4A8_ERR_DTYPE;
     if (((int)ydt == YDT_E4M3 || (int)ydt == YDT_SILU_E4M3) && (mode != MODE_CODE_EXACT || !y_scale)) return W4A8_ERR_DTYPE;
     if ((int)ydt == YDT_SILU_E4M3 && N % 32 != 0) return W4A8_ERR_SHAPE;
     int bm, bn;
@@ -577,7 +631,7 @@ int launch_linear_mfma2d(const uint8_t* x8, int64_t M, int64_t K, int64_t ldx8, 
     const int64_t needed = (total + XCDS2 - 1) / XCDS2 * XCDS2;
     if (workgroups > needed) workgroups = (int)needed;
     const dim3 grid((unsigned)workgroups);
-    LinearArgs a{x8, (int)M, ldx8, s_x, packed, scales, (int)N, n_tiles, C, cpg, NG, y, ldy, nullptr, 0, mode, y_scale};
+    LinearArgs a{x8, (int)M, ldx8, s_x, packed, scales, (int)N, n_tiles, C, cpg, NG, y, ldy, w_out, per_channel, mode, y_scale};
     int kernel_ydt = (int)ydt;
     if (ksplit > 1) {                                            // the tiles go to the workspace as unscaled float32
         a.y = workspace;

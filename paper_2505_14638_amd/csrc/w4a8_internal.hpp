@@ -82,7 +82,8 @@ int launch_linear_mfma_tiled(const uint8_t* x8, int64_t M, int64_t K, int64_t ld
                              int mode, const float* y_scale, hipStream_t st);
 // Second tiling of the many-token kernel (2-D grid of wavefronts, expansion shared through LDS, persistent workgroups).
 // cfg: a tile of mfma2d_tile; group_m = token blocks per super-column of the block order (0: chosen); workgroups = size of
-// the persistent grid (0: one per compute unit); mode: MODE_CODE_EXACT or MODE_POW2; ksplit > 1: K is multiplied in that
+// the persistent grid (0: one per compute unit); mode: MODE_CODE_EXACT, MODE_POW2 or MODE_TWO_LEVEL (w_out, per_channel as
+// in the first tiling; float32 / bf16 outputs, no split of K); ksplit > 1: K is multiplied in that
 // many ranges by different workgroups, their float32 partial sums go through `workspace` (mfma2d_splitk_bytes).
 bool mfma2d_tile(int cfg, int& bm, int& bn);
 
@@ -119,7 +120,7 @@ inline void mfma2d_choose_ksplit(int64_t M, int64_t K, int64_t N, int& cfg, int&
 int launch_linear_mfma2d(const uint8_t* x8, int64_t M, int64_t K, int64_t ldx8, const float* s_x, const uint8_t* packed,
                          const float* scales, int64_t N, int32_t G, void* y, w4a8_dtype ydt, int64_t ldy, int cfg,
                          int group_m, int workgroups, int mode, const float* y_scale, hipStream_t st, int ksplit = 1,
-                         void* workspace = nullptr);
+                         void* workspace = nullptr, const float* w_out = nullptr, int per_channel = 0);
 int launch_hessian_accumulate(const void* x, w4a8_dtype dt, int64_t T, int64_t K, int64_t ldx, float* h, hipStream_t st);
 int launch_gar_permutation(const float* hdiag, int64_t K, int32_t G, int32_t* perm, hipStream_t st);
 // U = upper Cholesky factor of the inverse dampened (and reordered) Hessian; workspace: hessian_factor_workspace_bytes(K)

@@ -21,5 +21,5 @@ int launch_silu_mul(const void*, int64_t, int64_t, int64_t, void*, int64_t, cons
 bool skinny_launch_shape(int64_t, int64_t, int64_t, int, int, int, int& nt, int& waves, int& depth) { nt = 1; waves = 8; depth = 2; return true; }
 bool mfma_launch_shape(int64_t, int64_t, int64_t, int, int& mf, int& ks, int& tpw, int& cfg2d) { mf = 16; ks = 1; tpw = 1; cfg2d = -1; return true; }
 bool mfma2d_tile(int cfg, int& bm, int& bn) { bm = 256; bn = 256; return cfg >= 0 && cfg <= 5; }
-int launch_linear_mfma2d(const uint8_t*, int64_t, int64_t, int64_t, const float*, const uint8_t*, const float*, int64_t, int32_t, void*, w4a8_dtype, int64_t, int, int, int, int, const float*, hipStream_t, int, void*) { return W4A8_OK; }
+int launch_linear_mfma2d(const uint8_t*, int64_t, int64_t, int64_t, const float*, const uint8_t*, const float*, int64_t, int32_t, void*, w4a8_dtype, int64_t, int, int, int, int, const float*, hipStream_t, int, void*, const float*, int) { return W4A8_OK; }
 }  // namespace w4a8

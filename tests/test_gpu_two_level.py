@@ -135,3 +135,72 @@ def test_two_level_llama_qkv_shape_sampled(gpu_lib, m):
     ok, worst = o.within_tolerance(y32[rows], ref, a, floor=FLOOR)
     print(f"  two-level qkv M={m}: worst err/bound {worst:.3e}", flush=True)
     assert ok
+
+
+# ---------------------------------------------------------------- the second tiling (2-D grid of wavefronts, persistent workgroups)
+TILES = (0, 1, 2, 3, 4, 5)
+
+
+def run_tile(x8, s_x, q, s8, s_w, g, tile, p1=0, per_tensor=False):
+    n, k = q.shape
+    m = x8.shape[0]
+    packed, scales = B.pack_weights(dev(q), g, B.LAYOUT_TILED, dev(s8))
+    so = dev(np.full(1, s_w[0], np.float32) if per_tensor else s_w)
+    sx = dev(np.array([s_x], np.float32))
+    y32 = torch.full((m, n), float("nan"), dtype=torch.float32, device=DEV)
+    y16 = torch.full((m, n), float("nan"), dtype=torch.bfloat16, device=DEV)
+    B.linear_two_level_variant(dev(x8), sx, packed, scales, so, n, g, y32, tile, p1)
+    B.linear_two_level_variant(dev(x8), sx, packed, scales, so, n, g, y16, tile, p1)
+    return host(y32), host(y16.view(torch.int16)).view(np.uint16)
+
+
+@pytest.mark.parametrize("tile", TILES)
+@pytest.mark.parametrize("m,k,n,g,p1", [(300, 1024, 520, 512, 0), (513, 256, 144, 256, 0), (70, 128, 20, 128, 0),
+                                        # persistent grids of 8 and 16 workgroups: several tiles per workgroup
+                                        (700, 384, 1100, 128, 1 | (8 << 8)), (1300, 640, 600, 128, 3 | (16 << 8))])
+def test_two_level_on_every_tile_of_the_second_tiling(gpu_lib, tile, m, k, n, g, p1):
+    """Ragged tokens and channels, groups of one or more chunks, the expanding wavefront's scales (not the multiplying
+    one's) and the per-channel output scale in the epilogue, against the oracle's literal reading."""
+    rng = np.random.default_rng([37, m, k, n])
+    w = syn.make_weights(rng, n, k)
+    x = syn.make_activations(rng, m, k, 0.02, 20.0)
+    s_x = syn.static_act_scale(x)
+    x8 = o.quantize_act(x, s_x)
+    q, s8, s_w = two_level_inputs(w, g)
+    ref, want8 = o.linear_ref_paper_literal(x8, s_x, q, s8, s_w, g)
+    a = float(np.float32(s_x)) * (np.abs(o.e4m3_decode(x8)) @ np.abs(o.e4m3_decode(want8)).T) * s_w.astype(np.float64)[None, :]
+    y32, y16 = run_tile(x8, s_x, q, s8, s_w, g, tile, p1)
+    ok, worst = o.within_tolerance(y32, ref, a, floor=FLOOR)
+    print(f"  two-level, second tiling, tile {tile}, {m}x{k}x{n} g{g}: worst err/bound {worst:.3e}", flush=True)
+    assert ok
+    assert np.array_equal(y16, o.round_to_bf16_bits(y32.astype(np.float64)))
+
+
+@pytest.mark.parametrize("tile", TILES)
+@pytest.mark.parametrize("m,g,p1", [(200, 128, 0), (600, 256, 2 | (8 << 8))])
+def test_two_level_exact_integer_case_on_every_tile_bit_for_bit(gpu_lib, tile, m, g, p1):
+    """As above with -8 in a quarter of the groups (the marked groups take the slow expansion after the steps of a chunk,
+    in the first chunk of a tile the one at its start), per-channel and per-tensor output scales; and the same bits as
+    the first tiling gives through w4a8_linear_two_level."""
+    rng = np.random.default_rng([39, m, g])
+    k, n = 2048, 304
+    ng = k // g
+    xi = rng.integers(-4, 5, size=(m, k))
+    x8 = o.e4m3_encode(xi.astype(np.float32))
+    q = rng.integers(-7, 8, size=(n, k)).astype(np.int8)
+    marked = rng.random((n, ng)) < 0.25
+    marked[:16] = False
+    marked[16:32, 0] = True                                             # the first chunk of a tile, too
+    for nn, gg in zip(*np.nonzero(marked)):
+        q[nn, gg * g + rng.choice(g, size=rng.integers(1, 4), replace=False)] = -8
+    e = rng.integers(-1, 3, size=(n, ng))
+    s8 = np.ldexp(1.0, e).astype(np.float32)
+    part = np.einsum("mgk,ngk->mng", xi.reshape(m, ng, g).astype(np.int64), q.reshape(n, ng, g).astype(np.int64))
+    acc = (part * np.ldexp(1.0, e)[None]).sum(axis=2)
+    s_w = np.ldexp(1.0, rng.integers(-3, 2, size=n)).astype(np.float32)
+    y32, _ = run_tile(x8, np.float32(0.5), q, s8, s_w, g, tile, p1)
+    assert np.array_equal(y32, (0.5 * acc * s_w[None, :]).astype(np.float32))
+    y32t, _ = run_tile(x8, np.float32(0.5), q, s8, np.full(n, 0.25, np.float32), g, tile, p1, per_tensor=True)
+    assert np.array_equal(y32t, (0.5 * 0.25 * acc).astype(np.float32))
+    first, _, _ = run(x8, np.float32(0.5), q, s8, s_w, g)
+    assert np.array_equal(first, y32)
