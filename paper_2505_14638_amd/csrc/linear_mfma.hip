@@ -465,7 +465,8 @@ void launch_one(const LinearArgs& a, dim3 grid, int grid_m, int grid_n, hipStrea
 //    with eight wavefronts (256 at a time) or with four (two workgroups per compute unit, 512 at a time; a tile takes
 //    longer while two share the unit).  Times per tile in microseconds, C = K / 128 chunks, from medians on the
 //    Llama-3 layer shapes with the weights coming from HBM: 6 + 1.66 C, 5 + 1.08 C, 5 + 1.28 C alone and 5 + 1.875 C
-//    shared.  The first tiling is priced at 0.265 C + flops / 1.35 PFLOP/s.  Against the rule this replaces (256 x 256 or
+//    shared (half of that for a last round of at most 256 tiles that follows full ones).  The first tiling is priced
+//    at 0.265 C + flops / 1.35 PFLOP/s.  Against the rule this replaces (256 x 256 or
 //    four-wavefront 256 x 128 tiles once they number 200): 640 tokens on gate|up 125 -> 104 us, 3072 / 4096 tokens on
 //    QKV 113 / 120 -> 101 / 108, 2048 tokens on the O projection 47 -> 42, 192...256 tokens on gate|up 48 -> 42.
 //  - First tiling: tall token blocks amortize the nibble expansion over more MFMAs; two bands per wavefront halve the
@@ -482,9 +483,11 @@ bool mfma_launch_shape(int64_t M, int64_t K, int64_t N, int mode, int& mf, int& 
         const double c = (double)C;
         const double e1 = (double)((t1 + 255) / 256) * (6.0 + 1.66 * c);
         const double e2 = (double)((t2 + 255) / 256) * (5.0 + 1.08 * c);
-        const int64_t rem = t2 % 512;
-        const double e4 = (double)(t2 / 512) * (5.0 + 1.875 * c) +
-                          (rem == 0 ? 0.0 : rem <= 256 ? 5.0 + 1.28 * c : 5.0 + 1.875 * c);
+        const int64_t full = t2 / 512, rem = t2 % 512;
+        const double shared = 5.0 + 1.875 * c;                   // a tile while two workgroups share the compute unit
+        // the last, partly filled round: alone on their units the workgroups run faster, and after full rounds they start
+        // it while others still finish theirs (measured: about half a shared round then)
+        const double e4 = (double)full * shared + (rem == 0 ? 0.0 : rem > 256 ? shared : full > 0 ? 0.5 * shared : 5.0 + 1.28 * c);
         const double first = 0.265 * c + 2.0 * (double)M * (double)K * (double)N / 1.35e9;
         const double best = e1 < e2 ? (e1 < e4 ? e1 : e4) : (e2 < e4 ? e2 : e4);
         if (best < first) {
