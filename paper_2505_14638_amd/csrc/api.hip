@@ -38,12 +38,12 @@ inline bool valid_layout(int l) { return l == W4A8_LAYOUT_CANONICAL || l == W4A8
 inline bool takes_skinny_path(int64_t M, int64_t K, int64_t N) {
     return M <= 32 || (M <= 64 && (N <= 4096 || (K >= 8192 && N <= 8192))) || (M <= 48 && N <= 6144);
 }
-// ... unless the caller brings a workspace and the layer is deep enough for K ranges across workgroups, which beat the
-// skinny kernel from 41 tokens on (Llama-3-8B down projection at 48 / 64 tokens: 24 / 29 us against 22)
+// ... unless the caller brings a workspace and the layer is deep enough (K >= 12288) for K ranges across workgroups,
+// which beat the skinny kernel from 41 tokens on (Llama-3-8B down projection at 48 / 64 tokens: 24 / 29 us against 22)
 inline bool prefers_split_k(int64_t M, int64_t K, int64_t N) {
     int cfg, ksplit;
     mfma2d_choose_ksplit(M, K, N, cfg, ksplit);
-    return ksplit > 1 && M > 40;
+    return ksplit > 1 && M > 40 && K >= 12288;
 }
 constexpr int64_t DIM_MAX = (int64_t)1 << 30;      // keeps every 32-bit tile / chunk index in range
 // One thread per packed byte, 64 per group scale, 64 per output of the canonical layout's layer: these launches stay

@@ -97,12 +97,13 @@ inline size_t mfma2d_splitk_bytes(int64_t M, int64_t N, int ksplit) {
 // none.  Few output tiles and a deep K (the down projection of a decoder block at 64...512 tokens): the tiles are multiplied
 // in `ksplit` K ranges by different workgroups, about as many as it takes to give every compute unit one.  Measured on the
 // Llama-3 shapes: 29 -> 22 us at 128 tokens on the 8B down projection (K = 14336), 84 -> 57 us on the 70B one (K = 28672);
-// no gain for K <= 8192, where the partial sums (written and read once) weigh as much as the weights.
+// at K = 8192 four or more ranges still win (70B O projection at 192 / 256 tokens: 36 / 38 -> 32 / 35 us) and two lose;
+// no gain for K = 4096, where the partial sums (written and read once) weigh as much as the weights.
 inline void mfma2d_choose_ksplit(int64_t M, int64_t K, int64_t N, int& cfg, int& ksplit) {
     cfg = 3;
     ksplit = 0;
     const int64_t C = K / 128;
-    if (M > 512 || K < 12288) return;
+    if (M > 512 || K < 8192) return;
     int64_t tiles = ((M + 127) / 128) * ((N + 255) / 256);      // 128 x 256 tiles ...
     if (tiles <= 16) {                                          // ... or 128 x 128 where those are very few
         cfg = 5;
@@ -111,7 +112,7 @@ inline void mfma2d_choose_ksplit(int64_t M, int64_t K, int64_t N, int& cfg, int&
     if (tiles > 128) return;
     int64_t s = 256 / tiles;
     if (s > C / 8) s = C / 8;
-    if (s < 2) return;
+    if (s < 2 || (K < 12288 && s < 4)) return;                  // K = 8192: two ranges lose, four or more win (measured)
     const int64_t cps = (C + s - 1) / s;
     s = (C + cps - 1) / cps;                                    // no empty range
     ksplit = s < 2 ? 0 : (int)s;
