@@ -172,3 +172,17 @@ def test_linear_with_workspace_on_the_down_projection(gpu_lib, m):
     ok, worst = o.within_tolerance(plain[rows], ref, a)
     say(f"  without workspace: worst err/bound = {worst:.3e}")
     assert ok
+
+
+def test_linear_with_workspace_at_k_8192(gpu_lib):
+    """K = 8192 takes K ranges across workgroups when that gives four or more of them: a narrow layer at 100 tokens through
+    w4a8_linear with the workspace it asks for, every output against the oracle."""
+    m, k, n, g = 100, 8192, 2048, 128
+    need = B.linear_workspace_bytes(m, k, n, g)
+    assert need > 0 and B.linear_launch_shape(m, k, n, g, True)[0] == 3 and B.linear_workspace_bytes(m, 4096, n, g) == 0
+    x8, s_x, packed, scales, ref, a = realistic([85], m, k, n, g, frac=0.01)
+    ws = torch.empty(need, dtype=torch.uint8, device=DEV)
+    sx_d, x8_d = dev(np.array([s_x])), dev(x8)
+    y32 = host(B.linear(x8_d, sx_d, packed, scales, n, g, B.LAYOUT_TILED, out_dtype=torch.float32, workspace=ws))
+    y16 = bf16_bits(B.linear(x8_d, sx_d, packed, scales, n, g, B.LAYOUT_TILED, out_dtype=torch.bfloat16, workspace=ws))
+    check_outputs(y32, y16, ref, a, "K = 8192 with workspace")
