@@ -31,6 +31,7 @@ class DecoderBlockLinears:
         self._buffers = {}
         self.quantize_in_up_to = 8                               # tokens up to which the QKV layer quantizes its own input
         self._workspace = None                                   # scratch of w4a8_linear (K ranges across workgroups), grown on demand
+        self._retired = []                                       # outgrown workspaces, kept for launches already captured
 
     def load_layer(self, name: str, w_f32: torch.Tensor) -> None:
         """Quantize (round-to-nearest INT4) and pack one [N, K] float32 weight matrix on the device."""
@@ -58,6 +59,8 @@ class DecoderBlockLinears:
         if need == 0:
             return None
         if self._workspace is None or self._workspace.numel() < need:
+            if self._workspace is not None:
+                self._retired.append(self._workspace)            # a captured graph may still write to it: never freed
             self._workspace = torch.empty(need, dtype=torch.uint8, device=self.device)
         return self._workspace
 
