@@ -140,7 +140,8 @@ size_t w4a8_linear_workspace_bytes(int64_t M, int64_t K, int64_t N, int32_t grou
  *   workspace_dev NULL: the layer runs without scratch (slower where w4a8_linear_workspace_bytes() is not 0, same
  *                 tolerance).  Not NULL: 16-byte aligned device memory of workspace_bytes bytes, which must be at least
  *                 w4a8_linear_workspace_bytes() for these sizes (W4A8_ERR_WORKSPACE otherwise); its contents are
- *                 scratch, owned by the call until the stream work completes.
+ *                 scratch, owned by the call until the stream work completes (a launch captured into a HIP graph uses it
+ *                 at every replay: it has to outlive the graph).
  * Kernel choice depends only on (M, K, N, layout) and on whether a workspace is given: up to 32 tokens (up to 64 on
  * layers of at most 4096 channels, or of at most 8192 when K >= 8192; up to 48 on at most 6144 channels) take the
  * bandwidth-bound few-token path, larger M the MFMA-tiled paths; with a workspace the shapes
